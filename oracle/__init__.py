@@ -1,0 +1,303 @@
+"""ctypes access to the CPU oracle (vamana_oracle.c).
+
+TEST INFRASTRUCTURE.  Only tests/, the smoke check and the benchmark's CPU
+baseline leg may import this package; the HIP library and its Python binding
+never do, and this package never imports them.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "vamana_oracle.c")
+_HDR = os.path.join(_HERE, "vamana_oracle.h")
+_LIB = os.path.join(_HERE, "libvamana_oracle.so")
+
+NONE = 0xFFFFFFFF
+U8, I8, F32 = 0, 1, 2
+L2SQ, MIPS = 0, 1
+
+_NP_DTYPE = {U8: np.uint8, I8: np.int8, F32: np.float32}
+
+
+def dtype_code(arr: np.ndarray) -> int:
+    if arr.dtype == np.uint8:
+        return U8
+    if arr.dtype == np.int8:
+        return I8
+    if arr.dtype == np.float32:
+        return F32
+    raise TypeError(f"unsupported dtype {arr.dtype}")
+
+
+def build_oracle(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP, no fast-math, no contraction)."""
+    stale = (
+        force
+        or not os.path.exists(_LIB)
+        or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_HDR))
+    )
+    if stale:
+        cmd = [
+            "gcc", "-std=c11", "-O2", "-fopenmp", "-fno-fast-math", "-ffp-contract=off",
+            "-fPIC", "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm",
+        ]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+class _Data(C.Structure):
+    _fields_ = [
+        ("points", C.c_void_p),
+        ("n", C.c_uint64),
+        ("d", C.c_uint32),
+        ("dtype", C.c_int),
+        ("metric", C.c_int),
+    ]
+
+
+class Stats(C.Structure):
+    _fields_ = [(k, C.c_uint64) for k in (
+        "searches", "hops", "evals", "prunes", "reprunes", "appends", "edges",
+        "prune_cand", "prune_evals", "rounds")]
+
+    def as_dict(self):
+        return {k: int(getattr(self, k)) for k, _ in self._fields_}
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build_oracle()
+        L = C.CDLL(_LIB)
+        L.vo_distance.restype = C.c_double
+        L.vo_distance.argtypes = [C.c_void_p, C.c_void_p, C.c_uint32, C.c_int, C.c_int]
+        L.vo_greedy_search.restype = C.c_int
+        L.vo_greedy_search.argtypes = [
+            C.POINTER(_Data), C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_uint32,
+            C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint64, C.POINTER(C.c_uint64), C.c_void_p,
+            C.c_void_p, C.POINTER(Stats)]
+        L.vo_prune.restype = C.c_uint32
+        L.vo_prune.argtypes = [
+            C.POINTER(_Data), C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint64, C.c_uint32,
+            C.c_double, C.c_void_p, C.POINTER(Stats)]
+        L.vo_start_vertex.restype = C.c_uint32
+        L.vo_start_vertex.argtypes = [C.POINTER(_Data)]
+        L.vo_insertion_order.restype = None
+        L.vo_insertion_order.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, C.c_void_p]
+        L.vo_schedule.restype = C.c_uint64
+        L.vo_schedule.argtypes = [C.c_uint64, C.c_uint64, C.c_void_p]
+        L.vo_insert.restype = C.c_int
+        L.vo_insert.argtypes = [
+            C.POINTER(_Data), C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
+            C.c_double, C.POINTER(Stats)]
+        L.vo_batch_insert.restype = C.c_int
+        L.vo_batch_insert.argtypes = [
+            C.POINTER(_Data), C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_uint64,
+            C.c_uint32, C.c_double, C.c_int, C.POINTER(Stats)]
+        L.vo_build.restype = C.c_int
+        L.vo_build.argtypes = [
+            C.POINTER(_Data), C.c_uint32, C.c_uint32, C.c_double, C.c_uint64, C.c_uint64,
+            C.c_uint32, C.c_void_p, C.c_uint64, C.c_int, C.c_void_p, C.POINTER(C.c_uint32),
+            C.POINTER(Stats)]
+        L.vo_build_sequential.restype = C.c_int
+        L.vo_build_sequential.argtypes = [
+            C.POINTER(_Data), C.c_uint32, C.c_uint32, C.c_double, C.c_uint32, C.c_void_p,
+            C.c_uint64, C.c_void_p, C.POINTER(Stats)]
+        L.vo_search_batch.restype = C.c_int
+        L.vo_search_batch.argtypes = [
+            C.POINTER(_Data), C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_uint64,
+            C.c_uint32, C.c_uint32, C.c_int, C.c_void_p, C.c_void_p, C.POINTER(Stats)]
+        L.vo_brute_force.restype = C.c_int
+        L.vo_brute_force.argtypes = [
+            C.POINTER(_Data), C.c_void_p, C.c_uint64, C.c_uint32, C.c_int, C.c_void_p,
+            C.c_void_p]
+        L.vo_threads.restype = C.c_int
+        L.vo_threads.argtypes = [C.c_int]
+        _lib = L
+    return _lib
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+@dataclass
+class Dataset:
+    """Row-major points plus metric, kept alive for the C struct."""
+    points: np.ndarray
+    metric: int = L2SQ
+
+    def __post_init__(self):
+        self.points = np.ascontiguousarray(self.points)
+        assert self.points.ndim == 2
+        self._c = _Data(self.points.ctypes.data, self.points.shape[0], self.points.shape[1],
+                        dtype_code(self.points), int(self.metric))
+
+    @property
+    def n(self):
+        return self.points.shape[0]
+
+    @property
+    def d(self):
+        return self.points.shape[1]
+
+    @property
+    def dtype(self):
+        return dtype_code(self.points)
+
+    def c(self):
+        return C.byref(self._c)
+
+
+def distance(a: np.ndarray, b: np.ndarray, metric: int = L2SQ) -> float:
+    a = np.ascontiguousarray(a)
+    b = np.ascontiguousarray(b)
+    assert a.dtype == b.dtype and a.shape == b.shape and a.ndim == 1
+    return float(lib().vo_distance(_ptr(a), _ptr(b), a.shape[0], dtype_code(a), int(metric)))
+
+
+def greedy_search(ds: Dataset, graph: np.ndarray, start: int, query: np.ndarray, L: int, k: int,
+                  stats: Stats | None = None, check: bool = True):
+    """Alg. 1.  Returns (V_ids, V_dists, K_ids, K_dists)."""
+    graph = np.ascontiguousarray(graph, dtype=np.uint32)
+    query = np.ascontiguousarray(query, dtype=ds.points.dtype)
+    R = graph.shape[1]
+    cap = ds.n
+    v_ids = np.empty(cap, np.uint32)
+    v_d = np.empty(cap, np.float64)
+    k_ids = np.empty(k, np.uint32)
+    k_d = np.empty(k, np.float64)
+    nv = C.c_uint64(0)
+    rc = lib().vo_greedy_search(ds.c(), _ptr(graph), R, start, _ptr(query), L, k, _ptr(v_ids),
+                                _ptr(v_d), cap, C.byref(nv), _ptr(k_ids), _ptr(k_d),
+                                C.byref(stats) if stats is not None else None)
+    if check and rc != 0:
+        raise RuntimeError(f"vo_greedy_search rc={rc}")
+    n = nv.value
+    return v_ids[:n].copy(), v_d[:n].copy(), k_ids, k_d
+
+
+def prune(ds: Dataset, p_vec: np.ndarray, p_id: int, cand: np.ndarray, R: int, alpha: float,
+          stats: Stats | None = None) -> np.ndarray:
+    """prune(p, C, R) of Sec. 4.1; returns the selected ids in selection order."""
+    cand = np.ascontiguousarray(cand, dtype=np.uint32)
+    p_vec = np.ascontiguousarray(p_vec, dtype=ds.points.dtype)
+    out = np.empty(R, np.uint32)
+    cnt = lib().vo_prune(ds.c(), _ptr(p_vec), p_id, _ptr(cand), cand.shape[0], R, float(alpha),
+                         _ptr(out), C.byref(stats) if stats is not None else None)
+    return out[:cnt].copy()
+
+
+def start_vertex(ds: Dataset) -> int:
+    return int(lib().vo_start_vertex(ds.c()))
+
+
+def insertion_order(n: int, start: int, seed: int) -> np.ndarray:
+    order = np.empty(max(n - 1, 0), np.uint32)
+    lib().vo_insertion_order(n, start, seed, _ptr(order))
+    return order
+
+
+def schedule(m: int, theta: int) -> np.ndarray:
+    rounds = lib().vo_schedule(m, theta, None)
+    bounds = np.empty(rounds + 1, np.uint64)
+    lib().vo_schedule(m, theta, _ptr(bounds))
+    return bounds
+
+
+def empty_graph(n: int, R: int) -> np.ndarray:
+    return np.full((n, R), NONE, np.uint32)
+
+
+def insert(ds: Dataset, graph: np.ndarray, start: int, p: int, L: int, alpha: float,
+           stats: Stats | None = None) -> None:
+    assert graph.dtype == np.uint32 and graph.flags.c_contiguous
+    rc = lib().vo_insert(ds.c(), _ptr(graph), graph.shape[1], start, p, L, float(alpha),
+                         C.byref(stats) if stats is not None else None)
+    if rc:
+        raise RuntimeError(f"vo_insert rc={rc}")
+
+
+def batch_insert(ds: Dataset, graph: np.ndarray, start: int, batch: np.ndarray, L: int,
+                 alpha: float, threads: int = 1, stats: Stats | None = None) -> None:
+    assert graph.dtype == np.uint32 and graph.flags.c_contiguous
+    batch = np.ascontiguousarray(batch, dtype=np.uint32)
+    rc = lib().vo_batch_insert(ds.c(), _ptr(graph), graph.shape[1], start, _ptr(batch),
+                               batch.shape[0], L, float(alpha), threads,
+                               C.byref(stats) if stats is not None else None)
+    if rc:
+        raise RuntimeError(f"vo_batch_insert rc={rc}")
+
+
+def build(ds: Dataset, R: int, L: int, alpha: float, seed: int = 1, theta: int = 0,
+          start: int | None = None, order: np.ndarray | None = None, max_rounds: int = 0,
+          threads: int = 1, stats: Stats | None = None):
+    """Alg. 3.  Returns (graph[n,R] uint32, start)."""
+    graph = np.empty((ds.n, R), np.uint32)
+    s_out = C.c_uint32(0)
+    if order is not None:
+        order = np.ascontiguousarray(order, dtype=np.uint32)
+        assert order.shape[0] == ds.n - 1
+    rc = lib().vo_build(ds.c(), R, L, float(alpha), seed, theta,
+                        NONE if start is None else start,
+                        _ptr(order) if order is not None else None, max_rounds, threads,
+                        _ptr(graph), C.byref(s_out),
+                        C.byref(stats) if stats is not None else None)
+    if rc:
+        raise RuntimeError(f"vo_build rc={rc}")
+    return graph, int(s_out.value)
+
+
+def build_sequential(ds: Dataset, R: int, L: int, alpha: float, start: int, order: np.ndarray,
+                     stats: Stats | None = None) -> np.ndarray:
+    graph = np.empty((ds.n, R), np.uint32)
+    order = np.ascontiguousarray(order, dtype=np.uint32)
+    rc = lib().vo_build_sequential(ds.c(), R, L, float(alpha), start, _ptr(order),
+                                   order.shape[0], _ptr(graph),
+                                   C.byref(stats) if stats is not None else None)
+    if rc:
+        raise RuntimeError(f"vo_build_sequential rc={rc}")
+    return graph
+
+
+def _dist_out(ds: Dataset, shape):
+    return np.empty(shape, np.float32 if ds.dtype == F32 else np.int32)
+
+
+def search_batch(ds: Dataset, graph: np.ndarray, start: int, queries: np.ndarray, k: int, L: int,
+                 threads: int = 1, stats: Stats | None = None):
+    graph = np.ascontiguousarray(graph, dtype=np.uint32)
+    queries = np.ascontiguousarray(queries, dtype=ds.points.dtype)
+    nq = queries.shape[0]
+    ids = np.empty((nq, k), np.uint32)
+    dists = _dist_out(ds, (nq, k))
+    rc = lib().vo_search_batch(ds.c(), _ptr(graph), graph.shape[1], start, _ptr(queries), nq, k,
+                               L, threads, _ptr(ids), _ptr(dists),
+                               C.byref(stats) if stats is not None else None)
+    if rc:
+        raise RuntimeError(f"vo_search_batch rc={rc}")
+    return ids, dists
+
+
+def brute_force(ds: Dataset, queries: np.ndarray, k: int, threads: int = 0):
+    queries = np.ascontiguousarray(queries, dtype=ds.points.dtype)
+    nq = queries.shape[0]
+    ids = np.empty((nq, k), np.uint32)
+    dists = _dist_out(ds, (nq, k))
+    rc = lib().vo_brute_force(ds.c(), _ptr(queries), nq, k, threads, _ptr(ids), _ptr(dists))
+    if rc:
+        raise RuntimeError(f"vo_brute_force rc={rc}")
+    return ids, dists
+
+
+def threads(t: int = 0) -> int:
+    return int(lib().vo_threads(t))
