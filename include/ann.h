@@ -1,0 +1,166 @@
+/*
+ * ann.h -- C ABI of the MI355X (gfx950) graph-ANNS library.
+ *
+ * The library builds a Vamana/DiskANN-style proximity graph by deterministic
+ * prefix-doubling batch insertion (Alg. 3 of the paper: batchBuild /
+ * BatchInsert) and answers batched k-NN queries with greedy beam search
+ * (Alg. 1).  Every step runs in hand-written HIP kernels on one GPU.
+ *
+ * Conventions shared by all calls
+ *   - "dev" pointers are HIP device pointers, "host" pointers are ordinary
+ *     host memory.  Matrices are row-major and contiguous.  Device base
+ *     pointers must be 16-byte aligned.
+ *   - Distances: squared Euclidean (ANN_L2SQ, any dtype) or negative inner
+ *     product (ANN_MIPS, ANN_F32 only).  Smaller is closer (Sec. 2).  For
+ *     u8/i8 the distance is the exact int32; for f32 it is computed in fp32.
+ *   - Every "closest" is decided under the total order (distance, id).
+ *   - A graph is n rows of R uint32 ids (fixed-length edge lists, Sec. 4.5);
+ *     valid neighbours come first, unused slots hold ANN_NONE.
+ *   - Vertex ids are < 2^31.  Supported row sizes: d*sizeof(elem) a multiple
+ *     of 4 bytes; up to 512 B if also a multiple of 16, else up to 256 B
+ *     (u8/i8); f32 needs d % 4 == 0 and d <= 256.
+ *   - Every function returns ANN_OK (0) or a negative ann_status; on error
+ *     outputs are untouched, *out handles are NULL and ann_last_error()
+ *     describes the failure.  No exception or abort crosses this boundary.
+ *   - `stream` is a hipStream_t passed as void* (NULL = default stream).
+ *   - The library allocates its own scratch with hipMalloc and frees it
+ *     before returning; the caller owns every buffer it passes in.
+ */
+#ifndef ANN_H
+#define ANN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ANN_NONE 0xFFFFFFFFu
+
+typedef enum { ANN_U8 = 0, ANN_I8 = 1, ANN_F32 = 2 } ann_dtype;
+typedef enum { ANN_L2SQ = 0, ANN_MIPS = 1 } ann_metric;
+
+typedef enum {
+  ANN_OK = 0,
+  ANN_EINVAL = -1, /* null pointer, zero size, k > L, unsupported shape ... */
+  ANN_ENOMEM = -2, /* a device or host allocation failed                    */
+  ANN_EHIP = -3,   /* a HIP call failed; text in ann_last_error()           */
+  ANN_EINTERNAL = -4
+} ann_status;
+
+/* Opaque graph handle.  Owns the device memory of the n x R adjacency rows. */
+typedef struct ann_graph ann_graph;
+
+/* Optional knobs of ann_build.  Zero-initialise, then set what is needed.   */
+typedef struct {
+  uint64_t batch_cap;    /* theta, the batch-size bound of Sec. 3.1; 0 = max(1, n/50)  */
+  uint32_t start;        /* start vertex s, used only when use_start is non-zero       */
+  uint32_t use_start;    /* zero: s = point nearest the mean (ann_start_vertex)        */
+  const uint32_t* order; /* host, n-1 ids: insertion order; NULL = seeded shuffle      */
+  uint32_t visited_cap;  /* slots per search for the visited list; 0 = max(256, 4L).
+                            Searches that visit more are redone with enough room, so
+                            the result never depends on this value.                    */
+  uint32_t hash_bits;    /* log2 size of the per-search visited filter in LDS; 0 = auto.
+                            The filter only saves work; results do not depend on it.   */
+  uint64_t max_rounds;   /* stop after this many batches (0 = all): partial builds     */
+  uint32_t collect_stats;/* non-zero: count hops, distance evaluations, ... (slower)   */
+} ann_build_opts;
+
+typedef struct {
+  uint64_t n;
+  uint32_t d;
+  uint32_t R;
+  uint32_t dtype;
+  uint32_t metric;
+  uint32_t start;
+  uint64_t rounds; /* batches inserted so far */
+} ann_graph_info_t;
+
+typedef struct {
+  uint64_t searches;    /* greedy searches run                                   */
+  uint64_t hops;        /* vertices processed, summed over searches (|V|)        */
+  uint64_t evals;       /* distances taken in searches, re-evaluations included  */
+  uint64_t prunes;      /* step-1 prunes                                         */
+  uint64_t reprunes;    /* step-2 prunes of overflowing rows                     */
+  uint64_t appends;     /* step-2 rows that only appended                        */
+  uint64_t edges;       /* reverse edges grouped                                 */
+  uint64_t prune_evals; /* pair distances taken inside prune                     */
+  uint64_t redone;      /* searches redone because the visited list overflowed   */
+  uint64_t rounds;
+  double ms_search, ms_prune, ms_sort, ms_merge, ms_total; /* device time per phase */
+} ann_stats;
+
+/*
+ * batchBuild(P, s, R, L) of Alg. 3.  Inserts the points in a seeded random
+ * order in batches of size 2, 4, 8, ... bounded by theta.  Per batch:
+ * every point runs greedySearch (Alg. 1) with beam width L from s over the
+ * graph as it stood before the batch; its visited set is pruned to at most R
+ * out-neighbours with the alpha rule of Sec. 4.1 (drop p' when
+ * alpha*d(p*,p') <= d(p,p')); the new edges are reversed, grouped by
+ * destination with an on-device radix sort, appended in batch order, and rows
+ * that exceed R are pruned again.
+ *
+ *   points_dev  n x d elements of `dtype` (device)
+ *   alpha       > 0 (must be <= 1 for ANN_MIPS, Appendix A).  For u8/i8 it is
+ *               quantised to llround(alpha * 65536) / 65536.
+ *   seed        drives the insertion order (SplitMix64 Fisher-Yates)
+ *   opts        may be NULL
+ *   *out        receives the graph; free with ann_graph_free
+ * Blocks until the build is complete.
+ */
+int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric,
+              uint32_t R, uint32_t L, float alpha, uint64_t seed, const ann_build_opts* opts,
+              void* stream, ann_graph** out);
+
+/*
+ * BatchInsert(P') of Alg. 3 on an existing graph: inserts the `b` points whose
+ * ids are in ids_host (all < n, not yet inserted, none equal to the start
+ * vertex) as ONE batch.  `points_dev` must be the array the graph was built
+ * over.  Blocks until done.
+ */
+int ann_insert_batch(ann_graph* g, const void* points_dev, const uint32_t* ids_host, uint64_t b,
+                     uint32_t L, float alpha, void* stream);
+
+/*
+ * greedySearch(q, s, L, k) of Alg. 1 for nq queries (one wavefront each).
+ *   queries_dev  nq x d elements of the graph's dtype (device)
+ *   ids_dev      nq x k uint32 (device): the k closest found, ascending by
+ *                (distance, id); ANN_NONE where fewer than k were reached
+ *   dists_dev    nq x k int32 (u8/i8) or float (f32); INT32_MAX / +inf padding
+ * Requires 1 <= k <= L <= 512.  Asynchronous on `stream`.
+ */
+int ann_search(const ann_graph* g, const void* points_dev, const void* queries_dev, uint64_t nq,
+               uint32_t k, uint32_t L, uint32_t* ids_dev, void* dists_dev, void* stream);
+
+/* Start vertex used by ann_build when none is given: the point nearest
+ * (squared L2) to the mean of all points, smallest id on ties.  Exact for
+ * u8/i8; fp64 for f32.  Blocks.                                             */
+int ann_start_vertex(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, void* stream,
+                     uint32_t* start_out);
+
+/* Wrap adjacency rows given on the host (n x R, ANN_NONE padded) as a graph. */
+int ann_graph_from_host(const uint32_t* rows_host, uint64_t n, uint32_t d, ann_dtype dtype,
+                        ann_metric metric, uint32_t R, uint32_t start, ann_graph** out);
+
+/* Copy the n x R adjacency rows to host memory.  Blocks.                    */
+int ann_graph_copy_neighbors(const ann_graph* g, uint32_t* rows_host);
+
+/* Device pointer to the n x R adjacency rows (owned by the graph).          */
+const uint32_t* ann_graph_device_rows(const ann_graph* g);
+
+int ann_graph_info(const ann_graph* g, ann_graph_info_t* info);
+int ann_get_stats(const ann_graph* g, ann_stats* stats); /* cumulative over build + inserts */
+void ann_graph_free(ann_graph* g);
+
+/* Stable LSD radix sort of `count` 64-bit keys by bits [32, 32+key_bits) only
+ * (the grouping step of BatchInsert; exposed for tests).  In place on
+ * keys_dev; blocks.                                                         */
+int ann_sort_edges(uint64_t* keys_dev, uint64_t count, uint32_t key_bits, void* stream);
+
+/* Thread-local description of the last error on this thread ("" if none).   */
+const char* ann_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,244 @@
+"""Thin ctypes binding of the C ABI in include/ann.h.
+
+Argument marshalling only: every step of the path runs in the HIP kernels of libannmi.so.
+PyTorch (ROCm) tensors serve as device allocations and give the current stream.  There is no
+CPU fallback: if the library has not been built, loading fails with an error.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+NONE = 0xFFFFFFFF
+U8, I8, F32 = 0, 1, 2
+L2SQ, MIPS = 0, 1
+
+
+class AnnError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"ann error {code}: {msg}")
+        self.code = code
+
+
+class BuildOpts(C.Structure):
+    _fields_ = [
+        ("batch_cap", C.c_uint64),
+        ("start", C.c_uint32),
+        ("use_start", C.c_uint32),
+        ("order", C.c_void_p),
+        ("visited_cap", C.c_uint32),
+        ("hash_bits", C.c_uint32),
+        ("max_rounds", C.c_uint64),
+        ("collect_stats", C.c_uint32),
+    ]
+
+
+class GraphInfo(C.Structure):
+    _fields_ = [("n", C.c_uint64), ("d", C.c_uint32), ("R", C.c_uint32), ("dtype", C.c_uint32),
+                ("metric", C.c_uint32), ("start", C.c_uint32), ("rounds", C.c_uint64)]
+
+
+class Stats(C.Structure):
+    _fields_ = [(k, C.c_uint64) for k in ("searches", "hops", "evals", "prunes", "reprunes", "appends",
+                                           "edges", "prune_evals", "redone", "rounds")] + \
+               [(k, C.c_double) for k in ("ms_search", "ms_prune", "ms_sort", "ms_merge", "ms_total")]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+EXPORTS = [
+    "ann_build", "ann_insert_batch", "ann_search", "ann_start_vertex", "ann_graph_from_host",
+    "ann_graph_copy_neighbors", "ann_graph_device_rows", "ann_graph_info", "ann_get_stats",
+    "ann_graph_free", "ann_sort_edges", "ann_last_error",
+]
+
+_lib = None
+
+
+def lib():
+    """Load libannmi.so (built in-tree by build.build_library); raise if it is missing."""
+    global _lib
+    if _lib is None:
+        path = _build.library_path()
+        if not os.path.exists(path):
+            raise ImportError(f"{path} not found: run __graft_entry__.build() "
+                              "(or paper_2305_04359_amd/build.py) first")
+        # PyTorch ships its own HIP runtime (same SONAME as the one hipcc links against).  Load it
+        # first so that this library binds to that copy: two runtimes in one process do not
+        # share a device context.
+        import torch  # noqa: F401
+        L = C.CDLL(path)
+        vp, u64, u32 = C.c_void_p, C.c_uint64, C.c_uint32
+        L.ann_build.restype = C.c_int
+        L.ann_build.argtypes = [vp, u64, u32, C.c_int, C.c_int, u32, u32, C.c_float, u64,
+                                C.POINTER(BuildOpts), vp, C.POINTER(vp)]
+        L.ann_insert_batch.restype = C.c_int
+        L.ann_insert_batch.argtypes = [vp, vp, vp, u64, u32, C.c_float, vp]
+        L.ann_search.restype = C.c_int
+        L.ann_search.argtypes = [vp, vp, vp, u64, u32, u32, vp, vp, vp]
+        L.ann_start_vertex.restype = C.c_int
+        L.ann_start_vertex.argtypes = [vp, u64, u32, C.c_int, vp, C.POINTER(u32)]
+        L.ann_graph_from_host.restype = C.c_int
+        L.ann_graph_from_host.argtypes = [vp, u64, u32, C.c_int, C.c_int, u32, u32, C.POINTER(vp)]
+        L.ann_graph_copy_neighbors.restype = C.c_int
+        L.ann_graph_copy_neighbors.argtypes = [vp, vp]
+        L.ann_graph_device_rows.restype = vp
+        L.ann_graph_device_rows.argtypes = [vp]
+        L.ann_graph_info.restype = C.c_int
+        L.ann_graph_info.argtypes = [vp, C.POINTER(GraphInfo)]
+        L.ann_get_stats.restype = C.c_int
+        L.ann_get_stats.argtypes = [vp, C.POINTER(Stats)]
+        L.ann_graph_free.restype = None
+        L.ann_graph_free.argtypes = [vp]
+        L.ann_sort_edges.restype = C.c_int
+        L.ann_sort_edges.argtypes = [vp, u64, u32, vp]
+        L.ann_last_error.restype = C.c_char_p
+        L.ann_last_error.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise AnnError(rc, lib().ann_last_error().decode())
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _dtype_code(t) -> int:
+    torch = _torch()
+    if t.dtype == torch.uint8:
+        return U8
+    if t.dtype == torch.int8:
+        return I8
+    if t.dtype == torch.float32:
+        return F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _stream_ptr():
+    return C.c_void_p(_torch().cuda.current_stream().cuda_stream)
+
+
+def _dev2d(t, name):
+    if not t.is_cuda or t.dim() != 2 or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous 2-D device tensor")
+    return t
+
+
+class Graph:
+    """Owner of an ann_graph handle."""
+
+    def __init__(self, handle):
+        self._h = C.c_void_p(handle)
+
+    def close(self):
+        if self._h:
+            lib().ann_graph_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def handle(self):
+        return self._h
+
+    def info(self) -> GraphInfo:
+        gi = GraphInfo()
+        _check(lib().ann_graph_info(self._h, C.byref(gi)))
+        return gi
+
+    def stats(self) -> dict:
+        st = Stats()
+        _check(lib().ann_get_stats(self._h, C.byref(st)))
+        return st.as_dict()
+
+    def neighbors(self) -> np.ndarray:
+        gi = self.info()
+        out = np.empty((gi.n, gi.R), np.uint32)
+        _check(lib().ann_graph_copy_neighbors(self._h, out.ctypes.data_as(C.c_void_p)))
+        return out
+
+
+def ann_build(points, R, L, alpha, seed=1, metric=L2SQ, batch_cap=0, start=None, order=None,
+              visited_cap=0, hash_bits=0, max_rounds=0, collect_stats=False) -> Graph:
+    """batchBuild of Alg. 3 over a device tensor of points (n x d; uint8, int8 or float32)."""
+    points = _dev2d(points, "points")
+    o = BuildOpts()
+    o.batch_cap = batch_cap
+    o.use_start = 0 if start is None else 1
+    o.start = 0 if start is None else int(start)
+    keep = None
+    if order is not None:
+        keep = np.ascontiguousarray(order, dtype=np.uint32)
+        if keep.shape != (points.shape[0] - 1,):
+            raise ValueError("order must hold n-1 ids")
+        o.order = keep.ctypes.data
+    o.visited_cap = visited_cap
+    o.hash_bits = hash_bits
+    o.max_rounds = max_rounds
+    o.collect_stats = 1 if collect_stats else 0
+    h = C.c_void_p()
+    _check(lib().ann_build(points.data_ptr(), points.shape[0], points.shape[1], _dtype_code(points),
+                           int(metric), R, L, float(alpha), seed, C.byref(o), _stream_ptr(), C.byref(h)))
+    return Graph(h.value)
+
+
+def ann_insert_batch(graph: Graph, points, ids, L, alpha) -> None:
+    points = _dev2d(points, "points")
+    ids = np.ascontiguousarray(ids, dtype=np.uint32)
+    _check(lib().ann_insert_batch(graph.handle, points.data_ptr(), ids.ctypes.data_as(C.c_void_p),
+                                  ids.shape[0], L, float(alpha), _stream_ptr()))
+
+
+def ann_search(graph: Graph, points, queries, k, L, ids_out=None, dists_out=None):
+    """greedySearch of Alg. 1 for each row of `queries`; returns (ids, dists) device tensors."""
+    torch = _torch()
+    points = _dev2d(points, "points")
+    queries = _dev2d(queries, "queries")
+    if queries.dtype != points.dtype or queries.shape[1] != points.shape[1]:
+        raise ValueError("queries must match points in dtype and dimension")
+    nq = queries.shape[0]
+    if ids_out is None:
+        ids_out = torch.empty((nq, k), dtype=torch.int32, device=points.device)
+    if dists_out is None:
+        dists_out = torch.empty((nq, k), dtype=torch.float32 if points.dtype == torch.float32 else torch.int32,
+                                device=points.device)
+    _check(lib().ann_search(graph.handle, points.data_ptr(), queries.data_ptr(), nq, k, L,
+                            ids_out.data_ptr(), dists_out.data_ptr(), _stream_ptr()))
+    return ids_out, dists_out
+
+
+def ann_start_vertex(points) -> int:
+    points = _dev2d(points, "points")
+    s = C.c_uint32(0)
+    _check(lib().ann_start_vertex(points.data_ptr(), points.shape[0], points.shape[1], _dtype_code(points),
+                                  _stream_ptr(), C.byref(s)))
+    return int(s.value)
+
+
+def ann_graph_from_host(rows: np.ndarray, d: int, dtype: int, metric: int, start: int) -> Graph:
+    rows = np.ascontiguousarray(rows, dtype=np.uint32)
+    h = C.c_void_p()
+    _check(lib().ann_graph_from_host(rows.ctypes.data_as(C.c_void_p), rows.shape[0], d, dtype, metric,
+                                     rows.shape[1], start, C.byref(h)))
+    return Graph(h.value)
+
+
+def ann_sort_edges(keys, key_bits: int) -> None:
+    """In-place stable sort of a device int64 tensor of edge keys by bits [32, 32+key_bits)."""
+    if not keys.is_cuda or keys.dim() != 1 or not keys.is_contiguous() or keys.element_size() != 8:
+        raise ValueError("keys must be a contiguous 1-D device tensor of 64-bit integers")
+    _check(lib().ann_sort_edges(keys.data_ptr(), keys.shape[0], key_bits, _stream_ptr()))

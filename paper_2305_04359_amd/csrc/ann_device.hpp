@@ -1,0 +1,270 @@
+// Device-side building blocks shared by the search, prune and merge kernels (gfx950, wave64).
+//
+// Work decomposition used everywhere: one wavefront owns one search / one prune.  Distances from
+// one "query" vector to a set of graph vertices are taken eight vertices at a time: the 64 lanes
+// split into 8 groups of 8 lanes, group g handles one vertex, and lane `sub` of the group loads
+// the 16-byte (or 4-byte) pieces sub, sub+8, sub+16, ... of that vertex' row, so one wave-wide
+// load instruction reads whole, contiguous rows.  Partial sums are combined inside each group
+// with three DPP steps.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace annmi {
+
+using u32 = uint32_t;
+using u64 = uint64_t;
+using i32 = int32_t;
+using i64 = int64_t;
+
+constexpr u32 NONE_ID = 0xFFFFFFFFu;
+constexpr u64 KEY_INF = ~0ull;
+constexpr int WAVE = 64;
+constexpr int LPC = 8;  // lanes per candidate
+
+// element kind + metric
+enum Kind : int { K_U8 = 0, K_I8 = 1, K_F32_L2 = 2, K_F32_IP = 3 };
+
+template <int KIND>
+struct KindTraits {
+  static constexpr bool is_int = (KIND == K_U8 || KIND == K_I8);
+};
+
+// ---------------------------------------------------------------------------------------------
+// keys: (order-preserving 32-bit distance) << 32 | id << 1 | flag.  Comparing keys as u64
+// compares (distance, id).  The flag marks "processed" in the beam and is 0 elsewhere.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ u32 dkey_from_int(i32 d) { return (u32)d ^ 0x80000000u; }
+__device__ __forceinline__ i32 int_from_dkey(u32 k) { return (i32)(k ^ 0x80000000u); }
+__device__ __forceinline__ u32 dkey_from_float(float f) {
+  u32 u = __float_as_uint(f + 0.0f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float float_from_dkey(u32 k) {
+  u32 u = (k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k;
+  return __uint_as_float(u);
+}
+__device__ __forceinline__ u64 make_key(u32 dkey, u32 id) { return ((u64)dkey << 32) | ((u64)id << 1); }
+__device__ __forceinline__ u32 key_id(u64 k) { return (u32)(k & 0xFFFFFFFFull) >> 1; }
+__device__ __forceinline__ u32 key_dkey(u64 k) { return (u32)(k >> 32); }
+
+// ---------------------------------------------------------------------------------------------
+// wave helpers
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ u64 ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
+__device__ __forceinline__ u64 lanemask_lt(int lane) { return (1ull << lane) - 1ull; }
+
+__device__ __forceinline__ u32 readlane_u32(u32 v, int lane) {
+  return (u32)__builtin_amdgcn_readlane((int)v, lane);
+}
+__device__ __forceinline__ u64 readlane_u64(u64 v, int lane) {
+  u32 lo = readlane_u32((u32)v, lane);
+  u32 hi = readlane_u32((u32)(v >> 32), lane);
+  return ((u64)hi << 32) | lo;
+}
+
+__device__ __forceinline__ u64 wave_min_u64(u64 v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    u32 lo = (u32)__shfl_xor((int)(u32)v, off, WAVE);
+    u32 hi = (u32)__shfl_xor((int)(u32)(v >> 32), off, WAVE);
+    u64 o = ((u64)hi << 32) | lo;
+    v = o < v ? o : v;
+  }
+  return v;
+}
+
+// Sum over the 8 lanes of a group; every lane of the group receives the same total.
+// quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror.
+__device__ __forceinline__ i32 group_sum(i32 v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, true);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, true);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, true);
+  return v;
+}
+__device__ __forceinline__ float group_sum(float v) {
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true));
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true));
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, true));
+  return v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// row pieces
+// ---------------------------------------------------------------------------------------------
+template <int VEC>
+struct Piece;
+template <>
+struct Piece<16> {
+  u32 w[4];
+};
+template <>
+struct Piece<4> {
+  u32 w[1];
+};
+
+template <int VEC>
+__device__ __forceinline__ Piece<VEC> load_piece(const char* p) {
+  Piece<VEC> r;
+  if constexpr (VEC == 16) {
+    uint4 t = *reinterpret_cast<const uint4*>(p);
+    r.w[0] = t.x;
+    r.w[1] = t.y;
+    r.w[2] = t.z;
+    r.w[3] = t.w;
+  } else {
+    r.w[0] = *reinterpret_cast<const u32*>(p);
+  }
+  return r;
+}
+template <int VEC>
+__device__ __forceinline__ Piece<VEC> zero_piece() {
+  Piece<VEC> r;
+#pragma unroll
+  for (int i = 0; i < VEC / 4; ++i) r.w[i] = 0;
+  return r;
+}
+
+// Where the vectors live.
+struct VecTable {
+  const char* base;
+  u64 row_bytes;
+  u32 npieces;  // pieces of VEC bytes per row
+};
+
+// The vector every distance is measured from, spread over the 8 lanes of each group (all 8
+// groups hold the same copy).
+template <int KIND, int VEC, int NCH>
+struct QueryRegs {
+  Piece<VEC> q[NCH];
+  i32 qq;  // <q,q> for the integer kinds
+};
+
+template <int KIND, int VEC, int NCH>
+__device__ __forceinline__ QueryRegs<KIND, VEC, NCH> load_query(const char* row, u32 npieces, int lane) {
+  QueryRegs<KIND, VEC, NCH> Q;
+  const int sub = lane & (LPC - 1);
+  i32 acc = 0;
+#pragma unroll
+  for (int u = 0; u < NCH; ++u) {
+    u32 pc = sub + LPC * u;
+    Q.q[u] = pc < npieces ? load_piece<VEC>(row + (u64)pc * VEC) : zero_piece<VEC>();
+    if constexpr (KIND == K_U8) {
+#pragma unroll
+      for (int i = 0; i < VEC / 4; ++i) acc = (i32)__builtin_amdgcn_udot4(Q.q[u].w[i], Q.q[u].w[i], (u32)acc, false);
+    } else if constexpr (KIND == K_I8) {
+#pragma unroll
+      for (int i = 0; i < VEC / 4; ++i) acc = __builtin_amdgcn_sdot4((i32)Q.q[u].w[i], (i32)Q.q[u].w[i], acc, false);
+    }
+  }
+  Q.qq = KindTraits<KIND>::is_int ? group_sum(acc) : 0;
+  return Q;
+}
+
+// Distance key from the lane-local pieces of one row; all 8 lanes of the group get the result.
+template <int KIND, int VEC, int NCH>
+__device__ __forceinline__ u32 distance_key(const QueryRegs<KIND, VEC, NCH>& Q, const Piece<VEC> (&x)[NCH]) {
+  if constexpr (KIND == K_U8) {
+    u32 xx = 0, qx = 0;
+#pragma unroll
+    for (int u = 0; u < NCH; ++u)
+#pragma unroll
+      for (int i = 0; i < VEC / 4; ++i) {
+        xx = __builtin_amdgcn_udot4(x[u].w[i], x[u].w[i], xx, false);
+        qx = __builtin_amdgcn_udot4(Q.q[u].w[i], x[u].w[i], qx, false);
+      }
+    i32 part = (i32)xx - 2 * (i32)qx;
+    return dkey_from_int(group_sum(part) + Q.qq);
+  } else if constexpr (KIND == K_I8) {
+    i32 xx = 0, qx = 0;
+#pragma unroll
+    for (int u = 0; u < NCH; ++u)
+#pragma unroll
+      for (int i = 0; i < VEC / 4; ++i) {
+        xx = __builtin_amdgcn_sdot4((i32)x[u].w[i], (i32)x[u].w[i], xx, false);
+        qx = __builtin_amdgcn_sdot4((i32)Q.q[u].w[i], (i32)x[u].w[i], qx, false);
+      }
+    return dkey_from_int(group_sum(xx - 2 * qx) + Q.qq);
+  } else {
+    float acc = 0.0f;
+#pragma unroll
+    for (int u = 0; u < NCH; ++u)
+#pragma unroll
+      for (int i = 0; i < VEC / 4; ++i) {
+        float a = __uint_as_float(Q.q[u].w[i]);
+        float b = __uint_as_float(x[u].w[i]);
+        if constexpr (KIND == K_F32_L2) {
+          float t = a - b;
+          acc = __builtin_fmaf(t, t, acc);
+        } else {
+          acc = __builtin_fmaf(a, b, acc);
+        }
+      }
+    acc = group_sum(acc);
+    return dkey_from_float(KIND == K_F32_IP ? -acc : acc);
+  }
+}
+
+// How many groups-of-8 candidates are loaded before any arithmetic starts (memory-level
+// parallelism against registers).
+template <int VEC, int NCH>
+struct PassBatch {
+  static constexpr int budget = (VEC == 16) ? 8 : 16;
+  static constexpr int value = (budget / NCH) < 1 ? 1 : ((budget / NCH) > 8 ? 8 : (budget / NCH));
+};
+
+// Distances from Q to the candidates id_at(0..cnt), cnt <= 64.  Lane l ends up with the key of
+// candidate cand_of_lane(l) = 8*(l&7) + (l>>3) when that index is < cnt.
+__device__ __forceinline__ u32 cand_of_lane(int lane) { return (u32)(8 * (lane & 7) + (lane >> 3)); }
+
+template <int KIND, int VEC, int NCH, class IdAt>
+__device__ __forceinline__ u32 eval_up_to_64(const VecTable& T, const QueryRegs<KIND, VEC, NCH>& Q,
+                                             IdAt id_at, u32 cnt, int lane) {
+  constexpr int PB = PassBatch<VEC, NCH>::value;
+  const int sub = lane & (LPC - 1);
+  const u32 grp = (u32)lane >> 3;
+  const u32 npass = (cnt + 7u) >> 3;
+  u32 result = 0;
+  for (u32 t0 = 0; t0 < npass; t0 += PB) {
+    Piece<VEC> x[PB][NCH];
+#pragma unroll
+    for (int tt = 0; tt < PB; ++tt) {
+      const u32 c = 8u * (t0 + tt) + grp;
+      const bool ok = c < cnt;
+      const u32 id = ok ? id_at(c) : 0u;
+      const char* row = T.base + (u64)id * T.row_bytes;
+#pragma unroll
+      for (int u = 0; u < NCH; ++u) {
+        const u32 pc = sub + LPC * u;
+        x[tt][u] = (ok && pc < T.npieces) ? load_piece<VEC>(row + (u64)pc * VEC) : zero_piece<VEC>();
+      }
+    }
+#pragma unroll
+    for (int tt = 0; tt < PB; ++tt) {
+      const u32 dk = distance_key<KIND, VEC, NCH>(Q, x[tt]);
+      if ((u32)sub == t0 + tt) result = dk;
+    }
+  }
+  return result;
+}
+
+// alpha * d(p*,p') <= d(p,p')  (Sec. 4.1).  Integer kinds: alpha is held as a16 = round(alpha*2^16)
+// and the test is exact in 64-bit integers; float kinds: one fp32 product.
+struct AlphaParam {
+  i64 a16;
+  float af;
+};
+template <int KIND>
+__device__ __forceinline__ bool alpha_dominates(const AlphaParam& A, u32 dkey_star_cand, u32 dkey_p_cand) {
+  if constexpr (KindTraits<KIND>::is_int) {
+    i64 lhs = A.a16 * (i64)int_from_dkey(dkey_star_cand);
+    i64 rhs = (i64)int_from_dkey(dkey_p_cand) * 65536;
+    return lhs <= rhs;
+  } else {
+    float prod = A.af * float_from_dkey(dkey_star_cand);
+    return prod <= float_from_dkey(dkey_p_cand);
+  }
+}
+
+}  // namespace annmi

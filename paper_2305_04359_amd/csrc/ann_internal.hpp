@@ -1,0 +1,103 @@
+// Host-visible declarations shared by the translation units of the library.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace annmi {
+
+using u32 = uint32_t;
+using u64 = uint64_t;
+
+// Which template instance serves a (dtype, metric, d) combination.
+struct DistCfg {
+  int kind;       // Kind
+  int vec;        // bytes per load: 16 or 4
+  int nch;        // pieces per lane: 1, 2, 4 or 8
+  u32 npieces;    // pieces per row
+  u64 row_bytes;  // d * sizeof(element)
+};
+
+// Device-side counters (all commutative integer sums).
+struct DevCounters {
+  unsigned long long searches, hops, evals, prunes, reprunes, appends, edges, prune_evals;
+};
+
+struct SearchArgs {
+  const char* points;     // vectors of the graph's vertices
+  const u32* graph;       // n x R
+  const char* queries;    // query vectors (the points themselves during a build)
+  const u32* qidx;        // optional: query i is row qidx[i] of `queries`
+  u64 qrow_bytes;
+  u32 nq;
+  u32 R;
+  u32 start;
+  u32 L;
+  u32 k;
+  u32 hash_bits;
+  // build: visited list, one slot of vis_cap keys per search (may be null)
+  u64* vis;
+  u32* nvis;
+  u32 vis_cap;
+  // query: results (may be null)
+  u32* out_ids;
+  void* out_dists;
+  DevCounters* counters;  // may be null
+};
+
+struct PruneArgs {
+  const char* points;
+  u32* graph;  // rows of the batch points are written
+  const u32* qidx;      // batch point ids
+  const u32* slotmap;   // optional: search i belongs to batch slot slotmap[i]
+  u32 nq;
+  u32 R;
+  const u64* vis;
+  const u32* nvis;
+  u32 vis_cap;
+  u64* vis_rw;          // same memory as vis: lists longer than the LDS buffer are pruned in place
+  u64* edges;           // batch_size x R keys (dest << 32 | source), ~0 in unused slots
+  u32* overflow_count;  // searches whose visited list did not fit
+  u32* overflow_list;   // their indices
+  long long a16;
+  float af;
+  DevCounters* counters;
+};
+
+struct MergeArgs {
+  const char* points;
+  u32* graph;
+  u32 R;
+  u64* keys;  // sorted edge keys (dest << 32 | source)
+  u64 nkeys;
+  const u32* seg_count;  // number of segments
+  const u32* seg_start;  // first key of each segment
+  u64* arena;            // spill space for candidate lists that do not fit in LDS
+  u64 arena_cap;
+  unsigned long long* arena_top;
+  u32* error_flag;
+  long long a16;
+  float af;
+  DevCounters* counters;
+};
+
+constexpr u32 PRUNE_LDS_CAP = 768;  // candidate keys held in LDS by the prune / merge kernels
+
+// launchers (each returns the hipGetLastError() of its launches)
+hipError_t launch_search(const DistCfg& cfg, const SearchArgs& a, hipStream_t s);
+hipError_t launch_prune(const DistCfg& cfg, const PruneArgs& a, hipStream_t s);
+hipError_t launch_segments(const u64* keys, u64 nkeys, u32* seg_count, u32* seg_start, hipStream_t s);
+hipError_t launch_merge(const DistCfg& cfg, const MergeArgs& a, u32 grid, hipStream_t s);
+
+// stable LSD radix sort of 64-bit keys on bits [32, 32+key_bits); result is left in `keys`
+// (`tmp` holds `count` keys, `hist` holds radix_hist_entries(count) u32)
+u64 radix_hist_entries(u64 count);
+hipError_t radix_sort_edges(u64* keys, u64* tmp, u32* hist, u64 count, u32 key_bits, hipStream_t s);
+
+// start vertex (point nearest the mean)
+hipError_t start_vertex_device(const void* points, u64 n, u32 d, int dtype, hipStream_t s, u32* start_out);
+
+u32 search_lds_bytes(u32 L, u32 hash_bits);
+u32 default_hash_bits(u32 L);
+
+}  // namespace annmi

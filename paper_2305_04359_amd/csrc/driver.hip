@@ -1,0 +1,611 @@
+// Host side of the library: the C ABI of include/ann.h, the prefix-doubling schedule of Alg. 3
+// (batchBuild) and the per-batch launch sequence of BatchInsert.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/ann.h"
+#include "ann_internal.hpp"
+
+using namespace annmi;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof(buf), fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                          \
+  do {                                                                                         \
+    hipError_t e_ = (expr);                                                                    \
+    if (e_ != hipSuccess)                                                                      \
+      return fail(e_ == hipErrorOutOfMemory ? ANN_ENOMEM : ANN_EHIP, "%s: %s", #expr,          \
+                  hipGetErrorString(e_));                                                      \
+  } while (0)
+
+// device buffer freed on scope exit
+struct DevBuf {
+  void* p = nullptr;
+  ~DevBuf() { release(); }
+  void release() {
+    if (p) (void)hipFree(p);
+    p = nullptr;
+  }
+  hipError_t alloc(size_t bytes) {
+    release();
+    return hipMalloc(&p, bytes ? bytes : 16);
+  }
+  template <typename T>
+  T* as() const {
+    return static_cast<T*>(p);
+  }
+};
+
+bool make_cfg(uint32_t d, int dtype, int metric, DistCfg* cfg, std::string* why) {
+  const u64 esz = dtype == ANN_F32 ? 4 : 1;
+  const u64 rb = (u64)d * esz;
+  if (dtype != ANN_U8 && dtype != ANN_I8 && dtype != ANN_F32) {
+    *why = "unknown dtype";
+    return false;
+  }
+  if (metric != ANN_L2SQ && metric != ANN_MIPS) {
+    *why = "unknown metric";
+    return false;
+  }
+  if (metric == ANN_MIPS && dtype != ANN_F32) {
+    *why = "ANN_MIPS is supported for ANN_F32 only";
+    return false;
+  }
+  if (d == 0 || rb % 4 != 0) {
+    *why = "row size must be a positive multiple of 4 bytes";
+    return false;
+  }
+  cfg->row_bytes = rb;
+  cfg->kind = dtype == ANN_U8 ? 0 : dtype == ANN_I8 ? 1 : (metric == ANN_L2SQ ? 2 : 3);
+  if (rb % 16 == 0) {
+    cfg->vec = 16;
+    cfg->npieces = (u32)(rb / 16);
+  } else {
+    cfg->vec = 4;
+    cfg->npieces = (u32)(rb / 4);
+  }
+  const u32 per_lane = (cfg->npieces + 7) / 8;
+  int nch = 1;
+  while ((u32)nch < per_lane) nch *= 2;
+  if (dtype == ANN_F32) {
+    if (cfg->vec != 16) {
+      *why = "f32 needs d % 4 == 0";
+      return false;
+    }
+    if (nch < 2) nch = 2;
+    if (nch > 8) {
+      *why = "f32 rows above 1024 bytes are not supported";
+      return false;
+    }
+  } else if (cfg->vec == 16) {
+    if (nch > 4) {
+      *why = "u8/i8 rows above 512 bytes are not supported";
+      return false;
+    }
+  } else {
+    if (nch < 2) nch = 2;
+    if (nch > 8) {
+      *why = "u8/i8 rows that are not a multiple of 16 bytes must be at most 256 bytes";
+      return false;
+    }
+  }
+  cfg->nch = nch;
+  return true;
+}
+
+u32 bits_for(u64 n) {  // smallest b with 2^b - 1 >= n
+  u32 b = 1;
+  while (((1ull << b) - 1ull) < n) ++b;
+  return b;
+}
+
+u64 splitmix64(u64& state) {
+  u64 z = (state += 0x9E3779B97F4A7C15ull);
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+}  // namespace
+
+struct ann_graph {
+  u64 n = 0;
+  u32 d = 0, R = 0;
+  int dtype = 0, metric = 0;
+  u32 start = 0;
+  u64 rounds = 0;
+  DistCfg cfg{};
+  u32* rows = nullptr;            // device, n x R
+  DevCounters* counters = nullptr;  // device
+  ann_stats stats{};
+  u32 hash_bits = 0;
+  u32 visited_cap = 0;
+  bool collect = false;
+};
+
+namespace {
+
+// Scratch of one BatchInsert call, sized for `bmax` points.
+struct BatchScratch {
+  u64 bmax = 0;
+  u32 vis_cap = 0;
+  DevBuf qidx, vis, nvis, edges, edges_tmp, hist, seg_start, small, ovf_list, arena;
+  u64 arena_cap = 0;
+  // small: [0] overflow_count u32, [1] seg_count u32, [2] error flag u32, [4..5] arena_top u64
+  int alloc(u64 b, u32 R, u32 cap) {
+    bmax = b;
+    vis_cap = cap;
+    const u64 E = b * R;
+    // a spilled candidate list is longer than PRUNE_LDS_CAP and has at most R old entries
+    arena_cap = E + (u64)R * (E / (PRUNE_LDS_CAP - R) + 1);
+    HIP_TRY(qidx.alloc(b * 4));
+    HIP_TRY(vis.alloc(b * cap * 8));
+    HIP_TRY(nvis.alloc(b * 4));
+    HIP_TRY(edges.alloc(E * 8));
+    HIP_TRY(edges_tmp.alloc(E * 8));
+    HIP_TRY(hist.alloc(radix_hist_entries(E) * 4));
+    HIP_TRY(seg_start.alloc(E * 4));
+    HIP_TRY(small.alloc(64));
+    HIP_TRY(ovf_list.alloc(b * 4));
+    HIP_TRY(arena.alloc(arena_cap * 8));
+    return ANN_OK;
+  }
+};
+
+struct PhaseTimer {
+  hipEvent_t ev[5]{};
+  bool on = false;
+  int init(bool enable) {
+    on = enable;
+    if (!on) return ANN_OK;
+    for (auto& e : ev) HIP_TRY(hipEventCreate(&e));
+    return ANN_OK;
+  }
+  void mark(int i, hipStream_t s) {
+    if (on) (void)hipEventRecord(ev[i], s);
+  }
+  ~PhaseTimer() {
+    if (on)
+      for (auto& e : ev)
+        if (e) (void)hipEventDestroy(e);
+  }
+};
+
+// BatchInsert(P') of Alg. 3 for the b ids in ids_host (device copy made here).
+int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u32* ids_dev, u64 b, u32 L,
+                 float alpha, BatchScratch& S, PhaseTimer& tm, hipStream_t st) {
+  if (b == 0) return ANN_OK;
+  const u32 R = g->R;
+  const u64 E = b * R;
+  const long long a16 = llround((double)alpha * 65536.0);
+  u32* small = S.small.as<u32>();
+  DevCounters* ctr = g->collect ? g->counters : nullptr;
+
+  HIP_TRY(hipMemsetAsync(small, 0, 64, st));
+  tm.mark(0, st);
+
+  // step 1a: greedySearch(p, s, L, 1) over the frozen graph, visited lists to scratch
+  SearchArgs sa{};
+  sa.points = static_cast<const char*>(points);
+  sa.graph = g->rows;
+  sa.queries = static_cast<const char*>(points);
+  sa.qidx = ids_dev;
+  sa.qrow_bytes = g->cfg.row_bytes;
+  sa.nq = (u32)b;
+  sa.R = R;
+  sa.start = g->start;
+  sa.L = L;
+  sa.k = 1;
+  sa.hash_bits = g->hash_bits ? g->hash_bits : default_hash_bits(L);
+  sa.vis = S.vis.as<u64>();
+  sa.nvis = S.nvis.as<u32>();
+  sa.vis_cap = S.vis_cap;
+  sa.counters = ctr;
+  HIP_TRY(launch_search(g->cfg, sa, st));
+  tm.mark(1, st);
+
+  // step 1b: N_out(p) <- prune(p, V, R); reversed edges to the edge array
+  PruneArgs pa{};
+  pa.points = static_cast<const char*>(points);
+  pa.graph = g->rows;
+  pa.qidx = ids_dev;
+  pa.slotmap = nullptr;
+  pa.nq = (u32)b;
+  pa.R = R;
+  pa.vis = S.vis.as<u64>();
+  pa.vis_rw = S.vis.as<u64>();
+  pa.nvis = S.nvis.as<u32>();
+  pa.vis_cap = S.vis_cap;
+  pa.edges = S.edges.as<u64>();
+  pa.overflow_count = small + 0;
+  pa.overflow_list = S.ovf_list.as<u32>();
+  pa.a16 = a16;
+  pa.af = alpha;
+  pa.counters = ctr;
+  HIP_TRY(launch_prune(g->cfg, pa, st));
+
+  // searches whose visited list outgrew its slot are redone with as much room as they need
+  u32 novf = 0;
+  HIP_TRY(hipMemcpyAsync(&novf, small + 0, 4, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  if (novf > 0) {
+    std::vector<u32> slots(novf), nv(b);
+    HIP_TRY(hipMemcpy(slots.data(), S.ovf_list.p, (size_t)novf * 4, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(nv.data(), S.nvis.p, (size_t)b * 4, hipMemcpyDeviceToHost));
+    u32 need = 0;
+    std::vector<u32> ids2(novf);
+    for (u32 i = 0; i < novf; ++i) {
+      need = nv[slots[i]] > need ? nv[slots[i]] : need;
+      ids2[i] = ids_host[slots[i]];
+    }
+    DevBuf ids2_d, slots_d, vis2, nvis2;
+    HIP_TRY(ids2_d.alloc((size_t)novf * 4));
+    HIP_TRY(slots_d.alloc((size_t)novf * 4));
+    HIP_TRY(vis2.alloc((size_t)novf * need * 8));
+    HIP_TRY(nvis2.alloc((size_t)novf * 4));
+    HIP_TRY(hipMemcpy(ids2_d.p, ids2.data(), (size_t)novf * 4, hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(slots_d.p, slots.data(), (size_t)novf * 4, hipMemcpyHostToDevice));
+    HIP_TRY(hipMemsetAsync(small + 0, 0, 4, st));
+    SearchArgs sb = sa;
+    sb.qidx = ids2_d.as<u32>();
+    sb.nq = novf;
+    sb.vis = vis2.as<u64>();
+    sb.nvis = nvis2.as<u32>();
+    sb.vis_cap = need;
+    sb.counters = nullptr;
+    HIP_TRY(launch_search(g->cfg, sb, st));
+    PruneArgs pb = pa;
+    pb.qidx = ids2_d.as<u32>();
+    pb.slotmap = slots_d.as<u32>();
+    pb.nq = novf;
+    pb.vis = vis2.as<u64>();
+    pb.vis_rw = vis2.as<u64>();
+    pb.nvis = nvis2.as<u32>();
+    pb.vis_cap = need;
+    HIP_TRY(launch_prune(g->cfg, pb, st));
+    u32 again = 0;
+    HIP_TRY(hipMemcpyAsync(&again, small + 0, 4, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    if (again != 0) return fail(ANN_EINTERNAL, "visited list overflowed again on retry");
+    g->stats.redone += novf;
+  }
+  tm.mark(2, st);
+
+  // step 2a: bring equal destinations together
+  HIP_TRY(radix_sort_edges(S.edges.as<u64>(), S.edges_tmp.as<u64>(), S.hist.as<u32>(), E, bits_for(g->n), st));
+  tm.mark(3, st);
+
+  // step 2b: one wave per destination: append, or prune the row if it overflows
+  HIP_TRY(launch_segments(S.edges.as<u64>(), E, small + 1, S.seg_start.as<u32>(), st));
+  MergeArgs ma{};
+  ma.points = static_cast<const char*>(points);
+  ma.graph = g->rows;
+  ma.R = R;
+  ma.keys = S.edges.as<u64>();
+  ma.nkeys = E;
+  ma.seg_count = small + 1;
+  ma.seg_start = S.seg_start.as<u32>();
+  ma.arena = S.arena.as<u64>();
+  ma.arena_cap = S.arena_cap;
+  ma.arena_top = reinterpret_cast<unsigned long long*>(small + 4);
+  ma.error_flag = small + 2;
+  ma.a16 = a16;
+  ma.af = alpha;
+  ma.counters = ctr;
+  const u64 want = E < 65536 ? E : 65536;
+  HIP_TRY(launch_merge(g->cfg, ma, (u32)(want ? want : 1), st));
+  tm.mark(4, st);
+
+  u32 flags[4] = {0, 0, 0, 0};
+  HIP_TRY(hipMemcpyAsync(flags, small, 16, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  if (flags[2] != 0) return fail(ANN_EINTERNAL, "merge spill arena exhausted");
+  if (tm.on) {
+    float ms = 0;
+    (void)hipEventElapsedTime(&ms, tm.ev[0], tm.ev[1]);
+    g->stats.ms_search += ms;
+    (void)hipEventElapsedTime(&ms, tm.ev[1], tm.ev[2]);
+    g->stats.ms_prune += ms;
+    (void)hipEventElapsedTime(&ms, tm.ev[2], tm.ev[3]);
+    g->stats.ms_sort += ms;
+    (void)hipEventElapsedTime(&ms, tm.ev[3], tm.ev[4]);
+    g->stats.ms_merge += ms;
+    (void)hipEventElapsedTime(&ms, tm.ev[0], tm.ev[4]);
+    g->stats.ms_total += ms;
+  }
+  g->rounds += 1;
+  g->stats.rounds += 1;
+  return ANN_OK;
+}
+
+int new_graph(u64 n, u32 d, int dtype, int metric, u32 R, ann_graph** out) {
+  std::string why;
+  DistCfg cfg{};
+  if (!make_cfg(d, dtype, metric, &cfg, &why)) return fail(ANN_EINVAL, "%s", why.c_str());
+  if (n < 1 || n >= (1ull << 31)) return fail(ANN_EINVAL, "n must be in [1, 2^31)");
+  if (R < 1 || R > 512) return fail(ANN_EINVAL, "R must be in [1, 512]");
+  ann_graph* g = new (std::nothrow) ann_graph();
+  if (!g) return fail(ANN_ENOMEM, "host allocation failed");
+  g->n = n;
+  g->d = d;
+  g->R = R;
+  g->dtype = dtype;
+  g->metric = metric;
+  g->cfg = cfg;
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&g->rows), (size_t)n * R * sizeof(u32));
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&g->counters), sizeof(DevCounters));
+  if (e == hipSuccess) e = hipMemset(g->counters, 0, sizeof(DevCounters));
+  if (e != hipSuccess) {
+    ann_graph_free(g);
+    return fail(e == hipErrorOutOfMemory ? ANN_ENOMEM : ANN_EHIP, "graph allocation: %s", hipGetErrorString(e));
+  }
+  *out = g;
+  return ANN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ann_last_error(void) { return g_err.c_str(); }
+
+void ann_graph_free(ann_graph* g) {
+  if (!g) return;
+  if (g->rows) (void)hipFree(g->rows);
+  if (g->counters) (void)hipFree(g->counters);
+  delete g;
+}
+
+int ann_graph_info(const ann_graph* g, ann_graph_info_t* info) {
+  if (!g || !info) return fail(ANN_EINVAL, "null argument");
+  info->n = g->n;
+  info->d = g->d;
+  info->R = g->R;
+  info->dtype = (uint32_t)g->dtype;
+  info->metric = (uint32_t)g->metric;
+  info->start = g->start;
+  info->rounds = g->rounds;
+  return ANN_OK;
+}
+
+int ann_get_stats(const ann_graph* g, ann_stats* stats) {
+  if (!g || !stats) return fail(ANN_EINVAL, "null argument");
+  DevCounters c{};
+  HIP_TRY(hipMemcpy(&c, g->counters, sizeof(c), hipMemcpyDeviceToHost));
+  *stats = g->stats;
+  stats->searches = c.searches;
+  stats->hops = c.hops;
+  stats->evals = c.evals;
+  stats->prunes = c.prunes;
+  stats->reprunes = c.reprunes;
+  stats->appends = c.appends;
+  stats->edges = c.edges;
+  stats->prune_evals = c.prune_evals;
+  return ANN_OK;
+}
+
+const uint32_t* ann_graph_device_rows(const ann_graph* g) { return g ? g->rows : nullptr; }
+
+int ann_graph_copy_neighbors(const ann_graph* g, uint32_t* rows_host) {
+  if (!g || !rows_host) return fail(ANN_EINVAL, "null argument");
+  HIP_TRY(hipMemcpy(rows_host, g->rows, (size_t)g->n * g->R * sizeof(u32), hipMemcpyDeviceToHost));
+  return ANN_OK;
+}
+
+int ann_graph_from_host(const uint32_t* rows_host, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric,
+                        uint32_t R, uint32_t start, ann_graph** out) {
+  if (out) *out = nullptr;
+  if (!rows_host || !out) return fail(ANN_EINVAL, "null argument");
+  if (start >= n) return fail(ANN_EINVAL, "start vertex out of range");
+  // every id must be a vertex or ANN_NONE: the kernels follow them without further checks
+  for (u64 i = 0; i < n * R; ++i)
+    if (rows_host[i] != ANN_NONE && rows_host[i] >= n) return fail(ANN_EINVAL, "neighbour id out of range");
+  ann_graph* g = nullptr;
+  int rc = new_graph(n, d, dtype, metric, R, &g);
+  if (rc) return rc;
+  g->start = start;
+  hipError_t e = hipMemcpy(g->rows, rows_host, (size_t)n * R * sizeof(u32), hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    ann_graph_free(g);
+    return fail(ANN_EHIP, "copy of rows: %s", hipGetErrorString(e));
+  }
+  *out = g;
+  return ANN_OK;
+}
+
+int ann_start_vertex(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, void* stream,
+                     uint32_t* start_out) {
+  if (!points_dev || !start_out || n < 1 || d < 1) return fail(ANN_EINVAL, "null argument or empty input");
+  if (dtype != ANN_U8 && dtype != ANN_I8 && dtype != ANN_F32) return fail(ANN_EINVAL, "unknown dtype");
+  u32 s = 0;
+  HIP_TRY(start_vertex_device(points_dev, n, d, dtype, static_cast<hipStream_t>(stream), &s));
+  *start_out = s;
+  return ANN_OK;
+}
+
+int ann_sort_edges(uint64_t* keys_dev, uint64_t count, uint32_t key_bits, void* stream) {
+  if (!keys_dev && count) return fail(ANN_EINVAL, "null argument");
+  if (key_bits < 1 || key_bits > 32) return fail(ANN_EINVAL, "key_bits must be in [1, 32]");
+  if (count >= (1ull << 32)) return fail(ANN_EINVAL, "too many keys");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  DevBuf tmp, hist;
+  HIP_TRY(tmp.alloc(count * 8));
+  HIP_TRY(hist.alloc(radix_hist_entries(count) * 4));
+  HIP_TRY(radix_sort_edges(keys_dev, tmp.as<u64>(), hist.as<u32>(), count, key_bits, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  return ANN_OK;
+}
+
+static int check_insert_params(const ann_graph* g, uint32_t L, float alpha) {
+  if (L < 1 || L > 512) return fail(ANN_EINVAL, "L must be in [1, 512]");
+  if (!(alpha > 0.0f) || !std::isfinite(alpha) || alpha > 30000.0f) return fail(ANN_EINVAL, "alpha must be in (0, 30000]");
+  if (g->metric == ANN_MIPS && alpha > 1.0f) return fail(ANN_EINVAL, "alpha must be <= 1 for ANN_MIPS");
+  return ANN_OK;
+}
+
+int ann_insert_batch(ann_graph* g, const void* points_dev, const uint32_t* ids_host, uint64_t b, uint32_t L,
+                     float alpha, void* stream) {
+  if (!g || !points_dev || (!ids_host && b)) return fail(ANN_EINVAL, "null argument");
+  int rc = check_insert_params(g, L, alpha);
+  if (rc) return rc;
+  if (b == 0) return ANN_OK;
+  if (b * g->R >= (1ull << 32)) return fail(ANN_EINVAL, "batch too large");
+  for (u64 i = 0; i < b; ++i)
+    if (ids_host[i] >= g->n || ids_host[i] == g->start) return fail(ANN_EINVAL, "bad id in batch");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  BatchScratch S;
+  const u32 cap = g->visited_cap ? g->visited_cap : (4 * L > 256 ? 4 * L : 256);
+  rc = S.alloc(b, g->R, cap);
+  if (rc) return rc;
+  HIP_TRY(hipMemcpy(S.qidx.p, ids_host, (size_t)b * 4, hipMemcpyHostToDevice));
+  PhaseTimer tm;
+  rc = tm.init(g->collect);
+  if (rc) return rc;
+  return batch_insert(g, points_dev, ids_host, S.qidx.as<u32>(), b, L, alpha, S, tm, st);
+}
+
+int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric, uint32_t R,
+              uint32_t L, float alpha, uint64_t seed, const ann_build_opts* opts, void* stream, ann_graph** out) {
+  if (out) *out = nullptr;
+  if (!points_dev || !out) return fail(ANN_EINVAL, "null argument");
+  ann_build_opts o{};
+  o.start = ANN_NONE;
+  if (opts) o = *opts;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  ann_graph* g = nullptr;
+  int rc = new_graph(n, d, dtype, metric, R, &g);
+  if (rc) return rc;
+  struct Guard {
+    ann_graph* g;
+    ~Guard() {
+      if (g) ann_graph_free(g);
+    }
+  } guard{g};
+  rc = check_insert_params(g, L, alpha);
+  if (rc) return rc;
+  g->collect = o.collect_stats != 0;
+  g->hash_bits = o.hash_bits;
+  if (g->hash_bits && (g->hash_bits < 4 || g->hash_bits > 13)) return fail(ANN_EINVAL, "hash_bits must be in [4, 13]");
+  g->visited_cap = o.visited_cap;
+  HIP_TRY(hipMemsetAsync(g->rows, 0xFF, (size_t)n * R * sizeof(u32), st));
+
+  // start vertex s: present from the beginning with an empty row, never inserted again
+  if (o.use_start) {
+    if (o.start >= n) return fail(ANN_EINVAL, "start vertex out of range");
+    g->start = o.start;
+  } else {
+    u32 s = 0;
+    HIP_TRY(start_vertex_device(points_dev, n, d, dtype, st, &s));
+    g->start = s;
+  }
+
+  // insertion order: the ids other than s, shuffled (Fisher-Yates driven by SplitMix64)
+  const u64 m = n - 1;
+  std::vector<u32> order(m ? m : 1);
+  if (o.order) {
+    std::vector<unsigned char> seen(n, 0);
+    for (u64 i = 0; i < m; ++i) {
+      const u32 id = o.order[i];
+      if (id >= n || id == g->start || seen[id]) return fail(ANN_EINVAL, "order must list every id but the start once");
+      seen[id] = 1;
+      order[i] = id;
+    }
+  } else {
+    u64 k = 0;
+    for (u64 i = 0; i < n; ++i)
+      if (i != g->start) order[k++] = (u32)i;
+    u64 state = seed;
+    for (u64 i = m; i-- > 1;) {
+      const u64 r = splitmix64(state);
+      const u64 j = (u64)(((unsigned __int128)r * (unsigned __int128)(i + 1)) >> 64);
+      const u32 t = order[i];
+      order[i] = order[j];
+      order[j] = t;
+    }
+  }
+
+  // batches of 2, 4, 8, ... points, never more than theta
+  u64 theta = o.batch_cap ? o.batch_cap : (n / 50 > 1 ? n / 50 : 1);
+  if (theta * R >= (1ull << 32)) theta = ((1ull << 32) - 1) / R;
+  std::vector<u64> bounds{0};
+  for (u64 done = 0; done < m;) {
+    u64 size = done + 2;
+    if (size > theta) size = theta;
+    if (size > m - done) size = m - done;
+    done += size;
+    bounds.push_back(done);
+  }
+  u64 bmax = 1;
+  for (size_t r = 0; r + 1 < bounds.size(); ++r) bmax = bounds[r + 1] - bounds[r] > bmax ? bounds[r + 1] - bounds[r] : bmax;
+
+  DevBuf order_dev;
+  HIP_TRY(order_dev.alloc(m * 4));
+  if (m) HIP_TRY(hipMemcpyAsync(order_dev.p, order.data(), m * 4, hipMemcpyHostToDevice, st));
+  BatchScratch S;
+  const u32 cap = g->visited_cap ? g->visited_cap : (4 * L > 256 ? 4 * L : 256);
+  rc = S.alloc(bmax, R, cap);
+  if (rc) return rc;
+  PhaseTimer tm;
+  rc = tm.init(g->collect);
+  if (rc) return rc;
+
+  for (size_t r = 0; r + 1 < bounds.size(); ++r) {
+    if (o.max_rounds && r >= o.max_rounds) break;
+    const u64 lo = bounds[r], b = bounds[r + 1] - bounds[r];
+    rc = batch_insert(g, points_dev, order.data() + lo, order_dev.as<u32>() + lo, b, L, alpha, S, tm, st);
+    if (rc) return rc;
+  }
+  HIP_TRY(hipStreamSynchronize(st));
+  guard.g = nullptr;
+  *out = g;
+  return ANN_OK;
+}
+
+int ann_search(const ann_graph* g, const void* points_dev, const void* queries_dev, uint64_t nq, uint32_t k,
+               uint32_t L, uint32_t* ids_dev, void* dists_dev, void* stream) {
+  if (!g || !points_dev) return fail(ANN_EINVAL, "null argument");
+  if (nq == 0) return ANN_OK;
+  if (!queries_dev || !ids_dev || !dists_dev) return fail(ANN_EINVAL, "null argument");
+  if (k < 1 || k > L) return fail(ANN_EINVAL, "need 1 <= k <= L");
+  if (L > 512) return fail(ANN_EINVAL, "L must be at most 512");
+  if (nq >= (1ull << 31)) return fail(ANN_EINVAL, "too many queries");
+  SearchArgs sa{};
+  sa.points = static_cast<const char*>(points_dev);
+  sa.graph = g->rows;
+  sa.queries = static_cast<const char*>(queries_dev);
+  sa.qidx = nullptr;
+  sa.qrow_bytes = g->cfg.row_bytes;
+  sa.nq = (u32)nq;
+  sa.R = g->R;
+  sa.start = g->start;
+  sa.L = L;
+  sa.k = k;
+  sa.hash_bits = g->hash_bits ? g->hash_bits : default_hash_bits(L);
+  sa.out_ids = ids_dev;
+  sa.out_dists = dists_dev;
+  sa.counters = g->collect ? g->counters : nullptr;
+  HIP_TRY(launch_search(g->cfg, sa, static_cast<hipStream_t>(stream)));
+  return ANN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,216 @@
+// Batched greedy beam search, one wavefront per search (Alg. 1 of the paper).
+//
+// The beam (at most L candidates ordered by (distance, id), each with a "processed" flag) lives
+// in registers, striped over the wave: entry i is held by lane i % 64 in slot i / 64.  LDS is the
+// exchange medium when new candidates are merged in.  The visited filter of Sec. 4.5 (a lossy
+// hash of vertex ids with one-sided error) is a per-wave LDS table: a collision only causes a
+// repeated distance evaluation, and the repeated candidate is then recognised as a duplicate of a
+// beam entry or is worse than the beam's last entry, so results do not depend on the table.
+#include "ann_device.hpp"
+#include "ann_internal.hpp"
+#include "ann_dispatch.hpp"
+
+namespace annmi {
+
+template <int KIND, int VEC, int NCH, int NSLOT>
+__global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  u64* beam = reinterpret_cast<u64*>(smem);
+  u32* cid = reinterpret_cast<u32*>(beam + NSLOT * 64);
+  u32* hash = cid + 64;
+
+  const int lane = threadIdx.x;
+  const u32 qi = blockIdx.x;
+  const u32 hsize = 1u << a.hash_bits;
+  const u32 hshift = 32u - a.hash_bits;
+  const u32 L = a.L;
+
+  const u32 qrow = a.qidx ? a.qidx[qi] : qi;
+  const QueryRegs<KIND, VEC, NCH> Q =
+      load_query<KIND, VEC, NCH>(a.queries + (u64)qrow * a.qrow_bytes, T.npieces, lane);
+
+  for (u32 i = lane; i < hsize; i += 64) hash[i] = NONE_ID;
+
+  u64 A[NSLOT];
+#pragma unroll
+  for (int s = 0; s < NSLOT; ++s) A[s] = KEY_INF;
+
+  // beam <- {s}
+  {
+    const u32 st = a.start;
+    u32 dk = eval_up_to_64<KIND, VEC, NCH>(T, Q, [st](u32) { return st; }, 1u, lane);
+    dk = readlane_u32(dk, 0);
+    if (lane == 0) A[0] = make_key(dk, st);
+  }
+  __syncthreads();
+  if (lane == 0) hash[(a.start * 0x9E3779B1u) >> hshift] = a.start;
+
+  u32 size = 1, nv = 0, evals = 1;
+
+  for (;;) {
+    // p* <- closest unprocessed member of the beam
+    int pos = -1;
+    u64 pk = 0;
+#pragma unroll
+    for (int s = 0; s < NSLOT; ++s) {
+      if (pos < 0) {
+        const u64 m = ballot(A[s] != KEY_INF && !(A[s] & 1ull));
+        if (m) {
+          const int l = __builtin_ctzll(m);
+          pos = s * 64 + l;
+          pk = readlane_u64(A[s], l);
+          if (lane == l) A[s] |= 1ull;
+        }
+      }
+    }
+    if (pos < 0) break;
+    const u32 pstar = key_id(pk);
+    if (a.vis != nullptr && lane == 0 && nv < a.vis_cap) a.vis[(u64)qi * a.vis_cap + nv] = pk;
+    ++nv;
+
+    // beam <- beam U N_out(p*), keep the L closest
+    const u32* row = a.graph + (u64)pstar * a.R;
+    for (u32 base = 0; base < a.R; base += 64) {
+      const u32 j = base + lane;
+      const u32 x = j < a.R ? row[j] : NONE_ID;
+      bool fresh = x != NONE_ID;
+      const u64 present = ballot(fresh);
+      if (fresh) {
+        const u32 h = (x * 0x9E3779B1u) >> hshift;
+        if (hash[h] == x)
+          fresh = false;
+        else
+          hash[h] = x;
+      }
+      const u64 fm = ballot(fresh);
+      const u32 m = __builtin_popcountll(fm);
+      if (m) {
+        const u32 rank = __builtin_popcountll(fm & lanemask_lt(lane));
+        if (fresh) cid[rank] = x;
+        __syncthreads();
+        const u32 dk = eval_up_to_64<KIND, VEC, NCH>(T, Q, [cid](u32 c) { return cid[c]; }, m, lane);
+        const u32 c = cand_of_lane(lane);
+        u64 mykey = c < m ? make_key(dk, cid[c]) : KEY_INF;
+        __syncthreads();
+        evals += m;
+
+        u64 worst = KEY_INF;
+        if (size == L) {
+#pragma unroll
+          for (int s = 0; s < NSLOT; ++s)
+            if ((int)((L - 1) >> 6) == s) worst = readlane_u64(A[s], (int)((L - 1) & 63)) | 1ull;
+        }
+        bool surv = mykey < worst;
+        u64 sm = ballot(surv);
+        if (sm) {
+          // rank of each survivor among the beam entries; drop survivors already in the beam
+          u32 myrA = 0;
+          for (u64 it = sm; it; it &= it - 1) {
+            const int l = __builtin_ctzll(it);
+            const u64 sk = readlane_u64(mykey, l);
+            u32 rA = 0;
+            bool dup = false;
+#pragma unroll
+            for (int s = 0; s < NSLOT; ++s) {
+              rA += __builtin_popcountll(ballot(A[s] < sk));
+              dup = dup || (ballot((A[s] | 1ull) == (sk | 1ull)) != 0);
+            }
+            if (lane == l) {
+              myrA = rA;
+              if (dup) surv = false;
+            }
+          }
+          sm = ballot(surv);
+          if (sm) {
+            u32 shift[NSLOT];
+#pragma unroll
+            for (int s = 0; s < NSLOT; ++s) shift[s] = 0;
+            u32 myrB = 0, ns = 0;
+            for (u64 it = sm; it; it &= it - 1) {
+              const int l = __builtin_ctzll(it);
+              const u64 sk = readlane_u64(mykey, l);
+              const u32 rB = __builtin_popcountll(ballot(surv && mykey < sk));
+#pragma unroll
+              for (int s = 0; s < NSLOT; ++s) shift[s] += (sk < A[s]) ? 1u : 0u;
+              if (lane == l) myrB = rB;
+              ++ns;
+            }
+#pragma unroll
+            for (int s = 0; s < NSLOT; ++s) {
+              const u32 np = (u32)(s * 64 + lane) + shift[s];
+              if (A[s] != KEY_INF && np < L) beam[np] = A[s];
+            }
+            if (surv) {
+              const u32 np = myrA + myrB;
+              if (np < L) beam[np] = mykey;
+            }
+            size = size + ns < L ? size + ns : L;
+            __syncthreads();
+#pragma unroll
+            for (int s = 0; s < NSLOT; ++s) {
+              const u32 idx = (u32)(s * 64 + lane);
+              A[s] = idx < size ? beam[idx] : KEY_INF;
+            }
+            __syncthreads();
+          }
+        }
+      }
+      if (present != ~0ull) break;  // rows are compact: the first gap ends the row
+    }
+  }
+
+  if (a.nvis != nullptr && lane == 0) a.nvis[qi] = nv;
+  if (a.out_ids != nullptr) {
+#pragma unroll
+    for (int s = 0; s < NSLOT; ++s) {
+      const u32 idx = (u32)(s * 64 + lane);
+      if (idx < a.k) {
+        const bool ok = A[s] != KEY_INF;
+        const u64 o = (u64)qi * a.k + idx;
+        a.out_ids[o] = ok ? key_id(A[s]) : NONE_ID;
+        if constexpr (KindTraits<KIND>::is_int)
+          reinterpret_cast<i32*>(a.out_dists)[o] = ok ? int_from_dkey(key_dkey(A[s])) : 0x7FFFFFFF;
+        else
+          reinterpret_cast<float*>(a.out_dists)[o] = ok ? float_from_dkey(key_dkey(A[s])) : __builtin_inff();
+      }
+    }
+  }
+  if (a.counters != nullptr && lane == 0) {
+    atomicAdd(&a.counters->searches, 1ull);
+    atomicAdd(&a.counters->hops, (unsigned long long)nv);
+    atomicAdd(&a.counters->evals, (unsigned long long)evals);
+  }
+}
+
+u32 default_hash_bits(u32 L) {
+  u32 want = 16u * L, bits = 9;
+  while ((1u << bits) < want && bits < 12) ++bits;
+  return bits;
+}
+
+static u32 nslot_for(u32 L) { return L <= 64 ? 1 : (L <= 128 ? 2 : (L <= 256 ? 4 : 8)); }
+
+u32 search_lds_bytes(u32 L, u32 hash_bits) {
+  return nslot_for(L) * 64 * 8 + 64 * 4 + (1u << hash_bits) * 4;
+}
+
+template <int KIND, int VEC, int NCH>
+static hipError_t launch_search_nslot(const SearchArgs& a, const VecTable& T, hipStream_t s) {
+  const u32 lds = search_lds_bytes(a.L, a.hash_bits);
+  const dim3 grid(a.nq), block(64);
+  switch (nslot_for(a.L)) {
+    case 1: hipLaunchKernelGGL((search_kernel<KIND, VEC, NCH, 1>), grid, block, lds, s, a, T); break;
+    case 2: hipLaunchKernelGGL((search_kernel<KIND, VEC, NCH, 2>), grid, block, lds, s, a, T); break;
+    case 4: hipLaunchKernelGGL((search_kernel<KIND, VEC, NCH, 4>), grid, block, lds, s, a, T); break;
+    default: hipLaunchKernelGGL((search_kernel<KIND, VEC, NCH, 8>), grid, block, lds, s, a, T); break;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_search(const DistCfg& cfg, const SearchArgs& a, hipStream_t s) {
+  if (a.nq == 0) return hipSuccess;
+  VecTable T{a.points, cfg.row_bytes, cfg.npieces};
+  ANN_DISPATCH_CFG(launch_search_nslot, a, T, s);
+}
+
+}  // namespace annmi

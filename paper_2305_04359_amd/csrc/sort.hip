@@ -1,0 +1,128 @@
+// Grouping of reversed edges by destination: a stable least-significant-digit radix sort of
+// 64-bit keys (destination << 32 | source) on the destination bits only.  It takes the place of
+// the semisort in BatchInsert (Alg. 3): equal destinations become consecutive, and, the sort
+// being stable, the sources of one destination stay in the order they were emitted (batch order).
+//
+// One wavefront owns a tile of consecutive keys and walks it 64 keys at a time, so ranking inside
+// a tile needs no cross-wave coordination: a key's rank among equal digits of its 64-key row is
+// a popcount over a match mask built from one ballot per digit bit.
+#include "ann_device.hpp"
+#include "ann_internal.hpp"
+
+namespace annmi {
+
+constexpr u32 RS_RADIX = 256;
+
+static u64 rs_tile_keys(u64 count) {
+  // at least 1024 keys per tile, at most 8192 tiles
+  u64 t = (count + 8191) / 8192;
+  if (t < 1024) t = 1024;
+  return (t + 63) / 64 * 64;
+}
+static u64 rs_tiles(u64 count) { return (count + rs_tile_keys(count) - 1) / rs_tile_keys(count); }
+
+u64 radix_hist_entries(u64 count) { return RS_RADIX * (rs_tiles(count) ? rs_tiles(count) : 1); }
+
+__global__ __launch_bounds__(64) void rs_hist_kernel(const u64* keys, u64 count, u64 tile_keys, u32 tiles,
+                                                     u32 shift, u32 mask, u32* hist) {
+  __shared__ u32 cnt[RS_RADIX];
+  const int lane = threadIdx.x;
+  for (u32 i = lane; i < RS_RADIX; i += 64) cnt[i] = 0;
+  __syncthreads();
+  const u64 lo = (u64)blockIdx.x * tile_keys;
+  const u64 hi = lo + tile_keys < count ? lo + tile_keys : count;
+  for (u64 i = lo + lane; i < hi; i += 64) {
+    const u32 dg = (u32)(keys[i] >> shift) & mask;
+    atomicAdd(&cnt[dg], 1u);
+  }
+  __syncthreads();
+  for (u32 i = lane; i < RS_RADIX; i += 64) hist[(u64)i * tiles + blockIdx.x] = cnt[i];
+}
+
+// exclusive scan of `total` counters in place, one workgroup
+__global__ __launch_bounds__(1024) void rs_scan_kernel(u32* hist, u64 total) {
+  __shared__ u32 part[1024];
+  const u32 t = threadIdx.x;
+  const u64 per = (total + 1023) / 1024;
+  const u64 lo = (u64)t * per < total ? (u64)t * per : total;
+  const u64 hi = lo + per < total ? lo + per : total;
+  u32 s = 0;
+  for (u64 i = lo; i < hi; ++i) s += hist[i];
+  part[t] = s;
+  __syncthreads();
+  // Hillis-Steele inclusive scan over the 1024 partial sums
+  for (u32 off = 1; off < 1024; off <<= 1) {
+    const u32 v = t >= off ? part[t - off] : 0u;
+    __syncthreads();
+    part[t] += v;
+    __syncthreads();
+  }
+  u32 run = t ? part[t - 1] : 0u;
+  for (u64 i = lo; i < hi; ++i) {
+    const u32 v = hist[i];
+    hist[i] = run;
+    run += v;
+  }
+}
+
+__global__ __launch_bounds__(64) void rs_scatter_kernel(const u64* keys, u64* out, u64 count, u64 tile_keys,
+                                                        u32 tiles, u32 shift, u32 mask, u32 nbits,
+                                                        const u32* hist) {
+  __shared__ u32 base[RS_RADIX];
+  const int lane = threadIdx.x;
+  for (u32 i = lane; i < RS_RADIX; i += 64) base[i] = hist[(u64)i * tiles + blockIdx.x];
+  __syncthreads();
+  const u64 lo = (u64)blockIdx.x * tile_keys;
+  const u64 hi = lo + tile_keys < count ? lo + tile_keys : count;
+  for (u64 i0 = lo; i0 < hi; i0 += 64) {
+    const u64 i = i0 + lane;
+    const bool valid = i < hi;
+    const u64 key = valid ? keys[i] : 0ull;
+    const u32 dg = (u32)(key >> shift) & mask;
+    u64 match = ballot(valid);
+    for (u32 b = 0; b < nbits; ++b) {
+      const bool bit = (dg >> b) & 1u;
+      const u64 bm = ballot(bit);
+      match &= bit ? bm : ~bm;
+    }
+    const u32 rank = (u32)__builtin_popcountll(match & lanemask_lt(lane));
+    u32 dst = 0;
+    if (valid) dst = base[dg] + rank;
+    __syncthreads();
+    // the highest lane of each group of equal digits advances the group's counter
+    if (valid && (match >> lane) == 1ull) base[dg] += (u32)__builtin_popcountll(match);
+    __syncthreads();
+    if (valid) out[dst] = key;
+  }
+}
+
+hipError_t radix_sort_edges(u64* keys, u64* tmp, u32* hist, u64 count, u32 key_bits, hipStream_t s) {
+  if (count < 2 || key_bits == 0) return hipSuccess;
+  if (key_bits > 32) key_bits = 32;
+  const u64 tile_keys = rs_tile_keys(count);
+  const u32 tiles = (u32)rs_tiles(count);
+  const u32 npass = (key_bits + 7) / 8;
+  const u32 per = (key_bits + npass - 1) / npass;
+  u64* src = keys;
+  u64* dst = tmp;
+  u32 done = 0;
+  for (u32 p = 0; p < npass; ++p) {
+    const u32 nb = key_bits - done < per ? key_bits - done : per;
+    const u32 shift = 32 + done;
+    const u32 mask = (1u << nb) - 1u;
+    hipLaunchKernelGGL(rs_hist_kernel, dim3(tiles), dim3(64), 0, s, src, count, tile_keys, tiles, shift, mask, hist);
+    hipLaunchKernelGGL(rs_scan_kernel, dim3(1), dim3(1024), 0, s, hist, (u64)RS_RADIX * tiles);
+    hipLaunchKernelGGL(rs_scatter_kernel, dim3(tiles), dim3(64), 0, s, src, dst, count, tile_keys, tiles, shift,
+                       mask, nb, hist);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    u64* t = src;
+    src = dst;
+    dst = t;
+    done += nb;
+  }
+  if (src != keys) return hipMemcpyAsync(keys, src, count * sizeof(u64), hipMemcpyDeviceToDevice, s);
+  return hipSuccess;
+}
+
+}  // namespace annmi
