@@ -1,0 +1,236 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path: one step = one full graph build (prefix-doubling batch insertion)
+plus one batched query search at the beam width that reaches recall@10 = 0.90.
+
+Prints ONE JSON line.  `value` is build points/s on one MI355X with inputs resident in HBM.
+The roofline object covers the dominant kernel (the build's beam search); the cpu_baseline
+object times the CPU oracle on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def ground_truth(torch, pts, qs, k, metric):
+    """Exact k-NN under (distance, id) with library GEMMs: measurement only, not the product."""
+    n = pts.shape[0]
+    out = []
+    if pts.dtype == torch.float32:
+        P = pts
+        pp = (P.double() ** 2).sum(1) if metric == 0 else None
+        for q0 in range(0, qs.shape[0], 1000):
+            Q = qs[q0:q0 + 1000]
+            ip = (Q.double() @ P.double().T)
+            d = (Q.double() ** 2).sum(1)[:, None] + pp[None, :] - 2 * ip if metric == 0 else -ip
+            out.append(torch.topk(d, k, dim=1, largest=False, sorted=True).indices)
+        return torch.cat(out).cpu().numpy().astype(np.uint32)
+    P = pts.float()
+    pp = (pts.long() ** 2).sum(1)
+    ids = torch.arange(n, device=pts.device, dtype=torch.int64)
+    for q0 in range(0, qs.shape[0], 500):
+        Q = qs[q0:q0 + 500]
+        qp = (Q.float() @ P.T).long()  # exact: every partial sum is an integer below 2^24
+        d = (Q.long() ** 2).sum(1)[:, None] + pp[None, :] - 2 * qp
+        key = d * (1 << 32) + ids[None, :]
+        out.append(torch.topk(key, k, dim=1, largest=False, sorted=True).values & 0xFFFFFFFF)
+    return torch.cat(out).cpu().numpy().astype(np.uint32)
+
+
+def recall(ids, gt):
+    k = gt.shape[1]
+    hit = 0
+    for a, b in zip(ids, gt):
+        hit += len(set(a.tolist()) & set(b.tolist()))
+    return hit / (k * len(gt))
+
+
+def time_search(torch, A, g, pts, qs, k, L, reps=5):
+    ids, dists = A.ann_search(g, pts, qs, k, L)  # warm-up
+    torch.cuda.synchronize()
+    ms = []
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        A.ann_search(g, pts, qs, k, L, ids, dists)
+        e1.record()
+        torch.cuda.synchronize()
+        ms.append(e0.elapsed_time(e1))
+    return float(np.median(ms)), ids
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="C2", choices=["C1", "C2", "C3", "C4"])
+    ap.add_argument("--n", type=int, default=None, help="override the number of base points")
+    ap.add_argument("--nq", type=int, default=None)
+    ap.add_argument("--cpu-sample", type=int, default=None, help="points of the last batch the oracle inserts")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(no collectives or sharding are part of it)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2305_04359_amd import binding as A
+    from paper_2305_04359_amd import workloads as W
+    A.lib()
+    torch.cuda.set_device(0)
+
+    t_gen = time.time()
+    w = W.make(args.config, args.n, args.nq)
+    metric = w.metric
+    pts = torch.from_numpy(w.points).cuda()
+    qs = torch.from_numpy(w.queries).cuda()
+    t_gen = time.time() - t_gen
+    k = w.k
+    row_bytes = w.d * w.points.dtype.itemsize
+
+    gt = ground_truth(torch, pts, qs, k, metric)
+
+    # warm-up builds; the first one also picks the beam widths for the recall targets
+    L90 = L95 = None
+    sweep = []
+    for i in range(max(1, args.warmup)):
+        g = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, metric=metric)
+        if i == 0:
+            for L in sorted(set(w.search_L)):
+                if L < k:
+                    continue
+                ms, ids = time_search(torch, A, g, pts, qs, k, L, reps=3)
+                r = recall(ids.cpu().numpy().view(np.uint32), gt)
+                sweep.append({"L": L, "recall": round(r, 4), "qps": round(qs.shape[0] / ms * 1e3, 1)})
+                if L90 is None and r >= 0.90:
+                    L90 = L
+                if L95 is None and r >= 0.95:
+                    L95 = L
+                if L95 is not None and r >= 0.995:
+                    break
+        del g
+    if L90 is None:
+        L90 = max(w.search_L)
+    if L95 is None:
+        L95 = max(w.search_L)
+
+    # timed steps
+    torch.cuda.synchronize()
+    step_ms, build_ms, stats_list = [], [], []
+    g = None
+    for _ in range(args.steps):
+        if g is not None:
+            del g
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        g = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, metric=metric, collect_stats=True)
+        t1 = time.perf_counter()
+        stats_list.append(g.stats())  # before the query search adds to the counters
+        A.ann_search(g, pts, qs, k, L90)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        build_ms.append((t1 - t0) * 1e3)
+        step_ms.append((t2 - t0) * 1e3)
+    st = stats_list[-1]
+    ms_per_step = float(np.mean(step_ms))
+    bms = float(np.mean(build_ms))
+    points_per_s = w.n / (bms / 1e3)
+
+    ms90, ids90 = time_search(torch, A, g, pts, qs, k, L90)
+    ms95, ids95 = time_search(torch, A, g, pts, qs, k, L95)
+    r90 = recall(ids90.cpu().numpy().view(np.uint32), gt)
+    r95 = recall(ids95.cpu().numpy().view(np.uint32), gt)
+
+    # roofline of the dominant kernel: the build's beam search.  Algorithmic bytes per launch =
+    # hops * 4R (adjacency rows) + distance evaluations * row bytes (gathered vectors)
+    # + 8 * hops (visited list), summed over the launches of the timed builds.
+    srch_bytes = st["hops"] * 4 * w.R + st["evals"] * row_bytes + 8 * st["hops"]
+    srch_s = st["ms_search"] / 1e3
+    achieved = srch_bytes / srch_s / 1e9 if srch_s > 0 else 0.0
+    roofline = {
+        "bound": "hbm", "kernel": "search_kernel (build, step 1 of BatchInsert)",
+        "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "launches": int(st["rounds"]), "avg_launch_ms": round(st["ms_search"] / max(1, st["rounds"]), 4),
+        "bytes_per_launch": int(srch_bytes / max(1, st["rounds"])),
+    }
+    phases = {kk: round(st[kk], 2) for kk in ("ms_search", "ms_prune", "ms_sort", "ms_merge", "ms_total")}
+
+    out = {
+        "metric": "index build points/sec; query QPS at recall@10=0.90 (1 GPU, HBM GB/s)",
+        "value": round(points_per_s, 1), "unit": "points/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 2), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": {np.dtype("uint8"): "u8", np.dtype("int8"): "i8", np.dtype("float32"): "f32"}[w.points.dtype],
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: n={w.n} d={w.d} {w.points.dtype} "
+                               f"{'L2sq' if metric == 0 else 'neg-inner-product'}, R={w.R} L={w.L} alpha={w.alpha}, "
+                               f"theta={w.theta}, nq={qs.shape[0]} k={k}", "note": w.note},
+        "build_ms": round(bms, 2),
+        "qps_at_recall_0.90": {"L": L90, "recall": round(r90, 4), "qps": round(qs.shape[0] / ms90 * 1e3, 1)},
+        "qps_at_recall_0.95": {"L": L95, "recall": round(r95, 4), "qps": round(qs.shape[0] / ms95 * 1e3, 1)},
+        "search_sweep": sweep,
+        "build_counters": {kk: int(st[kk]) for kk in ("searches", "hops", "evals", "prunes", "reprunes", "appends",
+                                                      "edges", "prune_evals", "redone", "rounds")},
+        "build_phase_ms": phases,
+        "roofline": roofline,
+        "datagen_s": round(t_gen, 1),
+    }
+
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(torch, A, w, pts, g, args.cpu_sample)
+    print(json.dumps(out))
+
+
+def cpu_baseline(torch, A, w, pts, g_full, sample):
+    """The oracle, as it stands, inserts the first `sample` points of the LAST batch into the
+    graph as it stood before that batch (taken from a GPU build stopped one batch early); the
+    GPU inserts the same batch into the same snapshot and the two results are compared."""
+    import oracle as O
+    info = g_full.info()
+    rounds = int(info.rounds)
+    metric = w.metric
+    snap = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, metric=metric, max_rounds=rounds - 1)
+    rows = snap.neighbors()
+    s = int(snap.info().start)
+    ds = O.Dataset(w.points, metric)
+    order = O.insertion_order(w.n, s, w.seed)
+    bounds = O.schedule(w.n - 1, w.theta).astype(np.int64)
+    last = order[bounds[rounds - 1]:bounds[rounds]]
+    if sample is None:
+        sample = min(len(last), 4000 if w.points.dtype != np.float32 else 1500)
+    batch = last[:sample]
+    cores = O.threads(0)
+    ost = O.Stats()
+    og = rows.copy()
+    t0 = time.perf_counter()
+    O.batch_insert(ds, og, s, batch, w.L, w.alpha, threads=0, stats=ost)
+    cpu_s = time.perf_counter() - t0
+    A.ann_insert_batch(snap, pts, batch, w.L, w.alpha)
+    gg = snap.neighbors()
+    same_rows = float((gg == og).all(1).mean())
+    return {
+        "value": round(len(batch) / cpu_s, 1), "unit": "points/s", "cores": cores, "kind": "oracle",
+        "sample": f"BatchInsert of the first {len(batch)} points of the last batch (round {rounds}) into the "
+                  f"{int(bounds[rounds - 1]) + 1}-point graph that precedes it, {cpu_s:.1f} s of wall time",
+        "rows_identical_to_gpu": same_rows,
+        "oracle_hops_per_search": round(ost.hops / max(1, ost.searches), 2),
+        "oracle_evals_per_search": round(ost.evals / max(1, ost.searches), 2),
+    }
+
+
+if __name__ == "__main__":
+    main()

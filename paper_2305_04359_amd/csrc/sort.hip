@@ -21,7 +21,7 @@ static u64 rs_tile_keys(u64 count) {
 }
 static u64 rs_tiles(u64 count) { return (count + rs_tile_keys(count) - 1) / rs_tile_keys(count); }
 
-u64 radix_hist_entries(u64 count) { return RS_RADIX * (rs_tiles(count) ? rs_tiles(count) : 1); }
+u64 radix_hist_entries(u64 count) { return RS_RADIX * ((rs_tiles(count) ? rs_tiles(count) : 1) + 1); }
 
 __global__ __launch_bounds__(64) void rs_hist_kernel(const u64* keys, u64 count, u64 tile_keys, u32 tiles,
                                                      u32 shift, u32 mask, u32* hist) {
@@ -39,38 +39,55 @@ __global__ __launch_bounds__(64) void rs_hist_kernel(const u64* keys, u64 count,
   for (u32 i = lane; i < RS_RADIX; i += 64) hist[(u64)i * tiles + blockIdx.x] = cnt[i];
 }
 
-// exclusive scan of `total` counters in place, one workgroup
-__global__ __launch_bounds__(1024) void rs_scan_kernel(u32* hist, u64 total) {
-  __shared__ u32 part[1024];
+// hist is a RS_RADIX x tiles table.  One workgroup per digit turns its row into an exclusive
+// prefix over the tiles and leaves the row total in digit_total[digit] ...
+__global__ __launch_bounds__(256) void rs_rowscan_kernel(u32* hist, u32 tiles, u32* digit_total) {
+  __shared__ u32 part[256];
   const u32 t = threadIdx.x;
-  const u64 per = (total + 1023) / 1024;
-  const u64 lo = (u64)t * per < total ? (u64)t * per : total;
-  const u64 hi = lo + per < total ? lo + per : total;
+  u32* row = hist + (u64)blockIdx.x * tiles;
+  const u32 per = (tiles + 255) / 256;
+  const u32 lo = t * per < tiles ? t * per : tiles;
+  const u32 hi = lo + per < tiles ? lo + per : tiles;
   u32 s = 0;
-  for (u64 i = lo; i < hi; ++i) s += hist[i];
+  for (u32 i = lo; i < hi; ++i) s += row[i];
   part[t] = s;
   __syncthreads();
-  // Hillis-Steele inclusive scan over the 1024 partial sums
-  for (u32 off = 1; off < 1024; off <<= 1) {
+  for (u32 off = 1; off < 256; off <<= 1) {
     const u32 v = t >= off ? part[t - off] : 0u;
     __syncthreads();
     part[t] += v;
     __syncthreads();
   }
   u32 run = t ? part[t - 1] : 0u;
-  for (u64 i = lo; i < hi; ++i) {
-    const u32 v = hist[i];
-    hist[i] = run;
+  for (u32 i = lo; i < hi; ++i) {
+    const u32 v = row[i];
+    row[i] = run;
     run += v;
   }
+  if (t == 255) digit_total[blockIdx.x] = part[255];
+}
+
+// ... and one workgroup turns the RS_RADIX totals into the first output index of each digit.
+__global__ __launch_bounds__(256) void rs_digitscan_kernel(u32* digit_total) {
+  __shared__ u32 part[256];
+  const u32 t = threadIdx.x;
+  part[t] = digit_total[t];
+  __syncthreads();
+  for (u32 off = 1; off < 256; off <<= 1) {
+    const u32 v = t >= off ? part[t - off] : 0u;
+    __syncthreads();
+    part[t] += v;
+    __syncthreads();
+  }
+  digit_total[t] = t ? part[t - 1] : 0u;
 }
 
 __global__ __launch_bounds__(64) void rs_scatter_kernel(const u64* keys, u64* out, u64 count, u64 tile_keys,
                                                         u32 tiles, u32 shift, u32 mask, u32 nbits,
-                                                        const u32* hist) {
+                                                        const u32* hist, const u32* digit_base) {
   __shared__ u32 base[RS_RADIX];
   const int lane = threadIdx.x;
-  for (u32 i = lane; i < RS_RADIX; i += 64) base[i] = hist[(u64)i * tiles + blockIdx.x];
+  for (u32 i = lane; i < RS_RADIX; i += 64) base[i] = digit_base[i] + hist[(u64)i * tiles + blockIdx.x];
   __syncthreads();
   const u64 lo = (u64)blockIdx.x * tile_keys;
   const u64 hi = lo + tile_keys < count ? lo + tile_keys : count;
@@ -111,9 +128,11 @@ hipError_t radix_sort_edges(u64* keys, u64* tmp, u32* hist, u64 count, u32 key_b
     const u32 shift = 32 + done;
     const u32 mask = (1u << nb) - 1u;
     hipLaunchKernelGGL(rs_hist_kernel, dim3(tiles), dim3(64), 0, s, src, count, tile_keys, tiles, shift, mask, hist);
-    hipLaunchKernelGGL(rs_scan_kernel, dim3(1), dim3(1024), 0, s, hist, (u64)RS_RADIX * tiles);
+    u32* digit_total = hist + (u64)RS_RADIX * tiles;
+    hipLaunchKernelGGL(rs_rowscan_kernel, dim3(RS_RADIX), dim3(256), 0, s, hist, tiles, digit_total);
+    hipLaunchKernelGGL(rs_digitscan_kernel, dim3(1), dim3(256), 0, s, digit_total);
     hipLaunchKernelGGL(rs_scatter_kernel, dim3(tiles), dim3(64), 0, s, src, dst, count, tile_keys, tiles, shift,
-                       mask, nb, hist);
+                       mask, nb, hist, digit_total);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     u64* t = src;
