@@ -64,6 +64,13 @@ __device__ __forceinline__ u64 readlane_u64(u64 v, int lane) {
   return ((u64)hi << 32) | lo;
 }
 
+// `old` with lane LANE replaced by the wave-uniform value `sval`
+template <int LANE>
+__device__ __forceinline__ u32 writelane_u32(u32 old, u32 sval) {
+  asm("v_writelane_b32 %0, %1, %2" : "+v"(old) : "s"(sval), "n"(LANE));
+  return old;
+}
+
 __device__ __forceinline__ u64 wave_min_u64(u64 v) {
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) {
@@ -218,6 +225,30 @@ struct PassBatch {
 // candidate cand_of_lane(l) = 8*(l&7) + (l>>3) when that index is < cnt.
 __device__ __forceinline__ u32 cand_of_lane(int lane) { return (u32)(8 * (lane & 7) + (lane >> 3)); }
 
+// passes t0 .. t0+PBX-1 (a pass = 8 candidates): all loads first, then the arithmetic
+template <int KIND, int VEC, int NCH, int PBX, class IdAt>
+__device__ __forceinline__ void eval_passes(const VecTable& T, const QueryRegs<KIND, VEC, NCH>& Q, IdAt id_at,
+                                            u32 cnt, u32 t0, int sub, u32 grp, u32& result) {
+  Piece<VEC> x[PBX][NCH];
+#pragma unroll
+  for (int tt = 0; tt < PBX; ++tt) {
+    const u32 c = 8u * (t0 + tt) + grp;
+    const bool ok = c < cnt;
+    const u32 id = ok ? id_at(c) : 0u;
+    const char* row = T.base + (u64)id * T.row_bytes;
+#pragma unroll
+    for (int u = 0; u < NCH; ++u) {
+      const u32 pc = sub + LPC * u;
+      x[tt][u] = (ok && pc < T.npieces) ? load_piece<VEC>(row + (u64)pc * VEC) : zero_piece<VEC>();
+    }
+  }
+#pragma unroll
+  for (int tt = 0; tt < PBX; ++tt) {
+    const u32 dk = distance_key<KIND, VEC, NCH>(Q, x[tt]);
+    if ((u32)sub == t0 + tt) result = dk;
+  }
+}
+
 template <int KIND, int VEC, int NCH, class IdAt>
 __device__ __forceinline__ u32 eval_up_to_64(const VecTable& T, const QueryRegs<KIND, VEC, NCH>& Q,
                                              IdAt id_at, u32 cnt, int lane) {
@@ -226,26 +257,34 @@ __device__ __forceinline__ u32 eval_up_to_64(const VecTable& T, const QueryRegs<
   const u32 grp = (u32)lane >> 3;
   const u32 npass = (cnt + 7u) >> 3;
   u32 result = 0;
-  for (u32 t0 = 0; t0 < npass; t0 += PB) {
-    Piece<VEC> x[PB][NCH];
-#pragma unroll
-    for (int tt = 0; tt < PB; ++tt) {
-      const u32 c = 8u * (t0 + tt) + grp;
-      const bool ok = c < cnt;
-      const u32 id = ok ? id_at(c) : 0u;
-      const char* row = T.base + (u64)id * T.row_bytes;
-#pragma unroll
-      for (int u = 0; u < NCH; ++u) {
-        const u32 pc = sub + LPC * u;
-        x[tt][u] = (ok && pc < T.npieces) ? load_piece<VEC>(row + (u64)pc * VEC) : zero_piece<VEC>();
-      }
-    }
-#pragma unroll
-    for (int tt = 0; tt < PB; ++tt) {
-      const u32 dk = distance_key<KIND, VEC, NCH>(Q, x[tt]);
-      if ((u32)sub == t0 + tt) result = dk;
+  u32 t0 = 0;
+  // whole batches, then the remainder with the smallest batch that covers it, so that a short
+  // candidate list does not pay for eight passes of arithmetic
+  while (npass - t0 >= (u32)PB) {
+    eval_passes<KIND, VEC, NCH, PB>(T, Q, id_at, cnt, t0, sub, grp, result);
+    t0 += PB;
+  }
+  const u32 rem = npass - t0;
+  if (rem == 0) return result;
+  if constexpr (PB >= 8) {
+    if (rem > 4) {
+      eval_passes<KIND, VEC, NCH, 8>(T, Q, id_at, cnt, t0, sub, grp, result);
+      return result;
     }
   }
+  if constexpr (PB >= 4) {
+    if (rem > 2) {
+      eval_passes<KIND, VEC, NCH, 4>(T, Q, id_at, cnt, t0, sub, grp, result);
+      return result;
+    }
+  }
+  if constexpr (PB >= 2) {
+    if (rem > 1) {
+      eval_passes<KIND, VEC, NCH, 2>(T, Q, id_at, cnt, t0, sub, grp, result);
+      return result;
+    }
+  }
+  eval_passes<KIND, VEC, NCH, 1>(T, Q, id_at, cnt, t0, sub, grp, result);
   return result;
 }
 

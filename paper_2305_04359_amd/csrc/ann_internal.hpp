@@ -81,7 +81,8 @@ struct MergeArgs {
   DevCounters* counters;
 };
 
-constexpr u32 PRUNE_LDS_CAP = 768;  // candidate keys held in LDS by the prune / merge kernels
+constexpr u32 PRUNE_LDS_CAP = 768;   // candidate keys held in LDS by the step-1 prune kernel
+constexpr u32 MERGE_SPILL_MIN = 1728;  // step-2 candidate lists longer than this go to the spill arena
 
 // launchers (each returns the hipGetLastError() of its launches)
 hipError_t launch_search(const DistCfg& cfg, const SearchArgs& a, hipStream_t s);

@@ -155,8 +155,8 @@ struct BatchScratch {
     bmax = b;
     vis_cap = cap;
     const u64 E = b * R;
-    // a spilled candidate list is longer than PRUNE_LDS_CAP and has at most R old entries
-    arena_cap = E + (u64)R * (E / (PRUNE_LDS_CAP - R) + 1);
+    // a spilled candidate list is longer than MERGE_SPILL_MIN and has at most R old entries
+    arena_cap = E + (u64)R * (E / (MERGE_SPILL_MIN - R) + 1);
     HIP_TRY(qidx.alloc(b * 4));
     HIP_TRY(vis.alloc(b * cap * 8));
     HIP_TRY(nvis.alloc(b * 4));

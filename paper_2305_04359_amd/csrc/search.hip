@@ -3,9 +3,10 @@
 // The beam (at most L candidates ordered by (distance, id), each with a "processed" flag) lives
 // in registers, striped over the wave: entry i is held by lane i % 64 in slot i / 64.  LDS is the
 // exchange medium when new candidates are merged in.  The visited filter of Sec. 4.5 (a lossy
-// hash of vertex ids with one-sided error) is a per-wave LDS table: a collision only causes a
-// repeated distance evaluation, and the repeated candidate is then recognised as a duplicate of a
-// beam entry or is worse than the beam's last entry, so results do not depend on the table.
+// hash of vertex ids with one-sided error) is a per-wave LDS table of 4-entry buckets, newest
+// first: a lost entry only causes a repeated distance evaluation, and the repeated candidate is
+// then recognised as a duplicate of a beam entry or is worse than the beam's last entry, so
+// results do not depend on the table.
 #include "ann_device.hpp"
 #include "ann_internal.hpp"
 #include "ann_dispatch.hpp"
@@ -17,12 +18,13 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
   extern __shared__ __align__(16) unsigned char smem[];
   u64* beam = reinterpret_cast<u64*>(smem);
   u32* cid = reinterpret_cast<u32*>(beam + NSLOT * 64);
-  u32* hash = cid + 64;
+  u32* hash = cid + 64;  // 16-byte aligned: the beam and cid are multiples of 16 bytes
 
   const int lane = threadIdx.x;
   const u32 qi = blockIdx.x;
-  const u32 hsize = 1u << a.hash_bits;
-  const u32 hshift = 32u - a.hash_bits;
+  const u32 hsize = 1u << a.hash_bits;        // entries; buckets of 4
+  const u32 hshift = 34u - a.hash_bits;       // 32 - log2(buckets)
+  uint4* bucket = reinterpret_cast<uint4*>(hash);
   const u32 L = a.L;
 
   const u32 qrow = a.qidx ? a.qidx[qi] : qi;
@@ -43,7 +45,7 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
     if (lane == 0) A[0] = make_key(dk, st);
   }
   __syncthreads();
-  if (lane == 0) hash[(a.start * 0x9E3779B1u) >> hshift] = a.start;
+  if (lane == 0) hash[4u * ((a.start * 0x9E3779B1u) >> hshift)] = a.start;
 
   u32 size = 1, nv = 0, evals = 1;
 
@@ -77,10 +79,11 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
       const u64 present = ballot(fresh);
       if (fresh) {
         const u32 h = (x * 0x9E3779B1u) >> hshift;
-        if (hash[h] == x)
+        const uint4 e = bucket[h];
+        if (e.x == x || e.y == x || e.z == x || e.w == x)
           fresh = false;
         else
-          hash[h] = x;
+          bucket[h] = make_uint4(x, e.x, e.y, e.z);
       }
       const u64 fm = ballot(fresh);
       const u32 m = __builtin_popcountll(fm);
