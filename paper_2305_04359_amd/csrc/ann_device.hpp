@@ -136,7 +136,7 @@ __device__ __forceinline__ Piece<VEC> zero_piece() {
 // Where the vectors live.
 struct VecTable {
   const char* base;
-  u64 row_bytes;
+  u32 row_bytes;
   u32 npieces;  // pieces of VEC bytes per row
 };
 
@@ -148,15 +148,25 @@ struct QueryRegs {
   i32 qq;  // <q,q> for the integer kinds
 };
 
+// The pieces only (no arithmetic on them, so the loads can stay in flight) ...
 template <int KIND, int VEC, int NCH>
-__device__ __forceinline__ QueryRegs<KIND, VEC, NCH> load_query(const char* row, u32 npieces, int lane) {
+__device__ __forceinline__ QueryRegs<KIND, VEC, NCH> load_query_raw(const char* row, u32 npieces, int lane) {
   QueryRegs<KIND, VEC, NCH> Q;
   const int sub = lane & (LPC - 1);
-  i32 acc = 0;
 #pragma unroll
   for (int u = 0; u < NCH; ++u) {
     u32 pc = sub + LPC * u;
     Q.q[u] = pc < npieces ? load_piece<VEC>(row + (u64)pc * VEC) : zero_piece<VEC>();
+  }
+  Q.qq = 0;
+  return Q;
+}
+// ... and <q,q>, needed before the first distance is taken
+template <int KIND, int VEC, int NCH>
+__device__ __forceinline__ void query_finish(QueryRegs<KIND, VEC, NCH>& Q) {
+  i32 acc = 0;
+#pragma unroll
+  for (int u = 0; u < NCH; ++u) {
     if constexpr (KIND == K_U8) {
 #pragma unroll
       for (int i = 0; i < VEC / 4; ++i) acc = (i32)__builtin_amdgcn_udot4(Q.q[u].w[i], Q.q[u].w[i], (u32)acc, false);
@@ -166,6 +176,12 @@ __device__ __forceinline__ QueryRegs<KIND, VEC, NCH> load_query(const char* row,
     }
   }
   Q.qq = KindTraits<KIND>::is_int ? group_sum(acc) : 0;
+}
+
+template <int KIND, int VEC, int NCH>
+__device__ __forceinline__ QueryRegs<KIND, VEC, NCH> load_query(const char* row, u32 npieces, int lane) {
+  QueryRegs<KIND, VEC, NCH> Q = load_query_raw<KIND, VEC, NCH>(row, npieces, lane);
+  query_finish<KIND, VEC, NCH>(Q);
   return Q;
 }
 

@@ -56,7 +56,9 @@ struct PruneArgs {
   const u32* nvis;
   u32 vis_cap;
   u64* vis_rw;          // same memory as vis: lists longer than the LDS buffer are pruned in place
+  u32* meta;            // per row: degree | clean prefix length << 16 (written for the batch points)
   u64* edges;           // batch_size x R keys (dest << 32 | source), ~0 in unused slots
+  u32 stage_bytes;      // dynamic LDS for the selected points' vectors (0: read them from memory)
   u32* overflow_count;  // searches whose visited list did not fit
   u32* overflow_list;   // their indices
   long long a16;
@@ -67,12 +69,17 @@ struct PruneArgs {
 struct MergeArgs {
   const char* points;
   u32* graph;
+  u32* meta;  // per row: degree | clean prefix length << 16
   u32 R;
-  u64* keys;  // sorted edge keys (dest << 32 | source)
+  const u64* keys;  // sorted edge keys (dest << 32 | source)
   u64 nkeys;
-  const u32* seg_count;  // number of segments
-  const u32* seg_start;  // first key of each segment
-  u64* arena;            // spill space for candidate lists that do not fit in LDS
+  u32* list_count;     // [3]: segments filed for the fast / gram / generic re-prune
+  u64* list_items[3];  // (segment length << 32 | index of its first key)
+  u32 fast_amax;       // most new entries the fast path takes
+  u32 gram_ok;         // the matrix-core path applies to this dtype / row size
+  u32 gram_tmax;       // and to at most this many candidates
+  u32 stage_bytes;     // dynamic LDS of the generic kernel for the selected points' vectors
+  u64* arena;          // spill space for candidate lists that do not fit in LDS
   u64 arena_cap;
   unsigned long long* arena_top;
   u32* error_flag;
@@ -81,14 +88,21 @@ struct MergeArgs {
   DevCounters* counters;
 };
 
-constexpr u32 PRUNE_LDS_CAP = 768;   // candidate keys held in LDS by the step-1 prune kernel
-constexpr u32 MERGE_SPILL_MIN = 1728;  // step-2 candidate lists longer than this go to the spill arena
+constexpr u32 PRUNE_LDS_CAP = 512;     // candidate keys sorted in LDS by the step-1 prune kernel (a power of two)
+constexpr u32 MERGE_SPILL_MIN = 1024;  // step-2 candidate lists longer than this go to the spill arena (a power of two)
+constexpr u32 STAGE_BUDGET = 10240;    // LDS bytes the prune kernels may spend on the selected points' vectors
 
 // launchers (each returns the hipGetLastError() of its launches)
 hipError_t launch_search(const DistCfg& cfg, const SearchArgs& a, hipStream_t s);
 hipError_t launch_prune(const DistCfg& cfg, const PruneArgs& a, hipStream_t s);
-hipError_t launch_segments(const u64* keys, u64 nkeys, u32* seg_count, u32* seg_start, hipStream_t s);
+hipError_t launch_plan(const MergeArgs& a, hipStream_t s);
 hipError_t launch_merge(const DistCfg& cfg, const MergeArgs& a, u32 grid, hipStream_t s);
+hipError_t launch_meta_from_rows(const u32* graph, u64 n, u32 R, u32* meta, hipStream_t s);
+hipError_t launch_meta_forget_clean(u64 n, u32* meta, hipStream_t s);
+bool gram_path_ok(const DistCfg& cfg);
+u32 gram_path_tmax();
+u32 fast_path_amax(const DistCfg& cfg);
+u32 prune_stage_bytes(u32 R, const DistCfg& cfg);
 
 // stable LSD radix sort of 64-bit keys on bits [32, 32+key_bits); result is left in `keys`
 // (`tmp` holds `count` keys, `hist` holds radix_hist_entries(count) u32)

@@ -135,6 +135,8 @@ struct ann_graph {
   u64 rounds = 0;
   DistCfg cfg{};
   u32* rows = nullptr;            // device, n x R
+  u32* meta = nullptr;            // device, n: degree | clean prefix length << 16
+  float clean_alpha = 0.0f;       // the alpha the clean prefixes were pruned with
   DevCounters* counters = nullptr;  // device
   ann_stats stats{};
   u32 hash_bits = 0;
@@ -148,9 +150,9 @@ namespace {
 struct BatchScratch {
   u64 bmax = 0;
   u32 vis_cap = 0;
-  DevBuf qidx, vis, nvis, edges, edges_tmp, hist, seg_start, small, ovf_list, arena;
+  DevBuf qidx, vis, nvis, edges, edges_tmp, hist, lists, small, ovf_list, arena;
   u64 arena_cap = 0;
-  // small: [0] overflow_count u32, [1] seg_count u32, [2] error flag u32, [4..5] arena_top u64
+  // small: [0] overflow_count u32, [2] error flag u32, [4..5] arena_top u64, [8..10] work list counts
   int alloc(u64 b, u32 R, u32 cap) {
     bmax = b;
     vis_cap = cap;
@@ -163,7 +165,7 @@ struct BatchScratch {
     HIP_TRY(edges.alloc(E * 8));
     HIP_TRY(edges_tmp.alloc(E * 8));
     HIP_TRY(hist.alloc(radix_hist_entries(E) * 4));
-    HIP_TRY(seg_start.alloc(E * 4));
+    HIP_TRY(lists.alloc(3 * E * 8));
     HIP_TRY(small.alloc(64));
     HIP_TRY(ovf_list.alloc(b * 4));
     HIP_TRY(arena.alloc(arena_cap * 8));
@@ -197,6 +199,11 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   const u32 R = g->R;
   const u64 E = b * R;
   const long long a16 = llround((double)alpha * 65536.0);
+  if (g->clean_alpha != alpha) {
+    // prefixes pruned with another alpha say nothing about this one
+    HIP_TRY(launch_meta_forget_clean(g->n, g->meta, st));
+    g->clean_alpha = alpha;
+  }
   u32* small = S.small.as<u32>();
   DevCounters* ctr = g->collect ? g->counters : nullptr;
 
@@ -235,6 +242,8 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   pa.vis_rw = S.vis.as<u64>();
   pa.nvis = S.nvis.as<u32>();
   pa.vis_cap = S.vis_cap;
+  pa.meta = g->meta;
+  pa.stage_bytes = prune_stage_bytes(R, g->cfg);
   pa.edges = S.edges.as<u64>();
   pa.overflow_count = small + 0;
   pa.overflow_list = S.ovf_list.as<u32>();
@@ -294,16 +303,21 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   HIP_TRY(radix_sort_edges(S.edges.as<u64>(), S.edges_tmp.as<u64>(), S.hist.as<u32>(), E, bits_for(g->n), st));
   tm.mark(3, st);
 
-  // step 2b: one wave per destination: append, or prune the row if it overflows
-  HIP_TRY(launch_segments(S.edges.as<u64>(), E, small + 1, S.seg_start.as<u32>(), st));
+  // step 2b: cut the keys into segments of equal destination; append where the row has room,
+  // otherwise one wave per row prunes it again
   MergeArgs ma{};
   ma.points = static_cast<const char*>(points);
   ma.graph = g->rows;
+  ma.meta = g->meta;
   ma.R = R;
   ma.keys = S.edges.as<u64>();
   ma.nkeys = E;
-  ma.seg_count = small + 1;
-  ma.seg_start = S.seg_start.as<u32>();
+  ma.list_count = small + 8;
+  for (int c = 0; c < 3; ++c) ma.list_items[c] = S.lists.as<u64>() + (u64)c * E;
+  ma.fast_amax = fast_path_amax(g->cfg);
+  ma.gram_ok = gram_path_ok(g->cfg) ? 1u : 0u;
+  ma.gram_tmax = gram_path_tmax();
+  ma.stage_bytes = prune_stage_bytes(R, g->cfg);
   ma.arena = S.arena.as<u64>();
   ma.arena_cap = S.arena_cap;
   ma.arena_top = reinterpret_cast<unsigned long long*>(small + 4);
@@ -311,7 +325,10 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   ma.a16 = a16;
   ma.af = alpha;
   ma.counters = ctr;
-  const u64 want = E < 65536 ? E : 65536;
+  HIP_TRY(launch_plan(ma, st));
+  // grid-stride kernels over work lists whose lengths stay on the device: enough waves to fill
+  // the chip, no more (idle workgroups are not free)
+  const u64 want = E < 8192 ? E : 8192;
   HIP_TRY(launch_merge(g->cfg, ma, (u32)(want ? want : 1), st));
   tm.mark(4, st);
 
@@ -352,6 +369,8 @@ int new_graph(u64 n, u32 d, int dtype, int metric, u32 R, ann_graph** out) {
   g->metric = metric;
   g->cfg = cfg;
   hipError_t e = hipMalloc(reinterpret_cast<void**>(&g->rows), (size_t)n * R * sizeof(u32));
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&g->meta), (size_t)n * sizeof(u32));
+  if (e == hipSuccess) e = hipMemset(g->meta, 0, (size_t)n * sizeof(u32));
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&g->counters), sizeof(DevCounters));
   if (e == hipSuccess) e = hipMemset(g->counters, 0, sizeof(DevCounters));
   if (e != hipSuccess) {
@@ -371,6 +390,7 @@ const char* ann_last_error(void) { return g_err.c_str(); }
 void ann_graph_free(ann_graph* g) {
   if (!g) return;
   if (g->rows) (void)hipFree(g->rows);
+  if (g->meta) (void)hipFree(g->meta);
   if (g->counters) (void)hipFree(g->counters);
   delete g;
 }
@@ -424,6 +444,8 @@ int ann_graph_from_host(const uint32_t* rows_host, uint64_t n, uint32_t d, ann_d
   if (rc) return rc;
   g->start = start;
   hipError_t e = hipMemcpy(g->rows, rows_host, (size_t)n * R * sizeof(u32), hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = launch_meta_from_rows(g->rows, n, R, g->meta, nullptr);
+  if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     ann_graph_free(g);
     return fail(ANN_EHIP, "copy of rows: %s", hipGetErrorString(e));

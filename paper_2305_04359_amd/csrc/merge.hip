@@ -1,0 +1,720 @@
+// Step 2 of BatchInsert (Alg. 3 of the paper): for every existing point b that was chosen by
+// batch points, N_out(b) <- N_out(b) U N, and prune(b, N_out(b), R) if that exceeds R.
+//
+// The sorted edge keys are cut into segments of equal destination by a planning kernel, which
+// appends directly where the row has room and otherwise files the segment under one of three
+// kinds of re-prune, each served by its own kernel (one wavefront per row):
+//
+//   fast     the row still starts with the output of its last prune (its "clean prefix": sorted
+//            by distance to b and free of pairs where one removes the other, which is what prune
+//            guarantees of what it keeps) and only a few entries are new.  Only pairs with a new
+//            entry can change anything, so the wave measures every candidate against b and
+//            against the new entries in one sweep and replays the scan on bit masks.
+//   gram     u8/i8 rows of at most 96 candidates: all pair distances from the int8 Gram matrix
+//            on the matrix cores (exact), then the scan on bit masks.
+//   generic  everything else: the wave-wide scan of prune_device.hpp, candidates in LDS or, for
+//            very long lists, in a spill arena in device memory.
+//
+// Every path computes exactly prune(b, U, R) with U = old row followed by the new sources in
+// batch order; they differ only in which distances they have to take.
+#include <utility>
+
+#include "ann_device.hpp"
+#include "ann_internal.hpp"
+#include "ann_dispatch.hpp"
+#include "prune_device.hpp"
+
+namespace annmi {
+
+__device__ __forceinline__ u32 meta_deg(u32 m) { return m & 0xFFFFu; }
+__device__ __forceinline__ u32 meta_clean(u32 m) { return m >> 16; }
+__device__ __forceinline__ u32 make_meta(u32 deg, u32 clean) { return deg | (clean << 16); }
+
+// ---------------------------------------------------------------------------------------------
+// planning: one thread per edge key; the first key of each segment does the work
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void plan_kernel(MergeArgs a) {
+  __shared__ u32 cnt_lds[3];
+  __shared__ u32 base_lds[3];
+  if (threadIdx.x < 3) cnt_lds[threadIdx.x] = 0;
+  __syncthreads();
+
+  const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+  int kind = -1;  // 0 fast, 1 gram, 2 generic
+  u32 slot = 0, cnt = 0;
+  if (i < a.nkeys) {
+    const u32 b = (u32)(a.keys[i] >> 32);
+    const bool head = b != NONE_ID && (i == 0 || (u32)(a.keys[i - 1] >> 32) != b);
+    if (head) {
+      // length of the segment: gallop, then bisect (keys are sorted by destination)
+      u64 lo = i, step = 1;
+      while (i + step < a.nkeys && (u32)(a.keys[i + step] >> 32) == b) {
+        lo = i + step;
+        step <<= 1;
+      }
+      u64 hi = i + step < a.nkeys ? i + step : a.nkeys;
+      while (hi - lo > 1) {
+        const u64 mid = (lo + hi) >> 1;
+        if ((u32)(a.keys[mid] >> 32) == b)
+          lo = mid;
+        else
+          hi = mid;
+      }
+      cnt = (u32)(hi - i);
+      const u32 m = a.meta[b];
+      const u32 deg = meta_deg(m), clean = meta_clean(m);
+      if (deg + cnt <= a.R) {
+        u32* row = a.graph + (u64)b * a.R;
+        for (u32 j = 0; j < cnt; ++j) row[deg + j] = (u32)(a.keys[i + j] & 0xFFFFFFFFull);
+        a.meta[b] = make_meta(deg + cnt, clean);
+        if (a.counters != nullptr) {
+          atomicAdd(&a.counters->appends, 1ull);
+          atomicAdd(&a.counters->edges, (unsigned long long)cnt);
+        }
+      } else {
+        const u32 fresh = deg - clean + cnt;
+        if (clean <= 64 && fresh <= a.fast_amax)
+          kind = 0;
+        else if (a.gram_ok && deg + cnt <= a.gram_tmax)
+          kind = 1;
+        else
+          kind = 2;
+        slot = atomicAdd(&cnt_lds[kind], 1u);
+      }
+    }
+  }
+  __syncthreads();
+  // one global atomic per work list and workgroup; the order of a list has no influence on any
+  // result, every segment is processed on its own
+  if (threadIdx.x < 3 && cnt_lds[threadIdx.x] != 0)
+    base_lds[threadIdx.x] = atomicAdd(&a.list_count[threadIdx.x], cnt_lds[threadIdx.x]);
+  __syncthreads();
+  if (kind >= 0) a.list_items[kind][base_lds[kind] + slot] = ((u64)cnt << 32) | (u32)i;
+}
+
+hipError_t launch_plan(const MergeArgs& a, hipStream_t s) {
+  if (a.nkeys == 0) return hipSuccess;
+  const u32 grid = (u32)((a.nkeys + 255) / 256);
+  hipLaunchKernelGGL(plan_kernel, dim3(grid), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// fast path: clean prefix plus at most FastAMax new entries
+// ---------------------------------------------------------------------------------------------
+template <int NCH>
+struct FastAMax {
+  static constexpr int value = NCH <= 2 ? 4 : (NCH <= 4 ? 2 : 1);
+};
+
+// lane-local part of the distance between a query and the row pieces x; `xx` is the shared
+// <x,x> part for the integer kinds
+template <int KIND, int VEC, int NCH>
+__device__ __forceinline__ i32 xx_part(const Piece<VEC> (&x)[NCH]) {
+  i32 xx = 0;
+  if constexpr (KIND == K_U8) {
+#pragma unroll
+    for (int u = 0; u < NCH; ++u)
+#pragma unroll
+      for (int i = 0; i < VEC / 4; ++i) xx = (i32)__builtin_amdgcn_udot4(x[u].w[i], x[u].w[i], (u32)xx, false);
+  } else if constexpr (KIND == K_I8) {
+#pragma unroll
+    for (int u = 0; u < NCH; ++u)
+#pragma unroll
+      for (int i = 0; i < VEC / 4; ++i) xx = __builtin_amdgcn_sdot4((i32)x[u].w[i], (i32)x[u].w[i], xx, false);
+  }
+  return xx;
+}
+
+template <int KIND, int VEC, int NCH>
+__device__ __forceinline__ u32 distance_key_xx(const QueryRegs<KIND, VEC, NCH>& Q, const Piece<VEC> (&x)[NCH], i32 xx) {
+  if constexpr (KIND == K_U8) {
+    u32 qx = 0;
+#pragma unroll
+    for (int u = 0; u < NCH; ++u)
+#pragma unroll
+      for (int i = 0; i < VEC / 4; ++i) qx = __builtin_amdgcn_udot4(Q.q[u].w[i], x[u].w[i], qx, false);
+    return dkey_from_int(group_sum(xx - 2 * (i32)qx) + Q.qq);
+  } else if constexpr (KIND == K_I8) {
+    i32 qx = 0;
+#pragma unroll
+    for (int u = 0; u < NCH; ++u)
+#pragma unroll
+      for (int i = 0; i < VEC / 4; ++i) qx = __builtin_amdgcn_sdot4((i32)Q.q[u].w[i], (i32)x[u].w[i], qx, false);
+    return dkey_from_int(group_sum(xx - 2 * qx) + Q.qq);
+  } else {
+    return distance_key<KIND, VEC, NCH>(Q, x);
+  }
+}
+
+template <int KIND, int VEC, int NCH>
+__global__ __launch_bounds__(64) void merge_fast_kernel(MergeArgs a, VecTable T) {
+  constexpr int AMAX = FastAMax<NCH>::value;
+  constexpr int PBF = PassBatch<VEC, NCH>::value > 4 ? 4 : PassBatch<VEC, NCH>::value;
+  __shared__ u32 ids_lds[64 + AMAX];       // clean ids by row position, then the new ids
+  __shared__ u32 dk_lds[1 + AMAX][64];     // distance keys by row position: to b, to each new entry
+
+  const int lane = threadIdx.x;
+  const int sub = lane & (LPC - 1);
+  const u32 grp = (u32)lane >> 3;
+  const u32 nitems = a.list_count[0];
+  const AlphaParam al{a.a16, a.af};
+  unsigned long long n_rep = 0, n_edges = 0, n_pair = 0;
+
+  for (u32 it = blockIdx.x; it < nitems; it += gridDim.x) {
+    const u64 item = a.list_items[0][it];
+    const u32 i0 = (u32)item, cnt = (u32)(item >> 32);
+    const u32 b = (u32)(a.keys[i0] >> 32);
+    const u32 m = a.meta[b];
+    const u32 deg = meta_deg(m), clean = meta_clean(m);
+    const u32 stale = deg - clean;  // appended since the last prune
+    const u32 na = stale + cnt;     // 1 <= na <= AMAX
+    u32* row = a.graph + (u64)b * a.R;
+
+    const u32 myid = (u32)lane < clean ? row[lane] : NONE_ID;
+    u32 mynew = NONE_ID;
+    if ((u32)lane < na) mynew = (u32)lane < stale ? row[clean + lane] : (u32)(a.keys[i0 + (lane - stale)] & 0xFFFFFFFFull);
+    ids_lds[lane] = myid;
+    if ((u32)lane < na) ids_lds[64 + lane] = mynew;
+
+    const QueryRegs<KIND, VEC, NCH> Qb = load_query<KIND, VEC, NCH>(T.base + (u64)b * T.row_bytes, T.npieces, lane);
+    QueryRegs<KIND, VEC, NCH> Qn[AMAX];
+    u32 nid[AMAX];
+#pragma unroll
+    for (int k = 0; k < AMAX; ++k) {
+      nid[k] = readlane_u32(mynew, k);
+      if ((u32)k < na)
+        Qn[k] = load_query<KIND, VEC, NCH>(T.base + (u64)nid[k] * T.row_bytes, T.npieces, lane);
+      else
+        Qn[k] = Qb;
+    }
+    __syncthreads();
+
+    // one sweep over the clean prefix and the new entries: candidate index c < clean is row
+    // position c, index 64 + k is new entry k; each is measured against b and every new entry
+    u32 res[1 + AMAX];
+#pragma unroll
+    for (int q = 0; q <= AMAX; ++q) res[q] = 0;
+    u32 newres[1 + AMAX];  // the same for the pass over the new entries (valid in lanes 8k)
+#pragma unroll
+    for (int q = 0; q <= AMAX; ++q) newres[q] = 0;
+    const u32 npass_clean = (clean + 7u) >> 3;
+    for (u32 t0 = 0; t0 < npass_clean + 1; t0 += PBF) {
+      Piece<VEC> x[PBF][NCH];
+#pragma unroll
+      for (int tt = 0; tt < PBF; ++tt) {
+        const u32 t = t0 + tt;
+        // passes 0..npass_clean-1 cover the clean prefix, pass npass_clean the new entries
+        const bool newpass = t == npass_clean;
+        const u32 c = newpass ? grp : 8u * t + grp;
+        const bool ok = newpass ? (grp < na) : (t < npass_clean && c < clean);
+        const u32 id = ok ? ids_lds[newpass ? 64 + grp : c] : 0u;
+        const char* src = T.base + (u64)id * T.row_bytes;
+#pragma unroll
+        for (int u = 0; u < NCH; ++u) {
+          const u32 pc = sub + LPC * u;
+          x[tt][u] = (ok && pc < T.npieces) ? load_piece<VEC>(src + (u64)pc * VEC) : zero_piece<VEC>();
+        }
+      }
+#pragma unroll
+      for (int tt = 0; tt < PBF; ++tt) {
+        const u32 t = t0 + tt;
+        if (t <= npass_clean) {  // uniform
+          const i32 xx = xx_part<KIND, VEC, NCH>(x[tt]);
+          const bool newpass = t == npass_clean;
+          const u32 d0 = distance_key_xx<KIND, VEC, NCH>(Qb, x[tt], xx);
+          if (newpass)
+            newres[0] = d0;
+          else if ((u32)sub == t)
+            res[0] = d0;
+#pragma unroll
+          for (int k = 0; k < AMAX; ++k) {
+            if ((u32)k < na) {  // uniform
+              const u32 dkk = distance_key_xx<KIND, VEC, NCH>(Qn[k], x[tt], xx);
+              if (newpass)
+                newres[1 + k] = dkk;
+              else if ((u32)sub == t)
+                res[1 + k] = dkk;
+            }
+          }
+        }
+      }
+    }
+    // lane l holds the results of row position cand_of_lane(l); bring them to lane = position
+    {
+      const u32 c = cand_of_lane(lane);
+#pragma unroll
+      for (int q = 0; q <= AMAX; ++q) dk_lds[q][c] = res[q];
+    }
+    __syncthreads();
+    const bool isc = (u32)lane < clean;
+    const u32 dB = dk_lds[0][lane];
+    const u64 keyc = isc ? make_key(dB, myid) : KEY_INF;
+
+    // per new entry k: its key, its place among the clean entries, what it removes, what removes it
+    u64 keyn[AMAX];
+    u32 rank[AMAX];
+    u64 removes[AMAX], removed_by[AMAX];
+    u32 dBn[AMAX];
+#pragma unroll
+    for (int k = 0; k < AMAX; ++k) {
+      dBn[k] = readlane_u32(newres[0], 8 * k);
+      keyn[k] = make_key(dBn[k], nid[k]);
+      const u32 dkj = dk_lds[1 + k][lane];  // distance new entry k <-> clean entry `lane`
+      rank[k] = (u32)__builtin_popcountll(ballot(isc && keyc < keyn[k]));
+      removes[k] = ballot(isc && alpha_dominates<KIND>(al, dkj, dB));
+      removed_by[k] = ballot(isc && alpha_dominates<KIND>(al, dkj, dBn[k]));
+    }
+    // replay the scan: clean entries never remove each other, so only the new entries matter
+    u64 alive = clean >= 64 ? ~0ull : ((1ull << clean) - 1ull);
+    u32 selnew = 0;
+#pragma unroll
+    for (int r = 0; r < AMAX; ++r) {
+      // the new entry that is r-th among the new entries in (distance, id) order
+#pragma unroll
+      for (int k = 0; k < AMAX; ++k) {
+        if ((u32)k < na) {
+          u32 ord = 0;
+#pragma unroll
+          for (int l = 0; l < AMAX; ++l)
+            if ((u32)l < na && keyn[l] < keyn[k]) ++ord;
+          if (ord == (u32)r) {
+            const u64 before = rank[k] >= 64 ? ~0ull : ((1ull << rank[k]) - 1ull);
+            bool killed = (removed_by[k] & alive & before) != 0;
+#pragma unroll
+            for (int l = 0; l < AMAX; ++l) {
+              if ((u32)l < na && l != k && ((selnew >> l) & 1u) && keyn[l] < keyn[k]) {
+                // distance new l <-> new k: query l against candidate k of the new pass
+                const u32 dlk = readlane_u32(newres[1 + l], 8 * k);
+                killed = killed || alpha_dominates<KIND>(al, dlk, dBn[k]);
+              }
+            }
+            if (!killed) {
+              selnew |= 1u << k;
+              alive &= ~(removes[k] & ~before);
+            }
+          }
+        }
+      }
+    }
+    // positions in the merged order, cut at R
+    u32 pos = (u32)__builtin_popcountll(alive & lanemask_lt(lane));
+    u32 newpos = 0;
+#pragma unroll
+    for (int k = 0; k < AMAX; ++k) {
+      if ((u32)k < na && ((selnew >> k) & 1u)) {
+        if (rank[k] <= (u32)lane) ++pos;  // new entry k precedes clean entry `lane`
+        const u64 before = rank[k] >= 64 ? ~0ull : ((1ull << rank[k]) - 1ull);
+        u32 pk = (u32)__builtin_popcountll(alive & before);
+#pragma unroll
+        for (int l = 0; l < AMAX; ++l)
+          if ((u32)l < na && ((selnew >> l) & 1u) && keyn[l] < keyn[k]) ++pk;
+        if (lane == k) newpos = pk;
+      }
+    }
+    const u32 nsel = (u32)__builtin_popcountll(alive) + (u32)__builtin_popcount(selnew);
+    const u32 kept = nsel < a.R ? nsel : a.R;
+    __syncthreads();
+    if (isc && ((alive >> lane) & 1ull) && pos < a.R) row[pos] = myid;
+    if ((u32)lane < na && ((selnew >> lane) & 1u) && newpos < a.R) row[newpos] = mynew;
+    for (u32 j = kept + lane; j < a.R; j += 64) row[j] = NONE_ID;
+    if (lane == 0) a.meta[b] = make_meta(kept, kept);
+    ++n_rep;
+    n_edges += cnt;
+    n_pair += (unsigned long long)(clean + na) * (na + 1);
+  }
+  if (a.counters != nullptr && lane == 0 && n_rep) {
+    atomicAdd(&a.counters->reprunes, n_rep);
+    atomicAdd(&a.counters->edges, n_edges);
+    atomicAdd(&a.counters->prune_evals, n_pair);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// prune of a short candidate list of u8/i8 vectors with the matrix cores
+//
+// An overflowing row has R old entries plus a few new ones.  For such a list every pair
+// distance the scan of prune() can ask for is an entry of the Gram matrix of the candidate
+// vectors, a small dense contraction.  The wave stages the vectors in LDS (u8 shifted by -128 so
+// that they are int8; distances are translation invariant), sorts the candidates by
+// (d(b,.), id), forms the Gram matrix of the sorted list with v_mfma_i32_32x32x32_i8 (exact in
+// int32), reduces each entry at once to the bit "i removes j" (alpha * D(i,j) <= d(b,j), as the
+// equivalent D(i,j) <= floor(d(b,j) * 2^16 / a16)), and then replays the scan of prune() on bit
+// masks with scalar instructions.
+// ---------------------------------------------------------------------------------------------
+constexpr u32 SM_TMAX = 96;     // candidates handled by this path
+constexpr u32 SM_STRIDE = 144;  // bytes between staged vectors (128 + 16: spreads LDS banks)
+
+struct SmallLds {
+  u64 key[SM_TMAX];   // by arrival index
+  u32 uid[SM_TMAX];   // ids by arrival index
+  u32 nrm[SM_TMAX];   // squared norms of the shifted vectors, by arrival index
+  u32 sid[SM_TMAX];   // ids, sorted by (distance to b, id)
+  u32 snrm[SM_TMAX];  // norms, sorted
+  i32 sthr[SM_TMAX];  // largest D(i,j) that still removes j, sorted
+  u32 inv[SM_TMAX];   // sorted position -> arrival index
+};
+
+typedef int v4i_t __attribute__((ext_vector_type(4)));
+typedef int v16i_t __attribute__((ext_vector_type(16)));
+
+template <int VEC, int NCH>
+struct SmallPathOk {
+  static constexpr bool value = (8 * NCH * VEC <= 128);
+};
+
+// floor(d * 2^16 / a16) for 0 <= d < 2^31, 0 < a16 < 2^31, clamped to INT32_MAX
+__device__ __forceinline__ i32 alpha_threshold(i32 d, i64 a16) {
+  const u64 x = (u64)(u32)d << 16;
+  u64 t = (u64)__builtin_floor((double)x / (double)a16);
+  if (t * (u64)a16 > x)
+    --t;
+  else if ((t + 1) * (u64)a16 <= x)
+    ++t;
+  return t > 0x7FFFFFFFull ? 0x7FFFFFFF : (i32)t;
+}
+
+// One 32x32 tile of the Gram matrix of the sorted candidates: rows 32*RB.., columns 32*CB...
+// Accumulator register r of lane l is entry (row 8*(r/4) + 4*(l/32) + r%4, column l%32), so one
+// ballot per register yields the 32 "removes" bits of two rows, which go to the lanes that own
+// those rows.
+template <int RB, int CB, int R_>
+__device__ __forceinline__ void gram_tile_reg(const v16i_t& acc, const SmallLds& S, bool colok, i32 ncol, i32 tcol,
+                                              u32 half, u32& Klo, u32& Khi) {
+  constexpr int mlo = 32 * RB + 8 * (R_ / 4) + (R_ % 4);
+  const i32 nrow = (i32)S.snrm[mlo + 4 * half];
+  const i32 D = nrow + ncol - 2 * acc[R_];
+  const u64 bm = ballot(colok && D <= tcol);
+  const u32 lo = (u32)bm, hi = (u32)(bm >> 32);
+  if constexpr (mlo < 64) {
+    Klo = writelane_u32<mlo>(Klo, lo);
+    Klo = writelane_u32<mlo + 4>(Klo, hi);
+  } else if constexpr (CB == 2) {
+    Khi = writelane_u32<mlo - 64>(Khi, lo);
+    Khi = writelane_u32<mlo + 4 - 64>(Khi, hi);
+  }
+}
+
+template <int RB, int CB, int... Rs>
+__device__ __forceinline__ void gram_tile_regs(const v16i_t& acc, const SmallLds& S, bool colok, i32 ncol, i32 tcol,
+                                               u32 half, u32& Klo, u32& Khi, std::integer_sequence<int, Rs...>) {
+  (gram_tile_reg<RB, CB, Rs>(acc, S, colok, ncol, tcol, half, Klo, Khi), ...);
+}
+
+template <int RB, int CB>
+__device__ __forceinline__ void gram_tile(const unsigned char* Xs, const SmallLds& S, u32 total, u32 ksteps, int lane,
+                                          u32& Klo, u32& Khi) {
+  const u32 half = (u32)lane >> 5;
+  const u32 ia = 32u * RB + (lane & 31), ib = 32u * CB + (lane & 31);
+  const u32 ra = ia < total ? S.inv[ia] : 0u;
+  const u32 rb = ib < total ? S.inv[ib] : 0u;
+  const unsigned char* pa = Xs + ra * SM_STRIDE + 16u * half;
+  const unsigned char* pb = Xs + rb * SM_STRIDE + 16u * half;
+  v16i_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  for (u32 ks = 0; ks < ksteps; ++ks) {
+    const v4i_t av = *reinterpret_cast<const v4i_t*>(pa + 32u * ks);
+    const v4i_t bv = *reinterpret_cast<const v4i_t*>(pb + 32u * ks);
+    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(av, bv, acc, 0, 0, 0);
+  }
+  const bool colok = ib < total;
+  const i32 ncol = colok ? (i32)S.snrm[ib] : 0;
+  const i32 tcol = colok ? S.sthr[ib] : -1;
+  gram_tile_regs<RB, CB>(acc, S, colok, ncol, tcol, half, Klo, Khi, std::make_integer_sequence<int, 16>{});
+}
+
+// S.uid[0..total) holds the candidate ids (old row entries first).  Writes the pruned row and
+// returns its length.
+template <int KIND, int VEC, int NCH>
+__device__ __forceinline__ u32 reprune_small_int(const VecTable& T, const QueryRegs<KIND, VEC, NCH>& Q,
+                                                 unsigned char* Xs, SmallLds& S, u32 total, u32 R, i64 a16,
+                                                 u32* row, int lane) {
+  constexpr int PB = PassBatch<VEC, NCH>::value;
+  const int sub = lane & (LPC - 1);
+  const u32 grp = (u32)lane >> 3;
+  const u32 npass = (total + 7u) >> 3;
+  const u32 flip = KIND == K_U8 ? 0x80808080u : 0u;
+
+  // stage the vectors, take d(b, x) and the norms
+  for (u32 t0 = 0; t0 < npass; t0 += PB) {
+    Piece<VEC> x[PB][NCH];
+    u32 ids[PB];
+#pragma unroll
+    for (int tt = 0; tt < PB; ++tt) {
+      const u32 c = 8u * (t0 + tt) + grp;
+      const bool ok = c < total;
+      ids[tt] = ok ? S.uid[c] : 0u;
+      const char* src = T.base + (u64)ids[tt] * T.row_bytes;
+#pragma unroll
+      for (int u = 0; u < NCH; ++u) {
+        const u32 pc = sub + LPC * u;
+        x[tt][u] = (ok && pc < T.npieces) ? load_piece<VEC>(src + (u64)pc * VEC) : zero_piece<VEC>();
+      }
+    }
+#pragma unroll
+    for (int tt = 0; tt < PB; ++tt) {
+      const u32 c = 8u * (t0 + tt) + grp;
+      const u32 dk = distance_key<KIND, VEC, NCH>(Q, x[tt]);
+      i32 nn = 0;
+#pragma unroll
+      for (int u = 0; u < NCH; ++u) {
+        const u32 pc = sub + LPC * u;
+#pragma unroll
+        for (int i = 0; i < VEC / 4; ++i) {
+          const u32 wv = pc < T.npieces ? (x[tt][u].w[i] ^ flip) : 0u;
+          nn = __builtin_amdgcn_sdot4((i32)wv, (i32)wv, nn, false);
+          if (c < total) *reinterpret_cast<u32*>(Xs + c * SM_STRIDE + pc * VEC + 4 * i) = wv;
+        }
+      }
+      nn = group_sum(nn);
+      if (sub == 0 && c < total) {
+        S.key[c] = make_key(dk, ids[tt]);
+        S.nrm[c] = (u32)nn;
+      }
+    }
+  }
+  __syncthreads();
+
+  // rank of every candidate under (distance, id); keys are distinct
+  {
+    const u32 j0 = lane, j1 = lane + 64;
+    const u64 k0 = j0 < total ? S.key[j0] : KEY_INF;
+    const u64 k1 = j1 < total ? S.key[j1] : KEY_INF;
+    u32 r0 = 0, r1 = 0;
+    for (u32 i = 0; i < total; ++i) {
+      const u64 ki = S.key[i];
+      r0 += ki < k0 ? 1u : 0u;
+      r1 += ki < k1 ? 1u : 0u;
+    }
+    if (j0 < total) {
+      S.sid[r0] = key_id(k0);
+      S.snrm[r0] = S.nrm[j0];
+      S.sthr[r0] = alpha_threshold(int_from_dkey(key_dkey(k0)), a16);
+      S.inv[r0] = j0;
+    }
+    if (j1 < total) {
+      S.sid[r1] = key_id(k1);
+      S.snrm[r1] = S.nrm[j1];
+      S.sthr[r1] = alpha_threshold(int_from_dkey(key_dkey(k1)), a16);
+      S.inv[r1] = j1;
+    }
+  }
+  __syncthreads();
+
+  // Gram matrix tile by tile; K0[c] of lane i = bits "sorted candidate i removes candidate 32c+j",
+  // K1 the same for candidates 64..95 (only column block 2 matters there)
+  const u32 nb = (total + 31u) >> 5;
+  const u32 ksteps = (u32)((T.row_bytes + 31) / 32);
+  u32 K0[3] = {0u, 0u, 0u};
+  u32 K1 = 0u;
+  gram_tile<0, 0>(Xs, S, total, ksteps, lane, K0[0], K1);
+  if (nb > 1) {
+    gram_tile<0, 1>(Xs, S, total, ksteps, lane, K0[1], K1);
+    gram_tile<1, 1>(Xs, S, total, ksteps, lane, K0[1], K1);
+  }
+  if (nb > 2) {
+    gram_tile<0, 2>(Xs, S, total, ksteps, lane, K0[2], K1);
+    gram_tile<1, 2>(Xs, S, total, ksteps, lane, K0[2], K1);
+    gram_tile<2, 2>(Xs, S, total, ksteps, lane, K0[2], K1);
+  }
+
+  // the scan of prune(): walk the sorted list, select what is still alive, remove what it removes
+  const u32 nlo = total < 64u ? total : 64u;
+  u64 rem_lo = nlo == 64u ? ~0ull : ((1ull << nlo) - 1ull);
+  u32 rem_hi = total > 64u ? ((total - 64u) >= 32u ? ~0u : ((1u << (total - 64u)) - 1u)) : 0u;
+  u64 sel_lo = 0;
+  u32 sel_hi = 0, nout = 0;
+  while (rem_lo != 0 && nout < R) {
+    const int i = __builtin_ctzll(rem_lo);
+    sel_lo |= 1ull << i;
+    ++nout;
+    const u64 klo = (u64)readlane_u32(K0[0], i) | ((u64)readlane_u32(K0[1], i) << 32);
+    rem_lo &= ~klo;
+    rem_lo &= ~(1ull << i);
+    rem_hi &= ~readlane_u32(K0[2], i);
+  }
+  while (rem_hi != 0 && nout < R) {
+    const int i = __builtin_ctz(rem_hi);
+    sel_hi |= 1u << i;
+    ++nout;
+    rem_hi &= ~readlane_u32(K1, i);
+    rem_hi &= ~(1u << i);
+  }
+
+  // write the row: selected ids in sorted order, then padding
+  if ((sel_lo >> lane) & 1ull) row[__builtin_popcountll(sel_lo & lanemask_lt(lane))] = S.sid[lane];
+  if (lane < 32 && ((sel_hi >> lane) & 1u))
+    row[__builtin_popcountll(sel_lo) + __builtin_popcount(sel_hi & ((1u << lane) - 1u))] = S.sid[64 + lane];
+  for (u32 j = nout + lane; j < R; j += 64) row[j] = NONE_ID;
+  __syncthreads();
+  return nout;
+}
+
+// ---------------------------------------------------------------------------------------------
+// gram path kernel
+// ---------------------------------------------------------------------------------------------
+template <int KIND, int VEC, int NCH>
+__global__ __launch_bounds__(64) void merge_gram_kernel(MergeArgs a, VecTable T) {
+  constexpr bool kOk = KindTraits<KIND>::is_int && SmallPathOk<VEC, NCH>::value;
+  if constexpr (kOk) {
+    __shared__ __align__(16) unsigned char Xs[SM_TMAX * SM_STRIDE];
+    __shared__ SmallLds small;
+    const int lane = threadIdx.x;
+    const u32 nitems = a.list_count[1];
+    unsigned long long n_rep = 0, n_edges = 0, n_pair = 0;
+    for (u32 it = blockIdx.x; it < nitems; it += gridDim.x) {
+      const u64 item = a.list_items[1][it];
+      const u32 i0 = (u32)item, cnt = (u32)(item >> 32);
+      const u32 b = (u32)(a.keys[i0] >> 32);
+      const u32 deg = meta_deg(a.meta[b]);
+      const u32 total = deg + cnt;
+      u32* row = a.graph + (u64)b * a.R;
+      for (u32 j = lane; j < total; j += 64)
+        small.uid[j] = j < deg ? row[j] : (u32)(a.keys[i0 + (j - deg)] & 0xFFFFFFFFull);
+      __syncthreads();
+      const QueryRegs<KIND, VEC, NCH> Qb = load_query<KIND, VEC, NCH>(T.base + (u64)b * T.row_bytes, T.npieces, lane);
+      const u32 kept = reprune_small_int<KIND, VEC, NCH>(T, Qb, Xs, small, total, a.R, a.a16, row, lane);
+      if (lane == 0) a.meta[b] = make_meta(kept, kept);
+      ++n_rep;
+      n_edges += cnt;
+      n_pair += (unsigned long long)total * (total + 1) / 2;
+    }
+    if (a.counters != nullptr && lane == 0 && n_rep) {
+      atomicAdd(&a.counters->reprunes, n_rep);
+      atomicAdd(&a.counters->edges, n_edges);
+      atomicAdd(&a.counters->prune_evals, n_pair);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// generic path kernel
+// ---------------------------------------------------------------------------------------------
+template <int KIND, int VEC, int NCH>
+__global__ __launch_bounds__(64) void merge_generic_kernel(MergeArgs a, VecTable T) {
+  __shared__ u64 cand_lds[MERGE_SPILL_MIN];
+  extern __shared__ __align__(16) unsigned char smem[];
+  u32* out = reinterpret_cast<u32*>(smem);  // R entries
+  SelStage st;
+  st.stride = stage_stride(T.row_bytes);
+  st.xx = out + a.R;
+  unsigned char* blk = smem + ((a.R * 8u + 15u) & ~15u);  // 8 rows + 8 norms
+  st.vec = a.stage_bytes ? blk + 8u * st.stride + 32u : nullptr;
+
+  const int lane = threadIdx.x;
+  const u32 nitems = a.list_count[2];
+  const AlphaParam al{a.a16, a.af};
+  unsigned long long n_rep = 0, n_edges = 0, n_pair = 0;
+
+  for (u32 it = blockIdx.x; it < nitems; it += gridDim.x) {
+    const u64 item = a.list_items[2][it];
+    const u32 i0 = (u32)item, cnt = (u32)(item >> 32);
+    const u32 b = (u32)(a.keys[i0] >> 32);
+    const u32 deg = meta_deg(a.meta[b]);
+    const u32 total = deg + cnt;
+    u32* row = a.graph + (u64)b * a.R;
+
+    // candidate list U = N_out(b) followed by the new sources
+    u64* cand;
+    const bool in_lds = total <= MERGE_SPILL_MIN;
+    if (in_lds) {
+      cand = cand_lds;
+    } else {
+      unsigned long long off = 0;
+      if (lane == 0) off = atomicAdd(a.arena_top, (unsigned long long)total);
+      off = readlane_u64(off, 0);
+      if (off + total > a.arena_cap) {  // cannot happen with the arena sized by the host
+        if (lane == 0) *a.error_flag = 1u;
+        continue;
+      }
+      cand = a.arena + off;
+    }
+    for (u32 j = lane; j < total; j += 64) {
+      const u32 id = j < deg ? row[j] : (u32)(a.keys[i0 + (j - deg)] & 0xFFFFFFFFull);
+      cand[j] = make_key(0u, id);
+    }
+    __syncthreads();
+
+    // distances d(b, x) for every x in U
+    const QueryRegs<KIND, VEC, NCH> Q = load_query<KIND, VEC, NCH>(T.base + (u64)b * T.row_bytes, T.npieces, lane);
+    for (u32 base = 0; base < total; base += 64) {
+      const u32 c64 = total - base < 64u ? total - base : 64u;
+      const u64* cb = cand + base;
+      const u32 dk = eval_up_to_64<KIND, VEC, NCH>(T, Q, [cb](u32 i) { return key_id(cb[i]); }, c64, lane);
+      const u32 c = cand_of_lane(lane);
+      const u32 id = c < c64 ? key_id(cb[c]) : 0u;
+      __syncthreads();
+      if (c < c64) cand[base + c] = make_key(dk, id);
+    }
+    __syncthreads();
+
+    u32 pair_evals = total;
+    u32 kept;
+    if (in_lds) {
+      u32 n2 = 64;
+      while (n2 < total) n2 <<= 1;
+      for (u32 j = total + lane; j < n2; j += 64) cand[j] = KEY_INF;
+      __syncthreads();
+      bitonic_sort_keys(cand, n2, lane);
+      kept = prune_sorted<KIND, VEC, NCH>(T, st, blk, cand, total, a.R, al, out, lane, pair_evals);
+    } else {
+      kept = prune_unsorted<KIND, VEC, NCH>(T, st, cand, total, a.R, al, out, lane, pair_evals);
+    }
+    __syncthreads();
+    for (u32 j = lane; j < a.R; j += 64) row[j] = j < kept ? out[j] : NONE_ID;
+    if (lane == 0) a.meta[b] = make_meta(kept, kept);
+    __syncthreads();
+    ++n_rep;
+    n_edges += cnt;
+    n_pair += pair_evals;
+  }
+  if (a.counters != nullptr && lane == 0 && n_rep) {
+    atomicAdd(&a.counters->reprunes, n_rep);
+    atomicAdd(&a.counters->edges, n_edges);
+    atomicAdd(&a.counters->prune_evals, n_pair);
+  }
+}
+
+template <int KIND, int VEC, int NCH>
+static hipError_t launch_merge_t(const MergeArgs& a, const VecTable& T, u32 grid, hipStream_t s) {
+  hipLaunchKernelGGL((merge_fast_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), 0, s, a, T);
+  if (a.gram_ok) hipLaunchKernelGGL((merge_gram_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), 0, s, a, T);
+  const u32 lds = ((a.R * 8u + 15u) & ~15u) + 8u * stage_stride(T.row_bytes) + 32u + a.stage_bytes;
+  hipLaunchKernelGGL((merge_generic_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), lds, s, a, T);
+  return hipGetLastError();
+}
+
+hipError_t launch_merge(const DistCfg& cfg, const MergeArgs& a, u32 grid, hipStream_t s) {
+  if (grid == 0) return hipSuccess;
+  VecTable T{a.points, (u32)cfg.row_bytes, cfg.npieces};
+  ANN_DISPATCH_CFG(launch_merge_t, a, T, grid, s);
+}
+
+bool gram_path_ok(const DistCfg& cfg) { return cfg.kind <= 1 && 8 * cfg.nch * cfg.vec <= 128; }
+u32 gram_path_tmax() { return SM_TMAX; }
+u32 prune_stage_bytes(u32 R, const DistCfg& cfg) { return stage_bytes(R, (u32)cfg.row_bytes, STAGE_BUDGET); }
+u32 fast_path_amax(const DistCfg& cfg) { return cfg.nch <= 2 ? 4u : (cfg.nch <= 4 ? 2u : 1u); }
+
+// rows given from outside: degree from the row itself, no clean prefix known
+__global__ __launch_bounds__(256) void meta_from_rows_kernel(const u32* graph, u64 n, u32 R, u32* meta) {
+  const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const u32* row = graph + i * R;
+  u32 deg = 0;
+  while (deg < R && row[deg] != NONE_ID) ++deg;
+  meta[i] = make_meta(deg, 0u);
+}
+__global__ __launch_bounds__(256) void meta_forget_clean_kernel(u64 n, u32* meta) {
+  const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) meta[i] &= 0xFFFFu;
+}
+
+hipError_t launch_meta_from_rows(const u32* graph, u64 n, u32 R, u32* meta, hipStream_t s) {
+  hipLaunchKernelGGL(meta_from_rows_kernel, dim3((u32)((n + 255) / 256)), dim3(256), 0, s, graph, n, R, meta);
+  return hipGetLastError();
+}
+hipError_t launch_meta_forget_clean(u64 n, u32* meta, hipStream_t s) {
+  hipLaunchKernelGGL(meta_forget_clean_kernel, dim3((u32)((n + 255) / 256)), dim3(256), 0, s, n, meta);
+  return hipGetLastError();
+}
+
+}  // namespace annmi
