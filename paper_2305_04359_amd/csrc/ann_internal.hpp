@@ -34,7 +34,8 @@ struct SearchArgs {
   u32 start;
   u32 L;
   u32 k;
-  u32 hash_bits;
+  u32 hash_bits;  // log2 of the visited filter's size in 32-bit words
+  u32 id_bits;    // > 0: the filter stores 16-bit tags of ids that fit in this many bits
   // build: visited list, one slot of vis_cap keys per search (may be null)
   u64* vis;
   u32* nvis;
@@ -96,7 +97,8 @@ constexpr u32 STAGE_BUDGET = 10240;    // LDS bytes the prune kernels may spend 
 hipError_t launch_search(const DistCfg& cfg, const SearchArgs& a, hipStream_t s);
 hipError_t launch_prune(const DistCfg& cfg, const PruneArgs& a, hipStream_t s);
 hipError_t launch_plan(const MergeArgs& a, hipStream_t s);
-hipError_t launch_merge(const DistCfg& cfg, const MergeArgs& a, u32 grid, hipStream_t s);
+hipError_t launch_merge(const DistCfg& cfg, const MergeArgs& a, u32 grid, hipStream_t s, hipStream_t s_gram,
+                        hipStream_t s_generic);
 hipError_t launch_meta_from_rows(const u32* graph, u64 n, u32 R, u32* meta, hipStream_t s);
 hipError_t launch_meta_forget_clean(u64 n, u32* meta, hipStream_t s);
 bool gram_path_ok(const DistCfg& cfg);
@@ -114,5 +116,6 @@ hipError_t start_vertex_device(const void* points, u64 n, u32 d, int dtype, hipS
 
 u32 search_lds_bytes(u32 L, u32 hash_bits);
 u32 default_hash_bits(u32 L);
+u32 compact_id_bits(u64 n, u32 hash_bits);  // 0 when 16-bit tags cannot identify every vertex
 
 }  // namespace annmi

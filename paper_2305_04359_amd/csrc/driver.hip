@@ -152,6 +152,17 @@ struct BatchScratch {
   u32 vis_cap = 0;
   DevBuf qidx, vis, nvis, edges, edges_tmp, hist, lists, small, ovf_list, arena;
   u64 arena_cap = 0;
+  // side streams (default priority) on which two of the three re-prune kernels run, and the
+  // events that order them against the caller's stream
+  hipStream_t side[2] = {nullptr, nullptr};
+  hipEvent_t ev_plan = nullptr, ev_side[2] = {nullptr, nullptr};
+  ~BatchScratch() {
+    for (auto& s : side)
+      if (s) (void)hipStreamDestroy(s);
+    if (ev_plan) (void)hipEventDestroy(ev_plan);
+    for (auto& e : ev_side)
+      if (e) (void)hipEventDestroy(e);
+  }
   // small: [0] overflow_count u32, [2] error flag u32, [4..5] arena_top u64, [8..10] work list counts
   int alloc(u64 b, u32 R, u32 cap) {
     bmax = b;
@@ -167,30 +178,56 @@ struct BatchScratch {
     HIP_TRY(hist.alloc(radix_hist_entries(E) * 4));
     HIP_TRY(lists.alloc(3 * E * 8));
     HIP_TRY(small.alloc(64));
+    HIP_TRY(hipMemset(small.p, 0, 64));
     HIP_TRY(ovf_list.alloc(b * 4));
     HIP_TRY(arena.alloc(arena_cap * 8));
+    for (auto& s : side) HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+    HIP_TRY(hipEventCreateWithFlags(&ev_plan, hipEventDisableTiming));
+    for (auto& e : ev_side) HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
     return ANN_OK;
   }
 };
 
+// HIP events around the phases of a batch.  Two sets, used alternately, so that the times of a
+// batch can be read at the next batch's synchronisation point instead of forcing one of its own.
 struct PhaseTimer {
-  hipEvent_t ev[5]{};
+  hipEvent_t ev[2][5]{};
   bool on = false;
+  int cur = 0;           // set being recorded
+  bool pending = false;  // the other set holds a finished, unread batch
   int init(bool enable) {
     on = enable;
     if (!on) return ANN_OK;
-    for (auto& e : ev) HIP_TRY(hipEventCreate(&e));
+    for (auto& set : ev)
+      for (auto& e : set) HIP_TRY(hipEventCreate(&e));
     return ANN_OK;
   }
   void mark(int i, hipStream_t s) {
-    if (on) (void)hipEventRecord(ev[i], s);
+    if (on) (void)hipEventRecord(ev[cur][i], s);
   }
   ~PhaseTimer() {
     if (on)
-      for (auto& e : ev)
-        if (e) (void)hipEventDestroy(e);
+      for (auto& set : ev)
+        for (auto& e : set)
+          if (e) (void)hipEventDestroy(e);
   }
 };
+
+// Adds the phase times of event set `set`, whose batch is known to have finished.
+void collect_phase_times(ann_graph* g, PhaseTimer& tm, int set) {
+  if (!tm.on) return;
+  float ms = 0;
+  (void)hipEventElapsedTime(&ms, tm.ev[set][0], tm.ev[set][1]);
+  g->stats.ms_search += ms;
+  (void)hipEventElapsedTime(&ms, tm.ev[set][1], tm.ev[set][2]);
+  g->stats.ms_prune += ms;
+  (void)hipEventElapsedTime(&ms, tm.ev[set][2], tm.ev[set][3]);
+  g->stats.ms_sort += ms;
+  (void)hipEventElapsedTime(&ms, tm.ev[set][3], tm.ev[set][4]);
+  g->stats.ms_merge += ms;
+  (void)hipEventElapsedTime(&ms, tm.ev[set][0], tm.ev[set][4]);
+  g->stats.ms_total += ms;
+}
 
 // BatchInsert(P') of Alg. 3 for the b ids in ids_host (device copy made here).
 int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u32* ids_dev, u64 b, u32 L,
@@ -207,7 +244,10 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   u32* small = S.small.as<u32>();
   DevCounters* ctr = g->collect ? g->counters : nullptr;
 
-  HIP_TRY(hipMemsetAsync(small, 0, 64, st));
+  // per-batch counters: [0] overflow count, [4..5] arena top, [8..10] work list lengths; the
+  // error flag [2] stays up once set
+  HIP_TRY(hipMemsetAsync(small, 0, 8, st));
+  HIP_TRY(hipMemsetAsync(small + 4, 0, 32, st));
   tm.mark(0, st);
 
   // step 1a: greedySearch(p, s, L, 1) over the frozen graph, visited lists to scratch
@@ -223,6 +263,7 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   sa.L = L;
   sa.k = 1;
   sa.hash_bits = g->hash_bits ? g->hash_bits : default_hash_bits(L);
+  sa.id_bits = compact_id_bits(g->n, sa.hash_bits);
   sa.vis = S.vis.as<u64>();
   sa.nvis = S.nvis.as<u32>();
   sa.vis_cap = S.vis_cap;
@@ -255,7 +296,11 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   // searches whose visited list outgrew its slot are redone with as much room as they need
   u32 novf = 0;
   HIP_TRY(hipMemcpyAsync(&novf, small + 0, 4, hipMemcpyDeviceToHost, st));
-  HIP_TRY(hipStreamSynchronize(st));
+  HIP_TRY(hipStreamSynchronize(st));  // the one host synchronisation of a batch
+  if (tm.pending) {
+    collect_phase_times(g, tm, tm.cur ^ 1);
+    tm.pending = false;
+  }
   if (novf > 0) {
     std::vector<u32> slots(novf), nv(b);
     HIP_TRY(hipMemcpy(slots.data(), S.ovf_list.p, (size_t)novf * 4, hipMemcpyDeviceToHost));
@@ -329,28 +374,34 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   // grid-stride kernels over work lists whose lengths stay on the device: enough waves to fill
   // the chip, no more (idle workgroups are not free)
   const u64 want = E < 8192 ? E : 8192;
-  HIP_TRY(launch_merge(g->cfg, ma, (u32)(want ? want : 1), st));
+  HIP_TRY(hipEventRecord(S.ev_plan, st));
+  for (int i = 0; i < 2; ++i) HIP_TRY(hipStreamWaitEvent(S.side[i], S.ev_plan, 0));
+  HIP_TRY(launch_merge(g->cfg, ma, (u32)(want ? want : 1), st, S.side[0], S.side[1]));
+  for (int i = 0; i < 2; ++i) {
+    HIP_TRY(hipEventRecord(S.ev_side[i], S.side[i]));
+    HIP_TRY(hipStreamWaitEvent(st, S.ev_side[i], 0));
+  }
   tm.mark(4, st);
-
-  u32 flags[4] = {0, 0, 0, 0};
-  HIP_TRY(hipMemcpyAsync(flags, small, 16, hipMemcpyDeviceToHost, st));
-  HIP_TRY(hipStreamSynchronize(st));
-  if (flags[2] != 0) return fail(ANN_EINTERNAL, "merge spill arena exhausted");
   if (tm.on) {
-    float ms = 0;
-    (void)hipEventElapsedTime(&ms, tm.ev[0], tm.ev[1]);
-    g->stats.ms_search += ms;
-    (void)hipEventElapsedTime(&ms, tm.ev[1], tm.ev[2]);
-    g->stats.ms_prune += ms;
-    (void)hipEventElapsedTime(&ms, tm.ev[2], tm.ev[3]);
-    g->stats.ms_sort += ms;
-    (void)hipEventElapsedTime(&ms, tm.ev[3], tm.ev[4]);
-    g->stats.ms_merge += ms;
-    (void)hipEventElapsedTime(&ms, tm.ev[0], tm.ev[4]);
-    g->stats.ms_total += ms;
+    tm.pending = true;
+    tm.cur ^= 1;
   }
   g->rounds += 1;
   g->stats.rounds += 1;
+  return ANN_OK;
+}
+
+// Waits for the batches issued so far; reports a spill-arena failure (cannot happen with the
+// arena sized as it is) and reads the phase times of the last batch.
+int finish_batches(ann_graph* g, BatchScratch& S, PhaseTimer& tm, hipStream_t st) {
+  u32 flags[4] = {0, 0, 0, 0};
+  HIP_TRY(hipMemcpyAsync(flags, S.small.p, 16, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  if (flags[2] != 0) return fail(ANN_EINTERNAL, "merge spill arena exhausted");
+  if (tm.pending) {
+    collect_phase_times(g, tm, tm.cur ^ 1);
+    tm.pending = false;
+  }
   return ANN_OK;
 }
 
@@ -502,7 +553,9 @@ int ann_insert_batch(ann_graph* g, const void* points_dev, const uint32_t* ids_h
   PhaseTimer tm;
   rc = tm.init(g->collect);
   if (rc) return rc;
-  return batch_insert(g, points_dev, ids_host, S.qidx.as<u32>(), b, L, alpha, S, tm, st);
+  rc = batch_insert(g, points_dev, ids_host, S.qidx.as<u32>(), b, L, alpha, S, tm, st);
+  if (rc) return rc;
+  return finish_batches(g, S, tm, st);
 }
 
 int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric, uint32_t R,
@@ -597,7 +650,8 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
     rc = batch_insert(g, points_dev, order.data() + lo, order_dev.as<u32>() + lo, b, L, alpha, S, tm, st);
     if (rc) return rc;
   }
-  HIP_TRY(hipStreamSynchronize(st));
+  rc = finish_batches(g, S, tm, st);
+  if (rc) return rc;
   guard.g = nullptr;
   *out = g;
   return ANN_OK;
@@ -623,6 +677,7 @@ int ann_search(const ann_graph* g, const void* points_dev, const void* queries_d
   sa.L = L;
   sa.k = k;
   sa.hash_bits = g->hash_bits ? g->hash_bits : default_hash_bits(L);
+  sa.id_bits = compact_id_bits(g->n, sa.hash_bits);
   sa.out_ids = ids_dev;
   sa.out_dists = dists_dev;
   sa.counters = g->collect ? g->counters : nullptr;

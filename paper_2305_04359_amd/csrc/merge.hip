@@ -36,7 +36,9 @@ __device__ __forceinline__ u32 make_meta(u32 deg, u32 clean) { return deg | (cle
 __global__ __launch_bounds__(256) void plan_kernel(MergeArgs a) {
   __shared__ u32 cnt_lds[3];
   __shared__ u32 base_lds[3];
+  __shared__ u32 stat_lds[2];  // appends, appended edges
   if (threadIdx.x < 3) cnt_lds[threadIdx.x] = 0;
+  if (threadIdx.x < 2) stat_lds[threadIdx.x] = 0;
   __syncthreads();
 
   const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
@@ -68,8 +70,8 @@ __global__ __launch_bounds__(256) void plan_kernel(MergeArgs a) {
         for (u32 j = 0; j < cnt; ++j) row[deg + j] = (u32)(a.keys[i + j] & 0xFFFFFFFFull);
         a.meta[b] = make_meta(deg + cnt, clean);
         if (a.counters != nullptr) {
-          atomicAdd(&a.counters->appends, 1ull);
-          atomicAdd(&a.counters->edges, (unsigned long long)cnt);
+          atomicAdd(&stat_lds[0], 1u);
+          atomicAdd(&stat_lds[1], cnt);
         }
       } else {
         const u32 fresh = deg - clean + cnt;
@@ -88,6 +90,10 @@ __global__ __launch_bounds__(256) void plan_kernel(MergeArgs a) {
   // result, every segment is processed on its own
   if (threadIdx.x < 3 && cnt_lds[threadIdx.x] != 0)
     base_lds[threadIdx.x] = atomicAdd(&a.list_count[threadIdx.x], cnt_lds[threadIdx.x]);
+  if (a.counters != nullptr && threadIdx.x == 0 && stat_lds[0] != 0) {
+    atomicAdd(&a.counters->appends, (unsigned long long)stat_lds[0]);
+    atomicAdd(&a.counters->edges, (unsigned long long)stat_lds[1]);
+  }
   __syncthreads();
   if (kind >= 0) a.list_items[kind][base_lds[kind] + slot] = ((u64)cnt << 32) | (u32)i;
 }
@@ -674,19 +680,23 @@ __global__ __launch_bounds__(64) void merge_generic_kernel(MergeArgs a, VecTable
   }
 }
 
+// The three kernels work on disjoint rows, so they may run side by side: s_gram and s_generic are
+// side streams the caller has already made wait for the planning kernel.
 template <int KIND, int VEC, int NCH>
-static hipError_t launch_merge_t(const MergeArgs& a, const VecTable& T, u32 grid, hipStream_t s) {
+static hipError_t launch_merge_t(const MergeArgs& a, const VecTable& T, u32 grid, hipStream_t s, hipStream_t s_gram,
+                                 hipStream_t s_generic) {
   hipLaunchKernelGGL((merge_fast_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), 0, s, a, T);
-  if (a.gram_ok) hipLaunchKernelGGL((merge_gram_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), 0, s, a, T);
+  if (a.gram_ok) hipLaunchKernelGGL((merge_gram_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), 0, s_gram, a, T);
   const u32 lds = ((a.R * 8u + 15u) & ~15u) + 8u * stage_stride(T.row_bytes) + 32u + a.stage_bytes;
-  hipLaunchKernelGGL((merge_generic_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), lds, s, a, T);
+  hipLaunchKernelGGL((merge_generic_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), lds, s_generic, a, T);
   return hipGetLastError();
 }
 
-hipError_t launch_merge(const DistCfg& cfg, const MergeArgs& a, u32 grid, hipStream_t s) {
+hipError_t launch_merge(const DistCfg& cfg, const MergeArgs& a, u32 grid, hipStream_t s, hipStream_t s_gram,
+                        hipStream_t s_generic) {
   if (grid == 0) return hipSuccess;
   VecTable T{a.points, (u32)cfg.row_bytes, cfg.npieces};
-  ANN_DISPATCH_CFG(launch_merge_t, a, T, grid, s);
+  ANN_DISPATCH_CFG(launch_merge_t, a, T, grid, s, s_gram, s_generic);
 }
 
 bool gram_path_ok(const DistCfg& cfg) { return cfg.kind <= 1 && 8 * cfg.nch * cfg.vec <= 128; }

@@ -3,15 +3,25 @@
 // The beam (at most L candidates ordered by (distance, id), each with a "processed" flag) lives
 // in registers, striped over the wave: entry i is held by lane i % 64 in slot i / 64.  LDS is the
 // exchange medium when new candidates are merged in.  The visited filter of Sec. 4.5 (a lossy
-// hash of vertex ids with one-sided error) is a per-wave LDS table of 4-entry buckets, newest
-// first: a lost entry only causes a repeated distance evaluation, and the repeated candidate is
-// then recognised as a duplicate of a beam entry or is worse than the beam's last entry, so
-// results do not depend on the table.
+// hash of vertex ids with one-sided error) is a per-wave LDS table of 16-byte buckets, newest
+// entry first: a lost entry only causes a repeated distance evaluation, and the repeated
+// candidate is then recognised as a duplicate of a beam entry or is worse than the beam's last
+// entry, so results do not depend on the table.  A bucket holds four 32-bit ids, or, when the
+// vertex count allows, eight 16-bit tags: the id is passed through a bijection of its B bits,
+// the top bits choose the bucket and the remaining (at most 15) bits are the tag, so a tag match
+// still identifies the vertex exactly while the table remembers twice as many vertices.
 #include "ann_device.hpp"
 #include "ann_internal.hpp"
 #include "ann_dispatch.hpp"
 
 namespace annmi {
+
+// a bijection of the low `bits` bits (odd multiplier, xor-shift, odd multiplier)
+__device__ __forceinline__ u32 mix_id(u32 x, u32 mask, u32 bits) {
+  u32 y = (x * 0x9E3779B1u) & mask;
+  y ^= y >> ((bits + 1u) >> 1);
+  return (y * 0x85EBCA6Bu) & mask;
+}
 
 template <int KIND, int VEC, int NCH, int NSLOT>
 __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
@@ -22,9 +32,12 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
 
   const int lane = threadIdx.x;
   const u32 qi = blockIdx.x;
-  const u32 hsize = 1u << a.hash_bits;        // entries; buckets of 4
+  const u32 hsize = 1u << a.hash_bits;        // table size in 32-bit words; buckets of 4 words
   const u32 hshift = 34u - a.hash_bits;       // 32 - log2(buckets)
   uint4* bucket = reinterpret_cast<uint4*>(hash);
+  const bool compact = a.id_bits != 0;        // 16-bit tag mode
+  const u32 idmask = compact ? ((1u << a.id_bits) - 1u) : 0u;
+  const u32 tagbits = compact ? a.id_bits - (a.hash_bits - 2u) : 0u;
   const u32 L = a.L;
 
   const u32 qrow = a.qidx ? a.qidx[qi] : qi;
@@ -45,7 +58,14 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
     if (lane == 0) A[0] = make_key(dk, st);
   }
   __syncthreads();
-  if (lane == 0) hash[4u * ((a.start * 0x9E3779B1u) >> hshift)] = a.start;
+  if (lane == 0) {
+    if (compact) {
+      const u32 y = mix_id(a.start, idmask, a.id_bits);
+      hash[4u * (y >> tagbits)] = 0xFFFF0000u | (y & ((1u << tagbits) - 1u));
+    } else {
+      hash[4u * ((a.start * 0x9E3779B1u) >> hshift)] = a.start;
+    }
+  }
 
   u32 size = 1, nv = 0, evals = 1;
 
@@ -78,14 +98,31 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
       bool fresh = x != NONE_ID;
       const u64 present = ballot(fresh);
       if (fresh) {
-        const u32 h = (x * 0x9E3779B1u) >> hshift;
-        const uint4 e = bucket[h];
-        const u32 m01 = (e.x ^ x) < (e.y ^ x) ? (e.x ^ x) : (e.y ^ x);
-        const u32 m23 = (e.z ^ x) < (e.w ^ x) ? (e.z ^ x) : (e.w ^ x);
-        if ((m01 < m23 ? m01 : m23) == 0u)
-          fresh = false;
-        else
-          bucket[h] = make_uint4(x, e.x, e.y, e.z);
+        if (compact) {
+          const u32 y = mix_id(x, idmask, a.id_bits);
+          const u32 h = y >> tagbits;
+          const u32 tag = y & ((1u << tagbits) - 1u);
+          const u32 tt = tag | (tag << 16);
+          const uint4 e = bucket[h];
+          // some 16-bit half equal to the tag?  (halves of e ^ tt that are zero)
+          const u32 z0 = e.x ^ tt, z1 = e.y ^ tt, z2 = e.z ^ tt, z3 = e.w ^ tt;
+          const u32 hz = ((z0 - 0x00010001u) & ~z0) | ((z1 - 0x00010001u) & ~z1) | ((z2 - 0x00010001u) & ~z2) |
+                         ((z3 - 0x00010001u) & ~z3);
+          if (hz & 0x80008000u)
+            fresh = false;
+          else  // shift the bucket by one tag, newest in front
+            bucket[h] = make_uint4((e.x << 16) | tag, (e.y << 16) | (e.x >> 16), (e.z << 16) | (e.y >> 16),
+                                   (e.w << 16) | (e.z >> 16));
+        } else {
+          const u32 h = (x * 0x9E3779B1u) >> hshift;
+          const uint4 e = bucket[h];
+          const u32 m01 = (e.x ^ x) < (e.y ^ x) ? (e.x ^ x) : (e.y ^ x);
+          const u32 m23 = (e.z ^ x) < (e.w ^ x) ? (e.z ^ x) : (e.w ^ x);
+          if ((m01 < m23 ? m01 : m23) == 0u)
+            fresh = false;
+          else
+            bucket[h] = make_uint4(x, e.x, e.y, e.z);
+        }
       }
       const u64 fm = ballot(fresh);
       const u32 m = __builtin_popcountll(fm);
@@ -214,6 +251,13 @@ static hipError_t launch_search_nslot(const SearchArgs& a, const VecTable& T, hi
     default: hipLaunchKernelGGL((search_kernel<KIND, VEC, NCH, 8>), grid, block, lds, s, a, T); break;
   }
   return hipGetLastError();
+}
+
+u32 compact_id_bits(u64 n, u32 hash_bits) {
+  u32 bits = 1;
+  while ((1ull << bits) < n) ++bits;  // ids < n <= 2^bits
+  if (bits < hash_bits) bits = hash_bits;
+  return bits - (hash_bits - 2u) <= 15u ? bits : 0u;
 }
 
 hipError_t launch_search(const DistCfg& cfg, const SearchArgs& a, hipStream_t s) {

@@ -121,7 +121,7 @@ def c1(n=10_000, nq=1_000):
     cen = centers_uniform(32, 128, 32.0, 224.0, DATA_SEED)
     return Workload("C1", gaussian_mixture_u8(n, 128, cen, 20.0, DATA_SEED, 0),
                     gaussian_mixture_u8(nq, 128, cen, 20.0, QUERY_SEED, 1), L2SQ,
-                    R=32, L=64, alpha=1.2, search_L=(20, 40, 80),
+                    R=32, L=64, alpha=1.2, search_L=(20, 30, 40, 50, 60, 80),
                     note="stand-in for a small SIFT-like set")
 
 
@@ -141,7 +141,7 @@ def c3(n=1_000_000, nq=10_000):
     return Workload("C3",
                     gaussian_mixture_u8(n, 100, cen, 25.0, DATA_SEED, 0, -127, 127, np.int8),
                     gaussian_mixture_u8(nq, 100, cen, 25.0, QUERY_SEED, 1, -127, 127, np.int8),
-                    L2SQ, R=64, L=128, alpha=1.2, search_L=(10, 20, 40, 80, 120, 200),
+                    L2SQ, R=64, L=128, alpha=1.2, search_L=(10, 15, 20, 25, 30, 35, 40, 50, 60, 80, 120, 200),
                     note="stand-in for MSSPACEV-1M (100-d int8, L2)")
 
 
@@ -153,7 +153,7 @@ def c4(n=1_000_000, nq=10_000):
     qcen = (cen.astype(np.float64) @ rot.T).astype(np.float32)
     return Workload("C4", sphere_mixture_f32(n, cen, 0.05, DATA_SEED, 0),
                     sphere_mixture_f32(nq, qcen, 0.05, QUERY_SEED, 1), MIPS,
-                    R=64, L=128, alpha=1.0, search_L=(10, 20, 40, 80, 120, 200),
+                    R=64, L=128, alpha=1.0, search_L=(10, 20, 30, 40, 45, 50, 60, 70, 80, 100, 120, 200),
                     note="stand-in for TEXT2IMAGE-1M (200-d float, inner product, OOD queries)")
 
 
