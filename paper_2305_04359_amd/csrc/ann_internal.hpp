@@ -60,6 +60,7 @@ struct PruneArgs {
   u32* meta;            // per row: degree | clean prefix length << 16 (written for the batch points)
   u64* edges;           // batch_size x R keys (dest << 32 | source), ~0 in unused slots
   u32 stage_bytes;      // dynamic LDS for the selected points' vectors (0: read them from memory)
+  u32 use_mfma;         // u8/i8 rows up to 128 B: pair distances on the matrix cores
   u32* overflow_count;  // searches whose visited list did not fit
   u32* overflow_list;   // their indices
   long long a16;
@@ -80,6 +81,7 @@ struct MergeArgs {
   u32 gram_ok;         // the matrix-core path applies to this dtype / row size
   u32 gram_tmax;       // and to at most this many candidates
   u32 stage_bytes;     // dynamic LDS of the generic kernel for the selected points' vectors
+  u32 use_mfma;        // the generic kernel takes pair distances on the matrix cores
   u64* arena;          // spill space for candidate lists that do not fit in LDS
   u64 arena_cap;
   unsigned long long* arena_top;
@@ -105,6 +107,7 @@ bool gram_path_ok(const DistCfg& cfg);
 u32 gram_path_tmax();
 u32 fast_path_amax(const DistCfg& cfg);
 u32 prune_stage_bytes(u32 R, const DistCfg& cfg);
+bool mfma_prune_ok(u32 R, const DistCfg& cfg);
 
 // stable LSD radix sort of 64-bit keys on bits [32, 32+key_bits); result is left in `keys`
 // (`tmp` holds `count` keys, `hist` holds radix_hist_entries(count) u32)

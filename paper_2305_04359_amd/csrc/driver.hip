@@ -285,6 +285,7 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   pa.vis_cap = S.vis_cap;
   pa.meta = g->meta;
   pa.stage_bytes = prune_stage_bytes(R, g->cfg);
+  pa.use_mfma = mfma_prune_ok(R, g->cfg) ? 1u : 0u;
   pa.edges = S.edges.as<u64>();
   pa.overflow_count = small + 0;
   pa.overflow_list = S.ovf_list.as<u32>();
@@ -363,6 +364,7 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   ma.gram_ok = gram_path_ok(g->cfg) ? 1u : 0u;
   ma.gram_tmax = gram_path_tmax();
   ma.stage_bytes = prune_stage_bytes(R, g->cfg);
+  ma.use_mfma = mfma_prune_ok(R, g->cfg) ? 1u : 0u;
   ma.arena = S.arena.as<u64>();
   ma.arena_cap = S.arena_cap;
   ma.arena_top = reinterpret_cast<unsigned long long*>(small + 4);

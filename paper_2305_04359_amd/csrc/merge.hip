@@ -153,30 +153,16 @@ __device__ __forceinline__ u32 distance_key_xx(const QueryRegs<KIND, VEC, NCH>& 
   }
 }
 
-template <int KIND, int VEC, int NCH>
-__global__ __launch_bounds__(64) void merge_fast_kernel(MergeArgs a, VecTable T) {
-  constexpr int AMAX = FastAMax<NCH>::value;
+// One row of the fast path with exactly NA new entries (a compile-time count keeps every loop
+// over the new entries fully unrolled and free of guards).
+template <int KIND, int VEC, int NCH, int NA>
+__device__ __forceinline__ u32 fast_item(const MergeArgs& a, const VecTable& T, const AlphaParam& al, u32* ids_lds,
+                                         u32 (*dk_lds)[64], u32 b, u32 i0, u32 clean, u32 stale, u32* row, u32 R,
+                                         int lane) {
   constexpr int PBF = PassBatch<VEC, NCH>::value > 4 ? 4 : PassBatch<VEC, NCH>::value;
-  __shared__ u32 ids_lds[64 + AMAX];       // clean ids by row position, then the new ids
-  __shared__ u32 dk_lds[1 + AMAX][64];     // distance keys by row position: to b, to each new entry
-
-  const int lane = threadIdx.x;
+  constexpr u32 na = NA;
   const int sub = lane & (LPC - 1);
   const u32 grp = (u32)lane >> 3;
-  const u32 nitems = a.list_count[0];
-  const AlphaParam al{a.a16, a.af};
-  unsigned long long n_rep = 0, n_edges = 0, n_pair = 0;
-
-  for (u32 it = blockIdx.x; it < nitems; it += gridDim.x) {
-    const u64 item = a.list_items[0][it];
-    const u32 i0 = (u32)item, cnt = (u32)(item >> 32);
-    const u32 b = (u32)(a.keys[i0] >> 32);
-    const u32 m = a.meta[b];
-    const u32 deg = meta_deg(m), clean = meta_clean(m);
-    const u32 stale = deg - clean;  // appended since the last prune
-    const u32 na = stale + cnt;     // 1 <= na <= AMAX
-    u32* row = a.graph + (u64)b * a.R;
-
     const u32 myid = (u32)lane < clean ? row[lane] : NONE_ID;
     u32 mynew = NONE_ID;
     if ((u32)lane < na) mynew = (u32)lane < stale ? row[clean + lane] : (u32)(a.keys[i0 + (lane - stale)] & 0xFFFFFFFFull);
@@ -184,10 +170,10 @@ __global__ __launch_bounds__(64) void merge_fast_kernel(MergeArgs a, VecTable T)
     if ((u32)lane < na) ids_lds[64 + lane] = mynew;
 
     const QueryRegs<KIND, VEC, NCH> Qb = load_query<KIND, VEC, NCH>(T.base + (u64)b * T.row_bytes, T.npieces, lane);
-    QueryRegs<KIND, VEC, NCH> Qn[AMAX];
-    u32 nid[AMAX];
+    QueryRegs<KIND, VEC, NCH> Qn[NA];
+    u32 nid[NA];
 #pragma unroll
-    for (int k = 0; k < AMAX; ++k) {
+    for (int k = 0; k < NA; ++k) {
       nid[k] = readlane_u32(mynew, k);
       if ((u32)k < na)
         Qn[k] = load_query<KIND, VEC, NCH>(T.base + (u64)nid[k] * T.row_bytes, T.npieces, lane);
@@ -198,12 +184,12 @@ __global__ __launch_bounds__(64) void merge_fast_kernel(MergeArgs a, VecTable T)
 
     // one sweep over the clean prefix and the new entries: candidate index c < clean is row
     // position c, index 64 + k is new entry k; each is measured against b and every new entry
-    u32 res[1 + AMAX];
+    u32 res[1 + NA];
 #pragma unroll
-    for (int q = 0; q <= AMAX; ++q) res[q] = 0;
-    u32 newres[1 + AMAX];  // the same for the pass over the new entries (valid in lanes 8k)
+    for (int q = 0; q <= NA; ++q) res[q] = 0;
+    u32 newres[1 + NA];  // the same for the pass over the new entries (valid in lanes 8k)
 #pragma unroll
-    for (int q = 0; q <= AMAX; ++q) newres[q] = 0;
+    for (int q = 0; q <= NA; ++q) newres[q] = 0;
     const u32 npass_clean = (clean + 7u) >> 3;
     for (u32 t0 = 0; t0 < npass_clean + 1; t0 += PBF) {
       Piece<VEC> x[PBF][NCH];
@@ -234,7 +220,7 @@ __global__ __launch_bounds__(64) void merge_fast_kernel(MergeArgs a, VecTable T)
           else if ((u32)sub == t)
             res[0] = d0;
 #pragma unroll
-          for (int k = 0; k < AMAX; ++k) {
+          for (int k = 0; k < NA; ++k) {
             if ((u32)k < na) {  // uniform
               const u32 dkk = distance_key_xx<KIND, VEC, NCH>(Qn[k], x[tt], xx);
               if (newpass)
@@ -250,7 +236,7 @@ __global__ __launch_bounds__(64) void merge_fast_kernel(MergeArgs a, VecTable T)
     {
       const u32 c = cand_of_lane(lane);
 #pragma unroll
-      for (int q = 0; q <= AMAX; ++q) dk_lds[q][c] = res[q];
+      for (int q = 0; q <= NA; ++q) dk_lds[q][c] = res[q];
     }
     __syncthreads();
     const bool isc = (u32)lane < clean;
@@ -258,12 +244,12 @@ __global__ __launch_bounds__(64) void merge_fast_kernel(MergeArgs a, VecTable T)
     const u64 keyc = isc ? make_key(dB, myid) : KEY_INF;
 
     // per new entry k: its key, its place among the clean entries, what it removes, what removes it
-    u64 keyn[AMAX];
-    u32 rank[AMAX];
-    u64 removes[AMAX], removed_by[AMAX];
-    u32 dBn[AMAX];
+    u64 keyn[NA];
+    u32 rank[NA];
+    u64 removes[NA], removed_by[NA];
+    u32 dBn[NA];
 #pragma unroll
-    for (int k = 0; k < AMAX; ++k) {
+    for (int k = 0; k < NA; ++k) {
       dBn[k] = readlane_u32(newres[0], 8 * k);
       keyn[k] = make_key(dBn[k], nid[k]);
       const u32 dkj = dk_lds[1 + k][lane];  // distance new entry k <-> clean entry `lane`
@@ -275,20 +261,20 @@ __global__ __launch_bounds__(64) void merge_fast_kernel(MergeArgs a, VecTable T)
     u64 alive = clean >= 64 ? ~0ull : ((1ull << clean) - 1ull);
     u32 selnew = 0;
 #pragma unroll
-    for (int r = 0; r < AMAX; ++r) {
+    for (int r = 0; r < NA; ++r) {
       // the new entry that is r-th among the new entries in (distance, id) order
 #pragma unroll
-      for (int k = 0; k < AMAX; ++k) {
+      for (int k = 0; k < NA; ++k) {
         if ((u32)k < na) {
           u32 ord = 0;
 #pragma unroll
-          for (int l = 0; l < AMAX; ++l)
+          for (int l = 0; l < NA; ++l)
             if ((u32)l < na && keyn[l] < keyn[k]) ++ord;
           if (ord == (u32)r) {
             const u64 before = rank[k] >= 64 ? ~0ull : ((1ull << rank[k]) - 1ull);
             bool killed = (removed_by[k] & alive & before) != 0;
 #pragma unroll
-            for (int l = 0; l < AMAX; ++l) {
+            for (int l = 0; l < NA; ++l) {
               if ((u32)l < na && l != k && ((selnew >> l) & 1u) && keyn[l] < keyn[k]) {
                 // distance new l <-> new k: query l against candidate k of the new pass
                 const u32 dlk = readlane_u32(newres[1 + l], 8 * k);
@@ -307,24 +293,61 @@ __global__ __launch_bounds__(64) void merge_fast_kernel(MergeArgs a, VecTable T)
     u32 pos = (u32)__builtin_popcountll(alive & lanemask_lt(lane));
     u32 newpos = 0;
 #pragma unroll
-    for (int k = 0; k < AMAX; ++k) {
+    for (int k = 0; k < NA; ++k) {
       if ((u32)k < na && ((selnew >> k) & 1u)) {
         if (rank[k] <= (u32)lane) ++pos;  // new entry k precedes clean entry `lane`
         const u64 before = rank[k] >= 64 ? ~0ull : ((1ull << rank[k]) - 1ull);
         u32 pk = (u32)__builtin_popcountll(alive & before);
 #pragma unroll
-        for (int l = 0; l < AMAX; ++l)
+        for (int l = 0; l < NA; ++l)
           if ((u32)l < na && ((selnew >> l) & 1u) && keyn[l] < keyn[k]) ++pk;
         if (lane == k) newpos = pk;
       }
     }
     const u32 nsel = (u32)__builtin_popcountll(alive) + (u32)__builtin_popcount(selnew);
-    const u32 kept = nsel < a.R ? nsel : a.R;
+    const u32 kept = nsel < R ? nsel : R;
     __syncthreads();
-    if (isc && ((alive >> lane) & 1ull) && pos < a.R) row[pos] = myid;
-    if ((u32)lane < na && ((selnew >> lane) & 1u) && newpos < a.R) row[newpos] = mynew;
-    for (u32 j = kept + lane; j < a.R; j += 64) row[j] = NONE_ID;
+    if (isc && ((alive >> lane) & 1ull) && pos < R) row[pos] = myid;
+    if ((u32)lane < na && ((selnew >> lane) & 1u) && newpos < R) row[newpos] = mynew;
+    for (u32 j = kept + lane; j < R; j += 64) row[j] = NONE_ID;
     if (lane == 0) a.meta[b] = make_meta(kept, kept);
+    return kept;
+}
+
+template <int KIND, int VEC, int NCH>
+__global__ __launch_bounds__(64) void merge_fast_kernel(MergeArgs a, VecTable T) {
+  constexpr int AMAX = FastAMax<NCH>::value;
+  __shared__ u32 ids_lds[64 + AMAX];    // clean ids by row position, then the new ids
+  __shared__ u32 dk_lds[1 + AMAX][64];  // distance keys by row position: to b, to each new entry
+
+  const int lane = threadIdx.x;
+  const u32 nitems = a.list_count[0];
+  const AlphaParam al{a.a16, a.af};
+  unsigned long long n_rep = 0, n_edges = 0, n_pair = 0;
+
+  for (u32 it = blockIdx.x; it < nitems; it += gridDim.x) {
+    const u64 item = a.list_items[0][it];
+    const u32 i0 = (u32)item, cnt = (u32)(item >> 32);
+    const u32 b = (u32)(a.keys[i0] >> 32);
+    const u32 m = a.meta[b];
+    const u32 deg = meta_deg(m), clean = meta_clean(m);
+    const u32 stale = deg - clean;  // appended since the last prune
+    const u32 na = stale + cnt;     // 1 <= na <= AMAX
+    u32* row = a.graph + (u64)b * a.R;
+    u32 kept = 0;
+    switch (na) {  // uniform
+      case 1: kept = fast_item<KIND, VEC, NCH, 1>(a, T, al, ids_lds, dk_lds, b, i0, clean, stale, row, a.R, lane); break;
+      case 2:
+        if constexpr (AMAX >= 2) kept = fast_item<KIND, VEC, NCH, 2>(a, T, al, ids_lds, dk_lds, b, i0, clean, stale, row, a.R, lane);
+        break;
+      case 3:
+        if constexpr (AMAX >= 4) kept = fast_item<KIND, VEC, NCH, 3>(a, T, al, ids_lds, dk_lds, b, i0, clean, stale, row, a.R, lane);
+        break;
+      default:
+        if constexpr (AMAX >= 4) kept = fast_item<KIND, VEC, NCH, 4>(a, T, al, ids_lds, dk_lds, b, i0, clean, stale, row, a.R, lane);
+        break;
+    }
+    (void)kept;
     ++n_rep;
     n_edges += cnt;
     n_pair += (unsigned long long)(clean + na) * (na + 1);
@@ -361,24 +384,10 @@ struct SmallLds {
   u32 inv[SM_TMAX];   // sorted position -> arrival index
 };
 
-typedef int v4i_t __attribute__((ext_vector_type(4)));
-typedef int v16i_t __attribute__((ext_vector_type(16)));
-
 template <int VEC, int NCH>
 struct SmallPathOk {
   static constexpr bool value = (8 * NCH * VEC <= 128);
 };
-
-// floor(d * 2^16 / a16) for 0 <= d < 2^31, 0 < a16 < 2^31, clamped to INT32_MAX
-__device__ __forceinline__ i32 alpha_threshold(i32 d, i64 a16) {
-  const u64 x = (u64)(u32)d << 16;
-  u64 t = (u64)__builtin_floor((double)x / (double)a16);
-  if (t * (u64)a16 > x)
-    --t;
-  else if ((t + 1) * (u64)a16 <= x)
-    ++t;
-  return t > 0x7FFFFFFFull ? 0x7FFFFFFF : (i32)t;
-}
 
 // One 32x32 tile of the Gram matrix of the sorted candidates: rows 32*RB.., columns 32*CB...
 // Accumulator register r of lane l is entry (row 8*(r/4) + 4*(l/32) + r%4, column l%32), so one
@@ -605,6 +614,8 @@ __global__ __launch_bounds__(64) void merge_generic_kernel(MergeArgs a, VecTable
   st.xx = out + a.R;
   unsigned char* blk = smem + ((a.R * 8u + 15u) & ~15u);  // 8 rows + 8 norms
   st.vec = a.stage_bytes ? blk + 8u * st.stride + 32u : nullptr;
+  constexpr bool kMfma = MfmaPruneOk<KIND, VEC, NCH>::value;
+  const MfmaLds M = mfma_lds_carve(smem + ((a.R * 4u + 15u) & ~15u), a.R);  // used when a.use_mfma
 
   const int lane = threadIdx.x;
   const u32 nitems = a.list_count[2];
@@ -661,9 +672,20 @@ __global__ __launch_bounds__(64) void merge_generic_kernel(MergeArgs a, VecTable
       for (u32 j = total + lane; j < n2; j += 64) cand[j] = KEY_INF;
       __syncthreads();
       bitonic_sort_keys(cand, n2, lane);
-      kept = prune_sorted<KIND, VEC, NCH>(T, st, blk, cand, total, a.R, al, out, lane, pair_evals);
+      bool done = false;
+      if constexpr (kMfma) {
+        if (a.use_mfma) {
+          kept = prune_sorted_mfma<KIND, VEC, NCH>(T, M, cand, total, a.R, a.a16, out, lane, pair_evals);
+          done = true;
+        }
+      }
+      if (!done) kept = prune_sorted<KIND, VEC, NCH>(T, st, blk, cand, total, a.R, al, out, lane, pair_evals);
     } else {
-      kept = prune_unsorted<KIND, VEC, NCH>(T, st, cand, total, a.R, al, out, lane, pair_evals);
+      // (the staged-vector areas are laid out for the walk in use; the minimum-search walk reads
+      // the selected vectors from device memory when the matrix-core layout is active)
+      SelStage st2 = st;
+      if (a.use_mfma) st2.vec = nullptr;
+      kept = prune_unsorted<KIND, VEC, NCH>(T, st2, cand, total, a.R, al, out, lane, pair_evals);
     }
     __syncthreads();
     for (u32 j = lane; j < a.R; j += 64) row[j] = j < kept ? out[j] : NONE_ID;
@@ -687,7 +709,8 @@ static hipError_t launch_merge_t(const MergeArgs& a, const VecTable& T, u32 grid
                                  hipStream_t s_generic) {
   hipLaunchKernelGGL((merge_fast_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), 0, s, a, T);
   if (a.gram_ok) hipLaunchKernelGGL((merge_gram_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), 0, s_gram, a, T);
-  const u32 lds = ((a.R * 8u + 15u) & ~15u) + 8u * stage_stride(T.row_bytes) + 32u + a.stage_bytes;
+  const u32 lds = a.use_mfma ? ((a.R * 4u + 15u) & ~15u) + mfma_lds_bytes(a.R)
+                            : ((a.R * 8u + 15u) & ~15u) + 8u * stage_stride(T.row_bytes) + 32u + a.stage_bytes;
   hipLaunchKernelGGL((merge_generic_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), lds, s_generic, a, T);
   return hipGetLastError();
 }
@@ -701,6 +724,9 @@ hipError_t launch_merge(const DistCfg& cfg, const MergeArgs& a, u32 grid, hipStr
 
 bool gram_path_ok(const DistCfg& cfg) { return cfg.kind <= 1 && 8 * cfg.nch * cfg.vec <= 128; }
 u32 gram_path_tmax() { return SM_TMAX; }
+bool mfma_prune_ok(u32 R, const DistCfg& cfg) {
+  return cfg.kind <= 1 && 8 * cfg.nch * cfg.vec <= 128 && mfma_lds_bytes(R) <= 24576u;
+}
 u32 prune_stage_bytes(u32 R, const DistCfg& cfg) { return stage_bytes(R, (u32)cfg.row_bytes, STAGE_BUDGET); }
 u32 fast_path_amax(const DistCfg& cfg) { return cfg.nch <= 2 ? 4u : (cfg.nch <= 4 ? 2u : 1u); }
 

@@ -21,6 +21,8 @@ __global__ __launch_bounds__(64) void prune_kernel(PruneArgs a, VecTable T) {
   st.xx = selxx;
   unsigned char* blk = smem + ((a.R * 8u + 15u) & ~15u);  // 8 rows + 8 norms
   st.vec = a.stage_bytes ? blk + 8u * st.stride + 32u : nullptr;
+  constexpr bool kMfma = MfmaPruneOk<KIND, VEC, NCH>::value;
+  const MfmaLds M = mfma_lds_carve(smem + ((a.R * 4u + 15u) & ~15u), a.R);  // used when a.use_mfma
 
   const int lane = threadIdx.x;
   const u32 qi = blockIdx.x;
@@ -49,11 +51,21 @@ __global__ __launch_bounds__(64) void prune_kernel(PruneArgs a, VecTable T) {
     for (u32 i = lane; i < n2; i += 64) cand_lds[i] = i < nv ? (vis[i] & ~1ull) : KEY_INF;
     __syncthreads();
     bitonic_sort_keys(cand_lds, n2, lane);
-    cnt = prune_sorted<KIND, VEC, NCH>(T, st, blk, cand_lds, nv, a.R, al, out, lane, pair_evals);
+    bool done = false;
+    cnt = 0;
+    if constexpr (kMfma) {
+      if (a.use_mfma) {
+        cnt = prune_sorted_mfma<KIND, VEC, NCH>(T, M, cand_lds, nv, a.R, a.a16, out, lane, pair_evals);
+        done = true;
+      }
+    }
+    if (!done) cnt = prune_sorted<KIND, VEC, NCH>(T, st, blk, cand_lds, nv, a.R, al, out, lane, pair_evals);
   } else {
     for (u32 i = lane; i < nv; i += 64) vis[i] &= ~1ull;
     __syncthreads();
-    cnt = prune_unsorted<KIND, VEC, NCH>(T, st, vis, nv, a.R, al, out, lane, pair_evals);
+    SelStage st2 = st;
+    if (a.use_mfma) st2.vec = nullptr;  // the LDS areas are laid out for the matrix-core walk
+    cnt = prune_unsorted<KIND, VEC, NCH>(T, st2, vis, nv, a.R, al, out, lane, pair_evals);
   }
   __syncthreads();
 
@@ -73,7 +85,8 @@ __global__ __launch_bounds__(64) void prune_kernel(PruneArgs a, VecTable T) {
 
 template <int KIND, int VEC, int NCH>
 static hipError_t launch_prune_t(const PruneArgs& a, const VecTable& T, hipStream_t s) {
-  const u32 lds = ((a.R * 8u + 15u) & ~15u) + 8u * stage_stride(T.row_bytes) + 32u + a.stage_bytes;
+  const u32 lds = a.use_mfma ? ((a.R * 4u + 15u) & ~15u) + mfma_lds_bytes(a.R)
+                            : ((a.R * 8u + 15u) & ~15u) + 8u * stage_stride(T.row_bytes) + 32u + a.stage_bytes;
   hipLaunchKernelGGL((prune_kernel<KIND, VEC, NCH>), dim3(a.nq), dim3(64), lds, s, a, T);
   return hipGetLastError();
 }

@@ -12,6 +12,8 @@
 // block ahead.
 #pragma once
 
+#include <utility>
+
 #include "ann_device.hpp"
 
 namespace annmi {
@@ -304,6 +306,217 @@ __device__ __forceinline__ u32 prune_sorted(const VecTable& T, const SelStage& s
           }
         }
         if (sub == 0) st.xx[slot] = (u32)cur.qq;
+      }
+    }
+    nout += nsel;
+    __syncthreads();
+  }
+  return nout;
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same walk for u8/i8 rows of at most 128 bytes, 32 candidates at a time, with the pair
+// distances taken on the matrix cores.
+//
+// For a block of 32 candidates two small matrix products decide everything: (selected so far) x
+// (block) tells which candidates are removed by an earlier selection, and (block) x (block) which
+// candidate would remove which later one.  Both are Gram-type products of int8 vectors (u8 data
+// is shifted by -128; distances do not change), exact in int32, computed with
+// v_mfma_i32_32x32x32_i8 from LDS copies of the vectors: D(i,j) = |x_i|^2 + |x_j|^2 - 2<x_i,x_j>,
+// and "i removes j" is D(i,j) <= floor(d(p,j) * 2^16 / a16).  The 32 verdicts are then settled in
+// order on bit masks.
+// ---------------------------------------------------------------------------------------------
+typedef int v4i_t __attribute__((ext_vector_type(4)));
+typedef int v16i_t __attribute__((ext_vector_type(16)));
+
+constexpr u32 MM_STRIDE = 144;  // bytes between staged rows (128 + 16: spreads LDS banks)
+constexpr u32 MM_BLOCK = 32;    // candidates per block
+
+template <int KIND, int VEC, int NCH>
+struct MfmaPruneOk {
+  static constexpr bool value = KindTraits<KIND>::is_int && (8 * NCH * VEC <= 128);
+};
+
+// floor(d * 2^16 / a16) for 0 <= d < 2^31, 0 < a16 < 2^31, clamped to INT32_MAX
+__device__ __forceinline__ i32 alpha_threshold(i32 d, i64 a16) {
+  const u64 x = (u64)(u32)d << 16;
+  u64 t = (u64)__builtin_floor((double)x / (double)a16);
+  if (t * (u64)a16 > x)
+    --t;
+  else if ((t + 1) * (u64)a16 <= x)
+    ++t;
+  return t > 0x7FFFFFFFull ? 0x7FFFFFFF : (i32)t;
+}
+
+// LDS areas of the matrix-core walk (all 16-byte aligned)
+struct MfmaLds {
+  unsigned char* sel;  // roundup(R, 32) rows of MM_STRIDE bytes: vectors of the selected points
+  u32* selnorm;        // roundup(R, 32): their squared norms (shifted vectors)
+  unsigned char* blk;  // 32 rows: the current block of candidates
+  u32* cnorm;          // 32
+  i32* cthr;           // 32: removal thresholds of the block's candidates
+  u32* cid;            // 32
+};
+__host__ __device__ inline u32 mfma_rows(u32 R) { return (R + 31u) & ~31u; }
+__host__ __device__ inline u32 mfma_lds_bytes(u32 R) {
+  return mfma_rows(R) * MM_STRIDE + mfma_rows(R) * 4u + MM_BLOCK * MM_STRIDE + 3u * MM_BLOCK * 4u;
+}
+__device__ __forceinline__ MfmaLds mfma_lds_carve(unsigned char* base, u32 R) {
+  MfmaLds M;
+  M.sel = base;
+  M.blk = M.sel + mfma_rows(R) * MM_STRIDE;
+  M.selnorm = reinterpret_cast<u32*>(M.blk + MM_BLOCK * MM_STRIDE);
+  M.cnorm = M.selnorm + mfma_rows(R);
+  M.cthr = reinterpret_cast<i32*>(M.cnorm + MM_BLOCK);
+  M.cid = reinterpret_cast<u32*>(M.cthr + MM_BLOCK);
+  return M;
+}
+
+template <int R_>
+__device__ __forceinline__ void mm_block_rows(const v16i_t& acc, const uint4 (&n4)[4], i32 ncol, i32 tcol, u32& by) {
+  // accumulator register R_ of lane l is entry (row 8*(R_/4) + 4*(l/32) + R_%4, column l%32)
+  constexpr int mlo = 8 * (R_ / 4) + (R_ % 4);
+  const u32 nrow = (R_ % 4) == 0 ? n4[R_ / 4].x : (R_ % 4) == 1 ? n4[R_ / 4].y : (R_ % 4) == 2 ? n4[R_ / 4].z : n4[R_ / 4].w;
+  const i32 D = (i32)nrow + ncol - 2 * acc[R_];
+  const u64 bm = ballot(D <= tcol);
+  by = writelane_u32<mlo>(by, (u32)bm);
+  by = writelane_u32<mlo + 4>(by, (u32)(bm >> 32));
+}
+template <int... Rs>
+__device__ __forceinline__ void mm_block_rows_all(const v16i_t& acc, const uint4 (&n4)[4], i32 ncol, i32 tcol, u32& by,
+                                                  std::integer_sequence<int, Rs...>) {
+  (mm_block_rows<Rs>(acc, n4, ncol, tcol, by), ...);
+}
+
+template <int KIND, int VEC, int NCH>
+__device__ __forceinline__ u32 prune_sorted_mfma(const VecTable& T, const MfmaLds& M, const u64* cand, u32 m, u32 R,
+                                                 i64 a16, u32* out, int lane, u32& pair_evals) {
+  const int sub = lane & (LPC - 1);
+  const u32 grp = (u32)lane >> 3;
+  const u32 half = (u32)lane >> 5;
+  const u32 col = (u32)lane & 31u;
+  const u32 flip = KIND == K_U8 ? 0x80808080u : 0u;
+  const u32 ksteps = (T.row_bytes + 31u) / 32u;  // <= 4
+  u32 nout = 0;
+  if (m == 0) return 0;
+
+  Piece<VEC> nx[4][NCH];  // the next block's vectors, 4 passes of 8 candidates
+  auto issue = [&](u32 i0) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const u32 c = i0 + 8u * p + grp;
+      const bool ok = c < m;
+      const u32 id = ok ? key_id(cand[c]) : 0u;
+      const char* src = T.base + (u64)id * T.row_bytes;
+#pragma unroll
+      for (int u = 0; u < NCH; ++u) {
+        const u32 pc = sub + LPC * u;
+        nx[p][u] = (ok && pc < T.npieces) ? load_piece<VEC>(src + (u64)pc * VEC) : zero_piece<VEC>();
+      }
+    }
+  };
+  issue(0);
+
+  for (u32 i0 = 0; i0 < m && nout < R; i0 += MM_BLOCK) {
+    const u32 nb = m - i0 < MM_BLOCK ? m - i0 : MM_BLOCK;
+    // park the block in LDS (as int8), take the norms
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const u32 c = 8u * p + grp;
+      const bool ok = c < nb;
+      i32 nn = 0;
+#pragma unroll
+      for (int u = 0; u < NCH; ++u) {
+        const u32 pc = sub + LPC * u;
+#pragma unroll
+        for (int i = 0; i < VEC / 4; ++i) {
+          const u32 wv = (ok && pc < T.npieces) ? (nx[p][u].w[i] ^ flip) : 0u;
+          nn = __builtin_amdgcn_sdot4((i32)wv, (i32)wv, nn, false);
+          *reinterpret_cast<u32*>(M.blk + c * MM_STRIDE + pc * VEC + 4 * i) = wv;
+        }
+      }
+      nn = group_sum(nn);
+      if (sub == 0) M.cnorm[c] = (u32)nn;
+    }
+    if (lane < (int)MM_BLOCK) {
+      const bool ok = (u32)lane < nb;
+      const u64 key = ok ? cand[i0 + lane] : KEY_INF;
+      M.cthr[lane] = ok ? alpha_threshold(int_from_dkey(key_dkey(key)), a16) : -1;
+      M.cid[lane] = key_id(key);
+    }
+    if (i0 + MM_BLOCK < m) issue(i0 + MM_BLOCK);  // travels while this block is settled
+    __syncthreads();
+
+    // column operand: candidate `col`, this lane's 16 bytes of every k-step
+    v4i_t bv[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+      bv[ks] = (u32)ks < ksteps ? *reinterpret_cast<const v4i_t*>(M.blk + col * MM_STRIDE + 32u * ks + 16u * half)
+                                : v4i_t{0, 0, 0, 0};
+    const i32 ncol = (i32)M.cnorm[col];
+    const i32 tcol = M.cthr[col];
+
+    // removed by a point selected before this block?
+    bool rem = false;
+    for (u32 s0 = 0; s0 < nout; s0 += 32) {
+      v16i_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        if ((u32)ks < ksteps) {
+          const v4i_t av = *reinterpret_cast<const v4i_t*>(M.sel + (s0 + col) * MM_STRIDE + 32u * ks + 16u * half);
+          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(av, bv[ks], acc, 0, 0, 0);
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const u32 sb = s0 + 8u * q + 4u * half;
+        const uint4 n4 = *reinterpret_cast<const uint4*>(M.selnorm + sb);
+        rem = rem | (sb + 0 < nout && (i32)n4.x + ncol - 2 * acc[4 * q + 0] <= tcol);
+        rem = rem | (sb + 1 < nout && (i32)n4.y + ncol - 2 * acc[4 * q + 1] <= tcol);
+        rem = rem | (sb + 2 < nout && (i32)n4.z + ncol - 2 * acc[4 * q + 2] <= tcol);
+        rem = rem | (sb + 3 < nout && (i32)n4.w + ncol - 2 * acc[4 * q + 3] <= tcol);
+      }
+    }
+    const u64 rm = ballot(rem);
+    const u32 removed_old = (u32)rm | (u32)(rm >> 32);
+
+    // which candidate of the block would remove which: lane t ends up with the mask of row t
+    u32 by = 0;
+    {
+      v16i_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+        if ((u32)ks < ksteps) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(bv[ks], bv[ks], acc, 0, 0, 0);
+      uint4 n4[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) n4[q] = *reinterpret_cast<const uint4*>(M.cnorm + 8u * q + 4u * half);
+      mm_block_rows_all(acc, n4, ncol, tcol, by, std::make_integer_sequence<int, 16>{});
+    }
+    pair_evals += nb * nout + nb * (nb - 1) / 2;
+
+    // settle the block in order
+    u32 alive = (nb >= 32u ? ~0u : ((1u << nb) - 1u)) & ~removed_old;
+    u32 selmask = 0, nsel = 0;
+    while (alive != 0 && nout + nsel < R) {
+      const int t = __builtin_ctz(alive);
+      selmask |= 1u << t;
+      ++nsel;
+      alive &= ~readlane_u32(by, t);
+      alive &= ~(1u << t);
+    }
+    // commit: ids, norms and vectors of the selected candidates, in order
+    if (lane < (int)MM_BLOCK && ((selmask >> lane) & 1u)) {
+      const u32 slot = nout + (u32)__builtin_popcount(selmask & ((1u << lane) - 1u));
+      out[slot] = M.cid[lane];
+      M.selnorm[slot] = M.cnorm[lane];
+    }
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const u32 t = 8u * p + grp;
+      if ((selmask >> t) & 1u) {
+        const u32 slot = nout + (u32)__builtin_popcount(selmask & ((1u << t) - 1u));
+        *reinterpret_cast<uint4*>(M.sel + slot * MM_STRIDE + 16u * sub) =
+            *reinterpret_cast<const uint4*>(M.blk + t * MM_STRIDE + 16u * sub);
       }
     }
     nout += nsel;
