@@ -58,8 +58,10 @@ typedef struct {
   uint32_t use_start;    /* zero: s = point nearest the mean (ann_start_vertex)        */
   const uint32_t* order; /* host, n-1 ids: insertion order; NULL = seeded shuffle      */
   uint32_t visited_cap;  /* slots per search for the visited list; 0 = max(256, 4L).
-                            Searches that visit more are redone with enough room, so
+                            A search that visits more moves its list to a spill chunk;
+                            if that fails too the search is redone with enough room, so
                             the result never depends on this value.                    */
+  uint64_t spill_cap;    /* keys of spill space for such lists; 0 = default            */
   uint32_t hash_bits;    /* log2 size of the per-search visited filter in LDS; 0 = auto.
                             The filter only saves work; results do not depend on it.   */
   uint64_t max_rounds;   /* stop after this many batches (0 = all): partial builds     */
@@ -85,7 +87,8 @@ typedef struct {
   uint64_t appends;     /* step-2 rows that only appended                        */
   uint64_t edges;       /* reverse edges grouped                                 */
   uint64_t prune_evals; /* pair distances taken inside prune                     */
-  uint64_t redone;      /* searches redone because the visited list overflowed   */
+  uint64_t redone;      /* searches redone because the visited list fit nowhere  */
+  uint64_t restarts;    /* builds started over in synchronised mode for that     */
   uint64_t rounds;
   double ms_search, ms_prune, ms_sort, ms_merge, ms_total; /* device time per phase */
 } ann_stats;

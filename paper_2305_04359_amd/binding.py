@@ -31,6 +31,7 @@ class BuildOpts(C.Structure):
         ("use_start", C.c_uint32),
         ("order", C.c_void_p),
         ("visited_cap", C.c_uint32),
+        ("spill_cap", C.c_uint64),
         ("hash_bits", C.c_uint32),
         ("max_rounds", C.c_uint64),
         ("collect_stats", C.c_uint32),
@@ -44,7 +45,7 @@ class GraphInfo(C.Structure):
 
 class Stats(C.Structure):
     _fields_ = [(k, C.c_uint64) for k in ("searches", "hops", "evals", "prunes", "reprunes", "appends",
-                                           "edges", "prune_evals", "redone", "rounds")] + \
+                                           "edges", "prune_evals", "redone", "restarts", "rounds")] + \
                [(k, C.c_double) for k in ("ms_search", "ms_prune", "ms_sort", "ms_merge", "ms_total")]
 
     def as_dict(self):
@@ -173,7 +174,7 @@ class Graph:
 
 
 def ann_build(points, R, L, alpha, seed=1, metric=L2SQ, batch_cap=0, start=None, order=None,
-              visited_cap=0, hash_bits=0, max_rounds=0, collect_stats=False) -> Graph:
+              visited_cap=0, hash_bits=0, max_rounds=0, collect_stats=False, spill_cap=0) -> Graph:
     """batchBuild of Alg. 3 over a device tensor of points (n x d; uint8, int8 or float32)."""
     points = _dev2d(points, "points")
     o = BuildOpts()
@@ -187,6 +188,7 @@ def ann_build(points, R, L, alpha, seed=1, metric=L2SQ, batch_cap=0, start=None,
             raise ValueError("order must hold n-1 ids")
         o.order = keep.ctypes.data
     o.visited_cap = visited_cap
+    o.spill_cap = spill_cap
     o.hash_bits = hash_bits
     o.max_rounds = max_rounds
     o.collect_stats = 1 if collect_stats else 0

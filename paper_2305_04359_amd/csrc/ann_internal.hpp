@@ -36,10 +36,17 @@ struct SearchArgs {
   u32 k;
   u32 hash_bits;  // log2 of the visited filter's size in 32-bit words
   u32 id_bits;    // > 0: the filter stores 16-bit tags of ids that fit in this many bits
-  // build: visited list, one slot of vis_cap keys per search (may be null)
+  // build: visited list, one slot of vis_cap keys per search (may be null).  A search that
+  // outgrows its slot moves its list to a chunk of vis_cap + spill_chunk keys taken from `spill`
+  // (if given) and records the chunk's offset in vis_where[search] (~0 = still in its slot).
   u64* vis;
   u32* nvis;
   u32 vis_cap;
+  u64* spill;
+  u64 spill_cap;
+  unsigned long long* spill_top;
+  u32 spill_chunk;
+  u64* vis_where;
   // query: results (may be null)
   u32* out_ids;
   void* out_dists;
@@ -57,6 +64,10 @@ struct PruneArgs {
   const u32* nvis;
   u32 vis_cap;
   u64* vis_rw;          // same memory as vis: lists longer than the LDS buffer are pruned in place
+  u64* spill;           // chunks of vis_cap + spill_chunk keys for lists that outgrew their slot
+  u32 spill_chunk;
+  const u64* vis_where; // per search: offset of its chunk in spill, or ~0 (may be null)
+  u32* lost_flag;       // set (and left set) when a list did not fit anywhere
   u32* meta;            // per row: degree | clean prefix length << 16 (written for the batch points)
   u64* edges;           // batch_size x R keys (dest << 32 | source), ~0 in unused slots
   u32 stage_bytes;      // dynamic LDS for the selected points' vectors (0: read them from memory)

@@ -112,6 +112,12 @@ bool make_cfg(uint32_t d, int dtype, int metric, DistCfg* cfg, std::string* why)
   return true;
 }
 
+// keys of spill space for visited lists that outgrow their slot: room for 1 in 64 searches
+u64 default_spill_keys(u64 batch) {
+  const u64 k = (batch / 64 + 16) * (8192 + 1024);
+  return k;
+}
+
 u32 bits_for(u64 n) {  // smallest b with 2^b - 1 >= n
   u32 b = 1;
   while (((1ull << b) - 1ull) < n) ++b;
@@ -141,6 +147,7 @@ struct ann_graph {
   ann_stats stats{};
   u32 hash_bits = 0;
   u32 visited_cap = 0;
+  u64 spill_keys = 0;  // 0 = default
   bool collect = false;
 };
 
@@ -150,7 +157,9 @@ namespace {
 struct BatchScratch {
   u64 bmax = 0;
   u32 vis_cap = 0;
-  DevBuf qidx, vis, nvis, edges, edges_tmp, hist, lists, small, ovf_list, arena;
+  DevBuf qidx, vis, nvis, edges, edges_tmp, hist, lists, small, ovf_list, arena, spill, vis_where;
+  u64 spill_cap = 0;    // keys
+  u32 spill_chunk = 0;  // extra keys a spilled list gets on top of vis_cap
   u64 arena_cap = 0;
   // side streams (default priority) on which two of the three re-prune kernels run, and the
   // events that order them against the caller's stream
@@ -163,10 +172,13 @@ struct BatchScratch {
     for (auto& e : ev_side)
       if (e) (void)hipEventDestroy(e);
   }
-  // small: [0] overflow_count u32, [2] error flag u32, [4..5] arena_top u64, [8..10] work list counts
-  int alloc(u64 b, u32 R, u32 cap) {
+  // small: [0] overflow_count u32, [2] arena error flag, [3] "a visited list was lost" flag,
+  // [4..5] arena_top u64, [6..7] spill_top u64, [8..10] work list counts
+  int alloc(u64 b, u32 R, u32 cap, u64 spill_keys) {
     bmax = b;
     vis_cap = cap;
+    spill_chunk = 8192;
+    spill_cap = spill_keys;
     const u64 E = b * R;
     // a spilled candidate list is longer than MERGE_SPILL_MIN and has at most R old entries
     arena_cap = E + (u64)R * (E / (MERGE_SPILL_MIN - R) + 1);
@@ -181,6 +193,8 @@ struct BatchScratch {
     HIP_TRY(hipMemset(small.p, 0, 64));
     HIP_TRY(ovf_list.alloc(b * 4));
     HIP_TRY(arena.alloc(arena_cap * 8));
+    HIP_TRY(spill.alloc(spill_cap * 8));
+    HIP_TRY(vis_where.alloc(b * 8));
     for (auto& s : side) HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
     HIP_TRY(hipEventCreateWithFlags(&ev_plan, hipEventDisableTiming));
     for (auto& e : ev_side) HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
@@ -188,51 +202,65 @@ struct BatchScratch {
   }
 };
 
-// HIP events around the phases of a batch.  Two sets, used alternately, so that the times of a
-// batch can be read at the next batch's synchronisation point instead of forcing one of its own.
+// HIP events around the phases of every batch, read when the batches have finished.
 struct PhaseTimer {
-  hipEvent_t ev[2][5]{};
+  std::vector<hipEvent_t> ev;  // 5 per batch
   bool on = false;
-  int cur = 0;           // set being recorded
-  bool pending = false;  // the other set holds a finished, unread batch
+  size_t cur = 0;  // batch being recorded
   int init(bool enable) {
     on = enable;
+    return ANN_OK;
+  }
+  int begin_batch() {
     if (!on) return ANN_OK;
-    for (auto& set : ev)
-      for (auto& e : set) HIP_TRY(hipEventCreate(&e));
+    cur = ev.size() / 5;
+    for (int i = 0; i < 5; ++i) {
+      hipEvent_t e;
+      HIP_TRY(hipEventCreate(&e));
+      ev.push_back(e);
+    }
     return ANN_OK;
   }
   void mark(int i, hipStream_t s) {
-    if (on) (void)hipEventRecord(ev[cur][i], s);
+    if (on) (void)hipEventRecord(ev[cur * 5 + i], s);
   }
-  ~PhaseTimer() {
-    if (on)
-      for (auto& set : ev)
-        for (auto& e : set)
-          if (e) (void)hipEventDestroy(e);
+  void clear() {
+    for (auto& e : ev) (void)hipEventDestroy(e);
+    ev.clear();
   }
+  ~PhaseTimer() { clear(); }
 };
 
-// Adds the phase times of event set `set`, whose batch is known to have finished.
-void collect_phase_times(ann_graph* g, PhaseTimer& tm, int set) {
+// Adds up the phase times of all recorded batches (the caller has synchronised the stream).
+void collect_phase_times(ann_graph* g, PhaseTimer& tm) {
   if (!tm.on) return;
-  float ms = 0;
-  (void)hipEventElapsedTime(&ms, tm.ev[set][0], tm.ev[set][1]);
-  g->stats.ms_search += ms;
-  (void)hipEventElapsedTime(&ms, tm.ev[set][1], tm.ev[set][2]);
-  g->stats.ms_prune += ms;
-  (void)hipEventElapsedTime(&ms, tm.ev[set][2], tm.ev[set][3]);
-  g->stats.ms_sort += ms;
-  (void)hipEventElapsedTime(&ms, tm.ev[set][3], tm.ev[set][4]);
-  g->stats.ms_merge += ms;
-  (void)hipEventElapsedTime(&ms, tm.ev[set][0], tm.ev[set][4]);
-  g->stats.ms_total += ms;
+  for (size_t k = 0; k + 5 <= tm.ev.size(); k += 5) {
+    float ms = 0;
+    (void)hipEventElapsedTime(&ms, tm.ev[k + 0], tm.ev[k + 1]);
+    g->stats.ms_search += ms;
+    (void)hipEventElapsedTime(&ms, tm.ev[k + 1], tm.ev[k + 2]);
+    g->stats.ms_prune += ms;
+    (void)hipEventElapsedTime(&ms, tm.ev[k + 2], tm.ev[k + 3]);
+    g->stats.ms_sort += ms;
+    (void)hipEventElapsedTime(&ms, tm.ev[k + 3], tm.ev[k + 4]);
+    g->stats.ms_merge += ms;
+    (void)hipEventElapsedTime(&ms, tm.ev[k + 0], tm.ev[k + 4]);
+    g->stats.ms_total += ms;
+  }
+  tm.clear();
 }
 
 // BatchInsert(P') of Alg. 3 for the b ids in ids_host (device copy made here).
+// With `sync` the host waits after step 1 and redoes, with as much room as they need, the searches
+// whose visited list fit neither its slot nor a spill chunk; without it nothing waits, such a
+// search leaves its point unconnected and raises a flag that finish_batches reports.
 int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u32* ids_dev, u64 b, u32 L,
-                 float alpha, BatchScratch& S, PhaseTimer& tm, hipStream_t st) {
+                 float alpha, BatchScratch& S, PhaseTimer& tm, hipStream_t st, bool sync) {
   if (b == 0) return ANN_OK;
+  {
+    int rc0 = tm.begin_batch();
+    if (rc0) return rc0;
+  }
   const u32 R = g->R;
   const u64 E = b * R;
   const long long a16 = llround((double)alpha * 65536.0);
@@ -244,8 +272,8 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   u32* small = S.small.as<u32>();
   DevCounters* ctr = g->collect ? g->counters : nullptr;
 
-  // per-batch counters: [0] overflow count, [4..5] arena top, [8..10] work list lengths; the
-  // error flag [2] stays up once set
+  // per-batch counters: [0] overflow count, [4..5] arena top, [6..7] spill top, [8..10] work list
+  // lengths; the flags [2] and [3] stay up once set
   HIP_TRY(hipMemsetAsync(small, 0, 8, st));
   HIP_TRY(hipMemsetAsync(small + 4, 0, 32, st));
   tm.mark(0, st);
@@ -267,6 +295,11 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   sa.vis = S.vis.as<u64>();
   sa.nvis = S.nvis.as<u32>();
   sa.vis_cap = S.vis_cap;
+  sa.spill = S.spill_cap ? S.spill.as<u64>() : nullptr;
+  sa.spill_cap = S.spill_cap;
+  sa.spill_top = reinterpret_cast<unsigned long long*>(small + 6);
+  sa.spill_chunk = S.spill_chunk;
+  sa.vis_where = S.vis_where.as<u64>();
   sa.counters = ctr;
   HIP_TRY(launch_search(g->cfg, sa, st));
   tm.mark(1, st);
@@ -283,6 +316,10 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   pa.vis_rw = S.vis.as<u64>();
   pa.nvis = S.nvis.as<u32>();
   pa.vis_cap = S.vis_cap;
+  pa.spill = S.spill.as<u64>();
+  pa.spill_chunk = S.spill_chunk;
+  pa.vis_where = S.vis_where.as<u64>();
+  pa.lost_flag = small + 3;
   pa.meta = g->meta;
   pa.stage_bytes = prune_stage_bytes(R, g->cfg);
   pa.use_mfma = mfma_prune_ok(R, g->cfg) ? 1u : 0u;
@@ -294,13 +331,11 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   pa.counters = ctr;
   HIP_TRY(launch_prune(g->cfg, pa, st));
 
-  // searches whose visited list outgrew its slot are redone with as much room as they need
+  // searches whose visited list fit nowhere are redone with as much room as they need
   u32 novf = 0;
-  HIP_TRY(hipMemcpyAsync(&novf, small + 0, 4, hipMemcpyDeviceToHost, st));
-  HIP_TRY(hipStreamSynchronize(st));  // the one host synchronisation of a batch
-  if (tm.pending) {
-    collect_phase_times(g, tm, tm.cur ^ 1);
-    tm.pending = false;
+  if (sync) {
+    HIP_TRY(hipMemcpyAsync(&novf, small + 0, 4, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
   }
   if (novf > 0) {
     std::vector<u32> slots(novf), nv(b);
@@ -326,6 +361,8 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
     sb.vis = vis2.as<u64>();
     sb.nvis = nvis2.as<u32>();
     sb.vis_cap = need;
+    sb.spill = nullptr;
+    sb.vis_where = nullptr;
     sb.counters = nullptr;
     HIP_TRY(launch_search(g->cfg, sb, st));
     PruneArgs pb = pa;
@@ -336,12 +373,14 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
     pb.vis_rw = vis2.as<u64>();
     pb.nvis = nvis2.as<u32>();
     pb.vis_cap = need;
+    pb.vis_where = nullptr;
     HIP_TRY(launch_prune(g->cfg, pb, st));
     u32 again = 0;
     HIP_TRY(hipMemcpyAsync(&again, small + 0, 4, hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     if (again != 0) return fail(ANN_EINTERNAL, "visited list overflowed again on retry");
     g->stats.redone += novf;
+    HIP_TRY(hipMemsetAsync(small + 3, 0, 4, st));  // every lost list has been made up for
   }
   tm.mark(2, st);
 
@@ -384,26 +423,22 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
     HIP_TRY(hipStreamWaitEvent(st, S.ev_side[i], 0));
   }
   tm.mark(4, st);
-  if (tm.on) {
-    tm.pending = true;
-    tm.cur ^= 1;
-  }
   g->rounds += 1;
   g->stats.rounds += 1;
   return ANN_OK;
 }
 
+constexpr int ANN_LOST_LIST = 1;  // internal: a visited list fit nowhere in a batch issued without sync
+
 // Waits for the batches issued so far; reports a spill-arena failure (cannot happen with the
-// arena sized as it is) and reads the phase times of the last batch.
+// arena sized as it is) or a lost visited list, and reads the phase times.
 int finish_batches(ann_graph* g, BatchScratch& S, PhaseTimer& tm, hipStream_t st) {
   u32 flags[4] = {0, 0, 0, 0};
   HIP_TRY(hipMemcpyAsync(flags, S.small.p, 16, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
+  collect_phase_times(g, tm);
   if (flags[2] != 0) return fail(ANN_EINTERNAL, "merge spill arena exhausted");
-  if (tm.pending) {
-    collect_phase_times(g, tm, tm.cur ^ 1);
-    tm.pending = false;
-  }
+  if (flags[3] != 0) return ANN_LOST_LIST;
   return ANN_OK;
 }
 
@@ -549,15 +584,16 @@ int ann_insert_batch(ann_graph* g, const void* points_dev, const uint32_t* ids_h
   hipStream_t st = static_cast<hipStream_t>(stream);
   BatchScratch S;
   const u32 cap = g->visited_cap ? g->visited_cap : (4 * L > 256 ? 4 * L : 256);
-  rc = S.alloc(b, g->R, cap);
+  rc = S.alloc(b, g->R, cap, g->spill_keys ? g->spill_keys : default_spill_keys(b));
   if (rc) return rc;
   HIP_TRY(hipMemcpy(S.qidx.p, ids_host, (size_t)b * 4, hipMemcpyHostToDevice));
   PhaseTimer tm;
   rc = tm.init(g->collect);
   if (rc) return rc;
-  rc = batch_insert(g, points_dev, ids_host, S.qidx.as<u32>(), b, L, alpha, S, tm, st);
+  rc = batch_insert(g, points_dev, ids_host, S.qidx.as<u32>(), b, L, alpha, S, tm, st, /*sync=*/true);
   if (rc) return rc;
-  return finish_batches(g, S, tm, st);
+  rc = finish_batches(g, S, tm, st);
+  return rc == ANN_LOST_LIST ? fail(ANN_EINTERNAL, "a visited list was lost in a synchronised batch") : rc;
 }
 
 int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric, uint32_t R,
@@ -584,6 +620,7 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
   g->hash_bits = o.hash_bits;
   if (g->hash_bits && (g->hash_bits < 4 || g->hash_bits > 13)) return fail(ANN_EINVAL, "hash_bits must be in [4, 13]");
   g->visited_cap = o.visited_cap;
+  g->spill_keys = o.spill_cap;
   HIP_TRY(hipMemsetAsync(g->rows, 0xFF, (size_t)n * R * sizeof(u32), st));
 
   // start vertex s: present from the beginning with an empty row, never inserted again
@@ -640,19 +677,38 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
   if (m) HIP_TRY(hipMemcpyAsync(order_dev.p, order.data(), m * 4, hipMemcpyHostToDevice, st));
   BatchScratch S;
   const u32 cap = g->visited_cap ? g->visited_cap : (4 * L > 256 ? 4 * L : 256);
-  rc = S.alloc(bmax, R, cap);
+  rc = S.alloc(bmax, R, cap, g->spill_keys ? g->spill_keys : default_spill_keys(bmax));
   if (rc) return rc;
   PhaseTimer tm;
   rc = tm.init(g->collect);
   if (rc) return rc;
 
-  for (size_t r = 0; r + 1 < bounds.size(); ++r) {
-    if (o.max_rounds && r >= o.max_rounds) break;
-    const u64 lo = bounds[r], b = bounds[r + 1] - bounds[r];
-    rc = batch_insert(g, points_dev, order.data() + lo, order_dev.as<u32>() + lo, b, L, alpha, S, tm, st);
-    if (rc) return rc;
+  // First try: every batch is issued without waiting for the previous one.  A search whose
+  // visited list fits neither its slot nor a spill chunk spoils that attempt (it is detected at
+  // the end); the build is then repeated from the empty graph with a host check after step 1 of
+  // every batch, which redoes such searches with as much room as they need.
+  for (int attempt = 0; attempt < 2; ++attempt) {
+    const bool sync = attempt == 1;
+    for (size_t r = 0; r + 1 < bounds.size(); ++r) {
+      if (o.max_rounds && r >= o.max_rounds) break;
+      const u64 lo = bounds[r], b = bounds[r + 1] - bounds[r];
+      rc = batch_insert(g, points_dev, order.data() + lo, order_dev.as<u32>() + lo, b, L, alpha, S, tm, st, sync);
+      if (rc) return rc;
+    }
+    rc = finish_batches(g, S, tm, st);
+    if (rc != ANN_LOST_LIST) break;
+    if (sync) return fail(ANN_EINTERNAL, "a visited list was lost in a synchronised batch");
+    // start over
+    HIP_TRY(hipMemsetAsync(g->rows, 0xFF, (size_t)n * R * sizeof(u32), st));
+    HIP_TRY(hipMemsetAsync(g->meta, 0, (size_t)n * sizeof(u32), st));
+    HIP_TRY(hipMemsetAsync(g->counters, 0, sizeof(DevCounters), st));
+    HIP_TRY(hipMemsetAsync(S.small.p, 0, 64, st));
+    const u64 redone = g->stats.redone;
+    g->stats = ann_stats{};
+    g->stats.redone = redone;
+    g->stats.restarts = 1;
+    g->rounds = 0;
   }
-  rc = finish_batches(g, S, tm, st);
   if (rc) return rc;
   guard.g = nullptr;
   *out = g;

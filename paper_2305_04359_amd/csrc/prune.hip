@@ -31,18 +31,21 @@ __global__ __launch_bounds__(64) void prune_kernel(PruneArgs a, VecTable T) {
   const u32 nv = a.nvis[qi];
   u64* edges = a.edges + (u64)slot * a.R;
 
-  if (nv > a.vis_cap) {
-    // the visited list did not fit: leave this point to the host's retry
+  const u64 where = a.vis_where != nullptr ? a.vis_where[qi] : ~0ull;
+  const u32 room = where == ~0ull ? a.vis_cap : a.vis_cap + a.spill_chunk;
+  if (nv > room) {
+    // the visited list did not fit anywhere: leave this point to the host
     if (lane == 0) {
       const u32 o = atomicAdd(a.overflow_count, 1u);
       a.overflow_list[o] = qi;
+      *a.lost_flag = 1u;
     }
     for (u32 j = lane; j < a.R; j += 64) edges[j] = KEY_INF;
     return;
   }
 
   const AlphaParam al{a.a16, a.af};
-  u64* vis = a.vis_rw + (u64)qi * a.vis_cap;
+  u64* vis = where == ~0ull ? a.vis_rw + (u64)qi * a.vis_cap : a.spill + where;
   u32 pair_evals = 0;
   u32 cnt;
   if (nv <= PRUNE_LDS_CAP) {

@@ -68,6 +68,11 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
   }
 
   u32 size = 1, nv = 0, evals = 1;
+  // where the visited list goes: the search's own slot, later perhaps a spill chunk
+  u64* vptr = a.vis != nullptr ? a.vis + (u64)qi * a.vis_cap : nullptr;
+  u32 vcap = a.vis_cap;
+  bool vspilled = false, vlost = false;
+  if (a.vis_where != nullptr && lane == 0) a.vis_where[qi] = ~0ull;
 
   for (;;) {
     // p* <- closest unprocessed member of the beam
@@ -87,7 +92,29 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
     }
     if (pos < 0) break;
     const u32 pstar = key_id(pk);
-    if (a.vis != nullptr && lane == 0 && nv < a.vis_cap) a.vis[(u64)qi * a.vis_cap + nv] = pk;
+    if (vptr != nullptr) {
+      if (nv == vcap && !vlost) {  // uniform: the list is full
+        vlost = true;
+        if (!vspilled && a.spill != nullptr) {
+          const u64 need = (u64)vcap + a.spill_chunk;
+          unsigned long long off = 0;
+          if (lane == 0) off = atomicAdd(a.spill_top, (unsigned long long)need);
+          off = readlane_u64(off, 0);
+          if (off + need <= a.spill_cap) {
+            __threadfence();
+            u64* dst = a.spill + off;
+            for (u32 i = lane; i < vcap; i += 64)
+              dst[i] = __hip_atomic_load(vptr + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (lane == 0) a.vis_where[qi] = off;
+            vptr = dst;
+            vcap = (u32)need;
+            vspilled = true;
+            vlost = false;
+          }
+        }
+      }
+      if (!vlost && lane == 0) vptr[nv] = pk;
+    }
     ++nv;
 
     // beam <- beam U N_out(p*), keep the L closest

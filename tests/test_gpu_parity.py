@@ -223,9 +223,27 @@ def test_build_does_not_depend_on_scratch_sizes(env, c1):
     ds = O.Dataset(pts_h, 0)
     og, s = O.build(ds, 16, 32, 1.2, seed=3, threads=0)
     pts = dev(torch, pts_h)
-    g = A.ann_build(pts, 16, 32, 1.2, seed=3, visited_cap=8, hash_bits=4, collect_stats=True)
+    # lists that outgrow their 8-entry slot move to spill chunks on the device ...
+    g = A.ann_build(pts, 16, 32, 1.2, seed=3, visited_cap=8, spill_cap=10 ** 6, hash_bits=4, collect_stats=True)
     assert (g.neighbors() == og).all()
-    assert g.stats()["redone"] > 1000
+    assert g.stats()["restarts"] == 0
+    # ... and with (almost) no spill space the build notices at the end, starts over and lets the
+    # host redo the searches that did not fit
+    g = A.ann_build(pts, 16, 32, 1.2, seed=3, visited_cap=8, spill_cap=1, hash_bits=4, collect_stats=True)
+    assert (g.neighbors() == og).all()
+    st = g.stats()
+    assert st["restarts"] == 1 and st["redone"] > 1000
+    # the same through the one-batch entry point, which always checks
+    s = O.start_vertex(ds)
+    order = O.insertion_order(n, s, 3)
+    bounds = O.schedule(n - 1, n // 50).astype(int)
+    r = len(bounds) - 3
+    before, _ = O.build(ds, 16, 32, 1.2, seed=3, max_rounds=r, threads=0)
+    after, _ = O.build(ds, 16, 32, 1.2, seed=3, max_rounds=r + 1, threads=0)
+    g3 = A.ann_build(pts, 16, 32, 1.2, seed=3, visited_cap=8, spill_cap=1, max_rounds=r)
+    assert (g3.neighbors() == before).all()
+    A.ann_insert_batch(g3, pts, order[bounds[r]:bounds[r + 1]], 32, 1.2)
+    assert (g3.neighbors() == after).all()
 
 
 def test_build_hub_segments_spill(env):
