@@ -90,6 +90,9 @@ typedef struct {
   uint64_t redone;      /* searches redone because the visited list fit nowhere  */
   uint64_t restarts;    /* builds started over in synchronised mode for that     */
   uint64_t rounds;
+  uint64_t passes;      /* searches: 8-vertex distance passes                    */
+  uint64_t survivors;   /* searches: candidates inserted into a beam             */
+  uint64_t insert_hops; /* searches: hops that inserted at least one candidate   */
   double ms_search, ms_prune, ms_sort, ms_merge, ms_total; /* device time per phase */
 } ann_stats;
 

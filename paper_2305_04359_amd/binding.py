@@ -45,7 +45,8 @@ class GraphInfo(C.Structure):
 
 class Stats(C.Structure):
     _fields_ = [(k, C.c_uint64) for k in ("searches", "hops", "evals", "prunes", "reprunes", "appends",
-                                           "edges", "prune_evals", "redone", "restarts", "rounds")] + \
+                                           "edges", "prune_evals", "redone", "restarts", "rounds", "passes", "survivors",
+                                           "insert_hops")] + \
                [(k, C.c_double) for k in ("ms_search", "ms_prune", "ms_sort", "ms_merge", "ms_total")]
 
     def as_dict(self):

@@ -21,6 +21,7 @@ struct DistCfg {
 // Device-side counters (all commutative integer sums).
 struct DevCounters {
   unsigned long long searches, hops, evals, prunes, reprunes, appends, edges, prune_evals;
+  unsigned long long passes, survivors, insert_hops;  // search kernel: 8-vertex distance passes, beam insertions, hops with an insertion
 };
 
 struct SearchArgs {

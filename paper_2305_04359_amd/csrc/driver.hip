@@ -508,6 +508,9 @@ int ann_get_stats(const ann_graph* g, ann_stats* stats) {
   stats->appends = c.appends;
   stats->edges = c.edges;
   stats->prune_evals = c.prune_evals;
+  stats->passes = c.passes;
+  stats->survivors = c.survivors;
+  stats->insert_hops = c.insert_hops;
   return ANN_OK;
 }
 

@@ -16,18 +16,24 @@
 
 namespace annmi {
 
-// a bijection of the low `bits` bits (odd multiplier, xor-shift, odd multiplier)
+// a bijection of the low `bits` <= 24 bits: multiplication by an odd constant modulo 2^bits
+// (its top bits, which choose the bucket, depend on all bits of x)
 __device__ __forceinline__ u32 mix_id(u32 x, u32 mask, u32 bits) {
-  u32 y = (x * 0x9E3779B1u) & mask;
-  y ^= y >> ((bits + 1u) >> 1);
-  return (y * 0x85EBCA6Bu) & mask;
+  (void)bits;
+  return __umul24(x, 0x9E3779u) & mask;
+}
+
+typedef unsigned short us2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u32 pk_min_u16(u32 a, u32 b) {
+  return __builtin_bit_cast(u32, __builtin_elementwise_min(__builtin_bit_cast(us2_t, a), __builtin_bit_cast(us2_t, b)));
 }
 
 template <int KIND, int VEC, int NCH, int NSLOT>
 __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
   extern __shared__ __align__(16) unsigned char smem[];
   u64* beam = reinterpret_cast<u64*>(smem);
-  u32* cid = reinterpret_cast<u32*>(beam + NSLOT * 64);
+  u64* skeys = beam + NSLOT * 64;  // survivors of one batch of candidates
+  u32* cid = reinterpret_cast<u32*>(skeys + 64);
   u32* hash = cid + 64;  // 16-byte aligned: the beam and cid are multiples of 16 bytes
 
   const int lane = threadIdx.x;
@@ -55,7 +61,10 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
     const u32 st = a.start;
     u32 dk = eval_up_to_64<KIND, VEC, NCH>(T, Q, [st](u32) { return st; }, 1u, lane);
     dk = readlane_u32(dk, 0);
-    if (lane == 0) A[0] = make_key(dk, st);
+    if (lane == 0) {
+      A[0] = make_key(dk, st);
+      beam[0] = A[0];  // the LDS copy of the beam is kept current (processed flags aside)
+    }
   }
   __syncthreads();
   if (lane == 0) {
@@ -68,6 +77,7 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
   }
 
   u32 size = 1, nv = 0, evals = 1;
+  u32 n_pass = 0, n_surv = 0, n_ins = 0;  // statistics only
   // where the visited list goes: the search's own slot, later perhaps a spill chunk
   u64* vptr = a.vis != nullptr ? a.vis + (u64)qi * a.vis_cap : nullptr;
   u32 vcap = a.vis_cap;
@@ -132,10 +142,8 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
           const u32 tt = tag | (tag << 16);
           const uint4 e = bucket[h];
           // some 16-bit half equal to the tag?  (halves of e ^ tt that are zero)
-          const u32 z0 = e.x ^ tt, z1 = e.y ^ tt, z2 = e.z ^ tt, z3 = e.w ^ tt;
-          const u32 hz = ((z0 - 0x00010001u) & ~z0) | ((z1 - 0x00010001u) & ~z1) | ((z2 - 0x00010001u) & ~z2) |
-                         ((z3 - 0x00010001u) & ~z3);
-          if (hz & 0x80008000u)
+          const u32 mz = pk_min_u16(pk_min_u16(e.x ^ tt, e.y ^ tt), pk_min_u16(e.z ^ tt, e.w ^ tt));
+          if ((mz & 0xFFFFu) == 0u || (mz >> 16) == 0u)
             fresh = false;
           else  // shift the bucket by one tag, newest in front
             bucket[h] = make_uint4((e.x << 16) | tag, (e.y << 16) | (e.x >> 16), (e.z << 16) | (e.y >> 16),
@@ -162,6 +170,7 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
         u64 mykey = c < m ? make_key(dk, cid[c]) : KEY_INF;
         __syncthreads();
         evals += m;
+        n_pass += (m + 7u) >> 3;
 
         u64 worst = KEY_INF;
         if (size == L) {
@@ -172,31 +181,62 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
         bool surv = mykey < worst;
         u64 sm = ballot(surv);
         if (sm) {
-          // rank of each survivor among the beam entries; a survivor that is already in the beam
-          // (the filter lost it) sits exactly at its rank there and is dropped
-          u32 myrA = 0;
-          for (u64 it = sm; it; it &= it - 1) {
-            const int l = __builtin_ctzll(it);
-            const u64 sk = readlane_u64(mykey, l);
-            u32 rA = 0;
+          u32 myrA = 0, myrB = 0, ns = 0;
+          u32 shift[NSLOT];
 #pragma unroll
-            for (int s = 0; s < NSLOT; ++s) rA += __builtin_popcountll(ballot(A[s] < sk));
-            u64 at = KEY_INF;
+          for (int s = 0; s < NSLOT; ++s) shift[s] = 0;
+          if (__builtin_popcountll(sm) >= 4) {
+            // many survivors: each finds its rank among the beam entries by bisection in the LDS
+            // copy of the beam; a survivor that is already in the beam (the filter lost it) sits
+            // exactly at its rank there and is dropped
+            constexpr int STEPS = (NSLOT == 1 ? 7 : NSLOT == 2 ? 8 : NSLOT == 4 ? 9 : 10);
+            const u64 sk1 = mykey | 1ull;
+            u32 lo = 0, hi = size;
 #pragma unroll
-            for (int s = 0; s < NSLOT; ++s)
-              if ((int)(rA >> 6) == s) at = readlane_u64(A[s], (int)(rA & 63));
-            const bool dup = (at | 1ull) == (sk | 1ull);
-            if (lane == l) {
-              myrA = rA;
-              if (dup) surv = false;
+            for (int it = 0; it < STEPS; ++it) {
+              const u32 mid = (lo + hi) >> 1;
+              const bool open = lo < hi;
+              const u64 v = beam[open ? mid : 0u] | 1ull;
+              if (open) {
+                if (v < sk1)
+                  lo = mid + 1;
+                else
+                  hi = mid;
+              }
             }
-          }
-          sm = ballot(surv);
-          if (sm) {
-            u32 shift[NSLOT];
+            myrA = lo;
+            if (surv && lo < size && (beam[lo] | 1ull) == sk1) surv = false;
+            sm = ballot(surv);
+            ns = (u32)__builtin_popcountll(sm);
+            if (surv) skeys[__builtin_popcountll(sm & lanemask_lt(lane))] = mykey;
+            __syncthreads();
+            // ranks among the survivors, and how far each beam entry moves
+            for (u32 j = 0; j < ns; ++j) {
+              const u64 sj = skeys[j];
+              myrB += (surv && sj < mykey) ? 1u : 0u;
 #pragma unroll
-            for (int s = 0; s < NSLOT; ++s) shift[s] = 0;
-            u32 myrB = 0, ns = 0;
+              for (int s = 0; s < NSLOT; ++s) shift[s] += (sj < A[s]) ? 1u : 0u;
+            }
+            __syncthreads();
+          } else {
+            // few survivors: one at a time, ranks from wave-wide compares
+            for (u64 it = sm; it; it &= it - 1) {
+              const int l = __builtin_ctzll(it);
+              const u64 sk = readlane_u64(mykey, l);
+              u32 rA = 0;
+#pragma unroll
+              for (int s = 0; s < NSLOT; ++s) rA += __builtin_popcountll(ballot(A[s] < sk));
+              u64 at = KEY_INF;
+#pragma unroll
+              for (int s = 0; s < NSLOT; ++s)
+                if ((int)(rA >> 6) == s) at = readlane_u64(A[s], (int)(rA & 63));
+              const bool dup = (at | 1ull) == (sk | 1ull);
+              if (lane == l) {
+                myrA = rA;
+                if (dup) surv = false;
+              }
+            }
+            sm = ballot(surv);
             for (u64 it = sm; it; it &= it - 1) {
               const int l = __builtin_ctzll(it);
               const u64 sk = readlane_u64(mykey, l);
@@ -206,6 +246,8 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
               if (lane == l) myrB = rB;
               ++ns;
             }
+          }
+          if (sm) {
 #pragma unroll
             for (int s = 0; s < NSLOT; ++s) {
               const u32 np = (u32)(s * 64 + lane) + shift[s];
@@ -215,6 +257,8 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
               const u32 np = myrA + myrB;
               if (np < L) beam[np] = mykey;
             }
+            n_surv += ns;
+            ++n_ins;
             size = size + ns < L ? size + ns : L;
             __syncthreads();
 #pragma unroll
@@ -250,6 +294,9 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
     atomicAdd(&a.counters->searches, 1ull);
     atomicAdd(&a.counters->hops, (unsigned long long)nv);
     atomicAdd(&a.counters->evals, (unsigned long long)evals);
+    atomicAdd(&a.counters->passes, (unsigned long long)n_pass);
+    atomicAdd(&a.counters->survivors, (unsigned long long)n_surv);
+    atomicAdd(&a.counters->insert_hops, (unsigned long long)n_ins);
   }
 }
 
@@ -264,7 +311,7 @@ u32 default_hash_bits(u32 L) {
 static u32 nslot_for(u32 L) { return L <= 64 ? 1 : (L <= 128 ? 2 : (L <= 256 ? 4 : 8)); }
 
 u32 search_lds_bytes(u32 L, u32 hash_bits) {
-  return nslot_for(L) * 64 * 8 + 64 * 4 + (1u << hash_bits) * 4;
+  return nslot_for(L) * 64 * 8 + 64 * 8 + 64 * 4 + (1u << hash_bits) * 4;
 }
 
 template <int KIND, int VEC, int NCH>
@@ -284,7 +331,7 @@ u32 compact_id_bits(u64 n, u32 hash_bits) {
   u32 bits = 1;
   while ((1ull << bits) < n) ++bits;  // ids < n <= 2^bits
   if (bits < hash_bits) bits = hash_bits;
-  return bits - (hash_bits - 2u) <= 15u ? bits : 0u;
+  return (bits <= 24u && bits - (hash_bits - 2u) <= 15u) ? bits : 0u;
 }
 
 hipError_t launch_search(const DistCfg& cfg, const SearchArgs& a, hipStream_t s) {
