@@ -5,7 +5,9 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
+#include <ctime>
 #include <new>
 #include <string>
 #include <vector>
@@ -608,6 +610,13 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
   if (opts) o = *opts;
   hipStream_t st = static_cast<hipStream_t>(stream);
 
+  const bool trace = getenv("ANN_TRACE_BUILD") != nullptr;  // wall-clock breakdown on stderr
+  auto now_ms = [] {
+    timespec ts;
+    clock_gettime(CLOCK_MONOTONIC, &ts);
+    return ts.tv_sec * 1e3 + ts.tv_nsec / 1e6;
+  };
+  const double t_begin = now_ms();
   ann_graph* g = nullptr;
   int rc = new_graph(n, d, dtype, metric, R, &g);
   if (rc) return rc;
@@ -636,6 +645,7 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
     g->start = s;
   }
 
+  const double t_start = now_ms();
   // insertion order: the ids other than s, shuffled (Fisher-Yates driven by SplitMix64)
   const u64 m = n - 1;
   std::vector<u32> order(m ? m : 1);
@@ -661,6 +671,7 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
     }
   }
 
+  const double t_order = now_ms();
   // batches of 2, 4, 8, ... points, never more than theta
   u64 theta = o.batch_cap ? o.batch_cap : (n / 50 > 1 ? n / 50 : 1);
   if (theta * R >= (1ull << 32)) theta = ((1ull << 32) - 1) / R;
@@ -686,6 +697,7 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
   rc = tm.init(g->collect);
   if (rc) return rc;
 
+  const double t_alloc = now_ms();
   // First try: every batch is issued without waiting for the previous one.  A search whose
   // visited list fits neither its slot nor a spill chunk spoils that attempt (it is detected at
   // the end); the build is then repeated from the empty graph with a host check after step 1 of
@@ -713,6 +725,9 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
     g->rounds = 0;
   }
   if (rc) return rc;
+  if (trace)
+    fprintf(stderr, "ann_build: graph alloc + start vertex %.2f ms, order %.2f ms, scratch %.2f ms, batches %.2f ms\n",
+            t_start - t_begin, t_order - t_start, t_alloc - t_order, now_ms() - t_alloc);
   guard.g = nullptr;
   *out = g;
   return ANN_OK;

@@ -615,7 +615,7 @@ __global__ __launch_bounds__(64) void merge_generic_kernel(MergeArgs a, VecTable
   unsigned char* blk = smem + ((a.R * 8u + 15u) & ~15u);  // 8 rows + 8 norms
   st.vec = a.stage_bytes ? blk + 8u * st.stride + 32u : nullptr;
   constexpr bool kMfma = MfmaPruneOk<KIND, VEC, NCH>::value;
-  const MfmaLds M = mfma_lds_carve(smem + ((a.R * 4u + 15u) & ~15u), a.R);  // used when a.use_mfma
+  const MfmaLds M = mfma_lds_carve(smem + ((a.R * 4u + 15u) & ~15u), a.R, T.row_bytes);  // used when a.use_mfma
 
   const int lane = threadIdx.x;
   const u32 nitems = a.list_count[2];
@@ -709,7 +709,7 @@ static hipError_t launch_merge_t(const MergeArgs& a, const VecTable& T, u32 grid
                                  hipStream_t s_generic) {
   hipLaunchKernelGGL((merge_fast_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), 0, s, a, T);
   if (a.gram_ok) hipLaunchKernelGGL((merge_gram_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), 0, s_gram, a, T);
-  const u32 lds = a.use_mfma ? ((a.R * 4u + 15u) & ~15u) + mfma_lds_bytes(a.R)
+  const u32 lds = a.use_mfma ? ((a.R * 4u + 15u) & ~15u) + mfma_lds_bytes(a.R, T.row_bytes)
                             : ((a.R * 8u + 15u) & ~15u) + 8u * stage_stride(T.row_bytes) + 32u + a.stage_bytes;
   hipLaunchKernelGGL((merge_generic_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), lds, s_generic, a, T);
   return hipGetLastError();
@@ -725,7 +725,7 @@ hipError_t launch_merge(const DistCfg& cfg, const MergeArgs& a, u32 grid, hipStr
 bool gram_path_ok(const DistCfg& cfg) { return cfg.kind <= 1 && 8 * cfg.nch * cfg.vec <= 128; }
 u32 gram_path_tmax() { return SM_TMAX; }
 bool mfma_prune_ok(u32 R, const DistCfg& cfg) {
-  return cfg.kind <= 1 && 8 * cfg.nch * cfg.vec <= 128 && mfma_lds_bytes(R) <= 24576u;
+  return cfg.kind <= 1 && 8 * cfg.nch * cfg.vec <= 128 && mfma_lds_bytes(R, (u32)cfg.row_bytes) <= 24576u;
 }
 u32 prune_stage_bytes(u32 R, const DistCfg& cfg) { return stage_bytes(R, (u32)cfg.row_bytes, STAGE_BUDGET); }
 u32 fast_path_amax(const DistCfg& cfg) { return cfg.nch <= 2 ? 4u : (cfg.nch <= 4 ? 2u : 1u); }

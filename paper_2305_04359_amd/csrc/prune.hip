@@ -22,7 +22,7 @@ __global__ __launch_bounds__(64) void prune_kernel(PruneArgs a, VecTable T) {
   unsigned char* blk = smem + ((a.R * 8u + 15u) & ~15u);  // 8 rows + 8 norms
   st.vec = a.stage_bytes ? blk + 8u * st.stride + 32u : nullptr;
   constexpr bool kMfma = MfmaPruneOk<KIND, VEC, NCH>::value;
-  const MfmaLds M = mfma_lds_carve(smem + ((a.R * 4u + 15u) & ~15u), a.R);  // used when a.use_mfma
+  const MfmaLds M = mfma_lds_carve(smem + ((a.R * 4u + 15u) & ~15u), a.R, T.row_bytes);  // used when a.use_mfma
 
   const int lane = threadIdx.x;
   const u32 qi = blockIdx.x;
@@ -88,7 +88,7 @@ __global__ __launch_bounds__(64) void prune_kernel(PruneArgs a, VecTable T) {
 
 template <int KIND, int VEC, int NCH>
 static hipError_t launch_prune_t(const PruneArgs& a, const VecTable& T, hipStream_t s) {
-  const u32 lds = a.use_mfma ? ((a.R * 4u + 15u) & ~15u) + mfma_lds_bytes(a.R)
+  const u32 lds = a.use_mfma ? ((a.R * 4u + 15u) & ~15u) + mfma_lds_bytes(a.R, T.row_bytes)
                             : ((a.R * 8u + 15u) & ~15u) + 8u * stage_stride(T.row_bytes) + 32u + a.stage_bytes;
   hipLaunchKernelGGL((prune_kernel<KIND, VEC, NCH>), dim3(a.nq), dim3(64), lds, s, a, T);
   return hipGetLastError();

@@ -350,7 +350,9 @@ __device__ __forceinline__ i32 alpha_threshold(i32 d, i64 a16) {
 
 // LDS areas of the matrix-core walk (all 16-byte aligned)
 struct MfmaLds {
-  unsigned char* sel;  // roundup(R, 32) rows of MM_STRIDE bytes: vectors of the selected points
+  unsigned char* sel;  // roundup(R, 32) rows of MM_STRIDE bytes: vectors of the selected points,
+                       // or null: rows are whole multiples of 32 bytes and the matrix operand is
+                       // loaded straight from the vectors in device memory (more waves per CU)
   u32* selnorm;        // roundup(R, 32): their squared norms (shifted vectors)
   unsigned char* blk;  // 32 rows: the current block of candidates
   u32* cnorm;          // 32
@@ -358,13 +360,16 @@ struct MfmaLds {
   u32* cid;            // 32
 };
 __host__ __device__ inline u32 mfma_rows(u32 R) { return (R + 31u) & ~31u; }
-__host__ __device__ inline u32 mfma_lds_bytes(u32 R) {
-  return mfma_rows(R) * MM_STRIDE + mfma_rows(R) * 4u + MM_BLOCK * MM_STRIDE + 3u * MM_BLOCK * 4u;
+__host__ __device__ inline bool mfma_sel_in_lds(u32 row_bytes) { return (row_bytes % 32u) != 0u; }
+__host__ __device__ inline u32 mfma_lds_bytes(u32 R, u32 row_bytes) {
+  return (mfma_sel_in_lds(row_bytes) ? mfma_rows(R) * MM_STRIDE : 0u) + mfma_rows(R) * 4u + MM_BLOCK * MM_STRIDE +
+         3u * MM_BLOCK * 4u;
 }
-__device__ __forceinline__ MfmaLds mfma_lds_carve(unsigned char* base, u32 R) {
+__device__ __forceinline__ MfmaLds mfma_lds_carve(unsigned char* base, u32 R, u32 row_bytes) {
   MfmaLds M;
-  M.sel = base;
-  M.blk = M.sel + mfma_rows(R) * MM_STRIDE;
+  const bool in_lds = mfma_sel_in_lds(row_bytes);
+  M.sel = in_lds ? base : nullptr;
+  M.blk = base + (in_lds ? mfma_rows(R) * MM_STRIDE : 0u);
   M.selnorm = reinterpret_cast<u32*>(M.blk + MM_BLOCK * MM_STRIDE);
   M.cnorm = M.selnorm + mfma_rows(R);
   M.cthr = reinterpret_cast<i32*>(M.cnorm + MM_BLOCK);
@@ -463,7 +468,14 @@ __device__ __forceinline__ u32 prune_sorted_mfma(const VecTable& T, const MfmaLd
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
         if ((u32)ks < ksteps) {
-          const v4i_t av = *reinterpret_cast<const v4i_t*>(M.sel + (s0 + col) * MM_STRIDE + 32u * ks + 16u * half);
+          v4i_t av;
+          if (M.sel != nullptr) {
+            av = *reinterpret_cast<const v4i_t*>(M.sel + (s0 + col) * MM_STRIDE + 32u * ks + 16u * half);
+          } else {
+            const u32 sid = s0 + col < nout ? out[s0 + col] : out[0];
+            av = *reinterpret_cast<const v4i_t*>(T.base + (u64)sid * T.row_bytes + 32u * ks + 16u * half);
+            av ^= (int)flip;
+          }
           acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(av, bv[ks], acc, 0, 0, 0);
         }
       }
@@ -513,7 +525,7 @@ __device__ __forceinline__ u32 prune_sorted_mfma(const VecTable& T, const MfmaLd
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
       const u32 t = 8u * p + grp;
-      if ((selmask >> t) & 1u) {
+      if (M.sel != nullptr && ((selmask >> t) & 1u)) {
         const u32 slot = nout + (u32)__builtin_popcount(selmask & ((1u << t) - 1u));
         *reinterpret_cast<uint4*>(M.sel + slot * MM_STRIDE + 16u * sub) =
             *reinterpret_cast<const uint4*>(M.blk + t * MM_STRIDE + 16u * sub);

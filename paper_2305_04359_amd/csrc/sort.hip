@@ -5,13 +5,15 @@
 //
 // One wavefront owns a tile of consecutive keys and walks it 64 keys at a time, so ranking inside
 // a tile needs no cross-wave coordination: a key's rank among equal digits of its 64-key row is
-// a popcount over a match mask built from one ballot per digit bit.
+// a popcount over a match mask built from one ballot per digit bit.  Digits are up to 10 bits
+// wide, so 20 destination bits (a million points) take two passes.
 #include "ann_device.hpp"
 #include "ann_internal.hpp"
 
 namespace annmi {
 
-constexpr u32 RS_RADIX = 256;
+constexpr u32 RS_DIGIT_BITS = 10;  // at most this many key bits per pass
+constexpr u32 RS_RADIX = 1u << RS_DIGIT_BITS;
 
 static u64 rs_tile_keys(u64 count) {
   // at least 1024 keys per tile, at most 8192 tiles
@@ -21,6 +23,7 @@ static u64 rs_tile_keys(u64 count) {
 }
 static u64 rs_tiles(u64 count) { return (count + rs_tile_keys(count) - 1) / rs_tile_keys(count); }
 
+// RS_RADIX x tiles counters and RS_RADIX digit totals
 u64 radix_hist_entries(u64 count) { return RS_RADIX * ((rs_tiles(count) ? rs_tiles(count) : 1) + 1); }
 
 __global__ __launch_bounds__(64) void rs_hist_kernel(const u64* keys, u64 count, u64 tile_keys, u32 tiles,
@@ -68,18 +71,30 @@ __global__ __launch_bounds__(256) void rs_rowscan_kernel(u32* hist, u32 tiles, u
 }
 
 // ... and one workgroup turns the RS_RADIX totals into the first output index of each digit.
+// (A "last workgroup does it" ticket inside the row scan was tried: RS_RADIX atomics on one
+// address cost more than this extra launch.)
 __global__ __launch_bounds__(256) void rs_digitscan_kernel(u32* digit_total) {
   __shared__ u32 part[256];
   const u32 t = threadIdx.x;
-  part[t] = digit_total[t];
+  constexpr u32 PT = RS_RADIX / 256;
+  u32 v[PT], sum = 0;
+  for (u32 k = 0; k < PT; ++k) {
+    v[k] = digit_total[t * PT + k];
+    sum += v[k];
+  }
+  part[t] = sum;
   __syncthreads();
   for (u32 off = 1; off < 256; off <<= 1) {
-    const u32 v = t >= off ? part[t - off] : 0u;
+    const u32 w = t >= off ? part[t - off] : 0u;
     __syncthreads();
-    part[t] += v;
+    part[t] += w;
     __syncthreads();
   }
-  digit_total[t] = t ? part[t - 1] : 0u;
+  u32 base = t ? part[t - 1] : 0u;
+  for (u32 k = 0; k < PT; ++k) {
+    digit_total[t * PT + k] = base;
+    base += v[k];
+  }
 }
 
 __global__ __launch_bounds__(64) void rs_scatter_kernel(const u64* keys, u64* out, u64 count, u64 tile_keys,
@@ -118,7 +133,7 @@ hipError_t radix_sort_edges(u64* keys, u64* tmp, u32* hist, u64 count, u32 key_b
   if (key_bits > 32) key_bits = 32;
   const u64 tile_keys = rs_tile_keys(count);
   const u32 tiles = (u32)rs_tiles(count);
-  const u32 npass = (key_bits + 7) / 8;
+  const u32 npass = (key_bits + RS_DIGIT_BITS - 1) / RS_DIGIT_BITS;
   const u32 per = (key_bits + npass - 1) / npass;
   u64* src = keys;
   u64* dst = tmp;

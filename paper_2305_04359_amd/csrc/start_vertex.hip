@@ -79,6 +79,44 @@ __device__ __forceinline__ u64 point_score(const T* row, u32 d, u64 n, const typ
   }
 }
 
+// Byte vectors with d % 4 == 0: eight lanes per point, each taking every eighth 4-byte word of
+// the row (coalesced reads), the exact 64-bit partial scores summed across the eight lanes.
+template <typename T>
+__global__ __launch_bounds__(256) void score8_kernel(const T* x, u64 n, u32 d, const long long* colsum,
+                                                     unsigned long long* best, u32* best_id, int pass) {
+  extern __shared__ long long cs[];  // column sums
+  for (u32 j = threadIdx.x; j < d; j += blockDim.x) cs[j] = colsum[j];
+  __syncthreads();
+  const u64 i = ((u64)blockIdx.x * blockDim.x + threadIdx.x) >> 3;
+  const u32 sub = threadIdx.x & 7u;
+  long long nn = 0, xs = 0;
+  if (i < n) {
+    const u32* row = reinterpret_cast<const u32*>(x + i * d);
+    for (u32 wd = sub; wd < d / 4; wd += 8) {
+      const u32 v4 = row[wd];
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const long long v = sizeof(T) == 1 && T(-1) < T(0) ? (long long)(signed char)(v4 >> (8 * b))
+                                                           : (long long)((v4 >> (8 * b)) & 0xFFu);
+        nn += v * v;
+        xs += v * cs[4 * wd + b];
+      }
+    }
+  }
+#pragma unroll
+  for (int off = 1; off < 8; off <<= 1) {
+    nn += __shfl_xor(nn, off, 64);
+    xs += __shfl_xor(xs, off, 64);
+  }
+  if (i < n && sub == 0) {
+    const u64 sc = score_bits((long long)n * nn - 2 * xs);
+    if (pass == 0)
+      atomicMin(best, (unsigned long long)sc);
+    else if (sc == *best)
+      atomicMin(best_id, (u32)i);
+  }
+}
+
 // pass 0: best score; pass 1: smallest id that attains it
 template <typename T>
 __global__ __launch_bounds__(256) void score_kernel(const T* x, u64 n, u32 d, const typename SumType<T>::type* colsum,
@@ -112,9 +150,23 @@ static hipError_t start_vertex_t(const T* x, u64 n, u32 d, hipStream_t s, u32* s
   hipLaunchKernelGGL((colsum_partial_kernel<T>), dim3(nblocks), dim3(256), 0, s, x, n, d, rpb, partial);
   hipLaunchKernelGGL((colsum_final_kernel<S>), dim3((d + 63) / 64), dim3(64), 0, s, partial, nblocks, d, colsum);
   (void)hipMemsetAsync(best, 0xFF, 12, s);
-  const u32 grid = (u32)((n + 255) / 256);
-  hipLaunchKernelGGL((score_kernel<T>), dim3(grid), dim3(256), 0, s, x, n, d, colsum, best, best_id, 0);
-  hipLaunchKernelGGL((score_kernel<T>), dim3(grid), dim3(256), 0, s, x, n, d, colsum, best, best_id, 1);
+  if constexpr (sizeof(T) == 1) {
+    if (d % 4 == 0 && d <= 4096) {
+      const u32 grid8 = (u32)((n * 8 + 255) / 256);
+      hipLaunchKernelGGL((score8_kernel<T>), dim3(grid8), dim3(256), d * sizeof(long long), s, x, n, d, colsum, best,
+                         best_id, 0);
+      hipLaunchKernelGGL((score8_kernel<T>), dim3(grid8), dim3(256), d * sizeof(long long), s, x, n, d, colsum, best,
+                         best_id, 1);
+    } else {
+      const u32 grid = (u32)((n + 255) / 256);
+      hipLaunchKernelGGL((score_kernel<T>), dim3(grid), dim3(256), 0, s, x, n, d, colsum, best, best_id, 0);
+      hipLaunchKernelGGL((score_kernel<T>), dim3(grid), dim3(256), 0, s, x, n, d, colsum, best, best_id, 1);
+    }
+  } else {
+    const u32 grid = (u32)((n + 255) / 256);
+    hipLaunchKernelGGL((score_kernel<T>), dim3(grid), dim3(256), 0, s, x, n, d, colsum, best, best_id, 0);
+    hipLaunchKernelGGL((score_kernel<T>), dim3(grid), dim3(256), 0, s, x, n, d, colsum, best, best_id, 1);
+  }
   e = hipGetLastError();
   if (e == hipSuccess) e = hipMemcpyAsync(start_out, best_id, sizeof(u32), hipMemcpyDeviceToHost, s);
   if (e == hipSuccess) e = hipStreamSynchronize(s);
