@@ -64,10 +64,18 @@ __device__ __forceinline__ u64 readlane_u64(u64 v, int lane) {
   return ((u64)hi << 32) | lo;
 }
 
-// `old` with lane LANE replaced by the wave-uniform value `sval`
-template <int LANE>
-__device__ __forceinline__ u32 writelane_u32(u32 old, u32 sval) {
-  asm("v_writelane_b32 %0, %1, %2" : "+v"(old) : "s"(sval), "n"(LANE));
+// `old` with lanes LO and HI replaced by the low and high half of the wave-uniform mask `m`.
+// The scalar operands usually come straight from a vector compare, and a scalar register written
+// by a vector instruction must not be read by a vector instruction in the next few issue slots.
+// The compiler pads its own instructions for that, but not the text of an asm statement (with
+// the write directly behind the compare the lanes were seen to keep their old value), so the
+// wait states are part of the statement.
+template <int LO, int HI>
+__device__ __forceinline__ u32 writelane_pair(u32 old, u64 m) {
+  const u32 lo = (u32)m, hi = (u32)(m >> 32);
+  asm("s_nop 3\n\tv_writelane_b32 %0, %1, %3\n\tv_writelane_b32 %0, %2, %4"
+      : "+v"(old)
+      : "s"(lo), "s"(hi), "n"(LO), "n"(HI));
   return old;
 }
 

@@ -335,18 +335,24 @@ __global__ __launch_bounds__(64) void merge_fast_kernel(MergeArgs a, VecTable T)
     const u32 na = stale + cnt;     // 1 <= na <= AMAX
     u32* row = a.graph + (u64)b * a.R;
     u32 kept = 0;
-    switch (na) {  // uniform
-      case 1: kept = fast_item<KIND, VEC, NCH, 1>(a, T, al, ids_lds, dk_lds, b, i0, clean, stale, row, a.R, lane); break;
-      case 2:
-        if constexpr (AMAX >= 2) kept = fast_item<KIND, VEC, NCH, 2>(a, T, al, ids_lds, dk_lds, b, i0, clean, stale, row, a.R, lane);
-        break;
-      case 3:
-        if constexpr (AMAX >= 4) kept = fast_item<KIND, VEC, NCH, 3>(a, T, al, ids_lds, dk_lds, b, i0, clean, stale, row, a.R, lane);
-        break;
-      default:
-        if constexpr (AMAX >= 4) kept = fast_item<KIND, VEC, NCH, 4>(a, T, al, ids_lds, dk_lds, b, i0, clean, stale, row, a.R, lane);
-        break;
+    // uniform dispatch on the number of new entries
+#define ANN_FAST_CASE(N)                                                                                     \
+  case N:                                                                                                    \
+    if constexpr (AMAX >= N)                                                                                 \
+      kept = fast_item<KIND, VEC, NCH, N>(a, T, al, ids_lds, dk_lds, b, i0, clean, stale, row, a.R, lane);   \
+    break;
+    switch (na) {
+      ANN_FAST_CASE(1)
+      ANN_FAST_CASE(2)
+      ANN_FAST_CASE(3)
+      ANN_FAST_CASE(4)
+      ANN_FAST_CASE(5)
+      ANN_FAST_CASE(6)
+      ANN_FAST_CASE(7)
+      ANN_FAST_CASE(8)
+      default: break;
     }
+#undef ANN_FAST_CASE
     (void)kept;
     ++n_rep;
     n_edges += cnt;
@@ -400,13 +406,10 @@ __device__ __forceinline__ void gram_tile_reg(const v16i_t& acc, const SmallLds&
   const i32 nrow = (i32)S.snrm[mlo + 4 * half];
   const i32 D = nrow + ncol - 2 * acc[R_];
   const u64 bm = ballot(colok && D <= tcol);
-  const u32 lo = (u32)bm, hi = (u32)(bm >> 32);
   if constexpr (mlo < 64) {
-    Klo = writelane_u32<mlo>(Klo, lo);
-    Klo = writelane_u32<mlo + 4>(Klo, hi);
+    Klo = writelane_pair<mlo, mlo + 4>(Klo, bm);
   } else if constexpr (CB == 2) {
-    Khi = writelane_u32<mlo - 64>(Khi, lo);
-    Khi = writelane_u32<mlo + 4 - 64>(Khi, hi);
+    Khi = writelane_pair<mlo - 64, mlo + 4 - 64>(Khi, bm);
   }
 }
 
@@ -426,11 +429,18 @@ __device__ __forceinline__ void gram_tile(const unsigned char* Xs, const SmallLd
   const unsigned char* pa = Xs + ra * SM_STRIDE + 16u * half;
   const unsigned char* pb = Xs + rb * SM_STRIDE + 16u * half;
   v16i_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-  for (u32 ks = 0; ks < ksteps; ++ks) {
-    const v4i_t av = *reinterpret_cast<const v4i_t*>(pa + 32u * ks);
-    const v4i_t bv = *reinterpret_cast<const v4i_t*>(pb + 32u * ks);
-    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(av, bv, acc, 0, 0, 0);
+  // all four k-steps unconditionally: operands beyond the row's last step are zeroed
+  v4i_t av[4], bv[4];
+#pragma unroll
+  for (u32 ks = 0; ks < 4; ++ks) {
+    const u32 kk = ks < ksteps ? ks : ksteps - 1u;
+    const v4i_t x = *reinterpret_cast<const v4i_t*>(pa + 32u * kk);
+    const v4i_t y = *reinterpret_cast<const v4i_t*>(pb + 32u * kk);
+    av[ks] = ks < ksteps ? x : v4i_t{0, 0, 0, 0};
+    bv[ks] = y;
   }
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(av[ks], bv[ks], acc, 0, 0, 0);
   const bool colok = ib < total;
   const i32 ncol = colok ? (i32)S.snrm[ib] : 0;
   const i32 tcol = colok ? S.sthr[ib] : -1;

@@ -384,8 +384,7 @@ __device__ __forceinline__ void mm_block_rows(const v16i_t& acc, const uint4 (&n
   const u32 nrow = (R_ % 4) == 0 ? n4[R_ / 4].x : (R_ % 4) == 1 ? n4[R_ / 4].y : (R_ % 4) == 2 ? n4[R_ / 4].z : n4[R_ / 4].w;
   const i32 D = (i32)nrow + ncol - 2 * acc[R_];
   const u64 bm = ballot(D <= tcol);
-  by = writelane_u32<mlo>(by, (u32)bm);
-  by = writelane_u32<mlo + 4>(by, (u32)(bm >> 32));
+  by = writelane_pair<mlo, mlo + 4>(by, bm);
 }
 template <int... Rs>
 __device__ __forceinline__ void mm_block_rows_all(const v16i_t& acc, const uint4 (&n4)[4], i32 ncol, i32 tcol, u32& by,
@@ -455,30 +454,46 @@ __device__ __forceinline__ u32 prune_sorted_mfma(const VecTable& T, const MfmaLd
     // column operand: candidate `col`, this lane's 16 bytes of every k-step
     v4i_t bv[4];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-      bv[ks] = (u32)ks < ksteps ? *reinterpret_cast<const v4i_t*>(M.blk + col * MM_STRIDE + 32u * ks + 16u * half)
-                                : v4i_t{0, 0, 0, 0};
+    for (u32 ks = 0; ks < 4; ++ks) {
+      const v4i_t v =
+          *reinterpret_cast<const v4i_t*>(M.blk + col * MM_STRIDE + 32u * (ks < ksteps ? ks : ksteps - 1u) + 16u * half);
+      bv[ks] = ks < ksteps ? v : v4i_t{0, 0, 0, 0};
+    }
     const i32 ncol = (i32)M.cnorm[col];
     const i32 tcol = M.cthr[col];
 
-    // removed by a point selected before this block?
+    // removed by a point selected before this block?  The row operand of each 32-point slice is
+    // requested in one go, and the next slice's before this one's products are taken, so that a
+    // block costs one trip to memory rather than one per instruction.
     bool rem = false;
-    for (u32 s0 = 0; s0 < nout; s0 += 32) {
-      v16i_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    const u32 kclamp = ksteps - 1u;
+    const u32 aflip = M.sel != nullptr ? 0u : flip;
+    auto load_slice = [&](u32 s0, v4i_t (&av)[4]) {
+      if (M.sel != nullptr) {
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        if ((u32)ks < ksteps) {
-          v4i_t av;
-          if (M.sel != nullptr) {
-            av = *reinterpret_cast<const v4i_t*>(M.sel + (s0 + col) * MM_STRIDE + 32u * ks + 16u * half);
-          } else {
-            const u32 sid = s0 + col < nout ? out[s0 + col] : out[0];
-            av = *reinterpret_cast<const v4i_t*>(T.base + (u64)sid * T.row_bytes + 32u * ks + 16u * half);
-            av ^= (int)flip;
-          }
-          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(av, bv[ks], acc, 0, 0, 0);
+        for (u32 ks = 0; ks < 4; ++ks)
+          av[ks] = *reinterpret_cast<const v4i_t*>(M.sel + (s0 + col) * MM_STRIDE + 32u * (ks < kclamp ? ks : kclamp) +
+                                                   16u * half);
+      } else {
+        const u32 sid = s0 + col < nout ? out[s0 + col] : out[0];
+        const char* src = T.base + (u64)sid * T.row_bytes + 16u * half;
+#pragma unroll
+        for (u32 ks = 0; ks < 4; ++ks) {
+          av[ks] = *reinterpret_cast<const v4i_t*>(src + 32u * (ks < kclamp ? ks : kclamp));
         }
       }
+    };
+    v4i_t av[4];
+    if (nout > 0) load_slice(0, av);
+    for (u32 s0 = 0; s0 < nout; s0 += 32) {
+      v4i_t cur[4];
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+        cur[ks] = (u32)ks < ksteps ? (av[ks] ^ (int)aflip) : v4i_t{0, 0, 0, 0};  // device memory holds u8
+      if (s0 + 32 < nout) load_slice(s0 + 32, av);
+      v16i_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur[ks], bv[ks], acc, 0, 0, 0);
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const u32 sb = s0 + 8u * q + 4u * half;
@@ -497,8 +512,7 @@ __device__ __forceinline__ u32 prune_sorted_mfma(const VecTable& T, const MfmaLd
     {
       v16i_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks)
-        if ((u32)ks < ksteps) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(bv[ks], bv[ks], acc, 0, 0, 0);
+      for (int ks = 0; ks < 4; ++ks) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(bv[ks], bv[ks], acc, 0, 0, 0);
       uint4 n4[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) n4[q] = *reinterpret_cast<const uint4*>(M.cnorm + 8u * q + 4u * half);
