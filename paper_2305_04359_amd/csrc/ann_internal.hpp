@@ -18,11 +18,18 @@ struct DistCfg {
   u64 row_bytes;  // d * sizeof(element)
 };
 
-// Device-side counters (all commutative integer sums).
-struct DevCounters {
+// Device-side counters (all commutative integer sums).  Thousands of wavefronts adding to one
+// address queue up at a single memory channel and slow every other access that goes there, so
+// there are COUNTER_COPIES copies, each on a cache line of its own; a block adds to the copy
+// picked by its index and the host adds the copies up.
+struct alignas(128) DevCounters {
   unsigned long long searches, hops, evals, prunes, reprunes, appends, edges, prune_evals;
   unsigned long long passes, survivors, insert_hops;  // search kernel: 8-vertex distance passes, beam insertions, hops with an insertion
 };
+constexpr u32 COUNTER_COPIES = 1024;
+__device__ __forceinline__ DevCounters* block_counters(DevCounters* base) {
+  return base + (blockIdx.x & (COUNTER_COPIES - 1u));
+}
 
 struct SearchArgs {
   const char* points;     // vectors of the graph's vertices

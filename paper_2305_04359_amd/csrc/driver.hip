@@ -461,8 +461,8 @@ int new_graph(u64 n, u32 d, int dtype, int metric, u32 R, ann_graph** out) {
   hipError_t e = hipMalloc(reinterpret_cast<void**>(&g->rows), (size_t)n * R * sizeof(u32));
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&g->meta), (size_t)n * sizeof(u32));
   if (e == hipSuccess) e = hipMemset(g->meta, 0, (size_t)n * sizeof(u32));
-  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&g->counters), sizeof(DevCounters));
-  if (e == hipSuccess) e = hipMemset(g->counters, 0, sizeof(DevCounters));
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&g->counters), COUNTER_COPIES * sizeof(DevCounters));
+  if (e == hipSuccess) e = hipMemset(g->counters, 0, COUNTER_COPIES * sizeof(DevCounters));
   if (e != hipSuccess) {
     ann_graph_free(g);
     return fail(e == hipErrorOutOfMemory ? ANN_ENOMEM : ANN_EHIP, "graph allocation: %s", hipGetErrorString(e));
@@ -499,8 +499,22 @@ int ann_graph_info(const ann_graph* g, ann_graph_info_t* info) {
 
 int ann_get_stats(const ann_graph* g, ann_stats* stats) {
   if (!g || !stats) return fail(ANN_EINVAL, "null argument");
+  std::vector<DevCounters> copies(COUNTER_COPIES);
+  HIP_TRY(hipMemcpy(copies.data(), g->counters, COUNTER_COPIES * sizeof(DevCounters), hipMemcpyDeviceToHost));
   DevCounters c{};
-  HIP_TRY(hipMemcpy(&c, g->counters, sizeof(c), hipMemcpyDeviceToHost));
+  for (const DevCounters& x : copies) {
+    c.searches += x.searches;
+    c.hops += x.hops;
+    c.evals += x.evals;
+    c.prunes += x.prunes;
+    c.reprunes += x.reprunes;
+    c.appends += x.appends;
+    c.edges += x.edges;
+    c.prune_evals += x.prune_evals;
+    c.passes += x.passes;
+    c.survivors += x.survivors;
+    c.insert_hops += x.insert_hops;
+  }
   *stats = g->stats;
   stats->searches = c.searches;
   stats->hops = c.hops;
@@ -716,7 +730,7 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
     // start over
     HIP_TRY(hipMemsetAsync(g->rows, 0xFF, (size_t)n * R * sizeof(u32), st));
     HIP_TRY(hipMemsetAsync(g->meta, 0, (size_t)n * sizeof(u32), st));
-    HIP_TRY(hipMemsetAsync(g->counters, 0, sizeof(DevCounters), st));
+    HIP_TRY(hipMemsetAsync(g->counters, 0, COUNTER_COPIES * sizeof(DevCounters), st));
     HIP_TRY(hipMemsetAsync(S.small.p, 0, 64, st));
     const u64 redone = g->stats.redone;
     g->stats = ann_stats{};

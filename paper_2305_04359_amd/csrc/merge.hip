@@ -91,8 +91,8 @@ __global__ __launch_bounds__(256) void plan_kernel(MergeArgs a) {
   if (threadIdx.x < 3 && cnt_lds[threadIdx.x] != 0)
     base_lds[threadIdx.x] = atomicAdd(&a.list_count[threadIdx.x], cnt_lds[threadIdx.x]);
   if (a.counters != nullptr && threadIdx.x == 0 && stat_lds[0] != 0) {
-    atomicAdd(&a.counters->appends, (unsigned long long)stat_lds[0]);
-    atomicAdd(&a.counters->edges, (unsigned long long)stat_lds[1]);
+    atomicAdd(&block_counters(a.counters)->appends, (unsigned long long)stat_lds[0]);
+    atomicAdd(&block_counters(a.counters)->edges, (unsigned long long)stat_lds[1]);
   }
   __syncthreads();
   if (kind >= 0) a.list_items[kind][base_lds[kind] + slot] = ((u64)cnt << 32) | (u32)i;
@@ -359,9 +359,9 @@ __global__ __launch_bounds__(64) void merge_fast_kernel(MergeArgs a, VecTable T)
     n_pair += (unsigned long long)(clean + na) * (na + 1);
   }
   if (a.counters != nullptr && lane == 0 && n_rep) {
-    atomicAdd(&a.counters->reprunes, n_rep);
-    atomicAdd(&a.counters->edges, n_edges);
-    atomicAdd(&a.counters->prune_evals, n_pair);
+    atomicAdd(&block_counters(a.counters)->reprunes, n_rep);
+    atomicAdd(&block_counters(a.counters)->edges, n_edges);
+    atomicAdd(&block_counters(a.counters)->prune_evals, n_pair);
   }
 }
 
@@ -604,9 +604,9 @@ __global__ __launch_bounds__(64) void merge_gram_kernel(MergeArgs a, VecTable T)
       n_pair += (unsigned long long)total * (total + 1) / 2;
     }
     if (a.counters != nullptr && lane == 0 && n_rep) {
-      atomicAdd(&a.counters->reprunes, n_rep);
-      atomicAdd(&a.counters->edges, n_edges);
-      atomicAdd(&a.counters->prune_evals, n_pair);
+      atomicAdd(&block_counters(a.counters)->reprunes, n_rep);
+      atomicAdd(&block_counters(a.counters)->edges, n_edges);
+      atomicAdd(&block_counters(a.counters)->prune_evals, n_pair);
     }
   }
 }
@@ -706,9 +706,9 @@ __global__ __launch_bounds__(64) void merge_generic_kernel(MergeArgs a, VecTable
     n_pair += pair_evals;
   }
   if (a.counters != nullptr && lane == 0 && n_rep) {
-    atomicAdd(&a.counters->reprunes, n_rep);
-    atomicAdd(&a.counters->edges, n_edges);
-    atomicAdd(&a.counters->prune_evals, n_pair);
+    atomicAdd(&block_counters(a.counters)->reprunes, n_rep);
+    atomicAdd(&block_counters(a.counters)->edges, n_edges);
+    atomicAdd(&block_counters(a.counters)->prune_evals, n_pair);
   }
 }
 

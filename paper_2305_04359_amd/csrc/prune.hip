@@ -11,7 +11,7 @@ namespace annmi {
 // step 1: N_out(p) <- prune(p, V, R) for every batch point; emit the reversed edges
 // ---------------------------------------------------------------------------------------------
 template <int KIND, int VEC, int NCH>
-__global__ __launch_bounds__(64) void prune_kernel(PruneArgs a, VecTable T) {
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(4, 4))) void prune_kernel(PruneArgs a, VecTable T) {
   __shared__ u64 cand_lds[PRUNE_LDS_CAP];
   extern __shared__ __align__(16) unsigned char smem[];
   u32* out = reinterpret_cast<u32*>(smem);  // R entries
@@ -81,8 +81,8 @@ __global__ __launch_bounds__(64) void prune_kernel(PruneArgs a, VecTable T) {
   }
   if (lane == 0) a.meta[p] = cnt | (cnt << 16);  // the whole row is the output of a prune
   if (a.counters != nullptr && lane == 0) {
-    atomicAdd(&a.counters->prunes, 1ull);
-    atomicAdd(&a.counters->prune_evals, (unsigned long long)pair_evals);
+    atomicAdd(&block_counters(a.counters)->prunes, 1ull);
+    atomicAdd(&block_counters(a.counters)->prune_evals, (unsigned long long)pair_evals);
   }
 }
 

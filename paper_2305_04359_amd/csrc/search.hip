@@ -291,12 +291,12 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
     }
   }
   if (a.counters != nullptr && lane == 0) {
-    atomicAdd(&a.counters->searches, 1ull);
-    atomicAdd(&a.counters->hops, (unsigned long long)nv);
-    atomicAdd(&a.counters->evals, (unsigned long long)evals);
-    atomicAdd(&a.counters->passes, (unsigned long long)n_pass);
-    atomicAdd(&a.counters->survivors, (unsigned long long)n_surv);
-    atomicAdd(&a.counters->insert_hops, (unsigned long long)n_ins);
+    atomicAdd(&block_counters(a.counters)->searches, 1ull);
+    atomicAdd(&block_counters(a.counters)->hops, (unsigned long long)nv);
+    atomicAdd(&block_counters(a.counters)->evals, (unsigned long long)evals);
+    atomicAdd(&block_counters(a.counters)->passes, (unsigned long long)n_pass);
+    atomicAdd(&block_counters(a.counters)->survivors, (unsigned long long)n_surv);
+    atomicAdd(&block_counters(a.counters)->insert_hops, (unsigned long long)n_ins);
   }
 }
 
