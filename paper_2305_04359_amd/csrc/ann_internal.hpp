@@ -111,7 +111,7 @@ struct MergeArgs {
 };
 
 constexpr u32 PRUNE_LDS_CAP = 512;     // candidate keys sorted in LDS by the step-1 prune kernel (a power of two)
-constexpr u32 MERGE_SPILL_MIN = 1024;  // step-2 candidate lists longer than this go to the spill arena (a power of two)
+constexpr u32 MERGE_SPILL_MIN = 4096;  // step-2 candidate lists longer than this go to the spill arena (a power of two)
 constexpr u32 STAGE_BUDGET = 10240;    // LDS bytes the prune kernels may spend on the selected points' vectors
 
 // launchers (each returns the hipGetLastError() of its launches)

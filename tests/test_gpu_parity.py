@@ -251,7 +251,7 @@ def test_build_hub_segments_spill(env):
     which exceeds the in-LDS candidate buffer of the merge kernel and takes the spill path."""
     torch, A, O = env
     rng = np.random.default_rng(2)
-    n = 6000
+    n = 20000
     pts_h = rng.integers(100, 104, (n, 16)).astype(np.uint8)
     ds = O.Dataset(pts_h, 0)
     s = 0
