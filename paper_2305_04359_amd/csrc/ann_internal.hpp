@@ -87,6 +87,15 @@ struct PruneArgs {
   DevCounters* counters;
 };
 
+// One overflowing row of step 2: its segment of the sorted edge keys and what the planning pass
+// already knows about the row, so that the worker need not chase keys[i0] -> meta[b] first.
+struct alignas(16) MergeItem {
+  u32 i0;    // index of the segment's first key
+  u32 cnt;   // segment length
+  u32 b;     // the row
+  u32 meta;  // its degree and clean-prefix length before this round's edges
+};
+
 struct MergeArgs {
   const char* points;
   u32* graph;
@@ -95,7 +104,7 @@ struct MergeArgs {
   const u64* keys;  // sorted edge keys (dest << 32 | source)
   u64 nkeys;
   u32* list_count;     // [3]: segments filed for the fast / gram / generic re-prune
-  u64* list_items[3];  // (segment length << 32 | index of its first key)
+  MergeItem* list_items[3];
   u32 fast_amax;       // most new entries the fast path takes
   u32 gram_ok;         // the matrix-core path applies to this dtype / row size
   u32 gram_tmax;       // and to at most this many candidates

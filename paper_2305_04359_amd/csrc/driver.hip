@@ -190,7 +190,7 @@ struct BatchScratch {
     HIP_TRY(edges.alloc(E * 8));
     HIP_TRY(edges_tmp.alloc(E * 8));
     HIP_TRY(hist.alloc(radix_hist_entries(E) * 4));
-    HIP_TRY(lists.alloc(3 * E * 8));
+    HIP_TRY(lists.alloc(3 * E * sizeof(MergeItem)));
     HIP_TRY(small.alloc(64));
     HIP_TRY(hipMemset(small.p, 0, 64));
     HIP_TRY(ovf_list.alloc(b * 4));
@@ -400,7 +400,7 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   ma.keys = S.edges.as<u64>();
   ma.nkeys = E;
   ma.list_count = small + 8;
-  for (int c = 0; c < 3; ++c) ma.list_items[c] = S.lists.as<u64>() + (u64)c * E;
+  for (int c = 0; c < 3; ++c) ma.list_items[c] = S.lists.as<MergeItem>() + (u64)c * E;
   ma.fast_amax = fast_path_amax(g->cfg);
   ma.gram_ok = gram_path_ok(g->cfg) ? 1u : 0u;
   ma.gram_tmax = gram_path_tmax();

@@ -43,9 +43,9 @@ __global__ __launch_bounds__(256) void plan_kernel(MergeArgs a) {
 
   const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
   int kind = -1;  // 0 fast, 1 gram, 2 generic
-  u32 slot = 0, cnt = 0;
+  u32 slot = 0, cnt = 0, b = 0, m = 0;
   if (i < a.nkeys) {
-    const u32 b = (u32)(a.keys[i] >> 32);
+    b = (u32)(a.keys[i] >> 32);
     const bool head = b != NONE_ID && (i == 0 || (u32)(a.keys[i - 1] >> 32) != b);
     if (head) {
       // length of the segment: gallop, then bisect (keys are sorted by destination)
@@ -63,7 +63,7 @@ __global__ __launch_bounds__(256) void plan_kernel(MergeArgs a) {
           hi = mid;
       }
       cnt = (u32)(hi - i);
-      const u32 m = a.meta[b];
+      m = a.meta[b];
       const u32 deg = meta_deg(m), clean = meta_clean(m);
       if (deg + cnt <= a.R) {
         u32* row = a.graph + (u64)b * a.R;
@@ -95,7 +95,7 @@ __global__ __launch_bounds__(256) void plan_kernel(MergeArgs a) {
     atomicAdd(&block_counters(a.counters)->edges, (unsigned long long)stat_lds[1]);
   }
   __syncthreads();
-  if (kind >= 0) a.list_items[kind][base_lds[kind] + slot] = ((u64)cnt << 32) | (u32)i;
+  if (kind >= 0) a.list_items[kind][base_lds[kind] + slot] = MergeItem{(u32)i, cnt, b, m};
 }
 
 hipError_t launch_plan(const MergeArgs& a, hipStream_t s) {
@@ -159,7 +159,9 @@ template <int KIND, int VEC, int NCH, int NA>
 __device__ __forceinline__ u32 fast_item(const MergeArgs& a, const VecTable& T, const AlphaParam& al, u32* ids_lds,
                                          u32 (*dk_lds)[64], u32 b, u32 i0, u32 clean, u32 stale, u32* row, u32 R,
                                          int lane) {
-  constexpr int PBF = PassBatch<VEC, NCH>::value > 4 ? 4 : PassBatch<VEC, NCH>::value;
+  // all nine passes (eight over the clean prefix, one over the new entries) requested at once when
+  // the pieces fit the register file: one trip to memory instead of three
+  constexpr int PBF = VEC * NCH <= 16 ? 9 : (VEC * NCH <= 32 ? 5 : (PassBatch<VEC, NCH>::value > 4 ? 4 : PassBatch<VEC, NCH>::value));
   constexpr u32 na = NA;
   const int sub = lane & (LPC - 1);
   const u32 grp = (u32)lane >> 3;
@@ -326,10 +328,8 @@ __global__ __launch_bounds__(64) void merge_fast_kernel(MergeArgs a, VecTable T)
   unsigned long long n_rep = 0, n_edges = 0, n_pair = 0;
 
   for (u32 it = blockIdx.x; it < nitems; it += gridDim.x) {
-    const u64 item = a.list_items[0][it];
-    const u32 i0 = (u32)item, cnt = (u32)(item >> 32);
-    const u32 b = (u32)(a.keys[i0] >> 32);
-    const u32 m = a.meta[b];
+    const MergeItem item = a.list_items[0][it];
+    const u32 i0 = item.i0, cnt = item.cnt, b = item.b, m = item.meta;
     const u32 deg = meta_deg(m), clean = meta_clean(m);
     const u32 stale = deg - clean;  // appended since the last prune
     const u32 na = stale + cnt;     // 1 <= na <= AMAX
@@ -453,7 +453,9 @@ template <int KIND, int VEC, int NCH>
 __device__ __forceinline__ u32 reprune_small_int(const VecTable& T, const QueryRegs<KIND, VEC, NCH>& Q,
                                                  unsigned char* Xs, SmallLds& S, u32 total, u32 R, i64 a16,
                                                  u32* row, int lane) {
-  constexpr int PB = PassBatch<VEC, NCH>::value;
+  // every pass of eight candidates is requested before the first is used (a pass is at most
+  // four registers here): one trip to memory for the whole list
+  constexpr int PB = SM_TMAX / 8;
   const int sub = lane & (LPC - 1);
   const u32 grp = (u32)lane >> 3;
   const u32 npass = (total + 7u) >> 3;
@@ -587,10 +589,9 @@ __global__ __launch_bounds__(64) void merge_gram_kernel(MergeArgs a, VecTable T)
     const u32 nitems = a.list_count[1];
     unsigned long long n_rep = 0, n_edges = 0, n_pair = 0;
     for (u32 it = blockIdx.x; it < nitems; it += gridDim.x) {
-      const u64 item = a.list_items[1][it];
-      const u32 i0 = (u32)item, cnt = (u32)(item >> 32);
-      const u32 b = (u32)(a.keys[i0] >> 32);
-      const u32 deg = meta_deg(a.meta[b]);
+      const MergeItem item = a.list_items[1][it];
+      const u32 i0 = item.i0, cnt = item.cnt, b = item.b;
+      const u32 deg = meta_deg(item.meta);
       const u32 total = deg + cnt;
       u32* row = a.graph + (u64)b * a.R;
       for (u32 j = lane; j < total; j += 64)
@@ -633,10 +634,9 @@ __global__ __launch_bounds__(64) void merge_generic_kernel(MergeArgs a, VecTable
   unsigned long long n_rep = 0, n_edges = 0, n_pair = 0;
 
   for (u32 it = blockIdx.x; it < nitems; it += gridDim.x) {
-    const u64 item = a.list_items[2][it];
-    const u32 i0 = (u32)item, cnt = (u32)(item >> 32);
-    const u32 b = (u32)(a.keys[i0] >> 32);
-    const u32 deg = meta_deg(a.meta[b]);
+    const MergeItem item = a.list_items[2][it];
+    const u32 i0 = item.i0, cnt = item.cnt, b = item.b;
+    const u32 deg = meta_deg(item.meta);
     const u32 total = deg + cnt;
     u32* row = a.graph + (u64)b * a.R;
 
