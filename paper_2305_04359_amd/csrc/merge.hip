@@ -630,6 +630,7 @@ __global__ __launch_bounds__(64) void merge_generic_kernel(MergeArgs a, VecTable
 
   const int lane = threadIdx.x;
   const u32 nitems = a.list_count[2];
+  if (blockIdx.x >= nitems) return;
   const AlphaParam al{a.a16, a.af};
   unsigned long long n_rep = 0, n_edges = 0, n_pair = 0;
 
@@ -717,11 +718,14 @@ __global__ __launch_bounds__(64) void merge_generic_kernel(MergeArgs a, VecTable
 template <int KIND, int VEC, int NCH>
 static hipError_t launch_merge_t(const MergeArgs& a, const VecTable& T, u32 grid, hipStream_t s, hipStream_t s_gram,
                                  hipStream_t s_generic) {
-  hipLaunchKernelGGL((merge_fast_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), 0, s, a, T);
-  if (a.gram_ok) hipLaunchKernelGGL((merge_gram_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), 0, s_gram, a, T);
+  // the generic kernel's few, long items first, so that they start at once instead of waiting
+  // for LDS that the other two kernels' workgroups hold; a small grid serves its short list
   const u32 lds = a.use_mfma ? ((a.R * 4u + 15u) & ~15u) + mfma_lds_bytes(a.R, T.row_bytes)
                             : ((a.R * 8u + 15u) & ~15u) + 8u * stage_stride(T.row_bytes) + 32u + a.stage_bytes;
-  hipLaunchKernelGGL((merge_generic_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), lds, s_generic, a, T);
+  const u32 grid_generic = grid < 1024u ? grid : 1024u;
+  hipLaunchKernelGGL((merge_generic_kernel<KIND, VEC, NCH>), dim3(grid_generic), dim3(64), lds, s_generic, a, T);
+  if (a.gram_ok) hipLaunchKernelGGL((merge_gram_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), 0, s_gram, a, T);
+  hipLaunchKernelGGL((merge_fast_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), 0, s, a, T);
   return hipGetLastError();
 }
 
