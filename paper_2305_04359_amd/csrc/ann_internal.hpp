@@ -42,8 +42,8 @@ struct SearchArgs {
   u32 start;
   u32 L;
   u32 k;
-  u32 hash_bits;  // log2 of the visited filter's size in 32-bit words
-  u32 id_bits;    // > 0: the filter stores 16-bit tags of ids that fit in this many bits
+  u32 hash_buckets;  // 16-byte buckets of the visited filter (any count from 4 to 2048)
+  u32 id_bits;       // > 0: the filter stores 16-bit tags of ids that fit in this many bits
   // build: visited list, one slot of vis_cap keys per search (may be null).  A search that
   // outgrows its slot moves its list to a chunk of vis_cap + spill_chunk keys taken from `spill`
   // (if given) and records the chunk's offset in vis_where[search] (~0 = still in its slot).
@@ -145,8 +145,8 @@ hipError_t radix_sort_edges(u64* keys, u64* tmp, u32* hist, u64 count, u32 key_b
 // start vertex (point nearest the mean)
 hipError_t start_vertex_device(const void* points, u64 n, u32 d, int dtype, hipStream_t s, u32* start_out);
 
-u32 search_lds_bytes(u32 L, u32 hash_bits);
-u32 default_hash_bits(u32 L);
-u32 compact_id_bits(u64 n, u32 hash_bits);  // 0 when 16-bit tags cannot identify every vertex
+u32 search_lds_bytes(u32 L, u32 hash_buckets);
+u32 search_hash_buckets(u32 L, u32 hash_bits);  // hash_bits: the caller's explicit choice, or 0
+u32 compact_id_bits(u64 n, u32 hash_buckets);  // 0 when 16-bit tags cannot identify every vertex
 
 }  // namespace annmi

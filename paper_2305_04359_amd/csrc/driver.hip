@@ -292,8 +292,8 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   sa.start = g->start;
   sa.L = L;
   sa.k = 1;
-  sa.hash_bits = g->hash_bits ? g->hash_bits : default_hash_bits(L);
-  sa.id_bits = compact_id_bits(g->n, sa.hash_bits);
+  sa.hash_buckets = search_hash_buckets(L, g->hash_bits);
+  sa.id_bits = compact_id_bits(g->n, sa.hash_buckets);
   sa.vis = S.vis.as<u64>();
   sa.nvis = S.nvis.as<u32>();
   sa.vis_cap = S.vis_cap;
@@ -766,8 +766,8 @@ int ann_search(const ann_graph* g, const void* points_dev, const void* queries_d
   sa.start = g->start;
   sa.L = L;
   sa.k = k;
-  sa.hash_bits = g->hash_bits ? g->hash_bits : default_hash_bits(L);
-  sa.id_bits = compact_id_bits(g->n, sa.hash_bits);
+  sa.hash_buckets = search_hash_buckets(L, g->hash_bits);
+  sa.id_bits = compact_id_bits(g->n, sa.hash_buckets);
   sa.out_ids = ids_dev;
   sa.out_dists = dists_dev;
   sa.counters = g->collect ? g->counters : nullptr;

@@ -7,9 +7,12 @@
 // entry first: a lost entry only causes a repeated distance evaluation, and the repeated
 // candidate is then recognised as a duplicate of a beam entry or is worse than the beam's last
 // entry, so results do not depend on the table.  A bucket holds four 32-bit ids, or, when the
-// vertex count allows, eight 16-bit tags: the id is passed through a bijection of its B bits,
-// the top bits choose the bucket and the remaining (at most 15) bits are the tag, so a tag match
-// still identifies the vertex exactly while the table remembers twice as many vertices.
+// vertex count allows, eight 16-bit tags: the id is passed through a bijection y of its B bits,
+// bucket = floor(top 14 bits of y * buckets / 2^14), tag = the low B - floor(log2 buckets) bits of
+// y (at most 15).  Two ids of one bucket differ by less than 2^B / buckets in y, so equal tags
+// mean equal ids: a tag match still identifies the vertex exactly while the table remembers
+// twice as many vertices.  The bucket count need not be a power of two; it is chosen so that
+// the wave's LDS lands on an occupancy step.
 #include "ann_device.hpp"
 #include "ann_internal.hpp"
 #include "ann_dispatch.hpp"
@@ -33,17 +36,22 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
   extern __shared__ __align__(16) unsigned char smem[];
   u64* beam = reinterpret_cast<u64*>(smem);
   u64* skeys = beam + NSLOT * 64;  // survivors of one batch of candidates
-  u32* cid = reinterpret_cast<u32*>(skeys + 64);
-  u32* hash = cid + 64;  // 16-byte aligned: the beam and cid are multiples of 16 bytes
+  u32* cid = reinterpret_cast<u32*>(skeys);  // the batch's ids: dead once its keys are formed
+  u32* hash = reinterpret_cast<u32*>(skeys + 64);  // 16-byte aligned
 
   const int lane = threadIdx.x;
   const u32 qi = blockIdx.x;
-  const u32 hsize = 1u << a.hash_bits;        // table size in 32-bit words; buckets of 4 words
-  const u32 hshift = 34u - a.hash_bits;       // 32 - log2(buckets)
+  const u32 nb = a.hash_buckets;
+  const u32 hsize = 4u * nb;  // table size in 32-bit words
   uint4* bucket = reinterpret_cast<uint4*>(hash);
-  const bool compact = a.id_bits != 0;        // 16-bit tag mode
+  const bool compact = a.id_bits != 0;  // 16-bit tag mode
   const u32 idmask = compact ? ((1u << a.id_bits) - 1u) : 0u;
-  const u32 tagbits = compact ? a.id_bits - (a.hash_bits - 2u) : 0u;
+  const u32 tagmask = compact ? ((1u << (a.id_bits - (31u - (u32)__builtin_clz(nb)))) - 1u) : 0u;
+  // y -> its top 14 bits (ids of fewer bits are shifted up)
+  const u32 y14r = a.id_bits > 14u ? a.id_bits - 14u : 0u;
+  const u32 y14l = a.id_bits < 14u ? 14u - a.id_bits : 0u;
+  auto bucket_of_y = [=](u32 y) { return __umul24((y >> y14r) << y14l, nb) >> 14; };
+  auto bucket_of_id = [=](u32 x) { return __umul24((x * 0x9E3779B1u) >> 18, nb) >> 14; };
   const u32 L = a.L;
 
   const u32 qrow = a.qidx ? a.qidx[qi] : qi;
@@ -70,9 +78,9 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
   if (lane == 0) {
     if (compact) {
       const u32 y = mix_id(a.start, idmask, a.id_bits);
-      hash[4u * (y >> tagbits)] = 0xFFFF0000u | (y & ((1u << tagbits) - 1u));
+      hash[4u * bucket_of_y(y)] = 0xFFFF0000u | (y & tagmask);
     } else {
-      hash[4u * ((a.start * 0x9E3779B1u) >> hshift)] = a.start;
+      hash[4u * bucket_of_id(a.start)] = a.start;
     }
   }
 
@@ -137,8 +145,8 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
       if (fresh) {
         if (compact) {
           const u32 y = mix_id(x, idmask, a.id_bits);
-          const u32 h = y >> tagbits;
-          const u32 tag = y & ((1u << tagbits) - 1u);
+          const u32 h = bucket_of_y(y);
+          const u32 tag = y & tagmask;
           const u32 tt = tag | (tag << 16);
           const uint4 e = bucket[h];
           // some 16-bit half equal to the tag?  (halves of e ^ tt that are zero)
@@ -149,7 +157,7 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
             bucket[h] = make_uint4((e.x << 16) | tag, (e.y << 16) | (e.x >> 16), (e.z << 16) | (e.y >> 16),
                                    (e.w << 16) | (e.z >> 16));
         } else {
-          const u32 h = (x * 0x9E3779B1u) >> hshift;
+          const u32 h = bucket_of_id(x);
           const uint4 e = bucket[h];
           const u32 m01 = (e.x ^ x) < (e.y ^ x) ? (e.x ^ x) : (e.y ^ x);
           const u32 m23 = (e.z ^ x) < (e.w ^ x) ? (e.z ^ x) : (e.w ^ x);
@@ -300,23 +308,37 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
   }
 }
 
-// 8 entries per beam slot, 512..4096: measured on 128-d uint8 data a larger table loses fewer
-// entries but costs more in occupancy than the repeated evaluations it saves
-u32 default_hash_bits(u32 L) {
-  u32 want = 8u * L, bits = 9;
-  while ((1u << bits) < want && bits < 12) ++bits;
-  return bits;
-}
-
 static u32 nslot_for(u32 L) { return L <= 64 ? 1 : (L <= 128 ? 2 : (L <= 256 ? 4 : 8)); }
 
-u32 search_lds_bytes(u32 L, u32 hash_bits) {
-  return nslot_for(L) * 64 * 8 + 64 * 8 + 64 * 4 + (1u << hash_bits) * 4;
+u32 search_lds_bytes(u32 L, u32 hash_buckets) { return nslot_for(L) * 64 * 8 + 64 * 8 + hash_buckets * 16; }
+
+// Size of the visited filter.  An explicit hash_bits (log2 of the size in 32-bit words) is taken
+// as it is.  Otherwise: 8 words per beam entry, rounded up to a power of two (512..4096 words),
+// then adjusted so that the wave's LDS lands exactly on the next occupancy step (waves per CU a
+// multiple of four, at most 32, LDS handed out in 512-byte units of 160 KB): measured on 128-d
+// uint8 data, occupancy is worth more than the evaluations a larger table saves.  The table is
+// never cut below 3/4 of the power of two.
+u32 search_hash_buckets(u32 L, u32 hash_bits) {
+  if (hash_bits) return 1u << (hash_bits - 2u);
+  u32 want = 8u * L, bits = 9;
+  while ((1u << bits) < want && bits < 12) ++bits;
+  const u32 full = 1u << (bits - 2u);
+  const u32 base = search_lds_bytes(L, 0);
+  const u32 lds_full = (search_lds_bytes(L, full) + 511u) & ~511u;
+  u32 waves = 163840u / lds_full;
+  waves = (waves + 3u) & ~3u;
+  if (waves > 32u) waves = 32u;
+  const u32 budget = (163840u / waves) & ~511u;
+  if (budget <= base) return full;
+  u32 nb = (budget - base) / 16u;
+  if (nb < full - full / 4u) return full;
+  if (nb > full) nb = full;
+  return nb;
 }
 
 template <int KIND, int VEC, int NCH>
 static hipError_t launch_search_nslot(const SearchArgs& a, const VecTable& T, hipStream_t s) {
-  const u32 lds = search_lds_bytes(a.L, a.hash_bits);
+  const u32 lds = search_lds_bytes(a.L, a.hash_buckets);
   const dim3 grid(a.nq), block(64);
   switch (nslot_for(a.L)) {
     case 1: hipLaunchKernelGGL((search_kernel<KIND, VEC, NCH, 1>), grid, block, lds, s, a, T); break;
@@ -327,11 +349,13 @@ static hipError_t launch_search_nslot(const SearchArgs& a, const VecTable& T, hi
   return hipGetLastError();
 }
 
-u32 compact_id_bits(u64 n, u32 hash_bits) {
+u32 compact_id_bits(u64 n, u32 hash_buckets) {
   u32 bits = 1;
   while ((1ull << bits) < n) ++bits;  // ids < n <= 2^bits
-  if (bits < hash_bits) bits = hash_bits;
-  return (bits <= 24u && bits - (hash_bits - 2u) <= 15u) ? bits : 0u;
+  u32 q = 0;
+  while ((2u << q) <= hash_buckets) ++q;  // floor(log2(buckets))
+  if (bits < q + 1u) bits = q + 1u;
+  return (bits <= 24u && bits - q <= 15u) ? bits : 0u;
 }
 
 hipError_t launch_search(const DistCfg& cfg, const SearchArgs& a, hipStream_t s) {
