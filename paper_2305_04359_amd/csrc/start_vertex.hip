@@ -108,12 +108,26 @@ __global__ __launch_bounds__(256) void score8_kernel(const T* x, u64 n, u32 d, c
     nn += __shfl_xor(nn, off, 64);
     xs += __shfl_xor(xs, off, 64);
   }
-  if (i < n && sub == 0) {
-    const u64 sc = score_bits((long long)n * nn - 2 * xs);
-    if (pass == 0)
-      atomicMin(best, (unsigned long long)sc);
-    else if (sc == *best)
-      atomicMin(best_id, (u32)i);
+  // one atomic per workgroup: thousands of atomics on one address queue up at a single channel
+  __shared__ unsigned long long red[4];
+  const bool mine = i < n && sub == 0;
+  const u64 sc = mine ? score_bits((long long)n * nn - 2 * xs) : ~0ull;
+  unsigned long long v = pass == 0 ? sc : ((mine && sc == *best) ? (unsigned long long)i : ~0ull);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const unsigned long long o = __shfl_xor(v, off, 64);
+    v = o < v ? o : v;
+  }
+  if ((threadIdx.x & 63u) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w) v = red[w] < v ? red[w] : v;
+    if (v != ~0ull) {
+      if (pass == 0)
+        atomicMin(best, v);
+      else
+        atomicMin(best_id, (u32)v);
+    }
   }
 }
 
@@ -122,12 +136,20 @@ template <typename T>
 __global__ __launch_bounds__(256) void score_kernel(const T* x, u64 n, u32 d, const typename SumType<T>::type* colsum,
                                                     unsigned long long* best, u32* best_id, int pass) {
   const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n) return;
-  const u64 sc = point_score<T>(x + i * d, d, n, colsum);
-  if (pass == 0)
-    atomicMin(best, (unsigned long long)sc);
-  else if (sc == *best)
-    atomicMin(best_id, (u32)i);
+  const bool mine = i < n;
+  const u64 sc = mine ? point_score<T>(x + i * d, d, n, colsum) : ~0ull;
+  unsigned long long v = pass == 0 ? sc : ((mine && sc == *best) ? (unsigned long long)i : ~0ull);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {  // one atomic per wavefront
+    const unsigned long long o = __shfl_xor(v, off, 64);
+    v = o < v ? o : v;
+  }
+  if ((threadIdx.x & 63u) == 0 && v != ~0ull) {
+    if (pass == 0)
+      atomicMin(best, v);
+    else
+      atomicMin(best_id, (u32)v);
+  }
 }
 
 template <typename T>
