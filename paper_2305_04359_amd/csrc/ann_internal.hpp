@@ -42,6 +42,8 @@ struct SearchArgs {
   u32 start;
   u32 L;
   u32 k;
+  u32* batch_counters;  // build only: the batch's counter words (overflow count [0], arena top [4..5], work
+                        // list lengths [8..10]); workgroup 0 zeroes them for the steps that follow
   u32 hash_buckets;  // 16-byte buckets of the visited filter (any count from 4 to 2048)
   u32 id_bits;       // > 0: the filter stores 16-bit tags of ids that fit in this many bits
   // build: visited list, one slot of vis_cap keys per search (may be null).  A search that
@@ -75,6 +77,7 @@ struct PruneArgs {
   u64* spill;           // chunks of vis_cap + spill_chunk keys for lists that outgrew their slot
   u32 spill_chunk;
   const u64* vis_where; // per search: offset of its chunk in spill, or ~0 (may be null)
+  unsigned long long* spill_top_reset;  // optional: zeroed by workgroup 0 for the next batch's searches
   u32* lost_flag;       // set (and left set) when a list did not fit anywhere
   u32* meta;            // per row: degree | clean prefix length << 16 (written for the batch points)
   u64* edges;           // batch_size x R keys (dest << 32 | source), ~0 in unused slots

@@ -275,9 +275,8 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   DevCounters* ctr = g->collect ? g->counters : nullptr;
 
   // per-batch counters: [0] overflow count, [4..5] arena top, [6..7] spill top, [8..10] work list
-  // lengths; the flags [2] and [3] stay up once set
-  HIP_TRY(hipMemsetAsync(small, 0, 8, st));
-  HIP_TRY(hipMemsetAsync(small + 4, 0, 32, st));
+  // lengths; the flags [2] and [3] stay up once set.  The scratch starts zeroed; afterwards the
+  // search kernel zeroes what the later steps count in, and the prune kernel the spill top.
   tm.mark(0, st);
 
   // step 1a: greedySearch(p, s, L, 1) over the frozen graph, visited lists to scratch
@@ -294,6 +293,7 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   sa.k = 1;
   sa.hash_buckets = search_hash_buckets(L, g->hash_bits);
   sa.id_bits = compact_id_bits(g->n, sa.hash_buckets);
+  sa.batch_counters = small;
   sa.vis = S.vis.as<u64>();
   sa.nvis = S.nvis.as<u32>();
   sa.vis_cap = S.vis_cap;
@@ -321,6 +321,7 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   pa.spill = S.spill.as<u64>();
   pa.spill_chunk = S.spill_chunk;
   pa.vis_where = S.vis_where.as<u64>();
+  pa.spill_top_reset = reinterpret_cast<unsigned long long*>(small + 6);
   pa.lost_flag = small + 3;
   pa.meta = g->meta;
   pa.stage_bytes = prune_stage_bytes(R, g->cfg);
@@ -364,6 +365,7 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
     sb.nvis = nvis2.as<u32>();
     sb.vis_cap = need;
     sb.spill = nullptr;
+    sb.batch_counters = nullptr;
     sb.vis_where = nullptr;
     sb.counters = nullptr;
     HIP_TRY(launch_search(g->cfg, sb, st));
@@ -376,6 +378,7 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
     pb.nvis = nvis2.as<u32>();
     pb.vis_cap = need;
     pb.vis_where = nullptr;
+    pb.spill_top_reset = nullptr;
     HIP_TRY(launch_prune(g->cfg, pb, st));
     u32 again = 0;
     HIP_TRY(hipMemcpyAsync(&again, small + 0, 4, hipMemcpyDeviceToHost, st));

@@ -30,6 +30,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   const u32 slot = a.slotmap ? a.slotmap[qi] : qi;
   const u32 nv = a.nvis[qi];
   u64* edges = a.edges + (u64)slot * a.R;
+  if (a.spill_top_reset != nullptr && qi == 0 && lane == 0) *a.spill_top_reset = 0ull;  // every search of this batch is over
 
   const u64 where = a.vis_where != nullptr ? a.vis_where[qi] : ~0ull;
   const u32 room = where == ~0ull ? a.vis_cap : a.vis_cap + a.spill_chunk;

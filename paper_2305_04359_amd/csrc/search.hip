@@ -59,6 +59,14 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
       load_query<KIND, VEC, NCH>(a.queries + (u64)qrow * a.qrow_bytes, T.npieces, lane);
 
   for (u32 i = lane; i < hsize; i += 64) hash[i] = NONE_ID;
+  if (a.batch_counters != nullptr && qi == 0 && lane == 0) {
+    a.batch_counters[0] = 0;
+    a.batch_counters[4] = 0;
+    a.batch_counters[5] = 0;
+    a.batch_counters[8] = 0;
+    a.batch_counters[9] = 0;
+    a.batch_counters[10] = 0;
+  }
 
   u64 A[NSLOT];
 #pragma unroll
