@@ -390,7 +390,8 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   tm.mark(2, st);
 
   // step 2a: bring equal destinations together
-  HIP_TRY(radix_sort_edges(S.edges.as<u64>(), S.edges_tmp.as<u64>(), S.hist.as<u32>(), E, bits_for(g->n), st));
+  HIP_TRY(radix_sort_edges(S.edges.as<u64>(), S.edges_tmp.as<u64>(), S.hist.as<u32>(), radix_hist_entries(S.bmax * R), E,
+                           bits_for(g->n), st));
   tm.mark(3, st);
 
   // step 2b: cut the keys into segments of equal destination; append where the row has room,
@@ -582,7 +583,7 @@ int ann_sort_edges(uint64_t* keys_dev, uint64_t count, uint32_t key_bits, void* 
   DevBuf tmp, hist;
   HIP_TRY(tmp.alloc(count * 8));
   HIP_TRY(hist.alloc(radix_hist_entries(count) * 4));
-  HIP_TRY(radix_sort_edges(keys_dev, tmp.as<u64>(), hist.as<u32>(), count, key_bits, st));
+  HIP_TRY(radix_sort_edges(keys_dev, tmp.as<u64>(), hist.as<u32>(), radix_hist_entries(count), count, key_bits, st));
   HIP_TRY(hipStreamSynchronize(st));
   return ANN_OK;
 }

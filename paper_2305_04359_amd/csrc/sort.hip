@@ -23,8 +23,14 @@ static u64 rs_tile_keys(u64 count) {
 }
 static u64 rs_tiles(u64 count) { return (count + rs_tile_keys(count) - 1) / rs_tile_keys(count); }
 
-// RS_RADIX x tiles counters and RS_RADIX digit totals
-u64 radix_hist_entries(u64 count) { return RS_RADIX * ((rs_tiles(count) ? rs_tiles(count) : 1) + 1); }
+// RS_RADIX x tiles counters and RS_RADIX digit totals, enough for any sort of AT MOST `count`
+// keys.  (The number of tiles is not monotone in the key count: 8,192 x 1,024 keys make 8,192
+// tiles, a few more keys make tiles of 1,088 keys and fewer of them.)
+u64 radix_hist_entries(u64 count) {
+  u64 tiles = (count + 1023) / 1024 + 1;
+  if (tiles > 8192) tiles = 8192;
+  return RS_RADIX * (tiles + 1);
+}
 
 __global__ __launch_bounds__(64) void rs_hist_kernel(const u64* keys, u64 count, u64 tile_keys, u32 tiles,
                                                      u32 shift, u32 mask, u32* hist) {
@@ -128,8 +134,10 @@ __global__ __launch_bounds__(64) void rs_scatter_kernel(const u64* keys, u64* ou
   }
 }
 
-hipError_t radix_sort_edges(u64* keys, u64* tmp, u32* hist, u64 count, u32 key_bits, hipStream_t s) {
+hipError_t radix_sort_edges(u64* keys, u64* tmp, u32* hist, u64 hist_entries, u64 count, u32 key_bits,
+                            hipStream_t s) {
   if (count < 2 || key_bits == 0) return hipSuccess;
+  if ((u64)RS_RADIX * (rs_tiles(count) + 1) > hist_entries) return hipErrorInvalidValue;  // histogram too small
   if (key_bits > 32) key_bits = 32;
   const u64 tile_keys = rs_tile_keys(count);
   const u32 tiles = (u32)rs_tiles(count);

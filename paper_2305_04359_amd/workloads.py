@@ -11,6 +11,8 @@ Rows are produced in blocks of ``BLOCK`` rows, block ``b`` of a stream seeded by
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
 
 import numpy as np
@@ -33,13 +35,26 @@ def _blocks(n: int):
 
 
 def gaussian_mixture_u8(n, d, centers, sigma, seed, stream, lo=0, hi=255, dtype=np.uint8):
-    """Rows = clip(round(center[k] + sigma * g), lo, hi), k uniform over the centres."""
+    """Rows = clip(round(center[k] + sigma * g), lo, hi), k uniform over the centres.
+    Blocks are independent streams, so large inputs are drawn by a few threads at once; the
+    result does not depend on how many."""
     out = np.empty((n, d), dtype)
-    for b, s, e in _blocks(n):
+
+    def draw(item):
+        b, s, e = item
         g = _rng(seed, stream, b)
         k = g.integers(0, centers.shape[0], size=e - s)
         x = centers[k] + sigma * g.standard_normal((e - s, d), dtype=np.float32)
         out[s:e] = np.clip(np.rint(x), lo, hi).astype(dtype)
+
+    items = list(_blocks(n))
+    workers = min(16, os.cpu_count() or 1, len(items))
+    if workers <= 1 or n < 4 * BLOCK:
+        for it in items:
+            draw(it)
+    else:
+        with ThreadPoolExecutor(max_workers=workers) as ex:
+            list(ex.map(draw, items))
     return out
 
 
