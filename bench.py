@@ -102,11 +102,19 @@ def main():
     ap.add_argument("--cpu-points", type=int, default=None,
                     help="instead: the oracle inserts only this many points of the last batch (large inputs)")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--progress", action="store_true", help="print the steps to stderr as they finish")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
               "(no collectives or sharding are part of it)", file=sys.stderr)
         sys.exit(2)
+
+    t_start = time.time()
+    progress = args.progress or args.config == "C5"
+
+    def say(msg):
+        if progress:
+            print(f"[bench {time.time() - t_start:7.1f}s] {msg}", file=sys.stderr, flush=True)
 
     import torch
     from paper_2305_04359_amd import binding as A
@@ -120,16 +128,19 @@ def main():
     pts = torch.from_numpy(w.points).cuda()
     qs = torch.from_numpy(w.queries).cuda()
     t_gen = time.time() - t_gen
+    say(f"inputs drawn and resident: {w.n} x {w.d} {w.points.dtype}")
     k = w.k
     row_bytes = w.d * w.points.dtype.itemsize
 
     gt = ground_truth(torch, pts, qs, k, metric)
+    say("exact neighbours of the queries computed")
 
     # warm-up builds; the first one also picks the beam widths for the recall targets
     L90 = L95 = None
     sweep = []
     for i in range(max(1, args.warmup)):
         g = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, metric=metric)
+        say(f"warm-up build {i + 1} done")
         if i == 0:
             for L in sorted(set(w.search_L)):
                 if L < k:
@@ -137,6 +148,7 @@ def main():
                 ms, ids = time_search(torch, A, g, pts, qs, k, L, reps=3)
                 r = recall(ids.cpu().numpy().view(np.uint32), gt)
                 sweep.append({"L": L, "recall": round(r, 4), "qps": round(qs.shape[0] / ms * 1e3, 1)})
+                say(f"queries at L={L}: recall {r:.4f}")
                 if L90 is None and r >= 0.90:
                     L90 = L
                 if L95 is None and r >= 0.95:
@@ -166,6 +178,7 @@ def main():
         t2 = time.perf_counter()
         build_ms.append((t1 - t0) * 1e3)
         step_ms.append((t2 - t0) * 1e3)
+        say(f"timed build: {(t1 - t0) * 1e3:.1f} ms")
     st = stats_list[-1]
     ms_per_step = float(np.mean(step_ms))
     bms = float(np.mean(build_ms))
@@ -180,7 +193,7 @@ def main():
     distinct_frac = 1.0
     if not args.no_cpu:
         cpu_points = args.cpu_points if args.cpu_points is not None else (20000 if w.n > 20_000_000 else None)
-        cpu = cpu_baseline(torch, A, w, pts, g, args.cpu_batches, cpu_points)
+        cpu = cpu_baseline(torch, A, w, pts, g, args.cpu_batches, cpu_points, say)
         distinct_frac = cpu.pop("_distinct_frac")
 
     # roofline of the dominant kernel: the build's beam search.  Algorithmic bytes per launch =
@@ -239,7 +252,7 @@ def measured_traffic(workload):
         return None
 
 
-def cpu_baseline(torch, A, w, pts, g_full, nbatches, npoints_only=None):
+def cpu_baseline(torch, A, w, pts, g_full, nbatches, npoints_only=None, say=lambda m: None):
     """The oracle, as it stands, runs the LAST `nbatches` batches of the build on all host cores,
     starting from the graph as it stood before them (taken from a GPU build stopped early).  The
     GPU inserts the same batches into the same snapshot and the resulting graphs are compared.
@@ -252,7 +265,9 @@ def cpu_baseline(torch, A, w, pts, g_full, nbatches, npoints_only=None):
     snap = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, metric=metric, max_rounds=rounds - nb,
                        collect_stats=True)
     st0 = snap.stats()
+    say("snapshot built on the GPU")
     rows = snap.neighbors()
+    say("snapshot copied to the host")
     s = int(snap.info().start)
     ds = O.Dataset(w.points, metric)
     order = O.insertion_order(w.n, s, w.seed)
@@ -269,6 +284,7 @@ def cpu_baseline(torch, A, w, pts, g_full, nbatches, npoints_only=None):
         O.batch_insert(ds, og, s, batch, w.L, w.alpha, threads=0, stats=ost)
         npoints += len(batch)
     cpu_s = time.perf_counter() - t0
+    say(f"oracle inserted {npoints} points in {cpu_s:.1f} s")
     for batch in batches:
         A.ann_insert_batch(snap, pts, batch, w.L, w.alpha)
     st1 = snap.stats()

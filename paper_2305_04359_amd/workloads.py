@@ -177,6 +177,7 @@ def c5(n=100_000_000, nq=10_000):
     w = c2(n, nq)
     w.name = "C5"
     w.note = "stand-in for BIGANN-100M"
+    w.search_L = w.search_L + (250, 300, 400, 512)
     return w
 
 
