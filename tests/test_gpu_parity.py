@@ -391,3 +391,80 @@ def test_f32_distances_and_recall(env, metric, alpha):
         assert abs(r_g - r_o) <= 0.002
     g2 = A.ann_build(pts, 32, 64, alpha, seed=1, metric=metric)
     assert (g2.neighbors() == rows).all()
+
+
+# ------------------------------------------------------------------------------------------
+# full size (the benchmark's workload and launch configuration), on samples the oracle can do
+# ------------------------------------------------------------------------------------------
+@pytest.fixture(scope="module")
+def c2_full(env):
+    torch, A, O = env
+    w = W.c2()
+    pts = dev(torch, w.points)
+    g = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, collect_stats=True)
+    g.build_stats = g.stats()  # before any query adds to the counters
+    return w, pts, g
+
+
+def test_c2_full_size_build_sampled_against_oracle(env, c2_full):
+    """The graph before the last batch comes from a GPU build stopped one batch early; the oracle
+    and the GPU both insert the same 3,000 points of the last batch into it: identical rows."""
+    torch, A, O = env
+    w, pts, g = c2_full
+    rounds = int(g.info().rounds)
+    snap = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, max_rounds=rounds - 1)
+    rows = snap.neighbors()
+    s = int(snap.info().start)
+    ds = O.Dataset(w.points, 0)
+    assert s == O.start_vertex(ds)
+    order = O.insertion_order(w.n, s, w.seed)
+    bounds = O.schedule(w.n - 1, w.theta).astype(np.int64)
+    assert len(bounds) - 1 == rounds
+    batch = order[bounds[rounds - 1]:bounds[rounds]][:3000]
+    say(f"oracle inserts {len(batch)} points into the {int(bounds[rounds - 1]) + 1}-point graph")
+    og = rows.copy()
+    O.batch_insert(ds, og, s, batch, w.L, w.alpha, threads=0)
+    A.ann_insert_batch(snap, pts, batch, w.L, w.alpha)
+    gg = snap.neighbors()
+    changed = np.nonzero((og != rows).any(1))[0]
+    assert len(changed) > len(batch)  # the batch's own rows and the rows that took reverse edges
+    bad = np.nonzero((gg != og).any(1))[0]
+    assert len(bad) == 0, f"rows differ: {bad[:10]}"
+
+
+def test_c2_full_size_queries_against_oracle(env, c2_full):
+    torch, A, O = env
+    w, pts, g = c2_full
+    rows = g.neighbors()
+    s = int(g.info().start)
+    ds = O.Dataset(w.points, 0)
+    qs_h = w.queries[:300]
+    qs = dev(torch, qs_h)
+    for L in (10, 50, 200):
+        say(f"300 queries on the full graph, L={L}")
+        ids, dists = A.ann_search(g, pts, qs, 10, L)
+        oi, od = O.search_batch(ds, rows, s, qs_h, 10, L, threads=0)
+        assert (ids.cpu().numpy().view(np.uint32) == oi).all()
+        assert (dists.cpu().numpy().view(np.int32) == od.view(np.int32)).all()
+
+
+def test_c2_full_size_invariants(env, c2_full):
+    """Properties that hold at any size: degree bounds, rows are compact lists of valid ids without
+    self loops or repeats, the counters add up, and a second build gives the same bytes."""
+    torch, A, O = env
+    w, pts, g = c2_full
+    rows = g.neighbors()
+    n = w.n
+    valid = rows != NONE
+    deg = valid.sum(1)
+    assert deg.max() <= w.R and deg.min() >= 1
+    # valid ids come first in every row
+    assert (valid[:, :-1] >= valid[:, 1:]).all()
+    assert rows[valid].max() < n
+    assert not (rows == np.arange(n, dtype=np.uint32)[:, None]).any()
+    srt = np.sort(rows, axis=1)
+    assert not ((srt[:, 1:] == srt[:, :-1]) & (srt[:, 1:] != NONE)).any()
+    st = g.build_stats
+    assert st["searches"] == n - 1 and st["prunes"] == n - 1 and st["restarts"] == 0
+    g2 = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed)
+    assert (g2.neighbors() == rows).all()
