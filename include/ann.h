@@ -16,15 +16,20 @@
  *   - Every "closest" is decided under the total order (distance, id).
  *   - A graph is n rows of R uint32 ids (fixed-length edge lists, Sec. 4.5);
  *     valid neighbours come first, unused slots hold ANN_NONE.
- *   - Vertex ids are < 2^31.  Supported row sizes: d*sizeof(elem) a multiple
- *     of 4 bytes; up to 512 B if also a multiple of 16, else up to 256 B
- *     (u8/i8); f32 needs d % 4 == 0 and d <= 256.
+ *   - Vertex ids are < 2^31.  Supported row sizes: u8/i8 1 <= d <= 512;
+ *     f32 needs d % 4 == 0 and d <= 256.  u8/i8 rows whose size is not a
+ *     multiple of 16 bytes are copied once, per points array, into zero-
+ *     padded rows that the graph object keeps (n x stride bytes of device
+ *     memory, stride = d rounded up to 16, or to a power of two where that
+ *     costs at most a quarter more); queries are copied per call.  The
+ *     points array must not change while a graph built on it is in use.
  *   - Every function returns ANN_OK (0) or a negative ann_status; on error
  *     outputs are untouched, *out handles are NULL and ann_last_error()
  *     describes the failure.  No exception or abort crosses this boundary.
  *   - `stream` is a hipStream_t passed as void* (NULL = default stream).
  *   - The library allocates its own scratch with hipMalloc and frees it
- *     before returning; the caller owns every buffer it passes in.
+ *     before returning (the padded copies named above live as long as the
+ *     graph); the caller owns every buffer it passes in.
  */
 #ifndef ANN_H
 #define ANN_H

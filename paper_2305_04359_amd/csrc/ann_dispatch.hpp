@@ -1,4 +1,5 @@
-// Maps a run-time DistCfg to the matching template instance <KIND, VEC, NCH>.
+// Maps a run-time DistCfg to the matching template instance <KIND, VEC, NCH>.  Rows are always
+// whole 16-byte pieces here (byte rows of other sizes are padded before they reach a kernel).
 #pragma once
 
 #define ANN_DISPATCH_CFG(FN, ...)                                                              \
@@ -8,15 +9,9 @@
       case K_U8 * 1000 + 161: return FN<K_U8, 16, 1>(__VA_ARGS__);                             \
       case K_U8 * 1000 + 162: return FN<K_U8, 16, 2>(__VA_ARGS__);                             \
       case K_U8 * 1000 + 164: return FN<K_U8, 16, 4>(__VA_ARGS__);                             \
-      case K_U8 * 1000 + 42: return FN<K_U8, 4, 2>(__VA_ARGS__);                               \
-      case K_U8 * 1000 + 44: return FN<K_U8, 4, 4>(__VA_ARGS__);                               \
-      case K_U8 * 1000 + 48: return FN<K_U8, 4, 8>(__VA_ARGS__);                               \
       case K_I8 * 1000 + 161: return FN<K_I8, 16, 1>(__VA_ARGS__);                             \
       case K_I8 * 1000 + 162: return FN<K_I8, 16, 2>(__VA_ARGS__);                             \
       case K_I8 * 1000 + 164: return FN<K_I8, 16, 4>(__VA_ARGS__);                             \
-      case K_I8 * 1000 + 42: return FN<K_I8, 4, 2>(__VA_ARGS__);                               \
-      case K_I8 * 1000 + 44: return FN<K_I8, 4, 4>(__VA_ARGS__);                               \
-      case K_I8 * 1000 + 48: return FN<K_I8, 4, 8>(__VA_ARGS__);                               \
       case K_F32_L2 * 1000 + 162: return FN<K_F32_L2, 16, 2>(__VA_ARGS__);                     \
       case K_F32_L2 * 1000 + 164: return FN<K_F32_L2, 16, 4>(__VA_ARGS__);                     \
       case K_F32_L2 * 1000 + 168: return FN<K_F32_L2, 16, 8>(__VA_ARGS__);                     \

@@ -72,43 +72,30 @@ bool make_cfg(uint32_t d, int dtype, int metric, DistCfg* cfg, std::string* why)
     *why = "ANN_MIPS is supported for ANN_F32 only";
     return false;
   }
-  if (d == 0 || rb % 4 != 0) {
-    *why = "row size must be a positive multiple of 4 bytes";
+  if (d == 0) {
+    *why = "d must be positive";
+    return false;
+  }
+  if (rb % 16 != 0) {  // byte rows are padded by the caller of this function; f32 rows are not
+    *why = "f32 needs d % 4 == 0";
     return false;
   }
   cfg->row_bytes = rb;
   cfg->kind = dtype == ANN_U8 ? 0 : dtype == ANN_I8 ? 1 : (metric == ANN_L2SQ ? 2 : 3);
-  if (rb % 16 == 0) {
-    cfg->vec = 16;
-    cfg->npieces = (u32)(rb / 16);
-  } else {
-    cfg->vec = 4;
-    cfg->npieces = (u32)(rb / 4);
-  }
+  cfg->vec = 16;
+  cfg->npieces = (u32)(rb / 16);
   const u32 per_lane = (cfg->npieces + 7) / 8;
   int nch = 1;
   while ((u32)nch < per_lane) nch *= 2;
   if (dtype == ANN_F32) {
-    if (cfg->vec != 16) {
-      *why = "f32 needs d % 4 == 0";
-      return false;
-    }
     if (nch < 2) nch = 2;
     if (nch > 8) {
       *why = "f32 rows above 1024 bytes are not supported";
       return false;
     }
-  } else if (cfg->vec == 16) {
-    if (nch > 4) {
-      *why = "u8/i8 rows above 512 bytes are not supported";
-      return false;
-    }
-  } else {
-    if (nch < 2) nch = 2;
-    if (nch > 8) {
-      *why = "u8/i8 rows that are not a multiple of 16 bytes must be at most 256 bytes";
-      return false;
-    }
+  } else if (nch > 4) {
+    *why = "u8/i8 rows above 512 bytes are not supported";
+    return false;
   }
   cfg->nch = nch;
   return true;
@@ -151,9 +138,77 @@ struct ann_graph {
   u32 visited_cap = 0;
   u64 spill_keys = 0;  // 0 = default
   bool collect = false;
+  // u8/i8 rows whose size is not a multiple of 16 bytes: the kernels work on a copy with rows of
+  // pad_stride bytes (zero tail, which changes no distance), made once per points array; queries
+  // are copied the same way on every call.  cfg describes the padded rows.
+  u64 pad_stride = 0;
+  mutable void* pad_buf = nullptr;
+  mutable const void* pad_src = nullptr;
+  mutable void* qpad_buf = nullptr;
+  mutable u64 qpad_rows = 0;
 };
 
 namespace {
+
+// dst row r = src row r followed by zeros; one thread per 4-byte word of dst (rows of any byte
+// length, so the source is read byte by byte at the ragged end)
+__global__ __launch_bounds__(256) void pad_rows_kernel(const unsigned char* src, u64 nrows, u32 rb, u32* dst,
+                                                       u32 stride) {
+  const u64 w = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+  const u32 wpr = stride / 4u;
+  if (w >= nrows * wpr) return;
+  const u64 r = w / wpr;
+  const u32 c = (u32)(w % wpr) * 4u;
+  const unsigned char* p = src + r * rb;
+  u32 v = 0;
+#pragma unroll
+  for (u32 k = 0; k < 4; ++k)
+    if (c + k < rb) v |= (u32)p[c + k] << (8u * k);
+  dst[w] = v;
+}
+
+int pad_rows(const void* src, u64 nrows, u32 rb, void* dst, u64 stride, hipStream_t st) {
+  const u64 words = nrows * (stride / 4);
+  if (words == 0) return ANN_OK;
+  hipLaunchKernelGGL(pad_rows_kernel, dim3((u32)((words + 255) / 256)), dim3(256), 0, st,
+                     static_cast<const unsigned char*>(src), nrows, rb, static_cast<u32*>(dst), (u32)stride);
+  HIP_TRY(hipGetLastError());
+  return ANN_OK;
+}
+
+// The array the kernels read for `points_dev`: itself, or the graph's padded copy of it.
+int resolve_points(const ann_graph* g, const void* points_dev, hipStream_t st, const void** out) {
+  *out = points_dev;
+  if (!g->pad_stride) return ANN_OK;
+  if (g->pad_src != points_dev) {
+    if (!g->pad_buf) HIP_TRY(hipMalloc(&g->pad_buf, (size_t)g->n * g->pad_stride));
+    g->pad_src = nullptr;
+    int rc = pad_rows(points_dev, g->n, g->d, g->pad_buf, g->pad_stride, st);
+    if (rc) return rc;
+    g->pad_src = points_dev;
+  }
+  *out = g->pad_buf;
+  return ANN_OK;
+}
+
+int resolve_queries(const ann_graph* g, const void* queries_dev, u64 nq, hipStream_t st, const void** out) {
+  *out = queries_dev;
+  if (!g->pad_stride) return ANN_OK;
+  if (g->qpad_rows < nq) {
+    if (g->qpad_buf) {
+      HIP_TRY(hipStreamSynchronize(st));  // an earlier call may still read the old buffer
+      (void)hipFree(g->qpad_buf);
+      g->qpad_buf = nullptr;
+      g->qpad_rows = 0;
+    }
+    HIP_TRY(hipMalloc(&g->qpad_buf, (size_t)nq * g->pad_stride));
+    g->qpad_rows = nq;
+  }
+  int rc = pad_rows(queries_dev, nq, g->d, g->qpad_buf, g->pad_stride, st);
+  if (rc) return rc;
+  *out = g->qpad_buf;
+  return ANN_OK;
+}
 
 // Scratch of one BatchInsert call, sized for `bmax` points.
 struct BatchScratch {
@@ -451,7 +506,16 @@ int finish_batches(ann_graph* g, BatchScratch& S, PhaseTimer& tm, hipStream_t st
 int new_graph(u64 n, u32 d, int dtype, int metric, u32 R, ann_graph** out) {
   std::string why;
   DistCfg cfg{};
-  if (!make_cfg(d, dtype, metric, &cfg, &why)) return fail(ANN_EINVAL, "%s", why.c_str());
+  u64 pad_stride = 0;
+  if ((dtype == ANN_U8 || dtype == ANN_I8) && d % 16 != 0) {
+    // multiple of 16 bytes; a power of two (whole cache lines) where that wastes at most a quarter
+    const u64 s16 = ((u64)d + 15) / 16 * 16;
+    u64 p2 = 16;
+    while (p2 < s16) p2 *= 2;
+    pad_stride = (p2 - s16) * 4 <= s16 ? p2 : s16;
+  }
+  if (!make_cfg(pad_stride ? (uint32_t)pad_stride : d, dtype, metric, &cfg, &why))
+    return fail(ANN_EINVAL, "%s", why.c_str());
   if (n < 1 || n >= (1ull << 31)) return fail(ANN_EINVAL, "n must be in [1, 2^31)");
   if (R < 1 || R > 512) return fail(ANN_EINVAL, "R must be in [1, 512]");
   ann_graph* g = new (std::nothrow) ann_graph();
@@ -462,6 +526,7 @@ int new_graph(u64 n, u32 d, int dtype, int metric, u32 R, ann_graph** out) {
   g->dtype = dtype;
   g->metric = metric;
   g->cfg = cfg;
+  g->pad_stride = pad_stride;
   hipError_t e = hipMalloc(reinterpret_cast<void**>(&g->rows), (size_t)n * R * sizeof(u32));
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&g->meta), (size_t)n * sizeof(u32));
   if (e == hipSuccess) e = hipMemset(g->meta, 0, (size_t)n * sizeof(u32));
@@ -486,6 +551,8 @@ void ann_graph_free(ann_graph* g) {
   if (g->rows) (void)hipFree(g->rows);
   if (g->meta) (void)hipFree(g->meta);
   if (g->counters) (void)hipFree(g->counters);
+  if (g->pad_buf) (void)hipFree(g->pad_buf);
+  if (g->qpad_buf) (void)hipFree(g->qpad_buf);
   delete g;
 }
 
@@ -613,7 +680,10 @@ int ann_insert_batch(ann_graph* g, const void* points_dev, const uint32_t* ids_h
   PhaseTimer tm;
   rc = tm.init(g->collect);
   if (rc) return rc;
-  rc = batch_insert(g, points_dev, ids_host, S.qidx.as<u32>(), b, L, alpha, S, tm, st, /*sync=*/true);
+  const void* pts = nullptr;
+  rc = resolve_points(g, points_dev, st, &pts);
+  if (rc) return rc;
+  rc = batch_insert(g, pts, ids_host, S.qidx.as<u32>(), b, L, alpha, S, tm, st, /*sync=*/true);
   if (rc) return rc;
   rc = finish_batches(g, S, tm, st);
   return rc == ANN_LOST_LIST ? fail(ANN_EINTERNAL, "a visited list was lost in a synchronised batch") : rc;
@@ -715,6 +785,10 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
   rc = tm.init(g->collect);
   if (rc) return rc;
 
+  const void* pts = nullptr;
+  rc = resolve_points(g, points_dev, st, &pts);
+  if (rc) return rc;
+
   const double t_alloc = now_ms();
   // First try: every batch is issued without waiting for the previous one.  A search whose
   // visited list fits neither its slot nor a spill chunk spoils that attempt (it is detected at
@@ -725,7 +799,7 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
     for (size_t r = 0; r + 1 < bounds.size(); ++r) {
       if (o.max_rounds && r >= o.max_rounds) break;
       const u64 lo = bounds[r], b = bounds[r + 1] - bounds[r];
-      rc = batch_insert(g, points_dev, order.data() + lo, order_dev.as<u32>() + lo, b, L, alpha, S, tm, st, sync);
+      rc = batch_insert(g, pts, order.data() + lo, order_dev.as<u32>() + lo, b, L, alpha, S, tm, st, sync);
       if (rc) return rc;
     }
     rc = finish_batches(g, S, tm, st);
@@ -760,9 +834,16 @@ int ann_search(const ann_graph* g, const void* points_dev, const void* queries_d
   if (L > 512) return fail(ANN_EINVAL, "L must be at most 512");
   if (nq >= (1ull << 31)) return fail(ANN_EINVAL, "too many queries");
   SearchArgs sa{};
-  sa.points = static_cast<const char*>(points_dev);
+  hipStream_t st_ = static_cast<hipStream_t>(stream);
+  const void* pts = nullptr;
+  const void* qsp = nullptr;
+  int rc_ = resolve_points(g, points_dev, st_, &pts);
+  if (rc_) return rc_;
+  rc_ = resolve_queries(g, queries_dev, nq, st_, &qsp);
+  if (rc_) return rc_;
+  sa.points = static_cast<const char*>(pts);
   sa.graph = g->rows;
-  sa.queries = static_cast<const char*>(queries_dev);
+  sa.queries = static_cast<const char*>(qsp);
   sa.qidx = nullptr;
   sa.qrow_bytes = g->cfg.row_bytes;
   sa.nq = (u32)nq;

@@ -292,7 +292,9 @@ def test_bad_arguments(env, c1):
         with pytest.raises(A.AnnError):
             A.ann_build(pts, **kw)
     with pytest.raises(A.AnnError):
-        A.ann_build(dev(torch, c1.points[:100, :6]), 8, 8, 1.2)  # 6-byte rows
+        A.ann_build(dev(torch, np.tile(c1.points[:100], (1, 5))[:, :520]), 8, 8, 1.2)  # 520-byte rows
+    with pytest.raises(A.AnnError):
+        A.ann_build(dev(torch, np.ones((100, 6), np.float32)), 8, 8, 1.2)  # f32 rows need d % 4 == 0
     with pytest.raises(A.AnnError):
         A.ann_build(pts, 8, 8, 1.2, metric=A.MIPS)  # inner product on u8
     with pytest.raises(A.AnnError):
@@ -322,17 +324,29 @@ def test_int8_d100_bit_exact(env):
         assert (ids.cpu().numpy().view(np.uint32) == oi).all() and (dists.cpu().numpy() == od).all()
 
 
-@pytest.mark.parametrize("d", [4, 20, 36, 64, 256, 512])
+@pytest.mark.parametrize("d", [1, 4, 6, 20, 30, 36, 64, 100, 256, 300, 512])
 def test_u8_other_dimensions(env, d):
+    """Rows of any byte length: those that are not a multiple of 16 bytes go through the padded
+    copy, queries included."""
     torch, A, O = env
     rng = np.random.default_rng(d)
     n = 1500
     cen = rng.uniform(40, 200, (8, d))
     pts_h = np.clip(np.rint(cen[rng.integers(0, 8, n)] + 15 * rng.standard_normal((n, d))), 0, 255).astype(np.uint8)
+    qs_h = np.clip(np.rint(cen[rng.integers(0, 8, 200)] + 15 * rng.standard_normal((200, d))), 0, 255).astype(np.uint8)
     ds = O.Dataset(pts_h, 0)
     og, s = O.build(ds, 12, 24, 1.2, seed=4, threads=0)
-    g = A.ann_build(dev(torch, pts_h), 12, 24, 1.2, seed=4)
+    pts = dev(torch, pts_h)
+    g = A.ann_build(pts, 12, 24, 1.2, seed=4)
     assert g.info().start == s and (g.neighbors() == og).all()
+    for nq in (200, 37):  # the second call reuses the query buffer of the first
+        ids, dists = A.ann_search(g, pts, dev(torch, qs_h[:nq]), 5, 30)
+        oi, od = O.search_batch(ds, og, s, qs_h[:nq], 5, 30, threads=0)
+        assert (ids.cpu().numpy().view(np.uint32) == oi).all() and (dists.cpu().numpy() == od).all()
+    # one more batch into a graph given from the host: the padded copy is made on first use
+    gg = A.ann_graph_from_host(og, d, A.U8, A.L2SQ, s)
+    ids, _ = A.ann_search(gg, pts, dev(torch, qs_h), 5, 30)
+    assert (ids.cpu().numpy().view(np.uint32) == O.search_batch(ds, og, s, qs_h, 5, 30, threads=0)[0]).all()
 
 
 def _float_distance_check(A, O, torch, w, metric, g_rows, s, L):
