@@ -8,8 +8,8 @@
 // candidate is then recognised as a duplicate of a beam entry or is worse than the beam's last
 // entry, so results do not depend on the table.  A bucket holds four 32-bit ids, or, when the
 // vertex count allows, eight 16-bit tags: the id is passed through a bijection y of its B bits,
-// bucket = floor(top 14 bits of y * buckets / 2^14), tag = the low B - floor(log2 buckets) bits of
-// y (at most 15).  Two ids of one bucket differ by less than 2^B / buckets in y, so equal tags
+// bucket = floor(y * buckets / 2^B), tag = the low B - floor(log2 buckets) bits of y (at most
+// 15).  Two ids of one bucket differ by less than 2^B / buckets in y, so equal tags
 // mean equal ids: a tag match still identifies the vertex exactly while the table remembers
 // twice as many vertices.  The bucket count need not be a power of two; it is chosen so that
 // the wave's LDS lands on an occupancy step.
@@ -24,6 +24,14 @@ namespace annmi {
 __device__ __forceinline__ u32 mix_id(u32 x, u32 mask, u32 bits) {
   (void)bits;
   return __umul24(x, 0x9E3779u) & mask;
+}
+
+// high 16 bits of the 48-bit product of two 24-bit numbers (both operands in vector registers:
+// nothing here reads a scalar register that a vector instruction may just have written)
+__device__ __forceinline__ u32 umulhi24(u32 a, u32 b) {
+  u32 r;
+  asm("v_mul_hi_u32_u24 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
 }
 
 typedef unsigned short us2_t __attribute__((ext_vector_type(2)));
@@ -47,11 +55,12 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
   const bool compact = a.id_bits != 0;  // 16-bit tag mode
   const u32 idmask = compact ? ((1u << a.id_bits) - 1u) : 0u;
   const u32 tagmask = compact ? ((1u << (a.id_bits - (31u - (u32)__builtin_clz(nb)))) - 1u) : 0u;
-  // y -> its top 14 bits (ids of fewer bits are shifted up)
-  const u32 y14r = a.id_bits > 14u ? a.id_bits - 14u : 0u;
-  const u32 y14l = a.id_bits < 14u ? 14u - a.id_bits : 0u;
-  auto bucket_of_y = [=](u32 y) { return __umul24((y >> y14r) << y14l, nb) >> 14; };
-  auto bucket_of_id = [=](u32 x) { return __umul24((x * 0x9E3779B1u) >> 18, nb) >> 14; };
+  // bucket = floor(y * nb / 2^bits), as the high part of a 24 x 24-bit product: (y << (24 - bits))
+  // * (nb << 8) >> 32
+  const u32 yshift = compact ? 24u - a.id_bits : 0u;
+  const u32 nb8 = nb << 8;
+  auto bucket_of_y = [=](u32 y) { return umulhi24(y << yshift, nb8); };
+  auto bucket_of_id = [=](u32 x) { return umulhi24((x * 0x9E3779B1u) >> 8, nb8); };
   const u32 L = a.L;
 
   const u32 qrow = a.qidx ? a.qidx[qi] : qi;
@@ -97,7 +106,6 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
   // where the visited list goes: the search's own slot, later perhaps a spill chunk
   u64* vptr = a.vis != nullptr ? a.vis + (u64)qi * a.vis_cap : nullptr;
   u32 vcap = a.vis_cap;
-  bool vspilled = false, vlost = false;
   if (a.vis_where != nullptr && lane == 0) a.vis_where[qi] = ~0ull;
 
   for (;;) {
@@ -118,10 +126,13 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
     }
     if (pos < 0) break;
     const u32 pstar = key_id(pk);
+    // visited list: (vptr, vcap) are wave-uniform; vptr turns null when the list is lost (it fits
+    // neither its slot nor a spill chunk: the prune kernel sees nv > room and reports it)
     if (vptr != nullptr) {
-      if (nv == vcap && !vlost) {  // uniform: the list is full
-        vlost = true;
-        if (!vspilled && a.spill != nullptr) {
+      if (nv == vcap) {  // the list is full
+        u64* moved = nullptr;
+        u32 newcap = 0;
+        if (vcap == a.vis_cap && a.spill != nullptr) {  // still in its slot: move to a spill chunk
           const u64 need = (u64)vcap + a.spill_chunk;
           unsigned long long off = 0;
           if (lane == 0) off = atomicAdd(a.spill_top, (unsigned long long)need);
@@ -132,14 +143,14 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
             for (u32 i = lane; i < vcap; i += 64)
               dst[i] = __hip_atomic_load(vptr + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (lane == 0) a.vis_where[qi] = off;
-            vptr = dst;
-            vcap = (u32)need;
-            vspilled = true;
-            vlost = false;
+            moved = dst;
+            newcap = (u32)need;
           }
         }
+        vptr = reinterpret_cast<u64*>(readlane_u64(reinterpret_cast<u64>(moved), 0));
+        vcap = readlane_u32(newcap, 0);
       }
-      if (!vlost && lane == 0) vptr[nv] = pk;
+      if (vptr != nullptr && lane == 0) vptr[nv] = pk;
     }
     ++nv;
 
