@@ -388,6 +388,10 @@ struct SmallLds {
   u32 snrm[SM_TMAX];  // norms, sorted
   i32 sthr[SM_TMAX];  // largest D(i,j) that still removes j, sorted
   u32 inv[SM_TMAX];   // sorted position -> arrival index
+  // the entries behind the clean prefix ("new"), by their index among the new entries
+  u32 nnrm[32];  // norms
+  i32 nthr[32];  // largest D that still removes the new entry
+  u32 npos[32];  // sorted positions
 };
 
 template <int VEC, int NCH>
@@ -447,12 +451,65 @@ __device__ __forceinline__ void gram_tile(const unsigned char* Xs, const SmallLd
   gram_tile_regs<RB, CB>(acc, S, colok, ncol, tcol, half, Klo, Khi, std::make_integer_sequence<int, 16>{});
 }
 
-// S.uid[0..total) holds the candidate ids (old row entries first).  Writes the pruned row and
+// The same tile with the NEW entries as rows (new entry t in row t, at most 32 of them) and the
+// sorted candidates 32*CB.. as columns.  Each accumulator register that holds rows below `na`
+// yields two ballots: "new t removes sorted candidate j" (alpha * D <= d(b, j)) and "sorted
+// candidate j removes new t" (alpha * D <= d(b, t)); lane t collects word CB of both masks.
+template <int CB, int R_>
+__device__ __forceinline__ void newrow_tile_reg(const v16i_t& acc, const SmallLds& S, u32 na, bool colok, i32 ncol,
+                                                i32 tcol, u32 half, u32& rem, u32& rby) {
+  constexpr int mlo = 8 * (R_ / 4) + (R_ % 4);
+  if (na > (u32)(8 * (R_ / 4))) {  // uniform: rows 8*(R_/4).. exist
+    const u32 t = (u32)mlo + 4u * half;
+    const bool ok = colok && t < na;
+    const i32 D = (i32)S.nnrm[t] + ncol - 2 * acc[R_];
+    const u64 b1 = ballot(ok && D <= tcol);
+    const u64 b2 = ballot(ok && D <= S.nthr[t]);
+    rem = writelane_pair<mlo, mlo + 4>(rem, b1);
+    rby = writelane_pair<mlo, mlo + 4>(rby, b2);
+  }
+}
+template <int CB, int... Rs>
+__device__ __forceinline__ void newrow_tile_regs(const v16i_t& acc, const SmallLds& S, u32 na, bool colok, i32 ncol,
+                                                 i32 tcol, u32 half, u32& rem, u32& rby,
+                                                 std::integer_sequence<int, Rs...>) {
+  (newrow_tile_reg<CB, Rs>(acc, S, na, colok, ncol, tcol, half, rem, rby), ...);
+}
+template <int CB>
+__device__ __forceinline__ void newrow_tile(const unsigned char* Xs, const SmallLds& S, u32 clean, u32 na, u32 total,
+                                            u32 ksteps, int lane, u32& rem, u32& rby) {
+  const u32 half = (u32)lane >> 5;
+  const u32 t = (u32)lane & 31u;
+  const u32 ib = 32u * CB + t;
+  const u32 ra = clean + (t < na ? t : na - 1u);
+  const u32 rb = ib < total ? S.inv[ib] : 0u;
+  const unsigned char* pa = Xs + ra * SM_STRIDE + 16u * half;
+  const unsigned char* pb = Xs + rb * SM_STRIDE + 16u * half;
+  v4i_t av[4], bv[4];
+#pragma unroll
+  for (u32 ks = 0; ks < 4; ++ks) {
+    const u32 kk = ks < ksteps ? ks : ksteps - 1u;
+    const v4i_t x = *reinterpret_cast<const v4i_t*>(pa + 32u * kk);
+    const v4i_t y = *reinterpret_cast<const v4i_t*>(pb + 32u * kk);
+    av[ks] = ks < ksteps ? x : v4i_t{0, 0, 0, 0};
+    bv[ks] = y;
+  }
+  v16i_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(av[ks], bv[ks], acc, 0, 0, 0);
+  const bool colok = ib < total;
+  const i32 ncol = colok ? (i32)S.snrm[ib] : 0;
+  const i32 tcol = colok ? S.sthr[ib] : -1;
+  newrow_tile_regs<CB>(acc, S, na, colok, ncol, tcol, half, rem, rby, std::make_integer_sequence<int, 16>{});
+}
+
+// S.uid[0..total) holds the candidate ids (old row entries first), the first `clean` of which
+// are the row's clean prefix: sorted, none removing another.  Writes the pruned row and
 // returns its length.
 template <int KIND, int VEC, int NCH>
 __device__ __forceinline__ u32 reprune_small_int(const VecTable& T, const QueryRegs<KIND, VEC, NCH>& Q,
-                                                 unsigned char* Xs, SmallLds& S, u32 total, u32 R, i64 a16,
-                                                 u32* row, int lane) {
+                                                 unsigned char* Xs, SmallLds& S, u32 total, u32 clean, u32 R,
+                                                 i64 a16, u32* row, int lane) {
   // every pass of eight candidates is requested before the first is used (a pass is at most
   // four registers here): one trip to memory for the whole list
   constexpr int PB = SM_TMAX / 8;
@@ -501,36 +558,139 @@ __device__ __forceinline__ u32 reprune_small_int(const VecTable& T, const QueryR
   }
   __syncthreads();
 
-  // rank of every candidate under (distance, id); keys are distinct
+  // rank of every candidate under (distance, id); keys are distinct.  With at most 32 entries
+  // behind the clean prefix only those are compared against everything: a clean entry's rank is
+  // its place in the prefix plus the new entries below it.
+  const u32 na = total - clean;
+  const bool by_new_rows = na <= 32u;
   {
     const u32 j0 = lane, j1 = lane + 64;
     const u64 k0 = j0 < total ? S.key[j0] : KEY_INF;
     const u64 k1 = j1 < total ? S.key[j1] : KEY_INF;
     u32 r0 = 0, r1 = 0;
-    for (u32 i = 0; i < total; ++i) {
-      const u64 ki = S.key[i];
-      r0 += ki < k0 ? 1u : 0u;
-      r1 += ki < k1 ? 1u : 0u;
+    if (by_new_rows) {
+      const bool c0 = j0 < clean, c1 = j1 < clean;
+      u32 below0 = 0, below1 = 0;  // for a new entry: clean entries below it
+      for (u32 k = clean; k < total; ++k) {
+        const u64 kk = S.key[k];
+        const bool g0 = kk < k0, g1 = kk < k1;
+        r0 += g0 ? 1u : 0u;
+        r1 += g1 ? 1u : 0u;
+        const u32 above = (u32)__builtin_popcountll(ballot(g0 && c0)) + (u32)__builtin_popcountll(ballot(g1 && c1));
+        if (j0 == k) below0 = clean - above;
+        if (j1 == k) below1 = clean - above;
+      }
+      r0 += c0 ? j0 : below0;
+      r1 += c1 ? j1 : below1;
+    } else {
+      for (u32 i = 0; i < total; ++i) {
+        const u64 ki = S.key[i];
+        r0 += ki < k0 ? 1u : 0u;
+        r1 += ki < k1 ? 1u : 0u;
+      }
     }
     if (j0 < total) {
+      const i32 thr = alpha_threshold(int_from_dkey(key_dkey(k0)), a16);
       S.sid[r0] = key_id(k0);
       S.snrm[r0] = S.nrm[j0];
-      S.sthr[r0] = alpha_threshold(int_from_dkey(key_dkey(k0)), a16);
+      S.sthr[r0] = thr;
       S.inv[r0] = j0;
+      if (by_new_rows && j0 >= clean) {
+        S.nnrm[j0 - clean] = S.nrm[j0];
+        S.nthr[j0 - clean] = thr;
+        S.npos[j0 - clean] = r0;
+      }
     }
     if (j1 < total) {
+      const i32 thr = alpha_threshold(int_from_dkey(key_dkey(k1)), a16);
       S.sid[r1] = key_id(k1);
       S.snrm[r1] = S.nrm[j1];
-      S.sthr[r1] = alpha_threshold(int_from_dkey(key_dkey(k1)), a16);
+      S.sthr[r1] = thr;
       S.inv[r1] = j1;
+      if (by_new_rows && j1 >= clean) {
+        S.nnrm[j1 - clean] = S.nrm[j1];
+        S.nthr[j1 - clean] = thr;
+        S.npos[j1 - clean] = r1;
+      }
     }
   }
   __syncthreads();
 
-  // Gram matrix tile by tile; K0[c] of lane i = bits "sorted candidate i removes candidate 32c+j",
-  // K1 the same for candidates 64..95 (only column block 2 matters there)
   const u32 nb = (total + 31u) >> 5;
   const u32 ksteps = (u32)((T.row_bytes + 31) / 32);
+  if (by_new_rows) {
+    // distances between the new entries and everything, reduced at once to two 96-bit masks per
+    // new entry (lane t: new entry t)
+    u32 REM[3] = {0u, 0u, 0u}, RBY[3] = {0u, 0u, 0u};
+    newrow_tile<0>(Xs, S, clean, na, total, ksteps, lane, REM[0], RBY[0]);
+    if (nb > 1) newrow_tile<1>(Xs, S, clean, na, total, ksteps, lane, REM[1], RBY[1]);
+    if (nb > 2) newrow_tile<2>(Xs, S, clean, na, total, ksteps, lane, REM[2], RBY[2]);
+    const u32 mypos = (u32)lane < na ? S.npos[lane] : 0xFFFFFFFFu;
+
+    // replay of the scan of prune() on positions of the sorted list: the clean entries are all
+    // selected until a selected new entry in front of them removes them; the new entries are
+    // decided in sorted order
+    const u32 nlo = total < 64u ? total : 64u;
+    u64 sel_lo = nlo == 64u ? ~0ull : ((1ull << nlo) - 1ull);
+    u32 sel_hi = total > 64u ? ((total - 64u) >= 32u ? ~0u : ((1u << (total - 64u)) - 1u)) : 0u;
+    u64 new_lo = 0;  // positions held by new entries
+    u32 new_hi = 0;
+    for (u32 t = 0; t < na; ++t) {
+      const u32 p = readlane_u32(mypos, (int)t);
+      if (p < 64u)
+        new_lo |= 1ull << p;
+      else
+        new_hi |= 1u << (p - 64u);
+    }
+    sel_lo &= ~new_lo;
+    sel_hi &= ~new_hi;
+    u64 todo_lo = new_lo;
+    u32 todo_hi = new_hi;
+    while (todo_lo != 0 || todo_hi != 0) {
+      u32 p;
+      if (todo_lo != 0) {
+        p = (u32)__builtin_ctzll(todo_lo);
+        todo_lo &= todo_lo - 1ull;
+      } else {
+        p = 64u + (u32)__builtin_ctz(todo_hi);
+        todo_hi &= todo_hi - 1u;
+      }
+      const int t = __builtin_ctzll(ballot(mypos == p));  // the new entry at position p
+      const u64 before_lo = p >= 64u ? ~0ull : ((1ull << p) - 1ull);
+      const u32 before_hi = p >= 64u ? ((1u << (p - 64u)) - 1u) : 0u;
+      const u64 rby_lo = (u64)readlane_u32(RBY[0], t) | ((u64)readlane_u32(RBY[1], t) << 32);
+      const u32 rby_hi = readlane_u32(RBY[2], t);
+      const bool killed = ((rby_lo & sel_lo & before_lo) | (u64)(rby_hi & sel_hi & before_hi)) != 0;
+      if (!killed) {
+        const u64 rem_lo = (u64)readlane_u32(REM[0], t) | ((u64)readlane_u32(REM[1], t) << 32);
+        const u32 rem_hi = readlane_u32(REM[2], t);
+        sel_lo &= ~(rem_lo & ~before_lo);
+        sel_hi &= ~(rem_hi & ~before_hi);
+        if (p < 64u)
+          sel_lo |= 1ull << p;
+        else
+          sel_hi |= 1u << (p - 64u);
+      }
+    }
+    // the first R selected positions, in order
+    const u32 cnt_lo = (u32)__builtin_popcountll(sel_lo);
+    const u32 nsel = cnt_lo + (u32)__builtin_popcount(sel_hi);
+    const u32 nout = nsel < R ? nsel : R;
+    if ((sel_lo >> lane) & 1ull) {
+      const u32 at = (u32)__builtin_popcountll(sel_lo & lanemask_lt(lane));
+      if (at < R) row[at] = S.sid[lane];
+    }
+    if (lane < 32 && ((sel_hi >> lane) & 1u)) {
+      const u32 at = cnt_lo + (u32)__builtin_popcount(sel_hi & ((1u << lane) - 1u));
+      if (at < R) row[at] = S.sid[64 + lane];
+    }
+    for (u32 j = nout + lane; j < R; j += 64) row[j] = NONE_ID;
+    __syncthreads();
+    return nout;
+  }
+
+  // Gram matrix tile by tile; K0[c] of lane i = bits "sorted candidate i removes candidate 32c+j",
+  // K1 the same for candidates 64..95 (only column block 2 matters there)
   u32 K0[3] = {0u, 0u, 0u};
   u32 K1 = 0u;
   gram_tile<0, 0>(Xs, S, total, ksteps, lane, K0[0], K1);
@@ -591,14 +751,14 @@ __global__ __launch_bounds__(64) void merge_gram_kernel(MergeArgs a, VecTable T)
     for (u32 it = blockIdx.x; it < nitems; it += gridDim.x) {
       const MergeItem item = a.list_items[1][it];
       const u32 i0 = item.i0, cnt = item.cnt, b = item.b;
-      const u32 deg = meta_deg(item.meta);
+      const u32 deg = meta_deg(item.meta), clean = meta_clean(item.meta);
       const u32 total = deg + cnt;
       u32* row = a.graph + (u64)b * a.R;
       for (u32 j = lane; j < total; j += 64)
         small.uid[j] = j < deg ? row[j] : (u32)(a.keys[i0 + (j - deg)] & 0xFFFFFFFFull);
       __syncthreads();
       const QueryRegs<KIND, VEC, NCH> Qb = load_query<KIND, VEC, NCH>(T.base + (u64)b * T.row_bytes, T.npieces, lane);
-      const u32 kept = reprune_small_int<KIND, VEC, NCH>(T, Qb, Xs, small, total, a.R, a.a16, row, lane);
+      const u32 kept = reprune_small_int<KIND, VEC, NCH>(T, Qb, Xs, small, total, clean, a.R, a.a16, row, lane);
       if (lane == 0) a.meta[b] = make_meta(kept, kept);
       ++n_rep;
       n_edges += cnt;
