@@ -456,28 +456,29 @@ __device__ __forceinline__ void gram_tile(const unsigned char* Xs, const SmallLd
 // yields two ballots: "new t removes sorted candidate j" (alpha * D <= d(b, j)) and "sorted
 // candidate j removes new t" (alpha * D <= d(b, t)); lane t collects word CB of both masks.
 template <int CB, int R_>
-__device__ __forceinline__ void newrow_tile_reg(const v16i_t& acc, const SmallLds& S, u32 na, bool colok, i32 ncol,
-                                                i32 tcol, u32 half, u32& rem, u32& rby) {
+__device__ __forceinline__ void newrow_tile_reg(const v16i_t& acc, const i32 (&rown)[16], const i32 (&rowt)[16], u32 na,
+                                                bool colok, i32 ncol, i32 tcol, u32 half, u32& rem, u32& rby) {
   constexpr int mlo = 8 * (R_ / 4) + (R_ % 4);
   if (na > (u32)(8 * (R_ / 4))) {  // uniform: rows 8*(R_/4).. exist
     const u32 t = (u32)mlo + 4u * half;
     const bool ok = colok && t < na;
-    const i32 D = (i32)S.nnrm[t] + ncol - 2 * acc[R_];
+    const i32 D = rown[R_] + ncol - 2 * acc[R_];
     const u64 b1 = ballot(ok && D <= tcol);
-    const u64 b2 = ballot(ok && D <= S.nthr[t]);
+    const u64 b2 = ballot(ok && D <= rowt[R_]);
     rem = writelane_pair<mlo, mlo + 4>(rem, b1);
     rby = writelane_pair<mlo, mlo + 4>(rby, b2);
   }
 }
 template <int CB, int... Rs>
-__device__ __forceinline__ void newrow_tile_regs(const v16i_t& acc, const SmallLds& S, u32 na, bool colok, i32 ncol,
-                                                 i32 tcol, u32 half, u32& rem, u32& rby,
+__device__ __forceinline__ void newrow_tile_regs(const v16i_t& acc, const i32 (&rown)[16], const i32 (&rowt)[16], u32 na,
+                                                 bool colok, i32 ncol, i32 tcol, u32 half, u32& rem, u32& rby,
                                                  std::integer_sequence<int, Rs...>) {
-  (newrow_tile_reg<CB, Rs>(acc, S, na, colok, ncol, tcol, half, rem, rby), ...);
+  (newrow_tile_reg<CB, Rs>(acc, rown, rowt, na, colok, ncol, tcol, half, rem, rby), ...);
 }
 template <int CB>
-__device__ __forceinline__ void newrow_tile(const unsigned char* Xs, const SmallLds& S, u32 clean, u32 na, u32 total,
-                                            u32 ksteps, int lane, u32& rem, u32& rby) {
+__device__ __forceinline__ void newrow_tile(const unsigned char* Xs, const SmallLds& S, const i32 (&rown)[16],
+                                            const i32 (&rowt)[16], u32 clean, u32 na, u32 total, u32 ksteps, int lane,
+                                            u32& rem, u32& rby) {
   const u32 half = (u32)lane >> 5;
   const u32 t = (u32)lane & 31u;
   const u32 ib = 32u * CB + t;
@@ -500,7 +501,7 @@ __device__ __forceinline__ void newrow_tile(const unsigned char* Xs, const Small
   const bool colok = ib < total;
   const i32 ncol = colok ? (i32)S.snrm[ib] : 0;
   const i32 tcol = colok ? S.sthr[ib] : -1;
-  newrow_tile_regs<CB>(acc, S, na, colok, ncol, tcol, half, rem, rby, std::make_integer_sequence<int, 16>{});
+  newrow_tile_regs<CB>(acc, rown, rowt, na, colok, ncol, tcol, half, rem, rby, std::make_integer_sequence<int, 16>{});
 }
 
 // S.uid[0..total) holds the candidate ids (old row entries first), the first `clean` of which
@@ -536,17 +537,27 @@ __device__ __forceinline__ u32 reprune_small_int(const VecTable& T, const QueryR
     }
 #pragma unroll
     for (int tt = 0; tt < PB; ++tt) {
+      if (t0 + tt >= npass) break;  // uniform
       const u32 c = 8u * (t0 + tt) + grp;
       const u32 dk = distance_key<KIND, VEC, NCH>(Q, x[tt]);
       i32 nn = 0;
 #pragma unroll
       for (int u = 0; u < NCH; ++u) {
         const u32 pc = sub + LPC * u;
+        u32 wv[VEC / 4];
 #pragma unroll
         for (int i = 0; i < VEC / 4; ++i) {
-          const u32 wv = pc < T.npieces ? (x[tt][u].w[i] ^ flip) : 0u;
-          nn = __builtin_amdgcn_sdot4((i32)wv, (i32)wv, nn, false);
-          if (c < total) *reinterpret_cast<u32*>(Xs + c * SM_STRIDE + pc * VEC + 4 * i) = wv;
+          wv[i] = pc < T.npieces ? (x[tt][u].w[i] ^ flip) : 0u;
+          nn = __builtin_amdgcn_sdot4((i32)wv[i], (i32)wv[i], nn, false);
+        }
+        if (c < total) {
+          unsigned char* dst = Xs + c * SM_STRIDE + pc * VEC;
+          if constexpr (VEC == 16) {
+            *reinterpret_cast<uint4*>(dst) = make_uint4(wv[0], wv[1], wv[2], wv[3]);
+          } else {
+#pragma unroll
+            for (int i = 0; i < VEC / 4; ++i) *reinterpret_cast<u32*>(dst + 4 * i) = wv[i];
+          }
         }
       }
       nn = group_sum(nn);
@@ -622,9 +633,22 @@ __device__ __forceinline__ u32 reprune_small_int(const VecTable& T, const QueryR
     // distances between the new entries and everything, reduced at once to two 96-bit masks per
     // new entry (lane t: new entry t)
     u32 REM[3] = {0u, 0u, 0u}, RBY[3] = {0u, 0u, 0u};
-    newrow_tile<0>(Xs, S, clean, na, total, ksteps, lane, REM[0], RBY[0]);
-    if (nb > 1) newrow_tile<1>(Xs, S, clean, na, total, ksteps, lane, REM[1], RBY[1]);
-    if (nb > 2) newrow_tile<2>(Xs, S, clean, na, total, ksteps, lane, REM[2], RBY[2]);
+    // norm and threshold of the row each accumulator register holds in this lane (the same in
+    // every tile); rows that do not exist are never looked at
+    i32 rown[16], rowt[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      rown[r] = 0;
+      rowt[r] = -1;
+      if (na > (u32)(8 * (r / 4))) {  // uniform
+        const u32 t = (u32)(8 * (r / 4) + (r % 4)) + 4u * ((u32)lane >> 5);
+        rown[r] = (i32)S.nnrm[t];
+        rowt[r] = S.nthr[t];
+      }
+    }
+    newrow_tile<0>(Xs, S, rown, rowt, clean, na, total, ksteps, lane, REM[0], RBY[0]);
+    if (nb > 1) newrow_tile<1>(Xs, S, rown, rowt, clean, na, total, ksteps, lane, REM[1], RBY[1]);
+    if (nb > 2) newrow_tile<2>(Xs, S, rown, rowt, clean, na, total, ksteps, lane, REM[2], RBY[2]);
     const u32 mypos = (u32)lane < na ? S.npos[lane] : 0xFFFFFFFFu;
 
     // replay of the scan of prune() on positions of the sorted list: the clean entries are all
