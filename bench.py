@@ -163,23 +163,27 @@ def main():
 
     # timed steps
     torch.cuda.synchronize()
-    step_ms, build_ms, stats_list = [], [], []
+    step_ms, build_ms = [], []
     g = None
     for _ in range(args.steps):
         if g is not None:
             del g
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        g = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, metric=metric, collect_stats=True)
+        g = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, metric=metric)
         t1 = time.perf_counter()
-        stats_list.append(g.stats())  # before the query search adds to the counters
         A.ann_search(g, pts, qs, k, L90)
         torch.cuda.synchronize()
         t2 = time.perf_counter()
         build_ms.append((t1 - t0) * 1e3)
         step_ms.append((t2 - t0) * 1e3)
         say(f"timed build: {(t1 - t0) * 1e3:.1f} ms")
-    st = stats_list[-1]
+    # one more build, untimed, with the library's counters and per-phase events switched on (they
+    # cost about 2 % of the build time): the source of the roofline figures
+    gs = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, metric=metric, collect_stats=True)
+    st = gs.stats()
+    del gs
+    say("build with statistics done")
     ms_per_step = float(np.mean(step_ms))
     bms = float(np.mean(build_ms))
     points_per_s = w.n / (bms / 1e3)

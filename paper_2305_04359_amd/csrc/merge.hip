@@ -908,8 +908,14 @@ static hipError_t launch_merge_t(const MergeArgs& a, const VecTable& T, u32 grid
                             : ((a.R * 8u + 15u) & ~15u) + 8u * stage_stride(T.row_bytes) + 32u + a.stage_bytes;
   const u32 grid_generic = grid < 1024u ? grid : 1024u;
   hipLaunchKernelGGL((merge_generic_kernel<KIND, VEC, NCH>), dim3(grid_generic), dim3(64), lds, s_generic, a, T);
-  if (a.gram_ok) hipLaunchKernelGGL((merge_gram_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), 0, s_gram, a, T);
-  hipLaunchKernelGGL((merge_fast_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), 0, s, a, T);
+  // the caller's stream takes the kernel that usually ends last, so that its waits for the other
+  // two streams are already satisfied when it reaches them
+  if (a.gram_ok) {
+    hipLaunchKernelGGL((merge_fast_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), 0, s_gram, a, T);
+    hipLaunchKernelGGL((merge_gram_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), 0, s, a, T);
+  } else {
+    hipLaunchKernelGGL((merge_fast_kernel<KIND, VEC, NCH>), dim3(grid), dim3(64), 0, s, a, T);
+  }
   return hipGetLastError();
 }
 
