@@ -10,6 +10,7 @@
 #include <ctime>
 #include <new>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "../../include/ann.h"
@@ -723,6 +724,32 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
   g->spill_keys = o.spill_cap;
   HIP_TRY(hipMemsetAsync(g->rows, 0xFF, (size_t)n * R * sizeof(u32), st));
 
+  // Insertion order: the ids other than s, shuffled (Fisher-Yates driven by SplitMix64).  The
+  // shuffle moves positions, whatever they hold, so it runs on the positions 0..m-1 on a host
+  // thread while the GPU finds s; position j then stands for the j-th id other than s.
+  const u64 m = n - 1;
+  std::vector<u32> order(m ? m : 1);
+  std::thread shuffler;
+  if (!o.order) {
+    shuffler = std::thread([&order, m, seed] {
+      for (u64 i = 0; i < m; ++i) order[i] = (u32)i;
+      u64 state = seed;
+      for (u64 i = m; i-- > 1;) {
+        const u64 r = splitmix64(state);
+        const u64 j = (u64)(((unsigned __int128)r * (unsigned __int128)(i + 1)) >> 64);
+        const u32 t = order[i];
+        order[i] = order[j];
+        order[j] = t;
+      }
+    });
+  }
+  struct Joiner {
+    std::thread& t;
+    ~Joiner() {
+      if (t.joinable()) t.join();
+    }
+  } joiner{shuffler};
+
   // start vertex s: present from the beginning with an empty row, never inserted again
   if (o.use_start) {
     if (o.start >= n) return fail(ANN_EINVAL, "start vertex out of range");
@@ -734,9 +761,6 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
   }
 
   const double t_start = now_ms();
-  // insertion order: the ids other than s, shuffled (Fisher-Yates driven by SplitMix64)
-  const u64 m = n - 1;
-  std::vector<u32> order(m ? m : 1);
   if (o.order) {
     std::vector<unsigned char> seen(n, 0);
     for (u64 i = 0; i < m; ++i) {
@@ -746,17 +770,9 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
       order[i] = id;
     }
   } else {
-    u64 k = 0;
-    for (u64 i = 0; i < n; ++i)
-      if (i != g->start) order[k++] = (u32)i;
-    u64 state = seed;
-    for (u64 i = m; i-- > 1;) {
-      const u64 r = splitmix64(state);
-      const u64 j = (u64)(((unsigned __int128)r * (unsigned __int128)(i + 1)) >> 64);
-      const u32 t = order[i];
-      order[i] = order[j];
-      order[j] = t;
-    }
+    shuffler.join();
+    const u32 s = g->start;
+    for (u64 i = 0; i < m; ++i) order[i] += order[i] >= s ? 1u : 0u;
   }
 
   const double t_order = now_ms();

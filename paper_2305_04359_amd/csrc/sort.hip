@@ -76,39 +76,38 @@ __global__ __launch_bounds__(256) void rs_rowscan_kernel(u32* hist, u32 tiles, u
   if (t == 255) digit_total[blockIdx.x] = part[255];
 }
 
-// ... and one workgroup turns the RS_RADIX totals into the first output index of each digit.
-// (A "last workgroup does it" ticket inside the row scan was tried: RS_RADIX atomics on one
-// address cost more than this extra launch.)
-__global__ __launch_bounds__(256) void rs_digitscan_kernel(u32* digit_total) {
-  __shared__ u32 part[256];
-  const u32 t = threadIdx.x;
-  constexpr u32 PT = RS_RADIX / 256;
-  u32 v[PT], sum = 0;
-  for (u32 k = 0; k < PT; ++k) {
-    v[k] = digit_total[t * PT + k];
-    sum += v[k];
-  }
-  part[t] = sum;
-  __syncthreads();
-  for (u32 off = 1; off < 256; off <<= 1) {
-    const u32 w = t >= off ? part[t - off] : 0u;
-    __syncthreads();
-    part[t] += w;
-    __syncthreads();
-  }
-  u32 base = t ? part[t - 1] : 0u;
-  for (u32 k = 0; k < PT; ++k) {
-    digit_total[t * PT + k] = base;
-    base += v[k];
-  }
-}
-
+// ... and every scatter workgroup turns the RS_RADIX totals into the first output index of each
+// digit for itself (an exclusive scan of 1,024 numbers in LDS costs a microsecond; a kernel of
+// its own for it cost six, and a "last workgroup does it" ticket inside the row scan more still:
+// RS_RADIX atomics on one address).
 __global__ __launch_bounds__(64) void rs_scatter_kernel(const u64* keys, u64* out, u64 count, u64 tile_keys,
                                                         u32 tiles, u32 shift, u32 mask, u32 nbits,
-                                                        const u32* hist, const u32* digit_base) {
+                                                        const u32* hist, const u32* digit_total) {
   __shared__ u32 base[RS_RADIX];
   const int lane = threadIdx.x;
-  for (u32 i = lane; i < RS_RADIX; i += 64) base[i] = digit_base[i] + hist[(u64)i * tiles + blockIdx.x];
+  {
+    // exclusive scan of the digit totals: lane l owns digits [PL*l, PL*(l+1))
+    constexpr u32 PL = RS_RADIX / 64;
+    u32 v[PL], sum = 0;
+#pragma unroll
+    for (u32 k = 0; k < PL; ++k) {
+      v[k] = digit_total[PL * lane + k];
+      sum += v[k];
+    }
+    u32 incl = sum;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const u32 o = (u32)__shfl_up((int)incl, off, 64);
+      if (lane >= off) incl += o;
+    }
+    u32 run = incl - sum;
+#pragma unroll
+    for (u32 k = 0; k < PL; ++k) {
+      const u32 dgt = PL * lane + k;
+      base[dgt] = run + hist[(u64)dgt * tiles + blockIdx.x];
+      run += v[k];
+    }
+  }
   __syncthreads();
   const u64 lo = (u64)blockIdx.x * tile_keys;
   const u64 hi = lo + tile_keys < count ? lo + tile_keys : count;
@@ -153,7 +152,6 @@ hipError_t radix_sort_edges(u64* keys, u64* tmp, u32* hist, u64 hist_entries, u6
     hipLaunchKernelGGL(rs_hist_kernel, dim3(tiles), dim3(64), 0, s, src, count, tile_keys, tiles, shift, mask, hist);
     u32* digit_total = hist + (u64)RS_RADIX * tiles;
     hipLaunchKernelGGL(rs_rowscan_kernel, dim3(RS_RADIX), dim3(256), 0, s, hist, tiles, digit_total);
-    hipLaunchKernelGGL(rs_digitscan_kernel, dim3(1), dim3(256), 0, s, digit_total);
     hipLaunchKernelGGL(rs_scatter_kernel, dim3(tiles), dim3(64), 0, s, src, dst, count, tile_keys, tiles, shift,
                        mask, nb, hist, digit_total);
     hipError_t e = hipGetLastError();
