@@ -706,31 +706,13 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
     return ts.tv_sec * 1e3 + ts.tv_nsec / 1e6;
   };
   const double t_begin = now_ms();
-  ann_graph* g = nullptr;
-  int rc = new_graph(n, d, dtype, metric, R, &g);
-  if (rc) return rc;
-  struct Guard {
-    ann_graph* g;
-    ~Guard() {
-      if (g) ann_graph_free(g);
-    }
-  } guard{g};
-  rc = check_insert_params(g, L, alpha);
-  if (rc) return rc;
-  g->collect = o.collect_stats != 0;
-  g->hash_bits = o.hash_bits;
-  if (g->hash_bits && (g->hash_bits < 4 || g->hash_bits > 13)) return fail(ANN_EINVAL, "hash_bits must be in [4, 13]");
-  g->visited_cap = o.visited_cap;
-  g->spill_keys = o.spill_cap;
-  HIP_TRY(hipMemsetAsync(g->rows, 0xFF, (size_t)n * R * sizeof(u32), st));
-
   // Insertion order: the ids other than s, shuffled (Fisher-Yates driven by SplitMix64).  The
   // shuffle moves positions, whatever they hold, so it runs on the positions 0..m-1 on a host
-  // thread while the GPU finds s; position j then stands for the j-th id other than s.
-  const u64 m = n - 1;
-  std::vector<u32> order(m ? m : 1);
+  // thread while the graph is allocated and the GPU finds s; position j then stands for the j-th id other than s.
+  const u64 m = n ? n - 1 : 0;
+  std::vector<u32> order(m && n < (1ull << 31) ? m : 1);
   std::thread shuffler;
-  if (!o.order) {
+  if (!o.order && n >= 1 && n < (1ull << 31)) {
     shuffler = std::thread([&order, m, seed] {
       for (u64 i = 0; i < m; ++i) order[i] = (u32)i;
       u64 state = seed;
@@ -749,6 +731,49 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
       if (t.joinable()) t.join();
     }
   } joiner{shuffler};
+
+  ann_graph* g = nullptr;
+  int rc = new_graph(n, d, dtype, metric, R, &g);
+  if (rc) return rc;
+  struct Guard {
+    ann_graph* g;
+    ~Guard() {
+      if (g) ann_graph_free(g);
+    }
+  } guard{g};
+  rc = check_insert_params(g, L, alpha);
+  if (rc) return rc;
+  g->collect = o.collect_stats != 0;
+  g->hash_bits = o.hash_bits;
+  if (g->hash_bits && (g->hash_bits < 4 || g->hash_bits > 13)) return fail(ANN_EINVAL, "hash_bits must be in [4, 13]");
+  g->visited_cap = o.visited_cap;
+  g->spill_keys = o.spill_cap;
+  HIP_TRY(hipMemsetAsync(g->rows, 0xFF, (size_t)n * R * sizeof(u32), st));
+
+  // (scratch is allocated here, while the shuffle runs)
+  // batches of 2, 4, 8, ... points, never more than theta
+  u64 theta = o.batch_cap ? o.batch_cap : (n / 50 > 1 ? n / 50 : 1);
+  if (theta * R >= (1ull << 32)) theta = ((1ull << 32) - 1) / R;
+  std::vector<u64> bounds{0};
+  for (u64 done = 0; done < m;) {
+    u64 size = done + 2;
+    if (size > theta) size = theta;
+    if (size > m - done) size = m - done;
+    done += size;
+    bounds.push_back(done);
+  }
+  u64 bmax = 1;
+  for (size_t r = 0; r + 1 < bounds.size(); ++r) bmax = bounds[r + 1] - bounds[r] > bmax ? bounds[r + 1] - bounds[r] : bmax;
+
+  DevBuf order_dev;
+  HIP_TRY(order_dev.alloc(m * 4));
+  BatchScratch S;
+  const u32 cap = g->visited_cap ? g->visited_cap : (4 * L > 256 ? 4 * L : 256);
+  rc = S.alloc(bmax, R, cap, g->spill_keys ? g->spill_keys : default_spill_keys(bmax));
+  if (rc) return rc;
+  PhaseTimer tm;
+  rc = tm.init(g->collect);
+  if (rc) return rc;
 
   // start vertex s: present from the beginning with an empty row, never inserted again
   if (o.use_start) {
@@ -776,31 +801,7 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
   }
 
   const double t_order = now_ms();
-  // batches of 2, 4, 8, ... points, never more than theta
-  u64 theta = o.batch_cap ? o.batch_cap : (n / 50 > 1 ? n / 50 : 1);
-  if (theta * R >= (1ull << 32)) theta = ((1ull << 32) - 1) / R;
-  std::vector<u64> bounds{0};
-  for (u64 done = 0; done < m;) {
-    u64 size = done + 2;
-    if (size > theta) size = theta;
-    if (size > m - done) size = m - done;
-    done += size;
-    bounds.push_back(done);
-  }
-  u64 bmax = 1;
-  for (size_t r = 0; r + 1 < bounds.size(); ++r) bmax = bounds[r + 1] - bounds[r] > bmax ? bounds[r + 1] - bounds[r] : bmax;
-
-  DevBuf order_dev;
-  HIP_TRY(order_dev.alloc(m * 4));
   if (m) HIP_TRY(hipMemcpyAsync(order_dev.p, order.data(), m * 4, hipMemcpyHostToDevice, st));
-  BatchScratch S;
-  const u32 cap = g->visited_cap ? g->visited_cap : (4 * L > 256 ? 4 * L : 256);
-  rc = S.alloc(bmax, R, cap, g->spill_keys ? g->spill_keys : default_spill_keys(bmax));
-  if (rc) return rc;
-  PhaseTimer tm;
-  rc = tm.init(g->collect);
-  if (rc) return rc;
-
   const void* pts = nullptr;
   rc = resolve_points(g, points_dev, st, &pts);
   if (rc) return rc;

@@ -786,7 +786,8 @@ __global__ __launch_bounds__(64) void merge_gram_kernel(MergeArgs a, VecTable T)
       if (lane == 0) a.meta[b] = make_meta(kept, kept);
       ++n_rep;
       n_edges += cnt;
-      n_pair += (unsigned long long)total * (total + 1) / 2;
+      // pairs whose distance was formed: all of them, or only those with a new entry in them
+      n_pair += total - clean <= 32u ? (unsigned long long)(total - clean) * total : (unsigned long long)total * (total + 1) / 2;
     }
     if (a.counters != nullptr && lane == 0 && n_rep) {
       atomicAdd(&block_counters(a.counters)->reprunes, n_rep);
