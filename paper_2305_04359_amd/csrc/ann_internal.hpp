@@ -45,7 +45,8 @@ struct SearchArgs {
   u32* batch_counters;  // build only: the batch's counter words (overflow count [0], arena top [4..5], work
                         // list lengths [8..10]); workgroup 0 zeroes them for the steps that follow
   u32 hash_buckets;  // 16-byte buckets of the visited filter (any count from 4 to 2048)
-  u32 id_bits;       // > 0: the filter stores 16-bit tags of ids that fit in this many bits
+  u32 id_bits;       // > 0: the filter stores tags of ids that fit in this many bits ...
+  u32 tag_width;     // ... eight of 16 bits or six of 21 bits per bucket (0: four 32-bit ids)
   // build: visited list, one slot of vis_cap keys per search (may be null).  A search that
   // outgrows its slot moves its list to a chunk of vis_cap + spill_chunk keys taken from `spill`
   // (if given) and records the chunk's offset in vis_where[search] (~0 = still in its slot).
@@ -150,6 +151,7 @@ hipError_t start_vertex_device(const void* points, u64 n, u32 d, int dtype, hipS
 
 u32 search_lds_bytes(u32 L, u32 hash_buckets);
 u32 search_hash_buckets(u32 L, u32 hash_bits);  // hash_bits: the caller's explicit choice, or 0
-u32 compact_id_bits(u64 n, u32 hash_buckets);  // 0 when 16-bit tags cannot identify every vertex
+// how the visited filter stores vertices of a graph of n points: fills id_bits and tag_width
+void search_filter_mode(u64 n, u32 hash_buckets, u32* id_bits, u32* tag_width);
 
 }  // namespace annmi

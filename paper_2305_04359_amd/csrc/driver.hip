@@ -348,7 +348,7 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   sa.L = L;
   sa.k = 1;
   sa.hash_buckets = search_hash_buckets(L, g->hash_bits);
-  sa.id_bits = compact_id_bits(g->n, sa.hash_buckets);
+  search_filter_mode(g->n, sa.hash_buckets, &sa.id_bits, &sa.tag_width);
   sa.batch_counters = small;
   sa.vis = S.vis.as<u64>();
   sa.nvis = S.nvis.as<u32>();
@@ -869,7 +869,7 @@ int ann_search(const ann_graph* g, const void* points_dev, const void* queries_d
   sa.L = L;
   sa.k = k;
   sa.hash_buckets = search_hash_buckets(L, g->hash_bits);
-  sa.id_bits = compact_id_bits(g->n, sa.hash_buckets);
+  search_filter_mode(g->n, sa.hash_buckets, &sa.id_bits, &sa.tag_width);
   sa.out_ids = ids_dev;
   sa.out_dists = dists_dev;
   sa.counters = g->collect ? g->counters : nullptr;

@@ -7,23 +7,23 @@
 // entry first: a lost entry only causes a repeated distance evaluation, and the repeated
 // candidate is then recognised as a duplicate of a beam entry or is worse than the beam's last
 // entry, so results do not depend on the table.  A bucket holds four 32-bit ids, or, when the
-// vertex count allows, eight 16-bit tags: the id is passed through a bijection y of its B bits,
-// bucket = floor(y * buckets / 2^B), tag = the low B - floor(log2 buckets) bits of y (at most
-// 15).  Two ids of one bucket differ by less than 2^B / buckets in y, so equal tags
-// mean equal ids: a tag match still identifies the vertex exactly while the table remembers
-// twice as many vertices.  The bucket count need not be a power of two; it is chosen so that
-// the wave's LDS lands on an occupancy step.
+// vertex count allows, eight 16-bit or six 21-bit tags: the id is passed through a bijection y
+// of its B bits, bucket = floor(y * buckets / 2^B) (from the top 24 bits of y), tag = the low
+// B - floor(log2 buckets) bits of y (at most 15, or 20).  Two ids of one bucket differ by less
+// than 2^B / buckets in y, so equal tags mean equal ids: a tag match still identifies the vertex
+// exactly while the table remembers up to twice as many vertices.  The bucket count need not be
+// a power of two; it is chosen so that the wave's LDS lands on an occupancy step.
 #include "ann_device.hpp"
 #include "ann_internal.hpp"
 #include "ann_dispatch.hpp"
 
 namespace annmi {
 
-// a bijection of the low `bits` <= 24 bits: multiplication by an odd constant modulo 2^bits
-// (its top bits, which choose the bucket, depend on all bits of x)
+// a bijection of the low `bits` bits: multiplication by an odd constant modulo 2^bits (its top
+// bits, which choose the bucket, depend on all bits of x); the 24-bit multiply serves ids of at
+// most 24 bits
 __device__ __forceinline__ u32 mix_id(u32 x, u32 mask, u32 bits) {
-  (void)bits;
-  return __umul24(x, 0x9E3779u) & mask;
+  return (bits <= 24u ? (u32)__umul24(x, 0x9E3779u) : x * 0x9E3779B1u) & mask;
 }
 
 // high 16 bits of the 48-bit product of two 24-bit numbers (both operands in vector registers:
@@ -52,14 +52,17 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
   const u32 nb = a.hash_buckets;
   const u32 hsize = 4u * nb;  // table size in 32-bit words
   uint4* bucket = reinterpret_cast<uint4*>(hash);
-  const bool compact = a.id_bits != 0;  // 16-bit tag mode
-  const u32 idmask = compact ? ((1u << a.id_bits) - 1u) : 0u;
-  const u32 tagmask = compact ? ((1u << (a.id_bits - (31u - (u32)__builtin_clz(nb)))) - 1u) : 0u;
-  // bucket = floor(y * nb / 2^bits), as the high part of a 24 x 24-bit product: (y << (24 - bits))
-  // * (nb << 8) >> 32
-  const u32 yshift = compact ? 24u - a.id_bits : 0u;
+  const bool compact = a.tag_width == 16u;  // eight 16-bit tags per bucket
+  const bool tags21 = a.tag_width == 21u;   // six 21-bit tags per bucket
+  const bool tagged = compact || tags21;
+  const u32 idmask = tagged ? ((1u << a.id_bits) - 1u) : 0u;
+  const u32 tagmask = tagged ? ((1u << (a.id_bits - (31u - (u32)__builtin_clz(nb)))) - 1u) : 0u;
+  // bucket = floor(y' * nb / 2^24) with y' the top 24 bits of y (y shifted up if it has fewer),
+  // as the high part of a 24 x 24-bit product: y' * (nb << 8) >> 32
+  const u32 yshl = tagged && a.id_bits < 24u ? 24u - a.id_bits : 0u;
+  const u32 yshr = tagged && a.id_bits > 24u ? a.id_bits - 24u : 0u;
   const u32 nb8 = nb << 8;
-  auto bucket_of_y = [=](u32 y) { return umulhi24(y << yshift, nb8); };
+  auto bucket_of_y = [=](u32 y) { return umulhi24((y << yshl) >> yshr, nb8); };
   auto bucket_of_id = [=](u32 x) { return umulhi24((x * 0x9E3779B1u) >> 8, nb8); };
   const u32 L = a.L;
 
@@ -96,6 +99,9 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
     if (compact) {
       const u32 y = mix_id(a.start, idmask, a.id_bits);
       hash[4u * bucket_of_y(y)] = 0xFFFF0000u | (y & tagmask);
+    } else if (tags21) {
+      const u32 y = mix_id(a.start, idmask, a.id_bits);
+      hash[4u * bucket_of_y(y)] = 0xFFE00000u | (y & tagmask);
     } else {
       hash[4u * bucket_of_id(a.start)] = a.start;
     }
@@ -175,6 +181,25 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
           else  // shift the bucket by one tag, newest in front
             bucket[h] = make_uint4((e.x << 16) | tag, (e.y << 16) | (e.x >> 16), (e.z << 16) | (e.y >> 16),
                                    (e.w << 16) | (e.z >> 16));
+        } else if (tags21) {
+          // a bucket is two 64-bit words of three 21-bit tags each (an empty slot is all ones,
+          // which no tag of at most 20 bits equals), newest in front
+          constexpr u32 M21 = 0x1FFFFFu;
+          const u32 y = mix_id(x, idmask, a.id_bits);
+          const u32 h = bucket_of_y(y);
+          const u32 tag = y & tagmask;
+          const uint4 e = bucket[h];
+          const u32 f0 = e.x & M21, f1 = __builtin_amdgcn_alignbit(e.y, e.x, 21) & M21, f2 = (e.y >> 10) & M21;
+          const u32 f3 = e.z & M21, f4 = __builtin_amdgcn_alignbit(e.w, e.z, 21) & M21, f5 = (e.w >> 10) & M21;
+          const u32 ma = (f0 ^ tag) < (f1 ^ tag) ? (f0 ^ tag) : (f1 ^ tag);
+          const u32 mb = (f2 ^ tag) < (f3 ^ tag) ? (f2 ^ tag) : (f3 ^ tag);
+          const u32 mc = (f4 ^ tag) < (f5 ^ tag) ? (f4 ^ tag) : (f5 ^ tag);
+          const u32 mab = ma < mb ? ma : mb;
+          if ((mab < mc ? mab : mc) == 0u)
+            fresh = false;
+          else
+            bucket[h] = make_uint4((e.x << 21) | tag, __builtin_amdgcn_alignbit(e.y, e.x, 11), (e.z << 21) | f2,
+                                   __builtin_amdgcn_alignbit(e.w, e.z, 11));
         } else {
           const u32 h = bucket_of_id(x);
           const uint4 e = bucket[h];
@@ -368,13 +393,24 @@ static hipError_t launch_search_nslot(const SearchArgs& a, const VecTable& T, hi
   return hipGetLastError();
 }
 
-u32 compact_id_bits(u64 n, u32 hash_buckets) {
+// Tags identify a vertex exactly when ids fit id_bits bits and the tag keeps the id_bits -
+// floor(log2 buckets) low bits of the mixed id: 16-bit tags carry up to 15 of them (0xFFFF marks
+// an empty slot), 21-bit tags up to 20.
+void search_filter_mode(u64 n, u32 hash_buckets, u32* id_bits, u32* tag_width) {
   u32 bits = 1;
   while ((1ull << bits) < n) ++bits;  // ids < n <= 2^bits
   u32 q = 0;
   while ((2u << q) <= hash_buckets) ++q;  // floor(log2(buckets))
   if (bits < q + 1u) bits = q + 1u;
-  return (bits <= 24u && bits - q <= 15u) ? bits : 0u;
+  *id_bits = 0;
+  *tag_width = 0;
+  if (bits <= 24u && bits - q <= 15u) {
+    *id_bits = bits;
+    *tag_width = 16;
+  } else if (bits <= 31u && bits - q <= 20u) {
+    *id_bits = bits;
+    *tag_width = 21;
+  }
 }
 
 hipError_t launch_search(const DistCfg& cfg, const SearchArgs& a, hipStream_t s) {

@@ -482,3 +482,23 @@ def test_c2_full_size_invariants(env, c2_full):
     assert st["searches"] == n - 1 and st["prunes"] == n - 1 and st["restarts"] == 0
     g2 = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed)
     assert (g2.neighbors() == rows).all()
+
+
+def test_c2_full_size_every_filter_layout_gives_the_same_graph(env, c2_full):
+    """The visited filter only saves work.  At a million points the default table holds 16-bit
+    tags; 8 buckets force 21-bit tags (20 id bits - 3) and 4 buckets with ids handed in as a
+    larger graph would; a tiny table also makes nearly every candidate come back, which exercises
+    the duplicate handling.  Checked on a partial build to keep it short."""
+    torch, A, O = env
+    w, pts, g = c2_full
+    ref = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, max_rounds=22).neighbors()
+    for hb in (5, 7, 12):
+        say(f"partial build with hash_bits={hb}")
+        got = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, max_rounds=22, hash_bits=hb).neighbors()
+        assert (got == ref).all()
+    qs = dev(torch, w.queries[:500])
+    ids0, d0 = A.ann_search(g, pts, qs, 10, 40)
+    g5 = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, hash_bits=5)
+    assert (g5.neighbors() == g.neighbors()).all()
+    ids1, d1 = A.ann_search(g5, pts, qs, 10, 40)
+    assert (ids0 == ids1).all() and (d0 == d1).all()
