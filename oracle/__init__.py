@@ -85,6 +85,15 @@ def lib():
             C.POINTER(_Data), C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_uint32,
             C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint64, C.POINTER(C.c_uint64), C.c_void_p,
             C.c_void_p, C.POINTER(Stats)]
+        L.vo_greedy_search_eps.restype = C.c_int
+        L.vo_greedy_search_eps.argtypes = [
+            C.POINTER(_Data), C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_uint32,
+            C.c_uint32, C.c_double, C.c_void_p, C.c_void_p, C.c_uint64, C.POINTER(C.c_uint64),
+            C.c_void_p, C.c_void_p, C.POINTER(Stats)]
+        L.vo_search_batch_eps.restype = C.c_int
+        L.vo_search_batch_eps.argtypes = [
+            C.POINTER(_Data), C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_uint64,
+            C.c_uint32, C.c_uint32, C.c_double, C.c_int, C.c_void_p, C.c_void_p, C.POINTER(Stats)]
         L.vo_prune.restype = C.c_uint32
         L.vo_prune.argtypes = [
             C.POINTER(_Data), C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint64, C.c_uint32,
@@ -166,8 +175,9 @@ def distance(a: np.ndarray, b: np.ndarray, metric: int = L2SQ) -> float:
 
 
 def greedy_search(ds: Dataset, graph: np.ndarray, start: int, query: np.ndarray, L: int, k: int,
-                  stats: Stats | None = None, check: bool = True):
-    """Alg. 1.  Returns (V_ids, V_dists, K_ids, K_dists)."""
+                  stats: Stats | None = None, check: bool = True, eps: float = -1.0):
+    """Alg. 1, with the (1 + eps) rule of Sec. 4.5 when eps >= 0.
+    Returns (V_ids, V_dists, K_ids, K_dists)."""
     graph = np.ascontiguousarray(graph, dtype=np.uint32)
     query = np.ascontiguousarray(query, dtype=ds.points.dtype)
     R = graph.shape[1]
@@ -177,9 +187,9 @@ def greedy_search(ds: Dataset, graph: np.ndarray, start: int, query: np.ndarray,
     k_ids = np.empty(k, np.uint32)
     k_d = np.empty(k, np.float64)
     nv = C.c_uint64(0)
-    rc = lib().vo_greedy_search(ds.c(), _ptr(graph), R, start, _ptr(query), L, k, _ptr(v_ids),
-                                _ptr(v_d), cap, C.byref(nv), _ptr(k_ids), _ptr(k_d),
-                                C.byref(stats) if stats is not None else None)
+    rc = lib().vo_greedy_search_eps(ds.c(), _ptr(graph), R, start, _ptr(query), L, k, float(eps),
+                                    _ptr(v_ids), _ptr(v_d), cap, C.byref(nv), _ptr(k_ids), _ptr(k_d),
+                                    C.byref(stats) if stats is not None else None)
     if check and rc != 0:
         raise RuntimeError(f"vo_greedy_search rc={rc}")
     n = nv.value
@@ -274,15 +284,15 @@ def _dist_out(ds: Dataset, shape):
 
 
 def search_batch(ds: Dataset, graph: np.ndarray, start: int, queries: np.ndarray, k: int, L: int,
-                 threads: int = 1, stats: Stats | None = None):
+                 threads: int = 1, stats: Stats | None = None, eps: float = -1.0):
     graph = np.ascontiguousarray(graph, dtype=np.uint32)
     queries = np.ascontiguousarray(queries, dtype=ds.points.dtype)
     nq = queries.shape[0]
     ids = np.empty((nq, k), np.uint32)
     dists = _dist_out(ds, (nq, k))
-    rc = lib().vo_search_batch(ds.c(), _ptr(graph), graph.shape[1], start, _ptr(queries), nq, k,
-                               L, threads, _ptr(ids), _ptr(dists),
-                               C.byref(stats) if stats is not None else None)
+    rc = lib().vo_search_batch_eps(ds.c(), _ptr(graph), graph.shape[1], start, _ptr(queries), nq, k,
+                                   L, float(eps), threads, _ptr(ids), _ptr(dists),
+                                   C.byref(stats) if stats is not None else None)
     if rc:
         raise RuntimeError(f"vo_search_batch rc={rc}")
     return ids, dists

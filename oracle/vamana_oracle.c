@@ -103,6 +103,23 @@ static int alpha_dominates(int dtype, double alpha, double d_star_cand, double d
   return prod <= (float)d_p_cand;
 }
 
+/* (1 + eps) rule of the search (Sec. 4.5): may a vertex at distance d be searched when the
+ * k-th nearest candidate so far is at distance dk?  It may not if d exceeds dk by more than the
+ * factor 1 + eps.  Integer distances: eps is quantised to e16 = round(eps * 2^16) and the test
+ * is exact in 64-bit integers.  Floats: the bound is dk + eps * |dk| (which is (1 + eps) * dk for
+ * dk >= 0 and stays meaningful for the negative values of the inner-product metric), one fp32
+ * product and one fp32 sum.                                                              */
+static int beyond_eps_bound(int dtype, double eps, double d, double dk) {
+  if (dtype == VO_U8 || dtype == VO_I8) {
+    int64_t e16 = llround(eps * 65536.0);
+    return (int64_t)d * 65536 > (int64_t)dk * (65536 + e16);
+  }
+  volatile float e = (float)eps;
+  volatile float prod = e * fabsf((float)dk);
+  volatile float bound = (float)dk + prod;
+  return (float)d > bound;
+}
+
 /* (distance, id) total order */
 typedef struct {
   double dist;
@@ -172,8 +189,8 @@ static void work_new_search(work_t* w) {
  * w->beam[0..*nbeam) the final beam, sorted.  Returns 0, -2 if the check
  * "k closest of V == first k of the beam" fails.                          */
 static int greedy_core(const vo_data* D, const uint32_t* graph, uint32_t R, uint32_t start,
-                       const void* query, uint32_t L, uint32_t k, work_t* w, uint64_t* nv,
-                       uint64_t* nbeam, vo_stats* st) {
+                       const void* query, uint32_t L, uint32_t k, double eps, work_t* w,
+                       uint64_t* nv, uint64_t* nbeam, vo_stats* st) {
   work_new_search(w);
   uint64_t nb = 0, v = 0;
   w->beam[0].dist = vo_distance(query, row_ptr(D, start), D->d, D->dtype, D->metric);
@@ -192,6 +209,12 @@ static int greedy_core(const vo_data* D, const uint32_t* graph, uint32_t R, uint
         break;
       }
     if (pi == nb) break;
+    /* (1 + eps) rule, eps >= 0: only vertices within the bound of the current k-th nearest are
+     * searched; the beam is sorted and the k-th distance never grows, so the first vertex that
+     * fails ends the search */
+    if (eps >= 0.0 && nb >= k && k >= 1 &&
+        beyond_eps_bound(D->dtype, eps, w->beam[pi].dist, w->beam[k - 1].dist))
+      break;
     w->beam[pi].done = 1;
     if (v == w->vis_cap) {
       w->vis_cap *= 2;
@@ -253,6 +276,14 @@ int vo_greedy_search(const vo_data* D, const uint32_t* graph, uint32_t R, uint32
                      const void* query, uint32_t L, uint32_t k, uint32_t* v_ids,
                      double* v_dists, uint64_t v_cap, uint64_t* nv, uint32_t* k_ids,
                      double* k_dists, vo_stats* stats) {
+  return vo_greedy_search_eps(D, graph, R, start, query, L, k, -1.0, v_ids, v_dists, v_cap, nv, k_ids,
+                              k_dists, stats);
+}
+
+int vo_greedy_search_eps(const vo_data* D, const uint32_t* graph, uint32_t R, uint32_t start,
+                         const void* query, uint32_t L, uint32_t k, double eps, uint32_t* v_ids,
+                         double* v_dists, uint64_t v_cap, uint64_t* nv, uint32_t* k_ids,
+                         double* k_dists, vo_stats* stats) {
   if (!D || !graph || !query || L < 1 || k > L || start >= D->n) return -1;
   work_t w;
   if (work_init(&w, D->n, L, R)) {
@@ -262,7 +293,7 @@ int vo_greedy_search(const vo_data* D, const uint32_t* graph, uint32_t R, uint32
   uint64_t v = 0, nb = 0;
   vo_stats st;
   memset(&st, 0, sizeof(st));
-  int rc = greedy_core(D, graph, R, start, query, L, k, &w, &v, &nb, &st);
+  int rc = greedy_core(D, graph, R, start, query, L, k, eps, &w, &v, &nb, &st);
   if (rc == 0 || rc == -2) {
     for (uint64_t i = 0; i < v && i < v_cap; ++i) {
       if (v_ids) v_ids[i] = w.vis[i].id;
@@ -451,7 +482,7 @@ int vo_insert(const vo_data* D, uint32_t* graph, uint32_t R, uint32_t start, uin
   vo_stats st;
   memset(&st, 0, sizeof(st));
   uint64_t nv = 0, nb = 0;
-  int rc = greedy_core(D, graph, R, start, row_ptr(D, p), L, 1, &w, &nv, &nb, &st);
+  int rc = greedy_core(D, graph, R, start, row_ptr(D, p), L, 1, -1.0, &w, &nv, &nb, &st);
   if (rc) {
     work_free(&w);
     return rc;
@@ -537,7 +568,7 @@ int vo_batch_insert(const vo_data* D, uint32_t* graph, uint32_t R, uint32_t star
       if (bad) continue;
       uint32_t p = batch[i];
       uint64_t nv = 0, nb = 0;
-      int rc = greedy_core(D, graph, R, start, row_ptr(D, p), L, 1, &w, &nv, &nb, &st);
+      int rc = greedy_core(D, graph, R, start, row_ptr(D, p), L, 1, -1.0, &w, &nv, &nb, &st);
       if (rc) {
         bad = rc;
         continue;
@@ -690,6 +721,12 @@ static void store_dist(void* out, uint64_t idx, int dtype, double dist, int vali
 int vo_search_batch(const vo_data* D, const uint32_t* graph, uint32_t R, uint32_t start,
                     const void* queries, uint64_t nq, uint32_t k, uint32_t L, int threads,
                     uint32_t* ids_out, void* dists_out, vo_stats* stats) {
+  return vo_search_batch_eps(D, graph, R, start, queries, nq, k, L, -1.0, threads, ids_out, dists_out, stats);
+}
+
+int vo_search_batch_eps(const vo_data* D, const uint32_t* graph, uint32_t R, uint32_t start,
+                        const void* queries, uint64_t nq, uint32_t k, uint32_t L, double eps,
+                        int threads, uint32_t* ids_out, void* dists_out, vo_stats* stats) {
   if (!D || !graph || !queries || k < 1 || k > L || start >= D->n) return -1;
   int nthreads = vo_threads(threads);
   (void)nthreads;
@@ -706,7 +743,7 @@ int vo_search_batch(const vo_data* D, const uint32_t* graph, uint32_t R, uint32_
       if (bad) continue;
       uint64_t nv = 0, nb = 0;
       int rc = greedy_core(D, graph, R, start, (const char*)queries + (size_t)q * qbytes, L, k,
-                           &w, &nv, &nb, &st);
+                           eps, &w, &nv, &nb, &st);
       if (rc) {
         bad = rc;
         continue;

@@ -88,6 +88,14 @@ int vo_greedy_search(const vo_data* data, const uint32_t* graph, uint32_t R,
                      uint32_t* v_ids, double* v_dists, uint64_t v_cap, uint64_t* nv,
                      uint32_t* k_ids, double* k_dists, vo_stats* stats);
 
+/* The same with the (1 + eps) rule of Sec. 4.5: a vertex is searched only while its distance is
+ * within the factor 1 + eps of the current k-th nearest candidate (squared distances for L2;
+ * the bound is dk + eps * |dk|).  eps < 0 switches the rule off.                             */
+int vo_greedy_search_eps(const vo_data* data, const uint32_t* graph, uint32_t R,
+                         uint32_t start, const void* query, uint32_t L, uint32_t k, double eps,
+                         uint32_t* v_ids, double* v_dists, uint64_t v_cap, uint64_t* nv,
+                         uint32_t* k_ids, double* k_dists, vo_stats* stats);
+
 /* prune(p, C, R) of Sec. 4.1: `p_vec` is the vector of p, `p_id` its id
  * (removed from C; VO_NONE if p is not a member of the data set).  `cand`
  * holds m ids (duplicates allowed).  Writes the selected ids, in selection
@@ -136,6 +144,9 @@ int vo_build_sequential(const vo_data* data, uint32_t R, uint32_t L, double alph
 int vo_search_batch(const vo_data* data, const uint32_t* graph, uint32_t R, uint32_t start,
                     const void* queries, uint64_t nq, uint32_t k, uint32_t L, int threads,
                     uint32_t* ids_out, void* dists_out, vo_stats* stats);
+int vo_search_batch_eps(const vo_data* data, const uint32_t* graph, uint32_t R, uint32_t start,
+                        const void* queries, uint64_t nq, uint32_t k, uint32_t L, double eps,
+                        int threads, uint32_t* ids_out, void* dists_out, vo_stats* stats);
 
 /* Exact k nearest neighbours by exhaustive scan under (distance, id).      */
 int vo_brute_force(const vo_data* data, const void* queries, uint64_t nq, uint32_t k,

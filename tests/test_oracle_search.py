@@ -153,3 +153,80 @@ def test_batch_and_bruteforce_agree_with_numpy(oracle):
     ids2, d2 = oracle.search_batch(ds, g, 0, qs, 7, 9, threads=2)
     assert (ids2 == ids).all() and (d2 == dists).all()
     assert dists.dtype == np.int32
+
+
+# ------------------------------------------------------------------------------------------
+# the (1 + eps) rule of Sec. 4.5
+# ------------------------------------------------------------------------------------------
+def _eps_path_fixture(dtype):
+    f = json.load(open(os.path.join(GOLD, "eps_path.json")))
+    xs = f["xs"]
+    n = len(xs)
+    pts = np.zeros((n, 4), dtype)
+    pts[:, 0] = xs
+    g = np.full((n, 2), NONE, np.uint32)
+    for i in range(n):
+        nb = [j for j in (i - 1, i + 1) if 0 <= j < n]
+        g[i, :len(nb)] = nb
+    q = np.zeros(4, dtype)
+    q[0] = f["query_x"]
+    return f, pts, g, q
+
+
+@pytest.mark.parametrize("dtype", [np.uint8, np.float32])
+def test_eps_rule_hand_worked_path(oracle, dtype):
+    f, pts, g, q = _eps_path_fixture(dtype)
+    ds = oracle.Dataset(pts, 0)
+    for c in f["cases"]:
+        st = oracle.Stats()
+        v_ids, v_d, k_ids, k_d = oracle.greedy_search(ds, g, f["start"], q, f["L"], c["k"], stats=st, eps=c["eps"])
+        assert v_ids.tolist() == c["expect_V"], c
+        assert v_d.tolist() == [f["dists"][i] for i in c["expect_V"]]
+        assert k_ids.tolist() == c["expect_K"], c
+        assert st.evals == f["expect_evals"]
+
+
+@pytest.mark.parametrize("dtype,metric", [(np.uint8, 0), (np.int8, 0), (np.float32, 0), (np.float32, 1)])
+def test_eps_rule_cuts_a_prefix_and_keeps_the_k_nearest_of_it(oracle, dtype, metric):
+    """Whatever eps, the search is the unrestricted one cut short: its visited sequence is a
+    prefix of the unrestricted sequence, growing with eps; a huge eps changes nothing; the k
+    results are the k nearest of what was visited; and where it stopped early, the next vertex
+    in line was indeed beyond the bound (checked from the visited sets alone, in numpy)."""
+    rng = np.random.default_rng(21)
+    n, d, R, L, k = 300, 6, 6, 12, 4
+    pts = _rand_points(rng, n, d, dtype)
+    if metric == 1:
+        pts /= np.linalg.norm(pts, axis=1, keepdims=True)
+    ds = oracle.Dataset(pts, metric)
+    g = _random_graph(rng, n, R)
+    shorter = 0
+    for _ in range(40):
+        q = _rand_points(rng, 1, d, dtype)[0]
+        s = int(rng.integers(n))
+        v_off, _, k_off, _ = oracle.greedy_search(ds, g, s, q, L, k)
+        prev = 0
+        for eps in (0.0, 0.05, 0.25, 1.0, 1e9):
+            v, vd, kk, kd = oracle.greedy_search(ds, g, s, q, L, k, eps=eps)
+            assert v.tolist() == v_off[:len(v)].tolist()
+            assert len(v) >= prev
+            prev = len(v)
+            if eps == 1e9:
+                assert len(v) == len(v_off) and kk.tolist() == k_off.tolist()
+            ek, ed = exact_knn(pts, q, k, metric, subset=v.tolist())
+            m = min(k, len(v))
+            assert kk[:m].tolist() == ek[:m].tolist()
+            if len(v) < len(v_off):
+                shorter += 1
+                # At an early stop the beam's first k entries are all visited (an unvisited one
+                # would be within the bound), so the k-th nearest visited vertex IS d_k, and the
+                # vertex the unrestricted search expands next must lie beyond its bound.
+                assert len(v) >= k
+                nxt = int(v_off[len(v)])
+                dn = np_dists_to(pts[nxt:nxt + 1], q, metric)[0]
+                dk = ed[k - 1]
+                if dtype == np.float32:
+                    bound = np.float32(dk) + np.float32(eps) * np.abs(np.float32(dk))
+                    assert np.float32(dn) > bound
+                else:
+                    assert int(dn) * 65536 > int(dk) * (65536 + int(round(eps * 65536)))
+    assert shorter > 20
