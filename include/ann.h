@@ -143,6 +143,21 @@ int ann_insert_batch(ann_graph* g, const void* points_dev, const uint32_t* ids_h
 int ann_search(const ann_graph* g, const void* points_dev, const void* queries_dev, uint64_t nq,
                uint32_t k, uint32_t L, uint32_t* ids_dev, void* dists_dev, void* stream);
 
+/*
+ * The same search with the (1 + eps) pruning of Sec. 4.5: a vertex is searched only while its
+ * distance to the query is within a factor 1 + eps of the current k-th nearest candidate.
+ * The test is made before the closest unprocessed beam member is expanded, once the beam
+ * holds k entries, and its first failure ends the search (the beam is sorted and its k-th
+ * distance never grows).  Distances are the ones the library computes (squared for ANN_L2SQ);
+ * u8/i8: d * 2^16 > d_k * (2^16 + round(eps * 2^16)) in 64-bit integers; f32: d > d_k + eps * |d_k|
+ * in fp32 (which also covers the negative values of ANN_MIPS).  Equality passes.
+ *   eps   0 <= eps < 16384 (the paper never uses more than 0.25); a negative eps switches the
+ *         rule off and makes the call identical to ann_search
+ * Other arguments, outputs and errors as ann_search.  Asynchronous on `stream`.
+ */
+int ann_search_eps(const ann_graph* g, const void* points_dev, const void* queries_dev, uint64_t nq,
+                   uint32_t k, uint32_t L, float eps, uint32_t* ids_dev, void* dists_dev, void* stream);
+
 /* Start vertex used by ann_build when none is given: the point nearest
  * (squared L2) to the mean of all points, smallest id on ties.  Exact for
  * u8/i8; fp64 for f32.  Blocks.                                             */

@@ -285,6 +285,7 @@ int vo_greedy_search_eps(const vo_data* D, const uint32_t* graph, uint32_t R, ui
                          double* v_dists, uint64_t v_cap, uint64_t* nv, uint32_t* k_ids,
                          double* k_dists, vo_stats* stats) {
   if (!D || !graph || !query || L < 1 || k > L || start >= D->n) return -1;
+  if (!(eps < 16384.0)) return -1; /* keeps the integer form of the rule inside 64 bits */
   work_t w;
   if (work_init(&w, D->n, L, R)) {
     work_free(&w);
@@ -728,6 +729,7 @@ int vo_search_batch_eps(const vo_data* D, const uint32_t* graph, uint32_t R, uin
                         const void* queries, uint64_t nq, uint32_t k, uint32_t L, double eps,
                         int threads, uint32_t* ids_out, void* dists_out, vo_stats* stats) {
   if (!D || !graph || !queries || k < 1 || k > L || start >= D->n) return -1;
+  if (!(eps < 16384.0)) return -1;
   int nthreads = vo_threads(threads);
   (void)nthreads;
   int err = 0;

@@ -90,7 +90,7 @@ int vo_greedy_search(const vo_data* data, const uint32_t* graph, uint32_t R,
 
 /* The same with the (1 + eps) rule of Sec. 4.5: a vertex is searched only while its distance is
  * within the factor 1 + eps of the current k-th nearest candidate (squared distances for L2;
- * the bound is dk + eps * |dk|).  eps < 0 switches the rule off.                             */
+ * the bound is dk + eps * |dk|).  eps < 0 switches the rule off; eps must be below 16384.     */
 int vo_greedy_search_eps(const vo_data* data, const uint32_t* graph, uint32_t R,
                          uint32_t start, const void* query, uint32_t L, uint32_t k, double eps,
                          uint32_t* v_ids, double* v_dists, uint64_t v_cap, uint64_t* nv,

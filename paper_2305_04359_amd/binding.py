@@ -54,7 +54,7 @@ class Stats(C.Structure):
 
 
 EXPORTS = [
-    "ann_build", "ann_insert_batch", "ann_search", "ann_start_vertex", "ann_graph_from_host",
+    "ann_build", "ann_insert_batch", "ann_search", "ann_search_eps", "ann_start_vertex", "ann_graph_from_host",
     "ann_graph_copy_neighbors", "ann_graph_device_rows", "ann_graph_info", "ann_get_stats",
     "ann_graph_free", "ann_sort_edges", "ann_last_error",
 ]
@@ -83,6 +83,8 @@ def lib():
         L.ann_insert_batch.argtypes = [vp, vp, vp, u64, u32, C.c_float, vp]
         L.ann_search.restype = C.c_int
         L.ann_search.argtypes = [vp, vp, vp, u64, u32, u32, vp, vp, vp]
+        L.ann_search_eps.restype = C.c_int
+        L.ann_search_eps.argtypes = [vp, vp, vp, u64, u32, u32, C.c_float, vp, vp, vp]
         L.ann_start_vertex.restype = C.c_int
         L.ann_start_vertex.argtypes = [vp, u64, u32, C.c_int, vp, C.POINTER(u32)]
         L.ann_graph_from_host.restype = C.c_int
@@ -206,8 +208,14 @@ def ann_insert_batch(graph: Graph, points, ids, L, alpha) -> None:
                                   ids.shape[0], L, float(alpha), _stream_ptr()))
 
 
-def ann_search(graph: Graph, points, queries, k, L, ids_out=None, dists_out=None):
-    """greedySearch of Alg. 1 for each row of `queries`; returns (ids, dists) device tensors."""
+def ann_search_eps(graph: Graph, points, queries, k, L, eps, ids_out=None, dists_out=None):
+    """greedySearch with the (1 + eps) pruning of Sec. 4.5; returns (ids, dists) device tensors."""
+    return ann_search(graph, points, queries, k, L, ids_out, dists_out, eps=eps)
+
+
+def ann_search(graph: Graph, points, queries, k, L, ids_out=None, dists_out=None, eps=None):
+    """greedySearch of Alg. 1 for each row of `queries`; returns (ids, dists) device tensors.
+    With `eps` the call goes to ann_search_eps."""
     torch = _torch()
     points = _dev2d(points, "points")
     queries = _dev2d(queries, "queries")
@@ -219,8 +227,12 @@ def ann_search(graph: Graph, points, queries, k, L, ids_out=None, dists_out=None
     if dists_out is None:
         dists_out = torch.empty((nq, k), dtype=torch.float32 if points.dtype == torch.float32 else torch.int32,
                                 device=points.device)
-    _check(lib().ann_search(graph.handle, points.data_ptr(), queries.data_ptr(), nq, k, L,
-                            ids_out.data_ptr(), dists_out.data_ptr(), _stream_ptr()))
+    if eps is None:
+        _check(lib().ann_search(graph.handle, points.data_ptr(), queries.data_ptr(), nq, k, L,
+                                ids_out.data_ptr(), dists_out.data_ptr(), _stream_ptr()))
+    else:
+        _check(lib().ann_search_eps(graph.handle, points.data_ptr(), queries.data_ptr(), nq, k, L, float(eps),
+                                    ids_out.data_ptr(), dists_out.data_ptr(), _stream_ptr()))
     return ids_out, dists_out
 
 

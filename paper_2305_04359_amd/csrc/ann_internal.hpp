@@ -44,6 +44,10 @@ struct SearchArgs {
   u32 k;
   u32* batch_counters;  // build only: the batch's counter words (overflow count [0], arena top [4..5], work
                         // list lengths [8..10]); workgroup 0 zeroes them for the steps that follow
+  // (1 + eps) rule of the search (Sec. 4.5): off when eps16 < 0; integer kinds use eps16 =
+  // round(eps * 2^16), float kinds epsf
+  long long eps16;
+  float epsf;
   u32 hash_buckets;  // 16-byte buckets of the visited filter (any count from 4 to 2048)
   u32 id_bits;       // > 0: the filter stores tags of ids that fit in this many bits ...
   u32 tag_width;     // ... eight of 16 bits or six of 21 bits per bucket (0: four 32-bit ids)

@@ -350,6 +350,8 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   sa.hash_buckets = search_hash_buckets(L, g->hash_bits);
   search_filter_mode(g->n, sa.hash_buckets, &sa.id_bits, &sa.tag_width);
   sa.batch_counters = small;
+  sa.eps16 = -1;
+  sa.epsf = 0.0f;
   sa.vis = S.vis.as<u64>();
   sa.nvis = S.nvis.as<u32>();
   sa.vis_cap = S.vis_cap;
@@ -844,7 +846,13 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
 
 int ann_search(const ann_graph* g, const void* points_dev, const void* queries_dev, uint64_t nq, uint32_t k,
                uint32_t L, uint32_t* ids_dev, void* dists_dev, void* stream) {
+  return ann_search_eps(g, points_dev, queries_dev, nq, k, L, -1.0f, ids_dev, dists_dev, stream);
+}
+
+int ann_search_eps(const ann_graph* g, const void* points_dev, const void* queries_dev, uint64_t nq, uint32_t k,
+                   uint32_t L, float eps, uint32_t* ids_dev, void* dists_dev, void* stream) {
   if (!g || !points_dev) return fail(ANN_EINVAL, "null argument");
+  if (!(eps < 16384.0f)) return fail(ANN_EINVAL, "eps must be below 16384 (negative: no pruning)");
   if (nq == 0) return ANN_OK;
   if (!queries_dev || !ids_dev || !dists_dev) return fail(ANN_EINVAL, "null argument");
   if (k < 1 || k > L) return fail(ANN_EINVAL, "need 1 <= k <= L");
@@ -870,6 +878,8 @@ int ann_search(const ann_graph* g, const void* points_dev, const void* queries_d
   sa.k = k;
   sa.hash_buckets = search_hash_buckets(L, g->hash_bits);
   search_filter_mode(g->n, sa.hash_buckets, &sa.id_bits, &sa.tag_width);
+  sa.eps16 = eps >= 0.0f ? llround((double)eps * 65536.0) : -1;
+  sa.epsf = eps >= 0.0f ? eps : 0.0f;
   sa.out_ids = ids_dev;
   sa.out_dists = dists_dev;
   sa.counters = g->collect ? g->counters : nullptr;

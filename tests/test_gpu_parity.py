@@ -502,3 +502,70 @@ def test_c2_full_size_every_filter_layout_gives_the_same_graph(env, c2_full):
     assert (g5.neighbors() == g.neighbors()).all()
     ids1, d1 = A.ann_search(g5, pts, qs, 10, 40)
     assert (ids0 == ids1).all() and (d0 == d1).all()
+
+
+# ------------------------------------------------------------------------------------------
+# the (1 + eps) rule of the search (Sec. 4.5)
+# ------------------------------------------------------------------------------------------
+def test_search_eps_hand_worked_path(env):
+    torch, A, O = env
+    f = json.load(open(os.path.join(GOLD, "eps_path.json")))
+    for dtype, code in ((np.uint8, A.U8), (np.float32, A.F32)):
+        xs = f["xs"]
+        n = len(xs)
+        pts = np.zeros((n, 4), dtype)
+        pts[:, 0] = xs
+        g = np.full((n, 2), NONE, np.uint32)
+        for i in range(n):
+            nb = [j for j in (i - 1, i + 1) if 0 <= j < n]
+            g[i, :len(nb)] = nb
+        q = np.zeros((1, 4), dtype)
+        q[0, 0] = f["query_x"]
+        gg = A.ann_graph_from_host(g, 4, code, A.L2SQ, f["start"])
+        ds = O.Dataset(pts, 0)
+        for c in f["cases"]:
+            ids, dists = A.ann_search(gg, dev(torch, pts), dev(torch, q), c["k"], f["L"], eps=c["eps"])
+            assert ids.cpu().numpy().view(np.uint32)[0].tolist() == c["expect_K"], (dtype, c)
+            oi, od = O.search_batch(ds, g, f["start"], q, c["k"], f["L"], eps=c["eps"])
+            assert (dists.cpu().numpy() == od).all()
+
+
+@pytest.mark.parametrize("eps", [0.0, 0.02, 0.1, 0.25, 3.0])
+def test_search_eps_c1_bit_exact(env, c1, c1_oracle, eps):
+    torch, A, O = env
+    ds, g, s = c1_oracle
+    gg = A.ann_graph_from_host(g, c1.d, A.U8, A.L2SQ, s)
+    pts, qs = dev(torch, c1.points), dev(torch, c1.queries)
+    for L, k in ((10, 10), (40, 10), (130, 10), (64, 1), (300, 70)):
+        say(f"search C1 eps={eps} L={L} k={k}")
+        ids, dists = A.ann_search_eps(gg, pts, qs, k, L, eps)
+        oi, od = O.search_batch(ds, g, s, c1.queries, k, L, threads=0, eps=eps)
+        assert (ids.cpu().numpy().view(np.uint32) == oi).all()
+        assert (dists.cpu().numpy() == od).all()
+    # a negative eps is plain ann_search
+    a0 = A.ann_search(gg, pts, qs, 10, 40)
+    a1 = A.ann_search_eps(gg, pts, qs, 10, 40, -1.0)
+    assert (a0[0] == a1[0]).all() and (a0[1] == a1[1]).all()
+    with pytest.raises(A.AnnError):
+        A.ann_search_eps(gg, pts, qs, 10, 40, float("nan"))
+    with pytest.raises(A.AnnError):
+        A.ann_search_eps(gg, pts, qs, 10, 40, 1e9)
+
+
+def test_search_eps_c2_full_size(env, c2_full):
+    """Full size: 300 queries against the oracle, and the rule really saves hops."""
+    torch, A, O = env
+    w, pts, g = c2_full
+    rows = g.neighbors()
+    s = int(g.info().start)
+    ds = O.Dataset(w.points, 0)
+    qs_h = w.queries[:300]
+    qs = dev(torch, qs_h)
+    for L, eps in ((30, 0.05), (100, 0.1), (200, 0.25)):
+        ids, dists = A.ann_search_eps(g, pts, qs, 10, L, eps)
+        so, sp = O.Stats(), O.Stats()
+        oi, od = O.search_batch(ds, rows, s, qs_h, 10, L, threads=0, eps=eps, stats=sp)
+        O.search_batch(ds, rows, s, qs_h, 10, L, threads=0, stats=so)
+        assert (ids.cpu().numpy().view(np.uint32) == oi).all()
+        assert (dists.cpu().numpy().view(np.int32) == od.view(np.int32)).all()
+        assert sp.hops < so.hops

@@ -205,12 +205,12 @@ def test_eps_rule_cuts_a_prefix_and_keeps_the_k_nearest_of_it(oracle, dtype, met
         s = int(rng.integers(n))
         v_off, _, k_off, _ = oracle.greedy_search(ds, g, s, q, L, k)
         prev = 0
-        for eps in (0.0, 0.05, 0.25, 1.0, 1e9):
+        for eps in (0.0, 0.05, 0.25, 1.0, 16000.0):
             v, vd, kk, kd = oracle.greedy_search(ds, g, s, q, L, k, eps=eps)
             assert v.tolist() == v_off[:len(v)].tolist()
             assert len(v) >= prev
             prev = len(v)
-            if eps == 1e9:
+            if eps == 16000.0:
                 assert len(v) == len(v_off) and kk.tolist() == k_off.tolist()
             ek, ed = exact_knn(pts, q, k, metric, subset=v.tolist())
             m = min(k, len(v))
