@@ -117,6 +117,14 @@ def lib():
             C.POINTER(_Data), C.c_uint32, C.c_uint32, C.c_double, C.c_uint64, C.c_uint64,
             C.c_uint32, C.c_void_p, C.c_uint64, C.c_int, C.c_void_p, C.POINTER(C.c_uint32),
             C.POINTER(Stats)]
+        L.vo_insert_points.restype = C.c_int
+        L.vo_insert_points.argtypes = [
+            C.POINTER(_Data), C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint64, C.c_uint32,
+            C.c_double, C.c_uint64, C.c_uint64, C.c_void_p, C.c_uint64, C.c_int, C.POINTER(Stats)]
+        L.vo_new_points_order.restype = None
+        L.vo_new_points_order.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, C.c_void_p]
+        L.vo_schedule_from.restype = C.c_uint64
+        L.vo_schedule_from.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, C.c_void_p]
         L.vo_build_sequential.restype = C.c_int
         L.vo_build_sequential.argtypes = [
             C.POINTER(_Data), C.c_uint32, C.c_uint32, C.c_double, C.c_uint32, C.c_void_p,
@@ -265,6 +273,38 @@ def build(ds: Dataset, R: int, L: int, alpha: float, seed: int = 1, theta: int =
     if rc:
         raise RuntimeError(f"vo_build rc={rc}")
     return graph, int(s_out.value)
+
+
+def new_points_order(first: int, count: int, seed: int) -> np.ndarray:
+    order = np.empty(count, np.uint32)
+    lib().vo_new_points_order(first, count, seed, _ptr(order))
+    return order
+
+
+def schedule_from(present: int, m: int, theta: int) -> np.ndarray:
+    rounds = lib().vo_schedule_from(present, m, theta, None)
+    bounds = np.empty(rounds + 1, np.uint64)
+    lib().vo_schedule_from(present, m, theta, _ptr(bounds))
+    return bounds
+
+
+def insert_points(ds: Dataset, graph_old: np.ndarray, start: int, L: int, alpha: float,
+                  seed: int = 1, theta: int = 0, order: np.ndarray | None = None,
+                  max_rounds: int = 0, threads: int = 1, stats: Stats | None = None) -> np.ndarray:
+    """Streams the points graph_old.shape[0]..ds.n-1 into the graph; returns the grown graph."""
+    n_old, R = graph_old.shape
+    assert graph_old.dtype == np.uint32 and n_old <= ds.n
+    graph = np.full((ds.n, R), NONE, np.uint32)
+    graph[:n_old] = graph_old
+    if order is not None:
+        order = np.ascontiguousarray(order, dtype=np.uint32)
+        assert order.shape[0] == ds.n - n_old
+    rc = lib().vo_insert_points(ds.c(), _ptr(graph), R, start, n_old, L, float(alpha), seed, theta,
+                                _ptr(order) if order is not None else None, max_rounds, threads,
+                                C.byref(stats) if stats is not None else None)
+    if rc:
+        raise RuntimeError(f"vo_insert_points rc={rc}")
+    return graph
 
 
 def build_sequential(ds: Dataset, R: int, L: int, alpha: float, start: int, order: np.ndarray,

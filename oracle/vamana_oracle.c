@@ -709,6 +709,87 @@ int vo_build(const vo_data* D, uint32_t R, uint32_t L, double alpha, uint64_t se
 }
 
 /* ------------------------------------------------------------------ */
+/* streaming insertion of new points: BatchInsert of Alg. 3 applied to   */
+/* points that arrive after the build, the schedule of Sec. 3.1 carried  */
+/* on from the points already present                                    */
+/* ------------------------------------------------------------------ */
+
+void vo_new_points_order(uint64_t first, uint64_t count, uint64_t seed, uint32_t* order) {
+  for (uint64_t i = 0; i < count; ++i) order[i] = (uint32_t)(first + i);
+  uint64_t state = seed;
+  for (uint64_t i = count; i-- > 1;) {
+    uint64_t r = splitmix64(&state);
+    uint64_t j = (uint64_t)(((unsigned __int128)r * (unsigned __int128)(i + 1)) >> 64);
+    uint32_t t = order[i];
+    order[i] = order[j];
+    order[j] = t;
+  }
+}
+
+uint64_t vo_schedule_from(uint64_t present, uint64_t m, uint64_t theta, uint64_t* bounds) {
+  if (theta < 1) theta = 1;
+  uint64_t taken = 0, rounds = 0;
+  if (bounds) bounds[0] = 0;
+  while (taken < m) {
+    /* a batch may at most double what is there (present + taken points
+     * besides the start vertex, plus the start vertex itself, plus one, as
+     * in the build), is capped by theta and by what is left                */
+    uint64_t size = present + taken + 2;
+    if (size > theta) size = theta;
+    if (size > m - taken) size = m - taken;
+    taken += size;
+    ++rounds;
+    if (bounds) bounds[rounds] = taken;
+  }
+  return rounds;
+}
+
+int vo_insert_points(const vo_data* D, uint32_t* graph, uint32_t R, uint32_t start, uint64_t n_old,
+                     uint32_t L, double alpha, uint64_t seed, uint64_t theta,
+                     const uint32_t* order, uint64_t max_rounds, int threads, vo_stats* stats) {
+  if (!D || !graph || R < 1 || L < 1 || n_old < 1 || n_old > D->n || start >= n_old) return -1;
+  uint64_t n = D->n, m = n - n_old;
+  if (m == 0) return 0;
+  if (theta == 0) theta = n / 50 > 1 ? n / 50 : 1;
+  uint32_t* own = NULL;
+  if (!order) {
+    own = (uint32_t*)malloc(m * sizeof(uint32_t));
+    if (!own) return -1;
+    vo_new_points_order(n_old, m, seed, own);
+    order = own;
+  } else {
+    /* every new id exactly once */
+    unsigned char* seen = (unsigned char*)calloc(m, 1);
+    if (!seen) return -1;
+    int bad = 0;
+    for (uint64_t i = 0; i < m && !bad; ++i) {
+      if (order[i] < n_old || order[i] >= n || seen[order[i] - n_old]) bad = 1;
+      else seen[order[i] - n_old] = 1;
+    }
+    free(seen);
+    if (bad) return -1;
+  }
+  uint64_t rounds = vo_schedule_from(n_old - 1, m, theta, NULL);
+  uint64_t* bounds = (uint64_t*)malloc((rounds + 1) * sizeof(uint64_t));
+  if (!bounds) {
+    free(own);
+    return -1;
+  }
+  vo_schedule_from(n_old - 1, m, theta, bounds);
+  int rc = 0;
+  for (uint64_t r = 0; r < rounds; ++r) {
+    if (max_rounds && r >= max_rounds) break;
+    rc = vo_batch_insert(D, graph, R, start, order + bounds[r], bounds[r + 1] - bounds[r], L,
+                         alpha, threads, stats);
+    if (stats) stats->rounds += 1;
+    if (rc) break;
+  }
+  free(bounds);
+  free(own);
+  return rc;
+}
+
+/* ------------------------------------------------------------------ */
 /* batched queries and exhaustive search                                */
 /* ------------------------------------------------------------------ */
 

@@ -38,7 +38,9 @@
  * (huge alpha), single neighbour (tiny alpha), a hand-worked 1-D example and
  * an independent audit of every kept/dropped candidate; the schedule against
  * its closed form; batch insertion with every batch of size one against
- * Alg. 2; a hand-worked five-point build; degree and snapshot invariants.
+ * Alg. 2; a hand-worked five-point build; degree and snapshot invariants;
+ * streaming insertion against the one-shot build whose batches it continues
+ * and, with theta = 1, against Alg. 2 point by point.
  */
 #ifndef VAMANA_ORACLE_H
 #define VAMANA_ORACLE_H
@@ -132,6 +134,27 @@ int vo_batch_insert(const vo_data* data, uint32_t* graph, uint32_t R, uint32_t s
 int vo_build(const vo_data* data, uint32_t R, uint32_t L, double alpha, uint64_t seed,
              uint64_t theta, uint32_t start, const uint32_t* order, uint64_t max_rounds,
              int threads, uint32_t* graph, uint32_t* start_out, vo_stats* stats);
+
+/* Streaming insertion of the points n_old..n-1 (n = data->n) into a graph
+ * that holds the points 0..n_old-1: `graph` is n x R, rows of the new ids
+ * all VO_NONE on entry.  The new ids are taken in `order` (n - n_old ids,
+ * each new id once) or, when it is NULL, in the order vo_new_points_order
+ * draws from `seed`; they are inserted with BatchInsert of Alg. 3 in batches
+ * of min(present + 2, theta, left) points, `present` counting the points
+ * other than the start vertex that the graph holds at that moment: the
+ * schedule of vo_build carried on.  theta = 0 means max(1, n/50).  The start
+ * vertex stays what it was.                                                 */
+int vo_insert_points(const vo_data* data, uint32_t* graph, uint32_t R, uint32_t start,
+                     uint64_t n_old, uint32_t L, double alpha, uint64_t seed, uint64_t theta,
+                     const uint32_t* order, uint64_t max_rounds, int threads, vo_stats* stats);
+
+/* The ids first..first+count-1 shuffled like vo_insertion_order shuffles
+ * the ids of a build (Fisher-Yates from the back, SplitMix64(seed)).        */
+void vo_new_points_order(uint64_t first, uint64_t count, uint64_t seed, uint32_t* order);
+
+/* vo_schedule for m further points when `present` are already in: bounds[0]
+ * = 0 < ... < bounds[rounds] = m, relative to the first new point.          */
+uint64_t vo_schedule_from(uint64_t present, uint64_t m, uint64_t theta, uint64_t* bounds);
 
 /* Sequential build: Alg. 2 applied to every id of the order, one by one.   */
 int vo_build_sequential(const vo_data* data, uint32_t R, uint32_t L, double alpha,

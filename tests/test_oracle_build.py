@@ -200,3 +200,113 @@ def test_quality(oracle, small):
     ids, _ = oracle.search_batch(ds, gs, s, small.queries, 10, 40, threads=4)
     ids_b, _ = oracle.search_batch(ds, g, s, small.queries, 10, 40, threads=4)
     assert abs(recall_at_k(ids, gt) - recall_at_k(ids_b, gt)) < 0.03
+
+
+# ---------------------------------------------------------------------------------------------
+# streaming insertion of new points (BatchInsert of Alg. 3 after the build, the schedule of
+# Sec. 3.1 carried on)
+# ---------------------------------------------------------------------------------------------
+
+def test_schedule_from_hand_worked_and_continuation(oracle):
+    # five points (besides the start vertex) are in, twenty follow, theta 8:
+    # min(5+2, 8, 20) = 7, min(12+2, 8, 13) = 8, min(20+2, 8, 5) = 5
+    assert np.diff(oracle.schedule_from(5, 20, 8).astype(np.int64)).tolist() == [7, 8, 5]
+    # nothing in yet: the build's own schedule
+    for m, theta in [(9999, 200), (1000, 3), (77, 10 ** 6), (0, 4)]:
+        assert oracle.schedule_from(0, m, theta).tolist() == oracle.schedule(m, theta).tolist()
+    # cut a build's schedule at any of its batch boundaries: what follows is the continuation
+    for m, theta in [(9999, 200), (300, 40), (1000, 10 ** 6)]:
+        b = oracle.schedule(m, theta).astype(np.int64)
+        for r in range(len(b)):
+            rest = oracle.schedule_from(int(b[r]), int(m - b[r]), theta).astype(np.int64)
+            assert (rest + b[r]).tolist() == b[r:].tolist()
+    # a large graph takes a small addition as one batch; theta still caps it
+    assert oracle.schedule_from(10 ** 6, 5000, 20100).tolist() == [0, 5000]
+    assert np.diff(oracle.schedule_from(10 ** 6, 5000, 2000).astype(np.int64)).tolist() == [2000, 2000, 1000]
+
+
+def test_new_points_order(oracle):
+    for first, count, seed in [(100, 1, 3), (100, 50, 3), (7, 1000, 12345678901234567)]:
+        got = oracle.new_points_order(first, count, seed)
+        ids = list(range(first, first + count))
+        st = seed
+        for i in range(count - 1, 0, -1):
+            st, r = _splitmix64(st)
+            j = (r * (i + 1)) >> 64
+            ids[i], ids[j] = ids[j], ids[i]
+        assert got.tolist() == ids
+    assert oracle.new_points_order(5, 0, 1).tolist() == []
+
+
+def test_streaming_insertion_continues_the_build(oracle, small):
+    """A build over all points, cut at a batch boundary, is the build over the points before the
+    cut followed by the streaming insertion of the rest (same start vertex, theta and order)."""
+    n, R, L, theta = 900, 8, 16, 60
+    pts = small.points[:n]
+    # put the start vertex among the first points and keep ids in insertion order, so that the
+    # prefix of the order is a prefix of the ids
+    full = oracle.Dataset(pts, 0)
+    s = 0
+    order = np.arange(1, n, dtype=np.uint32)
+    whole, _ = oracle.build(full, R, L, 1.2, theta=theta, start=s, order=order)
+    b = oracle.schedule(n - 1, theta).astype(np.int64)
+    for r in (3, 7, len(b) - 2):
+        n_old = int(b[r]) + 1
+        head, _ = oracle.build(oracle.Dataset(pts[:n_old], 0), R, L, 1.2, theta=theta, start=s,
+                               order=order[:n_old - 1])
+        grown = oracle.insert_points(full, head, s, L, 1.2, theta=theta, order=order[n_old - 1:])
+        assert (grown == whole).all()
+    # off a boundary the batches differ, and so does the graph
+    n_old = int(b[7]) + 1 + 5
+    head, _ = oracle.build(oracle.Dataset(pts[:n_old], 0), R, L, 1.2, theta=theta, start=s,
+                           order=order[:n_old - 1])
+    grown = oracle.insert_points(full, head, s, L, 1.2, theta=theta, order=order[n_old - 1:])
+    assert (grown != whole).any()
+
+
+def test_streaming_insertion_point_by_point_is_alg2(oracle, small):
+    n_old, n, R, L = 300, 420, 8, 16
+    pts = small.points[:n]
+    ds_old, ds = oracle.Dataset(pts[:n_old], 0), oracle.Dataset(pts, 0)
+    head, s = oracle.build(ds_old, R, L, 1.2, seed=5)
+    order = oracle.new_points_order(n_old, n - n_old, 9)
+    grown = oracle.insert_points(ds, head, s, L, 1.2, seed=9, theta=1)
+    ref = np.full((n, R), NONE, np.uint32)
+    ref[:n_old] = head
+    for p in order:
+        oracle.insert(ds, ref, s, int(p), L, 1.2)
+    assert (grown == ref).all()
+    # default order = the seeded shuffle of the new ids; an explicit order is taken as given
+    again = oracle.insert_points(ds, head, s, L, 1.2, theta=1, order=order)
+    assert (again == grown).all()
+
+
+def test_streaming_insertion_invariants_and_quality(oracle, small):
+    n_old, n, R, L = 1000, 1500, 16, 32
+    pts = small.points[:n]
+    ds = oracle.Dataset(pts, 0)
+    head, s = oracle.build(oracle.Dataset(pts[:n_old], 0), R, L, 1.2, seed=1)
+    st = oracle.Stats()
+    grown = oracle.insert_points(ds, head, s, L, 1.2, seed=2, stats=st)
+    # theta = 1500 / 50 = 30: 500 points in 17 batches
+    assert st.rounds == 17
+    for v in range(n):
+        row = row_list(grown[v])
+        assert len(row) == len(set(row)) and v not in row and all(u < n for u in row)
+        assert (grown[v][len(row):] == NONE).all()
+    assert all(len(row_list(grown[v])) > 0 for v in range(n_old, n))
+    # rows of old points changed only by gaining new ids or by a prune of old and new ids
+    touched = [v for v in range(n_old) if (grown[v] != head[v]).any()]
+    assert touched and all(any(u >= n_old for u in row_list(grown[v])) or
+                           set(row_list(grown[v])) < set(row_list(head[v])) | set(range(n_old, n))
+                           for v in touched)
+    # an invalid order is refused
+    with pytest.raises(RuntimeError):
+        oracle.insert_points(ds, head, s, L, 1.2, order=np.arange(n_old - 1, n - 1, dtype=np.uint32))
+    # the grown graph answers queries as well as a graph built in one go
+    q = small.queries[:100]
+    gt, _ = oracle.brute_force(ds, q, 10)
+    ids, _ = oracle.search_batch(ds, grown, s, q, 10, 32)
+    whole, s2 = oracle.build(ds, R, L, 1.2, seed=1)
+    ids2, _ = oracle.search_batch(ds, whole, s2, q, 10, 32)
+    assert recall_at_k(ids, gt) > recall_at_k(ids2, gt) - 0.03 > 0.8
