@@ -188,6 +188,26 @@ def main():
     st = gs.stats()
     del gs
     say("build with statistics done")
+    # streaming insertion (not part of the step): a graph over the first 90 % of the points takes
+    # the last 10 % with ann_insert_points, i.e. the same batches of theta points the build ends
+    # with, each followed by a host check
+    stream = None
+    if w.n <= 20_000_000 and w.n >= 1000:
+        n0 = w.n - w.n // 10
+        gi = A.ann_build(pts[:n0], w.R, w.L, w.alpha, seed=w.seed, metric=metric)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        A.ann_insert_points(gi, pts, w.L, w.alpha, seed=w.seed + 1)
+        torch.cuda.synchronize()
+        t_ins = time.perf_counter() - t0
+        batches = int(gi.info().rounds)
+        ms_i, ids_i = time_search(torch, A, gi, pts, qs, k, L90, reps=1, eps=eps90)
+        stream = {"graph_points": n0, "new_points": w.n - n0, "ms": round(t_ins * 1e3, 2),
+                  "points_per_s": round((w.n - n0) / t_ins, 1),
+                  "recall_after": round(recall(ids_i.cpu().numpy().view(np.uint32), gt), 4),
+                  "total_batches": batches}
+        del gi
+        say(f"streaming insertion of {w.n - n0} points: {t_ins * 1e3:.1f} ms")
     ms_per_step = float(np.mean(step_ms))
     bms = float(np.mean(build_ms))
     points_per_s = w.n / (bms / 1e3)
@@ -239,6 +259,7 @@ def main():
         "qps_at_recall_0.95": {"L": L95, "eps": eps95, "recall": round(r95, 4),
                                "qps": round(qs.shape[0] / ms95 * 1e3, 1)},
         "search_sweep": sweep,
+        "stream_insert": stream,
         "build_counters": {kk: int(st[kk]) for kk in ("searches", "hops", "evals", "prunes", "reprunes", "appends",
                                                       "edges", "prune_evals", "redone", "rounds")},
         "build_phase_ms": phases,

@@ -133,6 +133,39 @@ int ann_insert_batch(ann_graph* g, const void* points_dev, const uint32_t* ids_h
                      uint32_t L, float alpha, void* stream);
 
 /*
+ * Streaming insertion: the graph, which holds the points 0..n-1, takes in the
+ * points n..n_total-1 with BatchInsert of Alg. 3, in batches that carry on the
+ * prefix-doubling schedule of ann_build (Sec. 3.1): min(present + 2, theta,
+ * left) points at a time, `present` counting the graph's points other than
+ * the start vertex.  The start vertex stays what it is.  Deterministic like
+ * the build: the result depends on the arguments only.
+ *   points_dev  n_total x d elements of the graph's dtype (device); its first
+ *               n rows are the points the graph holds (the same array as
+ *               before, or a copy that was extended)
+ *   n_total     >= the graph's n and < 2^31; equal: nothing happens
+ *   seed        drives the order of the new ids (the shuffle of ann_build
+ *               applied to the list n, n+1, ..., n_total-1)
+ *   opts        may be NULL.  Read: batch_cap (theta; 0 = max(1, n_total/50)),
+ *               order (n_total - n ids, every new id once, host), max_rounds.
+ *               The other fields keep the values given to ann_build.
+ * The adjacency rows move to a larger allocation when the capacity is
+ * exceeded (see ann_graph_reserve): pointers from ann_graph_device_rows are
+ * stale after the call, and no other call on this graph may be in flight.
+ * After an error the graph may hold some of the new points, inserted or as
+ * unreachable vertices with empty rows.  Blocks until done.
+ */
+int ann_insert_points(ann_graph* g, const void* points_dev, uint64_t n_total, uint32_t L, float alpha,
+                      uint64_t seed, const ann_build_opts* opts, void* stream);
+
+/*
+ * Room for n_cap points in the graph's arrays, so that ann_insert_points up
+ * to that size moves nothing.  (Without it the capacity grows by half each
+ * time it is exceeded.)  Never shrinks.  Blocks; invalidates the pointer of
+ * ann_graph_device_rows when it grows.
+ */
+int ann_graph_reserve(ann_graph* g, uint64_t n_cap, void* stream);
+
+/*
  * greedySearch(q, s, L, k) of Alg. 1 for nq queries (one wavefront each).
  *   queries_dev  nq x d elements of the graph's dtype (device)
  *   ids_dev      nq x k uint32 (device): the k closest found, ascending by

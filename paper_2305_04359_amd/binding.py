@@ -54,7 +54,7 @@ class Stats(C.Structure):
 
 
 EXPORTS = [
-    "ann_build", "ann_insert_batch", "ann_search", "ann_search_eps", "ann_start_vertex", "ann_graph_from_host",
+    "ann_build", "ann_insert_batch", "ann_insert_points", "ann_graph_reserve", "ann_search", "ann_search_eps", "ann_start_vertex", "ann_graph_from_host",
     "ann_graph_copy_neighbors", "ann_graph_device_rows", "ann_graph_info", "ann_get_stats",
     "ann_graph_free", "ann_sort_edges", "ann_last_error",
 ]
@@ -81,6 +81,10 @@ def lib():
                                 C.POINTER(BuildOpts), vp, C.POINTER(vp)]
         L.ann_insert_batch.restype = C.c_int
         L.ann_insert_batch.argtypes = [vp, vp, vp, u64, u32, C.c_float, vp]
+        L.ann_insert_points.restype = C.c_int
+        L.ann_insert_points.argtypes = [vp, vp, u64, u32, C.c_float, u64, C.POINTER(BuildOpts), vp]
+        L.ann_graph_reserve.restype = C.c_int
+        L.ann_graph_reserve.argtypes = [vp, u64, vp]
         L.ann_search.restype = C.c_int
         L.ann_search.argtypes = [vp, vp, vp, u64, u32, u32, vp, vp, vp]
         L.ann_search_eps.restype = C.c_int
@@ -206,6 +210,27 @@ def ann_insert_batch(graph: Graph, points, ids, L, alpha) -> None:
     ids = np.ascontiguousarray(ids, dtype=np.uint32)
     _check(lib().ann_insert_batch(graph.handle, points.data_ptr(), ids.ctypes.data_as(C.c_void_p),
                                   ids.shape[0], L, float(alpha), _stream_ptr()))
+
+
+def ann_insert_points(graph: Graph, points, L, alpha, seed=1, batch_cap=0, order=None, max_rounds=0) -> None:
+    """Streams the rows of `points` beyond the graph's current size into the graph (BatchInsert of
+    Alg. 3 on the continued schedule); `points` holds the old points first, then the new ones."""
+    points = _dev2d(points, "points")
+    o = BuildOpts()
+    o.batch_cap = batch_cap
+    o.max_rounds = max_rounds
+    keep = None
+    if order is not None:
+        keep = np.ascontiguousarray(order, dtype=np.uint32)
+        o.order = keep.ctypes.data
+        if keep.shape != (points.shape[0] - graph.info().n,):
+            raise ValueError("order must hold one id per new point")
+    _check(lib().ann_insert_points(graph.handle, points.data_ptr(), points.shape[0], L, float(alpha), seed,
+                                   C.byref(o), _stream_ptr()))
+
+
+def ann_graph_reserve(graph: Graph, n_cap) -> None:
+    _check(lib().ann_graph_reserve(graph.handle, int(n_cap), _stream_ptr()))
 
 
 def ann_search_eps(graph: Graph, points, queries, k, L, eps, ids_out=None, dists_out=None):

@@ -123,8 +123,13 @@ u64 splitmix64(u64& state) {
 
 }  // namespace
 
+namespace {
+struct BatchScratch;
+}
+
 struct ann_graph {
   u64 n = 0;
+  u64 cap = 0;  // rows and meta are allocated for this many points (>= n)
   u32 d = 0, R = 0;
   int dtype = 0, metric = 0;
   u32 start = 0;
@@ -145,8 +150,13 @@ struct ann_graph {
   u64 pad_stride = 0;
   mutable void* pad_buf = nullptr;
   mutable const void* pad_src = nullptr;
+  mutable u64 pad_cap = 0;   // rows pad_buf has room for
+  mutable u64 pad_done = 0;  // leading rows of pad_src that pad_buf holds
   mutable void* qpad_buf = nullptr;
   mutable u64 qpad_rows = 0;
+  // scratch of the insertions that follow the build (ann_insert_batch, ann_insert_points), kept
+  // between calls: allocating and freeing it costs more than a batch of ten thousand points
+  BatchScratch* scratch = nullptr;
 };
 
 namespace {
@@ -177,16 +187,34 @@ int pad_rows(const void* src, u64 nrows, u32 rb, void* dst, u64 stride, hipStrea
   return ANN_OK;
 }
 
-// The array the kernels read for `points_dev`: itself, or the graph's padded copy of it.
+// The array the kernels read for `points_dev`: itself, or the graph's padded copy of it.  The
+// copy follows the graph as it grows: rows already copied from the same array stay, only the new
+// ones are added.
 int resolve_points(const ann_graph* g, const void* points_dev, hipStream_t st, const void** out) {
   *out = points_dev;
   if (!g->pad_stride) return ANN_OK;
-  if (g->pad_src != points_dev) {
-    if (!g->pad_buf) HIP_TRY(hipMalloc(&g->pad_buf, (size_t)g->n * g->pad_stride));
+  if (g->pad_cap < g->n) {
+    if (g->pad_buf) {
+      HIP_TRY(hipDeviceSynchronize());  // earlier calls may still read the old copy
+      (void)hipFree(g->pad_buf);
+      g->pad_buf = nullptr;
+    }
+    g->pad_cap = 0;
     g->pad_src = nullptr;
-    int rc = pad_rows(points_dev, g->n, g->d, g->pad_buf, g->pad_stride, st);
+    g->pad_done = 0;
+    const u64 want = g->cap > g->n ? g->cap : g->n;
+    HIP_TRY(hipMalloc(&g->pad_buf, (size_t)want * g->pad_stride));
+    g->pad_cap = want;
+  }
+  if (g->pad_src != points_dev) g->pad_done = 0;
+  if (g->pad_done < g->n) {
+    g->pad_src = nullptr;
+    const u64 first = g->pad_done;
+    int rc = pad_rows(static_cast<const char*>(points_dev) + first * g->d, g->n - first, g->d,
+                      static_cast<char*>(g->pad_buf) + first * g->pad_stride, g->pad_stride, st);
     if (rc) return rc;
     g->pad_src = points_dev;
+    g->pad_done = g->n;
   }
   *out = g->pad_buf;
   return ANN_OK;
@@ -223,7 +251,9 @@ struct BatchScratch {
   // events that order them against the caller's stream
   hipStream_t side[2] = {nullptr, nullptr};
   hipEvent_t ev_plan = nullptr, ev_side[2] = {nullptr, nullptr};
+  u32* host_flag = nullptr;  // pinned: where the host reads the overflow count of a batch
   ~BatchScratch() {
+    if (host_flag) (void)hipHostFree(host_flag);
     for (auto& s : side)
       if (s) (void)hipStreamDestroy(s);
     if (ev_plan) (void)hipEventDestroy(ev_plan);
@@ -253,6 +283,7 @@ struct BatchScratch {
     HIP_TRY(arena.alloc(arena_cap * 8));
     HIP_TRY(spill.alloc(spill_cap * 8));
     HIP_TRY(vis_where.alloc(b * 8));
+    HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&host_flag), 64, hipHostMallocDefault));
     for (auto& s : side) HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
     HIP_TRY(hipEventCreateWithFlags(&ev_plan, hipEventDisableTiming));
     for (auto& e : ev_side) HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
@@ -395,8 +426,9 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   // searches whose visited list fit nowhere are redone with as much room as they need
   u32 novf = 0;
   if (sync) {
-    HIP_TRY(hipMemcpyAsync(&novf, small + 0, 4, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(S.host_flag, small + 0, 4, hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
+    novf = S.host_flag[0];
   }
   if (novf > 0) {
     std::vector<u32> slots(novf), nv(b);
@@ -506,6 +538,29 @@ int finish_batches(ann_graph* g, BatchScratch& S, PhaseTimer& tm, hipStream_t st
   return ANN_OK;
 }
 
+// The graph's own scratch with room for a batch of b points, made or enlarged when needed.
+int graph_scratch(ann_graph* g, u64 b, u32 L, hipStream_t st, BatchScratch** out) {
+  const u32 cap = g->visited_cap ? g->visited_cap : (4 * L > 256 ? 4 * L : 256);
+  if (g->scratch && (g->scratch->bmax < b || g->scratch->vis_cap != cap)) {
+    delete g->scratch;
+    g->scratch = nullptr;
+  }
+  if (!g->scratch) {
+    g->scratch = new (std::nothrow) BatchScratch();
+    if (!g->scratch) return fail(ANN_ENOMEM, "host allocation failed");
+    int rc = g->scratch->alloc(b, g->R, cap, g->spill_keys ? g->spill_keys : default_spill_keys(b));
+    if (rc) {
+      delete g->scratch;
+      g->scratch = nullptr;
+      return rc;
+    }
+  } else {
+    HIP_TRY(hipMemsetAsync(g->scratch->small.p, 0, 64, st));  // flags of an earlier call that failed
+  }
+  *out = g->scratch;
+  return ANN_OK;
+}
+
 int new_graph(u64 n, u32 d, int dtype, int metric, u32 R, ann_graph** out) {
   std::string why;
   DistCfg cfg{};
@@ -524,6 +579,7 @@ int new_graph(u64 n, u32 d, int dtype, int metric, u32 R, ann_graph** out) {
   ann_graph* g = new (std::nothrow) ann_graph();
   if (!g) return fail(ANN_ENOMEM, "host allocation failed");
   g->n = n;
+  g->cap = n;
   g->d = d;
   g->R = R;
   g->dtype = dtype;
@@ -543,6 +599,49 @@ int new_graph(u64 n, u32 d, int dtype, int metric, u32 R, ann_graph** out) {
   return ANN_OK;
 }
 
+// Room for `want` points: rows and meta move to larger arrays when the capacity is exceeded
+// (everything that may still read the old ones is waited for first).
+int reserve_rows(ann_graph* g, u64 want, hipStream_t st) {
+  if (want <= g->cap) return ANN_OK;
+  if (want >= (1ull << 31)) return fail(ANN_EINVAL, "n must stay below 2^31");
+  u32* rows = nullptr;
+  u32* meta = nullptr;
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&rows), (size_t)want * g->R * sizeof(u32));
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&meta), (size_t)want * sizeof(u32));
+  if (e == hipSuccess)
+    e = hipMemcpyAsync(rows, g->rows, (size_t)g->n * g->R * sizeof(u32), hipMemcpyDeviceToDevice, st);
+  if (e == hipSuccess) e = hipMemcpyAsync(meta, g->meta, (size_t)g->n * sizeof(u32), hipMemcpyDeviceToDevice, st);
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e != hipSuccess) {
+    if (rows) (void)hipFree(rows);
+    if (meta) (void)hipFree(meta);
+    return fail(e == hipErrorOutOfMemory ? ANN_ENOMEM : ANN_EHIP, "graph growth: %s", hipGetErrorString(e));
+  }
+  (void)hipFree(g->rows);
+  (void)hipFree(g->meta);
+  g->rows = rows;
+  g->meta = meta;
+  g->cap = want;
+  return ANN_OK;
+}
+
+// The graph gets the vertices n..n_total-1, with empty rows.
+int grow_graph(ann_graph* g, u64 n_total, hipStream_t st) {
+  if (n_total > g->cap) {
+    // at least half as much again, so that a stream of small additions copies the rows rarely
+    u64 want = g->cap + g->cap / 2;
+    if (want < n_total) want = n_total;
+    if (want >= (1ull << 31)) want = n_total;
+    int rc = reserve_rows(g, want, st);
+    if (rc) return rc;
+  }
+  const u64 add = n_total - g->n;
+  HIP_TRY(hipMemsetAsync(g->rows + g->n * g->R, 0xFF, (size_t)add * g->R * sizeof(u32), st));
+  HIP_TRY(hipMemsetAsync(g->meta + g->n, 0, (size_t)add * sizeof(u32), st));
+  g->n = n_total;
+  return ANN_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -556,6 +655,7 @@ void ann_graph_free(ann_graph* g) {
   if (g->counters) (void)hipFree(g->counters);
   if (g->pad_buf) (void)hipFree(g->pad_buf);
   if (g->qpad_buf) (void)hipFree(g->qpad_buf);
+  delete g->scratch;
   delete g;
 }
 
@@ -675,10 +775,10 @@ int ann_insert_batch(ann_graph* g, const void* points_dev, const uint32_t* ids_h
   for (u64 i = 0; i < b; ++i)
     if (ids_host[i] >= g->n || ids_host[i] == g->start) return fail(ANN_EINVAL, "bad id in batch");
   hipStream_t st = static_cast<hipStream_t>(stream);
-  BatchScratch S;
-  const u32 cap = g->visited_cap ? g->visited_cap : (4 * L > 256 ? 4 * L : 256);
-  rc = S.alloc(b, g->R, cap, g->spill_keys ? g->spill_keys : default_spill_keys(b));
+  BatchScratch* Sp = nullptr;
+  rc = graph_scratch(g, b, L, st, &Sp);
   if (rc) return rc;
+  BatchScratch& S = *Sp;
   HIP_TRY(hipMemcpy(S.qidx.p, ids_host, (size_t)b * 4, hipMemcpyHostToDevice));
   PhaseTimer tm;
   rc = tm.init(g->collect);
@@ -689,6 +789,98 @@ int ann_insert_batch(ann_graph* g, const void* points_dev, const uint32_t* ids_h
   rc = batch_insert(g, pts, ids_host, S.qidx.as<u32>(), b, L, alpha, S, tm, st, /*sync=*/true);
   if (rc) return rc;
   rc = finish_batches(g, S, tm, st);
+  return rc == ANN_LOST_LIST ? fail(ANN_EINTERNAL, "a visited list was lost in a synchronised batch") : rc;
+}
+
+int ann_graph_reserve(ann_graph* g, uint64_t n_cap, void* stream) {
+  if (!g) return fail(ANN_EINVAL, "null argument");
+  return reserve_rows(g, n_cap, static_cast<hipStream_t>(stream));
+}
+
+int ann_insert_points(ann_graph* g, const void* points_dev, uint64_t n_total, uint32_t L, float alpha,
+                      uint64_t seed, const ann_build_opts* opts, void* stream) {
+  if (!g || !points_dev) return fail(ANN_EINVAL, "null argument");
+  int rc = check_insert_params(g, L, alpha);
+  if (rc) return rc;
+  if (n_total < g->n) return fail(ANN_EINVAL, "n_total is below the number of points in the graph");
+  if (n_total >= (1ull << 31)) return fail(ANN_EINVAL, "n must stay below 2^31");
+  ann_build_opts o{};
+  if (opts) o = *opts;
+  const u64 n_old = g->n, m = n_total - n_old;
+  if (m == 0) return ANN_OK;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const bool trace = getenv("ANN_TRACE_BUILD") != nullptr;  // wall-clock breakdown on stderr
+  auto now_ms = [] {
+    timespec ts;
+    clock_gettime(CLOCK_MONOTONIC, &ts);
+    return ts.tv_sec * 1e3 + ts.tv_nsec / 1e6;
+  };
+  const double t_begin = now_ms();
+
+  // the new ids in the order they go in: as given, or shuffled like the ids of a build
+  std::vector<u32> order(m);
+  if (o.order) {
+    std::vector<unsigned char> seen(m, 0);
+    for (u64 i = 0; i < m; ++i) {
+      const u32 id = o.order[i];
+      if (id < n_old || id >= n_total || seen[id - n_old]) return fail(ANN_EINVAL, "order must list every new id once");
+      seen[id - n_old] = 1;
+      order[i] = id;
+    }
+  } else {
+    for (u64 i = 0; i < m; ++i) order[i] = (u32)(n_old + i);
+    u64 state = seed;
+    for (u64 i = m; i-- > 1;) {
+      const u64 r = splitmix64(state);
+      const u64 j = (u64)(((unsigned __int128)r * (unsigned __int128)(i + 1)) >> 64);
+      const u32 t = order[i];
+      order[i] = order[j];
+      order[j] = t;
+    }
+  }
+
+  // the schedule of the build carried on: a batch at most doubles what is there, theta caps it
+  u64 theta = o.batch_cap ? o.batch_cap : (n_total / 50 > 1 ? n_total / 50 : 1);
+  if (theta * g->R >= (1ull << 32)) theta = ((1ull << 32) - 1) / g->R;
+  std::vector<u64> bounds{0};
+  u64 bmax = 1;
+  for (u64 taken = 0; taken < m;) {
+    u64 size = (n_old - 1) + taken + 2;
+    if (size > theta) size = theta;
+    if (size > m - taken) size = m - taken;
+    taken += size;
+    bounds.push_back(taken);
+    bmax = size > bmax ? size : bmax;
+  }
+
+  const double t_order = now_ms();
+  rc = grow_graph(g, n_total, st);
+  if (rc) return rc;
+  const double t_grow = now_ms();
+  BatchScratch* Sp = nullptr;
+  rc = graph_scratch(g, bmax, L, st, &Sp);
+  if (rc) return rc;
+  BatchScratch& S = *Sp;
+  PhaseTimer tm;
+  rc = tm.init(g->collect);
+  if (rc) return rc;
+  const void* pts = nullptr;
+  rc = resolve_points(g, points_dev, st, &pts);
+  if (rc) return rc;
+  const double t_alloc = now_ms();
+  // Every batch waits on the host after step 1 (the check for visited lists that fit nowhere):
+  // unlike a build, an insertion cannot start over from the empty graph.
+  for (size_t r = 0; r + 1 < bounds.size(); ++r) {
+    if (o.max_rounds && r >= o.max_rounds) break;
+    const u64 lo = bounds[r], b = bounds[r + 1] - bounds[r];
+    HIP_TRY(hipMemcpyAsync(S.qidx.p, order.data() + lo, b * 4, hipMemcpyHostToDevice, st));
+    rc = batch_insert(g, pts, order.data() + lo, S.qidx.as<u32>(), b, L, alpha, S, tm, st, /*sync=*/true);
+    if (rc) return rc;
+  }
+  rc = finish_batches(g, S, tm, st);
+  if (trace)
+    fprintf(stderr, "ann_insert_points: order %.2f ms, growth %.2f ms, scratch %.2f ms, %zu batches %.2f ms\n",
+            t_order - t_begin, t_grow - t_order, t_alloc - t_grow, bounds.size() - 1, now_ms() - t_alloc);
   return rc == ANN_LOST_LIST ? fail(ANN_EINTERNAL, "a visited list was lost in a synchronised batch") : rc;
 }
 

@@ -569,3 +569,156 @@ def test_search_eps_c2_full_size(env, c2_full):
         assert (ids.cpu().numpy().view(np.uint32) == oi).all()
         assert (dists.cpu().numpy().view(np.int32) == od.view(np.int32)).all()
         assert sp.hops < so.hops
+
+
+# ------------------------------------------------------------------------------------------
+# streaming insertion of new points (ann_insert_points): BatchInsert of Alg. 3 after the build
+# ------------------------------------------------------------------------------------------
+def test_insert_points_c1_bit_exact(env, c1):
+    """Build over the first 6,000 points, stream the rest in with two calls: rows, start vertex
+    and query answers identical to the oracle's at every stage; the capacity of the row array
+    (grown on demand, or reserved in advance) does not show."""
+    torch, A, O = env
+    cuts = (6000, 8500, c1.n)
+    pts = dev(torch, c1.points)
+    og, s = O.build(O.Dataset(c1.points[:cuts[0]], 0), c1.R, c1.L, c1.alpha, seed=c1.seed, threads=0)
+    g = A.ann_build(pts[:cuts[0]], c1.R, c1.L, c1.alpha, seed=c1.seed)
+    g2 = A.ann_build(pts[:cuts[0]], c1.R, c1.L, c1.alpha, seed=c1.seed)
+    A.ann_graph_reserve(g2, c1.n)
+    assert g.info().start == s and (g.neighbors() == og).all() and (g2.neighbors() == og).all()
+    for seed, n_tot in ((3, cuts[1]), (4, cuts[2])):
+        say(f"insert points up to {n_tot}")
+        ds = O.Dataset(c1.points[:n_tot], 0)
+        og = O.insert_points(ds, og, s, c1.L, c1.alpha, seed=seed, threads=0)
+        for gg in (g, g2):
+            A.ann_insert_points(gg, pts[:n_tot], c1.L, c1.alpha, seed=seed)
+            assert gg.info().n == n_tot and gg.info().start == s
+            rows = gg.neighbors()
+            assert rows.shape == og.shape
+            bad = np.nonzero((rows != og).any(1))[0]
+            assert len(bad) == 0, f"rows differ: {bad[:10]}"
+        ids, dists = A.ann_search(g, pts[:n_tot], dev(torch, c1.queries), 10, 40)
+        oi, od = O.search_batch(ds, og, s, c1.queries, 10, 40, threads=0)
+        assert (ids.cpu().numpy().view(np.uint32) == oi).all() and (dists.cpu().numpy() == od).all()
+    # nothing to add: nothing happens
+    A.ann_insert_points(g, pts, c1.L, c1.alpha, seed=9)
+    assert (g.neighbors() == og).all()
+
+
+def test_insert_points_continues_a_build(env, c1):
+    """A build cut at a batch boundary and continued by ann_insert_points is the one-shot build
+    (same start vertex, theta and order), also when the remainder arrives in two calls that
+    each end on a boundary."""
+    torch, A, O = env
+    n, theta = 5000, 300
+    pts = dev(torch, c1.points[:n])
+    order = np.arange(1, n, dtype=np.uint32)
+    whole = A.ann_build(pts, 16, 32, 1.2, batch_cap=theta, start=0, order=order).neighbors()
+    b = O.schedule(n - 1, theta).astype(np.int64)
+    r1, r2 = 9, 14
+    n1, n2 = int(b[r1]) + 1, int(b[r2]) + 1
+    g = A.ann_build(pts[:n1], 16, 32, 1.2, batch_cap=theta, start=0, order=order[:n1 - 1])
+    A.ann_insert_points(g, pts[:n2], 32, 1.2, batch_cap=theta, order=order[n1 - 1:n2 - 1])
+    A.ann_insert_points(g, pts, 32, 1.2, batch_cap=theta, order=order[n2 - 1:])
+    assert (g.neighbors() == whole).all()
+    # max_rounds stops early: the rows of the points not yet reached stay empty
+    g = A.ann_build(pts[:n1], 16, 32, 1.2, batch_cap=theta, start=0, order=order[:n1 - 1])
+    A.ann_insert_points(g, pts, 32, 1.2, batch_cap=theta, order=order[n1 - 1:], max_rounds=2)
+    rows = g.neighbors()
+    assert (rows[int(b[r1 + 2]) + 1:] == NONE).all() and (rows[n1:int(b[r1 + 2]) + 1, 0] != NONE).all()
+
+
+def test_insert_points_padded_rows_and_moved_arrays(env):
+    """100-byte int8 rows (the kernels read a padded copy that has to follow the graph): the new
+    points arrive in the array the graph was built over (the copy is made anew when it has to
+    grow, extended when there is room) and then in a fresh copy of the points."""
+    torch, A, O = env
+    w = W.c3(n=6000, nq=200)
+    og, s = O.build(O.Dataset(w.points[:3000], 0), 24, 48, 1.2, seed=2, threads=0)
+    pts = dev(torch, w.points)
+    g = A.ann_build(pts[:3000], 24, 48, 1.2, seed=2)
+    assert (g.neighbors() == og).all()
+    A.ann_graph_reserve(g, 6000)
+    for seed, n_tot in ((5, 4000), (6, 5000)):
+        og = O.insert_points(O.Dataset(w.points[:n_tot], 0), og, s, 48, 1.2, seed=seed, threads=0)
+        A.ann_insert_points(g, pts[:n_tot], 48, 1.2, seed=seed)
+        assert (g.neighbors() == og).all()
+    moved = dev(torch, w.points.copy())
+    assert moved.data_ptr() != pts.data_ptr()
+    ds = O.Dataset(w.points, 0)
+    og = O.insert_points(ds, og, s, 48, 1.2, seed=7, theta=100, threads=0)
+    A.ann_insert_points(g, moved, 48, 1.2, seed=7, batch_cap=100)
+    assert (g.neighbors() == og).all()
+    ids, dists = A.ann_search(g, moved, dev(torch, w.queries), 10, 50)
+    oi, od = O.search_batch(ds, og, s, w.queries, 10, 50, threads=0)
+    assert (ids.cpu().numpy().view(np.uint32) == oi).all() and (dists.cpu().numpy() == od).all()
+
+
+def test_insert_points_f32(env):
+    torch, A, O = env
+    w = W.c4(n=8000, nq=400)
+    n0 = 5000
+    ds = O.Dataset(w.points, 1)
+    pts, qs = dev(torch, w.points), dev(torch, w.queries)
+    g = A.ann_build(pts[:n0], 32, 64, 1.0, seed=1, metric=A.MIPS)
+    s = int(g.info().start)
+    head = g.neighbors()
+    # the oracle continues from the GPU's graph, so that only this call's arithmetic differs
+    og = O.insert_points(ds, head, s, 64, 1.0, seed=7, threads=0)
+    A.ann_insert_points(g, pts, 64, 1.0, seed=7)
+    rows = g.neighbors()
+    deg = (rows != NONE).sum(1)
+    assert deg.max() <= 32 and deg[np.arange(len(deg)) != s].min() >= 1
+    assert (rows == og).all(1).mean() > 0.9  # near-ties in fp32 may flip a few rows
+    gt, _ = O.brute_force(ds, w.queries, 10)
+    gi, _ = A.ann_search(g, pts, qs, 10, 64)
+    oi, _ = O.search_batch(ds, og, s, w.queries, 10, 64, threads=0)
+    r_g, r_o = recall_at_k(gi.cpu().numpy().view(np.uint32), gt), recall_at_k(oi, gt)
+    say(f"  recall after streaming insertion: gpu={r_g:.4f} oracle={r_o:.4f}")
+    assert abs(r_g - r_o) <= 0.002
+
+
+def test_insert_points_bad_arguments(env, c1):
+    torch, A, O = env
+    pts = dev(torch, c1.points[:3000])
+    g = A.ann_build(pts[:2000], 8, 16, 1.2)
+    rows = g.neighbors()
+    with pytest.raises(A.AnnError):
+        A.ann_insert_points(g, pts[:1500], 16, 1.2)                      # fewer points than the graph holds
+    with pytest.raises(A.AnnError):
+        A.ann_insert_points(g, pts, 0, 1.2)                              # L
+    with pytest.raises(A.AnnError):
+        A.ann_insert_points(g, pts, 16, -1.0)                            # alpha
+    bad = np.arange(2000, 3000, dtype=np.uint32)
+    bad[5] = 1999                                                        # an id the graph already holds
+    with pytest.raises(A.AnnError):
+        A.ann_insert_points(g, pts, 16, 1.2, order=bad)
+    bad[5] = 2006                                                        # a new id twice
+    with pytest.raises(A.AnnError):
+        A.ann_insert_points(g, pts, 16, 1.2, order=bad)
+    assert g.info().n == 2000 and (g.neighbors() == rows).all()          # refused calls change nothing
+
+
+def test_insert_points_c2_full_size(env):
+    """At the benchmark's size and launch configuration: a graph over 995,000 points takes the
+    last 5,000 (one batch, theta = 20,000); the oracle does the same on a copy of that graph."""
+    torch, A, O = env
+    w = W.c2()
+    n0 = w.n - 5000
+    pts = dev(torch, w.points)
+    g = A.ann_build(pts[:n0], w.R, w.L, w.alpha, seed=w.seed)
+    s = int(g.info().start)
+    head = g.neighbors()
+    ds = O.Dataset(w.points, 0)
+    say("oracle streams 5,000 points into the 995,000-point graph")
+    st = O.Stats()
+    og = O.insert_points(ds, head, s, w.L, w.alpha, seed=11, threads=0, stats=st)
+    assert st.rounds == 1
+    A.ann_insert_points(g, pts, w.L, w.alpha, seed=11)
+    rows = g.neighbors()
+    assert ((og[:n0] != head).any(1)).sum() > 5000  # many old rows took reverse edges
+    bad = np.nonzero((rows != og).any(1))[0]
+    assert len(bad) == 0, f"rows differ: {bad[:10]}"
+    ids, dists = A.ann_search(g, pts, dev(torch, w.queries[:300]), 10, 40)
+    oi, od = O.search_batch(ds, og, s, w.queries[:300], 10, 40, threads=0)
+    assert (ids.cpu().numpy().view(np.uint32) == oi).all() and (dists.cpu().numpy() == od).all()
