@@ -1,4 +1,4 @@
-"""ctypes access to the CPU oracle (vamana_oracle.c).
+"""ctypes access to the CPU oracle (vamana_oracle.c, hnsw_oracle.c).
 
 TEST INFRASTRUCTURE.  Only tests/, the smoke check and the benchmark's CPU
 baseline leg may import this package; the HIP library and its Python binding
@@ -14,8 +14,8 @@ from dataclasses import dataclass
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "vamana_oracle.c")
-_HDR = os.path.join(_HERE, "vamana_oracle.h")
+_SRCS = [os.path.join(_HERE, f) for f in ("vamana_oracle.c", "hnsw_oracle.c")]
+_HDRS = [os.path.join(_HERE, f) for f in ("vamana_oracle.h", "hnsw_oracle.h")]
 _LIB = os.path.join(_HERE, "libvamana_oracle.so")
 
 NONE = 0xFFFFFFFF
@@ -40,12 +40,12 @@ def build_oracle(force: bool = False) -> str:
     stale = (
         force
         or not os.path.exists(_LIB)
-        or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_HDR))
+        or os.path.getmtime(_LIB) < max(os.path.getmtime(f) for f in _SRCS + _HDRS)
     )
     if stale:
         cmd = [
             "gcc", "-std=c11", "-O2", "-fopenmp", "-fno-fast-math", "-ffp-contract=off",
-            "-fPIC", "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm",
+            "-fPIC", "-shared", "-Wall", "-Wextra", "-o", _LIB, *_SRCS, "-lm",
         ]
         subprocess.run(cmd, check=True)
     return _LIB
@@ -58,6 +58,17 @@ class _Data(C.Structure):
         ("d", C.c_uint32),
         ("dtype", C.c_int),
         ("metric", C.c_int),
+    ]
+
+
+class _Hnsw(C.Structure):
+    _fields_ = [
+        ("n", C.c_uint64),
+        ("m", C.c_uint32),
+        ("top", C.c_uint32),
+        ("entry", C.c_uint32),
+        ("level", C.POINTER(C.c_uint32)),
+        ("rows", C.POINTER(C.POINTER(C.c_uint32))),
     ]
 
 
@@ -137,6 +148,26 @@ def lib():
         L.vo_brute_force.argtypes = [
             C.POINTER(_Data), C.c_void_p, C.c_uint64, C.c_uint32, C.c_int, C.c_void_p,
             C.c_void_p]
+        L.vo_batch_insert_from.restype = C.c_int
+        L.vo_batch_insert_from.argtypes = [
+            C.POINTER(_Data), C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint64,
+            C.c_uint32, C.c_double, C.c_int, C.c_void_p, C.POINTER(Stats)]
+        L.vo_search_batch_from.restype = C.c_int
+        L.vo_search_batch_from.argtypes = [
+            C.POINTER(_Data), C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint64,
+            C.c_uint32, C.c_uint32, C.c_double, C.c_int, C.c_void_p, C.c_void_p, C.POINTER(Stats)]
+        L.vo_hnsw_level.restype = C.c_uint32
+        L.vo_hnsw_level.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32]
+        L.vo_hnsw_build.restype = C.c_int
+        L.vo_hnsw_build.argtypes = [
+            C.POINTER(_Data), C.c_uint32, C.c_uint32, C.c_double, C.c_uint64, C.c_uint64, C.c_void_p,
+            C.c_void_p, C.c_uint64, C.c_int, C.POINTER(C.POINTER(_Hnsw)), C.POINTER(Stats)]
+        L.vo_hnsw_free.restype = None
+        L.vo_hnsw_free.argtypes = [C.POINTER(_Hnsw)]
+        L.vo_hnsw_search_batch.restype = C.c_int
+        L.vo_hnsw_search_batch.argtypes = [
+            C.POINTER(_Data), C.POINTER(_Hnsw), C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint32,
+            C.c_double, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(Stats)]
         L.vo_threads.restype = C.c_int
         L.vo_threads.argtypes = [C.c_int]
         _lib = L
@@ -351,3 +382,109 @@ def brute_force(ds: Dataset, queries: np.ndarray, k: int, threads: int = 0):
 
 def threads(t: int = 0) -> int:
     return int(lib().vo_threads(t))
+
+
+# ---------------------------------------------------------------------------------------------
+# layered index (hnsw_oracle.c)
+# ---------------------------------------------------------------------------------------------
+def batch_insert_from(ds: Dataset, graph: np.ndarray, starts: np.ndarray, batch: np.ndarray, L: int,
+                      alpha: float, threads: int = 1, stats: Stats | None = None) -> np.ndarray:
+    """BatchInsert with one start vertex per batch point; returns, per point, the closest
+    vertex its search visited."""
+    assert graph.dtype == np.uint32 and graph.flags.c_contiguous
+    batch = np.ascontiguousarray(batch, dtype=np.uint32)
+    starts = np.ascontiguousarray(starts, dtype=np.uint32)
+    assert starts.shape == batch.shape
+    near = np.empty(batch.shape[0], np.uint32)
+    rc = lib().vo_batch_insert_from(ds.c(), _ptr(graph), graph.shape[1], 0, _ptr(starts), _ptr(batch),
+                                    batch.shape[0], L, float(alpha), threads, _ptr(near),
+                                    C.byref(stats) if stats is not None else None)
+    if rc:
+        raise RuntimeError(f"vo_batch_insert_from rc={rc}")
+    return near
+
+
+def search_batch_from(ds: Dataset, graph: np.ndarray, starts: np.ndarray, queries: np.ndarray, k: int,
+                      L: int, eps: float = -1.0, threads: int = 1, stats: Stats | None = None):
+    queries = np.ascontiguousarray(queries)
+    starts = np.ascontiguousarray(starts, dtype=np.uint32)
+    nq = queries.shape[0]
+    ids = np.empty((nq, k), np.uint32)
+    dists = _dist_out(ds, (nq, k))
+    rc = lib().vo_search_batch_from(ds.c(), _ptr(graph), graph.shape[1], 0, _ptr(starts), _ptr(queries),
+                                    nq, k, L, float(eps), threads, _ptr(ids), _ptr(dists),
+                                    C.byref(stats) if stats is not None else None)
+    if rc:
+        raise RuntimeError(f"vo_search_batch_from rc={rc}")
+    return ids, dists
+
+
+def hnsw_level(seed: int, i: int, m: int) -> int:
+    return int(lib().vo_hnsw_level(seed, i, m))
+
+
+class Hnsw:
+    """A layered index: `level` (n), `layers[l]` = n x (2m if l == 0 else m) rows of global ids,
+    `entry`, `m`.  Either built by the oracle or put together by hand (for pins of the search)."""
+
+    def __init__(self, m: int, level: np.ndarray, layers: list, entry: int):
+        self.m = int(m)
+        self.level = np.ascontiguousarray(level, dtype=np.uint32)
+        self.layers = [np.ascontiguousarray(a, dtype=np.uint32) for a in layers]
+        self.entry = int(entry)
+        for l, a in enumerate(self.layers):
+            assert a.shape == (self.level.shape[0], 2 * self.m if l == 0 else self.m)
+
+    @property
+    def top(self):
+        return len(self.layers) - 1
+
+    def c(self):
+        arr = (C.POINTER(C.c_uint32) * len(self.layers))(
+            *[a.ctypes.data_as(C.POINTER(C.c_uint32)) for a in self.layers])
+        self._keep = arr
+        return _Hnsw(self.level.shape[0], self.m, self.top, self.entry,
+                     self.level.ctypes.data_as(C.POINTER(C.c_uint32)), arr)
+
+
+def hnsw_build(ds: Dataset, m: int, efc: int, alpha: float, seed: int = 1, theta: int = 0,
+               level: np.ndarray | None = None, order: np.ndarray | None = None, max_rounds: int = 0,
+               threads: int = 1, stats: Stats | None = None) -> Hnsw:
+    if level is not None:
+        level = np.ascontiguousarray(level, dtype=np.uint32)
+        assert level.shape == (ds.n,)
+    if order is not None:
+        order = np.ascontiguousarray(order, dtype=np.uint32)
+        assert order.shape == (ds.n - 1,)
+    hp = C.POINTER(_Hnsw)()
+    rc = lib().vo_hnsw_build(ds.c(), m, efc, float(alpha), seed, theta,
+                             _ptr(level) if level is not None else None,
+                             _ptr(order) if order is not None else None, max_rounds, threads,
+                             C.byref(hp), C.byref(stats) if stats is not None else None)
+    if rc:
+        raise RuntimeError(f"vo_hnsw_build rc={rc}")
+    h = hp.contents
+    n = int(h.n)
+    lev = np.ctypeslib.as_array(h.level, shape=(n,)).copy()
+    layers = [np.ctypeslib.as_array(h.rows[l], shape=(n, 2 * m if l == 0 else m)).copy()
+              for l in range(int(h.top) + 1)]
+    out = Hnsw(m, lev, layers, int(h.entry))
+    lib().vo_hnsw_free(hp)
+    return out
+
+
+def hnsw_search_batch(ds: Dataset, h: Hnsw, queries: np.ndarray, k: int, L: int, eps: float = -1.0,
+                      threads: int = 1, stats: Stats | None = None):
+    """Returns (ids, dists, layer-0 start vertex of every query)."""
+    queries = np.ascontiguousarray(queries)
+    nq = queries.shape[0]
+    ids = np.empty((nq, k), np.uint32)
+    dists = _dist_out(ds, (nq, k))
+    entry = np.empty(nq, np.uint32)
+    hc = h.c()
+    rc = lib().vo_hnsw_search_batch(ds.c(), C.byref(hc), _ptr(queries), nq, k, L, float(eps), threads,
+                                    _ptr(ids), _ptr(dists), _ptr(entry),
+                                    C.byref(stats) if stats is not None else None)
+    if rc:
+        raise RuntimeError(f"vo_hnsw_search_batch rc={rc}")
+    return ids, dists, entry

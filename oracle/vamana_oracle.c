@@ -546,6 +546,12 @@ static int edge_cmp(const void* pa, const void* pb) {
 int vo_batch_insert(const vo_data* D, uint32_t* graph, uint32_t R, uint32_t start,
                     const uint32_t* batch, uint64_t b, uint32_t L, double alpha, int threads,
                     vo_stats* stats) {
+  return vo_batch_insert_from(D, graph, R, start, NULL, batch, b, L, alpha, threads, NULL, stats);
+}
+
+int vo_batch_insert_from(const vo_data* D, uint32_t* graph, uint32_t R, uint32_t start,
+                         const uint32_t* starts, const uint32_t* batch, uint64_t b, uint32_t L,
+                         double alpha, int threads, uint32_t* nearest_out, vo_stats* stats) {
   if (b == 0) return 0;
   int nthreads = vo_threads(threads);
   (void)nthreads;
@@ -569,11 +575,13 @@ int vo_batch_insert(const vo_data* D, uint32_t* graph, uint32_t R, uint32_t star
       if (bad) continue;
       uint32_t p = batch[i];
       uint64_t nv = 0, nb = 0;
-      int rc = greedy_core(D, graph, R, start, row_ptr(D, p), L, 1, -1.0, &w, &nv, &nb, &st);
+      int rc = greedy_core(D, graph, R, starts ? starts[i] : start, row_ptr(D, p), L, 1, -1.0, &w,
+                           &nv, &nb, &st);
       if (rc) {
         bad = rc;
         continue;
       }
+      if (nearest_out) nearest_out[i] = w.beam[0].id; /* the closest vertex of V */
       if (nv > ids_cap) {
         ids_cap = nv * 2;
         ids = (uint32_t*)realloc(ids, ids_cap * sizeof(uint32_t));
@@ -809,7 +817,19 @@ int vo_search_batch(const vo_data* D, const uint32_t* graph, uint32_t R, uint32_
 int vo_search_batch_eps(const vo_data* D, const uint32_t* graph, uint32_t R, uint32_t start,
                         const void* queries, uint64_t nq, uint32_t k, uint32_t L, double eps,
                         int threads, uint32_t* ids_out, void* dists_out, vo_stats* stats) {
-  if (!D || !graph || !queries || k < 1 || k > L || start >= D->n) return -1;
+  return vo_search_batch_from(D, graph, R, start, NULL, queries, nq, k, L, eps, threads, ids_out,
+                              dists_out, stats);
+}
+
+int vo_search_batch_from(const vo_data* D, const uint32_t* graph, uint32_t R, uint32_t start,
+                         const uint32_t* starts, const void* queries, uint64_t nq, uint32_t k,
+                         uint32_t L, double eps, int threads, uint32_t* ids_out, void* dists_out,
+                         vo_stats* stats) {
+  if (!D || !graph || !queries || k < 1 || k > L) return -1;
+  if (!starts && start >= D->n) return -1;
+  if (starts)
+    for (uint64_t q = 0; q < nq; ++q)
+      if (starts[q] >= D->n) return -1;
   if (!(eps < 16384.0)) return -1;
   int nthreads = vo_threads(threads);
   (void)nthreads;
@@ -825,8 +845,8 @@ int vo_search_batch_eps(const vo_data* D, const uint32_t* graph, uint32_t R, uin
     for (int64_t q = 0; q < (int64_t)nq; ++q) {
       if (bad) continue;
       uint64_t nv = 0, nb = 0;
-      int rc = greedy_core(D, graph, R, start, (const char*)queries + (size_t)q * qbytes, L, k,
-                           eps, &w, &nv, &nb, &st);
+      int rc = greedy_core(D, graph, R, starts ? starts[q] : start,
+                           (const char*)queries + (size_t)q * qbytes, L, k, eps, &w, &nv, &nb, &st);
       if (rc) {
         bad = rc;
         continue;
@@ -834,7 +854,8 @@ int vo_search_batch_eps(const vo_data* D, const uint32_t* graph, uint32_t R, uin
       for (uint32_t i = 0; i < k; ++i) {
         int valid = i < nb;
         ids_out[(size_t)q * k + i] = valid ? w.beam[i].id : VO_NONE;
-        store_dist(dists_out, (size_t)q * k + i, D->dtype, valid ? w.beam[i].dist : 0.0, valid);
+        if (dists_out)
+          store_dist(dists_out, (size_t)q * k + i, D->dtype, valid ? w.beam[i].dist : 0.0, valid);
       }
     }
 #pragma omp critical

@@ -127,6 +127,14 @@ int vo_batch_insert(const vo_data* data, uint32_t* graph, uint32_t R, uint32_t s
                     const uint32_t* batch, uint64_t b, uint32_t L, double alpha,
                     int threads, vo_stats* stats);
 
+/* The same with a start vertex of its own for every batch point (starts[i],
+ * or `start` for all when starts is NULL); nearest_out[i], when given,
+ * receives the vertex closest to batch[i] among those its search visited.
+ * This is the form the layers of an HNSW index need (hnsw_oracle.h).       */
+int vo_batch_insert_from(const vo_data* data, uint32_t* graph, uint32_t R, uint32_t start,
+                         const uint32_t* starts, const uint32_t* batch, uint64_t b, uint32_t L,
+                         double alpha, int threads, uint32_t* nearest_out, vo_stats* stats);
+
 /* Alg. 3: whole build.  `order` (n-1 ids) may be NULL: then it is drawn from
  * `seed`.  `start` may be VO_NONE: then vo_start_vertex is used.  theta = 0
  * means max(1, n/50).  `graph` receives n x R.  max_rounds = 0 runs all
@@ -170,6 +178,13 @@ int vo_search_batch(const vo_data* data, const uint32_t* graph, uint32_t R, uint
 int vo_search_batch_eps(const vo_data* data, const uint32_t* graph, uint32_t R, uint32_t start,
                         const void* queries, uint64_t nq, uint32_t k, uint32_t L, double eps,
                         int threads, uint32_t* ids_out, void* dists_out, vo_stats* stats);
+
+/* The same with a start vertex of its own for every query (starts[q]; NULL:
+ * `start` for all); dists_out may be NULL.                                  */
+int vo_search_batch_from(const vo_data* data, const uint32_t* graph, uint32_t R, uint32_t start,
+                         const uint32_t* starts, const void* queries, uint64_t nq, uint32_t k,
+                         uint32_t L, double eps, int threads, uint32_t* ids_out, void* dists_out,
+                         vo_stats* stats);
 
 /* Exact k nearest neighbours by exhaustive scan under (distance, id).      */
 int vo_brute_force(const vo_data* data, const void* queries, uint64_t nq, uint32_t k,
