@@ -28,8 +28,10 @@
  *     describes the failure.  No exception or abort crosses this boundary.
  *   - `stream` is a hipStream_t passed as void* (NULL = default stream).
  *   - The library allocates its own scratch with hipMalloc and frees it
- *     before returning (the padded copies named above live as long as the
- *     graph); the caller owns every buffer it passes in.
+ *     before returning, except for what an object keeps until it is freed:
+ *     the padded copies named above, and the scratch of ann_insert_batch /
+ *     ann_insert_points (sized for the largest batch so far).  The caller
+ *     owns every buffer it passes in.
  */
 #ifndef ANN_H
 #define ANN_H
@@ -215,6 +217,74 @@ void ann_graph_free(ann_graph* g);
  * (the grouping step of BatchInsert; exposed for tests).  In place on
  * keys_dev; blocks.                                                         */
 int ann_sort_edges(uint64_t* keys_dev, uint64_t count, uint32_t key_bits, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Layered index (Sec. 4.2, ParlayHNSW): layer l holds the points whose level
+ * is at least l; every layer is built with the batch insertion of Alg. 3
+ * ("batch insertion for each layer"); the degree bound is m above the bottom
+ * layer and 2m on it (appendix, parameter paragraph); prune is the alpha rule
+ * of Sec. 4.1 on every layer.
+ *   level of point i   with r = the (i+1)-th output of SplitMix64(seed): the
+ *                      largest l with r <= floor((2^64 - 1) / m^l)
+ *   entry point        the point of the highest level, smallest id on ties;
+ *                      present on every layer from the start, never inserted
+ *   order, batches     as ann_build, the entry point in the start vertex's
+ *                      place
+ *   one batch          every point walks down from the entry point: on a
+ *                      layer above its level a search with beam 1 over the
+ *                      layer as it stood before the batch; on its own layers
+ *                      BatchInsert with beam efc; either way the closest
+ *                      vertex found is where it enters the layer below
+ * ------------------------------------------------------------------------ */
+typedef struct ann_hnsw ann_hnsw;
+
+typedef struct {
+  uint64_t batch_cap;     /* theta; 0 = max(1, n/50)                              */
+  const uint32_t* order;  /* host, n-1 ids (all but the entry point); NULL = seeded */
+  const uint32_t* level;  /* host, n levels (each <= 63); NULL = drawn from seed   */
+  uint64_t max_rounds;    /* stop after this many batches (0 = all)                */
+  uint32_t collect_stats; /* non-zero: counters and phase times (slower)           */
+} ann_hnsw_opts;
+
+typedef struct {
+  uint64_t n;
+  uint32_t d;
+  uint32_t m;
+  uint32_t dtype;
+  uint32_t metric;
+  uint32_t top;   /* highest layer */
+  uint32_t entry; /* entry point   */
+  uint64_t rounds;
+} ann_hnsw_info_t;
+
+/* Builds the index over points_dev (n x d, device; same types and sizes as
+ * ann_build, with R = 2m, i.e. 2 <= m <= 256).  efc is the beam width of the
+ * insertions.  The upper layers keep copies of their points (a fraction
+ * 1/(m-1) of the input).  Blocks until done.                                 */
+int ann_hnsw_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric,
+                   uint32_t m, uint32_t efc, float alpha, uint64_t seed, const ann_hnsw_opts* opts,
+                   void* stream, ann_hnsw** out);
+
+/* Queries: beam 1 from the entry point down to layer 1, then greedySearch of
+ * Alg. 1 on layer 0 from the vertex reached (with the (1 + eps) rule of
+ * ann_search_eps when eps >= 0).  Arguments and outputs as ann_search_eps;
+ * points_dev is the array the index was built over.  Asynchronous on stream. */
+int ann_hnsw_search(const ann_hnsw* h, const void* points_dev, const void* queries_dev, uint64_t nq,
+                    uint32_t k, uint32_t L, float eps, uint32_t* ids_dev, void* dists_dev, void* stream);
+
+int ann_hnsw_info(const ann_hnsw* h, ann_hnsw_info_t* info);
+/* n levels to host memory.                                                   */
+int ann_hnsw_copy_levels(const ann_hnsw* h, uint32_t* level_host);
+/* Number of points on a layer (n for layer 0).                               */
+int ann_hnsw_layer_size(const ann_hnsw* h, uint32_t layer, uint64_t* count);
+/* A layer to host memory: ids_host receives the ids of its count points in
+ * ascending order, rows_host their count x (layer ? m : 2m) adjacency rows in
+ * the same order, holding point ids, ANN_NONE padded.  Blocks.               */
+int ann_hnsw_copy_layer(const ann_hnsw* h, uint32_t layer, uint32_t* ids_host, uint32_t* rows_host);
+/* Counters of one layer (the beam-1 passes of points that do not belong to
+ * the layer count as searches of it).                                        */
+int ann_hnsw_get_stats(const ann_hnsw* h, uint32_t layer, ann_stats* stats);
+void ann_hnsw_free(ann_hnsw* h);
 
 /* Thread-local description of the last error on this thread ("" if none).   */
 const char* ann_last_error(void);

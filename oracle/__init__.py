@@ -162,6 +162,10 @@ def lib():
         L.vo_hnsw_build.argtypes = [
             C.POINTER(_Data), C.c_uint32, C.c_uint32, C.c_double, C.c_uint64, C.c_uint64, C.c_void_p,
             C.c_void_p, C.c_uint64, C.c_int, C.POINTER(C.POINTER(_Hnsw)), C.POINTER(Stats)]
+        L.vo_hnsw_insert_batch.restype = C.c_int
+        L.vo_hnsw_insert_batch.argtypes = [
+            C.POINTER(_Data), C.POINTER(_Hnsw), C.c_void_p, C.c_uint64, C.c_uint32, C.c_double, C.c_int,
+            C.POINTER(Stats)]
         L.vo_hnsw_free.restype = None
         L.vo_hnsw_free.argtypes = [C.POINTER(_Hnsw)]
         L.vo_hnsw_search_batch.restype = C.c_int
@@ -471,6 +475,17 @@ def hnsw_build(ds: Dataset, m: int, efc: int, alpha: float, seed: int = 1, theta
     out = Hnsw(m, lev, layers, int(h.entry))
     lib().vo_hnsw_free(hp)
     return out
+
+
+def hnsw_insert_batch(ds: Dataset, h: Hnsw, batch: np.ndarray, efc: int, alpha: float, threads: int = 1,
+                      stats: Stats | None = None) -> None:
+    """One batch into an existing index (its layer arrays are modified in place)."""
+    batch = np.ascontiguousarray(batch, dtype=np.uint32)
+    hc = h.c()
+    rc = lib().vo_hnsw_insert_batch(ds.c(), C.byref(hc), _ptr(batch), batch.shape[0], efc, float(alpha),
+                                    threads, C.byref(stats) if stats is not None else None)
+    if rc:
+        raise RuntimeError(f"vo_hnsw_insert_batch rc={rc}")
 
 
 def hnsw_search_batch(ds: Dataset, h: Hnsw, queries: np.ndarray, k: int, L: int, eps: float = -1.0,

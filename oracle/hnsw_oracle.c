@@ -36,6 +36,65 @@ void vo_hnsw_free(vo_hnsw* h) {
   free(h);
 }
 
+int vo_hnsw_insert_batch(const vo_data* D, vo_hnsw* h, const uint32_t* batch, uint64_t b,
+                         uint32_t efc, double alpha, int threads, vo_stats* stats) {
+  if (!D || !h || !batch || h->n != D->n) return -1;
+  if (b == 0) return 0;
+  size_t vbytes = (size_t)D->d * elem_bytes(D->dtype);
+  uint32_t* cur = (uint32_t*)malloc(b * sizeof(uint32_t)); /* start vertex of every batch point */
+  uint32_t* sel = (uint32_t*)malloc(b * sizeof(uint32_t)); /* positions in the batch           */
+  uint32_t* ids = (uint32_t*)malloc(b * sizeof(uint32_t));
+  uint32_t* sts = (uint32_t*)malloc(b * sizeof(uint32_t));
+  uint32_t* got = (uint32_t*)malloc(b * sizeof(uint32_t));
+  char* qbuf = (char*)malloc(b * vbytes);
+  int rc = (cur && sel && ids && sts && got && qbuf) ? 0 : -1;
+  if (rc == 0) {
+    for (uint64_t i = 0; i < b; ++i) cur[i] = h->entry;
+    for (uint32_t l = h->top;; --l) {
+      uint32_t deg = layer_degree(h, l);
+      /* points whose level is below l pass through: beam 1 over the layer as it is now, i.e.
+       * as it stood before this batch (the batch's own insertion into it comes next) */
+      uint64_t nd = 0;
+      for (uint64_t i = 0; i < b; ++i)
+        if (h->level[batch[i]] < l) {
+          sel[nd] = (uint32_t)i;
+          sts[nd] = cur[i];
+          memcpy(qbuf + nd * vbytes, (const char*)D->points + (size_t)batch[i] * vbytes, vbytes);
+          ++nd;
+        }
+      if (nd) {
+        rc = vo_search_batch_from(D, h->rows[l], deg, 0, sts, qbuf, nd, 1, 1, -1.0, threads, got,
+                                  NULL, stats);
+        if (rc) break;
+        for (uint64_t j = 0; j < nd; ++j) cur[sel[j]] = got[j];
+      }
+      /* points of this layer: BatchInsert from their own start vertices */
+      uint64_t ni = 0;
+      for (uint64_t i = 0; i < b; ++i)
+        if (h->level[batch[i]] >= l) {
+          sel[ni] = (uint32_t)i;
+          sts[ni] = cur[i];
+          ids[ni] = batch[i];
+          ++ni;
+        }
+      if (ni) {
+        rc = vo_batch_insert_from(D, h->rows[l], deg, 0, sts, ids, ni, efc, alpha, threads, got,
+                                  stats);
+        if (rc) break;
+        for (uint64_t j = 0; j < ni; ++j) cur[sel[j]] = got[j];
+      }
+      if (l == 0) break;
+    }
+  }
+  free(cur);
+  free(sel);
+  free(ids);
+  free(sts);
+  free(got);
+  free(qbuf);
+  return rc;
+}
+
 int vo_hnsw_build(const vo_data* D, uint32_t m, uint32_t efc, double alpha, uint64_t seed,
                   uint64_t theta, const uint32_t* level, const uint32_t* order,
                   uint64_t max_rounds, int threads, vo_hnsw** out, vo_stats* stats) {
@@ -87,67 +146,13 @@ int vo_hnsw_build(const vo_data* D, uint32_t m, uint32_t efc, double alpha, uint
   uint64_t rounds = vo_schedule(cnt, theta, NULL);
   uint64_t* bounds = (uint64_t*)malloc((rounds + 1) * sizeof(uint64_t));
   vo_schedule(cnt, theta, bounds);
-  uint64_t bmax = 1;
-  for (uint64_t r = 0; r < rounds; ++r)
-    if (bounds[r + 1] - bounds[r] > bmax) bmax = bounds[r + 1] - bounds[r];
-
-  size_t vbytes = (size_t)D->d * elem_bytes(D->dtype);
-  uint32_t* cur = (uint32_t*)malloc(bmax * sizeof(uint32_t));  /* start vertex of every batch point */
-  uint32_t* sel = (uint32_t*)malloc(bmax * sizeof(uint32_t));  /* positions in the batch           */
-  uint32_t* ids = (uint32_t*)malloc(bmax * sizeof(uint32_t));
-  uint32_t* sts = (uint32_t*)malloc(bmax * sizeof(uint32_t));
-  uint32_t* got = (uint32_t*)malloc(bmax * sizeof(uint32_t));
-  char* qbuf = (char*)malloc(bmax * vbytes);
-  int rc = (cur && sel && ids && sts && got && qbuf && bounds) ? 0 : -1;
-
+  int rc = bounds ? 0 : -1;
   for (uint64_t r = 0; r < rounds && rc == 0; ++r) {
     if (max_rounds && r >= max_rounds) break;
-    const uint32_t* batch = order + bounds[r];
-    uint64_t b = bounds[r + 1] - bounds[r];
-    for (uint64_t i = 0; i < b; ++i) cur[i] = h->entry;
-    for (uint32_t l = h->top;; --l) {
-      uint32_t deg = layer_degree(h, l);
-      /* points whose level is below l pass through: beam 1 over the layer as it is now, i.e.
-       * as it stood before this batch (the batch's own insertion into it comes next) */
-      uint64_t nd = 0;
-      for (uint64_t i = 0; i < b; ++i)
-        if (h->level[batch[i]] < l) {
-          sel[nd] = (uint32_t)i;
-          sts[nd] = cur[i];
-          memcpy(qbuf + nd * vbytes, (const char*)D->points + (size_t)batch[i] * vbytes, vbytes);
-          ++nd;
-        }
-      if (nd) {
-        rc = vo_search_batch_from(D, h->rows[l], deg, 0, sts, qbuf, nd, 1, 1, -1.0, threads, got,
-                                  NULL, stats);
-        if (rc) break;
-        for (uint64_t j = 0; j < nd; ++j) cur[sel[j]] = got[j];
-      }
-      /* points of this layer: BatchInsert from their own start vertices */
-      uint64_t ni = 0;
-      for (uint64_t i = 0; i < b; ++i)
-        if (h->level[batch[i]] >= l) {
-          sel[ni] = (uint32_t)i;
-          sts[ni] = cur[i];
-          ids[ni] = batch[i];
-          ++ni;
-        }
-      if (ni) {
-        rc = vo_batch_insert_from(D, h->rows[l], deg, 0, sts, ids, ni, efc, alpha, threads, got,
-                                  stats);
-        if (rc) break;
-        for (uint64_t j = 0; j < ni; ++j) cur[sel[j]] = got[j];
-      }
-      if (l == 0) break;
-    }
+    rc = vo_hnsw_insert_batch(D, h, order + bounds[r], bounds[r + 1] - bounds[r], efc, alpha, threads,
+                              stats);
     if (stats) stats->rounds += 1;
   }
-  free(cur);
-  free(sel);
-  free(ids);
-  free(sts);
-  free(got);
-  free(qbuf);
   free(bounds);
   free(own);
   if (rc) {

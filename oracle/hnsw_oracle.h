@@ -68,6 +68,12 @@ int vo_hnsw_build(const vo_data* data, uint32_t m, uint32_t efc, double alpha, u
                   uint64_t theta, const uint32_t* level, const uint32_t* order,
                   uint64_t max_rounds, int threads, vo_hnsw** out, vo_stats* stats);
 
+/* One batch (what vo_hnsw_build does per round): the b points of `batch`,
+ * none of them in the index yet, walk down and are inserted as described
+ * above.  Their levels are read from h->level.                              */
+int vo_hnsw_insert_batch(const vo_data* data, vo_hnsw* h, const uint32_t* batch, uint64_t b,
+                         uint32_t efc, double alpha, int threads, vo_stats* stats);
+
 void vo_hnsw_free(vo_hnsw* h);
 
 /* Queries.  ids_out nq x k, dists_out as vo_search_batch (may be NULL);

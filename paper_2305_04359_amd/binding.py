@@ -53,10 +53,22 @@ class Stats(C.Structure):
         return {k: getattr(self, k) for k, _ in self._fields_}
 
 
+class HnswOpts(C.Structure):
+    _fields_ = [("batch_cap", C.c_uint64), ("order", C.c_void_p), ("level", C.c_void_p),
+                ("max_rounds", C.c_uint64), ("collect_stats", C.c_uint32)]
+
+
+class HnswInfo(C.Structure):
+    _fields_ = [("n", C.c_uint64), ("d", C.c_uint32), ("m", C.c_uint32), ("dtype", C.c_uint32),
+                ("metric", C.c_uint32), ("top", C.c_uint32), ("entry", C.c_uint32), ("rounds", C.c_uint64)]
+
+
 EXPORTS = [
     "ann_build", "ann_insert_batch", "ann_insert_points", "ann_graph_reserve", "ann_search", "ann_search_eps", "ann_start_vertex", "ann_graph_from_host",
     "ann_graph_copy_neighbors", "ann_graph_device_rows", "ann_graph_info", "ann_get_stats",
     "ann_graph_free", "ann_sort_edges", "ann_last_error",
+    "ann_hnsw_build", "ann_hnsw_search", "ann_hnsw_info", "ann_hnsw_copy_levels", "ann_hnsw_layer_size",
+    "ann_hnsw_copy_layer", "ann_hnsw_get_stats", "ann_hnsw_free",
 ]
 
 _lib = None
@@ -105,6 +117,23 @@ def lib():
         L.ann_graph_free.argtypes = [vp]
         L.ann_sort_edges.restype = C.c_int
         L.ann_sort_edges.argtypes = [vp, u64, u32, vp]
+        L.ann_hnsw_build.restype = C.c_int
+        L.ann_hnsw_build.argtypes = [vp, u64, u32, C.c_int, C.c_int, u32, u32, C.c_float, u64,
+                                     C.POINTER(HnswOpts), vp, C.POINTER(vp)]
+        L.ann_hnsw_search.restype = C.c_int
+        L.ann_hnsw_search.argtypes = [vp, vp, vp, u64, u32, u32, C.c_float, vp, vp, vp]
+        L.ann_hnsw_info.restype = C.c_int
+        L.ann_hnsw_info.argtypes = [vp, C.POINTER(HnswInfo)]
+        L.ann_hnsw_copy_levels.restype = C.c_int
+        L.ann_hnsw_copy_levels.argtypes = [vp, vp]
+        L.ann_hnsw_layer_size.restype = C.c_int
+        L.ann_hnsw_layer_size.argtypes = [vp, u32, C.POINTER(u64)]
+        L.ann_hnsw_copy_layer.restype = C.c_int
+        L.ann_hnsw_copy_layer.argtypes = [vp, u32, vp, vp]
+        L.ann_hnsw_get_stats.restype = C.c_int
+        L.ann_hnsw_get_stats.argtypes = [vp, u32, C.POINTER(Stats)]
+        L.ann_hnsw_free.restype = None
+        L.ann_hnsw_free.argtypes = [vp]
         L.ann_last_error.restype = C.c_char_p
         L.ann_last_error.argtypes = []
         _lib = L
@@ -282,3 +311,95 @@ def ann_sort_edges(keys, key_bits: int) -> None:
     if not keys.is_cuda or keys.dim() != 1 or not keys.is_contiguous() or keys.element_size() != 8:
         raise ValueError("keys must be a contiguous 1-D device tensor of 64-bit integers")
     _check(lib().ann_sort_edges(keys.data_ptr(), keys.shape[0], key_bits, _stream_ptr()))
+
+
+class Hnsw:
+    """Owner of an ann_hnsw handle."""
+
+    def __init__(self, handle):
+        self._h = C.c_void_p(handle)
+
+    def close(self):
+        if self._h:
+            lib().ann_hnsw_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def handle(self):
+        return self._h
+
+    def info(self) -> HnswInfo:
+        hi = HnswInfo()
+        _check(lib().ann_hnsw_info(self._h, C.byref(hi)))
+        return hi
+
+    def levels(self) -> np.ndarray:
+        out = np.empty(self.info().n, np.uint32)
+        _check(lib().ann_hnsw_copy_levels(self._h, out.ctypes.data_as(C.c_void_p)))
+        return out
+
+    def layer(self, l):
+        """(ids, rows) of layer l: the layer's point ids ascending and their adjacency rows."""
+        hi = self.info()
+        cnt = C.c_uint64(0)
+        _check(lib().ann_hnsw_layer_size(self._h, l, C.byref(cnt)))
+        ids = np.empty(cnt.value, np.uint32)
+        rows = np.empty((cnt.value, 2 * hi.m if l == 0 else hi.m), np.uint32)
+        _check(lib().ann_hnsw_copy_layer(self._h, l, ids.ctypes.data_as(C.c_void_p),
+                                         rows.ctypes.data_as(C.c_void_p)))
+        return ids, rows
+
+    def stats(self, l=0) -> dict:
+        st = Stats()
+        _check(lib().ann_hnsw_get_stats(self._h, l, C.byref(st)))
+        return st.as_dict()
+
+
+def ann_hnsw_build(points, m, efc, alpha, seed=1, metric=L2SQ, batch_cap=0, order=None, level=None,
+                   max_rounds=0, collect_stats=False) -> Hnsw:
+    """The layered index of Sec. 4.2 over a device tensor of points."""
+    points = _dev2d(points, "points")
+    o = HnswOpts()
+    o.batch_cap = batch_cap
+    o.max_rounds = max_rounds
+    o.collect_stats = 1 if collect_stats else 0
+    keep = []
+    if order is not None:
+        a = np.ascontiguousarray(order, dtype=np.uint32)
+        if a.shape != (points.shape[0] - 1,):
+            raise ValueError("order must hold n-1 ids")
+        keep.append(a)
+        o.order = a.ctypes.data
+    if level is not None:
+        a = np.ascontiguousarray(level, dtype=np.uint32)
+        if a.shape != (points.shape[0],):
+            raise ValueError("level must hold n entries")
+        keep.append(a)
+        o.level = a.ctypes.data
+    h = C.c_void_p()
+    _check(lib().ann_hnsw_build(points.data_ptr(), points.shape[0], points.shape[1], _dtype_code(points),
+                                int(metric), m, efc, float(alpha), seed, C.byref(o), _stream_ptr(), C.byref(h)))
+    return Hnsw(h.value)
+
+
+def ann_hnsw_search(index: Hnsw, points, queries, k, L, eps=-1.0, ids_out=None, dists_out=None):
+    torch = _torch()
+    points = _dev2d(points, "points")
+    queries = _dev2d(queries, "queries")
+    if queries.dtype != points.dtype or queries.shape[1] != points.shape[1]:
+        raise ValueError("queries must match points in dtype and dimension")
+    nq = queries.shape[0]
+    if ids_out is None:
+        ids_out = torch.empty((nq, k), dtype=torch.int32, device=points.device)
+    if dists_out is None:
+        dists_out = torch.empty((nq, k), dtype=torch.float32 if points.dtype == torch.float32 else torch.int32,
+                                device=points.device)
+    _check(lib().ann_hnsw_search(index.handle, points.data_ptr(), queries.data_ptr(), nq, k, L, float(eps),
+                                 ids_out.data_ptr(), dists_out.data_ptr(), _stream_ptr()))
+    return ids_out, dists_out

@@ -40,6 +40,15 @@ struct SearchArgs {
   u32 nq;
   u32 R;
   u32 start;
+  // Layered index (Sec. 4.2): a start vertex of its own for every search.  Search i works on
+  // position p = slot ? slot[i] : i of two arrays: it starts at starts[p] (when `starts` is
+  // given, else at `start`) and leaves the closest vertex it found, passed through `down` when
+  // that is given (the vertex's id one layer below), in next_start[p] (when given).  starts and
+  // next_start may be the same array: a search touches its own position only.
+  const u32* starts;
+  const u32* slot;
+  const u32* down;
+  u32* next_start;
   u32 L;
   u32 k;
   u32* batch_counters;  // build only: the batch's counter words (overflow count [0], arena top [4..5], work
@@ -62,7 +71,7 @@ struct SearchArgs {
   unsigned long long* spill_top;
   u32 spill_chunk;
   u64* vis_where;
-  // query: results (may be null)
+  // query: results (out_ids may be null: then nothing is written; out_dists may be null)
   u32* out_ids;
   void* out_dists;
   DevCounters* counters;  // may be null

@@ -1,26 +1,12 @@
 // Host side of the library: the C ABI of include/ann.h, the prefix-doubling schedule of Alg. 3
 // (batchBuild) and the per-batch launch sequence of BatchInsert.
-#include <hip/hip_runtime.h>
-
-#include <cmath>
-#include <cstdarg>
-#include <cstdio>
-#include <cstdlib>
-#include <cstring>
-#include <ctime>
-#include <new>
-#include <string>
-#include <thread>
-#include <vector>
-
-#include "../../include/ann.h"
-#include "ann_internal.hpp"
+#include "driver_internal.hpp"
 
 using namespace annmi;
 
-namespace {
+namespace annmi {
 
-thread_local std::string g_err;
+static thread_local std::string g_err;
 
 int fail(int code, const char* fmt, ...) {
   char buf[512];
@@ -32,31 +18,7 @@ int fail(int code, const char* fmt, ...) {
   return code;
 }
 
-#define HIP_TRY(expr)                                                                          \
-  do {                                                                                         \
-    hipError_t e_ = (expr);                                                                    \
-    if (e_ != hipSuccess)                                                                      \
-      return fail(e_ == hipErrorOutOfMemory ? ANN_ENOMEM : ANN_EHIP, "%s: %s", #expr,          \
-                  hipGetErrorString(e_));                                                      \
-  } while (0)
-
-// device buffer freed on scope exit
-struct DevBuf {
-  void* p = nullptr;
-  ~DevBuf() { release(); }
-  void release() {
-    if (p) (void)hipFree(p);
-    p = nullptr;
-  }
-  hipError_t alloc(size_t bytes) {
-    release();
-    return hipMalloc(&p, bytes ? bytes : 16);
-  }
-  template <typename T>
-  T* as() const {
-    return static_cast<T*>(p);
-  }
-};
+const char* last_error_text() { return g_err.c_str(); }
 
 bool make_cfg(uint32_t d, int dtype, int metric, DistCfg* cfg, std::string* why) {
   const u64 esz = dtype == ANN_F32 ? 4 : 1;
@@ -121,45 +83,10 @@ u64 splitmix64(u64& state) {
   return z ^ (z >> 31);
 }
 
-}  // namespace
+}  // namespace annmi
 
-namespace {
-struct BatchScratch;
-}
 
-struct ann_graph {
-  u64 n = 0;
-  u64 cap = 0;  // rows and meta are allocated for this many points (>= n)
-  u32 d = 0, R = 0;
-  int dtype = 0, metric = 0;
-  u32 start = 0;
-  u64 rounds = 0;
-  DistCfg cfg{};
-  u32* rows = nullptr;            // device, n x R
-  u32* meta = nullptr;            // device, n: degree | clean prefix length << 16
-  float clean_alpha = 0.0f;       // the alpha the clean prefixes were pruned with
-  DevCounters* counters = nullptr;  // device
-  ann_stats stats{};
-  u32 hash_bits = 0;
-  u32 visited_cap = 0;
-  u64 spill_keys = 0;  // 0 = default
-  bool collect = false;
-  // u8/i8 rows whose size is not a multiple of 16 bytes: the kernels work on a copy with rows of
-  // pad_stride bytes (zero tail, which changes no distance), made once per points array; queries
-  // are copied the same way on every call.  cfg describes the padded rows.
-  u64 pad_stride = 0;
-  mutable void* pad_buf = nullptr;
-  mutable const void* pad_src = nullptr;
-  mutable u64 pad_cap = 0;   // rows pad_buf has room for
-  mutable u64 pad_done = 0;  // leading rows of pad_src that pad_buf holds
-  mutable void* qpad_buf = nullptr;
-  mutable u64 qpad_rows = 0;
-  // scratch of the insertions that follow the build (ann_insert_batch, ann_insert_points), kept
-  // between calls: allocating and freeing it costs more than a batch of ten thousand points
-  BatchScratch* scratch = nullptr;
-};
-
-namespace {
+namespace annmi {
 
 // dst row r = src row r followed by zeros; one thread per 4-byte word of dst (rows of any byte
 // length, so the source is read byte by byte at the ragged end)
@@ -239,87 +166,6 @@ int resolve_queries(const ann_graph* g, const void* queries_dev, u64 nq, hipStre
   return ANN_OK;
 }
 
-// Scratch of one BatchInsert call, sized for `bmax` points.
-struct BatchScratch {
-  u64 bmax = 0;
-  u32 vis_cap = 0;
-  DevBuf qidx, vis, nvis, edges, edges_tmp, hist, lists, small, ovf_list, arena, spill, vis_where;
-  u64 spill_cap = 0;    // keys
-  u32 spill_chunk = 0;  // extra keys a spilled list gets on top of vis_cap
-  u64 arena_cap = 0;
-  // side streams (default priority) on which two of the three re-prune kernels run, and the
-  // events that order them against the caller's stream
-  hipStream_t side[2] = {nullptr, nullptr};
-  hipEvent_t ev_plan = nullptr, ev_side[2] = {nullptr, nullptr};
-  u32* host_flag = nullptr;  // pinned: where the host reads the overflow count of a batch
-  ~BatchScratch() {
-    if (host_flag) (void)hipHostFree(host_flag);
-    for (auto& s : side)
-      if (s) (void)hipStreamDestroy(s);
-    if (ev_plan) (void)hipEventDestroy(ev_plan);
-    for (auto& e : ev_side)
-      if (e) (void)hipEventDestroy(e);
-  }
-  // small: [0] overflow_count u32, [2] arena error flag, [3] "a visited list was lost" flag,
-  // [4..5] arena_top u64, [6..7] spill_top u64, [8..10] work list counts
-  int alloc(u64 b, u32 R, u32 cap, u64 spill_keys) {
-    bmax = b;
-    vis_cap = cap;
-    spill_chunk = 8192;
-    spill_cap = spill_keys;
-    const u64 E = b * R;
-    // a spilled candidate list is longer than MERGE_SPILL_MIN and has at most R old entries
-    arena_cap = E + (u64)R * (E / (MERGE_SPILL_MIN - R) + 1);
-    HIP_TRY(qidx.alloc(b * 4));
-    HIP_TRY(vis.alloc(b * cap * 8));
-    HIP_TRY(nvis.alloc(b * 4));
-    HIP_TRY(edges.alloc(E * 8));
-    HIP_TRY(edges_tmp.alloc(E * 8));
-    HIP_TRY(hist.alloc(radix_hist_entries(E) * 4));
-    HIP_TRY(lists.alloc(3 * E * sizeof(MergeItem)));
-    HIP_TRY(small.alloc(64));
-    HIP_TRY(hipMemset(small.p, 0, 64));
-    HIP_TRY(ovf_list.alloc(b * 4));
-    HIP_TRY(arena.alloc(arena_cap * 8));
-    HIP_TRY(spill.alloc(spill_cap * 8));
-    HIP_TRY(vis_where.alloc(b * 8));
-    HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&host_flag), 64, hipHostMallocDefault));
-    for (auto& s : side) HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
-    HIP_TRY(hipEventCreateWithFlags(&ev_plan, hipEventDisableTiming));
-    for (auto& e : ev_side) HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
-    return ANN_OK;
-  }
-};
-
-// HIP events around the phases of every batch, read when the batches have finished.
-struct PhaseTimer {
-  std::vector<hipEvent_t> ev;  // 5 per batch
-  bool on = false;
-  size_t cur = 0;  // batch being recorded
-  int init(bool enable) {
-    on = enable;
-    return ANN_OK;
-  }
-  int begin_batch() {
-    if (!on) return ANN_OK;
-    cur = ev.size() / 5;
-    for (int i = 0; i < 5; ++i) {
-      hipEvent_t e;
-      HIP_TRY(hipEventCreate(&e));
-      ev.push_back(e);
-    }
-    return ANN_OK;
-  }
-  void mark(int i, hipStream_t s) {
-    if (on) (void)hipEventRecord(ev[cur * 5 + i], s);
-  }
-  void clear() {
-    for (auto& e : ev) (void)hipEventDestroy(e);
-    ev.clear();
-  }
-  ~PhaseTimer() { clear(); }
-};
-
 // Adds up the phase times of all recorded batches (the caller has synchronised the stream).
 void collect_phase_times(ann_graph* g, PhaseTimer& tm) {
   if (!tm.on) return;
@@ -344,7 +190,7 @@ void collect_phase_times(ann_graph* g, PhaseTimer& tm) {
 // whose visited list fit neither its slot nor a spill chunk; without it nothing waits, such a
 // search leaves its point unconnected and raises a flag that finish_batches reports.
 int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u32* ids_dev, u64 b, u32 L,
-                 float alpha, BatchScratch& S, PhaseTimer& tm, hipStream_t st, bool sync) {
+                 float alpha, BatchScratch& S, PhaseTimer& tm, hipStream_t st, bool sync, const StartsArgs* starts) {
   if (b == 0) return ANN_OK;
   {
     int rc0 = tm.begin_batch();
@@ -376,6 +222,12 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   sa.nq = (u32)b;
   sa.R = R;
   sa.start = g->start;
+  if (starts) {
+    sa.starts = starts->cur;
+    sa.slot = starts->slot;
+    sa.down = starts->down;
+    sa.next_start = starts->next;
+  }
   sa.L = L;
   sa.k = 1;
   sa.hash_buckets = search_hash_buckets(L, g->hash_bits);
@@ -458,6 +310,15 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
     sb.batch_counters = nullptr;
     sb.vis_where = nullptr;
     sb.counters = nullptr;
+    DevBuf pos2;
+    if (starts) {
+      // redone search i stands at the position of batch slot slots[i]
+      std::vector<u32> p2(novf);
+      for (u32 i = 0; i < novf; ++i) p2[i] = starts->slot_host ? starts->slot_host[slots[i]] : slots[i];
+      HIP_TRY(pos2.alloc((size_t)novf * 4));
+      HIP_TRY(hipMemcpy(pos2.p, p2.data(), (size_t)novf * 4, hipMemcpyHostToDevice));
+      sb.slot = pos2.as<u32>();
+    }
     HIP_TRY(launch_search(g->cfg, sb, st));
     PruneArgs pb = pa;
     pb.qidx = ids2_d.as<u32>();
@@ -524,8 +385,6 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   return ANN_OK;
 }
 
-constexpr int ANN_LOST_LIST = 1;  // internal: a visited list fit nowhere in a batch issued without sync
-
 // Waits for the batches issued so far; reports a spill-arena failure (cannot happen with the
 // arena sized as it is) or a lost visited list, and reads the phase times.
 int finish_batches(ann_graph* g, BatchScratch& S, PhaseTimer& tm, hipStream_t st) {
@@ -558,6 +417,43 @@ int graph_scratch(ann_graph* g, u64 b, u32 L, hipStream_t st, BatchScratch** out
     HIP_TRY(hipMemsetAsync(g->scratch->small.p, 0, 64, st));  // flags of an earlier call that failed
   }
   *out = g->scratch;
+  return ANN_OK;
+}
+
+int query_launch(const ann_graph* g, const void* pts, const void* queries, const u32* qidx, u64 nq, u32 k, u32 L,
+                 float eps, const StartsArgs* starts, u32* out_ids, void* out_dists, hipStream_t st) {
+  SearchArgs sa{};
+  sa.points = static_cast<const char*>(pts);
+  sa.graph = g->rows;
+  sa.queries = static_cast<const char*>(queries);
+  sa.qidx = qidx;
+  sa.qrow_bytes = g->cfg.row_bytes;
+  sa.nq = (u32)nq;
+  sa.R = g->R;
+  sa.start = g->start;
+  if (starts) {
+    sa.starts = starts->cur;
+    sa.slot = starts->slot;
+    sa.down = starts->down;
+    sa.next_start = starts->next;
+  }
+  sa.L = L;
+  sa.k = k;
+  sa.hash_buckets = search_hash_buckets(L, g->hash_bits);
+  search_filter_mode(g->n, sa.hash_buckets, &sa.id_bits, &sa.tag_width);
+  sa.eps16 = eps >= 0.0f ? llround((double)eps * 65536.0) : -1;
+  sa.epsf = eps >= 0.0f ? eps : 0.0f;
+  sa.out_ids = out_ids;
+  sa.out_dists = out_dists;
+  sa.counters = g->collect ? g->counters : nullptr;
+  HIP_TRY(launch_search(g->cfg, sa, st));
+  return ANN_OK;
+}
+
+int check_insert_params(const ann_graph* g, uint32_t L, float alpha) {
+  if (L < 1 || L > 512) return fail(ANN_EINVAL, "L must be in [1, 512]");
+  if (!(alpha > 0.0f) || !std::isfinite(alpha) || alpha > 30000.0f) return fail(ANN_EINVAL, "alpha must be in (0, 30000]");
+  if (g->metric == ANN_MIPS && alpha > 1.0f) return fail(ANN_EINVAL, "alpha must be <= 1 for ANN_MIPS");
   return ANN_OK;
 }
 
@@ -642,11 +538,11 @@ int grow_graph(ann_graph* g, u64 n_total, hipStream_t st) {
   return ANN_OK;
 }
 
-}  // namespace
+}  // namespace annmi
 
 extern "C" {
 
-const char* ann_last_error(void) { return g_err.c_str(); }
+const char* ann_last_error(void) { return last_error_text(); }
 
 void ann_graph_free(ann_graph* g) {
   if (!g) return;
@@ -758,12 +654,6 @@ int ann_sort_edges(uint64_t* keys_dev, uint64_t count, uint32_t key_bits, void* 
   return ANN_OK;
 }
 
-static int check_insert_params(const ann_graph* g, uint32_t L, float alpha) {
-  if (L < 1 || L > 512) return fail(ANN_EINVAL, "L must be in [1, 512]");
-  if (!(alpha > 0.0f) || !std::isfinite(alpha) || alpha > 30000.0f) return fail(ANN_EINVAL, "alpha must be in (0, 30000]");
-  if (g->metric == ANN_MIPS && alpha > 1.0f) return fail(ANN_EINVAL, "alpha must be <= 1 for ANN_MIPS");
-  return ANN_OK;
-}
 
 int ann_insert_batch(ann_graph* g, const void* points_dev, const uint32_t* ids_host, uint64_t b, uint32_t L,
                      float alpha, void* stream) {
@@ -1050,7 +940,6 @@ int ann_search_eps(const ann_graph* g, const void* points_dev, const void* queri
   if (k < 1 || k > L) return fail(ANN_EINVAL, "need 1 <= k <= L");
   if (L > 512) return fail(ANN_EINVAL, "L must be at most 512");
   if (nq >= (1ull << 31)) return fail(ANN_EINVAL, "too many queries");
-  SearchArgs sa{};
   hipStream_t st_ = static_cast<hipStream_t>(stream);
   const void* pts = nullptr;
   const void* qsp = nullptr;
@@ -1058,24 +947,8 @@ int ann_search_eps(const ann_graph* g, const void* points_dev, const void* queri
   if (rc_) return rc_;
   rc_ = resolve_queries(g, queries_dev, nq, st_, &qsp);
   if (rc_) return rc_;
-  sa.points = static_cast<const char*>(pts);
-  sa.graph = g->rows;
-  sa.queries = static_cast<const char*>(qsp);
-  sa.qidx = nullptr;
-  sa.qrow_bytes = g->cfg.row_bytes;
-  sa.nq = (u32)nq;
-  sa.R = g->R;
-  sa.start = g->start;
-  sa.L = L;
-  sa.k = k;
-  sa.hash_buckets = search_hash_buckets(L, g->hash_bits);
-  search_filter_mode(g->n, sa.hash_buckets, &sa.id_bits, &sa.tag_width);
-  sa.eps16 = eps >= 0.0f ? llround((double)eps * 65536.0) : -1;
-  sa.epsf = eps >= 0.0f ? eps : 0.0f;
-  sa.out_ids = ids_dev;
-  sa.out_dists = dists_dev;
-  sa.counters = g->collect ? g->counters : nullptr;
-  HIP_TRY(launch_search(g->cfg, sa, static_cast<hipStream_t>(stream)));
+  rc_ = query_launch(g, pts, qsp, nullptr, nq, k, L, eps, nullptr, ids_dev, dists_dev, st_);
+  if (rc_) return rc_;
   return ANN_OK;
 }
 

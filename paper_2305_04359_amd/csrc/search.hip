@@ -1,6 +1,7 @@
 // Host side of the beam search: sizes of the per-wave LDS, the filter layout, and the launch of
 // the kernel variants without the (1 + eps) rule (the graph build and plain queries).  The
-// variants with the rule are compiled in a translation unit of their own, in parallel.
+// variants with the rule, and those of the layered index, are compiled in translation units of
+// their own, in parallel.
 #include "ann_dispatch.hpp"
 #include "search_kernel.hpp"
 
@@ -54,7 +55,7 @@ void search_filter_mode(u64 n, u32 hash_buckets, u32* id_bits, u32* tag_width) {
 
 template <int KIND, int VEC, int NCH>
 static hipError_t launch_plain(const SearchArgs& a, const VecTable& T, hipStream_t s) {
-  return launch_search_variant<KIND, VEC, NCH, false>(a, T, s);
+  return launch_search_variant<KIND, VEC, NCH, false, false>(a, T, s);
 }
 
 static hipError_t launch_search_plain(const DistCfg& cfg, const SearchArgs& a, const VecTable& T, hipStream_t s) {
@@ -64,6 +65,8 @@ static hipError_t launch_search_plain(const DistCfg& cfg, const SearchArgs& a, c
 hipError_t launch_search(const DistCfg& cfg, const SearchArgs& a, hipStream_t s) {
   if (a.nq == 0) return hipSuccess;
   VecTable T{a.points, (u32)cfg.row_bytes, cfg.npieces};
+  const bool own = a.starts != nullptr || a.next_start != nullptr;
+  if (own) return a.eps16 >= 0 ? launch_search_own_eps(cfg, a, T, s) : launch_search_own(cfg, a, T, s);
   return a.eps16 >= 0 ? launch_search_eps(cfg, a, T, s) : launch_search_plain(cfg, a, T, s);
 }
 

@@ -7,7 +7,7 @@ namespace annmi {
 
 template <int KIND, int VEC, int NCH>
 static hipError_t launch_eps(const SearchArgs& a, const VecTable& T, hipStream_t s) {
-  return launch_search_variant<KIND, VEC, NCH, true>(a, T, s);
+  return launch_search_variant<KIND, VEC, NCH, true, false>(a, T, s);
 }
 
 hipError_t launch_search_eps(const DistCfg& cfg, const SearchArgs& a, const VecTable& T, hipStream_t s) {

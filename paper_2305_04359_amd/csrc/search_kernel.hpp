@@ -42,7 +42,9 @@ __device__ __forceinline__ u32 pk_min_u16(u32 a, u32 b) {
 // EPS: the (1 + eps) rule is compiled in.  TAG16: the filter holds 16-bit tags (graphs of up to
 // a few million points); the other two layouts share the second variant, so that their code does
 // not weigh on the registers of the first.
-template <int KIND, int VEC, int NCH, int NSLOT, bool EPS, bool TAG16>
+// OWN: every search has a start vertex of its own and reports the closest vertex it found (the
+// layered index); compiled apart so that the flat graph's searches do not carry its arguments.
+template <int KIND, int VEC, int NCH, int NSLOT, bool EPS, bool TAG16, bool OWN>
 __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
   extern __shared__ __align__(16) unsigned char smem[];
   u64* beam = reinterpret_cast<u64*>(smem);
@@ -88,8 +90,11 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
   for (int s = 0; s < NSLOT; ++s) A[s] = KEY_INF;
 
   // beam <- {s}
+  u32 st = a.start;
+  if constexpr (OWN) {
+    if (a.starts != nullptr) st = a.starts[a.slot != nullptr ? a.slot[qi] : qi];
+  }
   {
-    const u32 st = a.start;
     u32 dk = eval_up_to_64<KIND, VEC, NCH>(T, Q, [st](u32) { return st; }, 1u, lane);
     dk = readlane_u32(dk, 0);
     if (lane == 0) {
@@ -100,13 +105,13 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
   __syncthreads();
   if (lane == 0) {
     if (compact) {
-      const u32 y = mix_id(a.start, idmask, a.id_bits);
+      const u32 y = mix_id(st, idmask, a.id_bits);
       hash[4u * bucket_of_y(y)] = 0xFFFF0000u | (y & tagmask);
     } else if (tags21) {
-      const u32 y = mix_id(a.start, idmask, a.id_bits);
+      const u32 y = mix_id(st, idmask, a.id_bits);
       hash[4u * bucket_of_y(y)] = 0xFFE00000u | (y & tagmask);
     } else {
-      hash[4u * bucket_of_id(a.start)] = a.start;
+      hash[4u * bucket_of_id(st)] = st;
     }
   }
 
@@ -349,6 +354,13 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
   }
 
   if (a.nvis != nullptr && lane == 0) a.nvis[qi] = nv;
+  if constexpr (OWN) {
+    if (a.next_start != nullptr && lane == 0) {
+      // the beam's first entry is the closest vertex the search visited (it always holds one)
+      const u32 best = key_id(A[0]);
+      a.next_start[a.slot != nullptr ? a.slot[qi] : qi] = a.down != nullptr ? a.down[best] : best;
+    }
+  }
   if (a.out_ids != nullptr) {
 #pragma unroll
     for (int s = 0; s < NSLOT; ++s) {
@@ -357,10 +369,12 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
         const bool ok = A[s] != KEY_INF;
         const u64 o = (u64)qi * a.k + idx;
         a.out_ids[o] = ok ? key_id(A[s]) : NONE_ID;
-        if constexpr (KindTraits<KIND>::is_int)
-          reinterpret_cast<i32*>(a.out_dists)[o] = ok ? int_from_dkey(key_dkey(A[s])) : 0x7FFFFFFF;
-        else
-          reinterpret_cast<float*>(a.out_dists)[o] = ok ? float_from_dkey(key_dkey(A[s])) : __builtin_inff();
+        if (a.out_dists != nullptr) {
+          if constexpr (KindTraits<KIND>::is_int)
+            reinterpret_cast<i32*>(a.out_dists)[o] = ok ? int_from_dkey(key_dkey(A[s])) : 0x7FFFFFFF;
+          else
+            reinterpret_cast<float*>(a.out_dists)[o] = ok ? float_from_dkey(key_dkey(A[s])) : __builtin_inff();
+        }
       }
     }
   }
@@ -375,22 +389,25 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
 }
 
 
-// launches the variants with the (1 + eps) rule (search_eps.hip)
+// launches of the variants that other translation units compile: with the (1 + eps) rule
+// (search_eps.hip), with start vertices of their own (search_own.hip), with both (search_own_eps.hip)
 hipError_t launch_search_eps(const DistCfg& cfg, const SearchArgs& a, const VecTable& T, hipStream_t s);
+hipError_t launch_search_own(const DistCfg& cfg, const SearchArgs& a, const VecTable& T, hipStream_t s);
+hipError_t launch_search_own_eps(const DistCfg& cfg, const SearchArgs& a, const VecTable& T, hipStream_t s);
 
 inline u32 search_nslot_for(u32 L) { return L <= 64 ? 1 : (L <= 128 ? 2 : (L <= 256 ? 4 : 8)); }
 
-// One launch for a fixed choice of EPS; the beam slots and the filter layout are picked here.
-template <int KIND, int VEC, int NCH, bool EPS>
+// One launch for a fixed choice of EPS and OWN; the beam slots and the filter layout are picked here.
+template <int KIND, int VEC, int NCH, bool EPS, bool OWN>
 inline hipError_t launch_search_variant(const SearchArgs& a, const VecTable& T, hipStream_t s) {
   const u32 lds = search_lds_bytes(a.L, a.hash_buckets);
   const dim3 grid(a.nq), block(64);
   const bool t16 = a.tag_width == 16u;
 #define ANN_LAUNCH_SEARCH(NS)                                                                            \
   if (t16)                                                                                               \
-    hipLaunchKernelGGL((search_kernel<KIND, VEC, NCH, NS, EPS, true>), grid, block, lds, s, a, T);       \
+    hipLaunchKernelGGL((search_kernel<KIND, VEC, NCH, NS, EPS, true, OWN>), grid, block, lds, s, a, T);  \
   else                                                                                                   \
-    hipLaunchKernelGGL((search_kernel<KIND, VEC, NCH, NS, EPS, false>), grid, block, lds, s, a, T)
+    hipLaunchKernelGGL((search_kernel<KIND, VEC, NCH, NS, EPS, false, OWN>), grid, block, lds, s, a, T)
   switch (search_nslot_for(a.L)) {
     case 1: ANN_LAUNCH_SEARCH(1); break;
     case 2: ANN_LAUNCH_SEARCH(2); break;

@@ -722,3 +722,160 @@ def test_insert_points_c2_full_size(env):
     ids, dists = A.ann_search(g, pts, dev(torch, w.queries[:300]), 10, 40)
     oi, od = O.search_batch(ds, og, s, w.queries[:300], 10, 40, threads=0)
     assert (ids.cpu().numpy().view(np.uint32) == oi).all() and (dists.cpu().numpy() == od).all()
+
+
+# ------------------------------------------------------------------------------------------
+# layered index (Sec. 4.2, ParlayHNSW)
+# ------------------------------------------------------------------------------------------
+def _hnsw_layers_global(h, n):
+    """The library's layers as n x degree arrays of point ids, the oracle's format."""
+    hi = h.info()
+    out = []
+    for l in range(hi.top + 1):
+        ids, rows = h.layer(l)
+        full = np.full((n, rows.shape[1]), NONE, np.uint32)
+        full[ids] = rows
+        out.append((ids, full))
+    return out
+
+
+def _check_hnsw_against(h, oh, n):
+    hi = h.info()
+    assert hi.top == oh.top and hi.entry == oh.entry
+    assert (h.levels() == oh.level).all()
+    for l, (ids, full) in enumerate(_hnsw_layers_global(h, n)):
+        assert (ids == np.flatnonzero(oh.level >= l)).all()
+        bad = np.nonzero((full != oh.layers[l]).any(1))[0]
+        assert len(bad) == 0, f"layer {l}: rows differ: {bad[:10]}"
+
+
+@pytest.mark.parametrize("m,efc,alpha", [(16, 64, 1.0), (4, 20, 1.2), (32, 128, 0.82)])
+def test_hnsw_c1_bit_exact(env, c1, m, efc, alpha):
+    torch, A, O = env
+    ds = O.Dataset(c1.points, 0)
+    say(f"layered index m={m} efc={efc} alpha={alpha}: oracle build")
+    oh = O.hnsw_build(ds, m, efc, alpha, seed=5, threads=0)
+    pts, qs = dev(torch, c1.points), dev(torch, c1.queries)
+    h = A.ann_hnsw_build(pts, m, efc, alpha, seed=5)
+    assert oh.top >= 2
+    _check_hnsw_against(h, oh, c1.n)
+    for L, k, eps in ((10, 10, -1.0), (40, 10, -1.0), (1, 1, -1.0), (130, 20, -1.0), (40, 10, 0.1), (40, 10, 0.0)):
+        ids, dists = A.ann_hnsw_search(h, pts, qs, k, L, eps=eps)
+        oi, od, _ = O.hnsw_search_batch(ds, oh, c1.queries, k, L, eps=eps, threads=0)
+        assert (ids.cpu().numpy().view(np.uint32) == oi).all() and (dists.cpu().numpy() == od).all()
+    # deterministic
+    h2 = A.ann_hnsw_build(pts, m, efc, alpha, seed=5)
+    for (_, a), (_, b) in zip(_hnsw_layers_global(h, c1.n), _hnsw_layers_global(h2, c1.n)):
+        assert (a == b).all()
+
+
+def test_hnsw_one_layer_is_the_flat_graph(env, c1):
+    torch, A, O = env
+    n, m = 4000, 12
+    pts = dev(torch, c1.points[:n])
+    h = A.ann_hnsw_build(pts, m, 48, 1.2, seed=3, level=np.zeros(n, np.uint32))
+    g = A.ann_build(pts, 2 * m, 48, 1.2, seed=3, start=0)
+    assert h.info().top == 0 and h.info().entry == 0
+    assert (h.layer(0)[1] == g.neighbors()).all()
+    qs = dev(torch, c1.queries)
+    a, b = A.ann_hnsw_search(h, pts, qs, 10, 30), A.ann_search(g, pts, qs, 10, 30)
+    assert (a[0] == b[0]).all() and (a[1] == b[1]).all()
+
+
+def test_hnsw_given_levels_order_and_partial_builds(env, c1):
+    """Levels and order given by the caller (a tall, thin hierarchy), stopped after a few batches:
+    identical to the oracle's at every stop."""
+    torch, A, O = env
+    n, m = 3000, 6
+    rng = np.random.default_rng(1)
+    level = rng.geometric(0.5, n).astype(np.uint32) - 1
+    level[level > 9] = 9
+    entry = int(np.flatnonzero(level == level.max())[0])
+    order = rng.permutation(np.delete(np.arange(n, dtype=np.uint32), entry))
+    ds = O.Dataset(c1.points[:n], 0)
+    pts = dev(torch, c1.points[:n])
+    for rounds in (1, 4, 12, 0):
+        oh = O.hnsw_build(ds, m, 30, 1.1, theta=100, level=level, order=order, max_rounds=rounds, threads=0)
+        h = A.ann_hnsw_build(pts, m, 30, 1.1, batch_cap=100, level=level, order=order, max_rounds=rounds)
+        _check_hnsw_against(h, oh, n)
+
+
+def test_hnsw_padded_int8_and_f32(env):
+    torch, A, O = env
+    w = W.c3(n=6000, nq=300)
+    ds = O.Dataset(w.points, 0)
+    oh = O.hnsw_build(ds, 12, 48, 1.0, seed=2, threads=0)
+    pts, qs = dev(torch, w.points), dev(torch, w.queries)
+    h = A.ann_hnsw_build(pts, 12, 48, 1.0, seed=2)
+    _check_hnsw_against(h, oh, w.n)
+    ids, dists = A.ann_hnsw_search(h, pts, qs, 10, 50)
+    oi, od, _ = O.hnsw_search_batch(ds, oh, w.queries, 10, 50, threads=0)
+    assert (ids.cpu().numpy().view(np.uint32) == oi).all() and (dists.cpu().numpy() == od).all()
+
+    w = W.c4(n=8000, nq=400)
+    ds = O.Dataset(w.points, 1)
+    oh = O.hnsw_build(ds, 16, 64, 1.0, seed=1, threads=0)
+    pts, qs = dev(torch, w.points), dev(torch, w.queries)
+    h = A.ann_hnsw_build(pts, 16, 64, 1.0, seed=1, metric=A.MIPS)
+    assert h.info().top == oh.top and h.info().entry == oh.entry
+    same = [(full == oh.layers[l]).all(1).mean() for l, (_, full) in enumerate(_hnsw_layers_global(h, w.n))]
+    say(f"  f32 layers: share of identical rows {same}")
+    assert min(same) > 0.9  # near-ties in fp32 may flip a few rows
+    gt, _ = O.brute_force(ds, w.queries, 10)
+    gi, _ = A.ann_hnsw_search(h, pts, qs, 10, 64)
+    oi, _, _ = O.hnsw_search_batch(ds, oh, w.queries, 10, 64, threads=0)
+    r_g, r_o = recall_at_k(gi.cpu().numpy().view(np.uint32), gt), recall_at_k(oi, gt)
+    say(f"  recall gpu={r_g:.4f} oracle={r_o:.4f}")
+    assert abs(r_g - r_o) <= 0.002
+
+
+def test_hnsw_bad_arguments(env, c1):
+    torch, A, O = env
+    pts = dev(torch, c1.points[:500])
+    for kw in (dict(m=1, efc=8, alpha=1.0), dict(m=300, efc=8, alpha=1.0), dict(m=8, efc=0, alpha=1.0),
+               dict(m=8, efc=8, alpha=0.0)):
+        with pytest.raises(A.AnnError):
+            A.ann_hnsw_build(pts, **kw)
+    with pytest.raises(A.AnnError):
+        A.ann_hnsw_build(pts, 8, 16, 1.0, level=np.full(500, 64, np.uint32))
+    with pytest.raises(A.AnnError):
+        A.ann_hnsw_build(pts, 8, 16, 1.0, order=np.zeros(499, np.uint32))
+    h = A.ann_hnsw_build(pts, 8, 16, 1.0)
+    qs = dev(torch, c1.queries[:10])
+    with pytest.raises(A.AnnError):
+        A.ann_hnsw_search(h, pts, qs, 10, 5)
+    with pytest.raises(A.AnnError):
+        h.layer(h.info().top + 1)
+    # a single point, and two
+    for n in (1, 2):
+        h = A.ann_hnsw_build(pts[:n], 4, 8, 1.0)
+        ids, _ = A.ann_hnsw_search(h, pts[:n], qs, 1, 4)
+        assert (ids.cpu().numpy() < n).all()
+
+
+def test_hnsw_c2_full_size_last_batch_against_oracle(env):
+    """The benchmark's size and launch configuration (m = 32, efc = 128, alpha = 0.82, the
+    appendix's setting for the 128-d uint8 set): the index before the last batch comes from a GPU
+    build stopped one batch early; the oracle inserts that batch into a copy of it, the GPU
+    finishes its own build; every layer identical, and so are query answers."""
+    torch, A, O = env
+    w = W.c2()
+    pts, qs = dev(torch, w.points), dev(torch, w.queries[:300])
+    m, efc, alpha = 32, 128, 0.82
+    full = A.ann_hnsw_build(pts, m, efc, alpha, seed=w.seed)
+    rounds = int(full.info().rounds)
+    part = A.ann_hnsw_build(pts, m, efc, alpha, seed=w.seed, max_rounds=rounds - 1)
+    hi = part.info()
+    level = part.levels()
+    oh = O.Hnsw(m, level, [f for _, f in _hnsw_layers_global(part, w.n)], hi.entry)
+    order = O.insertion_order(w.n, hi.entry, w.seed)
+    bounds = O.schedule(w.n - 1, w.theta).astype(np.int64)
+    assert len(bounds) - 1 == rounds
+    batch = order[bounds[rounds - 1]:]
+    ds = O.Dataset(w.points, 0)
+    say(f"oracle inserts the last batch ({len(batch)} points) into the {hi.top + 1}-layer index")
+    O.hnsw_insert_batch(ds, oh, batch, efc, alpha, threads=0)
+    _check_hnsw_against(full, oh, w.n)
+    ids, dists = A.ann_hnsw_search(full, pts, qs, 10, 40)
+    oi, od, _ = O.hnsw_search_batch(ds, oh, w.queries[:300], 10, 40, threads=0)
+    assert (ids.cpu().numpy().view(np.uint32) == oi).all() and (dists.cpu().numpy() == od).all()
