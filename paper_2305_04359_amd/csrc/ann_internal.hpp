@@ -77,6 +77,25 @@ struct SearchArgs {
   DevCounters* counters;  // may be null
 };
 
+// The walk of a query through the upper layers of the layered index (Sec. 4.2): a search with
+// beam 1 per layer, from the top down.
+struct DescendLayer {
+  const char* points;  // the layer's vectors
+  const u32* graph;    // its adjacency rows, R ids each
+  const u32* down;     // id of each of its vertices one layer below
+  u32 R;
+  u32 pad_;
+};
+struct DescendArgs {
+  const char* queries;
+  u64 qrow_bytes;
+  u32 nq;
+  u32 nlayers;                 // layers walked, listed from the top
+  u32 entry;                   // the entry point's id on the first of them
+  const DescendLayer* layers;  // device
+  u32* out;                    // nq ids on the layer below the last one walked
+};
+
 struct PruneArgs {
   const char* points;
   u32* graph;  // rows of the batch points are written
@@ -142,6 +161,7 @@ constexpr u32 STAGE_BUDGET = 10240;    // LDS bytes the prune kernels may spend 
 
 // launchers (each returns the hipGetLastError() of its launches)
 hipError_t launch_search(const DistCfg& cfg, const SearchArgs& a, hipStream_t s);
+hipError_t launch_descend(const DistCfg& cfg, const DescendArgs& a, hipStream_t s);
 hipError_t launch_prune(const DistCfg& cfg, const PruneArgs& a, hipStream_t s);
 hipError_t launch_plan(const MergeArgs& a, hipStream_t s);
 hipError_t launch_merge(const DistCfg& cfg, const MergeArgs& a, u32 grid, hipStream_t s, hipStream_t s_gram,

@@ -372,12 +372,16 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   // grid-stride kernels over work lists whose lengths stay on the device: enough waves to fill
   // the chip, no more (idle workgroups are not free)
   const u64 want = E < 8192 ? E : 8192;
-  HIP_TRY(hipEventRecord(S.ev_plan, st));
-  for (int i = 0; i < 2; ++i) HIP_TRY(hipStreamWaitEvent(S.side[i], S.ev_plan, 0));
-  HIP_TRY(launch_merge(g->cfg, ma, (u32)(want ? want : 1), st, S.side[0], S.side[1]));
-  for (int i = 0; i < 2; ++i) {
-    HIP_TRY(hipEventRecord(S.ev_side[i], S.side[i]));
-    HIP_TRY(hipStreamWaitEvent(st, S.ev_side[i], 0));
+  if (S.side[0] != nullptr) {
+    HIP_TRY(hipEventRecord(S.ev_plan, st));
+    for (int i = 0; i < 2; ++i) HIP_TRY(hipStreamWaitEvent(S.side[i], S.ev_plan, 0));
+    HIP_TRY(launch_merge(g->cfg, ma, (u32)(want ? want : 1), st, S.side[0], S.side[1]));
+    for (int i = 0; i < 2; ++i) {
+      HIP_TRY(hipEventRecord(S.ev_side[i], S.side[i]));
+      HIP_TRY(hipStreamWaitEvent(st, S.ev_side[i], 0));
+    }
+  } else {
+    HIP_TRY(launch_merge(g->cfg, ma, (u32)(want ? want : 1), st, st, st));  // small batches: one stream
   }
   tm.mark(4, st);
   g->rounds += 1;

@@ -117,7 +117,8 @@ struct BatchScratch {
   }
   // small: [0] overflow_count u32, [2] arena error flag, [3] "a visited list was lost" flag,
   // [4..5] arena_top u64, [6..7] spill_top u64, [8..10] work list counts
-  int alloc(u64 b, u32 R, u32 cap, u64 spill_keys) {
+  // with_side = false: the three re-prune kernels share the caller's stream (small batches)
+  int alloc(u64 b, u32 R, u32 cap, u64 spill_keys, bool with_side = true) {
     bmax = b;
     vis_cap = cap;
     spill_chunk = 8192;
@@ -139,9 +140,11 @@ struct BatchScratch {
     HIP_TRY(spill.alloc(spill_cap * 8));
     HIP_TRY(vis_where.alloc(b * 8));
     HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&host_flag), 64, hipHostMallocDefault));
-    for (auto& s : side) HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
-    HIP_TRY(hipEventCreateWithFlags(&ev_plan, hipEventDisableTiming));
-    for (auto& e : ev_side) HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    if (with_side) {
+      for (auto& s : side) HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+      HIP_TRY(hipEventCreateWithFlags(&ev_plan, hipEventDisableTiming));
+      for (auto& e : ev_side) HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    }
     return ANN_OK;
   }
 };

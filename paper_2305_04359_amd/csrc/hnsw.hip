@@ -32,8 +32,9 @@ struct ann_hnsw {
   std::vector<DevBuf> pts;            // pts[l], l >= 1: the layer's vectors, n_l x d
   std::vector<DevBuf> down;           // down[l], l >= 1: n_l ids one layer below
   std::vector<u32> entry_c;           // the entry point's id on every layer
-  // start vertices of the searches of one call (two arrays that swap roles layer by layer)
-  mutable DevBuf qcur[2];
+  DevBuf walk;  // the upper layers, from the top, as the descent kernel reads them (DescendLayer)
+  // where each query of a call enters the bottom layer
+  mutable DevBuf qcur;
   mutable u64 qcur_cap = 0;
 };
 
@@ -268,13 +269,44 @@ int ann_hnsw_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dty
     }
   }
 
-  BatchScratch S;
+  // Two scratch areas and two streams: the upper layers of a batch do not depend on layer 0, so
+  // they run on a stream of their own, up to two batches ahead of the bottom layer's stream, and
+  // their small kernels fill the gaps the large ones leave.
+  constexpr int RING = 2;
+  BatchScratch S0, Su;
   const u32 vcap = 4 * efc > 256 ? 4 * efc : 256;
-  rc = S.alloc(bmax, 2 * m, vcap, default_spill_keys(bmax));
+  rc = S0.alloc(bmax, 2 * m, vcap, default_spill_keys(bmax));
   if (rc) return rc;
-  DevBuf cur_a, cur_b;
-  HIP_TRY(cur_a.alloc(bmax * 4));
-  HIP_TRY(cur_b.alloc(bmax * 4));
+  u64 bup = 1;
+  for (u32 l = 1; l <= top; ++l)
+    for (size_t r = 0; r < nrounds; ++r) bup = std::max(bup, ins_off[l][r + 1] - ins_off[l][r]);
+  if (top > 0) {
+    rc = Su.alloc(bup, m, vcap, default_spill_keys(bup), /*with_side=*/false);
+    if (rc) return rc;
+  }
+  struct UpStream {
+    hipStream_t s = nullptr;
+    hipEvent_t cur_ready[RING] = {}, cur_free[RING] = {}, setup = nullptr;
+    ~UpStream() {
+      if (s) (void)hipStreamDestroy(s);
+      for (auto& e : cur_ready)
+        if (e) (void)hipEventDestroy(e);
+      for (auto& e : cur_free)
+        if (e) (void)hipEventDestroy(e);
+      if (setup) (void)hipEventDestroy(setup);
+    }
+  } us;
+  DevBuf cur_a[RING], cur_b[RING];
+  if (top > 0) {
+    HIP_TRY(hipStreamCreateWithFlags(&us.s, hipStreamNonBlocking));
+    HIP_TRY(hipEventCreateWithFlags(&us.setup, hipEventDisableTiming));
+    for (int k = 0; k < RING; ++k) {
+      HIP_TRY(hipEventCreateWithFlags(&us.cur_ready[k], hipEventDisableTiming));
+      HIP_TRY(hipEventCreateWithFlags(&us.cur_free[k], hipEventDisableTiming));
+      HIP_TRY(cur_a[k].alloc(bmax * 4));
+      HIP_TRY(cur_b[k].alloc(bmax * 4));
+    }
+  }
   PhaseTimer tm, tm_off;
   rc = tm.init(o.collect_stats != 0);
   if (rc) return rc;
@@ -291,13 +323,22 @@ int ann_hnsw_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dty
 
   for (int attempt = 0; attempt < 2; ++attempt) {
     const bool sync = attempt == 1;
+    // the second attempt waits on the host in every batch: one stream serves it
+    hipStream_t up = sync ? st : us.s;
+    if (top > 0) {
+      HIP_TRY(hipEventRecord(us.setup, st));
+      HIP_TRY(hipStreamWaitEvent(up, us.setup, 0));
+    }
     for (size_t r = 0; r < nrounds; ++r) {
       if (o.max_rounds && r >= o.max_rounds) break;
       const u64 lo = bounds[r], b = bounds[r + 1] - bounds[r];
-      u32* cur = cur_a.as<u32>();
-      u32* nxt = cur_b.as<u32>();
+      const int k = (int)(r % RING);
+      u32* cur = cur_a[k].as<u32>();
+      u32* nxt = cur_b[k].as<u32>();
       if (top > 0) {
-        rc = fill_u32(cur, b, h->entry_c[top], st);
+        // this pair of arrays was last read by the bottom layer's search RING batches ago
+        if (r >= (size_t)RING) HIP_TRY(hipStreamWaitEvent(up, us.cur_free[k], 0));
+        rc = fill_u32(cur, b, h->entry_c[top], up);
         if (rc) return rc;
       }
       for (u32 l = top; l >= 1; --l) {
@@ -307,7 +348,7 @@ int ann_hnsw_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dty
         sd.cur = cur;
         sd.next = nxt;
         sd.down = h->down[l].as<u32>();
-        rc = query_launch(g, lp[l], lp[0], order_dev.as<u32>() + lo, b, 1, 1, -1.0f, &sd, nullptr, nullptr, st);
+        rc = query_launch(g, lp[l], lp[0], order_dev.as<u32>() + lo, b, 1, 1, -1.0f, &sd, nullptr, nullptr, up);
         if (rc) return rc;
         // the layer's own points: BatchInsert from the same start vertices
         const u64 i0 = ins_off[l][r], bl = ins_off[l][r + 1] - i0;
@@ -315,29 +356,53 @@ int ann_hnsw_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dty
           StartsArgs si = sd;
           si.slot = ins_slot_dev[l].as<u32>() + i0;
           si.slot_host = ins_slot[l].data() + i0;
-          rc = batch_insert(g, lp[l], ins_c[l].data() + i0, ins_c_dev[l].as<u32>() + i0, bl, efc, alpha, S, tm_off, st,
+          rc = batch_insert(g, lp[l], ins_c[l].data() + i0, ins_c_dev[l].as<u32>() + i0, bl, efc, alpha, Su, tm_off, up,
                             sync, &si);
           if (rc) return rc;
         }
         std::swap(cur, nxt);
       }
+      if (top > 0) {
+        HIP_TRY(hipEventRecord(us.cur_ready[k], up));
+        HIP_TRY(hipStreamWaitEvent(st, us.cur_ready[k], 0));
+      }
       StartsArgs s0;
       s0.cur = cur;
-      rc = batch_insert(h->layer[0], lp[0], order.data() + lo, order_dev.as<u32>() + lo, b, efc, alpha, S, tm, st, sync,
+      rc = batch_insert(h->layer[0], lp[0], order.data() + lo, order_dev.as<u32>() + lo, b, efc, alpha, S0, tm, st, sync,
                         top > 0 ? &s0 : nullptr);
       if (rc) return rc;
+      if (top > 0) HIP_TRY(hipEventRecord(us.cur_free[k], st));
       h->rounds += 1;
     }
-    rc = finish_batches(h->layer[0], S, tm, st);
+    // the bottom layer's stream has waited for everything the other one was given
+    rc = finish_batches(h->layer[0], S0, tm, st);
+    if (top > 0 && (rc == ANN_OK || rc == ANN_LOST_LIST)) {
+      const int rc_up = finish_batches(h->layer[1], Su, tm_off, st);
+      if (rc_up != ANN_OK) rc = rc_up;
+    }
     if (rc != ANN_LOST_LIST) break;
     if (sync) return fail(ANN_EINTERNAL, "a visited list was lost in a synchronised batch");
     rc = reset_layers(h, st);  // start over, waiting after step 1 of every batch
     if (rc) return rc;
-    HIP_TRY(hipMemsetAsync(S.small.p, 0, 64, st));
+    HIP_TRY(hipMemsetAsync(S0.small.p, 0, 64, st));
+    if (top > 0) HIP_TRY(hipMemsetAsync(Su.small.p, 0, 64, st));
     h->layer[0]->stats.restarts = 1;
     h->rounds = 0;
   }
   if (rc) return rc;
+  if (top > 0) {
+    std::vector<DescendLayer> walk;
+    for (u32 l = top; l >= 1; --l) {
+      DescendLayer y{};
+      y.points = static_cast<const char*>(lp[l]);
+      y.graph = h->layer[l]->rows;
+      y.down = h->down[l].as<u32>();
+      y.R = m;
+      walk.push_back(y);
+    }
+    HIP_TRY(h->walk.alloc(walk.size() * sizeof(DescendLayer)));
+    HIP_TRY(hipMemcpy(h->walk.p, walk.data(), walk.size() * sizeof(DescendLayer), hipMemcpyHostToDevice));
+  }
   guard.h = nullptr;
   *out = h;
   return ANN_OK;
@@ -362,28 +427,27 @@ int ann_hnsw_search(const ann_hnsw* h, const void* points_dev, const void* queri
   if (rc) return rc;
   if (h->top == 0) return query_launch(g0, p0, qs, nullptr, nq, k, L, eps, nullptr, ids_dev, dists_dev, st);
   if (h->qcur_cap < nq) {
-    HIP_TRY(hipStreamSynchronize(st));  // an earlier call may still use the old arrays
-    for (auto& q : h->qcur) HIP_TRY(q.alloc(nq * 4));
+    HIP_TRY(hipStreamSynchronize(st));  // an earlier call may still use the old array
+    HIP_TRY(h->qcur.alloc(nq * 4));
     h->qcur_cap = nq;
   }
-  u32* cur = h->qcur[0].as<u32>();
-  u32* nxt = h->qcur[1].as<u32>();
-  rc = fill_u32(cur, nq, h->entry_c[h->top], st);
-  if (rc) return rc;
+  // the upper layers in one launch, then the bottom layer from where each query arrived
   for (u32 l = h->top; l >= 1; --l) {
     const void* pl = nullptr;
-    rc = resolve_points(h->layer[l], h->pts[l].p, st, &pl);
+    rc = resolve_points(h->layer[l], h->pts[l].p, st, &pl);  // (made at build time; nothing to do)
     if (rc) return rc;
-    StartsArgs sd;
-    sd.cur = cur;
-    sd.next = nxt;
-    sd.down = h->down[l].as<u32>();
-    rc = query_launch(h->layer[l], pl, qs, nullptr, nq, 1, 1, -1.0f, &sd, nullptr, nullptr, st);
-    if (rc) return rc;
-    std::swap(cur, nxt);
   }
+  DescendArgs da{};
+  da.queries = static_cast<const char*>(qs);
+  da.qrow_bytes = g0->cfg.row_bytes;
+  da.nq = (u32)nq;
+  da.nlayers = h->top;
+  da.entry = h->entry_c[h->top];
+  da.layers = h->walk.as<DescendLayer>();
+  da.out = h->qcur.as<u32>();
+  HIP_TRY(launch_descend(g0->cfg, da, st));
   StartsArgs s0;
-  s0.cur = cur;
+  s0.cur = h->qcur.as<u32>();
   return query_launch(g0, p0, qs, nullptr, nq, k, L, eps, &s0, ids_dev, dists_dev, st);
 }
 

@@ -14,6 +14,8 @@
 // exactly while the table remembers up to twice as many vertices.  The bucket count need not be
 // a power of two; it is chosen so that the wave's LDS lands on an occupancy step.
 #pragma once
+#include <cstddef>
+
 #include "ann_device.hpp"
 #include "ann_internal.hpp"
 
@@ -355,10 +357,19 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
 
   if (a.nvis != nullptr && lane == 0) a.nvis[qi] = nv;
   if constexpr (OWN) {
-    if (a.next_start != nullptr && lane == 0) {
-      // the beam's first entry is the closest vertex the search visited (it always holds one)
-      const u32 best = key_id(A[0]);
-      a.next_start[a.slot != nullptr ? a.slot[qi] : qi] = a.down != nullptr ? a.down[best] : best;
+    // The three pointers this needs are read from the kernel's argument block here, not through
+    // `a`: arguments named in the code are all fetched into scalar registers at the kernel's
+    // start and would occupy six of them for the whole search.
+    if (lane == 0) {
+      const char* kp = (const char*)__builtin_amdgcn_kernarg_segment_ptr();
+      u32* next = *reinterpret_cast<u32* const volatile*>(kp + offsetof(SearchArgs, next_start));
+      if (next != nullptr) {
+        const u32* slot = *reinterpret_cast<const u32* const volatile*>(kp + offsetof(SearchArgs, slot));
+        const u32* down = *reinterpret_cast<const u32* const volatile*>(kp + offsetof(SearchArgs, down));
+        // the beam's first entry is the closest vertex the search visited (it always holds one)
+        const u32 best = key_id(A[0]);
+        next[slot != nullptr ? slot[qi] : qi] = down != nullptr ? down[best] : best;
+      }
     }
   }
   if (a.out_ids != nullptr) {
