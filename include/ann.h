@@ -265,6 +265,14 @@ int ann_hnsw_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dty
                    uint32_t m, uint32_t efc, float alpha, uint64_t seed, const ann_hnsw_opts* opts,
                    void* stream, ann_hnsw** out);
 
+/* Wraps an index given on the host: level_host (n), the entry point (a point
+ * of the highest level), and rows_host[l] for l = 0..max level, each n x
+ * (l ? m : 2m) adjacency rows of point ids, ANN_NONE padded (the rows of
+ * points below layer l are ignored).  points_dev as ann_hnsw_build.  Blocks. */
+int ann_hnsw_from_host(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric,
+                       uint32_t m, const uint32_t* level_host, uint32_t entry,
+                       const uint32_t* const* rows_host, void* stream, ann_hnsw** out);
+
 /* Queries: beam 1 from the entry point down to layer 1, then greedySearch of
  * Alg. 1 on layer 0 from the vertex reached (with the (1 + eps) rule of
  * ann_search_eps when eps >= 0).  Arguments and outputs as ann_search_eps;

@@ -67,7 +67,7 @@ EXPORTS = [
     "ann_build", "ann_insert_batch", "ann_insert_points", "ann_graph_reserve", "ann_search", "ann_search_eps", "ann_start_vertex", "ann_graph_from_host",
     "ann_graph_copy_neighbors", "ann_graph_device_rows", "ann_graph_info", "ann_get_stats",
     "ann_graph_free", "ann_sort_edges", "ann_last_error",
-    "ann_hnsw_build", "ann_hnsw_search", "ann_hnsw_info", "ann_hnsw_copy_levels", "ann_hnsw_layer_size",
+    "ann_hnsw_build", "ann_hnsw_from_host", "ann_hnsw_search", "ann_hnsw_info", "ann_hnsw_copy_levels", "ann_hnsw_layer_size",
     "ann_hnsw_copy_layer", "ann_hnsw_get_stats", "ann_hnsw_free",
 ]
 
@@ -120,6 +120,9 @@ def lib():
         L.ann_hnsw_build.restype = C.c_int
         L.ann_hnsw_build.argtypes = [vp, u64, u32, C.c_int, C.c_int, u32, u32, C.c_float, u64,
                                      C.POINTER(HnswOpts), vp, C.POINTER(vp)]
+        L.ann_hnsw_from_host.restype = C.c_int
+        L.ann_hnsw_from_host.argtypes = [vp, u64, u32, C.c_int, C.c_int, u32, vp, u32, C.POINTER(vp), vp,
+                                         C.POINTER(vp)]
         L.ann_hnsw_search.restype = C.c_int
         L.ann_hnsw_search.argtypes = [vp, vp, vp, u64, u32, u32, C.c_float, vp, vp, vp]
         L.ann_hnsw_info.restype = C.c_int
@@ -385,6 +388,26 @@ def ann_hnsw_build(points, m, efc, alpha, seed=1, metric=L2SQ, batch_cap=0, orde
     h = C.c_void_p()
     _check(lib().ann_hnsw_build(points.data_ptr(), points.shape[0], points.shape[1], _dtype_code(points),
                                 int(metric), m, efc, float(alpha), seed, C.byref(o), _stream_ptr(), C.byref(h)))
+    return Hnsw(h.value)
+
+
+def ann_hnsw_from_host(points, m, level, entry, layers, metric=L2SQ) -> Hnsw:
+    """An index from host arrays: level (n), entry point, layers[l] = n x (2m if l == 0 else m)."""
+    points = _dev2d(points, "points")
+    n = points.shape[0]
+    level = np.ascontiguousarray(level, dtype=np.uint32)
+    layers = [np.ascontiguousarray(a, dtype=np.uint32) for a in layers]
+    if level.shape != (n,):
+        raise ValueError("level must hold n entries")
+    for l, a in enumerate(layers):
+        if a.shape != (n, 2 * m if l == 0 else m):
+            raise ValueError(f"layer {l} has the wrong shape")
+    ptrs = (C.c_void_p * len(layers))(*[a.ctypes.data for a in layers])
+    h = C.c_void_p()
+    if len(layers) != int(level.max()) + 1:
+        raise ValueError("one array per layer, up to the highest level")
+    _check(lib().ann_hnsw_from_host(points.data_ptr(), n, points.shape[1], _dtype_code(points), int(metric), m,
+                                    level.ctypes.data_as(C.c_void_p), int(entry), ptrs, _stream_ptr(), C.byref(h)))
     return Hnsw(h.value)
 
 

@@ -95,6 +95,81 @@ int reset_layers(ann_hnsw* h, hipStream_t st) {
   return ANN_OK;
 }
 
+// The layers of an index whose levels and entry point are set: vertices, compact vectors, maps
+// one layer down, empty rows.
+int make_layers(ann_hnsw* h, const void* points_dev, hipStream_t st) {
+  const u32 top = h->top, m = h->m, d = h->d;
+  const u64 n = h->n;
+  h->layer.assign(top + 1, nullptr);
+  h->ids.resize(top + 1);
+  h->pts.resize(top + 1);
+  h->down.resize(top + 1);
+  h->entry_c.assign(top + 1, 0);
+  const u64 esz = h->dtype == ANN_F32 ? 4 : 1;
+  int rc = new_graph(n, d, h->dtype, h->metric, 2 * m, &h->layer[0]);
+  if (rc) return rc;
+  for (u32 l = 1; l <= top; ++l)
+    for (u64 i = 0; i < n; ++i)
+      if (h->level[i] >= l) h->ids[l].push_back((u32)i);
+  for (u32 l = 1; l <= top; ++l) {
+    const std::vector<u32>& mine = h->ids[l];
+    const u64 nl = mine.size();
+    rc = new_graph(nl, d, h->dtype, h->metric, m, &h->layer[l]);
+    if (rc) return rc;
+    std::vector<u32> dn(nl);
+    if (l == 1) {
+      dn = mine;
+    } else {
+      const std::vector<u32>& below = h->ids[l - 1];
+      u64 j = 0;
+      for (u64 c = 0; c < nl; ++c) {
+        while (below[j] != mine[c]) ++j;  // both ascending, mine is a subset
+        dn[c] = (u32)j;
+      }
+    }
+    DevBuf idsd;
+    HIP_TRY(idsd.alloc(nl * 4));
+    HIP_TRY(hipMemcpyAsync(idsd.p, mine.data(), nl * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(h->down[l].alloc(nl * 4));
+    HIP_TRY(hipMemcpyAsync(h->down[l].p, dn.data(), nl * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(h->pts[l].alloc(nl * d * esz));
+    const u64 bytes = nl * d * esz;
+    hipLaunchKernelGGL(gather_rows_kernel, dim3((u32)((bytes + 255) / 256)), dim3(256), 0, st,
+                       static_cast<const unsigned char*>(points_dev), idsd.as<u32>(), nl, (u32)(d * esz),
+                       h->pts[l].as<unsigned char>());
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(st));  // idsd and the host vectors go out of scope
+    h->entry_c[l] = (u32)(std::lower_bound(mine.begin(), mine.end(), h->entry) - mine.begin());
+  }
+  h->entry_c[0] = h->entry;
+  for (u32 l = 0; l <= top; ++l) {
+    ann_graph* g = h->layer[l];
+    g->start = h->entry_c[l];
+    HIP_TRY(hipMemsetAsync(g->rows, 0xFF, (size_t)g->n * g->R * sizeof(u32), st));
+  }
+  return ANN_OK;
+}
+
+// The table the descent kernel reads: the upper layers from the top.
+int make_walk(ann_hnsw* h, hipStream_t st) {
+  if (h->top == 0) return ANN_OK;
+  std::vector<DescendLayer> walk;
+  for (u32 l = h->top; l >= 1; --l) {
+    const void* pl = nullptr;
+    int rc = resolve_points(h->layer[l], h->pts[l].p, st, &pl);
+    if (rc) return rc;
+    DescendLayer y{};
+    y.points = static_cast<const char*>(pl);
+    y.graph = h->layer[l]->rows;
+    y.down = h->down[l].as<u32>();
+    y.R = h->m;
+    walk.push_back(y);
+  }
+  HIP_TRY(h->walk.alloc(walk.size() * sizeof(DescendLayer)));
+  HIP_TRY(hipMemcpy(h->walk.p, walk.data(), walk.size() * sizeof(DescendLayer), hipMemcpyHostToDevice));
+  return ANN_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -173,57 +248,11 @@ int ann_hnsw_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dty
     for (u64 i = 0; i < cnt; ++i) order[i] += order[i] >= h->entry ? 1u : 0u;
   }
 
-  // the layers: vertices, compact vectors, maps one layer down
-  h->layer.assign(top + 1, nullptr);
-  h->ids.resize(top + 1);
-  h->pts.resize(top + 1);
-  h->down.resize(top + 1);
-  h->entry_c.assign(top + 1, 0);
-  const u64 esz = dtype == ANN_F32 ? 4 : 1;
-  int rc = new_graph(n, d, dtype, metric, 2 * m, &h->layer[0]);
+  int rc = make_layers(h, points_dev, st);
   if (rc) return rc;
   rc = check_insert_params(h->layer[0], efc, alpha);
   if (rc) return rc;
-  for (u32 l = 1; l <= top; ++l)
-    for (u64 i = 0; i < n; ++i)
-      if (h->level[i] >= l) h->ids[l].push_back((u32)i);
-  for (u32 l = 1; l <= top; ++l) {
-    const std::vector<u32>& mine = h->ids[l];
-    const u64 nl = mine.size();
-    rc = new_graph(nl, d, dtype, metric, m, &h->layer[l]);
-    if (rc) return rc;
-    std::vector<u32> dn(nl);
-    if (l == 1) {
-      dn = mine;
-    } else {
-      const std::vector<u32>& below = h->ids[l - 1];
-      u64 j = 0;
-      for (u64 c = 0; c < nl; ++c) {
-        while (below[j] != mine[c]) ++j;  // both ascending, mine is a subset
-        dn[c] = (u32)j;
-      }
-    }
-    DevBuf idsd;
-    HIP_TRY(idsd.alloc(nl * 4));
-    HIP_TRY(hipMemcpyAsync(idsd.p, mine.data(), nl * 4, hipMemcpyHostToDevice, st));
-    HIP_TRY(h->down[l].alloc(nl * 4));
-    HIP_TRY(hipMemcpyAsync(h->down[l].p, dn.data(), nl * 4, hipMemcpyHostToDevice, st));
-    HIP_TRY(h->pts[l].alloc(nl * d * esz));
-    const u64 bytes = nl * d * esz;
-    hipLaunchKernelGGL(gather_rows_kernel, dim3((u32)((bytes + 255) / 256)), dim3(256), 0, st,
-                       static_cast<const unsigned char*>(points_dev), idsd.as<u32>(), nl, (u32)(d * esz),
-                       h->pts[l].as<unsigned char>());
-    HIP_TRY(hipGetLastError());
-    HIP_TRY(hipStreamSynchronize(st));  // idsd and the host vectors go out of scope
-    h->entry_c[l] = (u32)(std::lower_bound(mine.begin(), mine.end(), h->entry) - mine.begin());
-  }
-  h->entry_c[0] = h->entry;
-  for (u32 l = 0; l <= top; ++l) {
-    ann_graph* g = h->layer[l];
-    g->start = h->entry_c[l];
-    g->collect = o.collect_stats != 0;
-    HIP_TRY(hipMemsetAsync(g->rows, 0xFF, (size_t)g->n * g->R * sizeof(u32), st));
-  }
+  for (ann_graph* g : h->layer) g->collect = o.collect_stats != 0;
 
   // schedule of Alg. 3
   u64 theta = o.batch_cap ? o.batch_cap : (n / 50 > 1 ? n / 50 : 1);
@@ -390,19 +419,68 @@ int ann_hnsw_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dty
     h->rounds = 0;
   }
   if (rc) return rc;
-  if (top > 0) {
-    std::vector<DescendLayer> walk;
-    for (u32 l = top; l >= 1; --l) {
-      DescendLayer y{};
-      y.points = static_cast<const char*>(lp[l]);
-      y.graph = h->layer[l]->rows;
-      y.down = h->down[l].as<u32>();
-      y.R = m;
-      walk.push_back(y);
-    }
-    HIP_TRY(h->walk.alloc(walk.size() * sizeof(DescendLayer)));
-    HIP_TRY(hipMemcpy(h->walk.p, walk.data(), walk.size() * sizeof(DescendLayer), hipMemcpyHostToDevice));
+  rc = make_walk(h, st);
+  if (rc) return rc;
+  guard.h = nullptr;
+  *out = h;
+  return ANN_OK;
+}
+
+int ann_hnsw_from_host(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric, uint32_t m,
+                       const uint32_t* level_host, uint32_t entry, const uint32_t* const* rows_host, void* stream,
+                       ann_hnsw** out) {
+  if (out) *out = nullptr;
+  if (!points_dev || !out || !level_host || !rows_host) return fail(ANN_EINVAL, "null argument");
+  if (m < 2 || m > 256) return fail(ANN_EINVAL, "m must be in [2, 256]");
+  if (n < 1 || n >= (1ull << 31)) return fail(ANN_EINVAL, "n must be in [1, 2^31)");
+  if (entry >= n) return fail(ANN_EINVAL, "entry point out of range");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  ann_hnsw* h = new (std::nothrow) ann_hnsw();
+  if (!h) return fail(ANN_ENOMEM, "host allocation failed");
+  struct Guard {
+    ann_hnsw* h;
+    ~Guard() { free_hnsw(h); }
+  } guard{h};
+  h->n = n;
+  h->d = d;
+  h->m = m;
+  h->dtype = dtype;
+  h->metric = metric;
+  h->entry = entry;
+  h->level.assign(level_host, level_host + n);
+  u32 top = 0;
+  for (u64 i = 0; i < n; ++i) {
+    if (h->level[i] > 63) return fail(ANN_EINVAL, "levels must be at most 63");
+    top = h->level[i] > top ? h->level[i] : top;
   }
+  if (h->level[entry] != top) return fail(ANN_EINVAL, "the entry point must be on the highest layer");
+  h->top = top;
+  for (u32 l = 0; l <= top; ++l)
+    if (!rows_host[l]) return fail(ANN_EINVAL, "null layer");
+  int rc = make_layers(h, points_dev, st);
+  if (rc) return rc;
+  // rows: ids of members of the layer only, translated to the layer's own numbering
+  for (u32 l = 0; l <= top; ++l) {
+    ann_graph* g = h->layer[l];
+    const u32 R = g->R;
+    const std::vector<u32>& mine = h->ids[l];
+    std::vector<u32> rows((size_t)g->n * R, ANN_NONE);
+    for (u64 c = 0; c < g->n; ++c) {
+      const u64 p = l ? mine[c] : c;
+      const u32* src = rows_host[l] + p * R;
+      u32 deg = 0;
+      for (u32 j = 0; j < R && src[j] != ANN_NONE; ++j) {
+        const u32 q = src[j];
+        if (q >= n || h->level[q] < l) return fail(ANN_EINVAL, "neighbour id out of range or not on the layer");
+        rows[c * R + deg++] = l ? (u32)(std::lower_bound(mine.begin(), mine.end(), q) - mine.begin()) : q;
+      }
+    }
+    HIP_TRY(hipMemcpyAsync(g->rows, rows.data(), rows.size() * sizeof(u32), hipMemcpyHostToDevice, st));
+    HIP_TRY(launch_meta_from_rows(g->rows, g->n, R, g->meta, st));
+    HIP_TRY(hipStreamSynchronize(st));
+  }
+  rc = make_walk(h, st);
+  if (rc) return rc;
   guard.h = nullptr;
   *out = h;
   return ANN_OK;
@@ -432,11 +510,6 @@ int ann_hnsw_search(const ann_hnsw* h, const void* points_dev, const void* queri
     h->qcur_cap = nq;
   }
   // the upper layers in one launch, then the bottom layer from where each query arrived
-  for (u32 l = h->top; l >= 1; --l) {
-    const void* pl = nullptr;
-    rc = resolve_points(h->layer[l], h->pts[l].p, st, &pl);  // (made at build time; nothing to do)
-    if (rc) return rc;
-  }
   DescendArgs da{};
   da.queries = static_cast<const char*>(qs);
   da.qrow_bytes = g0->cfg.row_bytes;

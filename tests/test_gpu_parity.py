@@ -879,3 +879,53 @@ def test_hnsw_c2_full_size_last_batch_against_oracle(env):
     ids, dists = A.ann_hnsw_search(full, pts, qs, 10, 40)
     oi, od, _ = O.hnsw_search_batch(ds, oh, w.queries[:300], 10, 40, threads=0)
     assert (ids.cpu().numpy().view(np.uint32) == oi).all() and (dists.cpu().numpy() == od).all()
+
+
+def test_hnsw_search_worked_by_hand(env):
+    torch, A, O = env
+    g = json.load(open(os.path.join(GOLD, "hnsw_descent.json")))
+    xs, m = g["xs"], g["m"]
+    n = len(xs)
+    layers = []
+    for l in range(len(g["layers"])):
+        rows = np.full((n, 2 * m if l == 0 else m), NONE, np.uint32)
+        for v, nb in g["layers"][str(l)].items():
+            rows[int(v), :len(nb)] = nb
+        layers.append(rows)
+    for dtype, d in ((np.uint8, 16), (np.uint8, 4), (np.float32, 4)):
+        pts = np.zeros((n, d), dtype)
+        pts[:, 0] = xs
+        h = A.ann_hnsw_from_host(dev(torch, pts), m, g["level"], g["entry"], layers)
+        for c in g["cases"]:
+            q = np.zeros((1, d), dtype)
+            q[0, 0] = c["query_x"]
+            ids, dists = A.ann_hnsw_search(h, dev(torch, pts), dev(torch, q), g["k"], g["L"])
+            assert ids.cpu().numpy()[0].tolist() == c["expect_ids"]
+            assert dists.cpu().numpy()[0].tolist() == c["expect_dists"]
+        # the layers come back as they went in
+        for l, rows in enumerate(layers):
+            ids_l, rows_l = h.layer(l)
+            assert (ids_l == np.flatnonzero(np.array(g["level"]) >= l)).all() and (rows_l == rows[ids_l]).all()
+
+
+def test_hnsw_from_host_round_trip(env, c1):
+    """An index built by the oracle, handed to the library: same answers as the oracle's search,
+    for every beam width (the walk down runs in a kernel of its own, with no visited set)."""
+    torch, A, O = env
+    n = 6000
+    ds = O.Dataset(c1.points[:n], 0)
+    oh = O.hnsw_build(ds, 5, 24, 1.2, seed=8, threads=0)
+    assert oh.top >= 3
+    pts, qs = dev(torch, c1.points[:n]), dev(torch, c1.queries)
+    h = A.ann_hnsw_from_host(pts, 5, oh.level, oh.entry, oh.layers)
+    _check_hnsw_against(h, oh, n)
+    for L, k in ((1, 1), (8, 5), (50, 10)):
+        ids, dists = A.ann_hnsw_search(h, pts, qs, k, L)
+        oi, od, _ = O.hnsw_search_batch(ds, oh, c1.queries, k, L, threads=0)
+        assert (ids.cpu().numpy().view(np.uint32) == oi).all() and (dists.cpu().numpy() == od).all()
+    bad = [a.copy() for a in oh.layers]
+    bad[1][np.flatnonzero(oh.level >= 1)[0], 0] = int(np.flatnonzero(oh.level == 0)[0])  # not on layer 1
+    with pytest.raises(A.AnnError):
+        A.ann_hnsw_from_host(pts, 5, oh.level, oh.entry, bad)
+    with pytest.raises(A.AnnError):
+        A.ann_hnsw_from_host(pts, 5, oh.level, int(np.flatnonzero(oh.level == 0)[0]), oh.layers)
