@@ -1,4 +1,4 @@
-"""ctypes access to the CPU oracle (vamana_oracle.c, hnsw_oracle.c).
+"""ctypes access to the CPU oracle (vamana_oracle.c, hnsw_oracle.c, hcnng_oracle.c).
 
 TEST INFRASTRUCTURE.  Only tests/, the smoke check and the benchmark's CPU
 baseline leg may import this package; the HIP library and its Python binding
@@ -14,8 +14,8 @@ from dataclasses import dataclass
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRCS = [os.path.join(_HERE, f) for f in ("vamana_oracle.c", "hnsw_oracle.c")]
-_HDRS = [os.path.join(_HERE, f) for f in ("vamana_oracle.h", "hnsw_oracle.h")]
+_SRCS = [os.path.join(_HERE, f) for f in ("vamana_oracle.c", "hnsw_oracle.c", "hcnng_oracle.c")]
+_HDRS = [os.path.join(_HERE, f) for f in ("vamana_oracle.h", "hnsw_oracle.h", "hcnng_oracle.h")]
 _LIB = os.path.join(_HERE, "libvamana_oracle.so")
 
 NONE = 0xFFFFFFFF
@@ -70,6 +70,10 @@ class _Hnsw(C.Structure):
         ("level", C.POINTER(C.c_uint32)),
         ("rows", C.POINTER(C.POINTER(C.c_uint32))),
     ]
+
+
+class HcnngStats(C.Structure):
+    _fields_ = [("leaves", C.c_uint64), ("tree_edges", C.c_uint64), ("neighbours", C.c_uint64)]
 
 
 class Stats(C.Structure):
@@ -172,6 +176,16 @@ def lib():
         L.vo_hnsw_search_batch.argtypes = [
             C.POINTER(_Data), C.POINTER(_Hnsw), C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint32,
             C.c_double, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(Stats)]
+        L.vo_hcnng_tree.restype = C.c_int
+        L.vo_hcnng_tree.argtypes = [C.POINTER(_Data), C.c_uint32, C.c_uint64, C.c_uint32, C.c_void_p,
+                                    C.c_void_p, C.POINTER(C.c_uint64)]
+        L.vo_hcnng_leaf.restype = C.c_int
+        L.vo_hcnng_leaf.argtypes = [C.POINTER(_Data), C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32,
+                                    C.c_void_p, C.c_void_p, C.POINTER(C.c_uint64)]
+        L.vo_hcnng_build.restype = C.c_int
+        L.vo_hcnng_build.argtypes = [C.POINTER(_Data), C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
+                                     C.c_uint32, C.c_double, C.c_uint64, C.c_int, C.c_void_p,
+                                     C.POINTER(HcnngStats)]
         L.vo_threads.restype = C.c_int
         L.vo_threads.argtypes = [C.c_int]
         _lib = L
@@ -503,3 +517,40 @@ def hnsw_search_batch(ds: Dataset, h: Hnsw, queries: np.ndarray, k: int, L: int,
     if rc:
         raise RuntimeError(f"vo_hnsw_search_batch rc={rc}")
     return ids, dists, entry
+
+
+# ---------------------------------------------------------------------------------------------
+# clustering-based builder (hcnng_oracle.c)
+# ---------------------------------------------------------------------------------------------
+def hcnng_tree(ds: Dataset, Ls: int, seed: int, tree: int):
+    """One cluster tree: (perm, leaf_off): the point ids leaf after leaf and the leaf boundaries."""
+    perm = np.empty(ds.n, np.uint32)
+    off = np.empty(ds.n + 1, np.uint64)
+    nl = C.c_uint64(0)
+    rc = lib().vo_hcnng_tree(ds.c(), Ls, seed, tree, _ptr(perm), _ptr(off), C.byref(nl))
+    if rc:
+        raise RuntimeError(f"vo_hcnng_tree rc={rc}")
+    return perm, off[:nl.value + 1].astype(np.int64)
+
+
+def hcnng_leaf(ds: Dataset, ids: np.ndarray, s: int, l: int) -> np.ndarray:
+    """The degree-bounded tree of one leaf: accepted pairs (u < v) in acceptance order."""
+    ids = np.ascontiguousarray(ids, dtype=np.uint32)
+    cnt = ids.shape[0]
+    eu = np.empty(max(cnt - 1, 1), np.uint32)
+    ev = np.empty(max(cnt - 1, 1), np.uint32)
+    ne = C.c_uint64(0)
+    rc = lib().vo_hcnng_leaf(ds.c(), _ptr(ids), cnt, s, l, _ptr(eu), _ptr(ev), C.byref(ne))
+    if rc:
+        raise RuntimeError(f"vo_hcnng_leaf rc={rc}")
+    return np.stack([eu[:ne.value], ev[:ne.value]], axis=1)
+
+
+def hcnng_build(ds: Dataset, T: int, Ls: int, s: int, l: int, R: int, alpha: float, seed: int = 1,
+                threads: int = 1, stats: HcnngStats | None = None) -> np.ndarray:
+    graph = np.empty((ds.n, R), np.uint32)
+    rc = lib().vo_hcnng_build(ds.c(), T, Ls, s, l, R, float(alpha), seed, threads, _ptr(graph),
+                              C.byref(stats) if stats is not None else None)
+    if rc:
+        raise RuntimeError(f"vo_hcnng_build rc={rc}")
+    return graph
