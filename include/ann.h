@@ -294,6 +294,44 @@ int ann_hnsw_copy_layer(const ann_hnsw* h, uint32_t layer, uint32_t* ids_host, u
 int ann_hnsw_get_stats(const ann_hnsw* h, uint32_t layer, ann_stats* stats);
 void ann_hnsw_free(ann_hnsw* h);
 
+/* ------------------------------------------------------------------------
+ * Clustering-based builder (Sec. 3.2 and 4.3, ParlayHCNNG).  T cluster trees;
+ * a node with more than Ls points is split by two pivots drawn among its
+ * points (a point goes with the pivot it is nearer to, the first on ties);
+ * in every leaf a spanning tree is grown by Kruskal's scan over the pairs
+ * (point, one of its l nearest neighbours in the leaf), no point taking more
+ * than s tree edges; a point's row is prune(p, its tree neighbours over all
+ * trees, R) with the alpha rule of Sec. 4.1.
+ *   random numbers   draw(tree, node, j) = the (k+1)-th output of
+ *                    SplitMix64(seed), k = 2 * (tree * 2^40 + node) + j,
+ *                    nodes numbered like a binary heap (root 1)
+ *   pivots           a node holds its c points in ascending id order; the
+ *                    pivots stand at positions mulhi64(draw(..,0), c) and
+ *                    mulhi64(draw(..,1), c - 1), the second moved up by one
+ *                    when it is not below the first
+ *   degenerate cut   when one side stays empty, or at depth 39, the node's
+ *                    order is cut in the middle (ceil(c/2) points left)
+ *   pairs            sorted by (distance, smaller id, larger id)
+ * The result is a graph like ann_build's (start vertex = ann_start_vertex);
+ * ann_search and ann_search_eps serve it.
+ *   dtype ANN_U8 or ANN_I8, metric ANN_L2SQ, d <= 128;
+ *   1 <= T < 2^20, 2 <= Ls <= 1024, 1 <= l <= 16, Ls * l <= 16384,
+ *   1 <= s <= 255, 1 <= R <= 512, T * 2n < 2^32.
+ * Blocks until done.
+ * ------------------------------------------------------------------------ */
+int ann_hcnng_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric,
+                    uint32_t T, uint32_t Ls, uint32_t s, uint32_t l, uint32_t R, float alpha, uint64_t seed,
+                    void* stream, ann_graph** out);
+
+/* One cluster tree and its leaves' spanning trees alone (for tests): perm_host
+ * receives the n point ids leaf after leaf, leaf_off_host the *nleaves + 1
+ * leaf boundaries (room for n + 1), pairs_host the accepted pairs (two ids
+ * each, room for n pairs) leaf after leaf in the order they were accepted.   */
+int ann_hcnng_tree_edges(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, uint32_t Ls,
+                         uint32_t s, uint32_t l, uint64_t seed, uint32_t tree, void* stream,
+                         uint32_t* perm_host, uint64_t* leaf_off_host, uint64_t* nleaves,
+                         uint32_t* pairs_host, uint64_t* npairs);
+
 /* Thread-local description of the last error on this thread ("" if none).   */
 const char* ann_last_error(void);
 

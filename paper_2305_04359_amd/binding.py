@@ -69,6 +69,7 @@ EXPORTS = [
     "ann_graph_free", "ann_sort_edges", "ann_last_error",
     "ann_hnsw_build", "ann_hnsw_from_host", "ann_hnsw_search", "ann_hnsw_info", "ann_hnsw_copy_levels", "ann_hnsw_layer_size",
     "ann_hnsw_copy_layer", "ann_hnsw_get_stats", "ann_hnsw_free",
+    "ann_hcnng_build", "ann_hcnng_tree_edges",
 ]
 
 _lib = None
@@ -137,6 +138,12 @@ def lib():
         L.ann_hnsw_get_stats.argtypes = [vp, u32, C.POINTER(Stats)]
         L.ann_hnsw_free.restype = None
         L.ann_hnsw_free.argtypes = [vp]
+        L.ann_hcnng_build.restype = C.c_int
+        L.ann_hcnng_build.argtypes = [vp, u64, u32, C.c_int, C.c_int, u32, u32, u32, u32, u32, C.c_float, u64, vp,
+                                      C.POINTER(vp)]
+        L.ann_hcnng_tree_edges.restype = C.c_int
+        L.ann_hcnng_tree_edges.argtypes = [vp, u64, u32, C.c_int, u32, u32, u32, u64, u32, vp, vp, vp,
+                                           C.POINTER(u64), vp, C.POINTER(u64)]
         L.ann_last_error.restype = C.c_char_p
         L.ann_last_error.argtypes = []
         _lib = L
@@ -426,3 +433,27 @@ def ann_hnsw_search(index: Hnsw, points, queries, k, L, eps=-1.0, ids_out=None, 
     _check(lib().ann_hnsw_search(index.handle, points.data_ptr(), queries.data_ptr(), nq, k, L, float(eps),
                                  ids_out.data_ptr(), dists_out.data_ptr(), _stream_ptr()))
     return ids_out, dists_out
+
+
+def ann_hcnng_build(points, T, Ls, s, l, R, alpha, seed=1, metric=L2SQ) -> Graph:
+    """The clustering-based builder of Sec. 4.3 over a device tensor of uint8 or int8 points."""
+    points = _dev2d(points, "points")
+    h = C.c_void_p()
+    _check(lib().ann_hcnng_build(points.data_ptr(), points.shape[0], points.shape[1], _dtype_code(points),
+                                 int(metric), T, Ls, s, l, R, float(alpha), seed, _stream_ptr(), C.byref(h)))
+    return Graph(h.value)
+
+
+def ann_hcnng_tree_edges(points, Ls, s, l, seed, tree):
+    """One cluster tree: (perm, leaf_off, pairs) as numpy arrays."""
+    points = _dev2d(points, "points")
+    n = points.shape[0]
+    perm = np.empty(n, np.uint32)
+    off = np.empty(n + 1, np.uint64)
+    pairs = np.empty((n, 2), np.uint32)
+    nl, npairs = C.c_uint64(0), C.c_uint64(0)
+    _check(lib().ann_hcnng_tree_edges(points.data_ptr(), n, points.shape[1], _dtype_code(points), Ls, s, l, seed,
+                                      tree, _stream_ptr(), perm.ctypes.data_as(C.c_void_p),
+                                      off.ctypes.data_as(C.c_void_p), C.byref(nl),
+                                      pairs.ctypes.data_as(C.c_void_p), C.byref(npairs)))
+    return perm, off[:nl.value + 1].astype(np.int64), pairs[:npairs.value].copy()

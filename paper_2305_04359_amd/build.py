@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libannmi.so")
-SOURCES = ["search.hip", "search_eps.hip", "search_own.hip", "search_own_eps.hip", "prune.hip", "merge.hip", "sort.hip", "start_vertex.hip", "driver.hip", "hnsw.hip", "descend.hip"]
+SOURCES = ["search.hip", "search_eps.hip", "search_own.hip", "search_own_eps.hip", "prune.hip", "merge.hip", "sort.hip", "start_vertex.hip", "driver.hip", "hnsw.hip", "descend.hip", "hcnng.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-result",

@@ -153,6 +153,8 @@ struct MergeArgs {
   long long a16;
   float af;
   DevCounters* counters;
+  u32 force_prune;  // non-zero: every segment is pruned, also where row and segment fit in R (the
+                    // clustering-based builder, Sec. 4.3; rows start empty there)
 };
 
 constexpr u32 PRUNE_LDS_CAP = 512;     // candidate keys sorted in LDS by the step-1 prune kernel (a power of two)
@@ -177,7 +179,8 @@ bool mfma_prune_ok(u32 R, const DistCfg& cfg);
 // stable LSD radix sort of 64-bit keys on bits [32, 32+key_bits); result is left in `keys`
 // (`tmp` holds `count` keys, `hist` holds radix_hist_entries(count) u32)
 u64 radix_hist_entries(u64 count);
-hipError_t radix_sort_edges(u64* keys, u64* tmp, u32* hist, u64 hist_entries, u64 count, u32 key_bits, hipStream_t s);
+hipError_t radix_sort_edges(u64* keys, u64* tmp, u32* hist, u64 hist_entries, u64 count, u32 key_bits, hipStream_t s,
+                            u32 first_bit = 32);
 
 // start vertex (point nearest the mean)
 hipError_t start_vertex_device(const void* points, u64 n, u32 d, int dtype, hipStream_t s, u32* start_out);

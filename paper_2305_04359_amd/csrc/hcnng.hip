@@ -1,0 +1,745 @@
+// The clustering-based builder of Sec. 4.3 (ParlayHCNNG) with the cluster trees of Sec. 3.2.
+//
+// Per tree: the points are split level by level (all nodes of a level in one pass: every point
+// takes the side of the nearer of its node's two pivots, a stable radix sort by child index puts
+// the children in place); the leaves' vectors are gathered into leaf order as int8; one wavefront
+// per 32 points of a leaf finds their l nearest neighbours inside the leaf on the matrix cores
+// (32 x 32 inner products per instruction group, every lane keeping the best of the candidates it
+// sees for its own point); one workgroup per leaf sorts the leaf's candidate pairs in LDS and runs
+// Kruskal's scan with the degree bound, 64 pairs at a time (a pair that fails once fails for
+// good, so the wave tests 64 in parallel and only the survivors are taken in order).
+// At the end the arcs of all trees are sorted by (point, neighbour), repeated ones dropped, and
+// every point's neighbours pruned with the alpha rule of Sec. 4.1 by the re-prune kernel of the
+// flat graph's BatchInsert.
+#include <algorithm>
+
+#include "ann_device.hpp"
+#include "driver_internal.hpp"
+
+using namespace annmi;
+
+namespace {
+
+constexpr u32 HC_MAX_LS = 1024;       // points per leaf
+constexpr u32 HC_MAX_L = 16;          // nearest neighbours per point that restrict the tree
+constexpr u32 HC_MAX_PAIRS = 16384;   // candidate pairs per leaf (sorted in LDS)
+constexpr u32 HC_MAX_DEPTH = 39;      // below this depth a node is cut in the middle of its order
+constexpr u32 HC_NONE = 0xFFFFFFFFu;
+
+typedef int v4i_t __attribute__((ext_vector_type(4)));
+typedef int v16i_t __attribute__((ext_vector_type(16)));
+
+u64 stream_output(u64 seed, u64 k) {  // the (k+1)-th output of SplitMix64(seed)
+  u64 z = seed + (k + 1) * 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+u64 mulhi64(u64 a, u64 b) { return (u64)(((unsigned __int128)a * (unsigned __int128)b) >> 64); }
+
+u32 bits_to_hold(u64 count) {  // smallest b with 2^b - 1 >= count: indices below count never have all b bits set
+  u32 b = 1;
+  while (((1ull << b) - 1ull) < count) ++b;
+  return b;
+}
+
+__global__ __launch_bounds__(256) void hc_iota_kernel(u64* keys, u64 n) {
+  const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) keys[i] = i;
+}
+
+// One level of one tree.  keys_in[i] = (anything << 32) | id of the point at position i; the
+// nodes of the level are the position ranges off[s]..off[s+1].  A node that splits names the
+// positions of its two pivots; its points get child index base[s] (left: at most as far from the
+// first pivot as from the second) or base[s] + 1.  Other nodes keep their points under base[s].
+// Eight lanes per point.
+template <bool SIGNED>
+__global__ __launch_bounds__(256) void hc_side_kernel(const unsigned char* pts, u32 row_bytes, const u64* keys_in, u64 n,
+                                                      const u32* off, u32 nseg, const u32* pos1, const u32* pos2,
+                                                      const u32* base, u64* keys_out) {
+  const u64 t = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+  const u64 i = t >> 3;
+  const u32 sub = (u32)t & 7u;
+  if (i >= n) return;
+  const u32 id = (u32)keys_in[i];
+  u32 lo = 0, hi = nseg;
+  while (hi - lo > 1) {
+    const u32 mid = (lo + hi) >> 1;
+    if ((u64)off[mid] <= i)
+      lo = mid;
+    else
+      hi = mid;
+  }
+  const u32 seg = lo;
+  u32 idx = base[seg];
+  const u32 p1 = pos1[seg];
+  if (p1 != HC_NONE) {
+    const u32 ida = (u32)keys_in[p1], idb = (u32)keys_in[pos2[seg]];
+    const uint4* x = reinterpret_cast<const uint4*>(pts + (u64)id * row_bytes);
+    const uint4* a = reinterpret_cast<const uint4*>(pts + (u64)ida * row_bytes);
+    const uint4* b = reinterpret_cast<const uint4*>(pts + (u64)idb * row_bytes);
+    i32 xa = 0, xb = 0, aa = 0, bb = 0;
+    for (u32 pc = sub; pc < row_bytes / 16; pc += 8) {
+      const uint4 vx = x[pc], va = a[pc], vb = b[pc];
+      const u32 wx[4] = {vx.x, vx.y, vx.z, vx.w}, wa[4] = {va.x, va.y, va.z, va.w}, wb[4] = {vb.x, vb.y, vb.z, vb.w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if constexpr (SIGNED) {
+          xa = __builtin_amdgcn_sdot4((i32)wx[k], (i32)wa[k], xa, false);
+          xb = __builtin_amdgcn_sdot4((i32)wx[k], (i32)wb[k], xb, false);
+          aa = __builtin_amdgcn_sdot4((i32)wa[k], (i32)wa[k], aa, false);
+          bb = __builtin_amdgcn_sdot4((i32)wb[k], (i32)wb[k], bb, false);
+        } else {
+          xa = (i32)__builtin_amdgcn_udot4(wx[k], wa[k], (u32)xa, false);
+          xb = (i32)__builtin_amdgcn_udot4(wx[k], wb[k], (u32)xb, false);
+          aa = (i32)__builtin_amdgcn_udot4(wa[k], wa[k], (u32)aa, false);
+          bb = (i32)__builtin_amdgcn_udot4(wb[k], wb[k], (u32)bb, false);
+        }
+      }
+    }
+    // |x-a|^2 <= |x-b|^2  <=>  |a|^2 - 2<x,a> <= |b|^2 - 2<x,b>
+    const i32 lhs = group_sum(aa - 2 * xa), rhs = group_sum(bb - 2 * xb);
+    if (lhs > rhs) idx += 1;
+  }
+  if (sub == 0) keys_out[i] = ((u64)idx << 32) | id;
+}
+
+// first[c] = first position whose key carries child index c (untouched where there is none)
+__global__ __launch_bounds__(256) void hc_bounds_kernel(const u64* keys, u64 n, u32* first) {
+  const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const u32 c = (u32)(keys[i] >> 32);
+  if (i == 0 || (u32)(keys[i - 1] >> 32) != c) first[c] = (u32)i;
+}
+
+// The vectors in leaf order, as int8 (uint8 data moved down by 128: distances do not change),
+// rows of lv_stride bytes (a multiple of 32, zero tail), and their squared norms.  Eight lanes
+// per point.
+template <bool SIGNED>
+__global__ __launch_bounds__(256) void hc_gather_kernel(const unsigned char* pts, u32 row_bytes, const u64* keys, u64 n,
+                                                        u32 lv_stride, unsigned char* leafvec, i32* leafnorm) {
+  const u64 t = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+  const u64 i = t >> 3;
+  const u32 sub = (u32)t & 7u;
+  if (i >= n) return;
+  const u32 id = (u32)keys[i];
+  const uint4* x = reinterpret_cast<const uint4*>(pts + (u64)id * row_bytes);
+  uint4* y = reinterpret_cast<uint4*>(leafvec + i * lv_stride);
+  i32 nn = 0;
+  for (u32 pc = sub; pc < lv_stride / 16; pc += 8) {
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (pc < row_bytes / 16) {
+      v = x[pc];
+      if constexpr (!SIGNED) {
+        v.x ^= 0x80808080u;
+        v.y ^= 0x80808080u;
+        v.z ^= 0x80808080u;
+        v.w ^= 0x80808080u;
+      }
+    }
+    y[pc] = v;
+    nn = __builtin_amdgcn_sdot4((i32)v.x, (i32)v.x, nn, false);
+    nn = __builtin_amdgcn_sdot4((i32)v.y, (i32)v.y, nn, false);
+    nn = __builtin_amdgcn_sdot4((i32)v.z, (i32)v.z, nn, false);
+    nn = __builtin_amdgcn_sdot4((i32)v.w, (i32)v.w, nn, false);
+  }
+  nn = group_sum(nn);
+  if (sub == 0) leafnorm[i] = nn;
+}
+
+// The l nearest neighbours, inside its leaf, of each of 32 consecutive points of a leaf (block
+// (leaf, 32-point block), one wavefront).  Matrix-core tile: rows = 32 candidates, columns = the
+// 32 points; lane (half, col) then holds, for point col, the inner products with 16 of the 32
+// candidates, and keeps the LCAP smallest (distance, position) keys it has seen in registers.
+// The two lanes of a point merge their lists at the end.  knn_pos / knn_d: l entries per point,
+// ascending; positions are relative to the leaf.
+template <int LCAP>
+__global__ __launch_bounds__(64) void hc_knn_kernel(const unsigned char* leafvec, const i32* leafnorm, u32 lv_stride,
+                                                    const u32* leaf_off, u32 l, unsigned short* knn_pos, i32* knn_d) {
+  const u32 off = leaf_off[blockIdx.x];
+  const u32 cnt = leaf_off[blockIdx.x + 1] - off;
+  const u32 q0 = blockIdx.y * 32u;
+  if (q0 >= cnt) return;
+  const int lane = threadIdx.x;
+  const u32 half = (u32)lane >> 5, col = (u32)lane & 31u;
+  const u32 ksteps = lv_stride / 32u;  // at most 4
+  const u32 q = q0 + col;
+  const u32 qrow = q < cnt ? q : cnt - 1u;
+  const i32 qn = leafnorm[off + qrow];
+  v4i_t bq[4];
+#pragma unroll
+  for (u32 ks = 0; ks < 4; ++ks) {
+    const u32 kk = ks < ksteps ? ks : ksteps - 1u;
+    const v4i_t y = *reinterpret_cast<const v4i_t*>(leafvec + (u64)(off + qrow) * lv_stride + 32u * kk + 16u * half);
+    bq[ks] = ks < ksteps ? y : v4i_t{0, 0, 0, 0};
+  }
+  u64 best[LCAP];
+#pragma unroll
+  for (int i = 0; i < LCAP; ++i) best[i] = KEY_INF;
+
+  for (u32 c0 = 0; c0 < cnt; c0 += 32u) {
+    const u32 c = c0 + col;
+    const u32 crow = c < cnt ? c : cnt - 1u;
+    v4i_t av[4];
+#pragma unroll
+    for (u32 ks = 0; ks < 4; ++ks) {
+      const u32 kk = ks < ksteps ? ks : ksteps - 1u;
+      av[ks] = *reinterpret_cast<const v4i_t*>(leafvec + (u64)(off + crow) * lv_stride + 32u * kk + 16u * half);
+    }
+    // norms of this lane's 16 candidates: rows 8g + 4 half + 0..3, g = 0..3 (the array has a tail
+    // of 64 entries, so reading past the leaf's end stays inside it)
+    v4i_t cn[4];
+#pragma unroll
+    for (u32 g = 0; g < 4; ++g) cn[g] = *reinterpret_cast<const v4i_t*>(leafnorm + off + c0 + 8u * g + 4u * half);
+    v16i_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(av[ks], bq[ks], acc, 0, 0, 0);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const u32 cand = c0 + 8u * (r / 4) + 4u * half + (r % 4);
+      const i32 dd = qn + cn[r / 4][r % 4] - 2 * acc[r];
+      u64 key = (cand < cnt && cand != q) ? (((u64)(u32)dd << 32) | cand) : KEY_INF;
+      if (ballot(key < best[LCAP - 1]) != 0ull) {
+#pragma unroll
+        for (int i = 0; i < LCAP; ++i) {
+          const u64 lo = key < best[i] ? key : best[i];
+          key = key < best[i] ? best[i] : key;
+          best[i] = lo;
+        }
+      }
+    }
+  }
+  // the other half of the candidates, from the partner lane
+  u64 other[LCAP];
+#pragma unroll
+  for (int i = 0; i < LCAP; ++i) other[i] = (u64)__shfl_xor((unsigned long long)best[i], 32, 64);
+#pragma unroll
+  for (int j = 0; j < LCAP; ++j) {
+    u64 key = other[j];
+#pragma unroll
+    for (int i = 0; i < LCAP; ++i) {
+      const u64 lo = key < best[i] ? key : best[i];
+      key = key < best[i] ? best[i] : key;
+      best[i] = lo;
+    }
+  }
+  if (half == 0 && q < cnt) {
+#pragma unroll
+    for (int j = 0; j < LCAP; ++j) {
+      if ((u32)j < l) {
+        const u64 o = (u64)(off + q) * l + j;
+        knn_pos[o] = best[j] == KEY_INF ? (unsigned short)0xFFFF : (unsigned short)(best[j] & 0xFFFFull);
+        knn_d[o] = (i32)(best[j] >> 32);
+      }
+    }
+  }
+}
+
+// One leaf: its candidate pairs (every point with its k = min(l, cnt-1) nearest) sorted by
+// (distance, smaller position, larger position) in LDS, then Kruskal's scan with the degree
+// bound s.  A pair whose ends are connected, or one of whose ends is full, stays so: the wave
+// tests 64 pairs at once against the state so far and walks through the survivors in order.
+// Accepted pairs go, as two arcs (point << 32 | neighbour), to arcs[2 * (off - leaf) ...] (a leaf
+// of cnt points accepts at most cnt - 1; unused entries keep what they hold).
+__global__ __launch_bounds__(256) void hc_mst_kernel(const u64* keys, const u32* leaf_off, u32 l, u32 s,
+                                                     const unsigned short* knn_pos, const i32* knn_d, u32 pmax,
+                                                     u64* arcs) {
+  extern __shared__ __align__(16) unsigned char hc_smem[];
+  u64* ek = reinterpret_cast<u64*>(hc_smem);
+  volatile unsigned short* parent = reinterpret_cast<volatile unsigned short*>(hc_smem + (size_t)pmax * 8);
+  volatile unsigned char* deg = reinterpret_cast<volatile unsigned char*>(hc_smem + (size_t)pmax * 8 + 2 * HC_MAX_LS);
+  const u32 leaf = blockIdx.x;
+  const u32 off = leaf_off[leaf];
+  const u32 cnt = leaf_off[leaf + 1] - off;
+  if (cnt < 2) return;
+  const u32 tid = threadIdx.x;
+  const u32 k = l < cnt - 1u ? l : cnt - 1u;
+  const u32 E = cnt * k;
+  u32 P = 64;
+  while (P < E) P <<= 1;  // at most pmax
+  for (u32 e = tid; e < P; e += 256) {
+    u64 key = KEY_INF;
+    if (e < E) {
+      const u32 a = e / k, j = e - a * k;
+      const u64 o = (u64)(off + a) * l + j;
+      const u32 b = knn_pos[o];
+      const u32 u = a < b ? a : b, v = a < b ? b : a;
+      key = ((u64)(u32)knn_d[o] << 32) | (u << 16) | v;
+    }
+    ek[e] = key;
+  }
+  for (u32 i = tid; i < cnt; i += 256) {
+    parent[i] = (unsigned short)i;
+    deg[i] = 0;
+  }
+  __syncthreads();
+  for (u32 k2 = 2; k2 <= P; k2 <<= 1) {
+    for (u32 j = k2 >> 1; j > 0; j >>= 1) {
+      for (u32 i = tid; i < P; i += 256) {
+        const u32 x = i ^ j;
+        if (x > i) {
+          const u64 a = ek[i], b = ek[x];
+          const bool asc = (i & k2) == 0;
+          if ((a > b) == asc) {
+            ek[i] = b;
+            ek[x] = a;
+          }
+        }
+      }
+      __syncthreads();
+    }
+  }
+  if (tid >= 64) return;  // the scan is one wavefront's work
+  const int lane = (int)tid;
+  u64* out = arcs + 2ull * (off - leaf);
+  u32 accepted = 0;
+  for (u32 c = 0; c < E && accepted < cnt - 1u; c += 64) {
+    const u32 e = c + (u32)lane;
+    const u64 key = e < E ? ek[e] : KEY_INF;
+    const bool dup = e > 0 && e < E && key == ek[e - 1];  // a pair chosen from both ends appears twice
+    const u32 u = (u32)(key >> 16) & 0xFFFFu, v = (u32)key & 0xFFFFu;
+    bool ok = key != KEY_INF && !dup;
+    if (ok) ok = deg[u] < s && deg[v] < s;
+    if (ok) {
+      u32 ru = u, rv = v;
+      while (parent[ru] != ru) ru = parent[ru];
+      while (parent[rv] != rv) rv = parent[rv];
+      ok = ru != rv;
+    }
+    u64 mask = ballot(ok);
+    while (mask != 0ull) {
+      const int j = __builtin_ctzll(mask);
+      mask &= mask - 1ull;
+      // every lane repeats the same step on the same LDS words
+      const u32 uu = readlane_u32(u, j), vv = readlane_u32(v, j);
+      if (deg[uu] < s && deg[vv] < s) {
+        u32 ru = uu, rv = vv;
+        while (parent[ru] != ru) ru = parent[ru];
+        while (parent[rv] != rv) rv = parent[rv];
+        if (ru != rv) {
+          __builtin_amdgcn_wave_barrier();  // every lane has read before any lane writes
+          parent[ru] = (unsigned short)rv;
+          const unsigned char du = deg[uu], dv = deg[vv];
+          __builtin_amdgcn_wave_barrier();
+          deg[uu] = du + 1;
+          deg[vv] = dv + 1;
+          if (lane == 0) {
+            const u64 gu = keys[off + uu] & 0xFFFFFFFFull, gv = keys[off + vv] & 0xFFFFFFFFull;
+            out[2 * accepted] = (gu << 32) | gv;
+            out[2 * accepted + 1] = (gv << 32) | gu;
+          }
+          ++accepted;
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+}
+
+// ---- repeated keys out of a sorted array --------------------------------------------------
+constexpr u32 UQ_TILE = 2048;  // keys per workgroup of 256 threads
+
+__device__ __forceinline__ bool uq_keep(const u64* keys, u64 i, u64 n) {
+  return i < n && keys[i] != KEY_INF && (i == 0 || keys[i] != keys[i - 1]);
+}
+
+__global__ __launch_bounds__(256) void uq_count_kernel(const u64* keys, u64 n, u32* counts) {
+  __shared__ u32 total;
+  if (threadIdx.x == 0) total = 0;
+  __syncthreads();
+  const u64 base = (u64)blockIdx.x * UQ_TILE + threadIdx.x * 8u;
+  u32 c = 0;
+  for (u32 k = 0; k < 8; ++k) c += uq_keep(keys, base + k, n) ? 1u : 0u;
+  atomicAdd(&total, c);
+  __syncthreads();
+  if (threadIdx.x == 0) counts[blockIdx.x] = total;
+}
+
+// counts[0..m) -> exclusive prefix sums in place, the grand total in counts[m]
+__global__ __launch_bounds__(1024) void uq_scan_kernel(u32* counts, u32 m) {
+  __shared__ unsigned long long part[1024];
+  const u32 t = threadIdx.x;
+  const u32 per = (m + 1023u) / 1024u;
+  const u32 lo = t * per < m ? t * per : m, hi = lo + per < m ? lo + per : m;
+  unsigned long long s = 0;
+  for (u32 i = lo; i < hi; ++i) s += counts[i];
+  part[t] = s;
+  __syncthreads();
+  for (u32 o = 1; o < 1024; o <<= 1) {
+    const unsigned long long v = t >= o ? part[t - o] : 0ull;
+    __syncthreads();
+    part[t] += v;
+    __syncthreads();
+  }
+  unsigned long long run = t ? part[t - 1] : 0ull;
+  for (u32 i = lo; i < hi; ++i) {
+    const u32 v = counts[i];
+    counts[i] = (u32)run;
+    run += v;
+  }
+  if (t == 1023) counts[m] = (u32)part[1023];
+}
+
+__global__ __launch_bounds__(256) void uq_scatter_kernel(const u64* keys, u64 n, const u32* offsets, u64* out) {
+  __shared__ u32 pre[256];
+  const u32 t = threadIdx.x;
+  const u64 base = (u64)blockIdx.x * UQ_TILE + t * 8u;
+  bool keep[8];
+  u32 c = 0;
+  for (u32 k = 0; k < 8; ++k) {
+    keep[k] = uq_keep(keys, base + k, n);
+    c += keep[k] ? 1u : 0u;
+  }
+  pre[t] = c;
+  __syncthreads();
+  for (u32 o = 1; o < 256; o <<= 1) {
+    const u32 v = t >= o ? pre[t - o] : 0u;
+    __syncthreads();
+    pre[t] += v;
+    __syncthreads();
+  }
+  u64 w = (u64)offsets[blockIdx.x] + (t ? pre[t - 1] : 0u);
+  for (u32 k = 0; k < 8; ++k)
+    if (keep[k]) out[w++] = keys[base + k];
+}
+
+struct Seg {
+  u64 off, cnt, node;
+  u32 depth;
+};
+
+// Everything one build needs on the device.
+struct HcCtx {
+  u64 n = 0;
+  u32 row_bytes = 0, lv_stride = 0;
+  bool is_signed = false;
+  const unsigned char* pts = nullptr;
+  u32 Ls = 0, s = 0, l = 0;
+  u64 seed = 0;
+  DevBuf keys[3], hist, segbuf, first, leafvec, leafnorm, leaf_off, knn_pos, knn_d;
+  u64 hist_entries = 0;
+  std::vector<u32> h_first;
+  int alloc() {
+    for (auto& k : keys) HIP_TRY(k.alloc(n * 8));
+    hist_entries = radix_hist_entries(n);
+    HIP_TRY(hist.alloc(hist_entries * 4));
+    HIP_TRY(segbuf.alloc((4 * n + 8) * 4));  // off (nseg+1), pos1, pos2, base: nseg <= n
+    HIP_TRY(first.alloc((n + 2) * 4));
+    HIP_TRY(leafvec.alloc(n * lv_stride));
+    HIP_TRY(leafnorm.alloc((n + 64) * 4));
+    HIP_TRY(hipMemset(leafnorm.p, 0, (n + 64) * 4));
+    HIP_TRY(leaf_off.alloc((n + 1) * 4));
+    HIP_TRY(knn_pos.alloc(n * l * 2));
+    HIP_TRY(knn_d.alloc(n * l * 4));
+    return ANN_OK;
+  }
+};
+
+// The cluster tree `tree`: on return keys[0] holds the point ids in leaf order (low words) and
+// `leaves` the leaves' position ranges, left to right.
+int hc_partition(HcCtx& X, u32 tree, std::vector<Seg>& leaves, hipStream_t st) {
+  const u64 n = X.n;
+  const u32 grid_n = (u32)((n + 255) / 256), grid_8n = (u32)((n * 8 + 255) / 256);
+  hipLaunchKernelGGL(hc_iota_kernel, dim3(grid_n), dim3(256), 0, st, X.keys[0].as<u64>(), n);
+  HIP_TRY(hipGetLastError());
+  std::vector<Seg> segs{Seg{0, n, 1, 0}};
+  std::vector<u32> up;
+  for (;;) {
+    bool any = false;
+    for (const Seg& sg : segs) any = any || sg.cnt > X.Ls;
+    if (!any) break;
+    const u32 nseg = (u32)segs.size();
+    // off[nseg+1] | pos1[nseg] | pos2[nseg] | base[nseg]
+    up.assign((size_t)4 * nseg + 1, HC_NONE);
+    u32* off = up.data();
+    u32* pos1 = off + nseg + 1;
+    u32* pos2 = pos1 + nseg;
+    u32* base = pos2 + nseg;
+    u32 nnew = 0;
+    for (u32 j = 0; j < nseg; ++j) {
+      const Seg& sg = segs[j];
+      off[j] = (u32)sg.off;
+      base[j] = nnew;
+      if (sg.cnt > X.Ls && sg.depth < HC_MAX_DEPTH) {
+        const u64 k = 2 * (((u64)tree << 40) + sg.node);
+        const u64 i1 = mulhi64(stream_output(X.seed, k), sg.cnt);
+        u64 i2 = mulhi64(stream_output(X.seed, k + 1), sg.cnt - 1);
+        if (i2 >= i1) ++i2;
+        pos1[j] = (u32)(sg.off + i1);
+        pos2[j] = (u32)(sg.off + i2);
+        nnew += 2;
+      } else {
+        nnew += 1;
+      }
+    }
+    off[nseg] = (u32)n;
+    u32* d_off = X.segbuf.as<u32>();
+    HIP_TRY(hipMemcpyAsync(d_off, up.data(), up.size() * 4, hipMemcpyHostToDevice, st));
+    if (X.is_signed)
+      hipLaunchKernelGGL(hc_side_kernel<true>, dim3(grid_8n), dim3(256), 0, st, X.pts, X.row_bytes, X.keys[0].as<u64>(), n,
+                         d_off, nseg, d_off + nseg + 1, d_off + 2 * nseg + 1, d_off + 3 * nseg + 1, X.keys[1].as<u64>());
+    else
+      hipLaunchKernelGGL(hc_side_kernel<false>, dim3(grid_8n), dim3(256), 0, st, X.pts, X.row_bytes, X.keys[0].as<u64>(), n,
+                         d_off, nseg, d_off + nseg + 1, d_off + 2 * nseg + 1, d_off + 3 * nseg + 1, X.keys[1].as<u64>());
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(radix_sort_edges(X.keys[1].as<u64>(), X.keys[2].as<u64>(), X.hist.as<u32>(), X.hist_entries, n,
+                             bits_to_hold(nnew), st));
+    HIP_TRY(hipMemsetAsync(X.first.p, 0xFF, ((size_t)nnew + 1) * 4, st));
+    hipLaunchKernelGGL(hc_bounds_kernel, dim3(grid_n), dim3(256), 0, st, X.keys[1].as<u64>(), n, X.first.as<u32>());
+    HIP_TRY(hipGetLastError());
+    X.h_first.resize(nnew);
+    HIP_TRY(hipMemcpyAsync(X.h_first.data(), X.first.p, (size_t)nnew * 4, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    std::vector<Seg> next;
+    next.reserve(nnew);
+    for (u32 j = 0; j < nseg; ++j) {
+      const Seg& sg = segs[j];
+      if (sg.cnt <= X.Ls) {
+        next.push_back(sg);
+        continue;
+      }
+      u64 cl;
+      if (pos1[j] == HC_NONE || X.h_first[base[j]] == HC_NONE || X.h_first[base[j] + 1] == HC_NONE)
+        cl = (sg.cnt + 1) / 2;  // too deep, or nothing separated: the order is cut in the middle
+      else
+        cl = X.h_first[base[j] + 1] - sg.off;
+      next.push_back(Seg{sg.off, cl, 2 * sg.node, sg.depth + 1});
+      next.push_back(Seg{sg.off + cl, sg.cnt - cl, 2 * sg.node + 1, sg.depth + 1});
+    }
+    segs.swap(next);
+    std::swap(X.keys[0], X.keys[1]);
+  }
+  leaves.swap(segs);
+  return ANN_OK;
+}
+
+// Leaves -> nearest neighbours -> degree-bounded trees; the accepted pairs of leaf j land, as
+// arcs, at arcs[2 * (off_j - j) ...].
+int hc_leaves(HcCtx& X, const std::vector<Seg>& leaves, u64* arcs, hipStream_t st) {
+  const u64 n = X.n;
+  const u32 nleaves = (u32)leaves.size();
+  std::vector<u32> lo(nleaves + 1);
+  u64 maxc = 0;
+  for (u32 j = 0; j < nleaves; ++j) {
+    lo[j] = (u32)leaves[j].off;
+    maxc = std::max(maxc, leaves[j].cnt);
+  }
+  lo[nleaves] = (u32)n;
+  HIP_TRY(hipMemcpyAsync(X.leaf_off.p, lo.data(), lo.size() * 4, hipMemcpyHostToDevice, st));
+  const u32 grid_8n = (u32)((n * 8 + 255) / 256);
+  if (X.is_signed)
+    hipLaunchKernelGGL(hc_gather_kernel<true>, dim3(grid_8n), dim3(256), 0, st, X.pts, X.row_bytes, X.keys[0].as<u64>(), n,
+                       X.lv_stride, X.leafvec.as<unsigned char>(), X.leafnorm.as<i32>());
+  else
+    hipLaunchKernelGGL(hc_gather_kernel<false>, dim3(grid_8n), dim3(256), 0, st, X.pts, X.row_bytes, X.keys[0].as<u64>(), n,
+                       X.lv_stride, X.leafvec.as<unsigned char>(), X.leafnorm.as<i32>());
+  HIP_TRY(hipGetLastError());
+  const dim3 kgrid(nleaves, (u32)((maxc + 31) / 32));
+  if (X.l <= 8)
+    hipLaunchKernelGGL(hc_knn_kernel<8>, kgrid, dim3(64), 0, st, X.leafvec.as<unsigned char>(), X.leafnorm.as<i32>(),
+                       X.lv_stride, X.leaf_off.as<u32>(), X.l, X.knn_pos.as<unsigned short>(), X.knn_d.as<i32>());
+  else
+    hipLaunchKernelGGL(hc_knn_kernel<16>, kgrid, dim3(64), 0, st, X.leafvec.as<unsigned char>(), X.leafnorm.as<i32>(),
+                       X.lv_stride, X.leaf_off.as<u32>(), X.l, X.knn_pos.as<unsigned short>(), X.knn_d.as<i32>());
+  HIP_TRY(hipGetLastError());
+  const u64 kk = X.l < maxc - 1 ? X.l : (maxc > 1 ? maxc - 1 : 1);
+  u32 pmax = 64;
+  while (pmax < maxc * kk) pmax <<= 1;
+  const u32 lds = pmax * 8 + 2 * HC_MAX_LS + HC_MAX_LS;
+  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(hc_mst_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)lds));
+  hipLaunchKernelGGL(hc_mst_kernel, dim3(nleaves), dim3(256), lds, st, X.keys[0].as<u64>(), X.leaf_off.as<u32>(), X.l, X.s,
+                     X.knn_pos.as<unsigned short>(), X.knn_d.as<i32>(), pmax, arcs);
+  HIP_TRY(hipGetLastError());
+  return ANN_OK;
+}
+
+int hc_check(uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric, uint32_t Ls, uint32_t s, uint32_t l) {
+  if (dtype != ANN_U8 && dtype != ANN_I8)
+    return fail(ANN_EINVAL, "the clustering-based builder takes ANN_U8 and ANN_I8 points only");
+  if (metric != ANN_L2SQ) return fail(ANN_EINVAL, "the clustering-based builder takes ANN_L2SQ only");
+  if (n < 1 || n >= (1ull << 31)) return fail(ANN_EINVAL, "n must be in [1, 2^31)");
+  if (d < 1 || d > 128) return fail(ANN_EINVAL, "the clustering-based builder takes rows of at most 128 bytes");
+  if (Ls < 2 || Ls > HC_MAX_LS) return fail(ANN_EINVAL, "leaf size must be in [2, 1024]");
+  if (l < 1 || l > HC_MAX_L) return fail(ANN_EINVAL, "l must be in [1, 16]");
+  if ((u64)Ls * l > HC_MAX_PAIRS) return fail(ANN_EINVAL, "leaf size times l must be at most 16384");
+  if (s < 1 || s > 255) return fail(ANN_EINVAL, "s must be in [1, 255]");
+  return ANN_OK;
+}
+
+int hc_setup(HcCtx& X, const ann_graph* g, const void* pts, uint32_t Ls, uint32_t s, uint32_t l, uint64_t seed) {
+  X.n = g->n;
+  X.row_bytes = (u32)g->cfg.row_bytes;
+  X.lv_stride = (X.row_bytes + 31u) / 32u * 32u;
+  X.is_signed = g->dtype == ANN_I8;
+  X.pts = static_cast<const unsigned char*>(pts);
+  X.Ls = Ls;
+  X.s = s;
+  X.l = l;
+  X.seed = seed;
+  return X.alloc();
+}
+
+}  // namespace
+
+extern "C" {
+
+int ann_hcnng_tree_edges(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, uint32_t Ls, uint32_t s,
+                         uint32_t l, uint64_t seed, uint32_t tree, void* stream, uint32_t* perm_host,
+                         uint64_t* leaf_off_host, uint64_t* nleaves, uint32_t* pairs_host, uint64_t* npairs) {
+  if (!points_dev || !perm_host || !leaf_off_host || !nleaves || !pairs_host || !npairs)
+    return fail(ANN_EINVAL, "null argument");
+  int rc = hc_check(n, d, dtype, ANN_L2SQ, Ls, s, l);
+  if (rc) return rc;
+  if (tree >= (1u << 20)) return fail(ANN_EINVAL, "tree index must be below 2^20");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  ann_graph* g = nullptr;
+  rc = new_graph(n, d, dtype, ANN_L2SQ, 1, &g);
+  if (rc) return rc;
+  struct Guard {
+    ann_graph* g;
+    ~Guard() { ann_graph_free(g); }
+  } guard{g};
+  const void* pts = nullptr;
+  rc = resolve_points(g, points_dev, st, &pts);
+  if (rc) return rc;
+  HcCtx X;
+  rc = hc_setup(X, g, pts, Ls, s, l, seed);
+  if (rc) return rc;
+  DevBuf arcs;
+  HIP_TRY(arcs.alloc(2 * n * 8));
+  HIP_TRY(hipMemsetAsync(arcs.p, 0xFF, 2 * n * 8, st));
+  std::vector<Seg> leaves;
+  rc = hc_partition(X, tree, leaves, st);
+  if (rc) return rc;
+  rc = hc_leaves(X, leaves, arcs.as<u64>(), st);
+  if (rc) return rc;
+  std::vector<u64> hk(n), ha(2 * n);
+  HIP_TRY(hipMemcpyAsync(hk.data(), X.keys[0].p, n * 8, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipMemcpyAsync(ha.data(), arcs.p, 2 * n * 8, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  for (u64 i = 0; i < n; ++i) perm_host[i] = (u32)hk[i];
+  for (size_t j = 0; j < leaves.size(); ++j) leaf_off_host[j] = leaves[j].off;
+  leaf_off_host[leaves.size()] = n;
+  *nleaves = leaves.size();
+  u64 np = 0;
+  for (u64 i = 0; i + 1 < 2 * n; i += 2)
+    if (ha[i] != ~0ull) {
+      pairs_host[2 * np] = (u32)(ha[i] >> 32);
+      pairs_host[2 * np + 1] = (u32)ha[i];
+      ++np;
+    }
+  *npairs = np;
+  return ANN_OK;
+}
+
+int ann_hcnng_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric, uint32_t T,
+                    uint32_t Ls, uint32_t s, uint32_t l, uint32_t R, float alpha, uint64_t seed, void* stream,
+                    ann_graph** out) {
+  if (out) *out = nullptr;
+  if (!points_dev || !out) return fail(ANN_EINVAL, "null argument");
+  int rc = hc_check(n, d, dtype, metric, Ls, s, l);
+  if (rc) return rc;
+  if (T < 1 || T >= (1u << 20)) return fail(ANN_EINVAL, "the number of trees must be in [1, 2^20)");
+  if ((u64)T * 2 * n >= (1ull << 32)) return fail(ANN_EINVAL, "trees times points must stay below 2^31");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  ann_graph* g = nullptr;
+  rc = new_graph(n, d, dtype, metric, R, &g);
+  if (rc) return rc;
+  struct Guard {
+    ann_graph* g;
+    ~Guard() {
+      if (g) ann_graph_free(g);
+    }
+  } guard{g};
+  rc = check_insert_params(g, 1, alpha);
+  if (rc) return rc;
+  HIP_TRY(hipMemsetAsync(g->rows, 0xFF, (size_t)n * R * sizeof(u32), st));
+  const void* pts = nullptr;
+  rc = resolve_points(g, points_dev, st, &pts);
+  if (rc) return rc;
+  {
+    u32 sv = 0;
+    HIP_TRY(start_vertex_device(points_dev, n, d, dtype, st, &sv));
+    g->start = sv;
+  }
+  HcCtx X;
+  rc = hc_setup(X, g, pts, Ls, s, l, seed);
+  if (rc) return rc;
+  const u64 total = (u64)T * 2 * n;
+  DevBuf arcs, arcs_tmp, big_hist, uq_counts, lists, small, arena;
+  HIP_TRY(arcs.alloc(total * 8));
+  HIP_TRY(arcs_tmp.alloc(total * 8));
+  HIP_TRY(hipMemsetAsync(arcs.p, 0xFF, total * 8, st));
+  std::vector<Seg> leaves;
+  for (u32 t = 0; t < T; ++t) {
+    rc = hc_partition(X, t, leaves, st);
+    if (rc) return rc;
+    rc = hc_leaves(X, leaves, arcs.as<u64>() + (u64)t * 2 * n, st);
+    if (rc) return rc;
+    g->stats.rounds += 1;
+  }
+  // all arcs by (point, neighbour): the neighbour bits first, then, stably, the point bits; the
+  // unused entries (all ones) end up behind every point
+  const u64 he = radix_hist_entries(total);
+  HIP_TRY(big_hist.alloc(he * 4));
+  const u32 idb = bits_to_hold(n);
+  HIP_TRY(radix_sort_edges(arcs.as<u64>(), arcs_tmp.as<u64>(), big_hist.as<u32>(), he, total, idb, st, 0));
+  HIP_TRY(radix_sort_edges(arcs.as<u64>(), arcs_tmp.as<u64>(), big_hist.as<u32>(), he, total, idb, st, 32));
+  // each (point, neighbour) once
+  const u32 ntiles = (u32)((total + UQ_TILE - 1) / UQ_TILE);
+  HIP_TRY(uq_counts.alloc(((size_t)ntiles + 1) * 4));
+  hipLaunchKernelGGL(uq_count_kernel, dim3(ntiles), dim3(256), 0, st, arcs.as<u64>(), total, uq_counts.as<u32>());
+  hipLaunchKernelGGL(uq_scan_kernel, dim3(1), dim3(1024), 0, st, uq_counts.as<u32>(), ntiles);
+  hipLaunchKernelGGL(uq_scatter_kernel, dim3(ntiles), dim3(256), 0, st, arcs.as<u64>(), total, uq_counts.as<u32>(),
+                     arcs_tmp.as<u64>());
+  HIP_TRY(hipGetLastError());
+  u32 nuniq = 0;
+  HIP_TRY(hipMemcpyAsync(&nuniq, uq_counts.as<u32>() + ntiles, 4, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  // prune(p, neighbours, R) for every point: the re-prune kernel of BatchInsert on empty rows
+  HIP_TRY(hipMemsetAsync(g->meta, 0, (size_t)n * sizeof(u32), st));
+  HIP_TRY(lists.alloc(3 * n * sizeof(MergeItem)));
+  HIP_TRY(small.alloc(64));
+  HIP_TRY(hipMemsetAsync(small.p, 0, 64, st));
+  const u64 longest = (u64)s * T;  // neighbours of one point, at most
+  const u64 arena_cap = longest > MERGE_SPILL_MIN ? (u64)nuniq : 16;
+  HIP_TRY(arena.alloc(arena_cap * 8));
+  MergeArgs ma{};
+  ma.points = static_cast<const char*>(pts);
+  ma.graph = g->rows;
+  ma.meta = g->meta;
+  ma.R = R;
+  ma.keys = arcs_tmp.as<u64>();
+  ma.nkeys = nuniq;
+  u32* sm = small.as<u32>();
+  ma.list_count = sm + 8;
+  for (int c = 0; c < 3; ++c) ma.list_items[c] = lists.as<MergeItem>() + (u64)c * n;
+  ma.fast_amax = fast_path_amax(g->cfg);
+  ma.gram_ok = gram_path_ok(g->cfg) ? 1u : 0u;
+  ma.gram_tmax = gram_path_tmax();
+  ma.stage_bytes = prune_stage_bytes(R, g->cfg);
+  ma.use_mfma = mfma_prune_ok(R, g->cfg) ? 1u : 0u;
+  ma.arena = arena.as<u64>();
+  ma.arena_cap = arena_cap;
+  ma.arena_top = reinterpret_cast<unsigned long long*>(sm + 4);
+  ma.error_flag = sm + 2;
+  ma.a16 = llround((double)alpha * 65536.0);
+  ma.af = alpha;
+  ma.counters = nullptr;
+  ma.force_prune = 1;
+  g->clean_alpha = alpha;
+  HIP_TRY(launch_plan(ma, st));
+  const u64 want = nuniq < 8192 ? nuniq : 8192;
+  HIP_TRY(launch_merge(g->cfg, ma, (u32)(want ? want : 1), st, st, st));
+  u32 flags[4] = {0, 0, 0, 0};
+  HIP_TRY(hipMemcpyAsync(flags, small.p, 16, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  if (flags[2] != 0) return fail(ANN_EINTERNAL, "merge spill arena exhausted");
+  g->stats.edges = nuniq;
+  guard.g = nullptr;
+  *out = g;
+  return ANN_OK;
+}
+
+}  // extern "C"

@@ -65,7 +65,7 @@ __global__ __launch_bounds__(256) void plan_kernel(MergeArgs a) {
       cnt = (u32)(hi - i);
       m = a.meta[b];
       const u32 deg = meta_deg(m), clean = meta_clean(m);
-      if (deg + cnt <= a.R) {
+      if (!a.force_prune && deg + cnt <= a.R) {
         u32* row = a.graph + (u64)b * a.R;
         for (u32 j = 0; j < cnt; ++j) row[deg + j] = (u32)(a.keys[i + j] & 0xFFFFFFFFull);
         a.meta[b] = make_meta(deg + cnt, clean);
@@ -75,7 +75,9 @@ __global__ __launch_bounds__(256) void plan_kernel(MergeArgs a) {
         }
       } else {
         const u32 fresh = deg - clean + cnt;
-        if (clean <= 64 && fresh <= a.fast_amax)
+        if (a.force_prune)
+          kind = 2;  // short rows that the other two paths were not written for (they never append)
+        else if (clean <= 64 && fresh <= a.fast_amax)
           kind = 0;
         else if (a.gram_ok && deg + cnt <= a.gram_tmax)
           kind = 1;
@@ -907,7 +909,7 @@ static hipError_t launch_merge_t(const MergeArgs& a, const VecTable& T, u32 grid
   // for LDS that the other two kernels' workgroups hold; a small grid serves its short list
   const u32 lds = a.use_mfma ? ((a.R * 4u + 15u) & ~15u) + mfma_lds_bytes(a.R, T.row_bytes)
                             : ((a.R * 8u + 15u) & ~15u) + 8u * stage_stride(T.row_bytes) + 32u + a.stage_bytes;
-  const u32 grid_generic = grid < 1024u ? grid : 1024u;
+  const u32 grid_generic = (grid < 1024u || a.force_prune) ? grid : 1024u;
   hipLaunchKernelGGL((merge_generic_kernel<KIND, VEC, NCH>), dim3(grid_generic), dim3(64), lds, s_generic, a, T);
   // the caller's stream takes the kernel that usually ends last, so that its waits for the other
   // two streams are already satisfied when it reaches them

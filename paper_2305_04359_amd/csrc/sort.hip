@@ -1,5 +1,6 @@
 // Grouping of reversed edges by destination: a stable least-significant-digit radix sort of
-// 64-bit keys (destination << 32 | source) on the destination bits only.  It takes the place of
+// 64-bit keys (destination << 32 | source) on the destination bits only (by default; a caller
+// may name another run of key bits).  It takes the place of
 // the semisort in BatchInsert (Alg. 3): equal destinations become consecutive, and, the sort
 // being stable, the sources of one destination stay in the order they were emitted (batch order).
 //
@@ -134,10 +135,10 @@ __global__ __launch_bounds__(64) void rs_scatter_kernel(const u64* keys, u64* ou
 }
 
 hipError_t radix_sort_edges(u64* keys, u64* tmp, u32* hist, u64 hist_entries, u64 count, u32 key_bits,
-                            hipStream_t s) {
+                            hipStream_t s, u32 first_bit) {
   if (count < 2 || key_bits == 0) return hipSuccess;
   if ((u64)RS_RADIX * (rs_tiles(count) + 1) > hist_entries) return hipErrorInvalidValue;  // histogram too small
-  if (key_bits > 32) key_bits = 32;
+  if (first_bit + key_bits > 64) key_bits = 64 - first_bit;  // (callers sort within the key)
   const u64 tile_keys = rs_tile_keys(count);
   const u32 tiles = (u32)rs_tiles(count);
   const u32 npass = (key_bits + RS_DIGIT_BITS - 1) / RS_DIGIT_BITS;
@@ -147,7 +148,7 @@ hipError_t radix_sort_edges(u64* keys, u64* tmp, u32* hist, u64 hist_entries, u6
   u32 done = 0;
   for (u32 p = 0; p < npass; ++p) {
     const u32 nb = key_bits - done < per ? key_bits - done : per;
-    const u32 shift = 32 + done;
+    const u32 shift = first_bit + done;
     const u32 mask = (1u << nb) - 1u;
     hipLaunchKernelGGL(rs_hist_kernel, dim3(tiles), dim3(64), 0, s, src, count, tile_keys, tiles, shift, mask, hist);
     u32* digit_total = hist + (u64)RS_RADIX * tiles;

@@ -929,3 +929,88 @@ def test_hnsw_from_host_round_trip(env, c1):
         A.ann_hnsw_from_host(pts, 5, oh.level, oh.entry, bad)
     with pytest.raises(A.AnnError):
         A.ann_hnsw_from_host(pts, 5, oh.level, int(np.flatnonzero(oh.level == 0)[0]), oh.layers)
+
+
+# ------------------------------------------------------------------------------------------
+# clustering-based builder (Sec. 3.2 and 4.3, ParlayHCNNG)
+# ------------------------------------------------------------------------------------------
+def _oracle_tree_pairs(O, ds, Ls, s, l, seed, tree):
+    perm, off = O.hcnng_tree(ds, Ls, seed, tree)
+    pairs = [O.hcnng_leaf(ds, perm[off[j]:off[j + 1]], s, l) for j in range(len(off) - 1)]
+    return perm, off, np.concatenate(pairs) if pairs else np.zeros((0, 2), np.uint32)
+
+
+@pytest.mark.parametrize("n,Ls,s,l", [(3000, 100, 3, 10), (2000, 37, 2, 4), (1500, 1024, 3, 10), (700, 64, 1, 16),
+                                      (900, 2, 3, 10), (1200, 150, 200, 16)])
+def test_hcnng_one_tree_bit_exact(env, c1, n, Ls, s, l):
+    """Cluster tree, leaves and every leaf's accepted pairs, in acceptance order."""
+    torch, A, O = env
+    pts_h = c1.points[:n]
+    ds = O.Dataset(pts_h, 0)
+    pts = dev(torch, pts_h)
+    for tree in (0, 3):
+        say(f"cluster tree {tree}: n={n} Ls={Ls} s={s} l={l}")
+        perm, off, pairs = A.ann_hcnng_tree_edges(pts, Ls, s, l, 5, tree)
+        operm, ooff, opairs = _oracle_tree_pairs(O, ds, Ls, s, l, 5, tree)
+        assert (off == ooff).all() and (perm == operm).all()
+        assert pairs.shape == opairs.shape and (pairs == opairs).all()
+
+
+def test_hcnng_equal_points_and_tiny_inputs(env):
+    torch, A, O = env
+    same = np.full((300, 16), 7, np.uint8)
+    same[100:] = 9
+    perm, off, pairs = A.ann_hcnng_tree_edges(dev(torch, same), 16, 3, 10, 1, 0)
+    operm, ooff, opairs = _oracle_tree_pairs(O, O.Dataset(same, 0), 16, 3, 10, 1, 0)
+    assert (off == ooff).all() and (perm == operm).all() and (pairs == opairs).all()
+    for n in (1, 2, 3):
+        pts_h = (np.arange(n * 8, dtype=np.uint8).reshape(n, 8) * 7) % 251
+        perm, off, pairs = A.ann_hcnng_tree_edges(dev(torch, pts_h), 2, 3, 10, 1, 0)
+        operm, ooff, opairs = _oracle_tree_pairs(O, O.Dataset(pts_h, 0), 2, 3, 10, 1, 0)
+        assert (off == ooff).all() and (perm == operm).all() and (pairs == opairs).all()
+
+
+@pytest.mark.parametrize("n,T,Ls,s,l,R,alpha", [(3000, 6, 120, 3, 10, 20, 1.2), (2500, 12, 60, 3, 10, 8, 1.0),
+                                                (2000, 3, 500, 5, 16, 64, 1.2), (1500, 40, 30, 3, 5, 32, 1.2)])
+def test_hcnng_build_bit_exact(env, c1, n, T, Ls, s, l, R, alpha):
+    torch, A, O = env
+    pts_h = c1.points[:n]
+    ds = O.Dataset(pts_h, 0)
+    say(f"clustering-based build n={n} T={T} Ls={Ls} s={s} l={l} R={R}")
+    og = O.hcnng_build(ds, T, Ls, s, l, R, alpha, seed=7, threads=0)
+    pts = dev(torch, pts_h)
+    g = A.ann_hcnng_build(pts, T, Ls, s, l, R, alpha, seed=7)
+    rows = g.neighbors()
+    bad = np.nonzero((rows != og).any(1))[0]
+    assert len(bad) == 0, f"rows differ: {bad[:10]}"
+    assert g.info().start == O.start_vertex(ds)
+    # the flat graph's search serves it
+    ids, dists = A.ann_search(g, pts, dev(torch, c1.queries), 10, 40)
+    oi, od = O.search_batch(ds, og, O.start_vertex(ds), c1.queries, 10, 40, threads=0)
+    assert (ids.cpu().numpy().view(np.uint32) == oi).all() and (dists.cpu().numpy() == od).all()
+    # deterministic
+    assert (A.ann_hcnng_build(pts, T, Ls, s, l, R, alpha, seed=7).neighbors() == rows).all()
+
+
+def test_hcnng_int8_padded_rows(env):
+    torch, A, O = env
+    w = W.c3(n=4000, nq=200)
+    ds = O.Dataset(w.points, 0)
+    og = O.hcnng_build(ds, 8, 100, 3, 10, 24, 1.2, seed=3, threads=0)
+    g = A.ann_hcnng_build(dev(torch, w.points), 8, 100, 3, 10, 24, 1.2, seed=3)
+    assert (g.neighbors() == og).all()
+
+
+def test_hcnng_bad_arguments(env, c1):
+    torch, A, O = env
+    pts = dev(torch, c1.points[:500])
+    ok = dict(T=4, Ls=100, s=3, l=10, R=16, alpha=1.2)
+    for bad in (dict(T=0), dict(Ls=1), dict(Ls=2000), dict(s=0), dict(s=300), dict(l=0), dict(l=17), dict(R=0),
+                dict(alpha=0.0)):
+        with pytest.raises(A.AnnError):
+            say(f"  refused: {bad}")
+            A.ann_hcnng_build(pts, **{**ok, **bad})
+    with pytest.raises(A.AnnError):  # float data is not taken
+        A.ann_hcnng_build(dev(torch, np.zeros((100, 8), np.float32)), **ok)
+    with pytest.raises(A.AnnError):  # rows above 128 bytes neither
+        A.ann_hcnng_build(dev(torch, np.zeros((100, 256), np.uint8)), **ok)
