@@ -5,9 +5,11 @@
 // the children in place); the leaves' vectors are gathered into leaf order as int8; one wavefront
 // per 32 points of a leaf finds their l nearest neighbours inside the leaf on the matrix cores
 // (32 x 32 inner products per instruction group, every lane keeping the best of the candidates it
-// sees for its own point); one workgroup per leaf sorts the leaf's candidate pairs in LDS and runs
-// Kruskal's scan with the degree bound, 64 pairs at a time (a pair that fails once fails for
-// good, so the wave tests 64 in parallel and only the survivors are taken in order).
+// sees for its own point); one workgroup per leaf sorts the leaf's candidate pairs in LDS, and
+// one wavefront per leaf runs Kruskal's scan with the degree bound, 64 pairs at a time (a pair
+// that fails once fails for good, so the wave tests 64 in parallel and only the survivors are
+// taken in order; the scan is a chain of dependent LDS reads, so thousands of leaves are scanned
+// side by side).
 // At the end the arcs of all trees are sorted by (point, neighbour), repeated ones dropped, and
 // every point's neighbours pruned with the alpha rule of Sec. 4.1 by the re-prune kernel of the
 // flat graph's BatchInsert.
@@ -41,11 +43,6 @@ u32 bits_to_hold(u64 count) {  // smallest b with 2^b - 1 >= count: indices belo
   u32 b = 1;
   while (((1ull << b) - 1ull) < count) ++b;
   return b;
-}
-
-__global__ __launch_bounds__(256) void hc_iota_kernel(u64* keys, u64 n) {
-  const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) keys[i] = i;
 }
 
 // One level of one tree.  keys_in[i] = (anything << 32) | id of the point at position i; the
@@ -235,19 +232,14 @@ __global__ __launch_bounds__(64) void hc_knn_kernel(const unsigned char* leafvec
   }
 }
 
-// One leaf: its candidate pairs (every point with its k = min(l, cnt-1) nearest) sorted by
-// (distance, smaller position, larger position) in LDS, then Kruskal's scan with the degree
-// bound s.  A pair whose ends are connected, or one of whose ends is full, stays so: the wave
-// tests 64 pairs at once against the state so far and walks through the survivors in order.
-// Accepted pairs go, as two arcs (point << 32 | neighbour), to arcs[2 * (off - leaf) ...] (a leaf
-// of cnt points accepts at most cnt - 1; unused entries keep what they hold).
-__global__ __launch_bounds__(256) void hc_mst_kernel(const u64* keys, const u32* leaf_off, u32 l, u32 s,
-                                                     const unsigned short* knn_pos, const i32* knn_d, u32 pmax,
-                                                     u64* arcs) {
+// One leaf, first half: its candidate pairs (every point with its k = min(l, cnt-1) nearest)
+// sorted by (distance, smaller position, larger position) in LDS.  The sorted pairs, as
+// (smaller << 16 | larger), replace the leaf's part of knn_d (E = cnt * k entries from
+// knn_d[off * l]; a pair chosen from both ends appears twice, side by side).
+__global__ __launch_bounds__(1024) void hc_pairs_kernel(const u32* leaf_off, u32 l, const unsigned short* knn_pos,
+                                                       i32* knn_d) {
   extern __shared__ __align__(16) unsigned char hc_smem[];
   u64* ek = reinterpret_cast<u64*>(hc_smem);
-  volatile unsigned short* parent = reinterpret_cast<volatile unsigned short*>(hc_smem + (size_t)pmax * 8);
-  volatile unsigned char* deg = reinterpret_cast<volatile unsigned char*>(hc_smem + (size_t)pmax * 8 + 2 * HC_MAX_LS);
   const u32 leaf = blockIdx.x;
   const u32 off = leaf_off[leaf];
   const u32 cnt = leaf_off[leaf + 1] - off;
@@ -256,8 +248,8 @@ __global__ __launch_bounds__(256) void hc_mst_kernel(const u64* keys, const u32*
   const u32 k = l < cnt - 1u ? l : cnt - 1u;
   const u32 E = cnt * k;
   u32 P = 64;
-  while (P < E) P <<= 1;  // at most pmax
-  for (u32 e = tid; e < P; e += 256) {
+  while (P < E) P <<= 1;  // within the launch's LDS: the host sized it for the largest leaf
+  for (u32 e = tid; e < P; e += 1024) {
     u64 key = KEY_INF;
     if (e < E) {
       const u32 a = e / k, j = e - a * k;
@@ -268,14 +260,10 @@ __global__ __launch_bounds__(256) void hc_mst_kernel(const u64* keys, const u32*
     }
     ek[e] = key;
   }
-  for (u32 i = tid; i < cnt; i += 256) {
-    parent[i] = (unsigned short)i;
-    deg[i] = 0;
-  }
   __syncthreads();
   for (u32 k2 = 2; k2 <= P; k2 <<= 1) {
     for (u32 j = k2 >> 1; j > 0; j >>= 1) {
-      for (u32 i = tid; i < P; i += 256) {
+      for (u32 i = tid; i < P; i += 1024) {
         const u32 x = i ^ j;
         if (x > i) {
           const u64 a = ek[i], b = ek[x];
@@ -289,23 +277,57 @@ __global__ __launch_bounds__(256) void hc_mst_kernel(const u64* keys, const u32*
       __syncthreads();
     }
   }
-  if (tid >= 64) return;  // the scan is one wavefront's work
-  const int lane = (int)tid;
+  u32* out = reinterpret_cast<u32*>(knn_d) + (u64)off * l;
+  for (u32 e = tid; e < E; e += 1024) out[e] = (u32)ek[e];
+}
+
+// Second half, one wavefront per leaf: Kruskal's scan over the sorted pairs with the degree bound
+// s.  A pair whose ends are connected, or one of whose ends is full, stays so: the wave tests 64
+// pairs at once against the state so far and walks through the survivors in order.  Accepted
+// pairs go, as two arcs (point << 32 | neighbour), to arcs[2 * (off - leaf) ...] (a leaf of cnt
+// points accepts at most cnt - 1; unused entries keep what they hold).
+__global__ __launch_bounds__(64) void hc_kruskal_kernel(const u64* keys, const u32* leaf_off, u32 l, u32 s,
+                                                        const i32* knn_d, u64* arcs) {
+  __shared__ unsigned short parent_lds[HC_MAX_LS];
+  __shared__ unsigned char deg_lds[HC_MAX_LS];
+  volatile unsigned short* parent = parent_lds;
+  volatile unsigned char* deg = deg_lds;
+  const u32 leaf = blockIdx.x;
+  const u32 off = leaf_off[leaf];
+  const u32 cnt = leaf_off[leaf + 1] - off;
+  if (cnt < 2) return;
+  const int lane = threadIdx.x;
+  const u32 k = l < cnt - 1u ? l : cnt - 1u;
+  const u32 E = cnt * k;
+  const u32* pairs = reinterpret_cast<const u32*>(knn_d) + (u64)off * l;
+  for (u32 i = (u32)lane; i < cnt; i += 64) {
+    parent[i] = (unsigned short)i;
+    deg[i] = 0;
+  }
+  __builtin_amdgcn_wave_barrier();
   u64* out = arcs + 2ull * (off - leaf);
   u32 accepted = 0;
+  bool flat = true;  // every point stands directly under its root
   for (u32 c = 0; c < E && accepted < cnt - 1u; c += 64) {
-    const u32 e = c + (u32)lane;
-    const u64 key = e < E ? ek[e] : KEY_INF;
-    const bool dup = e > 0 && e < E && key == ek[e - 1];  // a pair chosen from both ends appears twice
-    const u32 u = (u32)(key >> 16) & 0xFFFFu, v = (u32)key & 0xFFFFu;
-    bool ok = key != KEY_INF && !dup;
-    if (ok) ok = deg[u] < s && deg[v] < s;
-    if (ok) {
-      u32 ru = u, rv = v;
-      while (parent[ru] != ru) ru = parent[ru];
-      while (parent[rv] != rv) rv = parent[rv];
-      ok = ru != rv;
+    if (!flat) {
+      // the links made while the last 64 pairs were scanned are the only ones a search has to
+      // follow afterwards (without this the chains grow as long as the leaf)
+      for (u32 i = (u32)lane; i < cnt; i += 64) {
+        u32 r = i;
+        while (parent[r] != r) r = parent[r];
+        __builtin_amdgcn_wave_barrier();
+        parent[i] = (unsigned short)r;
+      }
+      __builtin_amdgcn_wave_barrier();
+      flat = true;
     }
+    const u32 e = c + (u32)lane;
+    const u32 pr = e < E ? pairs[e] : 0u;
+    const bool dup = e > 0 && e < E && pr == pairs[e - 1];
+    const u32 u = pr >> 16, v = pr & 0xFFFFu;
+    bool ok = e < E && !dup;
+    if (ok) ok = deg[u] < s && deg[v] < s;
+    if (ok) ok = parent[u] != parent[v];  // flat: parents are roots
     u64 mask = ballot(ok);
     while (mask != 0ull) {
       const int j = __builtin_ctzll(mask);
@@ -329,6 +351,7 @@ __global__ __launch_bounds__(256) void hc_mst_kernel(const u64* keys, const u32*
             out[2 * accepted + 1] = (gv << 32) | gu;
           }
           ++accepted;
+          flat = false;
         }
       }
       __builtin_amdgcn_wave_barrier();
@@ -403,153 +426,227 @@ __global__ __launch_bounds__(256) void uq_scatter_kernel(const u64* keys, u64 n,
     if (keep[k]) out[w++] = keys[base + k];
 }
 
+// first[c] ... and where the sorted points go from there: child r of the level covers the sorted
+// positions cstart[r]..cstart[r+1]; a finished child (a leaf) is copied to its final place
+// dest[r] in `final_keys`, an unfinished one to position dest[r] & 0x7FFFFFFF of the next level's
+// work array (top bit set).
+__global__ __launch_bounds__(256) void hc_route_kernel(const u64* sorted, u64 m, const u32* cstart, const u32* dest,
+                                                       u32 nchild, u64* final_keys, u64* next_work) {
+  const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= m) return;
+  u32 lo = 0, hi = nchild;
+  while (hi - lo > 1) {
+    const u32 mid = (lo + hi) >> 1;
+    if ((u64)cstart[mid] <= i)
+      lo = mid;
+    else
+      hi = mid;
+  }
+  const u32 d = dest[lo];
+  const u64 k = i - cstart[lo];
+  const u64 key = sorted[i] & 0xFFFFFFFFull;
+  if (d & 0x80000000u)
+    next_work[(u64)(d & 0x7FFFFFFFu) + k] = key;
+  else
+    final_keys[(u64)d + k] = key;
+}
+
+__global__ __launch_bounds__(256) void hc_iota_mod_kernel(u64* keys, u64 n, u64 total) {
+  const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < total) keys[i] = i % n;
+}
+
 struct Seg {
-  u64 off, cnt, node;
-  u32 depth;
+  u64 goff, cnt, node, woff;  // place in the final order, size, heap number, place in the work array
+  u32 depth, tree;
+};
+struct Leaf {
+  u64 goff, cnt;
 };
 
-// Everything one build needs on the device.
+// Everything one group of trees needs on the device.  The trees of a group are cut side by side:
+// tree g of the group owns the positions g*n .. (g+1)*n of every array.
 struct HcCtx {
-  u64 n = 0;
+  u64 n = 0, N = 0;  // points; positions of a full group
+  u32 G = 1;
   u32 row_bytes = 0, lv_stride = 0;
   bool is_signed = false;
   const unsigned char* pts = nullptr;
   u32 Ls = 0, s = 0, l = 0;
   u64 seed = 0;
-  DevBuf keys[3], hist, segbuf, first, leafvec, leafnorm, leaf_off, knn_pos, knn_d;
-  u64 hist_entries = 0;
+  DevBuf final_keys, work[3], hist, segbuf, first, leafvec, leafnorm, leaf_off, knn_pos, knn_d;
+  u64 hist_entries = 0, seg_words = 0;
   std::vector<u32> h_first;
   int alloc() {
-    for (auto& k : keys) HIP_TRY(k.alloc(n * 8));
-    hist_entries = radix_hist_entries(n);
+    HIP_TRY(final_keys.alloc(N * 8));
+    for (auto& k : work) HIP_TRY(k.alloc(N * 8));
+    hist_entries = radix_hist_entries(N);
     HIP_TRY(hist.alloc(hist_entries * 4));
-    HIP_TRY(segbuf.alloc((4 * n + 8) * 4));  // off (nseg+1), pos1, pos2, base: nseg <= n
-    HIP_TRY(first.alloc((n + 2) * 4));
-    HIP_TRY(leafvec.alloc(n * lv_stride));
-    HIP_TRY(leafnorm.alloc((n + 64) * 4));
-    HIP_TRY(hipMemset(leafnorm.p, 0, (n + 64) * 4));
-    HIP_TRY(leaf_off.alloc((n + 1) * 4));
-    HIP_TRY(knn_pos.alloc(n * l * 2));
-    HIP_TRY(knn_d.alloc(n * l * 4));
+    // nodes that split at one level: each holds more than Ls points
+    const u64 nact = N / ((u64)Ls + 1) + G + 1;
+    seg_words = 8 * nact + 16;
+    HIP_TRY(segbuf.alloc(seg_words * 4));
+    HIP_TRY(first.alloc((2 * nact + 2) * 4));
+    HIP_TRY(leafvec.alloc(N * lv_stride));
+    HIP_TRY(leafnorm.alloc((N + 64) * 4));
+    HIP_TRY(hipMemset(leafnorm.p, 0, (N + 64) * 4));
+    HIP_TRY(leaf_off.alloc((N + 1) * 4));
+    HIP_TRY(knn_pos.alloc(N * l * 2));
+    HIP_TRY(knn_d.alloc(N * l * 4));
     return ANN_OK;
   }
 };
 
-// The cluster tree `tree`: on return keys[0] holds the point ids in leaf order (low words) and
-// `leaves` the leaves' position ranges, left to right.
-int hc_partition(HcCtx& X, u32 tree, std::vector<Seg>& leaves, hipStream_t st) {
-  const u64 n = X.n;
-  const u32 grid_n = (u32)((n + 255) / 256), grid_8n = (u32)((n * 8 + 255) / 256);
-  hipLaunchKernelGGL(hc_iota_kernel, dim3(grid_n), dim3(256), 0, st, X.keys[0].as<u64>(), n);
+// The cluster trees tree0 .. tree0+G-1, level by level, all of them in the same launches.  Only
+// the points of nodes that still split are worked on: a node's place in the final order is known
+// when it is made (children share their parent's range), so finished nodes are copied there and
+// the rest is packed for the next level.  On return final_keys holds the point ids (low words),
+// tree after tree, leaf after leaf, and `leaves` the leaves in that order.
+int hc_partition(HcCtx& X, u32 tree0, u32 G, std::vector<Leaf>& leaves, hipStream_t st) {
+  const u64 n = X.n, N = (u64)G * n;
+  leaves.clear();
+  if (n <= X.Ls) {
+    hipLaunchKernelGGL(hc_iota_mod_kernel, dim3((u32)((N + 255) / 256)), dim3(256), 0, st, X.final_keys.as<u64>(), n, N);
+    HIP_TRY(hipGetLastError());
+    for (u32 g = 0; g < G; ++g) leaves.push_back(Leaf{(u64)g * n, n});
+    return ANN_OK;
+  }
+  hipLaunchKernelGGL(hc_iota_mod_kernel, dim3((u32)((N + 255) / 256)), dim3(256), 0, st, X.work[0].as<u64>(), n, N);
   HIP_TRY(hipGetLastError());
-  std::vector<Seg> segs{Seg{0, n, 1, 0}};
-  std::vector<u32> up;
-  for (;;) {
-    bool any = false;
-    for (const Seg& sg : segs) any = any || sg.cnt > X.Ls;
-    if (!any) break;
-    const u32 nseg = (u32)segs.size();
-    // off[nseg+1] | pos1[nseg] | pos2[nseg] | base[nseg]
-    up.assign((size_t)4 * nseg + 1, HC_NONE);
-    u32* off = up.data();
-    u32* pos1 = off + nseg + 1;
-    u32* pos2 = pos1 + nseg;
-    u32* base = pos2 + nseg;
-    u32 nnew = 0;
-    for (u32 j = 0; j < nseg; ++j) {
-      const Seg& sg = segs[j];
-      off[j] = (u32)sg.off;
-      base[j] = nnew;
-      if (sg.cnt > X.Ls && sg.depth < HC_MAX_DEPTH) {
-        const u64 k = 2 * (((u64)tree << 40) + sg.node);
+  std::vector<Seg> act, next;
+  for (u32 g = 0; g < G; ++g) act.push_back(Seg{(u64)g * n, n, 1, (u64)g * n, 0, tree0 + g});
+  u64 m = N;
+  std::vector<u32> up, route;
+  while (!act.empty()) {
+    const u32 nact = (u32)act.size();
+    if (8ull * nact + 16 > X.seg_words) return fail(ANN_EINTERNAL, "more splitting nodes than planned for");
+    // woff[nact+1] | pos1[nact] | pos2[nact] | base[nact]
+    up.assign((size_t)4 * nact + 1, HC_NONE);
+    u32* woff = up.data();
+    u32* pos1 = woff + nact + 1;
+    u32* pos2 = pos1 + nact;
+    u32* base = pos2 + nact;
+    for (u32 j = 0; j < nact; ++j) {
+      const Seg& sg = act[j];
+      woff[j] = (u32)sg.woff;
+      base[j] = 2 * j;
+      if (sg.depth < HC_MAX_DEPTH) {
+        const u64 k = 2 * (((u64)sg.tree << 40) + sg.node);
         const u64 i1 = mulhi64(stream_output(X.seed, k), sg.cnt);
         u64 i2 = mulhi64(stream_output(X.seed, k + 1), sg.cnt - 1);
         if (i2 >= i1) ++i2;
-        pos1[j] = (u32)(sg.off + i1);
-        pos2[j] = (u32)(sg.off + i2);
-        nnew += 2;
-      } else {
-        nnew += 1;
+        pos1[j] = (u32)(sg.woff + i1);
+        pos2[j] = (u32)(sg.woff + i2);
       }
     }
-    off[nseg] = (u32)n;
-    u32* d_off = X.segbuf.as<u32>();
-    HIP_TRY(hipMemcpyAsync(d_off, up.data(), up.size() * 4, hipMemcpyHostToDevice, st));
+    woff[nact] = (u32)m;
+    u32* d_seg = X.segbuf.as<u32>();
+    HIP_TRY(hipMemcpyAsync(d_seg, up.data(), up.size() * 4, hipMemcpyHostToDevice, st));
+    const u32 grid_m = (u32)((m + 255) / 256), grid_8m = (u32)((m * 8 + 255) / 256);
     if (X.is_signed)
-      hipLaunchKernelGGL(hc_side_kernel<true>, dim3(grid_8n), dim3(256), 0, st, X.pts, X.row_bytes, X.keys[0].as<u64>(), n,
-                         d_off, nseg, d_off + nseg + 1, d_off + 2 * nseg + 1, d_off + 3 * nseg + 1, X.keys[1].as<u64>());
+      hipLaunchKernelGGL(hc_side_kernel<true>, dim3(grid_8m), dim3(256), 0, st, X.pts, X.row_bytes, X.work[0].as<u64>(), m,
+                         d_seg, nact, d_seg + nact + 1, d_seg + 2 * nact + 1, d_seg + 3 * nact + 1, X.work[1].as<u64>());
     else
-      hipLaunchKernelGGL(hc_side_kernel<false>, dim3(grid_8n), dim3(256), 0, st, X.pts, X.row_bytes, X.keys[0].as<u64>(), n,
-                         d_off, nseg, d_off + nseg + 1, d_off + 2 * nseg + 1, d_off + 3 * nseg + 1, X.keys[1].as<u64>());
+      hipLaunchKernelGGL(hc_side_kernel<false>, dim3(grid_8m), dim3(256), 0, st, X.pts, X.row_bytes, X.work[0].as<u64>(), m,
+                         d_seg, nact, d_seg + nact + 1, d_seg + 2 * nact + 1, d_seg + 3 * nact + 1, X.work[1].as<u64>());
     HIP_TRY(hipGetLastError());
-    HIP_TRY(radix_sort_edges(X.keys[1].as<u64>(), X.keys[2].as<u64>(), X.hist.as<u32>(), X.hist_entries, n,
-                             bits_to_hold(nnew), st));
-    HIP_TRY(hipMemsetAsync(X.first.p, 0xFF, ((size_t)nnew + 1) * 4, st));
-    hipLaunchKernelGGL(hc_bounds_kernel, dim3(grid_n), dim3(256), 0, st, X.keys[1].as<u64>(), n, X.first.as<u32>());
+    HIP_TRY(radix_sort_edges(X.work[1].as<u64>(), X.work[2].as<u64>(), X.hist.as<u32>(), X.hist_entries, m,
+                             bits_to_hold(2ull * nact), st));
+    HIP_TRY(hipMemsetAsync(X.first.p, 0xFF, ((size_t)2 * nact + 1) * 4, st));
+    hipLaunchKernelGGL(hc_bounds_kernel, dim3(grid_m), dim3(256), 0, st, X.work[1].as<u64>(), m, X.first.as<u32>());
     HIP_TRY(hipGetLastError());
-    X.h_first.resize(nnew);
-    HIP_TRY(hipMemcpyAsync(X.h_first.data(), X.first.p, (size_t)nnew * 4, hipMemcpyDeviceToHost, st));
+    X.h_first.resize((size_t)2 * nact);
+    HIP_TRY(hipMemcpyAsync(X.h_first.data(), X.first.p, (size_t)2 * nact * 4, hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
-    std::vector<Seg> next;
-    next.reserve(nnew);
-    for (u32 j = 0; j < nseg; ++j) {
-      const Seg& sg = segs[j];
-      if (sg.cnt <= X.Ls) {
-        next.push_back(sg);
-        continue;
-      }
+    // the children: a stable sort by child index leaves every node in its range of the work array
+    next.clear();
+    route.assign((size_t)4 * nact + 1, 0);  // cstart[2 nact + 1] | dest[2 nact]
+    u32* cstart = route.data();
+    u32* dest = cstart + 2 * nact + 1;
+    u64 nm = 0;
+    for (u32 j = 0; j < nact; ++j) {
+      const Seg& sg = act[j];
       u64 cl;
-      if (pos1[j] == HC_NONE || X.h_first[base[j]] == HC_NONE || X.h_first[base[j] + 1] == HC_NONE)
+      if (pos1[j] == HC_NONE || X.h_first[2 * j] == HC_NONE || X.h_first[2 * j + 1] == HC_NONE)
         cl = (sg.cnt + 1) / 2;  // too deep, or nothing separated: the order is cut in the middle
       else
-        cl = X.h_first[base[j] + 1] - sg.off;
-      next.push_back(Seg{sg.off, cl, 2 * sg.node, sg.depth + 1});
-      next.push_back(Seg{sg.off + cl, sg.cnt - cl, 2 * sg.node + 1, sg.depth + 1});
+        cl = X.h_first[2 * j + 1] - sg.woff;
+      const u64 ccnt[2] = {cl, sg.cnt - cl};
+      const u64 cgo[2] = {sg.goff, sg.goff + cl};
+      const u64 cws[2] = {sg.woff, sg.woff + cl};
+      for (int c = 0; c < 2; ++c) {
+        cstart[2 * j + c] = (u32)cws[c];
+        if (ccnt[c] <= X.Ls) {
+          dest[2 * j + c] = (u32)cgo[c];
+          leaves.push_back(Leaf{cgo[c], ccnt[c]});
+        } else {
+          dest[2 * j + c] = 0x80000000u | (u32)nm;
+          next.push_back(Seg{cgo[c], ccnt[c], 2 * sg.node + (u64)c, nm, sg.depth + 1, sg.tree});
+          nm += ccnt[c];
+        }
+      }
     }
-    segs.swap(next);
-    std::swap(X.keys[0], X.keys[1]);
+    cstart[2 * nact] = (u32)m;
+    HIP_TRY(hipMemcpyAsync(d_seg, route.data(), route.size() * 4, hipMemcpyHostToDevice, st));
+    hipLaunchKernelGGL(hc_route_kernel, dim3(grid_m), dim3(256), 0, st, X.work[1].as<u64>(), m, d_seg, d_seg + 2 * nact + 1,
+                       2 * nact, X.final_keys.as<u64>(), X.work[0].as<u64>());
+    HIP_TRY(hipGetLastError());
+    // (the next level's upload into the same buffer is ordered behind this kernel on the stream,
+    // but the host vectors it comes from must not change before the copy has been staged)
+    HIP_TRY(hipStreamSynchronize(st));
+    act.swap(next);
+    m = nm;
   }
-  leaves.swap(segs);
+  std::sort(leaves.begin(), leaves.end(), [](const Leaf& a, const Leaf& b) { return a.goff < b.goff; });
   return ANN_OK;
 }
 
-// Leaves -> nearest neighbours -> degree-bounded trees; the accepted pairs of leaf j land, as
-// arcs, at arcs[2 * (off_j - j) ...].
-int hc_leaves(HcCtx& X, const std::vector<Seg>& leaves, u64* arcs, hipStream_t st) {
-  const u64 n = X.n;
+// Leaves -> nearest neighbours -> degree-bounded trees, for a whole group; the accepted pairs of
+// the group's j-th leaf land, as arcs, at arcs[2 * (goff_j - j) ...].
+int hc_leaves(HcCtx& X, u32 G, const std::vector<Leaf>& leaves, u64* arcs, hipStream_t st) {
+  const u64 N = (u64)G * X.n;
   const u32 nleaves = (u32)leaves.size();
   std::vector<u32> lo(nleaves + 1);
   u64 maxc = 0;
   for (u32 j = 0; j < nleaves; ++j) {
-    lo[j] = (u32)leaves[j].off;
+    lo[j] = (u32)leaves[j].goff;
     maxc = std::max(maxc, leaves[j].cnt);
   }
-  lo[nleaves] = (u32)n;
+  lo[nleaves] = (u32)N;
   HIP_TRY(hipMemcpyAsync(X.leaf_off.p, lo.data(), lo.size() * 4, hipMemcpyHostToDevice, st));
-  const u32 grid_8n = (u32)((n * 8 + 255) / 256);
+  HIP_TRY(hipStreamSynchronize(st));  // lo goes out of scope
+  const u32 grid_8n = (u32)((N * 8 + 255) / 256);
   if (X.is_signed)
-    hipLaunchKernelGGL(hc_gather_kernel<true>, dim3(grid_8n), dim3(256), 0, st, X.pts, X.row_bytes, X.keys[0].as<u64>(), n,
-                       X.lv_stride, X.leafvec.as<unsigned char>(), X.leafnorm.as<i32>());
+    hipLaunchKernelGGL(hc_gather_kernel<true>, dim3(grid_8n), dim3(256), 0, st, X.pts, X.row_bytes, X.final_keys.as<u64>(),
+                       N, X.lv_stride, X.leafvec.as<unsigned char>(), X.leafnorm.as<i32>());
   else
-    hipLaunchKernelGGL(hc_gather_kernel<false>, dim3(grid_8n), dim3(256), 0, st, X.pts, X.row_bytes, X.keys[0].as<u64>(), n,
-                       X.lv_stride, X.leafvec.as<unsigned char>(), X.leafnorm.as<i32>());
+    hipLaunchKernelGGL(hc_gather_kernel<false>, dim3(grid_8n), dim3(256), 0, st, X.pts, X.row_bytes, X.final_keys.as<u64>(),
+                       N, X.lv_stride, X.leafvec.as<unsigned char>(), X.leafnorm.as<i32>());
   HIP_TRY(hipGetLastError());
   const dim3 kgrid(nleaves, (u32)((maxc + 31) / 32));
-  if (X.l <= 8)
-    hipLaunchKernelGGL(hc_knn_kernel<8>, kgrid, dim3(64), 0, st, X.leafvec.as<unsigned char>(), X.leafnorm.as<i32>(),
-                       X.lv_stride, X.leaf_off.as<u32>(), X.l, X.knn_pos.as<unsigned short>(), X.knn_d.as<i32>());
+#define HC_KNN(LC)                                                                                                     \
+  hipLaunchKernelGGL(hc_knn_kernel<LC>, kgrid, dim3(64), 0, st, X.leafvec.as<unsigned char>(), X.leafnorm.as<i32>(), \
+                     X.lv_stride, X.leaf_off.as<u32>(), X.l, X.knn_pos.as<unsigned short>(), X.knn_d.as<i32>())
+  if (X.l <= 4)
+    HC_KNN(4);
+  else if (X.l <= 8)
+    HC_KNN(8);
+  else if (X.l <= 10)
+    HC_KNN(10);
   else
-    hipLaunchKernelGGL(hc_knn_kernel<16>, kgrid, dim3(64), 0, st, X.leafvec.as<unsigned char>(), X.leafnorm.as<i32>(),
-                       X.lv_stride, X.leaf_off.as<u32>(), X.l, X.knn_pos.as<unsigned short>(), X.knn_d.as<i32>());
+    HC_KNN(16);
+#undef HC_KNN
   HIP_TRY(hipGetLastError());
   const u64 kk = X.l < maxc - 1 ? X.l : (maxc > 1 ? maxc - 1 : 1);
   u32 pmax = 64;
   while (pmax < maxc * kk) pmax <<= 1;
-  const u32 lds = pmax * 8 + 2 * HC_MAX_LS + HC_MAX_LS;
-  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(hc_mst_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+  const u32 lds = pmax * 8;
+  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(hc_pairs_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                               (int)lds));
-  hipLaunchKernelGGL(hc_mst_kernel, dim3(nleaves), dim3(256), lds, st, X.keys[0].as<u64>(), X.leaf_off.as<u32>(), X.l, X.s,
-                     X.knn_pos.as<unsigned short>(), X.knn_d.as<i32>(), pmax, arcs);
+  hipLaunchKernelGGL(hc_pairs_kernel, dim3(nleaves), dim3(1024), lds, st, X.leaf_off.as<u32>(), X.l,
+                     X.knn_pos.as<unsigned short>(), X.knn_d.as<i32>());
+  hipLaunchKernelGGL(hc_kruskal_kernel, dim3(nleaves), dim3(64), 0, st, X.final_keys.as<u64>(), X.leaf_off.as<u32>(), X.l,
+                     X.s, X.knn_d.as<i32>(), arcs);
   HIP_TRY(hipGetLastError());
   return ANN_OK;
 }
@@ -567,8 +664,11 @@ int hc_check(uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric, uint32_
   return ANN_OK;
 }
 
-int hc_setup(HcCtx& X, const ann_graph* g, const void* pts, uint32_t Ls, uint32_t s, uint32_t l, uint64_t seed) {
+int hc_setup(HcCtx& X, const ann_graph* g, const void* pts, uint32_t Ls, uint32_t s, uint32_t l, uint64_t seed,
+             u32 G) {
   X.n = g->n;
+  X.G = G;
+  X.N = (u64)G * g->n;
   X.row_bytes = (u32)g->cfg.row_bytes;
   X.lv_stride = (X.row_bytes + 31u) / 32u * 32u;
   X.is_signed = g->dtype == ANN_I8;
@@ -604,22 +704,22 @@ int ann_hcnng_tree_edges(const void* points_dev, uint64_t n, uint32_t d, ann_dty
   rc = resolve_points(g, points_dev, st, &pts);
   if (rc) return rc;
   HcCtx X;
-  rc = hc_setup(X, g, pts, Ls, s, l, seed);
+  rc = hc_setup(X, g, pts, Ls, s, l, seed, 1);
   if (rc) return rc;
   DevBuf arcs;
   HIP_TRY(arcs.alloc(2 * n * 8));
   HIP_TRY(hipMemsetAsync(arcs.p, 0xFF, 2 * n * 8, st));
-  std::vector<Seg> leaves;
-  rc = hc_partition(X, tree, leaves, st);
+  std::vector<Leaf> leaves;
+  rc = hc_partition(X, tree, 1, leaves, st);
   if (rc) return rc;
-  rc = hc_leaves(X, leaves, arcs.as<u64>(), st);
+  rc = hc_leaves(X, 1, leaves, arcs.as<u64>(), st);
   if (rc) return rc;
   std::vector<u64> hk(n), ha(2 * n);
-  HIP_TRY(hipMemcpyAsync(hk.data(), X.keys[0].p, n * 8, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipMemcpyAsync(hk.data(), X.final_keys.p, n * 8, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipMemcpyAsync(ha.data(), arcs.p, 2 * n * 8, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
   for (u64 i = 0; i < n; ++i) perm_host[i] = (u32)hk[i];
-  for (size_t j = 0; j < leaves.size(); ++j) leaf_off_host[j] = leaves[j].off;
+  for (size_t j = 0; j < leaves.size(); ++j) leaf_off_host[j] = leaves[j].goff;
   leaf_off_host[leaves.size()] = n;
   *nleaves = leaves.size();
   u64 np = 0;
@@ -663,21 +763,25 @@ int ann_hcnng_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dt
     HIP_TRY(start_vertex_device(points_dev, n, d, dtype, st, &sv));
     g->start = sv;
   }
+  // trees are cut in groups, as many at a time as keep a group within 32 million positions
+  u32 G = (u32)std::max<u64>(1, (32ull << 20) / n);
+  if (G > T) G = T;
   HcCtx X;
-  rc = hc_setup(X, g, pts, Ls, s, l, seed);
+  rc = hc_setup(X, g, pts, Ls, s, l, seed, G);
   if (rc) return rc;
   const u64 total = (u64)T * 2 * n;
   DevBuf arcs, arcs_tmp, big_hist, uq_counts, lists, small, arena;
   HIP_TRY(arcs.alloc(total * 8));
   HIP_TRY(arcs_tmp.alloc(total * 8));
   HIP_TRY(hipMemsetAsync(arcs.p, 0xFF, total * 8, st));
-  std::vector<Seg> leaves;
-  for (u32 t = 0; t < T; ++t) {
-    rc = hc_partition(X, t, leaves, st);
+  std::vector<Leaf> leaves;
+  for (u32 t = 0; t < T; t += G) {
+    const u32 Gc = T - t < G ? T - t : G;
+    rc = hc_partition(X, t, Gc, leaves, st);
     if (rc) return rc;
-    rc = hc_leaves(X, leaves, arcs.as<u64>() + (u64)t * 2 * n, st);
+    rc = hc_leaves(X, Gc, leaves, arcs.as<u64>() + (u64)t * 2 * n, st);
     if (rc) return rc;
-    g->stats.rounds += 1;
+    g->stats.rounds += Gc;
   }
   // all arcs by (point, neighbour): the neighbour bits first, then, stably, the point bits; the
   // unused entries (all ones) end up behind every point
