@@ -250,6 +250,40 @@ def main():
                    "qps_at_recall_0.90": hbest[0.90], "qps_at_recall_0.95": hbest[0.95], "search_sweep": hsweep}
         del hx
         say(f"layered index: build {hb[-1]:.1f} ms")
+    # the clustering-based builder of Sec. 4.3 over the same points (not part of the step), with
+    # the appendix's parameters (30 trees, leaves of 1,000, tree degree 3) and l = 10 (Sec. 4.3)
+    clustered = None
+    if w.n <= 20_000_000 and w.points.dtype != np.float32 and row_bytes <= 128:
+        cb = []
+        for i in range(2):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            gc = A.ann_hcnng_build(pts, 30, 1000, 3, 10, w.R, w.alpha, seed=w.seed)
+            torch.cuda.synchronize()
+            cb.append((time.perf_counter() - t0) * 1e3)
+            if i == 0:
+                del gc
+        csweep = []
+        cbest = {0.90: None, 0.95: None}
+        for L in sorted(set(w.search_L)):
+            if L < k:
+                continue
+            ms_c, cid = time_search(torch, A, gc, pts, qs, k, L, reps=3)
+            r = recall(cid.cpu().numpy().view(np.uint32), gt)
+            qps = qs.shape[0] / ms_c * 1e3
+            csweep.append({"L": L, "recall": round(r, 4), "qps": round(qps, 1)})
+            for target in cbest:
+                if r >= target and (cbest[target] is None or qps > cbest[target]["qps"]):
+                    cbest[target] = csweep[-1]
+            if r >= 0.995:
+                break
+        cdeg = float((gc.neighbors() != 0xFFFFFFFF).sum(1).mean())
+        clustered = {"trees": 30, "leaf_size": 1000, "tree_degree": 3, "knn": 10, "R": w.R, "alpha": w.alpha,
+                     "build_ms": round(cb[-1], 2), "points_per_s": round(w.n / cb[-1] * 1e3, 1),
+                     "mean_degree": round(cdeg, 2),
+                     "qps_at_recall_0.90": cbest[0.90], "qps_at_recall_0.95": cbest[0.95], "search_sweep": csweep}
+        del gc
+        say(f"clustering-based build: {cb[-1]:.1f} ms")
     ms_per_step = float(np.mean(step_ms))
     bms = float(np.mean(build_ms))
     points_per_s = w.n / (bms / 1e3)
@@ -303,6 +337,7 @@ def main():
         "search_sweep": sweep,
         "stream_insert": stream,
         "layered_index": layered,
+        "clustering_based": clustered,
         "build_counters": {kk: int(st[kk]) for kk in ("searches", "hops", "evals", "prunes", "reprunes", "appends",
                                                       "edges", "prune_evals", "redone", "rounds")},
         "build_phase_ms": phases,

@@ -1014,3 +1014,48 @@ def test_hcnng_bad_arguments(env, c1):
         A.ann_hcnng_build(dev(torch, np.zeros((100, 8), np.float32)), **ok)
     with pytest.raises(A.AnnError):  # rows above 128 bytes neither
         A.ann_hcnng_build(dev(torch, np.zeros((100, 256), np.uint8)), **ok)
+
+
+def test_hcnng_c2_full_size(env):
+    """At the benchmark's size (a million 128-byte points, leaves of up to 1,000, s = 3, l = 10):
+    two cluster trees against the oracle's in full; the accepted pairs of sampled leaves against
+    the oracle's; and the rows of a four-tree build, for sampled points, against the oracle's
+    prune of the neighbours that the four trees give."""
+    torch, A, O = env
+    w = W.c2()
+    ds = O.Dataset(w.points, 0)
+    pts = dev(torch, w.points)
+    T, Ls, s, l, R, alpha, seed = 4, 1000, 3, 10, 64, 1.2, 9
+    rng = np.random.default_rng(0)
+    nb_u, nb_v = [], []
+    for t in range(T):
+        perm, off, pairs = A.ann_hcnng_tree_edges(pts, Ls, s, l, seed, t)
+        nb_u.append(pairs[:, 0])
+        nb_v.append(pairs[:, 1])
+        if t in (0, 3):
+            say(f"tree {t}: {len(off) - 1} leaves, {len(pairs)} pairs; oracle cuts the same tree")
+            operm, ooff = O.hcnng_tree(ds, Ls, seed, t)
+            assert (off == ooff).all() and (perm == operm).all()
+            leaf_of = np.empty(w.n, np.int64)
+            leaf_of[perm] = np.repeat(np.arange(len(off) - 1), np.diff(off))
+            pl = leaf_of[pairs[:, 0]]
+            assert (pl == leaf_of[pairs[:, 1]]).all() and (np.diff(pl) >= 0).all()
+            for j in rng.choice(len(off) - 1, 12, replace=False):
+                want = O.hcnng_leaf(ds, perm[off[j]:off[j + 1]], s, l)
+                assert (pairs[pl == j] == want).all(), f"tree {t} leaf {j}"
+    u = np.concatenate(nb_u + nb_v).astype(np.int64)
+    v = np.concatenate(nb_v + nb_u).astype(np.int64)
+    order = np.lexsort((v, u))
+    u, v = u[order], v[order]
+    keep = np.ones(len(u), bool)
+    keep[1:] = (u[1:] != u[:-1]) | (v[1:] != v[:-1])
+    u, v = u[keep], v[keep]
+    first = np.searchsorted(u, np.arange(w.n + 1))
+    say("four-tree build")
+    g = A.ann_hcnng_build(pts, T, Ls, s, l, R, alpha, seed=seed)
+    rows = g.neighbors()
+    deg = (rows != NONE).sum(1)
+    assert deg.max() <= R and (deg > 0).mean() > 0.999
+    for p in rng.choice(w.n, 2000, replace=False):
+        cand = v[first[p]:first[p + 1]].astype(np.uint32)
+        assert row_list(rows[p]) == O.prune(ds, w.points[p], int(p), cand, R, alpha).tolist(), f"point {p}"
