@@ -20,7 +20,8 @@
 
 using namespace annmi;
 
-namespace {
+namespace annmi {
+namespace hcnng {
 
 constexpr u32 HC_MAX_LS = 1024;       // points per leaf
 constexpr u32 HC_MAX_L = 16;          // nearest neighbours per point that restrict the tree
@@ -680,7 +681,9 @@ int hc_setup(HcCtx& X, const ann_graph* g, const void* pts, uint32_t Ls, uint32_
   return X.alloc();
 }
 
-}  // namespace
+}  // namespace hcnng
+}  // namespace annmi
+using namespace annmi::hcnng;
 
 extern "C" {
 
