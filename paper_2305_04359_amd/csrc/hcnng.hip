@@ -174,6 +174,28 @@ __global__ __launch_bounds__(64) void hc_knn_kernel(const unsigned char* leafvec
   u64 best[LCAP];
 #pragma unroll
   for (int i = 0; i < LCAP; ++i) best[i] = KEY_INF;
+  // Candidates below the lane's worst kept key wait in a queue of the lane's own (LDS, one
+  // column per lane) and are inserted when some lane's queue is full: the insertion code then
+  // runs a few times per wave with most lanes busy, not once per candidate for one lane's sake.
+  constexpr u32 QCAP = 8;
+  __shared__ u64 pend[QCAP][64];
+  u32 pc = 0;
+  u64 worst = KEY_INF;
+  auto drain = [&]() {
+#pragma unroll
+    for (u32 i = 0; i < QCAP; ++i) {
+      if (ballot(i < pc) == 0ull) break;
+      u64 key = i < pc ? pend[i][lane] : KEY_INF;
+#pragma unroll
+      for (int t = 0; t < LCAP; ++t) {
+        const u64 lo = key < best[t] ? key : best[t];
+        key = key < best[t] ? best[t] : key;
+        best[t] = lo;
+      }
+    }
+    pc = 0;
+    worst = best[LCAP - 1];
+  };
 
   for (u32 c0 = 0; c0 < cnt; c0 += 32u) {
     const u32 c = c0 + col;
@@ -196,17 +218,18 @@ __global__ __launch_bounds__(64) void hc_knn_kernel(const unsigned char* leafvec
     for (int r = 0; r < 16; ++r) {
       const u32 cand = c0 + 8u * (r / 4) + 4u * half + (r % 4);
       const i32 dd = qn + cn[r / 4][r % 4] - 2 * acc[r];
-      u64 key = (cand < cnt && cand != q) ? (((u64)(u32)dd << 32) | cand) : KEY_INF;
-      if (ballot(key < best[LCAP - 1]) != 0ull) {
-#pragma unroll
-        for (int i = 0; i < LCAP; ++i) {
-          const u64 lo = key < best[i] ? key : best[i];
-          key = key < best[i] ? best[i] : key;
-          best[i] = lo;
+      const u64 key = (cand < cnt && cand != q) ? (((u64)(u32)dd << 32) | cand) : KEY_INF;
+      const bool qual = key < worst;
+      if (ballot(qual) != 0ull) {
+        if (qual) {
+          pend[pc][lane] = key;
+          ++pc;
         }
+        if (ballot(pc == QCAP) != 0ull) drain();
       }
     }
   }
+  drain();
   // the other half of the candidates, from the partner lane
   u64 other[LCAP];
 #pragma unroll
@@ -262,8 +285,12 @@ __global__ __launch_bounds__(1024) void hc_pairs_kernel(const u32* leaf_off, u32
     ek[e] = key;
   }
   __syncthreads();
+  // bitonic sort; the steps whose partners lie within 64 consecutive keys (more than half of all
+  // steps) run in registers, one wavefront per 64 keys, with lane exchanges instead of LDS trips
+  // and workgroup barriers
   for (u32 k2 = 2; k2 <= P; k2 <<= 1) {
-    for (u32 j = k2 >> 1; j > 0; j >>= 1) {
+    u32 j = k2 >> 1;
+    for (; j >= 64; j >>= 1) {
       for (u32 i = tid; i < P; i += 1024) {
         const u32 x = i ^ j;
         if (x > i) {
@@ -277,6 +304,18 @@ __global__ __launch_bounds__(1024) void hc_pairs_kernel(const u32* leaf_off, u32
       }
       __syncthreads();
     }
+    for (u32 i = tid; i < P; i += 1024) {
+      u64 v = ek[i];
+      const bool asc = (i & k2) == 0;
+      for (u32 jj = j; jj > 0; jj >>= 1) {
+        const u64 o = (u64)__shfl_xor((unsigned long long)v, (int)jj, 64);
+        const bool lower = (i & jj) == 0;
+        const u64 mn = v < o ? v : o, mx = v < o ? o : v;
+        v = (lower == asc) ? mn : mx;
+      }
+      ek[i] = v;
+    }
+    __syncthreads();
   }
   u32* out = reinterpret_cast<u32*>(knn_d) + (u64)off * l;
   for (u32 e = tid; e < E; e += 1024) out[e] = (u32)ek[e];
