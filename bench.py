@@ -253,12 +253,12 @@ def main():
     # the clustering-based builder of Sec. 4.3 over the same points (not part of the step), with
     # the appendix's parameters (30 trees, leaves of 1,000, tree degree 3) and l = 10 (Sec. 4.3)
     clustered = None
-    if w.n <= 20_000_000 and w.points.dtype != np.float32 and row_bytes <= 128:
+    if w.n <= 20_000_000 and (row_bytes <= 128 if w.points.dtype != np.float32 else w.d <= 256):
         cb = []
         for i in range(2):
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            gc = A.ann_hcnng_build(pts, 30, 1000, 3, 10, w.R, w.alpha, seed=w.seed)
+            gc = A.ann_hcnng_build(pts, 30, 1000, 3, 10, w.R, w.alpha, seed=w.seed, metric=metric)
             torch.cuda.synchronize()
             cb.append((time.perf_counter() - t0) * 1e3)
             if i == 0:

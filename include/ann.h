@@ -314,7 +314,10 @@ void ann_hnsw_free(ann_hnsw* h);
  *   pairs            sorted by (distance, smaller id, larger id)
  * The result is a graph like ann_build's (start vertex = ann_start_vertex);
  * ann_search and ann_search_eps serve it.
- *   dtype ANN_U8 or ANN_I8, metric ANN_L2SQ, d <= 128;
+ *   ANN_U8 / ANN_I8 with ANN_L2SQ and d <= 128 (exact integers throughout), or
+ *   ANN_F32 with either metric, d % 4 == 0 and d <= 256 (fp32 sums on the
+ *   vector units and the fp32 matrix cores; squared L2 inside a leaf is taken
+ *   as |a|^2 + |b|^2 - 2<a,b>);
  *   1 <= T < 2^20, 2 <= Ls <= 1024, 1 <= l <= 16, Ls * l <= 16384,
  *   1 <= s <= 255, 1 <= R <= 512, T * 2n < 2^32.
  * Blocks until done.
@@ -327,8 +330,8 @@ int ann_hcnng_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dt
  * receives the n point ids leaf after leaf, leaf_off_host the *nleaves + 1
  * leaf boundaries (room for n + 1), pairs_host the accepted pairs (two ids
  * each, room for n pairs) leaf after leaf in the order they were accepted.   */
-int ann_hcnng_tree_edges(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, uint32_t Ls,
-                         uint32_t s, uint32_t l, uint64_t seed, uint32_t tree, void* stream,
+int ann_hcnng_tree_edges(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric,
+                         uint32_t Ls, uint32_t s, uint32_t l, uint64_t seed, uint32_t tree, void* stream,
                          uint32_t* perm_host, uint64_t* leaf_off_host, uint64_t* nleaves,
                          uint32_t* pairs_host, uint64_t* npairs);
 

@@ -142,7 +142,7 @@ def lib():
         L.ann_hcnng_build.argtypes = [vp, u64, u32, C.c_int, C.c_int, u32, u32, u32, u32, u32, C.c_float, u64, vp,
                                       C.POINTER(vp)]
         L.ann_hcnng_tree_edges.restype = C.c_int
-        L.ann_hcnng_tree_edges.argtypes = [vp, u64, u32, C.c_int, u32, u32, u32, u64, u32, vp, vp, vp,
+        L.ann_hcnng_tree_edges.argtypes = [vp, u64, u32, C.c_int, C.c_int, u32, u32, u32, u64, u32, vp, vp, vp,
                                            C.POINTER(u64), vp, C.POINTER(u64)]
         L.ann_last_error.restype = C.c_char_p
         L.ann_last_error.argtypes = []
@@ -444,7 +444,7 @@ def ann_hcnng_build(points, T, Ls, s, l, R, alpha, seed=1, metric=L2SQ) -> Graph
     return Graph(h.value)
 
 
-def ann_hcnng_tree_edges(points, Ls, s, l, seed, tree):
+def ann_hcnng_tree_edges(points, Ls, s, l, seed, tree, metric=L2SQ):
     """One cluster tree: (perm, leaf_off, pairs) as numpy arrays."""
     points = _dev2d(points, "points")
     n = points.shape[0]
@@ -452,7 +452,8 @@ def ann_hcnng_tree_edges(points, Ls, s, l, seed, tree):
     off = np.empty(n + 1, np.uint64)
     pairs = np.empty((n, 2), np.uint32)
     nl, npairs = C.c_uint64(0), C.c_uint64(0)
-    _check(lib().ann_hcnng_tree_edges(points.data_ptr(), n, points.shape[1], _dtype_code(points), Ls, s, l, seed,
+    _check(lib().ann_hcnng_tree_edges(points.data_ptr(), n, points.shape[1], _dtype_code(points), int(metric), Ls, s, l,
+                                      seed,
                                       tree, _stream_ptr(), perm.ctypes.data_as(C.c_void_p),
                                       off.ctypes.data_as(C.c_void_p), C.byref(nl),
                                       pairs.ctypes.data_as(C.c_void_p), C.byref(npairs)))

@@ -256,6 +256,197 @@ __global__ __launch_bounds__(64) void hc_knn_kernel(const unsigned char* leafvec
   }
 }
 
+// ---- float data ------------------------------------------------------------------------------
+// The same three steps for float vectors (squared L2, or the negative inner product).  Sums run in
+// fp32 in a fixed order; which of two nearly equal distances is the smaller may come out
+// differently from an fp64 computation, and with it a point's side, a neighbour or a tree edge.
+typedef float v16f_t __attribute__((ext_vector_type(16)));
+
+template <bool MIPS>
+__global__ __launch_bounds__(256) void hc_side_f32_kernel(const unsigned char* pts, u32 row_bytes, const u64* keys_in,
+                                                          u64 n, const u32* off, u32 nseg, const u32* pos1,
+                                                          const u32* pos2, const u32* base, u64* keys_out) {
+  const u64 t = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+  const u64 i = t >> 3;
+  const u32 sub = (u32)t & 7u;
+  if (i >= n) return;
+  const u32 id = (u32)keys_in[i];
+  u32 lo = 0, hi = nseg;
+  while (hi - lo > 1) {
+    const u32 mid = (lo + hi) >> 1;
+    if ((u64)off[mid] <= i)
+      lo = mid;
+    else
+      hi = mid;
+  }
+  const u32 seg = lo;
+  u32 idx = base[seg];
+  const u32 p1 = pos1[seg];
+  if (p1 != HC_NONE) {
+    const u32 ida = (u32)keys_in[p1], idb = (u32)keys_in[pos2[seg]];
+    const float4* x = reinterpret_cast<const float4*>(pts + (u64)id * row_bytes);
+    const float4* a = reinterpret_cast<const float4*>(pts + (u64)ida * row_bytes);
+    const float4* b = reinterpret_cast<const float4*>(pts + (u64)idb * row_bytes);
+    float da = 0.0f, db = 0.0f;
+    for (u32 pc = sub; pc < row_bytes / 16; pc += 8) {
+      const float4 vx = x[pc], va = a[pc], vb = b[pc];
+      const float fx[4] = {vx.x, vx.y, vx.z, vx.w}, fa[4] = {va.x, va.y, va.z, va.w}, fb[4] = {vb.x, vb.y, vb.z, vb.w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if constexpr (MIPS) {
+          da = __builtin_fmaf(-fx[k], fa[k], da);
+          db = __builtin_fmaf(-fx[k], fb[k], db);
+        } else {
+          const float ea = fx[k] - fa[k], eb = fx[k] - fb[k];
+          da = __builtin_fmaf(ea, ea, da);
+          db = __builtin_fmaf(eb, eb, db);
+        }
+      }
+    }
+    da = group_sum(da);
+    db = group_sum(db);
+    if (da > db) idx += 1;
+  }
+  if (sub == 0) keys_out[i] = ((u64)idx << 32) | id;
+}
+
+// vectors in leaf order (rows of lv_stride bytes, zero tail) and their squared norms
+__global__ __launch_bounds__(256) void hc_gather_f32_kernel(const unsigned char* pts, u32 row_bytes, const u64* keys,
+                                                            u64 n, u32 lv_stride, unsigned char* leafvec,
+                                                            float* leafnorm) {
+  const u64 t = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+  const u64 i = t >> 3;
+  const u32 sub = (u32)t & 7u;
+  if (i >= n) return;
+  const u32 id = (u32)keys[i];
+  const float4* x = reinterpret_cast<const float4*>(pts + (u64)id * row_bytes);
+  float4* y = reinterpret_cast<float4*>(leafvec + i * lv_stride);
+  float nn = 0.0f;
+  for (u32 pc = sub; pc < lv_stride / 16; pc += 8) {
+    float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    if (pc < row_bytes / 16) v = x[pc];
+    y[pc] = v;
+    nn = __builtin_fmaf(v.x, v.x, nn);
+    nn = __builtin_fmaf(v.y, v.y, nn);
+    nn = __builtin_fmaf(v.z, v.z, nn);
+    nn = __builtin_fmaf(v.w, v.w, nn);
+  }
+  nn = group_sum(nn);
+  if (sub == 0) leafnorm[i] = nn;
+}
+
+// Nearest neighbours inside the leaf on the fp32 matrix cores (v_mfma_f32_32x32x2f32: two
+// elements of the inner product per instruction; a lane feeds it, one after the other, the four
+// floats of a 16-byte piece, the lower half-wave taking bytes 0..15 of every 32 and the upper half
+// bytes 16..31: a reordering of the sum's terms that both operands share).  Squared L2 comes out
+// as |a|^2 + |b|^2 - 2<a,b>, clamped at zero.  Selection as in the integer kernel; knn_d receives
+// the order-preserving 32-bit image of the distance.
+template <int LCAP, bool MIPS>
+__global__ __launch_bounds__(64) void hc_knn_f32_kernel(const unsigned char* leafvec, const float* leafnorm,
+                                                        u32 lv_stride, const u32* leaf_off, u32 l,
+                                                        unsigned short* knn_pos, i32* knn_d) {
+  const u32 off = leaf_off[blockIdx.x];
+  const u32 cnt = leaf_off[blockIdx.x + 1] - off;
+  const u32 q0 = blockIdx.y * 32u;
+  if (q0 >= cnt) return;
+  const int lane = threadIdx.x;
+  const u32 half = (u32)lane >> 5, col = (u32)lane & 31u;
+  const u32 ksteps = lv_stride / 32u;
+  const u32 q = q0 + col;
+  const u32 qrow = q < cnt ? q : cnt - 1u;
+  const float qn = leafnorm[off + qrow];
+  const unsigned char* qp = leafvec + (u64)(off + qrow) * lv_stride + 16u * half;
+  u64 best[LCAP];
+#pragma unroll
+  for (int i = 0; i < LCAP; ++i) best[i] = KEY_INF;
+  constexpr u32 QCAP = 8;
+  __shared__ u64 pend[QCAP][64];
+  u32 pc = 0;
+  u64 worst = KEY_INF;
+  auto drain = [&]() {
+#pragma unroll
+    for (u32 i = 0; i < QCAP; ++i) {
+      if (ballot(i < pc) == 0ull) break;
+      u64 key = i < pc ? pend[i][lane] : KEY_INF;
+#pragma unroll
+      for (int t = 0; t < LCAP; ++t) {
+        const u64 lo = key < best[t] ? key : best[t];
+        key = key < best[t] ? best[t] : key;
+        best[t] = lo;
+      }
+    }
+    pc = 0;
+    worst = best[LCAP - 1];
+  };
+  for (u32 c0 = 0; c0 < cnt; c0 += 32u) {
+    const u32 c = c0 + col;
+    const u32 crow = c < cnt ? c : cnt - 1u;
+    const unsigned char* cp = leafvec + (u64)(off + crow) * lv_stride + 16u * half;
+    v16f_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    for (u32 ks = 0; ks < ksteps; ++ks) {
+      const float4 a = *reinterpret_cast<const float4*>(cp + 32u * ks);
+      const float4 b = *reinterpret_cast<const float4*>(qp + 32u * ks);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
+    }
+    float cn[16];
+#pragma unroll
+    for (u32 g = 0; g < 4; ++g) {
+      const float4 v = *reinterpret_cast<const float4*>(leafnorm + off + c0 + 8u * g + 4u * half);
+      cn[4 * g] = v.x;
+      cn[4 * g + 1] = v.y;
+      cn[4 * g + 2] = v.z;
+      cn[4 * g + 3] = v.w;
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const u32 cand = c0 + 8u * (r / 4) + 4u * half + (r % 4);
+      float dd;
+      if constexpr (MIPS) {
+        dd = -acc[r];
+      } else {
+        dd = (qn + cn[r]) - 2.0f * acc[r];
+        dd = dd < 0.0f ? 0.0f : dd;
+      }
+      const u64 key = (cand < cnt && cand != q) ? (((u64)dkey_from_float(dd) << 32) | cand) : KEY_INF;
+      const bool qual = key < worst;
+      if (ballot(qual) != 0ull) {
+        if (qual) {
+          pend[pc][lane] = key;
+          ++pc;
+        }
+        if (ballot(pc == QCAP) != 0ull) drain();
+      }
+    }
+  }
+  drain();
+  u64 other[LCAP];
+#pragma unroll
+  for (int i = 0; i < LCAP; ++i) other[i] = (u64)__shfl_xor((unsigned long long)best[i], 32, 64);
+#pragma unroll
+  for (int j = 0; j < LCAP; ++j) {
+    u64 key = other[j];
+#pragma unroll
+    for (int i = 0; i < LCAP; ++i) {
+      const u64 lo = key < best[i] ? key : best[i];
+      key = key < best[i] ? best[i] : key;
+      best[i] = lo;
+    }
+  }
+  if (half == 0 && q < cnt) {
+#pragma unroll
+    for (int j = 0; j < LCAP; ++j) {
+      if ((u32)j < l) {
+        const u64 o = (u64)(off + q) * l + j;
+        knn_pos[o] = best[j] == KEY_INF ? (unsigned short)0xFFFF : (unsigned short)(best[j] & 0xFFFFull);
+        knn_d[o] = (i32)(best[j] >> 32);
+      }
+    }
+  }
+}
+
 // One leaf, first half: its candidate pairs (every point with its k = min(l, cnt-1) nearest)
 // sorted by (distance, smaller position, larger position) in LDS.  The sorted pairs, as
 // (smaller << 16 | larger), replace the leaf's part of knn_d (E = cnt * k entries from
@@ -511,6 +702,7 @@ struct HcCtx {
   u32 G = 1;
   u32 row_bytes = 0, lv_stride = 0;
   bool is_signed = false;
+  bool is_f32 = false, is_mips = false;
   const unsigned char* pts = nullptr;
   u32 Ls = 0, s = 0, l = 0;
   u64 seed = 0;
@@ -583,12 +775,18 @@ int hc_partition(HcCtx& X, u32 tree0, u32 G, std::vector<Leaf>& leaves, hipStrea
     u32* d_seg = X.segbuf.as<u32>();
     HIP_TRY(hipMemcpyAsync(d_seg, up.data(), up.size() * 4, hipMemcpyHostToDevice, st));
     const u32 grid_m = (u32)((m + 255) / 256), grid_8m = (u32)((m * 8 + 255) / 256);
-    if (X.is_signed)
-      hipLaunchKernelGGL(hc_side_kernel<true>, dim3(grid_8m), dim3(256), 0, st, X.pts, X.row_bytes, X.work[0].as<u64>(), m,
-                         d_seg, nact, d_seg + nact + 1, d_seg + 2 * nact + 1, d_seg + 3 * nact + 1, X.work[1].as<u64>());
+#define HC_SIDE(KERNEL)                                                                                                  \
+  hipLaunchKernelGGL(KERNEL, dim3(grid_8m), dim3(256), 0, st, X.pts, X.row_bytes, X.work[0].as<u64>(), m, d_seg, nact, \
+                     d_seg + nact + 1, d_seg + 2 * nact + 1, d_seg + 3 * nact + 1, X.work[1].as<u64>())
+    if (X.is_f32 && X.is_mips)
+      HC_SIDE(hc_side_f32_kernel<true>);
+    else if (X.is_f32)
+      HC_SIDE(hc_side_f32_kernel<false>);
+    else if (X.is_signed)
+      HC_SIDE(hc_side_kernel<true>);
     else
-      hipLaunchKernelGGL(hc_side_kernel<false>, dim3(grid_8m), dim3(256), 0, st, X.pts, X.row_bytes, X.work[0].as<u64>(), m,
-                         d_seg, nact, d_seg + nact + 1, d_seg + 2 * nact + 1, d_seg + 3 * nact + 1, X.work[1].as<u64>());
+      HC_SIDE(hc_side_kernel<false>);
+#undef HC_SIDE
     HIP_TRY(hipGetLastError());
     HIP_TRY(radix_sort_edges(X.work[1].as<u64>(), X.work[2].as<u64>(), X.hist.as<u32>(), X.hist_entries, m,
                              bits_to_hold(2ull * nact), st));
@@ -656,7 +854,10 @@ int hc_leaves(HcCtx& X, u32 G, const std::vector<Leaf>& leaves, u64* arcs, hipSt
   HIP_TRY(hipMemcpyAsync(X.leaf_off.p, lo.data(), lo.size() * 4, hipMemcpyHostToDevice, st));
   HIP_TRY(hipStreamSynchronize(st));  // lo goes out of scope
   const u32 grid_8n = (u32)((N * 8 + 255) / 256);
-  if (X.is_signed)
+  if (X.is_f32)
+    hipLaunchKernelGGL(hc_gather_f32_kernel, dim3(grid_8n), dim3(256), 0, st, X.pts, X.row_bytes, X.final_keys.as<u64>(), N,
+                       X.lv_stride, X.leafvec.as<unsigned char>(), X.leafnorm.as<float>());
+  else if (X.is_signed)
     hipLaunchKernelGGL(hc_gather_kernel<true>, dim3(grid_8n), dim3(256), 0, st, X.pts, X.row_bytes, X.final_keys.as<u64>(),
                        N, X.lv_stride, X.leafvec.as<unsigned char>(), X.leafnorm.as<i32>());
   else
@@ -664,17 +865,28 @@ int hc_leaves(HcCtx& X, u32 G, const std::vector<Leaf>& leaves, u64* arcs, hipSt
                        N, X.lv_stride, X.leafvec.as<unsigned char>(), X.leafnorm.as<i32>());
   HIP_TRY(hipGetLastError());
   const dim3 kgrid(nleaves, (u32)((maxc + 31) / 32));
-#define HC_KNN(LC)                                                                                                     \
-  hipLaunchKernelGGL(hc_knn_kernel<LC>, kgrid, dim3(64), 0, st, X.leafvec.as<unsigned char>(), X.leafnorm.as<i32>(), \
-                     X.lv_stride, X.leaf_off.as<u32>(), X.l, X.knn_pos.as<unsigned short>(), X.knn_d.as<i32>())
-  if (X.l <= 4)
-    HC_KNN(4);
-  else if (X.l <= 8)
-    HC_KNN(8);
-  else if (X.l <= 10)
-    HC_KNN(10);
-  else
-    HC_KNN(16);
+#define HC_KNN(KERNEL, NORMT)                                                                                       \
+  hipLaunchKernelGGL(KERNEL, kgrid, dim3(64), 0, st, X.leafvec.as<unsigned char>(), X.leafnorm.as<NORMT>(), X.lv_stride, \
+                     X.leaf_off.as<u32>(), X.l, X.knn_pos.as<unsigned short>(), X.knn_d.as<i32>())
+  if (X.is_f32 && X.is_mips) {
+    if (X.l <= 10)
+      HC_KNN((hc_knn_f32_kernel<10, true>), float);
+    else
+      HC_KNN((hc_knn_f32_kernel<16, true>), float);
+  } else if (X.is_f32) {
+    if (X.l <= 10)
+      HC_KNN((hc_knn_f32_kernel<10, false>), float);
+    else
+      HC_KNN((hc_knn_f32_kernel<16, false>), float);
+  } else if (X.l <= 4) {
+    HC_KNN(hc_knn_kernel<4>, i32);
+  } else if (X.l <= 8) {
+    HC_KNN(hc_knn_kernel<8>, i32);
+  } else if (X.l <= 10) {
+    HC_KNN(hc_knn_kernel<10>, i32);
+  } else {
+    HC_KNN(hc_knn_kernel<16>, i32);
+  }
 #undef HC_KNN
   HIP_TRY(hipGetLastError());
   const u64 kk = X.l < maxc - 1 ? X.l : (maxc > 1 ? maxc - 1 : 1);
@@ -692,11 +904,12 @@ int hc_leaves(HcCtx& X, u32 G, const std::vector<Leaf>& leaves, u64* arcs, hipSt
 }
 
 int hc_check(uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric, uint32_t Ls, uint32_t s, uint32_t l) {
-  if (dtype != ANN_U8 && dtype != ANN_I8)
-    return fail(ANN_EINVAL, "the clustering-based builder takes ANN_U8 and ANN_I8 points only");
-  if (metric != ANN_L2SQ) return fail(ANN_EINVAL, "the clustering-based builder takes ANN_L2SQ only");
+  if (dtype != ANN_U8 && dtype != ANN_I8 && dtype != ANN_F32) return fail(ANN_EINVAL, "unknown dtype");
+  if (metric != ANN_L2SQ && !(metric == ANN_MIPS && dtype == ANN_F32))
+    return fail(ANN_EINVAL, "ANN_MIPS is supported for ANN_F32 only");
   if (n < 1 || n >= (1ull << 31)) return fail(ANN_EINVAL, "n must be in [1, 2^31)");
-  if (d < 1 || d > 128) return fail(ANN_EINVAL, "the clustering-based builder takes rows of at most 128 bytes");
+  if (dtype == ANN_F32 ? (d < 4 || d > 256) : (d < 1 || d > 128))
+    return fail(ANN_EINVAL, "the clustering-based builder takes rows of at most 128 bytes (1024 for ANN_F32)");
   if (Ls < 2 || Ls > HC_MAX_LS) return fail(ANN_EINVAL, "leaf size must be in [2, 1024]");
   if (l < 1 || l > HC_MAX_L) return fail(ANN_EINVAL, "l must be in [1, 16]");
   if ((u64)Ls * l > HC_MAX_PAIRS) return fail(ANN_EINVAL, "leaf size times l must be at most 16384");
@@ -712,6 +925,8 @@ int hc_setup(HcCtx& X, const ann_graph* g, const void* pts, uint32_t Ls, uint32_
   X.row_bytes = (u32)g->cfg.row_bytes;
   X.lv_stride = (X.row_bytes + 31u) / 32u * 32u;
   X.is_signed = g->dtype == ANN_I8;
+  X.is_f32 = g->dtype == ANN_F32;
+  X.is_mips = g->metric == ANN_MIPS;
   X.pts = static_cast<const unsigned char*>(pts);
   X.Ls = Ls;
   X.s = s;
@@ -726,17 +941,17 @@ using namespace annmi::hcnng;
 
 extern "C" {
 
-int ann_hcnng_tree_edges(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, uint32_t Ls, uint32_t s,
-                         uint32_t l, uint64_t seed, uint32_t tree, void* stream, uint32_t* perm_host,
+int ann_hcnng_tree_edges(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric,
+                         uint32_t Ls, uint32_t s, uint32_t l, uint64_t seed, uint32_t tree, void* stream, uint32_t* perm_host,
                          uint64_t* leaf_off_host, uint64_t* nleaves, uint32_t* pairs_host, uint64_t* npairs) {
   if (!points_dev || !perm_host || !leaf_off_host || !nleaves || !pairs_host || !npairs)
     return fail(ANN_EINVAL, "null argument");
-  int rc = hc_check(n, d, dtype, ANN_L2SQ, Ls, s, l);
+  int rc = hc_check(n, d, dtype, metric, Ls, s, l);
   if (rc) return rc;
   if (tree >= (1u << 20)) return fail(ANN_EINVAL, "tree index must be below 2^20");
   hipStream_t st = static_cast<hipStream_t>(stream);
   ann_graph* g = nullptr;
-  rc = new_graph(n, d, dtype, ANN_L2SQ, 1, &g);
+  rc = new_graph(n, d, dtype, metric, 1, &g);
   if (rc) return rc;
   struct Guard {
     ann_graph* g;

@@ -1010,8 +1010,10 @@ def test_hcnng_bad_arguments(env, c1):
         with pytest.raises(A.AnnError):
             say(f"  refused: {bad}")
             A.ann_hcnng_build(pts, **{**ok, **bad})
-    with pytest.raises(A.AnnError):  # float data is not taken
-        A.ann_hcnng_build(dev(torch, np.zeros((100, 8), np.float32)), **ok)
+    with pytest.raises(A.AnnError):  # float rows above 1,024 bytes are not taken
+        A.ann_hcnng_build(dev(torch, np.zeros((100, 260), np.float32)), **ok)
+    with pytest.raises(A.AnnError):  # the inner product is for float data
+        A.ann_hcnng_build(pts, metric=A.MIPS, **ok)
     with pytest.raises(A.AnnError):  # rows above 128 bytes neither
         A.ann_hcnng_build(dev(torch, np.zeros((100, 256), np.uint8)), **ok)
 
@@ -1059,3 +1061,50 @@ def test_hcnng_c2_full_size(env):
     for p in rng.choice(w.n, 2000, replace=False):
         cand = v[first[p]:first[p + 1]].astype(np.uint32)
         assert row_list(rows[p]) == O.prune(ds, w.points[p], int(p), cand, R, alpha).tolist(), f"point {p}"
+
+
+@pytest.mark.parametrize("metric,alpha", [(0, 1.2), (1, 1.0)])
+def test_hcnng_f32(env, metric, alpha):
+    """Float data: sums run in fp32 (squared L2 inside a leaf as |a|^2 + |b|^2 - 2<a,b> on the
+    fp32 matrix cores), so near-ties may fall the other way than in the oracle's fp64 sums and
+    move a point to the other side of a cut, or swap a neighbour or a tree edge.  Bounded here:
+    nearly every point in the same leaf, nearly every pair and row the same, recall within 0.002."""
+    torch, A, O = env
+    w = W.c4(n=6000, nq=400)
+    ds = O.Dataset(w.points, metric)
+    pts, qs = dev(torch, w.points), dev(torch, w.queries)
+    Ls, s, l = 150, 3, 10
+    perm, off, pairs = A.ann_hcnng_tree_edges(pts, Ls, s, l, 3, 1, metric=metric)
+    operm, ooff, opairs = _oracle_tree_pairs(O, ds, Ls, s, l, 3, 1)
+    assert sorted(perm.tolist()) == list(range(w.n)) and (np.diff(off) <= Ls).all() and (np.diff(off) >= 1).all()
+
+    def leaf_ids(perm, off):
+        sig = np.empty(w.n, np.int64)
+        for j in range(len(off) - 1):
+            ids = perm[off[j]:off[j + 1]]
+            assert (np.diff(ids.astype(np.int64)) > 0).all()
+            sig[ids] = int(ids[0]) * 100000 + len(ids)
+        return sig
+    same_leaf = (leaf_ids(perm, off) == leaf_ids(operm, ooff)).mean()
+    got = {(int(a), int(b)) for a, b in pairs}
+    want = {(int(a), int(b)) for a, b in opairs}
+    say(f"  metric {metric}: same leaf {same_leaf:.4f}, pairs in common {len(got & want) / len(want):.4f}")
+    assert same_leaf > 0.98 and len(got & want) / len(want) > 0.97
+    deg = np.bincount(pairs.ravel(), minlength=w.n)
+    assert deg.max() <= s
+
+    T, R = 8, 32
+    og = O.hcnng_build(ds, T, Ls, s, l, R, alpha, seed=3, threads=0)
+    g = A.ann_hcnng_build(pts, T, Ls, s, l, R, alpha, seed=3, metric=metric)
+    rows = g.neighbors()
+    same_rows = (rows == og).all(1).mean()
+    say(f"  rows identical {same_rows:.4f}")
+    assert same_rows > 0.9
+    gt, _ = O.brute_force(ds, w.queries, 10)
+    st = O.start_vertex(ds)
+    assert g.info().start == st
+    gi, _ = A.ann_search(g, pts, qs, 10, 64)
+    oi, _ = O.search_batch(ds, og, st, w.queries, 10, 64, threads=0)
+    r_g, r_o = recall_at_k(gi.cpu().numpy().view(np.uint32), gt), recall_at_k(oi, gt)
+    say(f"  recall gpu={r_g:.4f} oracle={r_o:.4f}")
+    assert abs(r_g - r_o) <= 0.002
