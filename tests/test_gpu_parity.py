@@ -1108,3 +1108,30 @@ def test_hcnng_f32(env, metric, alpha):
     r_g, r_o = recall_at_k(gi.cpu().numpy().view(np.uint32), gt), recall_at_k(oi, gt)
     say(f"  recall gpu={r_g:.4f} oracle={r_o:.4f}")
     assert abs(r_g - r_o) <= 0.002
+
+
+def test_hcnng_single_leaf_and_large_parameters(env, c1):
+    torch, A, O = env
+    # fewer points than a leaf holds: every tree is one leaf, all trees give the same edges
+    for n in (1, 2, 40):
+        pts_h = c1.points[:n]
+        og = O.hcnng_build(O.Dataset(pts_h, 0), 3, 64, 3, 10, 8, 1.2, seed=1)
+        assert (A.ann_hcnng_build(dev(torch, pts_h), 3, 64, 3, 10, 8, 1.2, seed=1).neighbors() == og).all()
+    # the largest leaf, l and degree bound the library takes
+    pts_h = c1.points[:2500]
+    og = O.hcnng_build(O.Dataset(pts_h, 0), 2, 1024, 255, 16, 512, 1.5, seed=2, threads=0)
+    assert (A.ann_hcnng_build(dev(torch, pts_h), 2, 1024, 255, 16, 512, 1.5, seed=2).neighbors() == og).all()
+
+
+def test_hnsw_wide_layers(env, c1):
+    """m = 128 (bottom rows of 256 ids, four beam slots at efc = 300)."""
+    torch, A, O = env
+    n = 2500
+    ds = O.Dataset(c1.points[:n], 0)
+    oh = O.hnsw_build(ds, 128, 300, 1.2, seed=6, level=(np.arange(n) % 7 == 0).astype(np.uint32), threads=0)
+    pts = dev(torch, c1.points[:n])
+    h = A.ann_hnsw_build(pts, 128, 300, 1.2, seed=6, level=(np.arange(n) % 7 == 0).astype(np.uint32))
+    _check_hnsw_against(h, oh, n)
+    ids, dists = A.ann_hnsw_search(h, pts, dev(torch, c1.queries), 10, 300)
+    oi, od, _ = O.hnsw_search_batch(ds, oh, c1.queries, 10, 300, threads=0)
+    assert (ids.cpu().numpy().view(np.uint32) == oi).all() and (dists.cpu().numpy() == od).all()
