@@ -447,34 +447,56 @@ __global__ __launch_bounds__(64) void hc_knn_f32_kernel(const unsigned char* lea
   }
 }
 
-// One leaf, first half: its candidate pairs (every point with its k = min(l, cnt-1) nearest)
+// One leaf, first half: its candidate pairs (every point with its k = min(l, cnt-1) nearest),
+// each once (the entry of the larger end is dropped when the smaller end lists the pair too),
 // sorted by (distance, smaller position, larger position) in LDS.  The sorted pairs, as
-// (smaller << 16 | larger), replace the leaf's part of knn_d (E = cnt * k entries from
-// knn_d[off * l]; a pair chosen from both ends appears twice, side by side).
-__global__ __launch_bounds__(1024) void hc_pairs_kernel(const u32* leaf_off, u32 l, const unsigned short* knn_pos,
-                                                       i32* knn_d) {
+// (smaller << 16 | larger), replace the head of the leaf's part of knn_d (from knn_d[off * l]);
+// their number goes to pair_cnt[leaf].
+__global__ __launch_bounds__(1024) void hc_pairs_kernel(const u32* leaf_list, const u32* leaf_off, u32 l,
+                                                       const unsigned short* knn_pos, i32* knn_d, u32* pair_cnt) {
   extern __shared__ __align__(16) unsigned char hc_smem[];
+  __shared__ u32 kept;
   u64* ek = reinterpret_cast<u64*>(hc_smem);
-  const u32 leaf = blockIdx.x;
+  const u32 leaf = leaf_list[blockIdx.x];  // the launch's leaves: those of one size class
   const u32 off = leaf_off[leaf];
   const u32 cnt = leaf_off[leaf + 1] - off;
-  if (cnt < 2) return;
+  if (cnt < 2) {
+    if (threadIdx.x == 0) pair_cnt[leaf] = 0;
+    return;
+  }
   const u32 tid = threadIdx.x;
+  const int lane = (int)(tid & 63u);
   const u32 k = l < cnt - 1u ? l : cnt - 1u;
   const u32 E = cnt * k;
-  u32 P = 64;
-  while (P < E) P <<= 1;  // within the launch's LDS: the host sized it for the largest leaf
-  for (u32 e = tid; e < P; e += 1024) {
+  if (tid == 0) kept = 0;
+  __syncthreads();
+  for (u32 e0 = tid - (u32)lane; e0 < E; e0 += 1024) {  // whole waves: the ballot below needs every lane
+    const u32 e = e0 + (u32)lane;
+    bool keep = false;
     u64 key = KEY_INF;
     if (e < E) {
       const u32 a = e / k, j = e - a * k;
       const u64 o = (u64)(off + a) * l + j;
       const u32 b = knn_pos[o];
+      keep = true;
+      if (a > b) {
+        const unsigned short* lb = knn_pos + (u64)(off + b) * l;
+        for (u32 t = 0; t < k; ++t) keep = keep && lb[t] != a;
+      }
       const u32 u = a < b ? a : b, v = a < b ? b : a;
       key = ((u64)(u32)knn_d[o] << 32) | (u << 16) | v;
     }
-    ek[e] = key;
+    const u64 m = ballot(keep);
+    u32 base = 0;
+    if (lane == 0 && m != 0ull) base = atomicAdd(&kept, (u32)__builtin_popcountll(m));
+    base = readlane_u32(base, 0);
+    if (keep) ek[base + (u32)__builtin_popcountll(m & lanemask_lt(lane))] = key;
   }
+  __syncthreads();
+  const u32 M = kept;
+  u32 P = 64;
+  while (P < M) P <<= 1;  // within the launch's LDS: the host sized it for the largest leaf
+  for (u32 e = M + tid; e < P; e += 1024) ek[e] = KEY_INF;
   __syncthreads();
   // bitonic sort; the steps whose partners lie within 64 consecutive keys (more than half of all
   // steps) run in registers, one wavefront per 64 keys, with lane exchanges instead of LDS trips
@@ -509,7 +531,8 @@ __global__ __launch_bounds__(1024) void hc_pairs_kernel(const u32* leaf_off, u32
     __syncthreads();
   }
   u32* out = reinterpret_cast<u32*>(knn_d) + (u64)off * l;
-  for (u32 e = tid; e < E; e += 1024) out[e] = (u32)ek[e];
+  for (u32 e = tid; e < M; e += 1024) out[e] = (u32)ek[e];
+  if (tid == 0) pair_cnt[leaf] = M;
 }
 
 // Second half, one wavefront per leaf: Kruskal's scan over the sorted pairs with the degree bound
@@ -518,7 +541,7 @@ __global__ __launch_bounds__(1024) void hc_pairs_kernel(const u32* leaf_off, u32
 // pairs go, as two arcs (point << 32 | neighbour), to arcs[2 * (off - leaf) ...] (a leaf of cnt
 // points accepts at most cnt - 1; unused entries keep what they hold).
 __global__ __launch_bounds__(64) void hc_kruskal_kernel(const u64* keys, const u32* leaf_off, u32 l, u32 s,
-                                                        const i32* knn_d, u64* arcs) {
+                                                        const i32* knn_d, const u32* pair_cnt, u64* arcs) {
   __shared__ unsigned short parent_lds[HC_MAX_LS];
   __shared__ unsigned char deg_lds[HC_MAX_LS];
   volatile unsigned short* parent = parent_lds;
@@ -528,8 +551,7 @@ __global__ __launch_bounds__(64) void hc_kruskal_kernel(const u64* keys, const u
   const u32 cnt = leaf_off[leaf + 1] - off;
   if (cnt < 2) return;
   const int lane = threadIdx.x;
-  const u32 k = l < cnt - 1u ? l : cnt - 1u;
-  const u32 E = cnt * k;
+  const u32 E = pair_cnt[leaf];
   const u32* pairs = reinterpret_cast<const u32*>(knn_d) + (u64)off * l;
   for (u32 i = (u32)lane; i < cnt; i += 64) {
     parent[i] = (unsigned short)i;
@@ -706,7 +728,8 @@ struct HcCtx {
   const unsigned char* pts = nullptr;
   u32 Ls = 0, s = 0, l = 0;
   u64 seed = 0;
-  DevBuf final_keys, work[3], hist, segbuf, first, leafvec, leafnorm, leaf_off, knn_pos, knn_d;
+  DevBuf final_keys, work[3], hist, segbuf, first, leafvec, leafnorm, leaf_off, knn_pos, knn_d, pair_cnt, leaf_list;
+  u64 pair_cnt_cap = 0;
   u64 hist_entries = 0, seg_words = 0;
   std::vector<u32> h_first;
   int alloc() {
@@ -889,16 +912,43 @@ int hc_leaves(HcCtx& X, u32 G, const std::vector<Leaf>& leaves, u64* arcs, hipSt
   }
 #undef HC_KNN
   HIP_TRY(hipGetLastError());
-  const u64 kk = X.l < maxc - 1 ? X.l : (maxc > 1 ? maxc - 1 : 1);
-  u32 pmax = 64;
-  while (pmax < maxc * kk) pmax <<= 1;
-  const u32 lds = pmax * 8;
-  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(hc_pairs_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)lds));
-  hipLaunchKernelGGL(hc_pairs_kernel, dim3(nleaves), dim3(1024), lds, st, X.leaf_off.as<u32>(), X.l,
-                     X.knn_pos.as<unsigned short>(), X.knn_d.as<i32>());
+  if (X.pair_cnt_cap < nleaves) {
+    HIP_TRY(hipStreamSynchronize(st));
+    HIP_TRY(X.pair_cnt.alloc(((size_t)nleaves + 1) * 4));
+    HIP_TRY(X.leaf_list.alloc(((size_t)nleaves + 1) * 4));
+    X.pair_cnt_cap = nleaves;
+  }
+  // the pair sort by size class: a leaf's LDS follows from its size, and the smaller the
+  // allocation the more leaves a compute unit sorts at a time
+  {
+    std::vector<u32> order;
+    order.reserve(nleaves);
+    u32 first_of[4] = {0, 0, 0, 0};
+    const u32 limit[3] = {4096, 8192, HC_MAX_PAIRS};
+    for (int c = 0; c < 3; ++c) {
+      first_of[c] = (u32)order.size();
+      for (u32 j = 0; j < nleaves; ++j) {
+        const u64 cj = leaves[j].cnt;
+        const u64 e = cj * (X.l < cj - 1 ? X.l : (cj > 1 ? cj - 1 : 1));
+        if (e <= limit[c] && (c == 0 || e > limit[c - 1])) order.push_back(j);
+      }
+    }
+    first_of[3] = (u32)order.size();
+    HIP_TRY(hipMemcpyAsync(X.leaf_list.p, order.data(), order.size() * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipStreamSynchronize(st));  // `order` goes out of scope
+    for (int c = 0; c < 3; ++c) {
+      const u32 cntc = first_of[c + 1] - first_of[c];
+      if (!cntc) continue;
+      const u32 lds = limit[c] * 8;
+      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(hc_pairs_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+      hipLaunchKernelGGL(hc_pairs_kernel, dim3(cntc), dim3(1024), lds, st, X.leaf_list.as<u32>() + first_of[c],
+                         X.leaf_off.as<u32>(), X.l, X.knn_pos.as<unsigned short>(), X.knn_d.as<i32>(),
+                         X.pair_cnt.as<u32>());
+    }
+  }
   hipLaunchKernelGGL(hc_kruskal_kernel, dim3(nleaves), dim3(64), 0, st, X.final_keys.as<u64>(), X.leaf_off.as<u32>(), X.l,
-                     X.s, X.knn_d.as<i32>(), arcs);
+                     X.s, X.knn_d.as<i32>(), X.pair_cnt.as<u32>(), arcs);
   HIP_TRY(hipGetLastError());
   return ANN_OK;
 }
