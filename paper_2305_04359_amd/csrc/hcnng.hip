@@ -102,14 +102,6 @@ __global__ __launch_bounds__(256) void hc_side_kernel(const unsigned char* pts, 
   if (sub == 0) keys_out[i] = ((u64)idx << 32) | id;
 }
 
-// first[c] = first position whose key carries child index c (untouched where there is none)
-__global__ __launch_bounds__(256) void hc_bounds_kernel(const u64* keys, u64 n, u32* first) {
-  const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n) return;
-  const u32 c = (u32)(keys[i] >> 32);
-  if (i == 0 || (u32)(keys[i - 1] >> 32) != c) first[c] = (u32)i;
-}
-
 // The vectors in leaf order, as int8 (uint8 data moved down by 128: distances do not change),
 // rows of lv_stride bytes (a multiple of 32, zero tail), and their squared norms.  Eight lanes
 // per point.
@@ -679,29 +671,88 @@ __global__ __launch_bounds__(256) void uq_scatter_kernel(const u64* keys, u64 n,
     if (keep[k]) out[w++] = keys[base + k];
 }
 
-// first[c] ... and where the sorted points go from there: child r of the level covers the sorted
-// positions cstart[r]..cstart[r+1]; a finished child (a leaf) is copied to its final place
-// dest[r] in `final_keys`, an unfinished one to position dest[r] & 0x7FFFFFFF of the next level's
-// work array (top bit set).
-__global__ __launch_bounds__(256) void hc_route_kernel(const u64* sorted, u64 m, const u32* cstart, const u32* dest,
-                                                       u32 nchild, u64* final_keys, u64* next_work) {
-  const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= m) return;
-  u32 lo = 0, hi = nchild;
-  while (hi - lo > 1) {
-    const u32 mid = (lo + hi) >> 1;
-    if ((u64)cstart[mid] <= i)
-      lo = mid;
-    else
-      hi = mid;
+// ---- a stable two-way split of every node, without a sort -------------------------------------
+// keys[i] = (side << 32) | id, side 0 = left.  With L(i) = number of left points before position
+// i, a point of the node [a, b) with nl = L(b) - L(a) left points goes to a + (L(i) - L(a)) if it
+// is a left point and to a + nl + (i - a) - (L(i) - L(a)) otherwise.
+constexpr u32 SP_TILE = 2048;  // positions per workgroup of 256 threads
+
+__global__ __launch_bounds__(256) void hc_count_left_kernel(const u64* keys, u64 m, u32* tile_cnt) {
+  __shared__ u32 total;
+  if (threadIdx.x == 0) total = 0;
+  __syncthreads();
+  const u64 base = (u64)blockIdx.x * SP_TILE + threadIdx.x * 8u;
+  u32 c = 0;
+  for (u32 k = 0; k < 8; ++k)
+    if (base + k < m && (u32)(keys[base + k] >> 32) == 0u) ++c;
+  atomicAdd(&total, c);
+  __syncthreads();
+  if (threadIdx.x == 0) tile_cnt[blockIdx.x] = total;
+}
+
+// Lb[j] = L(woff[j]) for the nact + 1 node boundaries; one wavefront each
+__global__ __launch_bounds__(64) void hc_seg_left_kernel(const u64* keys, u64 m, const u32* woff, const u32* tile_off,
+                                                         u32* Lb) {
+  const u64 a = woff[blockIdx.x];
+  const u64 t = a / SP_TILE;
+  u32 c = 0;
+  for (u64 i = t * SP_TILE + threadIdx.x; i < a; i += 64)
+    if ((u32)(keys[i] >> 32) == 0u) ++c;
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) c += (u32)__shfl_xor((int)c, o, 64);
+  if (threadIdx.x == 0) Lb[blockIdx.x] = tile_off[t] + c;
+}
+
+// Every point to its place: the split position sp inside its node as above, then the child that
+// covers sp (children 2 seg and 2 seg + 1 start at cstart[..]) and from there either the final
+// order (a finished child, dest = its first final position) or the next level's work array (top
+// bit of dest set).
+__global__ __launch_bounds__(256) void hc_split_route_kernel(const u64* keys, u64 m, const u32* woff, u32 nact,
+                                                             const u32* Lb, const u32* tile_off, const u32* cstart,
+                                                             const u32* dest, u64* final_keys, u64* next_work) {
+  __shared__ u32 pre[256];
+  const u32 t = threadIdx.x;
+  const u64 base = (u64)blockIdx.x * SP_TILE + t * 8u;
+  u64 key[8];
+  u32 c = 0;
+  for (u32 k = 0; k < 8; ++k) {
+    key[k] = base + k < m ? keys[base + k] : ~0ull;
+    c += (u32)(key[k] >> 32) == 0u ? 1u : 0u;
   }
-  const u32 d = dest[lo];
-  const u64 k = i - cstart[lo];
-  const u64 key = sorted[i] & 0xFFFFFFFFull;
-  if (d & 0x80000000u)
-    next_work[(u64)(d & 0x7FFFFFFFu) + k] = key;
-  else
-    final_keys[(u64)d + k] = key;
+  pre[t] = c;
+  __syncthreads();
+  for (u32 o = 1; o < 256; o <<= 1) {
+    const u32 v = t >= o ? pre[t - o] : 0u;
+    __syncthreads();
+    pre[t] += v;
+    __syncthreads();
+  }
+  u32 L = tile_off[blockIdx.x] + (t ? pre[t - 1] : 0u);  // left points before position base
+  for (u32 k = 0; k < 8; ++k) {
+    const u64 i = base + k;
+    if (i >= m) break;
+    const bool left = (u32)(key[k] >> 32) == 0u;
+    u32 lo = 0, hi = nact;
+    while (hi - lo > 1) {
+      const u32 mid = (lo + hi) >> 1;
+      if ((u64)woff[mid] <= i)
+        lo = mid;
+      else
+        hi = mid;
+    }
+    const u32 a = woff[lo], La = Lb[lo], nl = Lb[lo + 1] - La;
+    const u32 lr = L - La;
+    const u32 sp = left ? a + lr : a + nl + ((u32)i - a - lr);
+    const u32 r = sp >= cstart[2 * lo + 1] ? 2 * lo + 1 : 2 * lo;
+    const u32 d = dest[r];
+    const u64 kk = sp - cstart[r];
+    const u64 id = key[k] & 0xFFFFFFFFull;
+    if (d & 0x80000000u)
+      next_work[(u64)(d & 0x7FFFFFFFu) + kk] = id;
+    else
+      final_keys[(u64)d + kk] = id;
+    if (left) ++L;
+  }
 }
 
 __global__ __launch_bounds__(256) void hc_iota_mod_kernel(u64* keys, u64 n, u64 total) {
@@ -728,19 +779,19 @@ struct HcCtx {
   const unsigned char* pts = nullptr;
   u32 Ls = 0, s = 0, l = 0;
   u64 seed = 0;
-  DevBuf final_keys, work[3], hist, segbuf, first, leafvec, leafnorm, leaf_off, knn_pos, knn_d, pair_cnt, leaf_list;
+  DevBuf final_keys, work[2], segbuf, routebuf, tilebuf, first, leafvec, leafnorm, leaf_off, knn_pos, knn_d, pair_cnt, leaf_list;
   u64 pair_cnt_cap = 0;
-  u64 hist_entries = 0, seg_words = 0;
+  u64 seg_words = 0;
   std::vector<u32> h_first;
   int alloc() {
     HIP_TRY(final_keys.alloc(N * 8));
     for (auto& k : work) HIP_TRY(k.alloc(N * 8));
-    hist_entries = radix_hist_entries(N);
-    HIP_TRY(hist.alloc(hist_entries * 4));
     // nodes that split at one level: each holds more than Ls points
     const u64 nact = N / ((u64)Ls + 1) + G + 1;
     seg_words = 8 * nact + 16;
     HIP_TRY(segbuf.alloc(seg_words * 4));
+    HIP_TRY(routebuf.alloc(seg_words * 4));
+    HIP_TRY(tilebuf.alloc((N / SP_TILE + 4) * 4));
     HIP_TRY(first.alloc((2 * nact + 2) * 4));
     HIP_TRY(leafvec.alloc(N * lv_stride));
     HIP_TRY(leafnorm.alloc((N + 64) * 4));
@@ -784,7 +835,7 @@ int hc_partition(HcCtx& X, u32 tree0, u32 G, std::vector<Leaf>& leaves, hipStrea
     for (u32 j = 0; j < nact; ++j) {
       const Seg& sg = act[j];
       woff[j] = (u32)sg.woff;
-      base[j] = 2 * j;
+      base[j] = 0;  // the side is all the key carries: 0 left, 1 right
       if (sg.depth < HC_MAX_DEPTH) {
         const u64 k = 2 * (((u64)sg.tree << 40) + sg.node);
         const u64 i1 = mulhi64(stream_output(X.seed, k), sg.cnt);
@@ -797,7 +848,7 @@ int hc_partition(HcCtx& X, u32 tree0, u32 G, std::vector<Leaf>& leaves, hipStrea
     woff[nact] = (u32)m;
     u32* d_seg = X.segbuf.as<u32>();
     HIP_TRY(hipMemcpyAsync(d_seg, up.data(), up.size() * 4, hipMemcpyHostToDevice, st));
-    const u32 grid_m = (u32)((m + 255) / 256), grid_8m = (u32)((m * 8 + 255) / 256);
+    const u32 grid_8m = (u32)((m * 8 + 255) / 256);
 #define HC_SIDE(KERNEL)                                                                                                  \
   hipLaunchKernelGGL(KERNEL, dim3(grid_8m), dim3(256), 0, st, X.pts, X.row_bytes, X.work[0].as<u64>(), m, d_seg, nact, \
                      d_seg + nact + 1, d_seg + 2 * nact + 1, d_seg + 3 * nact + 1, X.work[1].as<u64>())
@@ -811,15 +862,18 @@ int hc_partition(HcCtx& X, u32 tree0, u32 G, std::vector<Leaf>& leaves, hipStrea
       HC_SIDE(hc_side_kernel<false>);
 #undef HC_SIDE
     HIP_TRY(hipGetLastError());
-    HIP_TRY(radix_sort_edges(X.work[1].as<u64>(), X.work[2].as<u64>(), X.hist.as<u32>(), X.hist_entries, m,
-                             bits_to_hold(2ull * nact), st));
-    HIP_TRY(hipMemsetAsync(X.first.p, 0xFF, ((size_t)2 * nact + 1) * 4, st));
-    hipLaunchKernelGGL(hc_bounds_kernel, dim3(grid_m), dim3(256), 0, st, X.work[1].as<u64>(), m, X.first.as<u32>());
+    // left points per tile, their running sums, and L at every node boundary
+    const u32 ntiles = (u32)((m + SP_TILE - 1) / SP_TILE);
+    u32* d_tile = X.tilebuf.as<u32>();
+    u32* d_Lb = X.first.as<u32>();
+    hipLaunchKernelGGL(hc_count_left_kernel, dim3(ntiles), dim3(256), 0, st, X.work[1].as<u64>(), m, d_tile);
+    hipLaunchKernelGGL(uq_scan_kernel, dim3(1), dim3(1024), 0, st, d_tile, ntiles);
+    hipLaunchKernelGGL(hc_seg_left_kernel, dim3(nact + 1), dim3(64), 0, st, X.work[1].as<u64>(), m, d_seg, d_tile, d_Lb);
     HIP_TRY(hipGetLastError());
-    X.h_first.resize((size_t)2 * nact);
-    HIP_TRY(hipMemcpyAsync(X.h_first.data(), X.first.p, (size_t)2 * nact * 4, hipMemcpyDeviceToHost, st));
+    X.h_first.resize((size_t)nact + 1);
+    HIP_TRY(hipMemcpyAsync(X.h_first.data(), d_Lb, ((size_t)nact + 1) * 4, hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
-    // the children: a stable sort by child index leaves every node in its range of the work array
+    // the children: the split leaves every node in its range of the work array
     next.clear();
     route.assign((size_t)4 * nact + 1, 0);  // cstart[2 nact + 1] | dest[2 nact]
     u32* cstart = route.data();
@@ -828,10 +882,11 @@ int hc_partition(HcCtx& X, u32 tree0, u32 G, std::vector<Leaf>& leaves, hipStrea
     for (u32 j = 0; j < nact; ++j) {
       const Seg& sg = act[j];
       u64 cl;
-      if (pos1[j] == HC_NONE || X.h_first[2 * j] == HC_NONE || X.h_first[2 * j + 1] == HC_NONE)
+      const u64 nl = X.h_first[j + 1] - X.h_first[j];
+      if (pos1[j] == HC_NONE || nl == 0 || nl == sg.cnt)
         cl = (sg.cnt + 1) / 2;  // too deep, or nothing separated: the order is cut in the middle
       else
-        cl = X.h_first[2 * j + 1] - sg.woff;
+        cl = nl;
       const u64 ccnt[2] = {cl, sg.cnt - cl};
       const u64 cgo[2] = {sg.goff, sg.goff + cl};
       const u64 cws[2] = {sg.woff, sg.woff + cl};
@@ -848,9 +903,10 @@ int hc_partition(HcCtx& X, u32 tree0, u32 G, std::vector<Leaf>& leaves, hipStrea
       }
     }
     cstart[2 * nact] = (u32)m;
-    HIP_TRY(hipMemcpyAsync(d_seg, route.data(), route.size() * 4, hipMemcpyHostToDevice, st));
-    hipLaunchKernelGGL(hc_route_kernel, dim3(grid_m), dim3(256), 0, st, X.work[1].as<u64>(), m, d_seg, d_seg + 2 * nact + 1,
-                       2 * nact, X.final_keys.as<u64>(), X.work[0].as<u64>());
+    u32* d_route = X.routebuf.as<u32>();
+    HIP_TRY(hipMemcpyAsync(d_route, route.data(), route.size() * 4, hipMemcpyHostToDevice, st));
+    hipLaunchKernelGGL(hc_split_route_kernel, dim3(ntiles), dim3(256), 0, st, X.work[1].as<u64>(), m, d_seg, nact, d_Lb,
+                       d_tile, d_route, d_route + 2 * nact + 1, X.final_keys.as<u64>(), X.work[0].as<u64>());
     HIP_TRY(hipGetLastError());
     // (the next level's upload into the same buffer is ordered behind this kernel on the stream,
     // but the host vectors it comes from must not change before the copy has been staged)
