@@ -60,15 +60,19 @@ __global__ __launch_bounds__(256) void hc_side_kernel(const unsigned char* pts, 
   const u32 sub = (u32)t & 7u;
   if (i >= n) return;
   const u32 id = (u32)keys_in[i];
+  // the node of position i: found once per wavefront for its first position (a uniform search
+  // that the scalar unit runs), then a step or two forward for the later positions
+  const u64 i0 = __builtin_amdgcn_readfirstlane((u32)(i >> 32)) * (1ull << 32) + __builtin_amdgcn_readfirstlane((u32)i);
   u32 lo = 0, hi = nseg;
   while (hi - lo > 1) {
     const u32 mid = (lo + hi) >> 1;
-    if ((u64)off[mid] <= i)
+    if ((u64)off[mid] <= i0)
       lo = mid;
     else
       hi = mid;
   }
-  const u32 seg = lo;
+  u32 seg = lo;
+  while ((u64)off[seg + 1] <= i) ++seg;
   u32 idx = base[seg];
   const u32 p1 = pos1[seg];
   if (p1 != HC_NONE) {
@@ -263,15 +267,19 @@ __global__ __launch_bounds__(256) void hc_side_f32_kernel(const unsigned char* p
   const u32 sub = (u32)t & 7u;
   if (i >= n) return;
   const u32 id = (u32)keys_in[i];
+  // the node of position i: found once per wavefront for its first position (a uniform search
+  // that the scalar unit runs), then a step or two forward for the later positions
+  const u64 i0 = __builtin_amdgcn_readfirstlane((u32)(i >> 32)) * (1ull << 32) + __builtin_amdgcn_readfirstlane((u32)i);
   u32 lo = 0, hi = nseg;
   while (hi - lo > 1) {
     const u32 mid = (lo + hi) >> 1;
-    if ((u64)off[mid] <= i)
+    if ((u64)off[mid] <= i0)
       lo = mid;
     else
       hi = mid;
   }
-  const u32 seg = lo;
+  u32 seg = lo;
+  while ((u64)off[seg + 1] <= i) ++seg;
   u32 idx = base[seg];
   const u32 p1 = pos1[seg];
   if (p1 != HC_NONE) {
@@ -728,18 +736,22 @@ __global__ __launch_bounds__(256) void hc_split_route_kernel(const u64* keys, u6
     __syncthreads();
   }
   u32 L = tile_off[blockIdx.x] + (t ? pre[t - 1] : 0u);  // left points before position base
-  for (u32 k = 0; k < 8; ++k) {
-    const u64 i = base + k;
-    if (i >= m) break;
-    const bool left = (u32)(key[k] >> 32) == 0u;
-    u32 lo = 0, hi = nact;
+  u32 lo = 0;
+  if (base < m) {  // the node of the thread's first position; its other seven are a step away
+    u32 hi = nact;
     while (hi - lo > 1) {
       const u32 mid = (lo + hi) >> 1;
-      if ((u64)woff[mid] <= i)
+      if ((u64)woff[mid] <= base)
         lo = mid;
       else
         hi = mid;
     }
+  }
+  for (u32 k = 0; k < 8; ++k) {
+    const u64 i = base + k;
+    if (i >= m) break;
+    const bool left = (u32)(key[k] >> 32) == 0u;
+    while ((u64)woff[lo + 1] <= i) ++lo;
     const u32 a = woff[lo], La = Lb[lo], nl = Lb[lo + 1] - La;
     const u32 lr = L - La;
     const u32 sp = left ? a + lr : a + nl + ((u32)i - a - lr);

@@ -76,7 +76,7 @@ __global__ __launch_bounds__(256) void plan_kernel(MergeArgs a) {
       } else {
         const u32 fresh = deg - clean + cnt;
         if (a.force_prune)
-          kind = 2;  // short rows that the other two paths were not written for (they never append)
+          kind = (a.gram_ok && deg + cnt <= a.gram_tmax) ? 1 : 2;  // (the fast path presumes a clean prefix)
         else if (clean <= 64 && fresh <= a.fast_amax)
           kind = 0;
         else if (a.gram_ok && deg + cnt <= a.gram_tmax)
