@@ -265,6 +265,17 @@ int ann_hnsw_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dty
                    uint32_t m, uint32_t efc, float alpha, uint64_t seed, const ann_hnsw_opts* opts,
                    void* stream, ann_hnsw** out);
 
+/* Streaming insertion into the layered index: it takes in the points
+ * n..n_total-1 the way ann_insert_points does for the flat graph (the build's
+ * schedule carried on, BatchInsert per layer).  A new point's level follows
+ * the index's rule (the seed given to ann_hnsw_build; 0 for an index from
+ * ann_hnsw_from_host) but is at most the index's highest layer, whose entry
+ * point stays.  opts: batch_cap, order (n_total - n new ids), level (n_total -
+ * n levels, in place of the rule), max_rounds.  seed drives the order.  Every
+ * batch waits on the host once; blocks until done.                           */
+int ann_hnsw_insert_points(ann_hnsw* h, const void* points_dev, uint64_t n_total, uint32_t efc, float alpha,
+                           uint64_t seed, const ann_hnsw_opts* opts, void* stream);
+
 /* Wraps an index given on the host: level_host (n), the entry point (a point
  * of the highest level), and rows_host[l] for l = 0..max level, each n x
  * (l ? m : 2m) adjacency rows of point ids, ANN_NONE padded (the rows of

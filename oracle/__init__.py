@@ -502,6 +502,35 @@ def hnsw_insert_batch(ds: Dataset, h: Hnsw, batch: np.ndarray, efc: int, alpha: 
         raise RuntimeError(f"vo_hnsw_insert_batch rc={rc}")
 
 
+def hnsw_insert_points(ds: Dataset, h: Hnsw, efc: int, alpha: float, seed: int = 1, level_seed: int = 1,
+                       theta: int = 0, order: np.ndarray | None = None, level: np.ndarray | None = None,
+                       max_rounds: int = 0, threads: int = 1) -> Hnsw:
+    """Streams the points h.n .. ds.n-1 into the index: levels by the index's rule (or given),
+    capped at its highest layer; order and batches as insert_points; one hnsw_insert_batch per
+    batch.  Returns the grown index."""
+    n_old, n = h.level.shape[0], ds.n
+    m_new = n - n_old
+    if level is None:
+        level = np.array([hnsw_level(level_seed, i, h.m) for i in range(n_old, n)], np.uint32)
+    level = np.minimum(np.asarray(level, np.uint32), h.top).astype(np.uint32)
+    layers = []
+    for l, a in enumerate(h.layers):
+        b = np.full((n, a.shape[1]), NONE, np.uint32)
+        b[:n_old] = a
+        layers.append(b)
+    out = Hnsw(h.m, np.concatenate([h.level, level]), layers, h.entry)
+    if order is None:
+        order = new_points_order(n_old, m_new, seed)
+    order = np.ascontiguousarray(order, dtype=np.uint32)
+    assert sorted(order.tolist()) == list(range(n_old, n))
+    bounds = schedule_from(n_old - 1, m_new, theta if theta else max(1, n // 50)).astype(np.int64)
+    for r in range(len(bounds) - 1):
+        if max_rounds and r >= max_rounds:
+            break
+        hnsw_insert_batch(ds, out, order[bounds[r]:bounds[r + 1]], efc, alpha, threads=threads)
+    return out
+
+
 def hnsw_search_batch(ds: Dataset, h: Hnsw, queries: np.ndarray, k: int, L: int, eps: float = -1.0,
                       threads: int = 1, stats: Stats | None = None):
     """Returns (ids, dists, layer-0 start vertex of every query)."""

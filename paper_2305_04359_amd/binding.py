@@ -67,7 +67,7 @@ EXPORTS = [
     "ann_build", "ann_insert_batch", "ann_insert_points", "ann_graph_reserve", "ann_search", "ann_search_eps", "ann_start_vertex", "ann_graph_from_host",
     "ann_graph_copy_neighbors", "ann_graph_device_rows", "ann_graph_info", "ann_get_stats",
     "ann_graph_free", "ann_sort_edges", "ann_last_error",
-    "ann_hnsw_build", "ann_hnsw_from_host", "ann_hnsw_search", "ann_hnsw_info", "ann_hnsw_copy_levels", "ann_hnsw_layer_size",
+    "ann_hnsw_build", "ann_hnsw_insert_points", "ann_hnsw_from_host", "ann_hnsw_search", "ann_hnsw_info", "ann_hnsw_copy_levels", "ann_hnsw_layer_size",
     "ann_hnsw_copy_layer", "ann_hnsw_get_stats", "ann_hnsw_free",
     "ann_hcnng_build", "ann_hcnng_tree_edges",
 ]
@@ -121,6 +121,8 @@ def lib():
         L.ann_hnsw_build.restype = C.c_int
         L.ann_hnsw_build.argtypes = [vp, u64, u32, C.c_int, C.c_int, u32, u32, C.c_float, u64,
                                      C.POINTER(HnswOpts), vp, C.POINTER(vp)]
+        L.ann_hnsw_insert_points.restype = C.c_int
+        L.ann_hnsw_insert_points.argtypes = [vp, vp, u64, u32, C.c_float, u64, C.POINTER(HnswOpts), vp]
         L.ann_hnsw_from_host.restype = C.c_int
         L.ann_hnsw_from_host.argtypes = [vp, u64, u32, C.c_int, C.c_int, u32, vp, u32, C.POINTER(vp), vp,
                                          C.POINTER(vp)]
@@ -396,6 +398,26 @@ def ann_hnsw_build(points, m, efc, alpha, seed=1, metric=L2SQ, batch_cap=0, orde
     _check(lib().ann_hnsw_build(points.data_ptr(), points.shape[0], points.shape[1], _dtype_code(points),
                                 int(metric), m, efc, float(alpha), seed, C.byref(o), _stream_ptr(), C.byref(h)))
     return Hnsw(h.value)
+
+
+def ann_hnsw_insert_points(index: Hnsw, points, efc, alpha, seed=1, batch_cap=0, order=None, level=None,
+                           max_rounds=0) -> None:
+    """Streams the rows of `points` beyond the index's current size into the layered index."""
+    points = _dev2d(points, "points")
+    n_new = points.shape[0] - index.info().n
+    o = HnswOpts()
+    o.batch_cap = batch_cap
+    o.max_rounds = max_rounds
+    keep = []
+    for name, arr in (("order", order), ("level", level)):
+        if arr is not None:
+            a = np.ascontiguousarray(arr, dtype=np.uint32)
+            if a.shape != (n_new,):
+                raise ValueError(f"{name} must hold one entry per new point")
+            keep.append(a)
+            setattr(o, name, a.ctypes.data)
+    _check(lib().ann_hnsw_insert_points(index.handle, points.data_ptr(), points.shape[0], efc, float(alpha), seed,
+                                        C.byref(o), _stream_ptr()))
 
 
 def ann_hnsw_from_host(points, m, level, entry, layers, metric=L2SQ) -> Hnsw:

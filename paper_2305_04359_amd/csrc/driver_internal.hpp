@@ -203,6 +203,8 @@ struct StartsArgs {
 
 int new_graph(u64 n, u32 d, int dtype, int metric, u32 R, ann_graph** out);
 int check_insert_params(const ann_graph* g, uint32_t L, float alpha);
+// the graph gets the vertices n..n_total-1, with empty rows (its arrays grow when they have to)
+int grow_graph(ann_graph* g, u64 n_total, hipStream_t st);
 int resolve_points(const ann_graph* g, const void* points_dev, hipStream_t st, const void** out);
 int resolve_queries(const ann_graph* g, const void* queries_dev, u64 nq, hipStream_t st, const void** out);
 int graph_scratch(ann_graph* g, u64 b, u32 L, hipStream_t st, BatchScratch** out);

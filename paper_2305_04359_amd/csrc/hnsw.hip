@@ -26,6 +26,7 @@ struct ann_hnsw {
   u32 top = 0;
   u32 entry = 0;  // global id
   u64 rounds = 0;
+  u64 level_seed = 0;  // levels are a function of this seed and the point's id
   std::vector<u32> level;             // host, n
   std::vector<ann_graph*> layer;      // 0..top
   std::vector<std::vector<u32>> ids;  // ids[l], l >= 1: global ids of the layer's vertices, ascending
@@ -170,105 +171,18 @@ int make_walk(ann_hnsw* h, hipStream_t st) {
   return ANN_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-void ann_hnsw_free(ann_hnsw* h) { free_hnsw(h); }
-
-int ann_hnsw_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric, uint32_t m,
-                   uint32_t efc, float alpha, uint64_t seed, const ann_hnsw_opts* opts, void* stream,
-                   ann_hnsw** out) {
-  if (out) *out = nullptr;
-  if (!points_dev || !out) return fail(ANN_EINVAL, "null argument");
-  if (m < 2 || m > 256) return fail(ANN_EINVAL, "m must be in [2, 256]");
-  if (n < 1 || n >= (1ull << 31)) return fail(ANN_EINVAL, "n must be in [1, 2^31)");
-  ann_hnsw_opts o{};
-  if (opts) o = *opts;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-
-  ann_hnsw* h = new (std::nothrow) ann_hnsw();
-  if (!h) return fail(ANN_ENOMEM, "host allocation failed");
-  struct Guard {
-    ann_hnsw* h;
-    ~Guard() { free_hnsw(h); }
-  } guard{h};
-  h->n = n;
-  h->d = d;
-  h->m = m;
-  h->dtype = dtype;
-  h->metric = metric;
-
-  // levels (several host threads: a hundred million draws take a third of a second on one)
-  h->level.resize(n);
-  if (o.level) {
-    for (u64 i = 0; i < n; ++i) {
-      if (o.level[i] > 63) return fail(ANN_EINVAL, "levels must be at most 63");
-      h->level[i] = o.level[i];
-    }
-  } else {
-    const unsigned nt = n < 200000 ? 1u : 8u;
-    std::vector<std::thread> workers;
-    u32* lv = h->level.data();
-    for (unsigned t = 0; t < nt; ++t)
-      workers.emplace_back([=] {
-        for (u64 i = n * t / nt; i < n * (t + 1) / nt; ++i) lv[i] = level_of(level_draw(seed, i), m);
-      });
-    for (auto& w : workers) w.join();
-  }
-  // entry point: highest level, smallest id
-  h->entry = 0;
-  for (u64 i = 1; i < n; ++i)
-    if (h->level[i] > h->level[h->entry]) h->entry = (u32)i;
-  h->top = h->level[h->entry];
-  const u32 top = h->top;
-
-  // insertion order: the ids other than the entry point, shuffled as in ann_build
-  const u64 cnt = n - 1;
-  std::vector<u32> order(cnt ? cnt : 1);
-  if (o.order) {
-    std::vector<unsigned char> seen(n, 0);
-    for (u64 i = 0; i < cnt; ++i) {
-      const u32 id = o.order[i];
-      if (id >= n || id == h->entry || seen[id])
-        return fail(ANN_EINVAL, "order must list every id but the entry point once");
-      seen[id] = 1;
-      order[i] = id;
-    }
-  } else {
-    for (u64 i = 0; i < cnt; ++i) order[i] = (u32)i;
-    u64 state = seed;
-    for (u64 i = cnt; i-- > 1;) {
-      const u64 r = splitmix64(state);
-      const u64 j = (u64)(((unsigned __int128)r * (unsigned __int128)(i + 1)) >> 64);
-      const u32 t = order[i];
-      order[i] = order[j];
-      order[j] = t;
-    }
-    for (u64 i = 0; i < cnt; ++i) order[i] += order[i] >= h->entry ? 1u : 0u;
-  }
-
-  int rc = make_layers(h, points_dev, st);
-  if (rc) return rc;
-  rc = check_insert_params(h->layer[0], efc, alpha);
-  if (rc) return rc;
-  for (ann_graph* g : h->layer) g->collect = o.collect_stats != 0;
-
-  // schedule of Alg. 3
-  u64 theta = o.batch_cap ? o.batch_cap : (n / 50 > 1 ? n / 50 : 1);
-  if (theta * 2 * m >= (1ull << 32)) theta = ((1ull << 32) - 1) / (2 * m);
-  std::vector<u64> bounds{0};
-  u64 bmax = 1;
-  for (u64 done = 0; done < cnt;) {
-    u64 size = done + 2;
-    if (size > theta) size = theta;
-    if (size > cnt - done) size = cnt - done;
-    done += size;
-    bounds.push_back(done);
-    bmax = size > bmax ? size : bmax;
-  }
+// The batches bounds[r]..bounds[r+1] of `order` go into the index.  With may_restart the first
+// attempt runs without host waits and, if a search lost its visited list, every layer is emptied
+// and the run repeated with a host check in every batch (a build); without it the one run has
+// those checks (insertion into an index that cannot be started over).
+int run_batches(ann_hnsw* h, const void* points_dev, const std::vector<u32>& order, const std::vector<u64>& bounds,
+                u32 efc, float alpha, u64 max_rounds, bool collect, bool may_restart, hipStream_t st) {
+  const u32 top = h->top, m = h->m;
   const size_t nrounds = bounds.size() - 1;
-
+  const u64 cnt = bounds.back();
+  u64 bmax = 1;
+  for (size_t r = 0; r < nrounds; ++r) bmax = std::max(bmax, bounds[r + 1] - bounds[r]);
+  int rc = ANN_OK;
   // per layer l >= 1: the batch points that belong to it, batch after batch: their ids on that
   // layer and their positions in their batch
   std::vector<std::vector<u32>> ins_c(top + 1), ins_slot(top + 1);
@@ -337,7 +251,7 @@ int ann_hnsw_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dty
     }
   }
   PhaseTimer tm, tm_off;
-  rc = tm.init(o.collect_stats != 0);
+  rc = tm.init(collect);
   if (rc) return rc;
   (void)tm_off.init(false);
 
@@ -350,7 +264,7 @@ int ann_hnsw_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dty
     if (rc) return rc;
   }
 
-  for (int attempt = 0; attempt < 2; ++attempt) {
+  for (int attempt = may_restart ? 0 : 1; attempt < 2; ++attempt) {
     const bool sync = attempt == 1;
     // the second attempt waits on the host in every batch: one stream serves it
     hipStream_t up = sync ? st : us.s;
@@ -359,7 +273,7 @@ int ann_hnsw_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dty
       HIP_TRY(hipStreamWaitEvent(up, us.setup, 0));
     }
     for (size_t r = 0; r < nrounds; ++r) {
-      if (o.max_rounds && r >= o.max_rounds) break;
+      if (max_rounds && r >= max_rounds) break;
       const u64 lo = bounds[r], b = bounds[r + 1] - bounds[r];
       const int k = (int)(r % RING);
       u32* cur = cur_a[k].as<u32>();
@@ -419,11 +333,213 @@ int ann_hnsw_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dty
     h->rounds = 0;
   }
   if (rc) return rc;
+  return rc;
+}
+
+}  // namespace
+
+extern "C" {
+
+void ann_hnsw_free(ann_hnsw* h) { free_hnsw(h); }
+
+int ann_hnsw_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric, uint32_t m,
+                   uint32_t efc, float alpha, uint64_t seed, const ann_hnsw_opts* opts, void* stream,
+                   ann_hnsw** out) {
+  if (out) *out = nullptr;
+  if (!points_dev || !out) return fail(ANN_EINVAL, "null argument");
+  if (m < 2 || m > 256) return fail(ANN_EINVAL, "m must be in [2, 256]");
+  if (n < 1 || n >= (1ull << 31)) return fail(ANN_EINVAL, "n must be in [1, 2^31)");
+  ann_hnsw_opts o{};
+  if (opts) o = *opts;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  ann_hnsw* h = new (std::nothrow) ann_hnsw();
+  if (!h) return fail(ANN_ENOMEM, "host allocation failed");
+  struct Guard {
+    ann_hnsw* h;
+    ~Guard() { free_hnsw(h); }
+  } guard{h};
+  h->n = n;
+  h->d = d;
+  h->m = m;
+  h->dtype = dtype;
+  h->metric = metric;
+  h->level_seed = seed;
+
+  // levels (several host threads: a hundred million draws take a third of a second on one)
+  h->level.resize(n);
+  if (o.level) {
+    for (u64 i = 0; i < n; ++i) {
+      if (o.level[i] > 63) return fail(ANN_EINVAL, "levels must be at most 63");
+      h->level[i] = o.level[i];
+    }
+  } else {
+    const unsigned nt = n < 200000 ? 1u : 8u;
+    std::vector<std::thread> workers;
+    u32* lv = h->level.data();
+    for (unsigned t = 0; t < nt; ++t)
+      workers.emplace_back([=] {
+        for (u64 i = n * t / nt; i < n * (t + 1) / nt; ++i) lv[i] = level_of(level_draw(seed, i), m);
+      });
+    for (auto& w : workers) w.join();
+  }
+  // entry point: highest level, smallest id
+  h->entry = 0;
+  for (u64 i = 1; i < n; ++i)
+    if (h->level[i] > h->level[h->entry]) h->entry = (u32)i;
+  h->top = h->level[h->entry];
+
+  // insertion order: the ids other than the entry point, shuffled as in ann_build
+  const u64 cnt = n - 1;
+  std::vector<u32> order(cnt ? cnt : 1);
+  if (o.order) {
+    std::vector<unsigned char> seen(n, 0);
+    for (u64 i = 0; i < cnt; ++i) {
+      const u32 id = o.order[i];
+      if (id >= n || id == h->entry || seen[id])
+        return fail(ANN_EINVAL, "order must list every id but the entry point once");
+      seen[id] = 1;
+      order[i] = id;
+    }
+  } else {
+    for (u64 i = 0; i < cnt; ++i) order[i] = (u32)i;
+    u64 state = seed;
+    for (u64 i = cnt; i-- > 1;) {
+      const u64 r = splitmix64(state);
+      const u64 j = (u64)(((unsigned __int128)r * (unsigned __int128)(i + 1)) >> 64);
+      const u32 t = order[i];
+      order[i] = order[j];
+      order[j] = t;
+    }
+    for (u64 i = 0; i < cnt; ++i) order[i] += order[i] >= h->entry ? 1u : 0u;
+  }
+
+  int rc = make_layers(h, points_dev, st);
+  if (rc) return rc;
+  rc = check_insert_params(h->layer[0], efc, alpha);
+  if (rc) return rc;
+  for (ann_graph* g : h->layer) g->collect = o.collect_stats != 0;
+
+  // schedule of Alg. 3
+  u64 theta = o.batch_cap ? o.batch_cap : (n / 50 > 1 ? n / 50 : 1);
+  if (theta * 2 * m >= (1ull << 32)) theta = ((1ull << 32) - 1) / (2 * m);
+  std::vector<u64> bounds{0};
+  for (u64 done = 0; done < cnt;) {
+    u64 size = done + 2;
+    if (size > theta) size = theta;
+    if (size > cnt - done) size = cnt - done;
+    done += size;
+    bounds.push_back(done);
+  }
+  rc = run_batches(h, points_dev, order, bounds, efc, alpha, o.max_rounds, o.collect_stats != 0, /*may_restart=*/true, st);
+  if (rc) return rc;
   rc = make_walk(h, st);
   if (rc) return rc;
   guard.h = nullptr;
   *out = h;
   return ANN_OK;
+}
+
+int ann_hnsw_insert_points(ann_hnsw* h, const void* points_dev, uint64_t n_total, uint32_t efc, float alpha,
+                           uint64_t seed, const ann_hnsw_opts* opts, void* stream) {
+  if (!h || !points_dev) return fail(ANN_EINVAL, "null argument");
+  int rc = check_insert_params(h->layer[0], efc, alpha);
+  if (rc) return rc;
+  if (n_total < h->n) return fail(ANN_EINVAL, "n_total is below the number of points in the index");
+  if (n_total >= (1ull << 31)) return fail(ANN_EINVAL, "n must stay below 2^31");
+  ann_hnsw_opts o{};
+  if (opts) o = *opts;
+  const u64 n_old = h->n, mnew = n_total - n_old;
+  if (mnew == 0) return ANN_OK;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const u32 top = h->top, m = h->m, d = h->d;
+  const u64 esz = h->dtype == ANN_F32 ? 4 : 1;
+
+  // levels of the new points, by the index's own rule, none above the index's highest layer
+  std::vector<u32> lv(mnew);
+  for (u64 i = 0; i < mnew; ++i) {
+    u32 x = o.level ? o.level[i] : level_of(level_draw(h->level_seed, n_old + i), m);
+    lv[i] = x > top ? top : x;
+  }
+  // their order: as given, or shuffled like the ids of a build
+  std::vector<u32> order(mnew);
+  if (o.order) {
+    std::vector<unsigned char> seen(mnew, 0);
+    for (u64 i = 0; i < mnew; ++i) {
+      const u32 id = o.order[i];
+      if (id < n_old || id >= n_total || seen[id - n_old]) return fail(ANN_EINVAL, "order must list every new id once");
+      seen[id - n_old] = 1;
+      order[i] = id;
+    }
+  } else {
+    for (u64 i = 0; i < mnew; ++i) order[i] = (u32)(n_old + i);
+    u64 state = seed;
+    for (u64 i = mnew; i-- > 1;) {
+      const u64 r = splitmix64(state);
+      const u64 j = (u64)(((unsigned __int128)r * (unsigned __int128)(i + 1)) >> 64);
+      const u32 t = order[i];
+      order[i] = order[j];
+      order[j] = t;
+    }
+  }
+  // the build's schedule carried on
+  u64 theta = o.batch_cap ? o.batch_cap : (n_total / 50 > 1 ? n_total / 50 : 1);
+  if (theta * 2 * m >= (1ull << 32)) theta = ((1ull << 32) - 1) / (2 * m);
+  std::vector<u64> bounds{0};
+  for (u64 taken = 0; taken < mnew;) {
+    u64 size = (n_old - 1) + taken + 2;
+    if (size > theta) size = theta;
+    if (size > mnew - taken) size = mnew - taken;
+    taken += size;
+    bounds.push_back(taken);
+  }
+
+  // the layers grow: new members go behind the old ones (their ids are larger), so every vertex
+  // keeps its number on every layer
+  h->level.insert(h->level.end(), lv.begin(), lv.end());
+  rc = grow_graph(h->layer[0], n_total, st);
+  if (rc) return rc;
+  for (u32 l = 1; l <= top; ++l) {
+    std::vector<u32> fresh;
+    for (u64 i = 0; i < mnew; ++i)
+      if (lv[i] >= l) fresh.push_back((u32)(n_old + i));
+    if (fresh.empty()) continue;
+    std::vector<u32>& mine = h->ids[l];
+    const u64 nl0 = mine.size(), nl1 = nl0 + fresh.size();
+    std::vector<u32> dn(fresh.size());
+    for (size_t c = 0; c < fresh.size(); ++c) {
+      if (l == 1) {
+        dn[c] = fresh[c];
+      } else {
+        const std::vector<u32>& below = h->ids[l - 1];  // already grown
+        dn[c] = (u32)(std::lower_bound(below.begin(), below.end(), fresh[c]) - below.begin());
+      }
+    }
+    mine.insert(mine.end(), fresh.begin(), fresh.end());
+    rc = grow_graph(h->layer[l], nl1, st);
+    if (rc) return rc;
+    DevBuf npts, ndown, idsd;
+    HIP_TRY(npts.alloc(nl1 * d * esz));
+    HIP_TRY(ndown.alloc(nl1 * 4));
+    HIP_TRY(idsd.alloc(fresh.size() * 4));
+    HIP_TRY(hipMemcpyAsync(npts.p, h->pts[l].p, nl0 * d * esz, hipMemcpyDeviceToDevice, st));
+    HIP_TRY(hipMemcpyAsync(ndown.p, h->down[l].p, nl0 * 4, hipMemcpyDeviceToDevice, st));
+    HIP_TRY(hipMemcpyAsync(ndown.as<u32>() + nl0, dn.data(), dn.size() * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(idsd.p, fresh.data(), fresh.size() * 4, hipMemcpyHostToDevice, st));
+    const u64 bytes = fresh.size() * d * esz;
+    hipLaunchKernelGGL(gather_rows_kernel, dim3((u32)((bytes + 255) / 256)), dim3(256), 0, st,
+                       static_cast<const unsigned char*>(points_dev), idsd.as<u32>(), (u64)fresh.size(), (u32)(d * esz),
+                       npts.as<unsigned char>() + nl0 * d * esz);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipDeviceSynchronize());  // the old arrays may still be read; the host vectors go out of scope
+    h->pts[l] = std::move(npts);
+    h->down[l] = std::move(ndown);
+  }
+  h->n = n_total;
+  rc = make_walk(h, st);
+  if (rc) return rc;
+  return run_batches(h, points_dev, order, bounds, efc, alpha, o.max_rounds, h->layer[0]->collect, /*may_restart=*/false,
+                     st);
 }
 
 int ann_hnsw_from_host(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric, uint32_t m,

@@ -1135,3 +1135,60 @@ def test_hnsw_wide_layers(env, c1):
     ids, dists = A.ann_hnsw_search(h, pts, dev(torch, c1.queries), 10, 300)
     oi, od, _ = O.hnsw_search_batch(ds, oh, c1.queries, 10, 300, threads=0)
     assert (ids.cpu().numpy().view(np.uint32) == oi).all() and (dists.cpu().numpy() == od).all()
+
+
+def test_hnsw_insert_points(env, c1):
+    """Points streamed into the layered index: every layer identical to the oracle's after each
+    call; levels by the index's rule, capped; a build cut at a batch boundary and continued this
+    way is the one-shot build."""
+    torch, A, O = env
+    m, efc, alpha = 8, 40, 1.2
+    cuts = (5000, 7000, c1.n)
+    pts, qs = dev(torch, c1.points), dev(torch, c1.queries)
+    oh = O.hnsw_build(O.Dataset(c1.points[:cuts[0]], 0), m, efc, alpha, seed=5, threads=0)
+    h = A.ann_hnsw_build(pts[:cuts[0]], m, efc, alpha, seed=5)
+    _check_hnsw_against(h, oh, cuts[0])
+    for seed, n_tot in ((3, cuts[1]), (4, cuts[2])):
+        say(f"layered index: points up to {n_tot}")
+        ds = O.Dataset(c1.points[:n_tot], 0)
+        oh = O.hnsw_insert_points(ds, oh, efc, alpha, seed=seed, level_seed=5, threads=0)
+        A.ann_hnsw_insert_points(h, pts[:n_tot], efc, alpha, seed=seed)
+        assert h.info().n == n_tot
+        _check_hnsw_against(h, oh, n_tot)
+        ids, dists = A.ann_hnsw_search(h, pts[:n_tot], qs, 10, 40)
+        oi, od, _ = O.hnsw_search_batch(ds, oh, c1.queries, 10, 40, threads=0)
+        assert (ids.cpu().numpy().view(np.uint32) == oi).all() and (dists.cpu().numpy() == od).all()
+    # continuation of a build
+    n, theta = 4000, 250
+    rng = np.random.default_rng(3)
+    level = np.minimum(rng.geometric(0.7, n) - 1, 3).astype(np.uint32)
+    level[0] = 3
+    order = np.arange(1, n, dtype=np.uint32)
+    whole = A.ann_hnsw_build(pts[:n], m, efc, alpha, batch_cap=theta, level=level, order=order)
+    b = O.schedule(n - 1, theta).astype(np.int64)
+    n1 = int(b[10]) + 1
+    part = A.ann_hnsw_build(pts[:n1], m, efc, alpha, batch_cap=theta, level=level[:n1], order=order[:n1 - 1])
+    A.ann_hnsw_insert_points(part, pts[:n], efc, alpha, batch_cap=theta, order=order[n1 - 1:], level=level[n1:])
+    for l in range(4):
+        (ia, ra), (ib, rb) = whole.layer(l), part.layer(l)
+        assert (ia == ib).all() and (ra == rb).all()
+    # refused calls
+    with pytest.raises(A.AnnError):
+        A.ann_hnsw_insert_points(part, pts[:100], efc, alpha)
+    with pytest.raises(A.AnnError):
+        A.ann_hnsw_insert_points(part, pts[:n + 10], efc, alpha, order=np.arange(10, dtype=np.uint32))
+
+
+def test_hnsw_insert_points_padded_rows(env):
+    torch, A, O = env
+    w = W.c3(n=5000, nq=200)
+    oh = O.hnsw_build(O.Dataset(w.points[:3000], 0), 10, 40, 1.0, seed=2, threads=0)
+    pts = dev(torch, w.points)
+    h = A.ann_hnsw_build(pts[:3000], 10, 40, 1.0, seed=2)
+    ds = O.Dataset(w.points, 0)
+    oh = O.hnsw_insert_points(ds, oh, 40, 1.0, seed=8, level_seed=2, threads=0)
+    A.ann_hnsw_insert_points(h, pts, 40, 1.0, seed=8)
+    _check_hnsw_against(h, oh, w.n)
+    ids, dists = A.ann_hnsw_search(h, pts, dev(torch, w.queries), 10, 50)
+    oi, od, _ = O.hnsw_search_batch(ds, oh, w.queries, 10, 50, threads=0)
+    assert (ids.cpu().numpy().view(np.uint32) == oi).all() and (dists.cpu().numpy() == od).all()

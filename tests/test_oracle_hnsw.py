@@ -155,3 +155,36 @@ def test_quality(oracle, small):
     assert recall_at_k(ids0, gt) <= recall_at_k(ids, gt)
     ids_big, _, ent2 = oracle.hnsw_search_batch(ds, h, small.queries, 10, 40, eps=1000.0)
     assert (ids_big == ids).all() and (ent == ent2).all()
+
+
+def test_streaming_into_the_layered_index_continues_the_build(oracle, small):
+    """An index over all points, its build cut at a batch boundary, is the index over the points
+    before the cut with the rest streamed in (same levels, order and theta; ids in insertion
+    order so that a prefix of the order is a prefix of the ids)."""
+    n, m, efc, theta = 900, 5, 16, 60
+    pts = small.points[:n]
+    rng = np.random.default_rng(2)
+    level = np.minimum(rng.geometric(0.6, n) - 1, 3).astype(np.uint32)
+    level[0] = 3  # the entry point comes first
+    order = np.arange(1, n, dtype=np.uint32)
+    full = oracle.Dataset(pts, 0)
+    whole = oracle.hnsw_build(full, m, efc, 1.2, theta=theta, level=level, order=order)
+    assert whole.entry == 0 and whole.top == 3
+    b = oracle.schedule(n - 1, theta).astype(np.int64)
+    for r in (4, 9):
+        n_old = int(b[r]) + 1
+        head = oracle.hnsw_build(oracle.Dataset(pts[:n_old], 0), m, efc, 1.2, theta=theta, level=level[:n_old],
+                                 order=order[:n_old - 1])
+        grown = oracle.hnsw_insert_points(full, head, efc, 1.2, theta=theta, order=order[n_old - 1:],
+                                          level=level[n_old:])
+        assert (grown.level == whole.level).all()
+        for l in range(whole.top + 1):
+            assert (grown.layers[l] == whole.layers[l]).all(), f"cut {r}, layer {l}"
+    # levels by the rule are capped at the index's highest layer
+    head = oracle.hnsw_build(oracle.Dataset(pts[:300], 0), 2, efc, 1.2, seed=4)
+    grown = oracle.hnsw_insert_points(full, head, efc, 1.2, seed=9, level_seed=4)
+    want = np.array([min(_level(4, i, 2), head.top) for i in range(300, n)])
+    assert (grown.level[300:] == want).all() and (grown.level[:300] == head.level).all()
+    for l, rows in enumerate(grown.layers):
+        assert (rows[grown.level < l] == NONE).all()
+        assert all(len(row_list(rows[v])) >= 1 for v in np.flatnonzero(grown.level >= l) if v != grown.entry)
