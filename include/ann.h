@@ -4,7 +4,9 @@
  * The library builds a Vamana/DiskANN-style proximity graph by deterministic
  * prefix-doubling batch insertion (Alg. 3 of the paper: batchBuild /
  * BatchInsert) and answers batched k-NN queries with greedy beam search
- * (Alg. 1).  Every step runs in hand-written HIP kernels on one GPU.
+ * (Alg. 1); with the same kernels it builds and searches the layered index of
+ * Sec. 4.2 and builds the clustering-based graph of Sec. 4.3 (both further
+ * down).  Every step runs in hand-written HIP kernels on one GPU.
  *
  * Conventions shared by all calls
  *   - "dev" pointers are HIP device pointers, "host" pointers are ordinary
