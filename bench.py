@@ -105,6 +105,9 @@ def main():
     ap.add_argument("--cpu-points", type=int, default=None,
                     help="instead: the oracle inserts only this many points of the last batch (large inputs)")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--filter-sweep", action="store_true",
+                    help="also build with several sizes of the search's visited filter (Sec. 4.5) and report "
+                         "the search time and distance evaluations of each")
     ap.add_argument("--progress", action="store_true", help="print the steps to stderr as they finish")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -284,6 +287,19 @@ def main():
                      "qps_at_recall_0.90": cbest[0.90], "qps_at_recall_0.95": cbest[0.95], "search_sweep": csweep}
         del gc
         say(f"clustering-based build: {cb[-1]:.1f} ms")
+    # the size of the visited filter (Sec. 4.5: a small lossy table beats an exact one): search
+    # time and evaluations of the build per table size; hash_bits = log2 of the size in words
+    filter_sweep = None
+    if args.filter_sweep:
+        filter_sweep = []
+        for hb in (0, 8, 9, 10, 11, 12, 13):
+            gf = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, metric=metric, collect_stats=True, hash_bits=hb)
+            sf = gf.stats()
+            filter_sweep.append({"hash_bits": hb if hb else "auto", "table_bytes": (4 << hb) if hb else None,
+                                 "ms_search": round(sf["ms_search"], 2), "ms_total": round(sf["ms_total"], 2),
+                                 "evals_per_search": round(sf["evals"] / max(1, sf["searches"]), 1)})
+            del gf
+            say(f"filter sweep: hash_bits={hb} search {sf['ms_search']:.1f} ms")
     ms_per_step = float(np.mean(step_ms))
     bms = float(np.mean(build_ms))
     points_per_s = w.n / (bms / 1e3)
@@ -335,6 +351,7 @@ def main():
         "qps_at_recall_0.95": {"L": L95, "eps": eps95, "recall": round(r95, 4),
                                "qps": round(qs.shape[0] / ms95 * 1e3, 1)},
         "search_sweep": sweep,
+        "filter_sweep": filter_sweep,
         "stream_insert": stream,
         "layered_index": layered,
         "clustering_based": clustered,
