@@ -308,6 +308,13 @@ def main():
     ms95, ids95 = time_search(torch, A, g, pts, qs, k, L95, eps=eps95)
     r90 = recall(ids90.cpu().numpy().view(np.uint32), gt)
     r95 = recall(ids95.cpu().numpy().view(np.uint32), gt)
+    # the workload's 10,000 queries are 1.2 waves per wave slot of the chip, so the figures above are
+    # the latency of two generations of searches; ten times the queries (the same ones, repeated)
+    # show the rate of a stream of queries
+    qs10 = qs.repeat(10, 1)
+    ms90x, _ = time_search(torch, A, g, pts, qs10, k, L90, reps=3, eps=eps90)
+    ms95x, _ = time_search(torch, A, g, pts, qs10, k, L95, reps=3, eps=eps95)
+    del qs10
 
     cpu = None
     distinct_frac = 1.0
@@ -350,6 +357,9 @@ def main():
                                "qps": round(qs.shape[0] / ms90 * 1e3, 1)},
         "qps_at_recall_0.95": {"L": L95, "eps": eps95, "recall": round(r95, 4),
                                "qps": round(qs.shape[0] / ms95 * 1e3, 1)},
+        "qps_stream_of_queries": {"queries": int(qs.shape[0]) * 10,
+                                  "at_recall_0.90": round(qs.shape[0] * 10 / ms90x * 1e3, 1),
+                                  "at_recall_0.95": round(qs.shape[0] * 10 / ms95x * 1e3, 1)},
         "search_sweep": sweep,
         "filter_sweep": filter_sweep,
         "stream_insert": stream,
