@@ -223,7 +223,7 @@ int ann_sort_edges(uint64_t* keys_dev, uint64_t count, uint32_t key_bits, void* 
 /* ------------------------------------------------------------------------
  * Layered index (Sec. 4.2, ParlayHNSW): layer l holds the points whose level
  * is at least l; every layer is built with the batch insertion of Alg. 3
- * ("batch insertion for each layer"); the degree bound is m above the bottom
+ * (one batch insertion per layer); the degree bound is m above the bottom
  * layer and 2m on it (appendix, parameter paragraph); prune is the alpha rule
  * of Sec. 4.1 on every layer.
  *   level of point i   with r = the (i+1)-th output of SplitMix64(seed): the

@@ -4,9 +4,9 @@
  * A plain CPU statement of the clustering-based builder of Sec. 4.3
  * (ParlayHCNNG) with the cluster trees of Sec. 3.2: T random cluster trees;
  * in every leaf a degree-bounded minimum spanning tree over the graph that
- * joins each point to its l nearest neighbours inside the leaf (the
- * "edge-restricted MST"); the union of all leaves' edges, pruned per point
- * with the alpha rule of Sec. 4.1.  Built on vo_distance and vo_prune of
+ * joins each point to its l nearest neighbours inside the leaf (a spanning
+ * tree restricted to those edges); the union of all leaves' edges, pruned
+ * per point with the alpha rule of Sec. 4.1.  Built on vo_distance and vo_prune of
  * vamana_oracle.h; shares no code with the HIP library.
  *
  * What the paper leaves open, as read here (the HIP library implements the

@@ -4,7 +4,7 @@
  * A plain CPU statement of the layered index of Sec. 4.2 (ParlayHNSW): a
  * hierarchy of graphs in which layer l holds the points whose level is at
  * least l, every layer built with the prefix-doubling batch insertion of
- * Alg. 3 ("batch insertion for each layer"), searched from the top with a
+ * Alg. 3 (one batch insertion per layer), searched from the top with a
  * beam of one down to layer 1 and with the full beam on layer 0.  It is
  * built on the primitives of vamana_oracle.h (greedy search, prune,
  * BatchInsert) and, like them, shares no code with the HIP library.
