@@ -13,6 +13,7 @@
 // At the end the arcs of all trees are sorted by (point, neighbour), repeated ones dropped, and
 // every point's neighbours pruned with the alpha rule of Sec. 4.1 by the re-prune kernel of the
 // flat graph's BatchInsert.
+#include <type_traits>
 #include <algorithm>
 
 #include "ann_device.hpp"
@@ -141,6 +142,17 @@ __global__ __launch_bounds__(256) void hc_gather_kernel(const unsigned char* pts
   if (sub == 0) leafnorm[i] = nn;
 }
 
+// Which leaf and which 32 queries of it a block of the nearest-neighbour kernels takes.  A leaf's
+// blocks all read the whole leaf, so they should run at the same time on one XCD and find it in
+// that XCD's L2: blocks go to the XCDs in turn, so block b belongs to XCD b % 8, and the blocks of
+// one XCD walk through the query tiles of a leaf before they move to the next leaf.
+__device__ inline bool knn_block(u32 nleaves, u32 ny, u32& leaf, u32& q0) {
+  const u32 xcd = blockIdx.x & 7u, k = blockIdx.x >> 3;
+  leaf = 8u * (k / ny) + xcd;
+  q0 = 32u * (k % ny);
+  return leaf < nleaves;
+}
+
 // The l nearest neighbours, inside its leaf, of each of 32 consecutive points of a leaf (block
 // (leaf, 32-point block), one wavefront).  Matrix-core tile: rows = 32 candidates, columns = the
 // 32 points; lane (half, col) then holds, for point col, the inner products with 16 of the 32
@@ -149,10 +161,12 @@ __global__ __launch_bounds__(256) void hc_gather_kernel(const unsigned char* pts
 // ascending; positions are relative to the leaf.
 template <int LCAP>
 __global__ __launch_bounds__(64) void hc_knn_kernel(const unsigned char* leafvec, const i32* leafnorm, u32 lv_stride,
-                                                    const u32* leaf_off, u32 l, unsigned short* knn_pos, i32* knn_d) {
-  const u32 off = leaf_off[blockIdx.x];
-  const u32 cnt = leaf_off[blockIdx.x + 1] - off;
-  const u32 q0 = blockIdx.y * 32u;
+                                                    const u32* leaf_off, u32 l, unsigned short* knn_pos, i32* knn_d,
+                                                    u32 nleaves, u32 ny) {
+  u32 leaf, q0;
+  if (!knn_block(nleaves, ny, leaf, q0)) return;
+  const u32 off = leaf_off[leaf];
+  const u32 cnt = leaf_off[leaf + 1] - off;
   if (q0 >= cnt) return;
   const int lane = threadIdx.x;
   const u32 half = (u32)lane >> 5, col = (u32)lane & 31u;
@@ -167,66 +181,93 @@ __global__ __launch_bounds__(64) void hc_knn_kernel(const unsigned char* leafvec
     const v4i_t y = *reinterpret_cast<const v4i_t*>(leafvec + (u64)(off + qrow) * lv_stride + 32u * kk + 16u * half);
     bq[ks] = ks < ksteps ? y : v4i_t{0, 0, 0, 0};
   }
-  u64 best[LCAP];
+  // A lane meets the candidates c0 + 8 (r / 4) + 4 half + r % 4: numbered c0 / 2 + r (below 512)
+  // they ascend with the candidate's position, and a squared distance of at most 128 bytes is
+  // below 2^23, so (distance << 9 | number) orders a lane's candidates like (distance, position)
+  // in one 32-bit word: an insertion step is a min and a max.
+  constexpr u32 K32_INF = 0xFFFFFFFFu;
+  u32 best32[LCAP];
 #pragma unroll
-  for (int i = 0; i < LCAP; ++i) best[i] = KEY_INF;
+  for (int i = 0; i < LCAP; ++i) best32[i] = K32_INF;
   // Candidates below the lane's worst kept key wait in a queue of the lane's own (LDS, one
   // column per lane) and are inserted when some lane's queue is full: the insertion code then
   // runs a few times per wave with most lanes busy, not once per candidate for one lane's sake.
-  constexpr u32 QCAP = 8;
-  __shared__ u64 pend[QCAP][64];
+  constexpr u32 QCAP = 24;  // a tile adds at most 16 per lane; drained once above 8
+  __shared__ u32 pend[QCAP][64];
   u32 pc = 0;
-  u64 worst = KEY_INF;
+  u32 worst = K32_INF;
   auto drain = [&]() {
-#pragma unroll
+#pragma unroll 1
     for (u32 i = 0; i < QCAP; ++i) {
       if (ballot(i < pc) == 0ull) break;
-      u64 key = i < pc ? pend[i][lane] : KEY_INF;
+      u32 key = i < pc ? pend[i][lane] : K32_INF;
 #pragma unroll
       for (int t = 0; t < LCAP; ++t) {
-        const u64 lo = key < best[t] ? key : best[t];
-        key = key < best[t] ? best[t] : key;
-        best[t] = lo;
+        const u32 hi = key > best32[t] ? key : best32[t];
+        best32[t] = key < best32[t] ? key : best32[t];
+        key = hi;
       }
     }
     pc = 0;
-    worst = best[LCAP - 1];
+    worst = best32[LCAP - 1];
   };
 
-  for (u32 c0 = 0; c0 < cnt; c0 += 32u) {
+  // the tile after the current one is requested before the current one is used
+  v4i_t av[4], cn[4];
+  auto request = [&](u32 c0, v4i_t (&a)[4], v4i_t (&nrm)[4]) {
     const u32 c = c0 + col;
     const u32 crow = c < cnt ? c : cnt - 1u;
-    v4i_t av[4];
 #pragma unroll
     for (u32 ks = 0; ks < 4; ++ks) {
       const u32 kk = ks < ksteps ? ks : ksteps - 1u;
-      av[ks] = *reinterpret_cast<const v4i_t*>(leafvec + (u64)(off + crow) * lv_stride + 32u * kk + 16u * half);
+      a[ks] = *reinterpret_cast<const v4i_t*>(leafvec + (u64)(off + crow) * lv_stride + 32u * kk + 16u * half);
     }
     // norms of this lane's 16 candidates: rows 8g + 4 half + 0..3, g = 0..3 (the array has a tail
     // of 64 entries, so reading past the leaf's end stays inside it)
-    v4i_t cn[4];
 #pragma unroll
-    for (u32 g = 0; g < 4; ++g) cn[g] = *reinterpret_cast<const v4i_t*>(leafnorm + off + c0 + 8u * g + 4u * half);
+    for (u32 g = 0; g < 4; ++g) nrm[g] = *reinterpret_cast<const v4i_t*>(leafnorm + off + c0 + 8u * g + 4u * half);
+  };
+  request(0, av, cn);
+  for (u32 c0 = 0; c0 < cnt; c0 += 32u) {
+    v4i_t av_next[4], cn_next[4];
+    const u32 cnext = c0 + 32u < cnt ? c0 + 32u : c0;  // (the last tile asks for itself again)
+    request(cnext, av_next, cn_next);
+    if (ballot(pc > QCAP - 16u) != 0ull) drain();  // room for this tile in every lane's queue
     v16i_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(av[ks], bq[ks], acc, 0, 0, 0);
+    // only the tile with the queries themselves and the leaf's last tile hold candidates to skip
+    auto scan = [&](auto checked) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const u32 cand = c0 + 8u * (r / 4) + 4u * half + (r % 4);
-      const i32 dd = qn + cn[r / 4][r % 4] - 2 * acc[r];
-      const u64 key = (cand < cnt && cand != q) ? (((u64)(u32)dd << 32) | cand) : KEY_INF;
-      const bool qual = key < worst;
-      if (ballot(qual) != 0ull) {
-        if (qual) {
-          pend[pc][lane] = key;
-          ++pc;
-        }
-        if (ballot(pc == QCAP) != 0ull) drain();
+      for (int r = 0; r < 16; ++r) {
+        const u32 cand = c0 + 8u * (r / 4) + 4u * half + (r % 4);
+        const i32 dd = qn + cn[r / 4][r % 4] - 2 * acc[r];
+        const bool valid = !decltype(checked)::value || (cand < cnt && cand != q);
+        const u32 key = valid ? (((u32)dd << 9) | ((c0 >> 1) + (u32)r)) : K32_INF;
+        // written in any case, kept when the count moves on: no lane is masked, no branch taken
+        pend[pc][lane] = key;
+        pc += key < worst ? 1u : 0u;
       }
+    };
+    if (c0 == q0 || c0 + 32u > cnt)
+      scan(std::true_type{});
+    else
+      scan(std::false_type{});
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      av[ks] = av_next[ks];
+      cn[ks] = cn_next[ks];
     }
   }
   drain();
-  // the other half of the candidates, from the partner lane
+  // back to (distance << 32 | position), then the other half of the candidates from the partner lane
+  u64 best[LCAP];
+#pragma unroll
+  for (int i = 0; i < LCAP; ++i) {
+    const u32 k = best32[i], nr = k & 511u;
+    const u32 cand = 32u * (nr >> 4) + 8u * ((nr & 15u) >> 2) + 4u * half + (nr & 3u);
+    best[i] = k == K32_INF ? KEY_INF : (((u64)(k >> 9) << 32) | cand);
+  }
   u64 other[LCAP];
 #pragma unroll
   for (int i = 0; i < LCAP; ++i) other[i] = (u64)__shfl_xor((unsigned long long)best[i], 32, 64);
@@ -344,10 +385,11 @@ __global__ __launch_bounds__(256) void hc_gather_f32_kernel(const unsigned char*
 template <int LCAP, bool MIPS>
 __global__ __launch_bounds__(64) void hc_knn_f32_kernel(const unsigned char* leafvec, const float* leafnorm,
                                                         u32 lv_stride, const u32* leaf_off, u32 l,
-                                                        unsigned short* knn_pos, i32* knn_d) {
-  const u32 off = leaf_off[blockIdx.x];
-  const u32 cnt = leaf_off[blockIdx.x + 1] - off;
-  const u32 q0 = blockIdx.y * 32u;
+                                                        unsigned short* knn_pos, i32* knn_d, u32 nleaves, u32 ny) {
+  u32 leaf, q0;
+  if (!knn_block(nleaves, ny, leaf, q0)) return;
+  const u32 off = leaf_off[leaf];
+  const u32 cnt = leaf_off[leaf + 1] - off;
   if (q0 >= cnt) return;
   const int lane = threadIdx.x;
   const u32 half = (u32)lane >> 5, col = (u32)lane & 31u;
@@ -359,12 +401,12 @@ __global__ __launch_bounds__(64) void hc_knn_f32_kernel(const unsigned char* lea
   u64 best[LCAP];
 #pragma unroll
   for (int i = 0; i < LCAP; ++i) best[i] = KEY_INF;
-  constexpr u32 QCAP = 8;
+  constexpr u32 QCAP = 24;  // a tile adds at most 16 per lane; drained once above 8
   __shared__ u64 pend[QCAP][64];
   u32 pc = 0;
   u64 worst = KEY_INF;
   auto drain = [&]() {
-#pragma unroll
+#pragma unroll 1
     for (u32 i = 0; i < QCAP; ++i) {
       if (ballot(i < pc) == 0ull) break;
       u64 key = i < pc ? pend[i][lane] : KEY_INF;
@@ -379,6 +421,7 @@ __global__ __launch_bounds__(64) void hc_knn_f32_kernel(const unsigned char* lea
     worst = best[LCAP - 1];
   };
   for (u32 c0 = 0; c0 < cnt; c0 += 32u) {
+    if (ballot(pc > QCAP - 16u) != 0ull) drain();  // room for this tile in every lane's queue
     const u32 c = c0 + col;
     const u32 crow = c < cnt ? c : cnt - 1u;
     const unsigned char* cp = leafvec + (u64)(off + crow) * lv_stride + 16u * half;
@@ -412,12 +455,9 @@ __global__ __launch_bounds__(64) void hc_knn_f32_kernel(const unsigned char* lea
       }
       const u64 key = (cand < cnt && cand != q) ? (((u64)dkey_from_float(dd) << 32) | cand) : KEY_INF;
       const bool qual = key < worst;
-      if (ballot(qual) != 0ull) {
-        if (qual) {
-          pend[pc][lane] = key;
-          ++pc;
-        }
-        if (ballot(pc == QCAP) != 0ull) drain();
+      if (qual) {
+        pend[pc][lane] = key;
+        ++pc;
       }
     }
   }
@@ -955,10 +995,11 @@ int hc_leaves(HcCtx& X, u32 G, const std::vector<Leaf>& leaves, u64* arcs, hipSt
     hipLaunchKernelGGL(hc_gather_kernel<false>, dim3(grid_8n), dim3(256), 0, st, X.pts, X.row_bytes, X.final_keys.as<u64>(),
                        N, X.lv_stride, X.leafvec.as<unsigned char>(), X.leafnorm.as<i32>());
   HIP_TRY(hipGetLastError());
-  const dim3 kgrid(nleaves, (u32)((maxc + 31) / 32));
+  const u32 kny = (u32)((maxc + 31) / 32);
+  const dim3 kgrid((u32)(((u64)nleaves + 7) / 8 * 8 * kny));
 #define HC_KNN(KERNEL, NORMT)                                                                                       \
   hipLaunchKernelGGL(KERNEL, kgrid, dim3(64), 0, st, X.leafvec.as<unsigned char>(), X.leafnorm.as<NORMT>(), X.lv_stride, \
-                     X.leaf_off.as<u32>(), X.l, X.knn_pos.as<unsigned short>(), X.knn_d.as<i32>())
+                     X.leaf_off.as<u32>(), X.l, X.knn_pos.as<unsigned short>(), X.knn_d.as<i32>(), (u32)nleaves, kny)
   if (X.is_f32 && X.is_mips) {
     if (X.l <= 10)
       HC_KNN((hc_knn_f32_kernel<10, true>), float);
