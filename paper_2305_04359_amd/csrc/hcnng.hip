@@ -47,6 +47,22 @@ u32 bits_to_hold(u64 count) {  // smallest b with 2^b - 1 >= count: indices belo
   return b;
 }
 
+// A wavefront of the side kernels takes SIDE_PER_WAVE consecutive positions, eight at a time
+// (eight lanes per point).  The node of its first position is found once, by a uniform search
+// that the scalar unit runs; the later positions step forward from there.
+constexpr u32 SIDE_PER_WAVE = 64;
+__device__ inline u32 side_first_node(const u32* off, u32 nseg, u64 w0) {
+  u32 lo = 0, hi = nseg;
+  while (hi - lo > 1) {
+    const u32 mid = (lo + hi) >> 1;
+    if ((u64)off[mid] <= w0)
+      lo = mid;
+    else
+      hi = mid;
+  }
+  return lo;
+}
+
 // One level of one tree.  keys_in[i] = (anything << 32) | id of the point at position i; the
 // nodes of the level are the position ranges off[s]..off[s+1].  A node that splits names the
 // positions of its two pivots; its points get child index base[s] (left: at most as far from the
@@ -56,55 +72,47 @@ template <bool SIGNED>
 __global__ __launch_bounds__(256) void hc_side_kernel(const unsigned char* pts, u32 row_bytes, const u64* keys_in, u64 n,
                                                       const u32* off, u32 nseg, const u32* pos1, const u32* pos2,
                                                       const u32* base, u64* keys_out) {
-  const u64 t = (u64)blockIdx.x * blockDim.x + threadIdx.x;
-  const u64 i = t >> 3;
-  const u32 sub = (u32)t & 7u;
-  if (i >= n) return;
-  const u32 id = (u32)keys_in[i];
-  // the node of position i: found once per wavefront for its first position (a uniform search
-  // that the scalar unit runs), then a step or two forward for the later positions
-  const u64 i0 = __builtin_amdgcn_readfirstlane((u32)(i >> 32)) * (1ull << 32) + __builtin_amdgcn_readfirstlane((u32)i);
-  u32 lo = 0, hi = nseg;
-  while (hi - lo > 1) {
-    const u32 mid = (lo + hi) >> 1;
-    if ((u64)off[mid] <= i0)
-      lo = mid;
-    else
-      hi = mid;
-  }
-  u32 seg = lo;
-  while ((u64)off[seg + 1] <= i) ++seg;
-  u32 idx = base[seg];
-  const u32 p1 = pos1[seg];
-  if (p1 != HC_NONE) {
-    const u32 ida = (u32)keys_in[p1], idb = (u32)keys_in[pos2[seg]];
-    const uint4* x = reinterpret_cast<const uint4*>(pts + (u64)id * row_bytes);
-    const uint4* a = reinterpret_cast<const uint4*>(pts + (u64)ida * row_bytes);
-    const uint4* b = reinterpret_cast<const uint4*>(pts + (u64)idb * row_bytes);
-    i32 xa = 0, xb = 0, aa = 0, bb = 0;
-    for (u32 pc = sub; pc < row_bytes / 16; pc += 8) {
-      const uint4 vx = x[pc], va = a[pc], vb = b[pc];
-      const u32 wx[4] = {vx.x, vx.y, vx.z, vx.w}, wa[4] = {va.x, va.y, va.z, va.w}, wb[4] = {vb.x, vb.y, vb.z, vb.w};
+  const u32 sub = threadIdx.x & 7u, grp = (threadIdx.x >> 3) & 7u;
+  const u64 w0 = ((u64)blockIdx.x * 4u + (u32)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6))) * SIDE_PER_WAVE;
+  if (w0 >= n) return;
+  u32 seg = side_first_node(off, nseg, w0);
+  for (u32 it = 0; it < SIDE_PER_WAVE / 8u; ++it) {
+    const u64 i = w0 + 8u * it + grp;
+    if (i >= n) break;
+    const u32 id = (u32)keys_in[i];
+    while ((u64)off[seg + 1] <= i) ++seg;
+    u32 idx = base[seg];
+    const u32 p1 = pos1[seg];
+    if (p1 != HC_NONE) {
+      const u32 ida = (u32)keys_in[p1], idb = (u32)keys_in[pos2[seg]];
+      const uint4* x = reinterpret_cast<const uint4*>(pts + (u64)id * row_bytes);
+      const uint4* a = reinterpret_cast<const uint4*>(pts + (u64)ida * row_bytes);
+      const uint4* b = reinterpret_cast<const uint4*>(pts + (u64)idb * row_bytes);
+      i32 xa = 0, xb = 0, aa = 0, bb = 0;
+      for (u32 pc = sub; pc < row_bytes / 16; pc += 8) {
+        const uint4 vx = x[pc], va = a[pc], vb = b[pc];
+        const u32 wx[4] = {vx.x, vx.y, vx.z, vx.w}, wa[4] = {va.x, va.y, va.z, va.w}, wb[4] = {vb.x, vb.y, vb.z, vb.w};
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        if constexpr (SIGNED) {
-          xa = __builtin_amdgcn_sdot4((i32)wx[k], (i32)wa[k], xa, false);
-          xb = __builtin_amdgcn_sdot4((i32)wx[k], (i32)wb[k], xb, false);
-          aa = __builtin_amdgcn_sdot4((i32)wa[k], (i32)wa[k], aa, false);
-          bb = __builtin_amdgcn_sdot4((i32)wb[k], (i32)wb[k], bb, false);
-        } else {
-          xa = (i32)__builtin_amdgcn_udot4(wx[k], wa[k], (u32)xa, false);
-          xb = (i32)__builtin_amdgcn_udot4(wx[k], wb[k], (u32)xb, false);
-          aa = (i32)__builtin_amdgcn_udot4(wa[k], wa[k], (u32)aa, false);
-          bb = (i32)__builtin_amdgcn_udot4(wb[k], wb[k], (u32)bb, false);
+        for (int k = 0; k < 4; ++k) {
+          if constexpr (SIGNED) {
+            xa = __builtin_amdgcn_sdot4((i32)wx[k], (i32)wa[k], xa, false);
+            xb = __builtin_amdgcn_sdot4((i32)wx[k], (i32)wb[k], xb, false);
+            aa = __builtin_amdgcn_sdot4((i32)wa[k], (i32)wa[k], aa, false);
+            bb = __builtin_amdgcn_sdot4((i32)wb[k], (i32)wb[k], bb, false);
+          } else {
+            xa = (i32)__builtin_amdgcn_udot4(wx[k], wa[k], (u32)xa, false);
+            xb = (i32)__builtin_amdgcn_udot4(wx[k], wb[k], (u32)xb, false);
+            aa = (i32)__builtin_amdgcn_udot4(wa[k], wa[k], (u32)aa, false);
+            bb = (i32)__builtin_amdgcn_udot4(wb[k], wb[k], (u32)bb, false);
+          }
         }
       }
+      // |x-a|^2 <= |x-b|^2  <=>  |a|^2 - 2<x,a> <= |b|^2 - 2<x,b>
+      const i32 lhs = group_sum(aa - 2 * xa), rhs = group_sum(bb - 2 * xb);
+      if (lhs > rhs) idx += 1;
     }
-    // |x-a|^2 <= |x-b|^2  <=>  |a|^2 - 2<x,a> <= |b|^2 - 2<x,b>
-    const i32 lhs = group_sum(aa - 2 * xa), rhs = group_sum(bb - 2 * xb);
-    if (lhs > rhs) idx += 1;
+    if (sub == 0) keys_out[i] = ((u64)idx << 32) | id;
   }
-  if (sub == 0) keys_out[i] = ((u64)idx << 32) | id;
 }
 
 // The vectors in leaf order, as int8 (uint8 data moved down by 128: distances do not change),
@@ -303,52 +311,44 @@ template <bool MIPS>
 __global__ __launch_bounds__(256) void hc_side_f32_kernel(const unsigned char* pts, u32 row_bytes, const u64* keys_in,
                                                           u64 n, const u32* off, u32 nseg, const u32* pos1,
                                                           const u32* pos2, const u32* base, u64* keys_out) {
-  const u64 t = (u64)blockIdx.x * blockDim.x + threadIdx.x;
-  const u64 i = t >> 3;
-  const u32 sub = (u32)t & 7u;
-  if (i >= n) return;
-  const u32 id = (u32)keys_in[i];
-  // the node of position i: found once per wavefront for its first position (a uniform search
-  // that the scalar unit runs), then a step or two forward for the later positions
-  const u64 i0 = __builtin_amdgcn_readfirstlane((u32)(i >> 32)) * (1ull << 32) + __builtin_amdgcn_readfirstlane((u32)i);
-  u32 lo = 0, hi = nseg;
-  while (hi - lo > 1) {
-    const u32 mid = (lo + hi) >> 1;
-    if ((u64)off[mid] <= i0)
-      lo = mid;
-    else
-      hi = mid;
-  }
-  u32 seg = lo;
-  while ((u64)off[seg + 1] <= i) ++seg;
-  u32 idx = base[seg];
-  const u32 p1 = pos1[seg];
-  if (p1 != HC_NONE) {
-    const u32 ida = (u32)keys_in[p1], idb = (u32)keys_in[pos2[seg]];
-    const float4* x = reinterpret_cast<const float4*>(pts + (u64)id * row_bytes);
-    const float4* a = reinterpret_cast<const float4*>(pts + (u64)ida * row_bytes);
-    const float4* b = reinterpret_cast<const float4*>(pts + (u64)idb * row_bytes);
-    float da = 0.0f, db = 0.0f;
-    for (u32 pc = sub; pc < row_bytes / 16; pc += 8) {
-      const float4 vx = x[pc], va = a[pc], vb = b[pc];
-      const float fx[4] = {vx.x, vx.y, vx.z, vx.w}, fa[4] = {va.x, va.y, va.z, va.w}, fb[4] = {vb.x, vb.y, vb.z, vb.w};
+  const u32 sub = threadIdx.x & 7u, grp = (threadIdx.x >> 3) & 7u;
+  const u64 w0 = ((u64)blockIdx.x * 4u + (u32)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6))) * SIDE_PER_WAVE;
+  if (w0 >= n) return;
+  u32 seg = side_first_node(off, nseg, w0);
+  for (u32 it = 0; it < SIDE_PER_WAVE / 8u; ++it) {
+    const u64 i = w0 + 8u * it + grp;
+    if (i >= n) break;
+    const u32 id = (u32)keys_in[i];
+    while ((u64)off[seg + 1] <= i) ++seg;
+    u32 idx = base[seg];
+    const u32 p1 = pos1[seg];
+    if (p1 != HC_NONE) {
+      const u32 ida = (u32)keys_in[p1], idb = (u32)keys_in[pos2[seg]];
+      const float4* x = reinterpret_cast<const float4*>(pts + (u64)id * row_bytes);
+      const float4* a = reinterpret_cast<const float4*>(pts + (u64)ida * row_bytes);
+      const float4* b = reinterpret_cast<const float4*>(pts + (u64)idb * row_bytes);
+      float da = 0.0f, db = 0.0f;
+      for (u32 pc = sub; pc < row_bytes / 16; pc += 8) {
+        const float4 vx = x[pc], va = a[pc], vb = b[pc];
+        const float fx[4] = {vx.x, vx.y, vx.z, vx.w}, fa[4] = {va.x, va.y, va.z, va.w}, fb[4] = {vb.x, vb.y, vb.z, vb.w};
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        if constexpr (MIPS) {
-          da = __builtin_fmaf(-fx[k], fa[k], da);
-          db = __builtin_fmaf(-fx[k], fb[k], db);
-        } else {
-          const float ea = fx[k] - fa[k], eb = fx[k] - fb[k];
-          da = __builtin_fmaf(ea, ea, da);
-          db = __builtin_fmaf(eb, eb, db);
+        for (int k = 0; k < 4; ++k) {
+          if constexpr (MIPS) {
+            da = __builtin_fmaf(-fx[k], fa[k], da);
+            db = __builtin_fmaf(-fx[k], fb[k], db);
+          } else {
+            const float ea = fx[k] - fa[k], eb = fx[k] - fb[k];
+            da = __builtin_fmaf(ea, ea, da);
+            db = __builtin_fmaf(eb, eb, db);
+          }
         }
       }
+      da = group_sum(da);
+      db = group_sum(db);
+      if (da > db) idx += 1;
     }
-    da = group_sum(da);
-    db = group_sum(db);
-    if (da > db) idx += 1;
+    if (sub == 0) keys_out[i] = ((u64)idx << 32) | id;
   }
-  if (sub == 0) keys_out[i] = ((u64)idx << 32) | id;
 }
 
 // vectors in leaf order (rows of lv_stride bytes, zero tail) and their squared norms
@@ -900,9 +900,9 @@ int hc_partition(HcCtx& X, u32 tree0, u32 G, std::vector<Leaf>& leaves, hipStrea
     woff[nact] = (u32)m;
     u32* d_seg = X.segbuf.as<u32>();
     HIP_TRY(hipMemcpyAsync(d_seg, up.data(), up.size() * 4, hipMemcpyHostToDevice, st));
-    const u32 grid_8m = (u32)((m * 8 + 255) / 256);
+    const u32 grid_side = (u32)((m + 4 * SIDE_PER_WAVE - 1) / (4 * SIDE_PER_WAVE));
 #define HC_SIDE(KERNEL)                                                                                                  \
-  hipLaunchKernelGGL(KERNEL, dim3(grid_8m), dim3(256), 0, st, X.pts, X.row_bytes, X.work[0].as<u64>(), m, d_seg, nact, \
+  hipLaunchKernelGGL(KERNEL, dim3(grid_side), dim3(256), 0, st, X.pts, X.row_bytes, X.work[0].as<u64>(), m, d_seg, nact, \
                      d_seg + nact + 1, d_seg + 2 * nact + 1, d_seg + 3 * nact + 1, X.work[1].as<u64>())
     if (X.is_f32 && X.is_mips)
       HC_SIDE(hc_side_f32_kernel<true>);
