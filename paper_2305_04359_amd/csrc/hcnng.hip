@@ -600,6 +600,16 @@ __global__ __launch_bounds__(64) void hc_kruskal_kernel(const u64* keys, const u
   __builtin_amdgcn_wave_barrier();
   u64* out = arcs + 2ull * (off - leaf);
   u32 accepted = 0;
+  // The accepted pairs wait in the lanes' registers, one per lane, and leave 64 at a time: the
+  // ids' loads then overlap, and none of them sits in the chain of dependent steps.
+  u32 mine = 0;
+  auto write_out = [&](u32 first, u32 count) {
+    if ((u32)lane < count) {
+      const u64 gu = keys[off + (mine >> 16)] & 0xFFFFFFFFull, gv = keys[off + (mine & 0xFFFFu)] & 0xFFFFFFFFull;
+      out[2 * (first + (u32)lane)] = (gu << 32) | gv;
+      out[2 * (first + (u32)lane) + 1] = (gv << 32) | gu;
+    }
+  };
   bool flat = true;  // every point stands directly under its root
   for (u32 c = 0; c < E && accepted < cnt - 1u; c += 64) {
     if (!flat) {
@@ -620,36 +630,46 @@ __global__ __launch_bounds__(64) void hc_kruskal_kernel(const u64* keys, const u
     const u32 u = pr >> 16, v = pr & 0xFFFFu;
     bool ok = e < E && !dup;
     if (ok) ok = deg[u] < s && deg[v] < s;
-    if (ok) ok = parent[u] != parent[v];  // flat: parents are roots
+    u32 pu = 0, pv = 0;  // the ends' roots as the chunk starts (flat: parents are roots)
+    if (ok) {
+      pu = parent[u];
+      pv = parent[v];
+      ok = pu != pv;
+    }
     u64 mask = ballot(ok);
     while (mask != 0ull) {
       const int j = __builtin_ctzll(mask);
       mask &= mask - 1ull;
-      // every lane repeats the same step on the same LDS words
+      // every lane repeats the same step on the same LDS words; the four reads a step starts
+      // with do not wait for one another, and only links made within this chunk add to them
       const u32 uu = readlane_u32(u, j), vv = readlane_u32(v, j);
-      if (deg[uu] < s && deg[vv] < s) {
-        u32 ru = uu, rv = vv;
-        while (parent[ru] != ru) ru = parent[ru];
-        while (parent[rv] != rv) rv = parent[rv];
+      u32 ru = readlane_u32(pu, j), rv = readlane_u32(pv, j);
+      const unsigned char du = deg[uu], dv = deg[vv];
+      u32 nu = parent[ru], nv = parent[rv];
+      if (du < s && dv < s) {
+        while (nu != ru) {
+          ru = nu;
+          nu = parent[ru];
+        }
+        while (nv != rv) {
+          rv = nv;
+          nv = parent[rv];
+        }
         if (ru != rv) {
           __builtin_amdgcn_wave_barrier();  // every lane has read before any lane writes
           parent[ru] = (unsigned short)rv;
-          const unsigned char du = deg[uu], dv = deg[vv];
-          __builtin_amdgcn_wave_barrier();
           deg[uu] = du + 1;
           deg[vv] = dv + 1;
-          if (lane == 0) {
-            const u64 gu = keys[off + uu] & 0xFFFFFFFFull, gv = keys[off + vv] & 0xFFFFFFFFull;
-            out[2 * accepted] = (gu << 32) | gv;
-            out[2 * accepted + 1] = (gv << 32) | gu;
-          }
+          if (lane == (int)(accepted & 63u)) mine = (uu << 16) | vv;
           ++accepted;
+          if ((accepted & 63u) == 0) write_out(accepted - 64u, 64u);
           flat = false;
         }
       }
       __builtin_amdgcn_wave_barrier();
     }
   }
+  write_out(accepted & ~63u, accepted & 63u);
 }
 
 // ---- repeated keys out of a sorted array --------------------------------------------------
