@@ -15,6 +15,9 @@
 // flat graph's BatchInsert.
 #include <type_traits>
 #include <algorithm>
+#include <chrono>
+#include <cstdio>
+#include <cstdlib>
 
 #include "ann_device.hpp"
 #include "driver_internal.hpp"
@@ -842,6 +845,23 @@ struct Leaf {
 
 // Everything one group of trees needs on the device.  The trees of a group are cut side by side:
 // tree g of the group owns the positions g*n .. (g+1)*n of every array.
+// Page-locked host memory: small copies to and from it are queued without a staging copy, and the
+// device reads it when the copy runs, so its contents must stay until then.
+struct HostBuf {
+  void* p = nullptr;
+  HostBuf() = default;
+  HostBuf(const HostBuf&) = delete;
+  HostBuf& operator=(const HostBuf&) = delete;
+  ~HostBuf() {
+    if (p) (void)hipHostFree(p);
+  }
+  hipError_t alloc(size_t bytes) { return hipHostMalloc(&p, bytes, hipHostMallocDefault); }
+  template <class T>
+  T* as() const {
+    return static_cast<T*>(p);
+  }
+};
+
 struct HcCtx {
   u64 n = 0, N = 0;  // points; positions of a full group
   u32 G = 1;
@@ -854,7 +874,7 @@ struct HcCtx {
   DevBuf final_keys, work[2], segbuf, routebuf, tilebuf, first, leafvec, leafnorm, leaf_off, knn_pos, knn_d, pair_cnt, leaf_list;
   u64 pair_cnt_cap = 0;
   u64 seg_words = 0;
-  std::vector<u32> h_first;
+  HostBuf h_up, h_route, h_first;  // a level's node table, its routing table, the left counts read back
   int alloc() {
     HIP_TRY(final_keys.alloc(N * 8));
     for (auto& k : work) HIP_TRY(k.alloc(N * 8));
@@ -863,6 +883,9 @@ struct HcCtx {
     seg_words = 8 * nact + 16;
     HIP_TRY(segbuf.alloc(seg_words * 4));
     HIP_TRY(routebuf.alloc(seg_words * 4));
+    HIP_TRY(h_up.alloc(seg_words * 4));
+    HIP_TRY(h_route.alloc(seg_words * 4));
+    HIP_TRY(h_first.alloc((2 * nact + 2) * 4));
     HIP_TRY(tilebuf.alloc((N / SP_TILE + 4) * 4));
     HIP_TRY(first.alloc((2 * nact + 2) * 4));
     HIP_TRY(leafvec.alloc(N * lv_stride));
@@ -894,13 +917,14 @@ int hc_partition(HcCtx& X, u32 tree0, u32 G, std::vector<Leaf>& leaves, hipStrea
   std::vector<Seg> act, next;
   for (u32 g = 0; g < G; ++g) act.push_back(Seg{(u64)g * n, n, 1, (u64)g * n, 0, tree0 + g});
   u64 m = N;
-  std::vector<u32> up, route;
   while (!act.empty()) {
     const u32 nact = (u32)act.size();
     if (8ull * nact + 16 > X.seg_words) return fail(ANN_EINTERNAL, "more splitting nodes than planned for");
     // woff[nact+1] | pos1[nact] | pos2[nact] | base[nact]
-    up.assign((size_t)4 * nact + 1, HC_NONE);
-    u32* woff = up.data();
+    // (the host tables are free again: the wait in the middle of the previous level came after
+    // this table's copy, and the routing table is not written before this level's wait)
+    u32* woff = X.h_up.as<u32>();
+    std::fill(woff, woff + (size_t)4 * nact + 1, HC_NONE);
     u32* pos1 = woff + nact + 1;
     u32* pos2 = pos1 + nact;
     u32* base = pos2 + nact;
@@ -919,7 +943,7 @@ int hc_partition(HcCtx& X, u32 tree0, u32 G, std::vector<Leaf>& leaves, hipStrea
     }
     woff[nact] = (u32)m;
     u32* d_seg = X.segbuf.as<u32>();
-    HIP_TRY(hipMemcpyAsync(d_seg, up.data(), up.size() * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(d_seg, woff, ((size_t)4 * nact + 1) * 4, hipMemcpyHostToDevice, st));
     const u32 grid_side = (u32)((m + 4 * SIDE_PER_WAVE - 1) / (4 * SIDE_PER_WAVE));
 #define HC_SIDE(KERNEL)                                                                                                  \
   hipLaunchKernelGGL(KERNEL, dim3(grid_side), dim3(256), 0, st, X.pts, X.row_bytes, X.work[0].as<u64>(), m, d_seg, nact, \
@@ -942,19 +966,18 @@ int hc_partition(HcCtx& X, u32 tree0, u32 G, std::vector<Leaf>& leaves, hipStrea
     hipLaunchKernelGGL(uq_scan_kernel, dim3(1), dim3(1024), 0, st, d_tile, ntiles);
     hipLaunchKernelGGL(hc_seg_left_kernel, dim3(nact + 1), dim3(64), 0, st, X.work[1].as<u64>(), m, d_seg, d_tile, d_Lb);
     HIP_TRY(hipGetLastError());
-    X.h_first.resize((size_t)nact + 1);
-    HIP_TRY(hipMemcpyAsync(X.h_first.data(), d_Lb, ((size_t)nact + 1) * 4, hipMemcpyDeviceToHost, st));
+    const u32* h_first = X.h_first.as<u32>();
+    HIP_TRY(hipMemcpyAsync(X.h_first.p, d_Lb, ((size_t)nact + 1) * 4, hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     // the children: the split leaves every node in its range of the work array
     next.clear();
-    route.assign((size_t)4 * nact + 1, 0);  // cstart[2 nact + 1] | dest[2 nact]
-    u32* cstart = route.data();
+    u32* cstart = X.h_route.as<u32>();  // cstart[2 nact + 1] | dest[2 nact]
     u32* dest = cstart + 2 * nact + 1;
     u64 nm = 0;
     for (u32 j = 0; j < nact; ++j) {
       const Seg& sg = act[j];
       u64 cl;
-      const u64 nl = X.h_first[j + 1] - X.h_first[j];
+      const u64 nl = h_first[j + 1] - h_first[j];
       if (pos1[j] == HC_NONE || nl == 0 || nl == sg.cnt)
         cl = (sg.cnt + 1) / 2;  // too deep, or nothing separated: the order is cut in the middle
       else
@@ -976,16 +999,14 @@ int hc_partition(HcCtx& X, u32 tree0, u32 G, std::vector<Leaf>& leaves, hipStrea
     }
     cstart[2 * nact] = (u32)m;
     u32* d_route = X.routebuf.as<u32>();
-    HIP_TRY(hipMemcpyAsync(d_route, route.data(), route.size() * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(d_route, cstart, ((size_t)4 * nact + 1) * 4, hipMemcpyHostToDevice, st));
     hipLaunchKernelGGL(hc_split_route_kernel, dim3(ntiles), dim3(256), 0, st, X.work[1].as<u64>(), m, d_seg, nact, d_Lb,
                        d_tile, d_route, d_route + 2 * nact + 1, X.final_keys.as<u64>(), X.work[0].as<u64>());
     HIP_TRY(hipGetLastError());
-    // (the next level's upload into the same buffer is ordered behind this kernel on the stream,
-    // but the host vectors it comes from must not change before the copy has been staged)
-    HIP_TRY(hipStreamSynchronize(st));
     act.swap(next);
     m = nm;
   }
+  HIP_TRY(hipStreamSynchronize(st));  // the host tables may be written again
   std::sort(leaves.begin(), leaves.end(), [](const Leaf& a, const Leaf& b) { return a.goff < b.goff; });
   return ANN_OK;
 }
@@ -1179,6 +1200,15 @@ int ann_hcnng_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dt
   if (T < 1 || T >= (1u << 20)) return fail(ANN_EINVAL, "the number of trees must be in [1, 2^20)");
   if ((u64)T * 2 * n >= (1ull << 32)) return fail(ANN_EINVAL, "trees times points must stay below 2^31");
   hipStream_t st = static_cast<hipStream_t>(stream);
+  const bool trace = getenv("ANN_TRACE_BUILD") != nullptr;  // wall-clock breakdown on stderr
+  auto t_last = std::chrono::steady_clock::now();
+  auto mark = [&](const char* what) {
+    if (!trace) return;
+    (void)hipStreamSynchronize(st);
+    const auto now = std::chrono::steady_clock::now();
+    fprintf(stderr, "[hcnng] %-28s %8.3f ms\n", what, std::chrono::duration<double, std::milli>(now - t_last).count());
+    t_last = now;
+  };
   ann_graph* g = nullptr;
   rc = new_graph(n, d, dtype, metric, R, &g);
   if (rc) return rc;
@@ -1202,21 +1232,26 @@ int ann_hcnng_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dt
   // trees are cut in groups, as many at a time as keep a group within 32 million positions
   u32 G = (u32)std::max<u64>(1, (32ull << 20) / n);
   if (G > T) G = T;
+  mark("graph, points, start vertex");
   HcCtx X;
   rc = hc_setup(X, g, pts, Ls, s, l, seed, G);
   if (rc) return rc;
+  mark("buffers of a tree group");
   const u64 total = (u64)T * 2 * n;
   DevBuf arcs, arcs_tmp, big_hist, uq_counts, lists, small, arena;
   HIP_TRY(arcs.alloc(total * 8));
   HIP_TRY(arcs_tmp.alloc(total * 8));
   HIP_TRY(hipMemsetAsync(arcs.p, 0xFF, total * 8, st));
+  mark("arc buffers");
   std::vector<Leaf> leaves;
   for (u32 t = 0; t < T; t += G) {
     const u32 Gc = T - t < G ? T - t : G;
     rc = hc_partition(X, t, Gc, leaves, st);
     if (rc) return rc;
+    mark("cluster trees");
     rc = hc_leaves(X, Gc, leaves, arcs.as<u64>() + (u64)t * 2 * n, st);
     if (rc) return rc;
+    mark("leaves");
     g->stats.rounds += Gc;
   }
   // all arcs by (point, neighbour): the neighbour bits first, then, stably, the point bits; the
@@ -1237,6 +1272,7 @@ int ann_hcnng_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dt
   u32 nuniq = 0;
   HIP_TRY(hipMemcpyAsync(&nuniq, uq_counts.as<u32>() + ntiles, 4, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
+  mark("arcs sorted, each once");
   // prune(p, neighbours, R) for every point: the re-prune kernel of BatchInsert on empty rows
   HIP_TRY(hipMemsetAsync(g->meta, 0, (size_t)n * sizeof(u32), st));
   HIP_TRY(lists.alloc(3 * n * sizeof(MergeItem)));
@@ -1276,6 +1312,7 @@ int ann_hcnng_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dt
   HIP_TRY(hipMemcpyAsync(flags, small.p, 16, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
   if (flags[2] != 0) return fail(ANN_EINTERNAL, "merge spill arena exhausted");
+  mark("prune");
   g->stats.edges = nuniq;
   guard.g = nullptr;
   *out = g;
