@@ -523,8 +523,16 @@ __global__ __launch_bounds__(1024) void hc_pairs_kernel(const u32* leaf_list, co
       const u32 b = knn_pos[o];
       keep = true;
       if (a > b) {
+        // does b list a?  Eight entries of b's list at a time, all requested before the first is
+        // looked at (entries past the list's end repeat its last one)
         const unsigned short* lb = knn_pos + (u64)(off + b) * l;
-        for (u32 t = 0; t < k; ++t) keep = keep && lb[t] != a;
+        for (u32 t0 = 0; t0 < k; t0 += 8) {
+          unsigned short w[8];
+#pragma unroll
+          for (u32 t = 0; t < 8; ++t) w[t] = lb[t0 + t < k ? t0 + t : k - 1u];
+#pragma unroll
+          for (u32 t = 0; t < 8; ++t) keep = keep && w[t] != a;
+        }
       }
       const u32 u = a < b ? a : b, v = a < b ? b : a;
       key = ((u64)(u32)knn_d[o] << 32) | (u << 16) | v;
@@ -547,29 +555,48 @@ __global__ __launch_bounds__(1024) void hc_pairs_kernel(const u32* leaf_list, co
   for (u32 k2 = 2; k2 <= P; k2 <<= 1) {
     u32 j = k2 >> 1;
     for (; j >= 64; j >>= 1) {
-      for (u32 i = tid; i < P; i += 1024) {
-        const u32 x = i ^ j;
-        if (x > i) {
-          const u64 a = ek[i], b = ek[x];
-          const bool asc = (i & k2) == 0;
-          if ((a > b) == asc) {
-            ek[i] = b;
-            ek[x] = a;
-          }
+      // one thread per pair (i, i + j): i has bit j clear
+      for (u32 pi = tid; pi < P / 2; pi += 1024) {
+        const u32 i = ((pi & ~(j - 1u)) << 1) | (pi & (j - 1u));
+        const u32 x = i | j;
+        const u64 a = ek[i], b = ek[x];
+        const bool asc = (i & k2) == 0;
+        if ((a > b) == asc) {
+          ek[i] = b;
+          ek[x] = a;
         }
       }
       __syncthreads();
     }
-    for (u32 i = tid; i < P; i += 1024) {
-      u64 v = ek[i];
-      const bool asc = (i & k2) == 0;
-      for (u32 jj = j; jj > 0; jj >>= 1) {
-        const u64 o = (u64)__shfl_xor((unsigned long long)v, (int)jj, 64);
-        const bool lower = (i & jj) == 0;
-        const u64 mn = v < o ? v : o, mx = v < o ? o : v;
-        v = (lower == asc) ? mn : mx;
+    // four keys of a thread at a time, so that the lane exchanges of one do not wait for another's
+    for (u32 i0 = tid; i0 < P; i0 += 4096) {
+      u64 v[4];
+      bool keep_low[4];  // this position keeps the smaller key of an exchange across bit jj ...
+#pragma unroll
+      for (u32 q = 0; q < 4; ++q) {
+        const u32 i = i0 + 1024u * q;
+        v[q] = i < P ? ek[i] : KEY_INF;
+        keep_low[q] = (i & k2) == 0;  // ... when its own bit jj is clear; the other way round otherwise
       }
-      ek[i] = v;
+      for (u32 jj = j; jj > 0; jj >>= 1) {
+        const int src = (int)(((u32)lane ^ jj) << 2);
+        const bool low_side = ((u32)lane & jj) == 0;
+#pragma unroll
+        for (u32 q = 0; q < 4; ++q) {
+          const u32 olo = (u32)__builtin_amdgcn_ds_bpermute(src, (int)(u32)v[q]);
+          const u32 ohi = (u32)__builtin_amdgcn_ds_bpermute(src, (int)(u32)(v[q] >> 32));
+          const u64 o = ((u64)ohi << 32) | olo;
+          // keeps its own key if that is the one wanted here: the smaller on the low side of an
+          // ascending run and on the high side of a descending one (equal keys: either)
+          const bool want_low = low_side == keep_low[q];
+          v[q] = ((v[q] < o) == want_low) ? v[q] : o;
+        }
+      }
+#pragma unroll
+      for (u32 q = 0; q < 4; ++q) {
+        const u32 i = i0 + 1024u * q;
+        if (i < P) ek[i] = v[q];
+      }
     }
     __syncthreads();
   }
