@@ -490,6 +490,37 @@ __global__ __launch_bounds__(64) void hc_knn_f32_kernel(const unsigned char* lea
   }
 }
 
+// NS consecutive steps of a bitonic merge (strides jtop, jtop / 2, ... >= 64) over the P keys in
+// LDS, for the stage that builds runs of k2 keys: the keys whose positions differ only in the NS
+// stride bits exchange among themselves alone, so one thread reads those 2^NS keys, takes the
+// steps in registers and writes them back.
+template <int NS>
+__device__ __forceinline__ void lds_steps(u64* ek, u32 P, u32 k2, u32 jtop, u32 tid) {
+  constexpr u32 NK = 1u << NS;
+  const u32 jlow = jtop >> (NS - 1);
+  for (u32 g = tid; g < (P >> NS); g += 1024) {
+    const u32 i = ((g & ~(jlow - 1u)) << NS) | (g & (jlow - 1u));  // the stride bits clear
+    const bool asc = (i & k2) == 0;
+    u64 v[NK];
+#pragma unroll
+    for (u32 m = 0; m < NK; ++m) v[m] = ek[i + m * jlow];
+#pragma unroll
+    for (u32 bit = NK >> 1; bit > 0; bit >>= 1) {
+#pragma unroll
+      for (u32 m = 0; m < NK; ++m) {
+        if ((m & bit) == 0) {
+          const u64 a = v[m], b = v[m | bit];
+          const bool swap = (a > b) == asc;
+          v[m] = swap ? b : a;
+          v[m | bit] = swap ? a : b;
+        }
+      }
+    }
+#pragma unroll
+    for (u32 m = 0; m < NK; ++m) ek[i + m * jlow] = v[m];
+  }
+}
+
 // One leaf, first half: its candidate pairs (every point with its k = min(l, cnt-1) nearest),
 // each once (the entry of the larger end is dropped when the smaller end lists the pair too),
 // sorted by (distance, smaller position, larger position) in LDS.  The sorted pairs, as
@@ -554,17 +585,18 @@ __global__ __launch_bounds__(1024) void hc_pairs_kernel(const u32* leaf_list, co
   // and workgroup barriers
   for (u32 k2 = 2; k2 <= P; k2 <<= 1) {
     u32 j = k2 >> 1;
-    for (; j >= 64; j >>= 1) {
-      // one thread per pair (i, i + j): i has bit j clear
-      for (u32 pi = tid; pi < P / 2; pi += 1024) {
-        const u32 i = ((pi & ~(j - 1u)) << 1) | (pi & (j - 1u));
-        const u32 x = i | j;
-        const u64 a = ek[i], b = ek[x];
-        const bool asc = (i & k2) == 0;
-        if ((a > b) == asc) {
-          ek[i] = b;
-          ek[x] = a;
-        }
+    // the steps across 64 keys or more, up to three in one trip through LDS: a thread takes the 2,
+    // 4 or 8 keys that those steps exchange among themselves
+    while (j >= 64) {
+      if (j >= 256) {
+        lds_steps<3>(ek, P, k2, j, tid);
+        j >>= 3;
+      } else if (j >= 128) {
+        lds_steps<2>(ek, P, k2, j, tid);
+        j >>= 2;
+      } else {
+        lds_steps<1>(ek, P, k2, j, tid);
+        j >>= 1;
       }
       __syncthreads();
     }
