@@ -79,42 +79,70 @@ __global__ __launch_bounds__(256) void hc_side_kernel(const unsigned char* pts, 
   const u64 w0 = ((u64)blockIdx.x * 4u + (u32)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6))) * SIDE_PER_WAVE;
   if (w0 >= n) return;
   u32 seg = side_first_node(off, nseg, w0);
-  for (u32 it = 0; it < SIDE_PER_WAVE / 8u; ++it) {
-    const u64 i = w0 + 8u * it + grp;
-    if (i >= n) break;
-    const u32 id = (u32)keys_in[i];
-    while ((u64)off[seg + 1] <= i) ++seg;
-    u32 idx = base[seg];
-    const u32 p1 = pos1[seg];
-    if (p1 != HC_NONE) {
-      const u32 ida = (u32)keys_in[p1], idb = (u32)keys_in[pos2[seg]];
-      const uint4* x = reinterpret_cast<const uint4*>(pts + (u64)id * row_bytes);
-      const uint4* a = reinterpret_cast<const uint4*>(pts + (u64)ida * row_bytes);
-      const uint4* b = reinterpret_cast<const uint4*>(pts + (u64)idb * row_bytes);
-      i32 xa = 0, xb = 0, aa = 0, bb = 0;
-      for (u32 pc = sub; pc < row_bytes / 16; pc += 8) {
-        const uint4 vx = x[pc], va = a[pc], vb = b[pc];
-        const u32 wx[4] = {vx.x, vx.y, vx.z, vx.w}, wa[4] = {va.x, va.y, va.z, va.w}, wb[4] = {vb.x, vb.y, vb.z, vb.w};
+  const bool has_piece = sub < row_bytes / 16;  // a row is at most 128 bytes: one 16-byte piece per lane
+  // Four positions of a group at a time, every load of one kind requested for all four before the
+  // first answer is used: the kernel waits for memory, and this way four waits overlap.
+  constexpr u32 NB = 4;
+  for (u32 it0 = 0; it0 < SIDE_PER_WAVE / 8u; it0 += NB) {
+    u64 pos[NB];
+    bool live[NB];
+    u32 id[NB];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          if constexpr (SIGNED) {
-            xa = __builtin_amdgcn_sdot4((i32)wx[k], (i32)wa[k], xa, false);
-            xb = __builtin_amdgcn_sdot4((i32)wx[k], (i32)wb[k], xb, false);
-            aa = __builtin_amdgcn_sdot4((i32)wa[k], (i32)wa[k], aa, false);
-            bb = __builtin_amdgcn_sdot4((i32)wb[k], (i32)wb[k], bb, false);
-          } else {
-            xa = (i32)__builtin_amdgcn_udot4(wx[k], wa[k], (u32)xa, false);
-            xb = (i32)__builtin_amdgcn_udot4(wx[k], wb[k], (u32)xb, false);
-            aa = (i32)__builtin_amdgcn_udot4(wa[k], wa[k], (u32)aa, false);
-            bb = (i32)__builtin_amdgcn_udot4(wb[k], wb[k], (u32)bb, false);
-          }
+    for (u32 q = 0; q < NB; ++q) {
+      pos[q] = w0 + 8u * (it0 + q) + grp;
+      live[q] = pos[q] < n;
+      id[q] = live[q] ? (u32)keys_in[pos[q]] : 0u;
+    }
+    u32 idx[NB], p1[NB], p2[NB];
+#pragma unroll
+    for (u32 q = 0; q < NB; ++q) {
+      if (live[q])
+        while ((u64)off[seg + 1] <= pos[q]) ++seg;
+      idx[q] = base[seg];
+      p1[q] = live[q] ? pos1[seg] : HC_NONE;
+      p2[q] = pos2[seg];
+    }
+    u32 ida[NB], idb[NB];
+#pragma unroll
+    for (u32 q = 0; q < NB; ++q) {
+      const bool split = p1[q] != HC_NONE;
+      ida[q] = split ? (u32)keys_in[p1[q]] : 0u;
+      idb[q] = split ? (u32)keys_in[p2[q]] : 0u;
+    }
+    uint4 vx[NB], va[NB], vb[NB];
+#pragma unroll
+    for (u32 q = 0; q < NB; ++q) {
+      vx[q] = va[q] = vb[q] = make_uint4(0, 0, 0, 0);
+      if (p1[q] != HC_NONE && has_piece) {
+        vx[q] = reinterpret_cast<const uint4*>(pts + (u64)id[q] * row_bytes)[sub];
+        va[q] = reinterpret_cast<const uint4*>(pts + (u64)ida[q] * row_bytes)[sub];
+        vb[q] = reinterpret_cast<const uint4*>(pts + (u64)idb[q] * row_bytes)[sub];
+      }
+    }
+#pragma unroll
+    for (u32 q = 0; q < NB; ++q) {
+      const u32 wx[4] = {vx[q].x, vx[q].y, vx[q].z, vx[q].w}, wa[4] = {va[q].x, va[q].y, va[q].z, va[q].w},
+                wb[4] = {vb[q].x, vb[q].y, vb[q].z, vb[q].w};
+      i32 xa = 0, xb = 0, aa = 0, bb = 0;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if constexpr (SIGNED) {
+          xa = __builtin_amdgcn_sdot4((i32)wx[k], (i32)wa[k], xa, false);
+          xb = __builtin_amdgcn_sdot4((i32)wx[k], (i32)wb[k], xb, false);
+          aa = __builtin_amdgcn_sdot4((i32)wa[k], (i32)wa[k], aa, false);
+          bb = __builtin_amdgcn_sdot4((i32)wb[k], (i32)wb[k], bb, false);
+        } else {
+          xa = (i32)__builtin_amdgcn_udot4(wx[k], wa[k], (u32)xa, false);
+          xb = (i32)__builtin_amdgcn_udot4(wx[k], wb[k], (u32)xb, false);
+          aa = (i32)__builtin_amdgcn_udot4(wa[k], wa[k], (u32)aa, false);
+          bb = (i32)__builtin_amdgcn_udot4(wb[k], wb[k], (u32)bb, false);
         }
       }
-      // |x-a|^2 <= |x-b|^2  <=>  |a|^2 - 2<x,a> <= |b|^2 - 2<x,b>
+      // |x-a|^2 <= |x-b|^2  <=>  |a|^2 - 2<x,a> <= |b|^2 - 2<x,b>  (a node that does not split: 0 <= 0)
       const i32 lhs = group_sum(aa - 2 * xa), rhs = group_sum(bb - 2 * xb);
-      if (lhs > rhs) idx += 1;
+      if (lhs > rhs) idx[q] += 1;
+      if (live[q] && sub == 0) keys_out[pos[q]] = ((u64)idx[q] << 32) | id[q];
     }
-    if (sub == 0) keys_out[i] = ((u64)idx << 32) | id;
   }
 }
 
