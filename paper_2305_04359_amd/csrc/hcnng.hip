@@ -53,7 +53,7 @@ u32 bits_to_hold(u64 count) {  // smallest b with 2^b - 1 >= count: indices belo
 // A wavefront of the side kernels takes SIDE_PER_WAVE consecutive positions, eight at a time
 // (eight lanes per point).  The node of its first position is found once, by a uniform search
 // that the scalar unit runs; the later positions step forward from there.
-constexpr u32 SIDE_PER_WAVE = 64;
+constexpr u32 SIDE_PER_WAVE = 32;
 __device__ inline u32 side_first_node(const u32* off, u32 nseg, u64 w0) {
   u32 lo = 0, hi = nseg;
   while (hi - lo > 1) {
