@@ -970,6 +970,28 @@ def test_hcnng_equal_points_and_tiny_inputs(env):
         assert (off == ooff).all() and (perm == operm).all() and (pairs == opairs).all()
 
 
+@pytest.mark.parametrize("signed", [False, True])
+def test_hcnng_largest_distances(env, signed):
+    """Rows of 128 bytes at the ends of the value range: squared distances up to 128 * 255^2, the
+    largest the nearest-neighbour kernel's packed (distance, candidate) keys have to hold."""
+    torch, A, O = env
+    rng = np.random.default_rng(11)
+    n, d = 1400, 128
+    lo, hi = (-128, 127) if signed else (0, 255)
+    pts_h = rng.integers(lo, hi + 1, (n, d)).astype(np.int8 if signed else np.uint8)
+    kind = rng.integers(0, 4, n)
+    pts_h[kind == 0] = lo  # many equal rows at either end, and rows that mix the two ends
+    pts_h[kind == 1] = hi
+    mixed = np.nonzero(kind == 2)[0]
+    pts_h[mixed] = np.where(rng.integers(0, 2, (len(mixed), d)) == 1, hi, lo).astype(pts_h.dtype)
+    ds = O.Dataset(pts_h, 0)
+    say(f"largest distances, signed={signed}")
+    perm, off, pairs = A.ann_hcnng_tree_edges(dev(torch, pts_h), 700, 3, 10, 3, 0)
+    operm, ooff, opairs = _oracle_tree_pairs(O, ds, 700, 3, 10, 3, 0)
+    assert (off == ooff).all() and (perm == operm).all()
+    assert pairs.shape == opairs.shape and (pairs == opairs).all()
+
+
 @pytest.mark.parametrize("n,T,Ls,s,l,R,alpha", [(3000, 6, 120, 3, 10, 20, 1.2), (2500, 12, 60, 3, 10, 8, 1.0),
                                                 (2000, 3, 500, 5, 16, 64, 1.2), (1500, 40, 30, 3, 5, 32, 1.2)])
 def test_hcnng_build_bit_exact(env, c1, n, T, Ls, s, l, R, alpha):
