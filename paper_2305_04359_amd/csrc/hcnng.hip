@@ -146,19 +146,44 @@ __global__ __launch_bounds__(256) void hc_side_kernel(const unsigned char* pts, 
   }
 }
 
-// The vectors in leaf order, as int8 (uint8 data moved down by 128: distances do not change),
-// rows of lv_stride bytes (a multiple of 32, zero tail), and their squared norms.  Eight lanes
-// per point.
+// Leaf vectors are kept in tiles of 32 consecutive points of ONE leaf (a leaf's tiles follow one
+// another from tile_of_leaf[leaf]; the unused rows of its last tile are zero, and nothing that is
+// kept is computed from them): inside a tile the 16-byte
+// piece c of row r lies at (c * 32 + r) * 16, so that the matrix-core operand of the
+// nearest-neighbour kernels -- lane (row, half) takes piece 2 ks + half of its row -- is 1 KB of
+// consecutive bytes per load instead of 32 bytes out of each of 32 rows.
+__device__ inline u32 leaf_of_tile(const u32* tile_of_leaf, u32 nleaves, u32 tile) {
+  u32 lo = 0, hi = nleaves;  // uniform: the scalar unit runs this
+  while (hi - lo > 1) {
+    const u32 mid = (lo + hi) >> 1;
+    if (tile_of_leaf[mid] <= tile)
+      lo = mid;
+    else
+      hi = mid;
+  }
+  return lo;
+}
+
+// The vectors in that layout, as int8 (uint8 data moved down by 128: distances do not change),
+// rows of lv_stride bytes (a multiple of 32, zero tail), and their squared norms by position.  One
+// workgroup per tile, eight lanes per point.
 template <bool SIGNED>
-__global__ __launch_bounds__(256) void hc_gather_kernel(const unsigned char* pts, u32 row_bytes, const u64* keys, u64 n,
+__global__ __launch_bounds__(256) void hc_gather_kernel(const unsigned char* pts, u32 row_bytes, const u64* keys,
+                                                        const u32* leaf_off, const u32* tile_of_leaf, u32 nleaves,
                                                         u32 lv_stride, unsigned char* leafvec, i32* leafnorm) {
-  const u64 t = (u64)blockIdx.x * blockDim.x + threadIdx.x;
-  const u64 i = t >> 3;
-  const u32 sub = (u32)t & 7u;
-  if (i >= n) return;
+  const u32 tile = blockIdx.x;
+  const u32 leaf = leaf_of_tile(tile_of_leaf, nleaves, tile);
+  const u32 r = threadIdx.x >> 3, sub = threadIdx.x & 7u;
+  const u32 in_leaf = 32u * (tile - tile_of_leaf[leaf]) + r;
+  unsigned char* y = leafvec + (u64)tile * 32u * lv_stride;
+  if (in_leaf >= leaf_off[leaf + 1] - leaf_off[leaf]) {  // an unused row of the leaf's last tile: zeros
+    for (u32 pc = sub; pc < lv_stride / 16; pc += 8)
+      *reinterpret_cast<uint4*>(y + ((u64)pc * 32u + r) * 16u) = make_uint4(0, 0, 0, 0);
+    return;
+  }
+  const u64 i = (u64)leaf_off[leaf] + in_leaf;
   const u32 id = (u32)keys[i];
   const uint4* x = reinterpret_cast<const uint4*>(pts + (u64)id * row_bytes);
-  uint4* y = reinterpret_cast<uint4*>(leafvec + i * lv_stride);
   i32 nn = 0;
   for (u32 pc = sub; pc < lv_stride / 16; pc += 8) {
     uint4 v = make_uint4(0, 0, 0, 0);
@@ -171,7 +196,7 @@ __global__ __launch_bounds__(256) void hc_gather_kernel(const unsigned char* pts
         v.w ^= 0x80808080u;
       }
     }
-    y[pc] = v;
+    *reinterpret_cast<uint4*>(y + ((u64)pc * 32u + r) * 16u) = v;
     nn = __builtin_amdgcn_sdot4((i32)v.x, (i32)v.x, nn, false);
     nn = __builtin_amdgcn_sdot4((i32)v.y, (i32)v.y, nn, false);
     nn = __builtin_amdgcn_sdot4((i32)v.z, (i32)v.z, nn, false);
@@ -200,13 +225,14 @@ __device__ inline bool knn_block(u32 nleaves, u32 ny, u32& leaf, u32& q0) {
 // ascending; positions are relative to the leaf.
 template <int LCAP>
 __global__ __launch_bounds__(64) void hc_knn_kernel(const unsigned char* leafvec, const i32* leafnorm, u32 lv_stride,
-                                                    const u32* leaf_off, u32 l, unsigned short* knn_pos, i32* knn_d,
-                                                    u32 nleaves, u32 ny) {
+                                                    const u32* leaf_off, const u32* tile_of_leaf, u32 l,
+                                                    unsigned short* knn_pos, i32* knn_d, u32 nleaves, u32 ny) {
   u32 leaf, q0;
   if (!knn_block(nleaves, ny, leaf, q0)) return;
   const u32 off = leaf_off[leaf];
   const u32 cnt = leaf_off[leaf + 1] - off;
   if (q0 >= cnt) return;
+  const unsigned char* tiles = leafvec + (u64)tile_of_leaf[leaf] * 32u * lv_stride;  // the leaf's first tile
   const int lane = threadIdx.x;
   const u32 half = (u32)lane >> 5, col = (u32)lane & 31u;
   const u32 ksteps = lv_stride / 32u;  // at most 4
@@ -217,7 +243,7 @@ __global__ __launch_bounds__(64) void hc_knn_kernel(const unsigned char* leafvec
 #pragma unroll
   for (u32 ks = 0; ks < 4; ++ks) {
     const u32 kk = ks < ksteps ? ks : ksteps - 1u;
-    const v4i_t y = *reinterpret_cast<const v4i_t*>(leafvec + (u64)(off + qrow) * lv_stride + 32u * kk + 16u * half);
+    const v4i_t y = *reinterpret_cast<const v4i_t*>(tiles + (u64)q0 * lv_stride + ((2u * kk + half) * 32u + col) * 16u);
     bq[ks] = ks < ksteps ? y : v4i_t{0, 0, 0, 0};
   }
   // A lane meets the candidates c0 + 8 (r / 4) + 4 half + r % 4: numbered c0 / 2 + r (below 512)
@@ -254,12 +280,10 @@ __global__ __launch_bounds__(64) void hc_knn_kernel(const unsigned char* leafvec
   // the tile after the current one is requested before the current one is used
   v4i_t av[4], cn[4];
   auto request = [&](u32 c0, v4i_t (&a)[4], v4i_t (&nrm)[4]) {
-    const u32 c = c0 + col;
-    const u32 crow = c < cnt ? c : cnt - 1u;
 #pragma unroll
     for (u32 ks = 0; ks < 4; ++ks) {
       const u32 kk = ks < ksteps ? ks : ksteps - 1u;
-      a[ks] = *reinterpret_cast<const v4i_t*>(leafvec + (u64)(off + crow) * lv_stride + 32u * kk + 16u * half);
+      a[ks] = *reinterpret_cast<const v4i_t*>(tiles + (u64)c0 * lv_stride + ((2u * kk + half) * 32u + col) * 16u);
     }
     // norms of this lane's 16 candidates: rows 8g + 4 half + 0..3, g = 0..3 (the array has a tail
     // of 64 entries, so reading past the leaf's end stays inside it)
@@ -384,20 +408,26 @@ __global__ __launch_bounds__(256) void hc_side_f32_kernel(const unsigned char* p
 
 // vectors in leaf order (rows of lv_stride bytes, zero tail) and their squared norms
 __global__ __launch_bounds__(256) void hc_gather_f32_kernel(const unsigned char* pts, u32 row_bytes, const u64* keys,
-                                                            u64 n, u32 lv_stride, unsigned char* leafvec,
-                                                            float* leafnorm) {
-  const u64 t = (u64)blockIdx.x * blockDim.x + threadIdx.x;
-  const u64 i = t >> 3;
-  const u32 sub = (u32)t & 7u;
-  if (i >= n) return;
+                                                            const u32* leaf_off, const u32* tile_of_leaf, u32 nleaves,
+                                                            u32 lv_stride, unsigned char* leafvec, float* leafnorm) {
+  const u32 tile = blockIdx.x;
+  const u32 leaf = leaf_of_tile(tile_of_leaf, nleaves, tile);
+  const u32 r = threadIdx.x >> 3, sub = threadIdx.x & 7u;
+  const u32 in_leaf = 32u * (tile - tile_of_leaf[leaf]) + r;
+  unsigned char* y = leafvec + (u64)tile * 32u * lv_stride;
+  if (in_leaf >= leaf_off[leaf + 1] - leaf_off[leaf]) {  // an unused row of the leaf's last tile: zeros
+    for (u32 pc = sub; pc < lv_stride / 16; pc += 8)
+      *reinterpret_cast<float4*>(y + ((u64)pc * 32u + r) * 16u) = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    return;
+  }
+  const u64 i = (u64)leaf_off[leaf] + in_leaf;
   const u32 id = (u32)keys[i];
   const float4* x = reinterpret_cast<const float4*>(pts + (u64)id * row_bytes);
-  float4* y = reinterpret_cast<float4*>(leafvec + i * lv_stride);
   float nn = 0.0f;
   for (u32 pc = sub; pc < lv_stride / 16; pc += 8) {
     float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     if (pc < row_bytes / 16) v = x[pc];
-    y[pc] = v;
+    *reinterpret_cast<float4*>(y + ((u64)pc * 32u + r) * 16u) = v;
     nn = __builtin_fmaf(v.x, v.x, nn);
     nn = __builtin_fmaf(v.y, v.y, nn);
     nn = __builtin_fmaf(v.z, v.z, nn);
@@ -415,8 +445,9 @@ __global__ __launch_bounds__(256) void hc_gather_f32_kernel(const unsigned char*
 // the order-preserving 32-bit image of the distance.
 template <int LCAP, bool MIPS>
 __global__ __launch_bounds__(64) void hc_knn_f32_kernel(const unsigned char* leafvec, const float* leafnorm,
-                                                        u32 lv_stride, const u32* leaf_off, u32 l,
-                                                        unsigned short* knn_pos, i32* knn_d, u32 nleaves, u32 ny) {
+                                                        u32 lv_stride, const u32* leaf_off, const u32* tile_of_leaf,
+                                                        u32 l, unsigned short* knn_pos, i32* knn_d, u32 nleaves,
+                                                        u32 ny) {
   u32 leaf, q0;
   if (!knn_block(nleaves, ny, leaf, q0)) return;
   const u32 off = leaf_off[leaf];
@@ -428,7 +459,9 @@ __global__ __launch_bounds__(64) void hc_knn_f32_kernel(const unsigned char* lea
   const u32 q = q0 + col;
   const u32 qrow = q < cnt ? q : cnt - 1u;
   const float qn = leafnorm[off + qrow];
-  const unsigned char* qp = leafvec + (u64)(off + qrow) * lv_stride + 16u * half;
+  const unsigned char* tiles = leafvec + (u64)tile_of_leaf[leaf] * 32u * lv_stride;  // the leaf's first tile
+  const u32 in_tile = (half * 32u + col) * 16u;  // piece 2 ks + half of row col: at in_tile + ks * 1024
+  const unsigned char* qp = tiles + (u64)q0 * lv_stride + in_tile;
   u64 best[LCAP];
 #pragma unroll
   for (int i = 0; i < LCAP; ++i) best[i] = KEY_INF;
@@ -453,13 +486,11 @@ __global__ __launch_bounds__(64) void hc_knn_f32_kernel(const unsigned char* lea
   };
   for (u32 c0 = 0; c0 < cnt; c0 += 32u) {
     if (ballot(pc > QCAP - 16u) != 0ull) drain();  // room for this tile in every lane's queue
-    const u32 c = c0 + col;
-    const u32 crow = c < cnt ? c : cnt - 1u;
-    const unsigned char* cp = leafvec + (u64)(off + crow) * lv_stride + 16u * half;
+    const unsigned char* cp = tiles + (u64)c0 * lv_stride + in_tile;
     v16f_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     for (u32 ks = 0; ks < ksteps; ++ks) {
-      const float4 a = *reinterpret_cast<const float4*>(cp + 32u * ks);
-      const float4 b = *reinterpret_cast<const float4*>(qp + 32u * ks);
+      const float4 a = *reinterpret_cast<const float4*>(cp + 1024u * ks);
+      const float4 b = *reinterpret_cast<const float4*>(qp + 1024u * ks);
       acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc, 0, 0, 0);
       acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc, 0, 0, 0);
       acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc, 0, 0, 0);
@@ -960,6 +991,7 @@ struct HcCtx {
   u64 seed = 0;
   DevBuf final_keys, work[2], segbuf, routebuf, tilebuf, first, leafvec, leafnorm, leaf_off, knn_pos, knn_d, pair_cnt, leaf_list;
   u64 pair_cnt_cap = 0;
+  u64 leaf_tiles = 0;  // tiles of 32 rows that leafvec holds
   u64 seg_words = 0;
   HostBuf h_up, h_route, h_first;  // a level's node table, its routing table, the left counts read back
   int alloc() {
@@ -975,10 +1007,13 @@ struct HcCtx {
     HIP_TRY(h_first.alloc((2 * nact + 2) * 4));
     HIP_TRY(tilebuf.alloc((N / SP_TILE + 4) * 4));
     HIP_TRY(first.alloc((2 * nact + 2) * 4));
-    HIP_TRY(leafvec.alloc(N * lv_stride));
+    // every leaf but a tree's smallest few is well above 32 points: room for one partly used tile
+    // per Ls / 4 positions (hc_leaves allocates again if a group needs more)
+    leaf_tiles = N / 32 + 4 * (N / Ls) + G + 64;
+    HIP_TRY(leafvec.alloc(leaf_tiles * 32 * lv_stride));
     HIP_TRY(leafnorm.alloc((N + 64) * 4));
     HIP_TRY(hipMemset(leafnorm.p, 0, (N + 64) * 4));
-    HIP_TRY(leaf_off.alloc((N + 1) * 4));
+    HIP_TRY(leaf_off.alloc(2 * (N + 1) * 4));
     HIP_TRY(knn_pos.alloc(N * l * 2));
     HIP_TRY(knn_d.alloc(N * l * 4));
     return ANN_OK;
@@ -1103,31 +1138,45 @@ int hc_partition(HcCtx& X, u32 tree0, u32 G, std::vector<Leaf>& leaves, hipStrea
 int hc_leaves(HcCtx& X, u32 G, const std::vector<Leaf>& leaves, u64* arcs, hipStream_t st) {
   const u64 N = (u64)G * X.n;
   const u32 nleaves = (u32)leaves.size();
-  std::vector<u32> lo(nleaves + 1);
-  u64 maxc = 0;
+  // leaf_off[nleaves + 1] | tile_of_leaf[nleaves + 1]: where a leaf's points and its tiles of 32 begin
+  std::vector<u32> lo(2 * ((size_t)nleaves + 1));
+  u32* lt = lo.data() + nleaves + 1;
+  u64 maxc = 0, ntile = 0;
   for (u32 j = 0; j < nleaves; ++j) {
     lo[j] = (u32)leaves[j].goff;
+    lt[j] = (u32)ntile;
+    ntile += (leaves[j].cnt + 31) / 32;
     maxc = std::max(maxc, leaves[j].cnt);
   }
   lo[nleaves] = (u32)N;
+  lt[nleaves] = (u32)ntile;
+  if (ntile > X.leaf_tiles) {  // many small leaves: more partly used tiles than planned for
+    HIP_TRY(hipStreamSynchronize(st));
+    HIP_TRY(X.leafvec.alloc(ntile * 32 * X.lv_stride));
+    X.leaf_tiles = ntile;
+  }
   HIP_TRY(hipMemcpyAsync(X.leaf_off.p, lo.data(), lo.size() * 4, hipMemcpyHostToDevice, st));
   HIP_TRY(hipStreamSynchronize(st));  // lo goes out of scope
-  const u32 grid_8n = (u32)((N * 8 + 255) / 256);
+  const u32* d_leaf_off = X.leaf_off.as<u32>();
+  const u32* d_tile_of_leaf = d_leaf_off + nleaves + 1;
   if (X.is_f32)
-    hipLaunchKernelGGL(hc_gather_f32_kernel, dim3(grid_8n), dim3(256), 0, st, X.pts, X.row_bytes, X.final_keys.as<u64>(), N,
-                       X.lv_stride, X.leafvec.as<unsigned char>(), X.leafnorm.as<float>());
+    hipLaunchKernelGGL(hc_gather_f32_kernel, dim3((u32)ntile), dim3(256), 0, st, X.pts, X.row_bytes, X.final_keys.as<u64>(),
+                       d_leaf_off, d_tile_of_leaf, nleaves, X.lv_stride, X.leafvec.as<unsigned char>(),
+                       X.leafnorm.as<float>());
   else if (X.is_signed)
-    hipLaunchKernelGGL(hc_gather_kernel<true>, dim3(grid_8n), dim3(256), 0, st, X.pts, X.row_bytes, X.final_keys.as<u64>(),
-                       N, X.lv_stride, X.leafvec.as<unsigned char>(), X.leafnorm.as<i32>());
+    hipLaunchKernelGGL(hc_gather_kernel<true>, dim3((u32)ntile), dim3(256), 0, st, X.pts, X.row_bytes,
+                       X.final_keys.as<u64>(), d_leaf_off, d_tile_of_leaf, nleaves, X.lv_stride,
+                       X.leafvec.as<unsigned char>(), X.leafnorm.as<i32>());
   else
-    hipLaunchKernelGGL(hc_gather_kernel<false>, dim3(grid_8n), dim3(256), 0, st, X.pts, X.row_bytes, X.final_keys.as<u64>(),
-                       N, X.lv_stride, X.leafvec.as<unsigned char>(), X.leafnorm.as<i32>());
+    hipLaunchKernelGGL(hc_gather_kernel<false>, dim3((u32)ntile), dim3(256), 0, st, X.pts, X.row_bytes,
+                       X.final_keys.as<u64>(), d_leaf_off, d_tile_of_leaf, nleaves, X.lv_stride,
+                       X.leafvec.as<unsigned char>(), X.leafnorm.as<i32>());
   HIP_TRY(hipGetLastError());
   const u32 kny = (u32)((maxc + 31) / 32);
   const dim3 kgrid((u32)(((u64)nleaves + 7) / 8 * 8 * kny));
 #define HC_KNN(KERNEL, NORMT)                                                                                       \
   hipLaunchKernelGGL(KERNEL, kgrid, dim3(64), 0, st, X.leafvec.as<unsigned char>(), X.leafnorm.as<NORMT>(), X.lv_stride, \
-                     X.leaf_off.as<u32>(), X.l, X.knn_pos.as<unsigned short>(), X.knn_d.as<i32>(), (u32)nleaves, kny)
+                     d_leaf_off, d_tile_of_leaf, X.l, X.knn_pos.as<unsigned short>(), X.knn_d.as<i32>(), (u32)nleaves, kny)
   if (X.is_f32 && X.is_mips) {
     if (X.l <= 10)
       HC_KNN((hc_knn_f32_kernel<10, true>), float);
