@@ -165,8 +165,8 @@ __device__ inline u32 leaf_of_tile(const u32* tile_of_leaf, u32 nleaves, u32 til
 }
 
 // The vectors in that layout, as int8 (uint8 data moved down by 128: distances do not change),
-// rows of lv_stride bytes (a multiple of 32, zero tail), and their squared norms by position.  One
-// workgroup per tile, eight lanes per point.
+// rows of lv_stride bytes (a multiple of 32, zero tail), and their squared norms (times 512) by
+// position.  One workgroup per tile, eight lanes per point.
 template <bool SIGNED>
 __global__ __launch_bounds__(256) void hc_gather_kernel(const unsigned char* pts, u32 row_bytes, const u64* keys,
                                                         const u32* leaf_off, const u32* tile_of_leaf, u32 nleaves,
@@ -203,7 +203,7 @@ __global__ __launch_bounds__(256) void hc_gather_kernel(const unsigned char* pts
     nn = __builtin_amdgcn_sdot4((i32)v.w, (i32)v.w, nn, false);
   }
   nn = group_sum(nn);
-  if (sub == 0) leafnorm[i] = nn;
+  if (sub == 0) leafnorm[i] = nn << 9;  // where the nearest-neighbour kernel's keys hold the distance
 }
 
 // Which leaf and which 32 queries of it a block of the nearest-neighbour kernels takes.  A leaf's
@@ -238,7 +238,7 @@ __global__ __launch_bounds__(64) void hc_knn_kernel(const unsigned char* leafvec
   const u32 ksteps = lv_stride / 32u;  // at most 4
   const u32 q = q0 + col;
   const u32 qrow = q < cnt ? q : cnt - 1u;
-  const i32 qn = leafnorm[off + qrow];
+  const u32 qn = (u32)leafnorm[off + qrow];  // (times 512, like the candidates' norms)
   v4i_t bq[4];
 #pragma unroll
   for (u32 ks = 0; ks < 4; ++ks) {
@@ -300,13 +300,19 @@ __global__ __launch_bounds__(64) void hc_knn_kernel(const unsigned char* leafvec
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(av[ks], bq[ks], acc, 0, 0, 0);
     // only the tile with the queries themselves and the leaf's last tile hold candidates to skip
+    const u32 qn_tile = qn + (c0 >> 1);
+    const int minus_1024 = -1024;
     auto scan = [&](auto checked) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const u32 cand = c0 + 8u * (r / 4) + 4u * half + (r % 4);
-        const i32 dd = qn + cn[r / 4][r % 4] - 2 * acc[r];
+        // (|q|^2 + |c|^2 - 2<q,c>) << 9 | number, from norms that come shifted: an add and a
+        // multiply-add
+        const u32 base = (u32)cn[r / 4][r % 4] + qn_tile + (u32)r;
+        u32 packed;  // base - 1024 * <q,c>: an inner product over 128 bytes fits 24 bits
+        asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(packed) : "v"(acc[r]), "s"(minus_1024), "v"(base));
         const bool valid = !decltype(checked)::value || (cand < cnt && cand != q);
-        const u32 key = valid ? (((u32)dd << 9) | ((c0 >> 1) + (u32)r)) : K32_INF;
+        const u32 key = valid ? packed : K32_INF;
         // written in any case, kept when the count moves on: no lane is masked, no branch taken
         pend[pc][lane] = key;
         pc += key < worst ? 1u : 0u;
