@@ -876,10 +876,11 @@ __global__ __launch_bounds__(256) void hc_count_left_kernel(const u64* keys, u64
   __shared__ u32 total;
   if (threadIdx.x == 0) total = 0;
   __syncthreads();
-  const u64 base = (u64)blockIdx.x * SP_TILE + threadIdx.x * 8u;
+  const u64 base = (u64)blockIdx.x * SP_TILE + threadIdx.x;  // neighbouring lanes, neighbouring keys
   u32 c = 0;
+#pragma unroll
   for (u32 k = 0; k < 8; ++k)
-    if (base + k < m && (u32)(keys[base + k] >> 32) == 0u) ++c;
+    if (base + 256u * k < m && (u32)(keys[base + 256u * k] >> 32) == 0u) ++c;
   atomicAdd(&total, c);
   __syncthreads();
   if (threadIdx.x == 0) tile_cnt[blockIdx.x] = total;
@@ -905,42 +906,45 @@ __global__ __launch_bounds__(64) void hc_seg_left_kernel(const u64* keys, u64 m,
 __global__ __launch_bounds__(256) void hc_split_route_kernel(const u64* keys, u64 m, const u32* woff, u32 nact,
                                                              const u32* Lb, const u32* tile_off, const u32* cstart,
                                                              const u32* dest, u64* final_keys, u64* next_work) {
-  __shared__ u32 pre[256];
-  const u32 t = threadIdx.x;
-  const u64 base = (u64)blockIdx.x * SP_TILE + t * 8u;
-  u64 key[8];
-  u32 c = 0;
+  // The tile's 2,048 positions in eight rows of 256: a wavefront reads 64 neighbouring keys at a
+  // time and writes the left ones (and the right ones) of a node to neighbouring places.
+  __shared__ u32 before[32];  // left points of the tile before row k's quarter w, at [4 k + w]
+  const u32 t = threadIdx.x, w = t >> 6;
+  const int lane = (int)(t & 63u);
+  const u64 tile0 = (u64)blockIdx.x * SP_TILE;
+  u64 key[8], lefts[8];
+#pragma unroll
   for (u32 k = 0; k < 8; ++k) {
-    key[k] = base + k < m ? keys[base + k] : ~0ull;
-    c += (u32)(key[k] >> 32) == 0u ? 1u : 0u;
+    const u64 i = tile0 + 256u * k + t;
+    key[k] = i < m ? keys[i] : ~0ull;
+    lefts[k] = ballot((u32)(key[k] >> 32) == 0u);
+    if (lane == 0) before[4 * k + w] = (u32)__builtin_popcountll(lefts[k]);
   }
-  pre[t] = c;
   __syncthreads();
-  for (u32 o = 1; o < 256; o <<= 1) {
-    const u32 v = t >= o ? pre[t - o] : 0u;
-    __syncthreads();
-    pre[t] += v;
-    __syncthreads();
-  }
-  u32 L = tile_off[blockIdx.x] + (t ? pre[t - 1] : 0u);  // left points before position base
-  u32 lo = 0;
-  if (base < m) {  // the node of the thread's first position; its other seven are a step away
-    u32 hi = nact;
-    while (hi - lo > 1) {
-      const u32 mid = (lo + hi) >> 1;
-      if ((u64)woff[mid] <= base)
-        lo = mid;
-      else
-        hi = mid;
+  if (t < 32) {  // exclusive running sums of the 32 counts
+    const u32 own = before[t];
+    u32 v = own;
+#pragma unroll
+    for (int o = 1; o < 32; o <<= 1) {
+      const u32 up = (u32)__shfl_up((int)v, o, 64);
+      if ((int)t >= o) v += up;
     }
+    before[t] = v - own;
   }
+  __syncthreads();
+  const u64 first = tile0 + 64u * w;  // the wavefront's first position: its node by a uniform search
+  if (first >= m) return;
+  u32 lo = side_first_node(woff, nact, first);
+  const u32 tile_left = tile_off[blockIdx.x];
+#pragma unroll
   for (u32 k = 0; k < 8; ++k) {
-    const u64 i = base + k;
+    const u64 i = tile0 + 256u * k + t;
     if (i >= m) break;
     const bool left = (u32)(key[k] >> 32) == 0u;
+    const u32 L = tile_left + before[4 * k + w] + (u32)__builtin_popcountll(lefts[k] & lanemask_lt(lane));
     while ((u64)woff[lo + 1] <= i) ++lo;
     const u32 a = woff[lo], La = Lb[lo], nl = Lb[lo + 1] - La;
-    const u32 lr = L - La;
+    const u32 lr = L - La;  // left points of the node before this one
     const u32 sp = left ? a + lr : a + nl + ((u32)i - a - lr);
     const u32 r = sp >= cstart[2 * lo + 1] ? 2 * lo + 1 : 2 * lo;
     const u32 d = dest[r];
@@ -950,7 +954,6 @@ __global__ __launch_bounds__(256) void hc_split_route_kernel(const u64* keys, u6
       next_work[(u64)(d & 0x7FFFFFFFu) + kk] = id;
     else
       final_keys[(u64)d + kk] = id;
-    if (left) ++L;
   }
 }
 
