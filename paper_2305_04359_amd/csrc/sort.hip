@@ -41,9 +41,14 @@ __global__ __launch_bounds__(64) void rs_hist_kernel(const u64* keys, u64 count,
   __syncthreads();
   const u64 lo = (u64)blockIdx.x * tile_keys;
   const u64 hi = lo + tile_keys < count ? lo + tile_keys : count;
-  for (u64 i = lo + lane; i < hi; i += 64) {
-    const u32 dg = (u32)(keys[i] >> shift) & mask;
-    atomicAdd(&cnt[dg], 1u);
+  // four rows of 64 keys requested at a time: the walk waits for memory, not for arithmetic
+  for (u64 i0 = lo + lane; i0 < hi; i0 += 256) {
+    u64 k4[4];
+#pragma unroll
+    for (u32 q = 0; q < 4; ++q) k4[q] = i0 + 64u * q < hi ? keys[i0 + 64u * q] : 0ull;
+#pragma unroll
+    for (u32 q = 0; q < 4; ++q)
+      if (i0 + 64u * q < hi) atomicAdd(&cnt[(u32)(k4[q] >> shift) & mask], 1u);
   }
   __syncthreads();
   for (u32 i = lane; i < RS_RADIX; i += 64) hist[(u64)i * tiles + blockIdx.x] = cnt[i];
@@ -112,25 +117,33 @@ __global__ __launch_bounds__(64) void rs_scatter_kernel(const u64* keys, u64* ou
   __syncthreads();
   const u64 lo = (u64)blockIdx.x * tile_keys;
   const u64 hi = lo + tile_keys < count ? lo + tile_keys : count;
-  for (u64 i0 = lo; i0 < hi; i0 += 64) {
-    const u64 i = i0 + lane;
-    const bool valid = i < hi;
-    const u64 key = valid ? keys[i] : 0ull;
-    const u32 dg = (u32)(key >> shift) & mask;
-    u64 match = ballot(valid);
-    for (u32 b = 0; b < nbits; ++b) {
-      const bool bit = (dg >> b) & 1u;
-      const u64 bm = ballot(bit);
-      match &= bit ? bm : ~bm;
+  for (u64 i4 = lo; i4 < hi; i4 += 256) {
+    u64 k4[4];  // four rows requested before the first is ranked
+#pragma unroll
+    for (u32 q = 0; q < 4; ++q) k4[q] = i4 + 64u * q + lane < hi ? keys[i4 + 64u * q + lane] : 0ull;
+#pragma unroll
+    for (u32 q = 0; q < 4; ++q) {
+      const u64 i0 = i4 + 64u * q;
+      if (i0 >= hi) break;  // uniform
+      const u64 i = i0 + lane;
+      const bool valid = i < hi;
+      const u64 key = k4[q];
+      const u32 dg = (u32)(key >> shift) & mask;
+      u64 match = ballot(valid);
+      for (u32 b = 0; b < nbits; ++b) {
+        const bool bit = (dg >> b) & 1u;
+        const u64 bm = ballot(bit);
+        match &= bit ? bm : ~bm;
+      }
+      const u32 rank = (u32)__builtin_popcountll(match & lanemask_lt(lane));
+      u32 dst = 0;
+      if (valid) dst = base[dg] + rank;
+      __syncthreads();
+      // the highest lane of each group of equal digits advances the group's counter
+      if (valid && (match >> lane) == 1ull) base[dg] += (u32)__builtin_popcountll(match);
+      __syncthreads();
+      if (valid) out[dst] = key;
     }
-    const u32 rank = (u32)__builtin_popcountll(match & lanemask_lt(lane));
-    u32 dst = 0;
-    if (valid) dst = base[dg] + rank;
-    __syncthreads();
-    // the highest lane of each group of equal digits advances the group's counter
-    if (valid && (match >> lane) == 1ull) base[dg] += (u32)__builtin_popcountll(match);
-    __syncthreads();
-    if (valid) out[dst] = key;
   }
 }
 
