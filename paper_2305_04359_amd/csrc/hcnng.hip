@@ -1,15 +1,16 @@
 // The clustering-based builder of Sec. 4.3 (ParlayHCNNG) with the cluster trees of Sec. 3.2.
 //
-// Per tree: the points are split level by level (all nodes of a level in one pass: every point
-// takes the side of the nearer of its node's two pivots, a stable radix sort by child index puts
-// the children in place); the leaves' vectors are gathered into leaf order as int8; one wavefront
-// per 32 points of a leaf finds their l nearest neighbours inside the leaf on the matrix cores
-// (32 x 32 inner products per instruction group, every lane keeping the best of the candidates it
-// sees for its own point); one workgroup per leaf sorts the leaf's candidate pairs in LDS, and
-// one wavefront per leaf runs Kruskal's scan with the degree bound, 64 pairs at a time (a pair
-// that fails once fails for good, so the wave tests 64 in parallel and only the survivors are
-// taken in order; the scan is a chain of dependent LDS reads, so thousands of leaves are scanned
-// side by side).
+// Per group of trees: the points are split level by level (all splitting nodes of a level in one
+// pass: every point takes the side of the nearer of its node's two pivots; a stable two-way split
+// from running counts of left points puts the children in place, finished children straight into
+// the final order); the leaves' vectors are gathered as int8 into tiles of 32 rows laid out as
+// the matrix cores read them; one wavefront per 32 points of a leaf finds their l nearest
+// neighbours inside the leaf on the matrix cores (32 x 32 inner products per instruction group,
+// every lane keeping the best of the candidates it sees for its own point); one workgroup per
+// leaf sorts the leaf's candidate pairs in LDS, and one wavefront per leaf runs Kruskal's scan
+// with the degree bound, 64 pairs at a time (a pair that fails once fails for good, so the wave
+// tests 64 in parallel and only the survivors are taken in order; the scan is a chain of
+// dependent LDS reads, so thousands of leaves are scanned side by side).
 // At the end the arcs of all trees are sorted by (point, neighbour), repeated ones dropped, and
 // every point's neighbours pruned with the alpha rule of Sec. 4.1 by the re-prune kernel of the
 // flat graph's BatchInsert.
