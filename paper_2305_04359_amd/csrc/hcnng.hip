@@ -14,11 +14,11 @@
 // At the end the arcs of all trees are sorted by (point, neighbour), repeated ones dropped, and
 // every point's neighbours pruned with the alpha rule of Sec. 4.1 by the re-prune kernel of the
 // flat graph's BatchInsert.
-#include <type_traits>
 #include <algorithm>
 #include <chrono>
 #include <cstdio>
 #include <cstdlib>
+#include <type_traits>
 
 #include "ann_device.hpp"
 #include "driver_internal.hpp"
