@@ -676,20 +676,30 @@ __global__ __launch_bounds__(1024) void hc_pairs_kernel(const u32* leaf_list, co
         v[q] = i < P ? ek[i] : KEY_INF;
         keep_low[q] = (i & k2) == 0;  // ... when its own bit jj is clear; the other way round otherwise
       }
-      for (u32 jj = j; jj > 0; jj >>= 1) {
+      // keeps its own key if that is the one wanted here: the smaller on the low side of an
+      // ascending run and on the high side of a descending one (equal keys: either)
+      auto settle = [&](u32 q, u32 jj, u32 olo, u32 ohi) {
+        const u64 o = ((u64)ohi << 32) | olo;
+        const bool want_low = (((u32)lane & jj) == 0) == keep_low[q];
+        v[q] = ((v[q] < o) == want_low) ? v[q] : o;
+      };
+      for (u32 jj = j; jj >= 4; jj >>= 1) {  // partners 4 to 32 lanes away: through the LDS crossbar
         const int src = (int)(((u32)lane ^ jj) << 2);
-        const bool low_side = ((u32)lane & jj) == 0;
 #pragma unroll
-        for (u32 q = 0; q < 4; ++q) {
-          const u32 olo = (u32)__builtin_amdgcn_ds_bpermute(src, (int)(u32)v[q]);
-          const u32 ohi = (u32)__builtin_amdgcn_ds_bpermute(src, (int)(u32)(v[q] >> 32));
-          const u64 o = ((u64)ohi << 32) | olo;
-          // keeps its own key if that is the one wanted here: the smaller on the low side of an
-          // ascending run and on the high side of a descending one (equal keys: either)
-          const bool want_low = low_side == keep_low[q];
-          v[q] = ((v[q] < o) == want_low) ? v[q] : o;
-        }
+        for (u32 q = 0; q < 4; ++q)
+          settle(q, jj, (u32)__builtin_amdgcn_ds_bpermute(src, (int)(u32)v[q]),
+                 (u32)__builtin_amdgcn_ds_bpermute(src, (int)(u32)(v[q] >> 32)));
       }
+      if (j >= 2) {  // partners inside a group of four lanes: quad_perm [2,3,0,1], then [1,0,3,2]
+#pragma unroll
+        for (u32 q = 0; q < 4; ++q)
+          settle(q, 2u, (u32)__builtin_amdgcn_update_dpp(0, (int)(u32)v[q], 0x4E, 0xF, 0xF, true),
+                 (u32)__builtin_amdgcn_update_dpp(0, (int)(u32)(v[q] >> 32), 0x4E, 0xF, 0xF, true));
+      }
+#pragma unroll
+      for (u32 q = 0; q < 4; ++q)
+        settle(q, 1u, (u32)__builtin_amdgcn_update_dpp(0, (int)(u32)v[q], 0xB1, 0xF, 0xF, true),
+               (u32)__builtin_amdgcn_update_dpp(0, (int)(u32)(v[q] >> 32), 0xB1, 0xF, 0xF, true));
 #pragma unroll
       for (u32 q = 0; q < 4; ++q) {
         const u32 i = i0 + 1024u * q;
