@@ -683,12 +683,32 @@ __global__ __launch_bounds__(1024) void hc_pairs_kernel(const u32* leaf_list, co
         const bool want_low = (((u32)lane & jj) == 0) == keep_low[q];
         v[q] = ((v[q] < o) == want_low) ? v[q] : o;
       };
-      for (u32 jj = j; jj >= 4; jj >>= 1) {  // partners 4 to 32 lanes away: through the LDS crossbar
+      for (u32 jj = j; jj >= 16; jj >>= 1) {  // partners 16 or 32 lanes away: through the LDS crossbar
         const int src = (int)(((u32)lane ^ jj) << 2);
 #pragma unroll
         for (u32 q = 0; q < 4; ++q)
           settle(q, jj, (u32)__builtin_amdgcn_ds_bpermute(src, (int)(u32)v[q]),
                  (u32)__builtin_amdgcn_ds_bpermute(src, (int)(u32)(v[q] >> 32)));
+      }
+      // partners inside a row of 16 lanes: data-parallel-primitive moves.  8 away: the row turned
+      // by 8.  4 away: the row turned by 12 for the lanes whose partner is above (banks 0 and 2),
+      // by 4 for those whose partner is below (banks 1 and 3).
+      if (j >= 8) {
+#pragma unroll
+        for (u32 q = 0; q < 4; ++q)
+          settle(q, 8u, (u32)__builtin_amdgcn_update_dpp(0, (int)(u32)v[q], 0x128, 0xF, 0xF, true),
+                 (u32)__builtin_amdgcn_update_dpp(0, (int)(u32)(v[q] >> 32), 0x128, 0xF, 0xF, true));
+      }
+      if (j >= 4) {
+#pragma unroll
+        for (u32 q = 0; q < 4; ++q) {
+          const int lo = (int)(u32)v[q], hi = (int)(u32)(v[q] >> 32);
+          const int olo = __builtin_amdgcn_update_dpp(__builtin_amdgcn_update_dpp(0, lo, 0x12C, 0xF, 0x5, false), lo,
+                                                      0x124, 0xF, 0xA, false);
+          const int ohi = __builtin_amdgcn_update_dpp(__builtin_amdgcn_update_dpp(0, hi, 0x12C, 0xF, 0x5, false), hi,
+                                                      0x124, 0xF, 0xA, false);
+          settle(q, 4u, (u32)olo, (u32)ohi);
+        }
       }
       if (j >= 2) {  // partners inside a group of four lanes: quad_perm [2,3,0,1], then [1,0,3,2]
 #pragma unroll
