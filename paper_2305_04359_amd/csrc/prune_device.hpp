@@ -18,8 +18,9 @@
 
 namespace annmi {
 
-// In-place ascending bitonic sort of n2 keys (a power of two >= 2) by one wave.
-__device__ __forceinline__ void bitonic_sort_keys(u64* a, u32 n2, int lane) {
+// In-place ascending bitonic sort of n2 keys (a power of two >= 2) by one wave, every step a trip
+// through LDS: for the sizes the register version below does not cover.
+__device__ __forceinline__ void bitonic_sort_keys_lds(u64* a, u32 n2, int lane) {
   for (u32 k = 2; k <= n2; k <<= 1) {
     for (u32 j = k >> 1; j > 0; j >>= 1) {
       for (u32 t = lane; t < (n2 >> 1); t += 64) {
@@ -35,6 +36,88 @@ __device__ __forceinline__ void bitonic_sort_keys(u64* a, u32 n2, int lane) {
       __syncthreads();
     }
   }
+}
+
+// The same sort with the keys in registers: key 64 q + lane is v[q] of the lane.  Partners 64
+// keys or more apart are two registers of one lane; partners inside a row of 16 lanes are reached
+// with data-parallel-primitive moves (quad permutations for 1 and 2 lanes, the row turned by 8,
+// and for 4 lanes the row turned by 12 for the banks whose partner is above, by 4 for the others);
+// only partners 16 and 32 lanes away go through the LDS crossbar.  No barrier, no LDS round trip.
+template <u32 J>
+__device__ __forceinline__ u32 lane_partner_word(u32 x, int lane) {
+  if constexpr (J == 1) {
+    return (u32)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, true);
+  } else if constexpr (J == 2) {
+    return (u32)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xF, 0xF, true);
+  } else if constexpr (J == 4) {
+    return (u32)__builtin_amdgcn_update_dpp(__builtin_amdgcn_update_dpp(0, (int)x, 0x12C, 0xF, 0x5, false), (int)x, 0x124,
+                                            0xF, 0xA, false);
+  } else if constexpr (J == 8) {
+    return (u32)__builtin_amdgcn_update_dpp(0, (int)x, 0x128, 0xF, 0xF, true);
+  } else {
+    return (u32)__builtin_amdgcn_ds_bpermute((int)(((u32)lane ^ J) << 2), (int)x);
+  }
+}
+
+template <int KPL, u32 K, u32 J>
+struct BitonicStep {
+  static __device__ __forceinline__ void run(u64 (&v)[KPL], int lane) {
+    if constexpr (J >= 64) {
+      constexpr u32 dq = J / 64;
+#pragma unroll
+      for (u32 q = 0; q < (u32)KPL; ++q) {
+        if ((q & dq) == 0) {
+          const bool asc = ((64u * q) & K) == 0;  // (K > J >= 64: the lane bits do not matter)
+          const u64 x = v[q], y = v[q | dq];
+          const bool swap = (x > y) == asc;
+          v[q] = swap ? y : x;
+          v[q | dq] = swap ? x : y;
+        }
+      }
+    } else {
+      const bool low_side = ((u32)lane & J) == 0;
+#pragma unroll
+      for (u32 q = 0; q < (u32)KPL; ++q) {
+        const bool asc = ((64u * q + (u32)lane) & K) == 0;
+        const u64 o = ((u64)lane_partner_word<J>((u32)(v[q] >> 32), lane) << 32) | lane_partner_word<J>((u32)v[q], lane);
+        // keeps its own key if that is the one wanted here: the smaller on the low side of an
+        // ascending run, the larger on its high side (keys are distinct or equal: either)
+        v[q] = ((v[q] < o) == (low_side == asc)) ? v[q] : o;
+      }
+    }
+    if constexpr (J > 1) BitonicStep<KPL, K, J / 2>::run(v, lane);
+  }
+};
+
+template <int KPL, u32 K>
+struct BitonicStage {
+  static __device__ __forceinline__ void run(u64 (&v)[KPL], int lane) {
+    BitonicStep<KPL, K, K / 2>::run(v, lane);
+    if constexpr (K < 64u * KPL) BitonicStage<KPL, 2 * K>::run(v, lane);
+  }
+};
+
+template <int KPL>
+__device__ __forceinline__ void bitonic_sort_regs(u64* a, int lane) {
+  u64 v[KPL];
+#pragma unroll
+  for (int q = 0; q < KPL; ++q) v[q] = a[64 * q + lane];
+  BitonicStage<KPL, 2>::run(v, lane);
+#pragma unroll
+  for (int q = 0; q < KPL; ++q) a[64 * q + lane] = v[q];
+}
+
+// In-place ascending sort of n2 keys in LDS (a power of two >= 64) by one wave; the keys must be
+// visible to the wave when it is called and are visible to it on return.
+__device__ __forceinline__ void bitonic_sort_keys(u64* a, u32 n2, int lane) {
+  switch (n2) {
+    case 64: bitonic_sort_regs<1>(a, lane); break;
+    case 128: bitonic_sort_regs<2>(a, lane); break;
+    case 256: bitonic_sort_regs<4>(a, lane); break;
+    case 512: bitonic_sort_regs<8>(a, lane); break;
+    default: bitonic_sort_keys_lds(a, n2, lane); return;
+  }
+  __syncthreads();
 }
 
 // LDS copy of the selected points' vectors
