@@ -34,6 +34,10 @@
  *     the padded copies named above, and the scratch of ann_insert_batch /
  *     ann_insert_points (sized for the largest batch so far).  The caller
  *     owns every buffer it passes in.
+ *   - With ANN_TRACE_BUILD set in the environment, ann_build,
+ *     ann_insert_points and ann_hcnng_build print a wall-clock breakdown of
+ *     their phases on stderr (they wait for the stream between phases to do
+ *     so: for measurement only).
  */
 #ifndef ANN_H
 #define ANN_H
