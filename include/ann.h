@@ -36,8 +36,8 @@
  *     owns every buffer it passes in.
  *   - With ANN_TRACE_BUILD set in the environment, ann_build,
  *     ann_insert_points and ann_hcnng_build print a wall-clock breakdown of
- *     their phases on stderr (they wait for the stream between phases to do
- *     so: for measurement only).
+ *     their phases on stderr (the clustering-based builder waits for the
+ *     stream between phases to do so: for measurement only).
  */
 #ifndef ANN_H
 #define ANN_H
