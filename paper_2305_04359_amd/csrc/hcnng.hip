@@ -1050,6 +1050,7 @@ struct HcCtx {
     // every leaf but a tree's smallest few is well above 32 points: room for one partly used tile
     // per Ls / 4 positions (hc_leaves allocates again if a group needs more)
     leaf_tiles = N / 32 + 4 * (N / Ls) + G + 64;
+    if (getenv("ANN_HCNNG_FEW_TILES") != nullptr) leaf_tiles = 1;  // (lets a test reach the second allocation)
     HIP_TRY(leafvec.alloc(leaf_tiles * 32 * lv_stride));
     HIP_TRY(leafnorm.alloc((N + 64) * 4));
     HIP_TRY(hipMemset(leafnorm.p, 0, (N + 64) * 4));

@@ -970,6 +970,18 @@ def test_hcnng_equal_points_and_tiny_inputs(env):
         assert (off == ooff).all() and (perm == operm).all() and (pairs == opairs).all()
 
 
+def test_hcnng_leaf_tiles_allocated_again(env, c1, monkeypatch):
+    """The buffer of leaf tiles starts too small (one tile) and is allocated again for the group."""
+    torch, A, O = env
+    monkeypatch.setenv("ANN_HCNNG_FEW_TILES", "1")
+    n, T, Ls, s, l, R = 2000, 5, 90, 3, 10, 24
+    pts_h = c1.points[:n]
+    og = O.hcnng_build(O.Dataset(pts_h, 0), T, Ls, s, l, R, 1.2, seed=3, threads=0)
+    say("clustering-based build with the tile buffer grown on demand")
+    g = A.ann_hcnng_build(dev(torch, pts_h), T, Ls, s, l, R, 1.2, seed=3)
+    assert (g.neighbors() == og).all()
+
+
 @pytest.mark.parametrize("signed", [False, True])
 def test_hcnng_largest_distances(env, signed):
     """Rows of 128 bytes at the ends of the value range: squared distances up to 128 * 255^2, the
