@@ -2,9 +2,19 @@
 """Benchmark of the hot path: one step = one full graph build (prefix-doubling batch insertion)
 plus one batched query search at the beam width that reaches recall@10 = 0.90.
 
-Prints ONE JSON line.  `value` is build points/s on one MI355X with inputs resident in HBM.
-The roofline object covers the dominant kernel (the build's beam search); the cpu_baseline
-object times the CPU oracle on a bounded sample of the same workload.
+Prints ONE JSON line.  `value` is build points/s on one MI355X with inputs resident in HBM, for
+the workload named in `config` (C2, a million points, unless --config says otherwise).  The
+default run then repeats the measurement ONCE at the largest configuration that fits one GPU
+(C5, 10^8 points: one timed build, queries, roofline, oracle sample) and reports it under `c5`.
+The roofline objects cover the dominant kernel (the build's beam search) and the query search;
+the cpu_baseline objects time the CPU oracle on a bounded sample of the same workload.
+
+Modes for profilers (everything after `--` of a rocprofv3 command is this file itself):
+  --only-build            inputs, warm-up builds, `--steps` builds, nothing else
+  --only-build --search-L 15 [--search-eps E] [--search-nq N]
+                          ... followed by query launches at that beam width
+  --copy-probe MIB        a plain device copy of known size: the calibration of the
+                          FETCH_SIZE / WRITE_SIZE counters
 """
 from __future__ import annotations
 
@@ -21,16 +31,23 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+EPS_SWEEP = (0.02, 0.05, 0.1, 0.25)  # the (1 + eps) rule of the search; the paper stays below 0.25
+TARGETS = (0.90, 0.95)
+STREAM_QUERIES = 100_000  # distinct queries of the "stream of queries" rate
 
 
+# ------------------------------------------------------------------------------------------------
+# exact neighbours and recall (measurement only: library GEMMs, not the product)
+# ------------------------------------------------------------------------------------------------
 def ground_truth(torch, pts, qs, k, metric, point_chunk=2_000_000):
-    """Exact k-NN under (distance, id) with library GEMMs: measurement only, not the product.
-    The points are taken in chunks; the k best of every chunk are merged at the end."""
+    """Exact k-NN under (distance, id).  Returns (ids[nq,k] uint32, kth[nq]): kth is the distance
+    of the k-th true neighbour (int64 for integer rows, float64 for float rows).  The points are
+    taken in chunks; the k best of every chunk are merged at the end."""
     n = pts.shape[0]
     nq = qs.shape[0]
     is_f32 = pts.dtype == torch.float32
     qstep = 1000 if is_f32 else 500
-    best = [[] for _ in range(0, nq, qstep)]  # per query chunk: list of (keys or (d, ids)) per point chunk
+    best = [[] for _ in range(0, nq, qstep)]
     for p0 in range(0, n, point_chunk):
         Pc = pts[p0:p0 + point_chunk]
         ids = torch.arange(p0, p0 + Pc.shape[0], device=pts.device, dtype=torch.int64)
@@ -52,7 +69,7 @@ def ground_truth(torch, pts, qs, k, metric, point_chunk=2_000_000):
                 d = (Q.long() ** 2).sum(1)[:, None] + pp[None, :] - 2 * qp
                 key = d * (1 << 32) + ids[None, :]
                 best[qi].append(torch.topk(key, min(k, key.shape[1]), dim=1, largest=False, sorted=True).values)
-    out = []
+    out, kth = [], []
     for parts in best:
         if is_f32:
             dv = torch.cat([p[0] for p in parts], 1)
@@ -62,18 +79,32 @@ def ground_truth(torch, pts, qs, k, metric, point_chunk=2_000_000):
             dv, di = torch.gather(dv, 1, o), torch.gather(di, 1, o)
             o = torch.argsort(dv, dim=1, stable=True)[:, :k]
             out.append(torch.gather(di, 1, o))
+            kth.append(torch.gather(dv, 1, o)[:, -1])
         else:
-            key = torch.cat(parts, 1)
-            out.append(torch.topk(key, k, dim=1, largest=False, sorted=True).values & 0xFFFFFFFF)
-    return torch.cat(out).cpu().numpy().astype(np.uint32)
+            key = torch.topk(torch.cat(parts, 1), k, dim=1, largest=False, sorted=True).values
+            out.append(key & 0xFFFFFFFF)
+            kth.append(key[:, -1] >> 32)
+    return torch.cat(out).cpu().numpy().astype(np.uint32), torch.cat(kth).cpu().numpy()
 
 
 def recall(ids, gt):
+    """Mean over the queries of |K intersect K'| / k (Sec. 2)."""
     k = gt.shape[1]
     hit = 0
     for a, b in zip(ids, gt):
         hit += len(set(a.tolist()) & set(b.tolist()))
     return hit / (k * len(gt))
+
+
+def recall_ties(ids, dists, kth):
+    """Tie-aware recall: a returned vertex counts when it is no farther than the k-th true
+    neighbour (integer rows have exact ties, which the plain count charges to the search)."""
+    valid = ids != 0xFFFFFFFF
+    if dists.dtype.kind == "f":
+        ok = dists.astype(np.float64) <= kth[:, None] + 1e-5 * np.abs(kth[:, None])
+    else:
+        ok = dists.astype(np.int64) <= kth[:, None]
+    return float((ok & valid).sum() / ids.size)
 
 
 def time_search(torch, A, g, pts, qs, k, L, reps=5, eps=None):
@@ -87,10 +118,282 @@ def time_search(torch, A, g, pts, qs, k, L, reps=5, eps=None):
         e1.record()
         torch.cuda.synchronize()
         ms.append(e0.elapsed_time(e1))
-    return float(np.median(ms)), ids
+    return float(np.median(ms)), ids, dists
 
 
-EPS_SWEEP = (0.02, 0.05, 0.1, 0.25)  # the (1 + eps) rule of the search; the paper stays below 0.25
+def sweep_queries(torch, A, g, pts, qs, k, search_L, gt, gt_rows, say, eps_list=(None,) + EPS_SWEEP, reps=3):
+    """The two query parameters of Sec. 4.5, the beam width L and the eps of the (1 + eps) rule:
+    recall (on the first gt_rows queries, whose exact neighbours are known) and rate of every
+    setting, and the fastest setting per recall target (None where no setting reaches it)."""
+    sweep = []
+    best = {t: None for t in TARGETS}
+    for eps in eps_list:
+        for L in sorted(set(search_L)):
+            if L < k:
+                continue
+            ms, ids, _ = time_search(torch, A, g, pts, qs, k, L, reps=reps, eps=eps)
+            r = recall(ids[:gt_rows].cpu().numpy().view(np.uint32), gt)
+            qps = qs.shape[0] / ms * 1e3
+            sweep.append({"L": L, "eps": eps, "recall": round(r, 4), "qps": round(qps, 1)})
+            say(f"queries at L={L} eps={eps}: recall {r:.4f}, {qps / 1e6:.2f} M/s")
+            for t in best:
+                if r >= t and (best[t] is None or qps > best[t][2]):
+                    best[t] = (L, eps, qps)
+            if r >= 0.995:
+                break
+    return sweep, best
+
+
+def query_point(torch, A, O, w, g_stats, pts, qs, qs_stream, k, setting, gt, kth, gt_rows, graph_rows, start):
+    """One operating point of the query path: rate on the workload's queries (one launch is about
+    one generation of wavefronts: a latency) and on a stream of distinct queries (the throughput),
+    plain and tie-aware recall, and the roofline of the search kernel on the stream: per query
+    hops * 4R (adjacency rows) + DISTINCT distance evaluations * row bytes + k * 8 (results), hops
+    and evaluations from the library's counters, the distinct share from the oracle's search of a
+    sample of the same queries (the kernel's visited filter is lossy and counts repeats too)."""
+    if setting is None:
+        return None
+    L, eps, _ = setting
+    row_bytes = w.d * w.points.dtype.itemsize
+    ms, ids, dists = time_search(torch, A, g_stats, pts, qs, k, L, reps=5, eps=eps)
+    ids_h = ids[:gt_rows].cpu().numpy().view(np.uint32)
+    out = {"L": L, "eps": eps, "recall": round(recall(ids_h, gt), 4),
+           "recall_tie_aware": round(recall_ties(ids_h, dists[:gt_rows].cpu().numpy(), kth), 4),
+           "qps": round(qs.shape[0] / ms * 1e3, 1)}
+    st0 = g_stats.stats()
+    ms_s, _, _ = time_search(torch, A, g_stats, pts, qs_stream, k, L, reps=3, eps=eps)
+    st1 = g_stats.stats()
+    nlaunch = 4  # warm-up + 3
+    nqs = qs_stream.shape[0]
+    hops = (st1["hops"] - st0["hops"]) / (nlaunch * nqs)
+    evals = (st1["evals"] - st0["evals"]) / (nlaunch * nqs)
+    distinct = 1.0
+    if O is not None and graph_rows is not None:
+        ns = min(1000, qs.shape[0])
+        ost = O.Stats()
+        O.search_batch(O.Dataset(w.points, w.metric), graph_rows, start, w.queries[:ns], k, L, threads=0, stats=ost,
+                       eps=-1.0 if eps is None else eps)
+        sa = g_stats.stats()
+        A.ann_search(g_stats, pts, qs[:ns], k, L, eps=eps)
+        torch.cuda.synchronize()
+        sb = g_stats.stats()
+        distinct = min(1.0, ost.evals / max(1, sb["evals"] - sa["evals"]))
+    per_query = hops * 4 * w.R + evals * distinct * row_bytes + 8 * k
+    achieved = per_query * nqs / (ms_s / 1e3) / 1e9
+    out["qps_stream"] = round(nqs / ms_s * 1e3, 1)
+    out["stream_queries"] = nqs
+    out["roofline_query"] = {"bound": "hbm", "kernel": "search_kernel (queries)", "achieved": round(achieved, 1),
+                             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                             "hops_per_query": round(hops, 2), "evals_per_query": round(evals, 2),
+                             "distinct_eval_fraction": round(distinct, 4), "bytes_per_query": int(per_query),
+                             "launch_ms": round(ms_s, 4)}
+    return out
+
+
+def build_roofline(st, w, distinct_frac, traffic):
+    """Roofline of the dominant kernel, the build's beam search.  Algorithmic bytes per launch =
+    hops * 4R (adjacency rows) + DISTINCT distance evaluations * row bytes (gathered vectors) +
+    8 * hops (visited list), averaged over the launches of a build; the time is the sum of the HIP
+    events the library records around each launch on the caller's stream."""
+    row_bytes = w.d * w.points.dtype.itemsize
+    srch_bytes = st["hops"] * (4 * w.R + 8) + st["evals"] * distinct_frac * row_bytes
+    srch_s = st["ms_search"] / 1e3
+    achieved = srch_bytes / srch_s / 1e9 if srch_s > 0 else 0.0
+    return {
+        "bound": "hbm", "kernel": "search_kernel (build, step 1 of BatchInsert)",
+        "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+        "launches": int(st["rounds"]), "avg_launch_ms": round(st["ms_search"] / max(1, st["rounds"]), 4),
+        "bytes_per_launch": int(srch_bytes / max(1, st["rounds"])),
+        "distinct_eval_fraction": round(distinct_frac, 4),
+        "evals_counted": "distinct (repeats of the lossy visited filter excluded)",
+    }
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch of the search kernel from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size), or None."""
+    path = os.path.join(ROOT, "profiles", "search_kernel_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload, {}).get("bytes_per_launch")
+    except (OSError, ValueError):
+        return None
+
+
+def cpu_baseline(torch, A, w, pts, rounds, nbatches, npoints_only=None, one_thread_points=2000, say=lambda m: None):
+    """The oracle, as it stands, runs the LAST `nbatches` batches of the build on all host cores,
+    starting from the graph as it stood before them (taken from a GPU build stopped early).  The
+    GPU inserts the same batches into the same snapshot and the resulting graphs are compared.
+    The oracle's rate on ONE thread is taken on the first `one_thread_points` points of the first
+    of these batches, on a copy of the snapshot.
+    With `npoints_only` (inputs whose batches would take the oracle many minutes) the sample is
+    the first so many points of the last batch, inserted as two batches on both sides: the first
+    `one_thread_points` by the oracle on one thread, the rest on all cores (no copy of the
+    snapshot is needed then).
+    Returns (record, statistics of the snapshot build)."""
+    import oracle as O
+    metric = w.metric
+    nb = 1 if npoints_only else max(1, min(nbatches, rounds - 1))
+    snap = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, metric=metric, max_rounds=rounds - nb,
+                       collect_stats=True)
+    st0 = snap.stats()
+    say("snapshot built on the GPU")
+    og = snap.neighbors()
+    say("snapshot copied to the host")
+    s = int(snap.info().start)
+    ds = O.Dataset(w.points, metric)
+    order = O.insertion_order(w.n, s, w.seed)
+    bounds = O.schedule(w.n - 1, w.theta).astype(np.int64)
+    batches = [order[bounds[r]:bounds[r + 1]] for r in range(rounds - nb, rounds)]
+    cores = O.threads(0)
+    one, one_s = None, 0.0
+    if npoints_only:
+        b = batches[0][:npoints_only]
+        cut = min(one_thread_points, len(b) // 2)
+        batches = [b[:cut], b[cut:]] if cut else [b]
+        if cut:
+            t0 = time.perf_counter()
+            O.batch_insert(ds, og, s, batches[0], w.L, w.alpha, threads=1)
+            one_s = time.perf_counter() - t0
+            one = {"value": round(cut / one_s, 1), "unit": "points/s", "cores": 1,
+                   "sample": f"the first {cut} points of the sample as a batch of their own, {one_s:.1f} s"}
+    elif one_thread_points:
+        sample = batches[0][:one_thread_points]
+        og1 = og.copy()
+        t0 = time.perf_counter()
+        O.batch_insert(ds, og1, s, sample, w.L, w.alpha, threads=1)
+        one_s = time.perf_counter() - t0
+        del og1
+        one = {"value": round(len(sample) / one_s, 1), "unit": "points/s", "cores": 1,
+               "sample": f"the first {len(sample)} points of the sample as one batch on a copy of the snapshot, "
+                         f"{one_s:.1f} s"}
+    if one:
+        say(f"oracle on one thread: {one['sample']}")
+    ost = O.Stats()
+    npoints = 0
+    t0 = time.perf_counter()
+    for batch in batches[1 if (npoints_only and one) else 0:]:
+        O.batch_insert(ds, og, s, batch, w.L, w.alpha, threads=0, stats=ost)
+        npoints += len(batch)
+    cpu_s = time.perf_counter() - t0
+    say(f"oracle inserted {npoints} points in {cpu_s:.1f} s on {cores} threads")
+    st_a = st0
+    for i, batch in enumerate(batches):
+        if npoints_only and one and i == 1:
+            st_a = snap.stats()  # the evaluations counted below belong to the all-cores part
+        A.ann_insert_batch(snap, pts, batch, w.L, w.alpha)
+    st1 = snap.stats()
+    gg = snap.neighbors()
+    same, step = 0, 1 << 22
+    for i in range(0, len(gg), step):
+        same += int((gg[i:i + step] == og[i:i + step]).all(1).sum())
+    same_rows = same / len(gg)
+    gpu_evals = st1["evals"] - st_a["evals"]
+    total = sum(len(b) for b in batches)
+    what = (f"the first {total} points of the last batch" if npoints_only
+            else f"the last {nb} batch(es) of the build, {total} points")
+    rec = {
+        "value": round(npoints / cpu_s, 1), "unit": "points/s", "cores": cores, "kind": "oracle",
+        "sample": f"{what}, inserted into the {int(bounds[rounds - nb]) + 1}-point graph that precedes them; "
+                  f"{npoints} of them in {cpu_s:.1f} s of wall time on {cores} threads",
+        "one_thread": one,
+        "rows_identical_to_gpu": same_rows,
+        "oracle_hops_per_search": round(ost.hops / max(1, ost.searches), 2),
+        "oracle_evals_per_search": round(ost.evals / max(1, ost.searches), 2),
+        "gpu_evals_per_search_same_batches": round(gpu_evals / max(1, npoints), 2),
+        "_distinct_frac": min(1.0, ost.evals / max(1, gpu_evals)),
+    }
+    del snap
+    return rec, st0
+
+
+def workload_text(w, nq, k):
+    return (f"{w.name}: n={w.n} d={w.d} {w.points.dtype} {'L2sq' if w.metric == 0 else 'neg-inner-product'}, "
+            f"R={w.R} L={w.L} alpha={w.alpha}, theta={w.theta}, nq={nq} k={k}")
+
+
+def copy_probe(mib):
+    import torch
+    n = mib * (1 << 20) // 4
+    a = torch.arange(n, dtype=torch.int32, device="cuda:0")
+    b = torch.empty_like(a)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        b.copy_(a)  # one elementwise copy kernel: reads n * 4 bytes, writes n * 4 bytes
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_probe": True, "read_bytes_per_kernel": n * 4, "written_bytes_per_kernel": n * 4}))
+
+
+# ------------------------------------------------------------------------------------------------
+# the largest configuration, once
+# ------------------------------------------------------------------------------------------------
+def measure_c5(torch, A, W, args, say):
+    """C5: one timed build over 10^8 points resident in HBM; the queries; the roofline of the
+    build's search kernel; the oracle on a sample of the last batch."""
+    t0 = time.time()
+    w = W.make("C5", args.c5_n, None)
+    pts = torch.from_numpy(w.points).cuda()
+    qs = torch.from_numpy(w.queries).cuda()
+    t_gen = time.time() - t0
+    say(f"C5 inputs drawn and resident: {w.n} x {w.d} {w.points.dtype} ({t_gen:.1f} s)")
+    k = w.k
+    gt_rows = min(1000, qs.shape[0])
+    gt, kth = ground_truth(torch, pts, qs[:gt_rows], k, w.metric)
+    say(f"C5: exact neighbours of {gt_rows} queries computed")
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    g = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, metric=w.metric)
+    torch.cuda.synchronize()
+    build_s = time.perf_counter() - t0
+    rounds = int(g.info().rounds)
+    say(f"C5 timed build: {build_s:.2f} s, {rounds} batches")
+
+    sweep, best = sweep_queries(torch, A, g, pts, qs, k, w.search_L, gt, gt_rows, say, eps_list=(None,), reps=2)
+
+    # the query operating points, on the timed graph with its counters switched on from here
+    O, rows_q = None, None
+    if not args.no_cpu:
+        import oracle as O
+        rows_q = g.neighbors()
+        say("C5 graph copied to the host")
+    g.set_stats(True)
+    qs_stream = torch.from_numpy(W.make("C5", 0, STREAM_QUERIES).queries).cuda()
+    points = {}
+    for t in TARGETS:
+        points[t] = query_point(torch, A, O, w, g, pts, qs, qs_stream, k, best[t], gt, kth, gt_rows, rows_q,
+                                int(g.info().start))
+        say(f"C5 queries at recall {t}: {points[t]}")
+    del g, rows_q, qs_stream
+
+    # counters and phase times of the build, and the oracle's sample: a second build, with the
+    # statistics on (2 % slower), stopped before the last batch
+    cpu, distinct = None, 1.0
+    if not args.no_cpu:
+        cpu, st = cpu_baseline(torch, A, w, pts, rounds, 1, args.cpu_points or 20000, 500, say)
+        distinct = cpu.pop("_distinct_frac")
+        counted = f"the first {rounds - 1} of the {rounds} batches (a second build, with counters)"
+    else:
+        gs = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, metric=w.metric, collect_stats=True)
+        st = gs.stats()
+        del gs
+        counted = "a second build, with counters"
+    out = {
+        "workload": workload_text(w, qs.shape[0], k), "note": w.note, "builds_timed": 1,
+        "build_s": round(build_s, 3), "points_per_s": round(w.n / build_s, 1),
+        "build_counters": {kk: int(st[kk]) for kk in ("searches", "hops", "evals", "prunes", "reprunes", "appends",
+                                                      "edges", "prune_evals", "redone", "restarts", "rounds")},
+        "build_phase_ms": {kk: round(st[kk], 1) for kk in ("ms_search", "ms_prune", "ms_sort", "ms_merge", "ms_total")},
+        "counters_cover": counted,
+        "roofline": build_roofline(st, w, distinct, measured_traffic("C5")),
+        "qps_at_recall_0.90": points[0.90], "qps_at_recall_0.95": points[0.95],
+        "recall_measured_on": f"the first {gt_rows} queries (exact neighbours by exhaustive search)",
+        "search_sweep": sweep, "datagen_s": round(t_gen, 1),
+    }
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
+    return out
 
 
 def main():
@@ -105,18 +408,35 @@ def main():
     ap.add_argument("--cpu-points", type=int, default=None,
                     help="instead: the oracle inserts only this many points of the last batch (large inputs)")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-c5", action="store_true", help="leave out the single run at 10^8 points")
+    ap.add_argument("--c5-n", type=int, default=None, help="points of that run (default: the configuration's 10^8)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="leave out streaming insertion, the layered index and the clustering-based builder")
     ap.add_argument("--filter-sweep", action="store_true",
                     help="also build with several sizes of the search's visited filter (Sec. 4.5) and report "
                          "the search time and distance evaluations of each")
+    ap.add_argument("--only-build", action="store_true", help="profiling: builds only (plus --search-L launches)")
+    ap.add_argument("--search-L", type=int, default=0)
+    ap.add_argument("--search-eps", type=float, default=None)
+    ap.add_argument("--search-nq", type=int, default=STREAM_QUERIES)
+    ap.add_argument("--search-reps", type=int, default=5)
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB")
+    ap.add_argument("--allocator", default="torch", choices=["torch", "hip"],
+                    help="where the library's device memory comes from: PyTorch's caching allocator through the "
+                         "alloc/free callbacks, or hipMalloc")
     ap.add_argument("--progress", action="store_true", help="print the steps to stderr as they finish")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
               "(no collectives or sharding are part of it)", file=sys.stderr)
         sys.exit(2)
+    if args.copy_probe:
+        copy_probe(args.copy_probe)
+        return
 
     t_start = time.time()
-    progress = args.progress or args.config == "C5"
+    with_c5 = args.config == "C2" and not args.no_c5 and not args.only_build and args.n is None
+    progress = args.progress or args.config == "C5" or with_c5
 
     def say(msg):
         if progress:
@@ -127,6 +447,10 @@ def main():
     from paper_2305_04359_amd import workloads as W
     A.lib()
     torch.cuda.set_device(0)
+    alloc = "torch" if args.allocator == "torch" else None
+
+    def build(**kw):
+        return A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, metric=metric, allocator=alloc, **kw)
 
     t_gen = time.time()
     w = W.make(args.config, args.n, args.nq)
@@ -138,35 +462,42 @@ def main():
     k = w.k
     row_bytes = w.d * w.points.dtype.itemsize
 
-    gt = ground_truth(torch, pts, qs, k, metric)
+    if args.only_build:
+        g = None
+        for i in range(args.warmup):
+            g = build()
+        torch.cuda.synchronize()
+        ms = []
+        for i in range(args.steps):
+            g = None
+            t0 = time.perf_counter()
+            g = build()
+            torch.cuda.synchronize()
+            ms.append((time.perf_counter() - t0) * 1e3)
+            say(f"build {i + 1}: {ms[-1]:.1f} ms")
+        out = {"only_build": True, "workload": workload_text(w, qs.shape[0], k), "build_ms": [round(x, 2) for x in ms]}
+        if args.search_L:
+            qx = torch.from_numpy(W.make(args.config, 0, args.search_nq).queries).cuda()
+            msq, _, _ = time_search(torch, A, g, pts, qx, k, args.search_L, reps=args.search_reps, eps=args.search_eps)
+            out["search"] = {"L": args.search_L, "eps": args.search_eps, "queries": int(qx.shape[0]), "ms": round(msq, 4)}
+        print(json.dumps(out))
+        return
+
+    gt_rows = qs.shape[0] if w.n <= 20_000_000 else min(1000, qs.shape[0])
+    gt, kth = ground_truth(torch, pts, qs[:gt_rows], k, metric)
     say("exact neighbours of the queries computed")
 
-    # warm-up builds; the first one also sweeps the two query parameters of Sec. 4.5, the beam
-    # width L and the eps of the (1 + eps) rule, and picks the fastest setting per recall target
-    sweep = []
-    best = {0.90: None, 0.95: None}
+    # warm-up builds; the first one also sweeps the query parameters and picks the fastest setting
+    # per recall target
+    sweep, best = [], {t: None for t in TARGETS}
     for i in range(max(1, args.warmup)):
-        g = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, metric=metric)
+        g = build()
         say(f"warm-up build {i + 1} done")
         if i == 0:
-            for eps in (None,) + EPS_SWEEP:
-                for L in sorted(set(w.search_L)):
-                    if L < k:
-                        continue
-                    ms, ids = time_search(torch, A, g, pts, qs, k, L, reps=3, eps=eps)
-                    r = recall(ids.cpu().numpy().view(np.uint32), gt)
-                    qps = qs.shape[0] / ms * 1e3
-                    sweep.append({"L": L, "eps": eps, "recall": round(r, 4), "qps": round(qps, 1)})
-                    say(f"queries at L={L} eps={eps}: recall {r:.4f}, {qps / 1e6:.2f} M/s")
-                    for target in best:
-                        if r >= target and (best[target] is None or qps > best[target][2]):
-                            best[target] = (L, eps, qps)
-                    if r >= 0.995:
-                        break
+            sweep, best = sweep_queries(torch, A, g, pts, qs, k, w.search_L, gt, gt_rows, say)
         del g
-    fallback = (max(w.search_L), None, 0.0)
-    L90, eps90, _ = best[0.90] or fallback
-    L95, eps95, _ = best[0.95] or fallback
+    # the step's search: the setting that reaches 0.90; where none does, the widest beam swept
+    L_step, eps_step = (best[0.90][0], best[0.90][1]) if best[0.90] else (max(w.search_L), None)
 
     # timed steps
     torch.cuda.synchronize()
@@ -177,25 +508,121 @@ def main():
             del g
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        g = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, metric=metric)
+        g = build()
         t1 = time.perf_counter()
-        A.ann_search(g, pts, qs, k, L90, eps=eps90)
+        A.ann_search(g, pts, qs, k, L_step, eps=eps_step)
         torch.cuda.synchronize()
         t2 = time.perf_counter()
         build_ms.append((t1 - t0) * 1e3)
         step_ms.append((t2 - t0) * 1e3)
         say(f"timed build: {(t1 - t0) * 1e3:.1f} ms")
+    rounds = int(g.info().rounds)
+    del g
+    # the same build with the library's own hipMalloc / hipFree instead of the allocator callbacks
+    other = None if alloc == "torch" else "torch"
+    torch.cuda.synchronize()
+    alt_ms = []
+    for _ in range(3 if w.n <= 20_000_000 else 0):
+        t0 = time.perf_counter()
+        gx = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, metric=metric, allocator=other)
+        torch.cuda.synchronize()
+        alt_ms.append((time.perf_counter() - t0) * 1e3)
+        del gx
     # one more build, untimed, with the library's counters and per-phase events switched on (they
-    # cost about 2 % of the build time): the source of the roofline figures
-    gs = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, metric=metric, collect_stats=True)
+    # cost about 2 % of the build time): the source of the roofline figures and of the query counters
+    gs = build(collect_stats=True)
     st = gs.stats()
-    del gs
     say("build with statistics done")
-    # streaming insertion (not part of the step): a graph over the first 90 % of the points takes
-    # the last 10 % with ann_insert_points, i.e. the same batches of theta points the build ends
-    # with, each followed by a host check
+
+    cpu, rows_final = None, None
+    distinct_frac = 1.0
+    O = None
+    if not args.no_cpu:
+        import oracle as O
+        cpu_points = args.cpu_points if args.cpu_points is not None else (20000 if w.n > 20_000_000 else None)
+        cpu, _ = cpu_baseline(torch, A, w, pts, rounds, args.cpu_batches, cpu_points,
+                              500 if w.n > 20_000_000 else 3000, say)
+        distinct_frac = cpu.pop("_distinct_frac")
+        rows_final = gs.neighbors()
+
+    # the query path at its two operating points
+    qs_stream = torch.from_numpy(W.make(args.config, 0, STREAM_QUERIES).queries).cuda()
+    start = int(gs.info().start)
+    qpoints = {t: query_point(torch, A, O, w, gs, pts, qs, qs_stream, k, best[t], gt, kth, gt_rows, rows_final, start)
+               for t in TARGETS}
+    say("query operating points measured")
+    del gs, rows_final
+
+    extras = {}
+    if not args.no_extras:
+        extras = measure_extras(torch, A, w, pts, qs, k, gt, gt_rows, best, say)
+    # the size of the visited filter (Sec. 4.5: a small lossy table beats an exact one): search
+    # time and evaluations of the build per table size; hash_bits = log2 of the size in words
+    filter_sweep = None
+    if args.filter_sweep:
+        filter_sweep = []
+        for hb in (0, 8, 9, 10, 11, 12, 13):
+            gf = build(collect_stats=True, hash_bits=hb)
+            sf = gf.stats()
+            filter_sweep.append({"hash_bits": hb if hb else "auto", "table_bytes": (4 << hb) if hb else None,
+                                 "ms_search": round(sf["ms_search"], 2), "ms_total": round(sf["ms_total"], 2),
+                                 "evals_per_search": round(sf["evals"] / max(1, sf["searches"]), 1)})
+            del gf
+            say(f"filter sweep: hash_bits={hb} search {sf['ms_search']:.1f} ms")
+    ms_per_step = float(np.mean(step_ms))
+    bms = float(np.mean(build_ms))
+    points_per_s = w.n / (bms / 1e3)
+
+    out = {
+        "metric": "index build points/sec; query QPS at recall@10=0.90 (1 GPU, HBM GB/s)",
+        "value": round(points_per_s, 1), "unit": "points/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 2), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": {np.dtype("uint8"): "u8", np.dtype("int8"): "i8", np.dtype("float32"): "f32"}[w.points.dtype],
+        "data": "synthetic",
+        "config": {"workload": workload_text(w, qs.shape[0], k), "note": w.note,
+                   "also_measured": "C5 (n=10^8), once, under \"c5\"" if with_c5 else None},
+        "build_ms": round(bms, 2),
+        "allocator": {"timed_builds": "PyTorch caching allocator (alloc/free callbacks)" if alloc else "hipMalloc",
+                      "build_ms_other": round(float(np.median(alt_ms)), 2) if alt_ms else None,
+                      "other": "PyTorch caching allocator (alloc/free callbacks)" if other else "hipMalloc"},
+        "qps_at_recall_0.90": qpoints[0.90],
+        "qps_at_recall_0.95": qpoints[0.95],
+        "search_sweep": sweep,
+        "filter_sweep": filter_sweep,
+        **extras,
+        "build_counters": {kk: int(st[kk]) for kk in ("searches", "hops", "evals", "prunes", "reprunes", "appends",
+                                                      "edges", "prune_evals", "redone", "rounds", "passes", "survivors",
+                                                      "insert_hops")},
+        "build_phase_ms": {kk: round(st[kk], 2) for kk in ("ms_search", "ms_prune", "ms_sort", "ms_merge", "ms_total")},
+        "roofline": build_roofline(st, w, distinct_frac, measured_traffic(w.name)),
+        "datagen_s": round(t_gen, 1),
+    }
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
+    if with_c5:
+        del pts, qs, qs_stream
+        torch.cuda.empty_cache()
+        out["c5"] = measure_c5(torch, A, W, args, say)
+    out["bench_wall_s"] = round(time.time() - t_start, 1)
+    print(json.dumps(out))
+
+
+def measure_extras(torch, A, w, pts, qs, k, gt, gt_rows, best, say):
+    """Streaming insertion, the layered index and the clustering-based builder over the same
+    points (not part of the step)."""
+    metric = w.metric
+    row_bytes = w.d * w.points.dtype.itemsize
+    L90, eps90 = (best[0.90][0], best[0.90][1]) if best[0.90] else (max(w.search_L), None)
+
+    def rec(ids):
+        return recall(ids[:gt_rows].cpu().numpy().view(np.uint32), gt)
+
+    # streaming insertion: a graph over the first 90 % of the points takes the last 10 % with
+    # ann_insert_points, i.e. the same batches of theta points the build ends with, each followed
+    # by a host check
     stream = None
-    if w.n <= 20_000_000 and w.n >= 1000:
+    if 1000 <= w.n <= 20_000_000:
         n0 = w.n - w.n // 10
         gi = A.ann_build(pts[:n0], w.R, w.L, w.alpha, seed=w.seed, metric=metric)
         torch.cuda.synchronize()
@@ -204,15 +631,38 @@ def main():
         torch.cuda.synchronize()
         t_ins = time.perf_counter() - t0
         batches = int(gi.info().rounds)
-        ms_i, ids_i = time_search(torch, A, gi, pts, qs, k, L90, reps=1, eps=eps90)
+        _, ids_i, _ = time_search(torch, A, gi, pts, qs, k, L90, reps=1, eps=eps90)
         stream = {"graph_points": n0, "new_points": w.n - n0, "ms": round(t_ins * 1e3, 2),
-                  "points_per_s": round((w.n - n0) / t_ins, 1),
-                  "recall_after": round(recall(ids_i.cpu().numpy().view(np.uint32), gt), 4),
+                  "points_per_s": round((w.n - n0) / t_ins, 1), "recall_after": round(rec(ids_i), 4),
                   "total_batches": batches}
         del gi
         say(f"streaming insertion of {w.n - n0} points: {t_ins * 1e3:.1f} ms")
-    # the layered index of Sec. 4.2 over the same points (not part of the step): m = R/2, efc = L
-    # as in the appendix; alpha is the flat graph's (the appendix quotes its reciprocal)
+
+    def sweep_L(search):
+        out, bst = [], {t: None for t in TARGETS}
+        for L in sorted(set(w.search_L)):
+            if L < k:
+                continue
+            ms_l = []
+            for rep in range(4):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                ids = search(L)
+                e1.record()
+                torch.cuda.synchronize()
+                if rep:
+                    ms_l.append(e0.elapsed_time(e1))
+            r = rec(ids)
+            out.append({"L": L, "recall": round(r, 4), "qps": round(qs.shape[0] / float(np.median(ms_l)) * 1e3, 1)})
+            for t in bst:
+                if r >= t and (bst[t] is None or out[-1]["qps"] > bst[t]["qps"]):
+                    bst[t] = out[-1]
+            if r >= 0.995:
+                break
+        return out, bst
+
+    # the layered index of Sec. 4.2: m = R/2, efc = L as in the appendix; alpha is the flat
+    # graph's (the appendix quotes its reciprocal)
     layered = None
     if w.n <= 20_000_000 and w.R % 2 == 0:
         hb = []
@@ -224,37 +674,15 @@ def main():
             hb.append((time.perf_counter() - t0) * 1e3)
             if i == 0:
                 del hx
-        hsweep = []
-        hbest = {0.90: None, 0.95: None}
-        for L in sorted(set(w.search_L)):
-            if L < k:
-                continue
-            torch.cuda.synchronize()
-            ms_l = []
-            for rep in range(4):
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                hid, _ = A.ann_hnsw_search(hx, pts, qs, k, L)
-                e1.record()
-                torch.cuda.synchronize()
-                if rep:
-                    ms_l.append(e0.elapsed_time(e1))
-            r = recall(hid.cpu().numpy().view(np.uint32), gt)
-            qps = qs.shape[0] / float(np.median(ms_l)) * 1e3
-            hsweep.append({"L": L, "recall": round(r, 4), "qps": round(qps, 1)})
-            for target in hbest:
-                if r >= target and (hbest[target] is None or qps > hbest[target]["qps"]):
-                    hbest[target] = hsweep[-1]
-            if r >= 0.995:
-                break
+        hsweep, hbest = sweep_L(lambda L: A.ann_hnsw_search(hx, pts, qs, k, L)[0])
         hi = hx.info()
         layered = {"m": w.R // 2, "efc": w.L, "alpha": w.alpha, "layers": int(hi.top) + 1,
                    "build_ms": round(hb[-1], 2), "points_per_s": round(w.n / hb[-1] * 1e3, 1),
                    "qps_at_recall_0.90": hbest[0.90], "qps_at_recall_0.95": hbest[0.95], "search_sweep": hsweep}
         del hx
         say(f"layered index: build {hb[-1]:.1f} ms")
-    # the clustering-based builder of Sec. 4.3 over the same points (not part of the step), with
-    # the appendix's parameters (30 trees, leaves of 1,000, tree degree 3) and l = 10 (Sec. 4.3)
+    # the clustering-based builder of Sec. 4.3 with the appendix's parameters (30 trees, leaves of
+    # 1,000, tree degree 3) and l = 10 (Sec. 4.3)
     clustered = None
     if w.n <= 20_000_000 and (row_bytes <= 128 if w.points.dtype != np.float32 else w.d <= 256):
         cb = []
@@ -266,20 +694,7 @@ def main():
             cb.append((time.perf_counter() - t0) * 1e3)
             if i == 0:
                 del gc
-        csweep = []
-        cbest = {0.90: None, 0.95: None}
-        for L in sorted(set(w.search_L)):
-            if L < k:
-                continue
-            ms_c, cid = time_search(torch, A, gc, pts, qs, k, L, reps=3)
-            r = recall(cid.cpu().numpy().view(np.uint32), gt)
-            qps = qs.shape[0] / ms_c * 1e3
-            csweep.append({"L": L, "recall": round(r, 4), "qps": round(qps, 1)})
-            for target in cbest:
-                if r >= target and (cbest[target] is None or qps > cbest[target]["qps"]):
-                    cbest[target] = csweep[-1]
-            if r >= 0.995:
-                break
+        csweep, cbest = sweep_L(lambda L: A.ann_search(gc, pts, qs, k, L)[0])
         cdeg = float((gc.neighbors() != 0xFFFFFFFF).sum(1).mean())
         clustered = {"trees": 30, "leaf_size": 1000, "tree_degree": 3, "knn": 10, "R": w.R, "alpha": w.alpha,
                      "build_ms": round(cb[-1], 2), "points_per_s": round(w.n / cb[-1] * 1e3, 1),
@@ -287,161 +702,7 @@ def main():
                      "qps_at_recall_0.90": cbest[0.90], "qps_at_recall_0.95": cbest[0.95], "search_sweep": csweep}
         del gc
         say(f"clustering-based build: {cb[-1]:.1f} ms")
-    # the size of the visited filter (Sec. 4.5: a small lossy table beats an exact one): search
-    # time and evaluations of the build per table size; hash_bits = log2 of the size in words
-    filter_sweep = None
-    if args.filter_sweep:
-        filter_sweep = []
-        for hb in (0, 8, 9, 10, 11, 12, 13):
-            gf = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, metric=metric, collect_stats=True, hash_bits=hb)
-            sf = gf.stats()
-            filter_sweep.append({"hash_bits": hb if hb else "auto", "table_bytes": (4 << hb) if hb else None,
-                                 "ms_search": round(sf["ms_search"], 2), "ms_total": round(sf["ms_total"], 2),
-                                 "evals_per_search": round(sf["evals"] / max(1, sf["searches"]), 1)})
-            del gf
-            say(f"filter sweep: hash_bits={hb} search {sf['ms_search']:.1f} ms")
-    ms_per_step = float(np.mean(step_ms))
-    bms = float(np.mean(build_ms))
-    points_per_s = w.n / (bms / 1e3)
-
-    ms90, ids90 = time_search(torch, A, g, pts, qs, k, L90, eps=eps90)
-    ms95, ids95 = time_search(torch, A, g, pts, qs, k, L95, eps=eps95)
-    r90 = recall(ids90.cpu().numpy().view(np.uint32), gt)
-    r95 = recall(ids95.cpu().numpy().view(np.uint32), gt)
-    # the workload's 10,000 queries are 1.2 waves per wave slot of the chip, so the figures above are
-    # the latency of two generations of searches; ten times the queries (the same ones, repeated)
-    # show the rate of a stream of queries
-    qs10 = qs.repeat(10, 1)
-    ms90x, _ = time_search(torch, A, g, pts, qs10, k, L90, reps=3, eps=eps90)
-    ms95x, _ = time_search(torch, A, g, pts, qs10, k, L95, reps=3, eps=eps95)
-    del qs10
-
-    cpu = None
-    distinct_frac = 1.0
-    if not args.no_cpu:
-        cpu_points = args.cpu_points if args.cpu_points is not None else (20000 if w.n > 20_000_000 else None)
-        cpu = cpu_baseline(torch, A, w, pts, g, args.cpu_batches, cpu_points, say)
-        distinct_frac = cpu.pop("_distinct_frac")
-
-    # roofline of the dominant kernel: the build's beam search.  Algorithmic bytes per launch =
-    # hops * 4R (adjacency rows) + DISTINCT distance evaluations * row bytes (gathered vectors)
-    # + 8 * hops (visited list), averaged over the launches of the timed build.  The kernel counts
-    # every evaluation, repeated ones included (its visited filter is lossy); the share of distinct
-    # ones is measured on the batches the oracle re-runs for the CPU baseline.
-    evals_distinct = st["evals"] * distinct_frac
-    srch_bytes = st["hops"] * 4 * w.R + evals_distinct * row_bytes + 8 * st["hops"]
-    srch_s = st["ms_search"] / 1e3
-    achieved = srch_bytes / srch_s / 1e9 if srch_s > 0 else 0.0
-    roofline = {
-        "bound": "hbm", "kernel": "search_kernel (build, step 1 of BatchInsert)",
-        "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(w.name),
-        "launches": int(st["rounds"]), "avg_launch_ms": round(st["ms_search"] / max(1, st["rounds"]), 4),
-        "bytes_per_launch": int(srch_bytes / max(1, st["rounds"])),
-        "distinct_eval_fraction": round(distinct_frac, 4),
-    }
-    phases = {kk: round(st[kk], 2) for kk in ("ms_search", "ms_prune", "ms_sort", "ms_merge", "ms_total")}
-
-    out = {
-        "metric": "index build points/sec; query QPS at recall@10=0.90 (1 GPU, HBM GB/s)",
-        "value": round(points_per_s, 1), "unit": "points/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 2), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None,
-        "dtype": {np.dtype("uint8"): "u8", np.dtype("int8"): "i8", np.dtype("float32"): "f32"}[w.points.dtype],
-        "data": "synthetic",
-        "config": {"workload": f"{w.name}: n={w.n} d={w.d} {w.points.dtype} "
-                               f"{'L2sq' if metric == 0 else 'neg-inner-product'}, R={w.R} L={w.L} alpha={w.alpha}, "
-                               f"theta={w.theta}, nq={qs.shape[0]} k={k}", "note": w.note},
-        "build_ms": round(bms, 2),
-        "qps_at_recall_0.90": {"L": L90, "eps": eps90, "recall": round(r90, 4),
-                               "qps": round(qs.shape[0] / ms90 * 1e3, 1)},
-        "qps_at_recall_0.95": {"L": L95, "eps": eps95, "recall": round(r95, 4),
-                               "qps": round(qs.shape[0] / ms95 * 1e3, 1)},
-        "qps_stream_of_queries": {"queries": int(qs.shape[0]) * 10,
-                                  "at_recall_0.90": round(qs.shape[0] * 10 / ms90x * 1e3, 1),
-                                  "at_recall_0.95": round(qs.shape[0] * 10 / ms95x * 1e3, 1)},
-        "search_sweep": sweep,
-        "filter_sweep": filter_sweep,
-        "stream_insert": stream,
-        "layered_index": layered,
-        "clustering_based": clustered,
-        "build_counters": {kk: int(st[kk]) for kk in ("searches", "hops", "evals", "prunes", "reprunes", "appends",
-                                                      "edges", "prune_evals", "redone", "rounds")},
-        "build_phase_ms": phases,
-        "roofline": roofline,
-        "datagen_s": round(t_gen, 1),
-    }
-
-    if cpu is not None:
-        out["cpu_baseline"] = cpu
-    print(json.dumps(out))
-
-
-def measured_traffic(workload):
-    """HBM bytes per launch of the search kernel from the committed rocprofv3 --pmc summary
-    (FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size), or None."""
-    path = os.path.join(ROOT, "profiles", "search_kernel_traffic.json")
-    try:
-        with open(path) as f:
-            return json.load(f).get(workload, {}).get("bytes_per_launch")
-    except (OSError, ValueError):
-        return None
-
-
-def cpu_baseline(torch, A, w, pts, g_full, nbatches, npoints_only=None, say=lambda m: None):
-    """The oracle, as it stands, runs the LAST `nbatches` batches of the build on all host cores,
-    starting from the graph as it stood before them (taken from a GPU build stopped early).  The
-    GPU inserts the same batches into the same snapshot and the resulting graphs are compared.
-    With `npoints_only` the sample is one batch made of the first so many points of the last
-    batch (for inputs whose batches would take the oracle many minutes)."""
-    import oracle as O
-    rounds = int(g_full.info().rounds)
-    metric = w.metric
-    nb = 1 if npoints_only else max(1, min(nbatches, rounds - 1))
-    snap = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, metric=metric, max_rounds=rounds - nb,
-                       collect_stats=True)
-    st0 = snap.stats()
-    say("snapshot built on the GPU")
-    rows = snap.neighbors()
-    say("snapshot copied to the host")
-    s = int(snap.info().start)
-    ds = O.Dataset(w.points, metric)
-    order = O.insertion_order(w.n, s, w.seed)
-    bounds = O.schedule(w.n - 1, w.theta).astype(np.int64)
-    batches = [order[bounds[r]:bounds[r + 1]] for r in range(rounds - nb, rounds)]
-    if npoints_only:
-        batches = [batches[0][:npoints_only]]
-    cores = O.threads(0)
-    ost = O.Stats()
-    og = rows.copy()
-    npoints = 0
-    t0 = time.perf_counter()
-    for batch in batches:
-        O.batch_insert(ds, og, s, batch, w.L, w.alpha, threads=0, stats=ost)
-        npoints += len(batch)
-    cpu_s = time.perf_counter() - t0
-    say(f"oracle inserted {npoints} points in {cpu_s:.1f} s")
-    for batch in batches:
-        A.ann_insert_batch(snap, pts, batch, w.L, w.alpha)
-    st1 = snap.stats()
-    gg = snap.neighbors()
-    same, step = 0, 1 << 22
-    for i in range(0, len(gg), step):
-        same += int((gg[i:i + step] == og[i:i + step]).all(1).sum())
-    same_rows = same / len(gg)
-    gpu_evals = st1["evals"] - st0["evals"]
-    what = (f"one batch of the first {npoints} points of the last batch" if npoints_only
-            else f"the last {nb} batch(es) of the build, {npoints} points")
-    return {
-        "value": round(npoints / cpu_s, 1), "unit": "points/s", "cores": cores, "kind": "oracle",
-        "sample": f"{what}, inserted into the {int(bounds[rounds - nb]) + 1}-point graph that precedes them, "
-                  f"{cpu_s:.1f} s of wall time on {cores} threads",
-        "rows_identical_to_gpu": same_rows,
-        "oracle_hops_per_search": round(ost.hops / max(1, ost.searches), 2),
-        "oracle_evals_per_search": round(ost.evals / max(1, ost.searches), 2),
-        "gpu_evals_per_search_same_batches": round(gpu_evals / max(1, npoints), 2),
-        "_distinct_frac": min(1.0, ost.evals / max(1, gpu_evals)),
-    }
+    return {"stream_insert": stream, "layered_index": layered, "clustering_based": clustered}
 
 
 if __name__ == "__main__":

@@ -29,11 +29,18 @@
  *     outputs are untouched, *out handles are NULL and ann_last_error()
  *     describes the failure.  No exception or abort crosses this boundary.
  *   - `stream` is a hipStream_t passed as void* (NULL = default stream).
- *   - The library allocates its own scratch with hipMalloc and frees it
- *     before returning, except for what an object keeps until it is freed:
+ *   - The library allocates its own scratch and frees it before returning,
+ *     except for what an object keeps until it is freed: the adjacency rows,
  *     the padded copies named above, and the scratch of ann_insert_batch /
- *     ann_insert_points (sized for the largest batch so far).  The caller
- *     owns every buffer it passes in.
+ *     ann_insert_points (sized for the largest batch so far).  The memory
+ *     comes from hipMalloc / hipFree, or from the `alloc` / `free` callbacks
+ *     of ann_build_opts / ann_hnsw_opts, which the object then keeps for all
+ *     its later allocations and for its own release (the clustering-based
+ *     builder always uses hipMalloc).  The caller owns every buffer it
+ *     passes in.
+ *   - Calls that use one graph or index object must be issued on one stream
+ *     (or be ordered by the caller): the object's padded query copy and
+ *     insertion scratch are shared by all calls on it.
  *   - With ANN_TRACE_BUILD set in the environment, ann_build,
  *     ann_insert_points and ann_hcnng_build print a wall-clock breakdown of
  *     their phases on stderr (the clustering-based builder waits for the
@@ -42,6 +49,7 @@
 #ifndef ANN_H
 #define ANN_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -64,6 +72,18 @@ typedef enum {
 /* Opaque graph handle.  Owns the device memory of the n x R adjacency rows. */
 typedef struct ann_graph ann_graph;
 
+/* Device-memory callbacks (Sec. 2's problem statement leaves memory to the
+ * caller; a host program that runs its own caching allocator hands it in
+ * here).  `alloc` returns a device pointer aligned to at least 256 bytes that
+ * is valid on `stream` (the stream of the call that allocates), or NULL when
+ * it has no memory: the call then fails with ANN_ENOMEM.  `free` takes back a
+ * pointer `alloc` returned; the library has waited for its own work on that
+ * memory, except in ann_graph_free / ann_hnsw_free, which do not wait for
+ * searches the caller still has in flight.  Neither may call into this
+ * library.  Both are called on the thread of the API call that needs them. */
+typedef void* (*ann_alloc_fn)(size_t bytes, void* stream, void* user);
+typedef void (*ann_free_fn)(void* ptr, void* user);
+
 /* Optional knobs of ann_build.  Zero-initialise, then set what is needed.   */
 typedef struct {
   uint64_t batch_cap;    /* theta, the batch-size bound of Sec. 3.1; 0 = max(1, n/50)  */
@@ -79,6 +99,9 @@ typedef struct {
                             The filter only saves work; results do not depend on it.   */
   uint64_t max_rounds;   /* stop after this many batches (0 = all): partial builds     */
   uint32_t collect_stats;/* non-zero: count hops, distance evaluations, ... (slower)   */
+  ann_alloc_fn alloc;    /* device memory for the graph and all scratch; NULL = hipMalloc */
+  ann_free_fn free;      /* its counterpart; both or neither                           */
+  void* alloc_user;      /* passed to both                                             */
 } ann_build_opts;
 
 typedef struct {
@@ -121,7 +144,8 @@ typedef struct {
  *
  *   points_dev  n x d elements of `dtype` (device)
  *   alpha       > 0 (must be <= 1 for ANN_MIPS, Appendix A).  For u8/i8 it is
- *               quantised to llround(alpha * 65536) / 65536.
+ *               quantised to llround(alpha * 65536) / 65536, which must be
+ *               at least 1 / 65536.
  *   seed        drives the insertion order (SplitMix64 Fisher-Yates)
  *   opts        may be NULL
  *   *out        receives the graph; free with ann_graph_free
@@ -133,8 +157,8 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
 
 /*
  * BatchInsert(P') of Alg. 3 on an existing graph: inserts the `b` points whose
- * ids are in ids_host (all < n, not yet inserted, none equal to the start
- * vertex) as ONE batch.  `points_dev` must be the array the graph was built
+ * ids are in ids_host (all < n, none twice, none equal to the start vertex,
+ * none with out-neighbours already: ANN_EINVAL otherwise) as ONE batch.  `points_dev` must be the array the graph was built
  * over.  Blocks until done.
  */
 int ann_insert_batch(ann_graph* g, const void* points_dev, const uint32_t* ids_host, uint64_t b,
@@ -179,7 +203,8 @@ int ann_graph_reserve(ann_graph* g, uint64_t n_cap, void* stream);
  *   ids_dev      nq x k uint32 (device): the k closest found, ascending by
  *                (distance, id); ANN_NONE where fewer than k were reached
  *   dists_dev    nq x k int32 (u8/i8) or float (f32); INT32_MAX / +inf padding
- * Requires 1 <= k <= L <= 512.  Asynchronous on `stream`.
+ * Requires 1 <= k <= L <= 2048 (the beam of Sec. 4.5's sweeps; builds take L <= 512).
+ * Asynchronous on `stream`.
  */
 int ann_search(const ann_graph* g, const void* points_dev, const void* queries_dev, uint64_t nq,
                uint32_t k, uint32_t L, uint32_t* ids_dev, void* dists_dev, void* stream);
@@ -217,6 +242,10 @@ const uint32_t* ann_graph_device_rows(const ann_graph* g);
 
 int ann_graph_info(const ann_graph* g, ann_graph_info_t* info);
 int ann_get_stats(const ann_graph* g, ann_stats* stats); /* cumulative over build + inserts */
+/* Switches the counters of ann_get_stats on or off for the calls that follow
+ * (builds start with opts->collect_stats).  With them on, searches on this
+ * graph add their hops and distance evaluations too.                        */
+int ann_graph_set_stats(ann_graph* g, int on);
 void ann_graph_free(ann_graph* g);
 
 /* Stable LSD radix sort of `count` 64-bit keys by bits [32, 32+key_bits) only
@@ -250,6 +279,9 @@ typedef struct {
   const uint32_t* level;  /* host, n levels (each <= 63); NULL = drawn from seed   */
   uint64_t max_rounds;    /* stop after this many batches (0 = all)                */
   uint32_t collect_stats; /* non-zero: counters and phase times (slower)           */
+  ann_alloc_fn alloc;     /* device memory for the index and all scratch; NULL =    */
+  ann_free_fn free;       /* hipMalloc / hipFree; both or neither                   */
+  void* alloc_user;
 } ann_hnsw_opts;
 
 typedef struct {
@@ -338,6 +370,11 @@ void ann_hnsw_free(ann_hnsw* h);
  *   1 <= T < 2^20, 2 <= Ls <= 1024, 1 <= l <= 16, Ls * l <= 16384,
  *   1 <= s <= 255, 1 <= R <= 512, T * 2n < 2^32.
  * Blocks until done.
+ * Test-only option: with ANN_HCNNG_FEW_TILES set in the environment the
+ * buffer of leaf tiles starts with room for one tile, so that every build
+ * takes the path that allocates it again at the size a group of trees needs
+ * (otherwise reached only by inputs that split into very many tiny leaves).
+ * The result does not depend on it.
  * ------------------------------------------------------------------------ */
 int ann_hcnng_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric,
                     uint32_t T, uint32_t Ls, uint32_t s, uint32_t l, uint32_t R, float alpha, uint64_t seed,

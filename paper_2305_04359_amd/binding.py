@@ -35,6 +35,9 @@ class BuildOpts(C.Structure):
         ("hash_bits", C.c_uint32),
         ("max_rounds", C.c_uint64),
         ("collect_stats", C.c_uint32),
+        ("alloc", C.c_void_p),
+        ("free", C.c_void_p),
+        ("alloc_user", C.c_void_p),
     ]
 
 
@@ -55,7 +58,8 @@ class Stats(C.Structure):
 
 class HnswOpts(C.Structure):
     _fields_ = [("batch_cap", C.c_uint64), ("order", C.c_void_p), ("level", C.c_void_p),
-                ("max_rounds", C.c_uint64), ("collect_stats", C.c_uint32)]
+                ("max_rounds", C.c_uint64), ("collect_stats", C.c_uint32),
+                ("alloc", C.c_void_p), ("free", C.c_void_p), ("alloc_user", C.c_void_p)]
 
 
 class HnswInfo(C.Structure):
@@ -65,7 +69,7 @@ class HnswInfo(C.Structure):
 
 EXPORTS = [
     "ann_build", "ann_insert_batch", "ann_insert_points", "ann_graph_reserve", "ann_search", "ann_search_eps", "ann_start_vertex", "ann_graph_from_host",
-    "ann_graph_copy_neighbors", "ann_graph_device_rows", "ann_graph_info", "ann_get_stats",
+    "ann_graph_copy_neighbors", "ann_graph_device_rows", "ann_graph_info", "ann_get_stats", "ann_graph_set_stats",
     "ann_graph_free", "ann_sort_edges", "ann_last_error",
     "ann_hnsw_build", "ann_hnsw_insert_points", "ann_hnsw_from_host", "ann_hnsw_search", "ann_hnsw_info", "ann_hnsw_copy_levels", "ann_hnsw_layer_size",
     "ann_hnsw_copy_layer", "ann_hnsw_get_stats", "ann_hnsw_free",
@@ -114,6 +118,8 @@ def lib():
         L.ann_graph_info.argtypes = [vp, C.POINTER(GraphInfo)]
         L.ann_get_stats.restype = C.c_int
         L.ann_get_stats.argtypes = [vp, C.POINTER(Stats)]
+        L.ann_graph_set_stats.restype = C.c_int
+        L.ann_graph_set_stats.argtypes = [vp, C.c_int]
         L.ann_graph_free.restype = None
         L.ann_graph_free.argtypes = [vp]
         L.ann_sort_edges.restype = C.c_int
@@ -177,6 +183,69 @@ def _stream_ptr():
     return C.c_void_p(_torch().cuda.current_stream().cuda_stream)
 
 
+ALLOC_FN = C.CFUNCTYPE(C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p)
+FREE_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
+
+
+class TorchAllocator:
+    """The `alloc` / `free` callbacks of ann_build_opts / ann_hnsw_opts served by PyTorch's caching
+    allocator, so that the graph and every scratch buffer of a call are PyTorch's memory.  One
+    instance serves any number of calls; it must outlive every object built with it (the
+    objects made by this module keep a reference)."""
+
+    def __init__(self):
+        torch = _torch()
+        self.calls = 0
+        self.bytes = 0
+        self.live = 0
+
+        def _alloc(nbytes, stream, user):
+            try:
+                p = torch.cuda.caching_allocator_alloc(int(nbytes), stream=int(stream or 0))
+            except Exception:  # out of memory: the library reports ANN_ENOMEM
+                return None
+            self.calls += 1
+            self.bytes += int(nbytes)
+            self.live += 1
+            return p
+
+        def _free(ptr, user):
+            try:
+                torch.cuda.caching_allocator_delete(ptr)
+                self.live -= 1
+            except Exception:  # (interpreter shutting down: the process is about to end)
+                pass
+
+        self.alloc = ALLOC_FN(_alloc)
+        self.free = FREE_FN(_free)
+
+    def fill(self, opts):
+        opts.alloc = C.cast(self.alloc, C.c_void_p)
+        opts.free = C.cast(self.free, C.c_void_p)
+        opts.alloc_user = None
+
+
+_torch_allocator = None
+
+
+def torch_allocator() -> TorchAllocator:
+    """The shared TorchAllocator of this process."""
+    global _torch_allocator
+    if _torch_allocator is None:
+        _torch_allocator = TorchAllocator()
+    return _torch_allocator
+
+
+def _use_allocator(opts, allocator):
+    """Puts the callbacks of `allocator` into `opts`: "torch" = the process's TorchAllocator, None
+    = the library's own hipMalloc / hipFree, or any object with a fill(opts) method."""
+    if allocator is None:
+        return None
+    a = torch_allocator() if isinstance(allocator, str) and allocator == "torch" else allocator
+    a.fill(opts)
+    return a
+
+
 def _dev2d(t, name):
     if not t.is_cuda or t.dim() != 2 or not t.is_contiguous():
         raise ValueError(f"{name} must be a contiguous 2-D device tensor")
@@ -186,8 +255,9 @@ def _dev2d(t, name):
 class Graph:
     """Owner of an ann_graph handle."""
 
-    def __init__(self, handle):
+    def __init__(self, handle, allocator=None):
         self._h = C.c_void_p(handle)
+        self._allocator = allocator  # its callbacks are called when the graph is freed
 
     def close(self):
         if self._h:
@@ -214,6 +284,9 @@ class Graph:
         _check(lib().ann_get_stats(self._h, C.byref(st)))
         return st.as_dict()
 
+    def set_stats(self, on: bool) -> None:
+        _check(lib().ann_graph_set_stats(self._h, 1 if on else 0))
+
     def neighbors(self) -> np.ndarray:
         gi = self.info()
         out = np.empty((gi.n, gi.R), np.uint32)
@@ -222,10 +295,13 @@ class Graph:
 
 
 def ann_build(points, R, L, alpha, seed=1, metric=L2SQ, batch_cap=0, start=None, order=None,
-              visited_cap=0, hash_bits=0, max_rounds=0, collect_stats=False, spill_cap=0) -> Graph:
-    """batchBuild of Alg. 3 over a device tensor of points (n x d; uint8, int8 or float32)."""
+              visited_cap=0, hash_bits=0, max_rounds=0, collect_stats=False, spill_cap=0,
+              allocator="torch") -> Graph:
+    """batchBuild of Alg. 3 over a device tensor of points (n x d; uint8, int8 or float32).
+    The graph and the build's scratch are PyTorch's memory unless allocator=None."""
     points = _dev2d(points, "points")
     o = BuildOpts()
+    al = _use_allocator(o, allocator)
     o.batch_cap = batch_cap
     o.use_start = 0 if start is None else 1
     o.start = 0 if start is None else int(start)
@@ -243,7 +319,7 @@ def ann_build(points, R, L, alpha, seed=1, metric=L2SQ, batch_cap=0, start=None,
     h = C.c_void_p()
     _check(lib().ann_build(points.data_ptr(), points.shape[0], points.shape[1], _dtype_code(points),
                            int(metric), R, L, float(alpha), seed, C.byref(o), _stream_ptr(), C.byref(h)))
-    return Graph(h.value)
+    return Graph(h.value, al)
 
 
 def ann_insert_batch(graph: Graph, points, ids, L, alpha) -> None:
@@ -328,8 +404,9 @@ def ann_sort_edges(keys, key_bits: int) -> None:
 class Hnsw:
     """Owner of an ann_hnsw handle."""
 
-    def __init__(self, handle):
+    def __init__(self, handle, allocator=None):
         self._h = C.c_void_p(handle)
+        self._allocator = allocator  # its callbacks are called when the index is freed
 
     def close(self):
         if self._h:
@@ -374,10 +451,11 @@ class Hnsw:
 
 
 def ann_hnsw_build(points, m, efc, alpha, seed=1, metric=L2SQ, batch_cap=0, order=None, level=None,
-                   max_rounds=0, collect_stats=False) -> Hnsw:
+                   max_rounds=0, collect_stats=False, allocator="torch") -> Hnsw:
     """The layered index of Sec. 4.2 over a device tensor of points."""
     points = _dev2d(points, "points")
     o = HnswOpts()
+    al = _use_allocator(o, allocator)
     o.batch_cap = batch_cap
     o.max_rounds = max_rounds
     o.collect_stats = 1 if collect_stats else 0
@@ -397,7 +475,7 @@ def ann_hnsw_build(points, m, efc, alpha, seed=1, metric=L2SQ, batch_cap=0, orde
     h = C.c_void_p()
     _check(lib().ann_hnsw_build(points.data_ptr(), points.shape[0], points.shape[1], _dtype_code(points),
                                 int(metric), m, efc, float(alpha), seed, C.byref(o), _stream_ptr(), C.byref(h)))
-    return Hnsw(h.value)
+    return Hnsw(h.value, al)
 
 
 def ann_hnsw_insert_points(index: Hnsw, points, efc, alpha, seed=1, batch_cap=0, order=None, level=None,

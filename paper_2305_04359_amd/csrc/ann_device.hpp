@@ -69,7 +69,9 @@ __device__ __forceinline__ u64 readlane_u64(u64 v, int lane) {
 // by a vector instruction must not be read by a vector instruction in the next few issue slots.
 // The compiler pads its own instructions for that, but not the text of an asm statement (with
 // the write directly behind the compare the lanes were seen to keep their old value), so the
-// wait states are part of the statement.
+// wait states are part of the statement: four, what the instruction-set manual asks between a
+// vector instruction that writes a scalar register and a lane instruction that reads it.  (This
+// compiler offers no writelane builtin, which would leave the counting to it.)
 template <int LO, int HI>
 __device__ __forceinline__ u32 writelane_pair(u32 old, u64 m) {
   const u32 lo = (u32)m, hi = (u32)(m >> 32);

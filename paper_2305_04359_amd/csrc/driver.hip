@@ -20,6 +20,33 @@ int fail(int code, const char* fmt, ...) {
 
 const char* last_error_text() { return g_err.c_str(); }
 
+Allocator& current_allocator() {
+  static thread_local Allocator a;
+  return a;
+}
+
+bool allocator_from(ann_alloc_fn a, ann_free_fn f, void* user, void* stream, Allocator* out) {
+  *out = Allocator{};
+  if ((a == nullptr) != (f == nullptr)) return false;
+  out->alloc = a;
+  out->free = f;
+  out->user = a != nullptr ? user : nullptr;
+  out->stream = a != nullptr ? stream : nullptr;
+  return true;
+}
+
+int on_exception() {
+  try {
+    throw;
+  } catch (const std::bad_alloc&) {
+    return fail(ANN_ENOMEM, "host allocation failed");
+  } catch (const std::exception& e) {
+    return fail(ANN_EINTERNAL, "exception: %s", e.what());
+  } catch (...) {
+    return fail(ANN_EINTERNAL, "unknown exception");
+  }
+}
+
 bool make_cfg(uint32_t d, int dtype, int metric, DistCfg* cfg, std::string* why) {
   const u64 esz = dtype == ANN_F32 ? 4 : 1;
   const u64 rb = (u64)d * esz;
@@ -105,6 +132,12 @@ __global__ __launch_bounds__(256) void pad_rows_kernel(const unsigned char* src,
   dst[w] = v;
 }
 
+// how many of the listed vertices have out-neighbours (degree in the low 16 bits of meta)
+__global__ __launch_bounds__(256) void count_inserted_kernel(const u32* ids, u64 b, const u32* meta, u32* count) {
+  const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < b && (meta[ids[i]] & 0xFFFFu) != 0u) atomicAdd(count, 1u);
+}
+
 int pad_rows(const void* src, u64 nrows, u32 rb, void* dst, u64 stride, hipStream_t st) {
   const u64 words = nrows * (stride / 4);
   if (words == 0) return ANN_OK;
@@ -123,14 +156,14 @@ int resolve_points(const ann_graph* g, const void* points_dev, hipStream_t st, c
   if (g->pad_cap < g->n) {
     if (g->pad_buf) {
       HIP_TRY(hipDeviceSynchronize());  // earlier calls may still read the old copy
-      (void)hipFree(g->pad_buf);
+      g->al.put(g->pad_buf);
       g->pad_buf = nullptr;
     }
     g->pad_cap = 0;
     g->pad_src = nullptr;
     g->pad_done = 0;
     const u64 want = g->cap > g->n ? g->cap : g->n;
-    HIP_TRY(hipMalloc(&g->pad_buf, (size_t)want * g->pad_stride));
+    HIP_TRY(g->al.get(&g->pad_buf, (size_t)want * g->pad_stride));
     g->pad_cap = want;
   }
   if (g->pad_src != points_dev) g->pad_done = 0;
@@ -152,12 +185,13 @@ int resolve_queries(const ann_graph* g, const void* queries_dev, u64 nq, hipStre
   if (!g->pad_stride) return ANN_OK;
   if (g->qpad_rows < nq) {
     if (g->qpad_buf) {
-      HIP_TRY(hipStreamSynchronize(st));  // an earlier call may still read the old buffer
-      (void)hipFree(g->qpad_buf);
+      // an earlier call, on whatever stream it was issued, may still read the old buffer
+      HIP_TRY(hipDeviceSynchronize());
+      g->al.put(g->qpad_buf);
       g->qpad_buf = nullptr;
       g->qpad_rows = 0;
     }
-    HIP_TRY(hipMalloc(&g->qpad_buf, (size_t)nq * g->pad_stride));
+    HIP_TRY(g->al.get(&g->qpad_buf, (size_t)nq * g->pad_stride));
     g->qpad_rows = nq;
   }
   int rc = pad_rows(queries_dev, nq, g->d, g->qpad_buf, g->pad_stride, st);
@@ -457,6 +491,9 @@ int query_launch(const ann_graph* g, const void* pts, const void* queries, const
 int check_insert_params(const ann_graph* g, uint32_t L, float alpha) {
   if (L < 1 || L > 512) return fail(ANN_EINVAL, "L must be in [1, 512]");
   if (!(alpha > 0.0f) || !std::isfinite(alpha) || alpha > 30000.0f) return fail(ANN_EINVAL, "alpha must be in (0, 30000]");
+  // integer rows test alpha as round(alpha * 2^16) / 2^16: that must not be zero
+  if (g->dtype != ANN_F32 && llround((double)alpha * 65536.0) < 1)
+    return fail(ANN_EINVAL, "alpha is below 1/65536, the smallest value u8/i8 rows can be pruned with");
   if (g->metric == ANN_MIPS && alpha > 1.0f) return fail(ANN_EINVAL, "alpha must be <= 1 for ANN_MIPS");
   return ANN_OK;
 }
@@ -486,10 +523,11 @@ int new_graph(u64 n, u32 d, int dtype, int metric, u32 R, ann_graph** out) {
   g->metric = metric;
   g->cfg = cfg;
   g->pad_stride = pad_stride;
-  hipError_t e = hipMalloc(reinterpret_cast<void**>(&g->rows), (size_t)n * R * sizeof(u32));
-  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&g->meta), (size_t)n * sizeof(u32));
+  g->al = current_allocator();
+  hipError_t e = g->al.get(reinterpret_cast<void**>(&g->rows), (size_t)n * R * sizeof(u32));
+  if (e == hipSuccess) e = g->al.get(reinterpret_cast<void**>(&g->meta), (size_t)n * sizeof(u32));
   if (e == hipSuccess) e = hipMemset(g->meta, 0, (size_t)n * sizeof(u32));
-  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&g->counters), COUNTER_COPIES * sizeof(DevCounters));
+  if (e == hipSuccess) e = g->al.get(reinterpret_cast<void**>(&g->counters), COUNTER_COPIES * sizeof(DevCounters));
   if (e == hipSuccess) e = hipMemset(g->counters, 0, COUNTER_COPIES * sizeof(DevCounters));
   if (e != hipSuccess) {
     ann_graph_free(g);
@@ -506,19 +544,19 @@ int reserve_rows(ann_graph* g, u64 want, hipStream_t st) {
   if (want >= (1ull << 31)) return fail(ANN_EINVAL, "n must stay below 2^31");
   u32* rows = nullptr;
   u32* meta = nullptr;
-  hipError_t e = hipMalloc(reinterpret_cast<void**>(&rows), (size_t)want * g->R * sizeof(u32));
-  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&meta), (size_t)want * sizeof(u32));
+  hipError_t e = g->al.get(reinterpret_cast<void**>(&rows), (size_t)want * g->R * sizeof(u32));
+  if (e == hipSuccess) e = g->al.get(reinterpret_cast<void**>(&meta), (size_t)want * sizeof(u32));
   if (e == hipSuccess)
     e = hipMemcpyAsync(rows, g->rows, (size_t)g->n * g->R * sizeof(u32), hipMemcpyDeviceToDevice, st);
   if (e == hipSuccess) e = hipMemcpyAsync(meta, g->meta, (size_t)g->n * sizeof(u32), hipMemcpyDeviceToDevice, st);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
-    if (rows) (void)hipFree(rows);
-    if (meta) (void)hipFree(meta);
+    g->al.put(rows);
+    g->al.put(meta);
     return fail(e == hipErrorOutOfMemory ? ANN_ENOMEM : ANN_EHIP, "graph growth: %s", hipGetErrorString(e));
   }
-  (void)hipFree(g->rows);
-  (void)hipFree(g->meta);
+  g->al.put(g->rows);
+  g->al.put(g->meta);
   g->rows = rows;
   g->meta = meta;
   g->cap = want;
@@ -550,16 +588,16 @@ const char* ann_last_error(void) { return last_error_text(); }
 
 void ann_graph_free(ann_graph* g) {
   if (!g) return;
-  if (g->rows) (void)hipFree(g->rows);
-  if (g->meta) (void)hipFree(g->meta);
-  if (g->counters) (void)hipFree(g->counters);
-  if (g->pad_buf) (void)hipFree(g->pad_buf);
-  if (g->qpad_buf) (void)hipFree(g->qpad_buf);
+  g->al.put(g->rows);
+  g->al.put(g->meta);
+  g->al.put(g->counters);
+  g->al.put(g->pad_buf);
+  g->al.put(g->qpad_buf);
   delete g->scratch;
   delete g;
 }
 
-int ann_graph_info(const ann_graph* g, ann_graph_info_t* info) {
+int ann_graph_info(const ann_graph* g, ann_graph_info_t* info) try {
   if (!g || !info) return fail(ANN_EINVAL, "null argument");
   info->n = g->n;
   info->d = g->d;
@@ -569,9 +607,11 @@ int ann_graph_info(const ann_graph* g, ann_graph_info_t* info) {
   info->start = g->start;
   info->rounds = g->rounds;
   return ANN_OK;
+} catch (...) {
+  return annmi::on_exception();
 }
 
-int ann_get_stats(const ann_graph* g, ann_stats* stats) {
+int ann_get_stats(const ann_graph* g, ann_stats* stats) try {
   if (!g || !stats) return fail(ANN_EINVAL, "null argument");
   std::vector<DevCounters> copies(COUNTER_COPIES);
   HIP_TRY(hipMemcpy(copies.data(), g->counters, COUNTER_COPIES * sizeof(DevCounters), hipMemcpyDeviceToHost));
@@ -602,18 +642,28 @@ int ann_get_stats(const ann_graph* g, ann_stats* stats) {
   stats->survivors = c.survivors;
   stats->insert_hops = c.insert_hops;
   return ANN_OK;
+} catch (...) {
+  return annmi::on_exception();
+}
+
+int ann_graph_set_stats(ann_graph* g, int on) {
+  if (!g) return fail(ANN_EINVAL, "null argument");
+  g->collect = on != 0;
+  return ANN_OK;
 }
 
 const uint32_t* ann_graph_device_rows(const ann_graph* g) { return g ? g->rows : nullptr; }
 
-int ann_graph_copy_neighbors(const ann_graph* g, uint32_t* rows_host) {
+int ann_graph_copy_neighbors(const ann_graph* g, uint32_t* rows_host) try {
   if (!g || !rows_host) return fail(ANN_EINVAL, "null argument");
   HIP_TRY(hipMemcpy(rows_host, g->rows, (size_t)g->n * g->R * sizeof(u32), hipMemcpyDeviceToHost));
   return ANN_OK;
+} catch (...) {
+  return annmi::on_exception();
 }
 
 int ann_graph_from_host(const uint32_t* rows_host, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric,
-                        uint32_t R, uint32_t start, ann_graph** out) {
+                        uint32_t R, uint32_t start, ann_graph** out) try {
   if (out) *out = nullptr;
   if (!rows_host || !out) return fail(ANN_EINVAL, "null argument");
   if (start >= n) return fail(ANN_EINVAL, "start vertex out of range");
@@ -633,19 +683,23 @@ int ann_graph_from_host(const uint32_t* rows_host, uint64_t n, uint32_t d, ann_d
   }
   *out = g;
   return ANN_OK;
+} catch (...) {
+  return annmi::on_exception();
 }
 
 int ann_start_vertex(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, void* stream,
-                     uint32_t* start_out) {
+                     uint32_t* start_out) try {
   if (!points_dev || !start_out || n < 1 || d < 1) return fail(ANN_EINVAL, "null argument or empty input");
   if (dtype != ANN_U8 && dtype != ANN_I8 && dtype != ANN_F32) return fail(ANN_EINVAL, "unknown dtype");
   u32 s = 0;
   HIP_TRY(start_vertex_device(points_dev, n, d, dtype, static_cast<hipStream_t>(stream), &s));
   *start_out = s;
   return ANN_OK;
+} catch (...) {
+  return annmi::on_exception();
 }
 
-int ann_sort_edges(uint64_t* keys_dev, uint64_t count, uint32_t key_bits, void* stream) {
+int ann_sort_edges(uint64_t* keys_dev, uint64_t count, uint32_t key_bits, void* stream) try {
   if (!keys_dev && count) return fail(ANN_EINVAL, "null argument");
   if (key_bits < 1 || key_bits > 32) return fail(ANN_EINVAL, "key_bits must be in [1, 32]");
   if (count >= (1ull << 32)) return fail(ANN_EINVAL, "too many keys");
@@ -656,24 +710,50 @@ int ann_sort_edges(uint64_t* keys_dev, uint64_t count, uint32_t key_bits, void* 
   HIP_TRY(radix_sort_edges(keys_dev, tmp.as<u64>(), hist.as<u32>(), radix_hist_entries(count), count, key_bits, st));
   HIP_TRY(hipStreamSynchronize(st));
   return ANN_OK;
+} catch (...) {
+  return annmi::on_exception();
 }
 
 
 int ann_insert_batch(ann_graph* g, const void* points_dev, const uint32_t* ids_host, uint64_t b, uint32_t L,
-                     float alpha, void* stream) {
+                     float alpha, void* stream) try {
   if (!g || !points_dev || (!ids_host && b)) return fail(ANN_EINVAL, "null argument");
   int rc = check_insert_params(g, L, alpha);
   if (rc) return rc;
   if (b == 0) return ANN_OK;
   if (b * g->R >= (1ull << 32)) return fail(ANN_EINVAL, "batch too large");
-  for (u64 i = 0; i < b; ++i)
-    if (ids_host[i] >= g->n || ids_host[i] == g->start) return fail(ANN_EINVAL, "bad id in batch");
+  {
+    // two searches of one point would write the same row
+    std::vector<u64> seen((g->n + 63) / 64, 0ull);
+    for (u64 i = 0; i < b; ++i) {
+      const u32 id = ids_host[i];
+      if (id >= g->n || id == g->start) return fail(ANN_EINVAL, "bad id in batch");
+      if (seen[id >> 6] >> (id & 63) & 1ull) return fail(ANN_EINVAL, "id %u is listed twice in the batch", id);
+      seen[id >> 6] |= 1ull << (id & 63);
+    }
+  }
   hipStream_t st = static_cast<hipStream_t>(stream);
+  Allocator al = g->al;
+  al.stream = stream;
+  AllocScope scope(al);
   BatchScratch* Sp = nullptr;
   rc = graph_scratch(g, b, L, st, &Sp);
   if (rc) return rc;
   BatchScratch& S = *Sp;
   HIP_TRY(hipMemcpy(S.qidx.p, ids_host, (size_t)b * 4, hipMemcpyHostToDevice));
+  {
+    // a point that has out-neighbours is in the graph already: searching from s would reach it
+    // and it would become its own candidate
+    u32* flag = S.small.as<u32>() + 12;
+    HIP_TRY(hipMemsetAsync(flag, 0, 4, st));
+    hipLaunchKernelGGL(count_inserted_kernel, dim3((u32)((b + 255) / 256)), dim3(256), 0, st, S.qidx.as<u32>(), b,
+                       g->meta, flag);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipMemcpyAsync(S.host_flag + 4, flag, 4, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    if (S.host_flag[4] != 0)
+      return fail(ANN_EINVAL, "%u of the batch's points are in the graph already", S.host_flag[4]);
+  }
   PhaseTimer tm;
   rc = tm.init(g->collect);
   if (rc) return rc;
@@ -684,15 +764,19 @@ int ann_insert_batch(ann_graph* g, const void* points_dev, const uint32_t* ids_h
   if (rc) return rc;
   rc = finish_batches(g, S, tm, st);
   return rc == ANN_LOST_LIST ? fail(ANN_EINTERNAL, "a visited list was lost in a synchronised batch") : rc;
+} catch (...) {
+  return annmi::on_exception();
 }
 
-int ann_graph_reserve(ann_graph* g, uint64_t n_cap, void* stream) {
+int ann_graph_reserve(ann_graph* g, uint64_t n_cap, void* stream) try {
   if (!g) return fail(ANN_EINVAL, "null argument");
   return reserve_rows(g, n_cap, static_cast<hipStream_t>(stream));
+} catch (...) {
+  return annmi::on_exception();
 }
 
 int ann_insert_points(ann_graph* g, const void* points_dev, uint64_t n_total, uint32_t L, float alpha,
-                      uint64_t seed, const ann_build_opts* opts, void* stream) {
+                      uint64_t seed, const ann_build_opts* opts, void* stream) try {
   if (!g || !points_dev) return fail(ANN_EINVAL, "null argument");
   int rc = check_insert_params(g, L, alpha);
   if (rc) return rc;
@@ -700,6 +784,9 @@ int ann_insert_points(ann_graph* g, const void* points_dev, uint64_t n_total, ui
   if (n_total >= (1ull << 31)) return fail(ANN_EINVAL, "n must stay below 2^31");
   ann_build_opts o{};
   if (opts) o = *opts;
+  Allocator al = g->al;
+  al.stream = stream;
+  AllocScope scope(al);
   const u64 n_old = g->n, m = n_total - n_old;
   if (m == 0) return ANN_OK;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -776,16 +863,22 @@ int ann_insert_points(ann_graph* g, const void* points_dev, uint64_t n_total, ui
     fprintf(stderr, "ann_insert_points: order %.2f ms, growth %.2f ms, scratch %.2f ms, %zu batches %.2f ms\n",
             t_order - t_begin, t_grow - t_order, t_alloc - t_grow, bounds.size() - 1, now_ms() - t_alloc);
   return rc == ANN_LOST_LIST ? fail(ANN_EINTERNAL, "a visited list was lost in a synchronised batch") : rc;
+} catch (...) {
+  return annmi::on_exception();
 }
 
 int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric, uint32_t R,
-              uint32_t L, float alpha, uint64_t seed, const ann_build_opts* opts, void* stream, ann_graph** out) {
+              uint32_t L, float alpha, uint64_t seed, const ann_build_opts* opts, void* stream, ann_graph** out) try {
   if (out) *out = nullptr;
   if (!points_dev || !out) return fail(ANN_EINVAL, "null argument");
   ann_build_opts o{};
   o.start = ANN_NONE;
   if (opts) o = *opts;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  Allocator al;
+  if (!allocator_from(o.alloc, o.free, o.alloc_user, stream, &al))
+    return fail(ANN_EINVAL, "alloc and free must be given together");
+  AllocScope scope(al);
 
   const bool trace = getenv("ANN_TRACE_BUILD") != nullptr;  // wall-clock breakdown on stderr
   auto now_ms = [] {
@@ -928,6 +1021,8 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
   guard.g = nullptr;
   *out = g;
   return ANN_OK;
+} catch (...) {
+  return annmi::on_exception();
 }
 
 int ann_search(const ann_graph* g, const void* points_dev, const void* queries_dev, uint64_t nq, uint32_t k,
@@ -936,13 +1031,13 @@ int ann_search(const ann_graph* g, const void* points_dev, const void* queries_d
 }
 
 int ann_search_eps(const ann_graph* g, const void* points_dev, const void* queries_dev, uint64_t nq, uint32_t k,
-                   uint32_t L, float eps, uint32_t* ids_dev, void* dists_dev, void* stream) {
+                   uint32_t L, float eps, uint32_t* ids_dev, void* dists_dev, void* stream) try {
   if (!g || !points_dev) return fail(ANN_EINVAL, "null argument");
   if (!(eps < 16384.0f)) return fail(ANN_EINVAL, "eps must be below 16384 (negative: no pruning)");
   if (nq == 0) return ANN_OK;
   if (!queries_dev || !ids_dev || !dists_dev) return fail(ANN_EINVAL, "null argument");
   if (k < 1 || k > L) return fail(ANN_EINVAL, "need 1 <= k <= L");
-  if (L > 512) return fail(ANN_EINVAL, "L must be at most 512");
+  if (L > 2048) return fail(ANN_EINVAL, "L must be at most 2048");
   if (nq >= (1ull << 31)) return fail(ANN_EINVAL, "too many queries");
   hipStream_t st_ = static_cast<hipStream_t>(stream);
   const void* pts = nullptr;
@@ -954,6 +1049,8 @@ int ann_search_eps(const ann_graph* g, const void* points_dev, const void* queri
   rc_ = query_launch(g, pts, qsp, nullptr, nq, k, L, eps, nullptr, ids_dev, dists_dev, st_);
   if (rc_) return rc_;
   return ANN_OK;
+} catch (...) {
+  return annmi::on_exception();
 }
 
 }  // extern "C"

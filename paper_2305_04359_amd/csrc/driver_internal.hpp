@@ -30,29 +30,68 @@ int fail(int code, const char* fmt, ...);
                            hipGetErrorString(e_));                                             \
   } while (0)
 
+// Where device memory comes from: the caller's callbacks (ann_build_opts / ann_hnsw_opts), or
+// hipMalloc / hipFree.  A call sets the allocator of its thread for its duration (AllocScope);
+// every buffer remembers the allocator it came from and goes back to it.
+struct Allocator {
+  ann_alloc_fn alloc = nullptr;
+  ann_free_fn free = nullptr;
+  void* user = nullptr;
+  void* stream = nullptr;  // handed to `alloc`: the stream the memory is first used on
+  hipError_t get(void** p, size_t bytes) const {
+    if (bytes == 0) bytes = 16;
+    if (alloc == nullptr) return hipMalloc(p, bytes);
+    *p = alloc(bytes, stream, user);
+    return *p != nullptr ? hipSuccess : hipErrorOutOfMemory;
+  }
+  void put(void* p) const {
+    if (p == nullptr) return;
+    if (free != nullptr)
+      free(p, user);
+    else
+      (void)hipFree(p);
+  }
+};
+Allocator& current_allocator();  // of this thread
+struct AllocScope {
+  Allocator saved;
+  explicit AllocScope(const Allocator& a) : saved(current_allocator()) { current_allocator() = a; }
+  AllocScope(const AllocScope&) = delete;
+  AllocScope& operator=(const AllocScope&) = delete;
+  ~AllocScope() { current_allocator() = saved; }
+};
+// the allocator named by a pair of callbacks (both or neither); false if only one is given
+bool allocator_from(ann_alloc_fn a, ann_free_fn f, void* user, void* stream, Allocator* out);
+
+// what a C entry point returns for an exception that reached it (none may cross the boundary)
+int on_exception();
+
 // device buffer freed on scope exit
 struct DevBuf {
   void* p = nullptr;
+  Allocator al;
   DevBuf() = default;
   DevBuf(const DevBuf&) = delete;
   DevBuf& operator=(const DevBuf&) = delete;
-  DevBuf(DevBuf&& o) noexcept : p(o.p) { o.p = nullptr; }
+  DevBuf(DevBuf&& o) noexcept : p(o.p), al(o.al) { o.p = nullptr; }
   DevBuf& operator=(DevBuf&& o) noexcept {
     if (this != &o) {
       release();
       p = o.p;
+      al = o.al;
       o.p = nullptr;
     }
     return *this;
   }
   ~DevBuf() { release(); }
   void release() {
-    if (p) (void)hipFree(p);
+    al.put(p);
     p = nullptr;
   }
   hipError_t alloc(size_t bytes) {
     release();
-    return hipMalloc(&p, bytes ? bytes : 16);
+    al = current_allocator();
+    return al.get(&p, bytes);
   }
   template <typename T>
   T* as() const {
@@ -75,6 +114,7 @@ struct ann_graph {
   annmi::u32 start = 0;
   annmi::u64 rounds = 0;
   annmi::DistCfg cfg{};
+  annmi::Allocator al;                   // where rows, meta, counters and the padded copies come from
   annmi::u32* rows = nullptr;            // device, n x R
   annmi::u32* meta = nullptr;            // device, n: degree | clean prefix length << 16
   float clean_alpha = 0.0f;       // the alpha the clean prefixes were pruned with

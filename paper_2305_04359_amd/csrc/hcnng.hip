@@ -1050,7 +1050,9 @@ struct HcCtx {
     // every leaf but a tree's smallest few is well above 32 points: room for one partly used tile
     // per Ls / 4 positions (hc_leaves allocates again if a group needs more)
     leaf_tiles = N / 32 + 4 * (N / Ls) + G + 64;
-    if (getenv("ANN_HCNNG_FEW_TILES") != nullptr) leaf_tiles = 1;  // (lets a test reach the second allocation)
+    // test-only option of ann_hcnng_build (see ann.h): start with one tile, so that hc_leaves
+    // takes the path that allocates the buffer again
+    if (getenv("ANN_HCNNG_FEW_TILES") != nullptr) leaf_tiles = 1;
     HIP_TRY(leafvec.alloc(leaf_tiles * 32 * lv_stride));
     HIP_TRY(leafnorm.alloc((N + 64) * 4));
     HIP_TRY(hipMemset(leafnorm.p, 0, (N + 64) * 4));
@@ -1320,7 +1322,7 @@ extern "C" {
 
 int ann_hcnng_tree_edges(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric,
                          uint32_t Ls, uint32_t s, uint32_t l, uint64_t seed, uint32_t tree, void* stream, uint32_t* perm_host,
-                         uint64_t* leaf_off_host, uint64_t* nleaves, uint32_t* pairs_host, uint64_t* npairs) {
+                         uint64_t* leaf_off_host, uint64_t* nleaves, uint32_t* pairs_host, uint64_t* npairs) try {
   if (!points_dev || !perm_host || !leaf_off_host || !nleaves || !pairs_host || !npairs)
     return fail(ANN_EINVAL, "null argument");
   int rc = hc_check(n, d, dtype, metric, Ls, s, l);
@@ -1365,11 +1367,13 @@ int ann_hcnng_tree_edges(const void* points_dev, uint64_t n, uint32_t d, ann_dty
     }
   *npairs = np;
   return ANN_OK;
+} catch (...) {
+  return annmi::on_exception();
 }
 
 int ann_hcnng_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric, uint32_t T,
                     uint32_t Ls, uint32_t s, uint32_t l, uint32_t R, float alpha, uint64_t seed, void* stream,
-                    ann_graph** out) {
+                    ann_graph** out) try {
   if (out) *out = nullptr;
   if (!points_dev || !out) return fail(ANN_EINVAL, "null argument");
   int rc = hc_check(n, d, dtype, metric, Ls, s, l);
@@ -1494,6 +1498,8 @@ int ann_hcnng_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dt
   guard.g = nullptr;
   *out = g;
   return ANN_OK;
+} catch (...) {
+  return annmi::on_exception();
 }
 
 }  // extern "C"

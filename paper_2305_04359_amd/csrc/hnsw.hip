@@ -27,6 +27,7 @@ struct ann_hnsw {
   u32 entry = 0;  // global id
   u64 rounds = 0;
   u64 level_seed = 0;  // levels are a function of this seed and the point's id
+  Allocator al;        // where the index's device memory comes from
   std::vector<u32> level;             // host, n
   std::vector<ann_graph*> layer;      // 0..top
   std::vector<std::vector<u32>> ids;  // ids[l], l >= 1: global ids of the layer's vertices, ascending
@@ -344,7 +345,7 @@ void ann_hnsw_free(ann_hnsw* h) { free_hnsw(h); }
 
 int ann_hnsw_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric, uint32_t m,
                    uint32_t efc, float alpha, uint64_t seed, const ann_hnsw_opts* opts, void* stream,
-                   ann_hnsw** out) {
+                   ann_hnsw** out) try {
   if (out) *out = nullptr;
   if (!points_dev || !out) return fail(ANN_EINVAL, "null argument");
   if (m < 2 || m > 256) return fail(ANN_EINVAL, "m must be in [2, 256]");
@@ -352,6 +353,10 @@ int ann_hnsw_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dty
   ann_hnsw_opts o{};
   if (opts) o = *opts;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  Allocator al;
+  if (!allocator_from(o.alloc, o.free, o.alloc_user, stream, &al))
+    return fail(ANN_EINVAL, "alloc and free must be given together");
+  AllocScope scope(al);
 
   ann_hnsw* h = new (std::nothrow) ann_hnsw();
   if (!h) return fail(ANN_ENOMEM, "host allocation failed");
@@ -359,6 +364,7 @@ int ann_hnsw_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dty
     ann_hnsw* h;
     ~Guard() { free_hnsw(h); }
   } guard{h};
+  h->al = al;
   h->n = n;
   h->d = d;
   h->m = m;
@@ -438,10 +444,12 @@ int ann_hnsw_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dty
   guard.h = nullptr;
   *out = h;
   return ANN_OK;
+} catch (...) {
+  return annmi::on_exception();
 }
 
 int ann_hnsw_insert_points(ann_hnsw* h, const void* points_dev, uint64_t n_total, uint32_t efc, float alpha,
-                           uint64_t seed, const ann_hnsw_opts* opts, void* stream) {
+                           uint64_t seed, const ann_hnsw_opts* opts, void* stream) try {
   if (!h || !points_dev) return fail(ANN_EINVAL, "null argument");
   int rc = check_insert_params(h->layer[0], efc, alpha);
   if (rc) return rc;
@@ -452,6 +460,9 @@ int ann_hnsw_insert_points(ann_hnsw* h, const void* points_dev, uint64_t n_total
   const u64 n_old = h->n, mnew = n_total - n_old;
   if (mnew == 0) return ANN_OK;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  Allocator al = h->al;
+  al.stream = stream;
+  AllocScope scope(al);
   const u32 top = h->top, m = h->m, d = h->d;
   const u64 esz = h->dtype == ANN_F32 ? 4 : 1;
 
@@ -540,11 +551,13 @@ int ann_hnsw_insert_points(ann_hnsw* h, const void* points_dev, uint64_t n_total
   if (rc) return rc;
   return run_batches(h, points_dev, order, bounds, efc, alpha, o.max_rounds, h->layer[0]->collect, /*may_restart=*/false,
                      st);
+} catch (...) {
+  return annmi::on_exception();
 }
 
 int ann_hnsw_from_host(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric, uint32_t m,
                        const uint32_t* level_host, uint32_t entry, const uint32_t* const* rows_host, void* stream,
-                       ann_hnsw** out) {
+                       ann_hnsw** out) try {
   if (out) *out = nullptr;
   if (!points_dev || !out || !level_host || !rows_host) return fail(ANN_EINVAL, "null argument");
   if (m < 2 || m > 256) return fail(ANN_EINVAL, "m must be in [2, 256]");
@@ -600,16 +613,18 @@ int ann_hnsw_from_host(const void* points_dev, uint64_t n, uint32_t d, ann_dtype
   guard.h = nullptr;
   *out = h;
   return ANN_OK;
+} catch (...) {
+  return annmi::on_exception();
 }
 
 int ann_hnsw_search(const ann_hnsw* h, const void* points_dev, const void* queries_dev, uint64_t nq, uint32_t k,
-                    uint32_t L, float eps, uint32_t* ids_dev, void* dists_dev, void* stream) {
+                    uint32_t L, float eps, uint32_t* ids_dev, void* dists_dev, void* stream) try {
   if (!h || !points_dev) return fail(ANN_EINVAL, "null argument");
   if (!(eps < 16384.0f)) return fail(ANN_EINVAL, "eps must be below 16384 (negative: no pruning)");
   if (nq == 0) return ANN_OK;
   if (!queries_dev || !ids_dev || !dists_dev) return fail(ANN_EINVAL, "null argument");
   if (k < 1 || k > L) return fail(ANN_EINVAL, "need 1 <= k <= L");
-  if (L > 512) return fail(ANN_EINVAL, "L must be at most 512");
+  if (L > 2048) return fail(ANN_EINVAL, "L must be at most 2048");
   if (nq >= (1ull << 31)) return fail(ANN_EINVAL, "too many queries");
   hipStream_t st = static_cast<hipStream_t>(stream);
   const ann_graph* g0 = h->layer[0];
@@ -621,7 +636,10 @@ int ann_hnsw_search(const ann_hnsw* h, const void* points_dev, const void* queri
   if (rc) return rc;
   if (h->top == 0) return query_launch(g0, p0, qs, nullptr, nq, k, L, eps, nullptr, ids_dev, dists_dev, st);
   if (h->qcur_cap < nq) {
-    HIP_TRY(hipStreamSynchronize(st));  // an earlier call may still use the old array
+    HIP_TRY(hipDeviceSynchronize());  // an earlier call, on whatever stream, may still use the old array
+    Allocator al = h->al;
+    al.stream = stream;
+    AllocScope scope(al);
     HIP_TRY(h->qcur.alloc(nq * 4));
     h->qcur_cap = nq;
   }
@@ -638,9 +656,11 @@ int ann_hnsw_search(const ann_hnsw* h, const void* points_dev, const void* queri
   StartsArgs s0;
   s0.cur = h->qcur.as<u32>();
   return query_launch(g0, p0, qs, nullptr, nq, k, L, eps, &s0, ids_dev, dists_dev, st);
+} catch (...) {
+  return annmi::on_exception();
 }
 
-int ann_hnsw_info(const ann_hnsw* h, ann_hnsw_info_t* info) {
+int ann_hnsw_info(const ann_hnsw* h, ann_hnsw_info_t* info) try {
   if (!h || !info) return fail(ANN_EINVAL, "null argument");
   info->n = h->n;
   info->d = h->d;
@@ -651,22 +671,28 @@ int ann_hnsw_info(const ann_hnsw* h, ann_hnsw_info_t* info) {
   info->entry = h->entry;
   info->rounds = h->rounds;
   return ANN_OK;
+} catch (...) {
+  return annmi::on_exception();
 }
 
-int ann_hnsw_copy_levels(const ann_hnsw* h, uint32_t* level_host) {
+int ann_hnsw_copy_levels(const ann_hnsw* h, uint32_t* level_host) try {
   if (!h || !level_host) return fail(ANN_EINVAL, "null argument");
   memcpy(level_host, h->level.data(), h->n * sizeof(u32));
   return ANN_OK;
+} catch (...) {
+  return annmi::on_exception();
 }
 
-int ann_hnsw_layer_size(const ann_hnsw* h, uint32_t layer, uint64_t* count) {
+int ann_hnsw_layer_size(const ann_hnsw* h, uint32_t layer, uint64_t* count) try {
   if (!h || !count) return fail(ANN_EINVAL, "null argument");
   if (layer > h->top) return fail(ANN_EINVAL, "no such layer");
   *count = h->layer[layer]->n;
   return ANN_OK;
+} catch (...) {
+  return annmi::on_exception();
 }
 
-int ann_hnsw_copy_layer(const ann_hnsw* h, uint32_t layer, uint32_t* ids_host, uint32_t* rows_host) {
+int ann_hnsw_copy_layer(const ann_hnsw* h, uint32_t layer, uint32_t* ids_host, uint32_t* rows_host) try {
   if (!h || !ids_host || !rows_host) return fail(ANN_EINVAL, "null argument");
   if (layer > h->top) return fail(ANN_EINVAL, "no such layer");
   const ann_graph* g = h->layer[layer];
@@ -680,12 +706,16 @@ int ann_hnsw_copy_layer(const ann_hnsw* h, uint32_t layer, uint32_t* ids_host, u
   for (u64 i = 0; i < g->n * g->R; ++i)
     if (rows_host[i] != ANN_NONE) rows_host[i] = mine[rows_host[i]];
   return ANN_OK;
+} catch (...) {
+  return annmi::on_exception();
 }
 
-int ann_hnsw_get_stats(const ann_hnsw* h, uint32_t layer, ann_stats* stats) {
+int ann_hnsw_get_stats(const ann_hnsw* h, uint32_t layer, ann_stats* stats) try {
   if (!h || !stats) return fail(ANN_EINVAL, "null argument");
   if (layer > h->top) return fail(ANN_EINVAL, "no such layer");
   return ann_get_stats(h->layer[layer], stats);
+} catch (...) {
+  return annmi::on_exception();
 }
 
 }  // extern "C"

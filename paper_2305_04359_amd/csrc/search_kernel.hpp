@@ -270,7 +270,8 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
             // many survivors: each finds its rank among the beam entries by bisection in the LDS
             // copy of the beam; a survivor that is already in the beam (the filter lost it) sits
             // exactly at its rank there and is dropped
-            constexpr int STEPS = (NSLOT == 1 ? 7 : NSLOT == 2 ? 8 : NSLOT == 4 ? 9 : 10);
+            // positions 0..size are possible answers: ceil(log2(64 * NSLOT + 1)) halvings
+            constexpr int STEPS = (NSLOT == 1 ? 7 : NSLOT == 2 ? 8 : NSLOT == 4 ? 9 : NSLOT == 8 ? 10 : NSLOT == 16 ? 11 : 12);
             const u64 sk1 = mykey | 1ull;
             u32 lo = 0, hi = size;
 #pragma unroll
@@ -406,7 +407,12 @@ hipError_t launch_search_eps(const DistCfg& cfg, const SearchArgs& a, const VecT
 hipError_t launch_search_own(const DistCfg& cfg, const SearchArgs& a, const VecTable& T, hipStream_t s);
 hipError_t launch_search_own_eps(const DistCfg& cfg, const SearchArgs& a, const VecTable& T, hipStream_t s);
 
-inline u32 search_nslot_for(u32 L) { return L <= 64 ? 1 : (L <= 128 ? 2 : (L <= 256 ? 4 : 8)); }
+// beam slots per lane: the smallest power of two that holds L entries (beams of up to 2,048)
+inline u32 search_nslot_for(u32 L) {
+  u32 ns = 1;
+  while (ns * 64u < L && ns < 32u) ns *= 2u;
+  return ns;
+}
 
 // One launch for a fixed choice of EPS and OWN; the beam slots and the filter layout are picked here.
 template <int KIND, int VEC, int NCH, bool EPS, bool OWN>
@@ -423,7 +429,9 @@ inline hipError_t launch_search_variant(const SearchArgs& a, const VecTable& T, 
     case 1: ANN_LAUNCH_SEARCH(1); break;
     case 2: ANN_LAUNCH_SEARCH(2); break;
     case 4: ANN_LAUNCH_SEARCH(4); break;
-    default: ANN_LAUNCH_SEARCH(8); break;
+    case 8: ANN_LAUNCH_SEARCH(8); break;
+    case 16: ANN_LAUNCH_SEARCH(16); break;
+    default: ANN_LAUNCH_SEARCH(32); break;
   }
 #undef ANN_LAUNCH_SEARCH
   return hipGetLastError();

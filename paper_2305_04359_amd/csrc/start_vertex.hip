@@ -7,6 +7,7 @@
 // sum taken in a fixed order so that repeated runs agree bit for bit.
 #include "ann_device.hpp"
 #include "ann_internal.hpp"
+#include "driver_internal.hpp"
 
 namespace annmi {
 
@@ -261,20 +262,14 @@ static hipError_t start_vertex_t(const T* x, u64 n, u32 d, hipStream_t s, u32* s
   const u64 rpb = (n + nblocks - 1) / nblocks;
   const bool byte_words = sizeof(T) == 1 && d % 4 == 0 && d <= 4096;
   const u32 nwg = byte_words ? (u32)((n * 8 + 255) / 256) : (u32)((n + 255) / 256);
-  S* partial = nullptr;
-  S* colsum = nullptr;
-  unsigned long long* wg = nullptr;  // nwg scores, nwg ids, then the result
+  DevBuf partial_b, colsum_b, wg_b;  // (from the calling thread's allocator)
   hipError_t e;
-  if ((e = hipMalloc(&partial, (size_t)nblocks * d * sizeof(S))) != hipSuccess) return e;
-  if ((e = hipMalloc(&colsum, (size_t)d * sizeof(S))) != hipSuccess) {
-    (void)hipFree(partial);
-    return e;
-  }
-  if ((e = hipMalloc(&wg, ((size_t)2 * nwg + 1) * sizeof(unsigned long long))) != hipSuccess) {
-    (void)hipFree(partial);
-    (void)hipFree(colsum);
-    return e;
-  }
+  if ((e = partial_b.alloc((size_t)nblocks * d * sizeof(S))) != hipSuccess) return e;
+  if ((e = colsum_b.alloc((size_t)d * sizeof(S))) != hipSuccess) return e;
+  if ((e = wg_b.alloc(((size_t)2 * nwg + 1) * sizeof(unsigned long long))) != hipSuccess) return e;
+  S* partial = partial_b.as<S>();
+  S* colsum = colsum_b.as<S>();
+  unsigned long long* wg = wg_b.as<unsigned long long>();  // nwg scores, nwg ids, then the result
   u32* best_id = reinterpret_cast<u32*>(wg + 2 * (size_t)nwg);
   if constexpr (sizeof(T) == 1) {
     if (byte_words)
@@ -298,11 +293,8 @@ static hipError_t start_vertex_t(const T* x, u64 n, u32 d, hipStream_t s, u32* s
   hipLaunchKernelGGL(best_final_kernel, dim3(1), dim3(1024), 0, s, wg, wg + nwg, nwg, best_id);
   e = hipGetLastError();
   if (e == hipSuccess) e = hipMemcpyAsync(start_out, best_id, sizeof(u32), hipMemcpyDeviceToHost, s);
-  if (e == hipSuccess) e = hipStreamSynchronize(s);
-  (void)hipFree(partial);
-  (void)hipFree(colsum);
-  (void)hipFree(wg);
-  return e;
+  const hipError_t e2 = hipStreamSynchronize(s);  // also before the buffers go back
+  return e != hipSuccess ? e : e2;
 }
 
 hipError_t start_vertex_device(const void* points, u64 n, u32 d, int dtype, hipStream_t s, u32* start_out) {

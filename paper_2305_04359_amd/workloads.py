@@ -177,7 +177,7 @@ def c5(n=100_000_000, nq=10_000):
     w = c2(n, nq)
     w.name = "C5"
     w.note = "stand-in for BIGANN-100M"
-    w.search_L = w.search_L + (250, 300, 400, 512)
+    w.search_L = w.search_L + (250, 300, 400, 512, 700, 1000, 1400, 2048)
     return w
 
 

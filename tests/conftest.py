@@ -17,3 +17,13 @@ def oracle():
     import oracle as O
     O.build_oracle()
     return O
+
+
+@pytest.fixture(scope="session")
+def env(oracle):
+    """(torch, binding, oracle) for the GPU tests: the HIP library must load and a GPU be there."""
+    import torch
+    from paper_2305_04359_amd import binding as A
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    A.lib()
+    return torch, A, oracle

@@ -80,3 +80,12 @@ def recall_at_k(ids, gt):
 
 def row_list(row):
     return [int(x) for x in row if int(x) != NONE]
+
+
+def dev(torch, a):
+    """A host array as a device tensor."""
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def say(msg):
+    print(msg, flush=True)

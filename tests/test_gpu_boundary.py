@@ -1,0 +1,207 @@
+"""GPU tests of the boundary itself: wide beams, the allocator callbacks, argument checks that
+need the device, and the counters' switch.  All results are compared with the CPU oracle."""
+import numpy as np
+import pytest
+
+from helpers import dev, say
+from paper_2305_04359_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def c1():
+    return W.c1()
+
+
+@pytest.fixture(scope="module")
+def c1_oracle(oracle, c1):
+    ds = oracle.Dataset(c1.points, 0)
+    g, s = oracle.build(ds, c1.R, c1.L, c1.alpha, seed=c1.seed, threads=0)
+    return ds, g, s
+
+
+@pytest.mark.parametrize("L,k", [(513, 10), (600, 10), (1000, 100), (1024, 1000), (1025, 10), (2048, 70)])
+def test_search_wide_beams_bit_exact(env, c1, c1_oracle, L, k):
+    """Beams beyond 512 entries (Sec. 4.5 sweeps the beam width to reach high recall): 16 and 32
+    beam slots per lane, with and without the (1 + eps) rule."""
+    torch, A, O = env
+    ds, og, s = c1_oracle
+    pts = dev(torch, c1.points)
+    g = A.ann_graph_from_host(og, c1.d, A.U8, A.L2SQ, s)
+    qs_h = c1.queries[:200]
+    qs = dev(torch, qs_h)
+    for eps in (None, 0.1):
+        ids, dists = A.ann_search(g, pts, qs, k, L, eps=eps)
+        oi, od = O.search_batch(ds, og, s, qs_h, k, L, threads=0, eps=-1.0 if eps is None else eps)
+        assert (ids.cpu().numpy().view(np.uint32) == oi).all(), f"ids differ at L={L} eps={eps}"
+        assert (dists.cpu().numpy() == od).all(), f"distances differ at L={L} eps={eps}"
+
+
+def test_search_wide_beams_other_types_and_limits(env):
+    torch, A, O = env
+    # float rows, inner product, a beam wider than the graph has vertices
+    w = W.c4(n=1500, nq=60)
+    ds = O.Dataset(w.points, 1)
+    og, s = O.build(ds, 16, 32, 1.0, seed=1, threads=0)
+    pts, qs = dev(torch, w.points), dev(torch, w.queries)
+    g = A.ann_graph_from_host(og, w.d, A.F32, A.MIPS, s)
+    ids, dists = A.ann_search(g, pts, qs, 10, 2048)
+    oi, od = O.search_batch(ds, og, s, w.queries, 10, 2048, threads=0)
+    assert (ids.cpu().numpy().view(np.uint32) == oi).mean() >= 0.99  # fp32 near-ties
+    assert np.allclose(dists.cpu().numpy(), od, rtol=1e-5, atol=1e-6)
+    # int8 rows of 100 bytes (padded inside the library), beam 700
+    w3 = W.c3(n=3000, nq=80)
+    ds3 = O.Dataset(w3.points, 0)
+    og3, s3 = O.build(ds3, 16, 32, 1.2, seed=1, threads=0)
+    p3 = dev(torch, w3.points)
+    g3 = A.ann_graph_from_host(og3, w3.d, A.I8, A.L2SQ, s3)
+    ids, dists = A.ann_search(g3, p3, dev(torch, w3.queries), 10, 700)
+    oi, od = O.search_batch(ds3, og3, s3, w3.queries, 10, 700, threads=0)
+    assert (ids.cpu().numpy().view(np.uint32) == oi).all() and (dists.cpu().numpy() == od).all()
+    # the layered index takes the same beams
+    oh = O.hnsw_build(ds3, 8, 32, 1.2, seed=2, threads=0)
+    h = A.ann_hnsw_build(p3, 8, 32, 1.2, seed=2)
+    ids, dists = A.ann_hnsw_search(h, p3, dev(torch, w3.queries), 10, 900)
+    oi, od, _ = O.hnsw_search_batch(ds3, oh, w3.queries, 10, 900, threads=0)
+    assert (ids.cpu().numpy().view(np.uint32) == oi).all() and (dists.cpu().numpy() == od).all()
+    with pytest.raises(A.AnnError):
+        A.ann_search(g3, p3, dev(torch, w3.queries), 10, 2049)
+    with pytest.raises(A.AnnError):
+        A.ann_build(p3, 16, 513, 1.2)  # builds keep the beam at 512
+
+
+class CountingAllocator:
+    """alloc / free callbacks over torch tensors that records every call (and can run dry)."""
+
+    def __init__(self, A, torch, fail_after=None):
+        self.A, self.torch = A, torch
+        self.live = {}
+        self.allocs = self.frees = 0
+        self.fail_after = fail_after
+
+        def _alloc(nbytes, stream, user):
+            if self.fail_after is not None and self.allocs >= self.fail_after:
+                return None
+            t = torch.empty(int(nbytes) + 256, dtype=torch.uint8, device="cuda:0")
+            p = (t.data_ptr() + 255) // 256 * 256
+            self.live[p] = t
+            self.allocs += 1
+            return p
+
+        def _free(ptr, user):
+            del self.live[ptr]
+            self.frees += 1
+
+        self.alloc = A.ALLOC_FN(_alloc)
+        self.free = A.FREE_FN(_free)
+
+    def fill(self, opts):
+        import ctypes as C
+        opts.alloc = C.cast(self.alloc, C.c_void_p)
+        opts.free = C.cast(self.free, C.c_void_p)
+        opts.alloc_user = None
+
+
+def test_allocator_callbacks(env, c1, c1_oracle):
+    """The graph and every scratch buffer come from the caller's callbacks and go back to them;
+    the result does not depend on where the memory comes from."""
+    torch, A, O = env
+    ds, og, s = c1_oracle
+    pts = dev(torch, c1.points)
+    rows = {}
+    for name in (None, "torch"):
+        g = A.ann_build(pts, c1.R, c1.L, c1.alpha, seed=c1.seed, allocator=name)
+        rows[name] = g.neighbors()
+        ids, _ = A.ann_search(g, pts, dev(torch, c1.queries[:50]), 10, 40)
+        assert (ids.cpu().numpy().view(np.uint32) == O.search_batch(ds, og, s, c1.queries[:50], 10, 40)[0]).all()
+        del g
+    assert (rows[None] == og).all() and (rows["torch"] == og).all()
+    ca = CountingAllocator(A, torch)
+    g = A.ann_build(pts, c1.R, c1.L, c1.alpha, seed=c1.seed, allocator=ca)
+    assert (g.neighbors() == og).all()
+    say(f"  a build made {ca.allocs} allocations; {len(ca.live)} are the graph's")
+    assert ca.allocs >= 10 and len(ca.live) == 3  # rows, degrees, counters stay; all scratch went back
+    # insertions after the build draw on the graph's allocator too, and keep their scratch
+    g2 = A.ann_build(pts[:8000], c1.R, c1.L, c1.alpha, seed=c1.seed, allocator=ca)
+    before = ca.allocs
+    A.ann_insert_points(g2, pts, c1.L, c1.alpha, seed=3)
+    assert ca.allocs > before
+    og2 = O.insert_points(ds, O.build(O.Dataset(c1.points[:8000], 0), c1.R, c1.L, c1.alpha, seed=c1.seed,
+                                      threads=0)[0], int(g2.info().start), c1.L, c1.alpha, seed=3, threads=0)
+    assert (g2.neighbors() == og2).all()
+    del g, g2
+    assert len(ca.live) == 0 and ca.allocs == ca.frees
+    # the layered index
+    h = A.ann_hnsw_build(pts, 8, 32, 1.2, seed=2, allocator=ca)
+    oh = O.hnsw_build(ds, 8, 32, 1.2, seed=2, threads=0)
+    for l in range(oh.top + 1):
+        lid, lrows = h.layer(l)
+        assert (lrows == oh.layers[l][lid]).all()
+    A.ann_hnsw_search(h, pts, dev(torch, c1.queries[:50]), 10, 40)
+    torch.cuda.synchronize()
+    del h
+    assert len(ca.live) == 0 and ca.allocs == ca.frees
+    # an allocator that runs dry part of the way: ANN_ENOMEM, and everything handed out comes back
+    for k in (0, 2, 7):
+        dry = CountingAllocator(A, torch, fail_after=k)
+        with pytest.raises(A.AnnError) as e:
+            A.ann_build(pts, c1.R, c1.L, c1.alpha, seed=c1.seed, allocator=dry)
+        assert e.value.code == -2
+        assert len(dry.live) == 0 and dry.allocs == dry.frees == k
+    # one callback without the other
+    import ctypes as C
+    o = A.BuildOpts()
+    o.alloc = C.cast(ca.alloc, C.c_void_p)
+    h_out = C.c_void_p()
+    rc = A.lib().ann_build(pts.data_ptr(), pts.shape[0], pts.shape[1], A.U8, A.L2SQ, 8, 8, 1.2, 1, C.byref(o),
+                           None, C.byref(h_out))
+    assert rc == -1 and not h_out.value
+
+
+def test_insert_batch_checks_its_ids(env, c1):
+    torch, A, O = env
+    pts = dev(torch, c1.points[:2000])
+    g = A.ann_build(pts, 16, 32, 1.2, seed=1, max_rounds=8)  # 182 points and the start vertex are in
+    s = int(g.info().start)
+    order = O.insertion_order(2000, s, 1)
+    rows = g.neighbors()
+    new = order[600:700]
+    with pytest.raises(A.AnnError):
+        A.ann_insert_batch(g, pts, np.concatenate([new, new[:1]]), 32, 1.2)  # an id twice
+    with pytest.raises(A.AnnError):
+        A.ann_insert_batch(g, pts, np.concatenate([new, order[:1]]), 32, 1.2)  # a point that is in already
+    with pytest.raises(A.AnnError):
+        A.ann_insert_batch(g, pts, np.array([s], np.uint32), 32, 1.2)
+    with pytest.raises(A.AnnError):
+        A.ann_insert_batch(g, pts, new, 32, 1e-6)  # rounds to alpha = 0 for integer rows
+    assert (g.neighbors() == rows).all()  # nothing was touched
+    A.ann_insert_batch(g, pts, new, 32, 1.2)
+    og = rows.copy()
+    O.batch_insert(O.Dataset(c1.points[:2000], 0), og, s, new, 32, 1.2)
+    assert (g.neighbors() == og).all()
+    # float rows take any positive alpha
+    wf = W.c4(n=600, nq=10)
+    gf = A.ann_build(dev(torch, wf.points), 8, 16, 1e-6, seed=1, metric=A.MIPS)
+    assert int(gf.info().n) == 600
+
+
+def test_counters_switch(env, c1, c1_oracle):
+    torch, A, O = env
+    ds, og, s = c1_oracle
+    pts, qs = dev(torch, c1.points), dev(torch, c1.queries[:100])
+    g = A.ann_graph_from_host(og, c1.d, A.U8, A.L2SQ, s)
+    A.ann_search(g, pts, qs, 10, 40)
+    torch.cuda.synchronize()
+    assert g.stats()["searches"] == 0
+    g.set_stats(True)
+    A.ann_search(g, pts, qs, 10, 40)
+    torch.cuda.synchronize()
+    st = g.stats()
+    ost = O.Stats()
+    O.search_batch(ds, og, s, c1.queries[:100], 10, 40, stats=ost)
+    assert st["searches"] == 100 and st["hops"] == ost.hops and st["evals"] >= ost.evals
+    g.set_stats(False)
+    A.ann_search(g, pts, qs, 10, 40)
+    torch.cuda.synchronize()
+    assert g.stats()["searches"] == 100

@@ -33,6 +33,9 @@ def test_struct_layouts_match_header():
     body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
     fields = re.findall(r"(\w+)\s*;", body)
     assert fields == [f for f, _ in A.BuildOpts._fields_]
+    body = struct_body("ann_hnsw_opts")
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    assert re.findall(r"(\w+)\s*;", body) == [f for f, _ in A.HnswOpts._fields_]
     body = struct_body("ann_stats")
     body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
     fields = [x.strip() for part in re.findall(r"(?:uint64_t|double)\s+([^;]+);", body) for x in part.split(",")]

@@ -183,6 +183,21 @@ def test_deterministic_and_thread_independent(oracle, small):
     assert (a != d).any()
 
 
+def test_build_is_the_loop_of_batch_inserts(oracle, small):
+    """vo_build is start vertex + order + schedule + one batch_insert per batch: the GPU tests at
+    full size drive the oracle batch by batch from Python (to report progress) and rely on it."""
+    ds = oracle.Dataset(small.points, 0)
+    R, L, alpha, seed = 12, 24, 1.2, 7
+    full, s = oracle.build(ds, R, L, alpha, seed=seed, threads=2)
+    assert s == oracle.start_vertex(ds)
+    order = oracle.insertion_order(ds.n, s, seed)
+    bounds = oracle.schedule(ds.n - 1, max(1, ds.n // 50)).astype(np.int64)
+    g = oracle.empty_graph(ds.n, R)
+    for r in range(len(bounds) - 1):
+        oracle.batch_insert(ds, g, s, order[bounds[r]:bounds[r + 1]], L, alpha, threads=2)
+    assert (g == full).all()
+
+
 def test_quality(oracle, small):
     """The built graph answers queries well, recall grows with L, and the prefix-doubling
     build is about as good as the sequential one (Sec. 3.1, batch size truncation)."""
