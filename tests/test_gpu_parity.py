@@ -107,7 +107,7 @@ def test_search_unreachable_padding_and_degenerate(env):
     with pytest.raises(A.AnnError):
         A.ann_search(gg, dev(torch, pts), dev(torch, pts[:1]), 9, 8)  # k > L
     with pytest.raises(A.AnnError):
-        A.ann_search(gg, dev(torch, pts), dev(torch, pts[:1]), 1, 1000)
+        A.ann_search(gg, dev(torch, pts), dev(torch, pts[:1]), 1, 3000)  # beams end at 2,048
 
 
 # ------------------------------------------------------------------------------------------
