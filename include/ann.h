@@ -224,6 +224,26 @@ int ann_search(const ann_graph* g, const void* points_dev, const void* queries_d
 int ann_search_eps(const ann_graph* g, const void* points_dev, const void* queries_dev, uint64_t nq,
                    uint32_t k, uint32_t L, float eps, uint32_t* ids_dev, void* dists_dev, void* stream);
 
+/*
+ * ann_search_eps for callers that cannot allocate device memory: code under HIP graph capture,
+ * serving loops, harnesses that forbid hipMalloc.  It calls no allocator of any kind.  The one
+ * buffer the search needs beyond its inputs and outputs, the zero-padded copy of the queries
+ * for u8/i8 rows whose size is not a multiple of 16 bytes, is a device array inside the library
+ * of ANN_NOALLOC_SCRATCH_MIB MiB, which every GPU the library runs on holds until the process
+ * ends.  (Rows that need no padding use no scratch at all.)
+ *   - nq * padded row size must fit the array: ANN_EINVAL otherwise, with the largest nq in the
+ *     message (65,536 queries for rows padded to 128 bytes).
+ *   - For padded rows the graph must already hold the padded copy of `points_dev`: ann_build
+ *     makes it, and so does one call of ann_search; ANN_EINVAL otherwise.
+ *   - All calls on one GPU share the array: calls that overlap in time on one GPU (two streams,
+ *     two threads, two graphs) race on it.  The caller orders them.
+ * Arguments, results and errors otherwise as ann_search_eps (eps < 0: plain ann_search).
+ * Asynchronous on `stream`.
+ */
+#define ANN_NOALLOC_SCRATCH_MIB 8
+int ann_search_noalloc(const ann_graph* g, const void* points_dev, const void* queries_dev, uint64_t nq,
+                       uint32_t k, uint32_t L, float eps, uint32_t* ids_dev, void* dists_dev, void* stream);
+
 /* Start vertex used by ann_build when none is given: the point nearest
  * (squared L2) to the mean of all points, smallest id on ties.  Exact for
  * u8/i8; fp64 for f32.  Blocks.                                             */

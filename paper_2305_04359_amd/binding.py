@@ -68,7 +68,7 @@ class HnswInfo(C.Structure):
 
 
 EXPORTS = [
-    "ann_build", "ann_insert_batch", "ann_insert_points", "ann_graph_reserve", "ann_search", "ann_search_eps", "ann_start_vertex", "ann_graph_from_host",
+    "ann_build", "ann_insert_batch", "ann_insert_points", "ann_graph_reserve", "ann_search", "ann_search_eps", "ann_search_noalloc", "ann_start_vertex", "ann_graph_from_host",
     "ann_graph_copy_neighbors", "ann_graph_device_rows", "ann_graph_info", "ann_get_stats", "ann_graph_set_stats",
     "ann_graph_free", "ann_sort_edges", "ann_last_error",
     "ann_hnsw_build", "ann_hnsw_insert_points", "ann_hnsw_from_host", "ann_hnsw_search", "ann_hnsw_info", "ann_hnsw_copy_levels", "ann_hnsw_layer_size",
@@ -106,6 +106,8 @@ def lib():
         L.ann_search.argtypes = [vp, vp, vp, u64, u32, u32, vp, vp, vp]
         L.ann_search_eps.restype = C.c_int
         L.ann_search_eps.argtypes = [vp, vp, vp, u64, u32, u32, C.c_float, vp, vp, vp]
+        L.ann_search_noalloc.restype = C.c_int
+        L.ann_search_noalloc.argtypes = [vp, vp, vp, u64, u32, u32, C.c_float, vp, vp, vp]
         L.ann_start_vertex.restype = C.c_int
         L.ann_start_vertex.argtypes = [vp, u64, u32, C.c_int, vp, C.POINTER(u32)]
         L.ann_graph_from_host.restype = C.c_int
@@ -376,6 +378,14 @@ def ann_search(graph: Graph, points, queries, k, L, ids_out=None, dists_out=None
         _check(lib().ann_search_eps(graph.handle, points.data_ptr(), queries.data_ptr(), nq, k, L, float(eps),
                                     ids_out.data_ptr(), dists_out.data_ptr(), _stream_ptr()))
     return ids_out, dists_out
+
+
+def ann_search_noalloc(graph: Graph, points, queries, k, L, ids_out, dists_out, eps=-1.0) -> None:
+    """ann_search / ann_search_eps without any allocation: the caller brings the outputs (nq x k
+    int32 ids; int32 or float32 distances) and nothing is allocated here or in the library."""
+    nq = queries.shape[0]
+    _check(lib().ann_search_noalloc(graph.handle, points.data_ptr(), queries.data_ptr(), nq, k, L, float(eps),
+                                    ids_out.data_ptr(), dists_out.data_ptr(), _stream_ptr()))
 
 
 def ann_start_vertex(points) -> int:

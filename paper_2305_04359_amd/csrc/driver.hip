@@ -2,6 +2,8 @@
 // (batchBuild) and the per-batch launch sequence of BatchInsert.
 #include "driver_internal.hpp"
 
+#include <mutex>
+
 using namespace annmi;
 
 namespace annmi {
@@ -582,6 +584,37 @@ int grow_graph(ann_graph* g, u64 n_total, hipStream_t st) {
 
 }  // namespace annmi
 
+// ---------------------------------------------------------------------------------------------
+// ann_search_noalloc: the query search for callers that cannot allocate.  The one buffer the
+// search may need beyond its inputs and outputs, the zero-padded copy of the queries (byte rows
+// that are not a multiple of 16 bytes), lives in a device array of this library instead of a
+// hipMalloc'ed one.  Each device holds its own copy of the array, at its own address, until the
+// process ends; the address is asked for once per device, with that device current.
+// ---------------------------------------------------------------------------------------------
+constexpr size_t NOALLOC_SCRATCH_BYTES = (size_t)ANN_NOALLOC_SCRATCH_MIB << 20;
+static __device__ __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+void* g_scratch_ptr[MAX_DEVICES];  // per device: where `scratch` lives there (null: not asked yet)
+std::mutex g_scratch_lock;
+
+int noalloc_scratch(void** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) return fail(ANN_EINVAL, "device %d is beyond the %d this call serves", dev, MAX_DEVICES);
+  std::lock_guard<std::mutex> hold(g_scratch_lock);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (p == nullptr) return fail(ANN_EINTERNAL, "the scratch array has no address on device %d", dev);
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return ANN_OK;
+}
+}  // namespace
+
 extern "C" {
 
 const char* ann_last_error(void) { return last_error_text(); }
@@ -1049,6 +1082,41 @@ int ann_search_eps(const ann_graph* g, const void* points_dev, const void* queri
   rc_ = query_launch(g, pts, qsp, nullptr, nq, k, L, eps, nullptr, ids_dev, dists_dev, st_);
   if (rc_) return rc_;
   return ANN_OK;
+} catch (...) {
+  return annmi::on_exception();
+}
+
+int ann_search_noalloc(const ann_graph* g, const void* points_dev, const void* queries_dev, uint64_t nq, uint32_t k,
+                       uint32_t L, float eps, uint32_t* ids_dev, void* dists_dev, void* stream) try {
+  if (!g || !points_dev) return fail(ANN_EINVAL, "null argument");
+  if (!(eps < 16384.0f)) return fail(ANN_EINVAL, "eps must be below 16384 (negative: no pruning)");
+  if (nq == 0) return ANN_OK;
+  if (!queries_dev || !ids_dev || !dists_dev) return fail(ANN_EINVAL, "null argument");
+  if (k < 1 || k > L) return fail(ANN_EINVAL, "need 1 <= k <= L");
+  if (L > 2048) return fail(ANN_EINVAL, "L must be at most 2048");
+  if (nq >= (1ull << 31)) return fail(ANN_EINVAL, "too many queries");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const void* pts = points_dev;
+  const void* qsp = queries_dev;
+  if (g->pad_stride) {
+    // the padded copy of the points is the graph's, made by the build or by an earlier search
+    if (g->pad_buf == nullptr || g->pad_src != points_dev || g->pad_done < g->n || g->pad_cap < g->n)
+      return fail(ANN_EINVAL, "the graph holds no padded copy of this points array yet: ann_build makes it, and so "
+                              "does one call of ann_search");
+    if (nq * g->pad_stride > NOALLOC_SCRATCH_BYTES)
+      return fail(ANN_EINVAL, "%llu queries of %llu padded bytes exceed the %d MiB this call can stage (at most %llu queries)",
+                  (unsigned long long)nq, (unsigned long long)g->pad_stride, ANN_NOALLOC_SCRATCH_MIB,
+                  (unsigned long long)(NOALLOC_SCRATCH_BYTES / g->pad_stride));
+    void* sp = nullptr;
+    int rc = noalloc_scratch(&sp);
+    if (rc) return rc;
+    // every word of the rows used is written (zero tails included): nothing of an earlier call shows
+    rc = pad_rows(queries_dev, nq, g->d, sp, g->pad_stride, st);
+    if (rc) return rc;
+    pts = g->pad_buf;
+    qsp = sp;
+  }
+  return query_launch(g, pts, qsp, nullptr, nq, k, L, eps, nullptr, ids_dev, dists_dev, st);
 } catch (...) {
   return annmi::on_exception();
 }
