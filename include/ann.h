@@ -266,6 +266,11 @@ int ann_get_stats(const ann_graph* g, ann_stats* stats); /* cumulative over buil
  * (builds start with opts->collect_stats).  With them on, searches on this
  * graph add their hops and distance evaluations too.                        */
 int ann_graph_set_stats(ann_graph* g, int on);
+/* Size of the visited filter of the searches that follow on this graph, as
+ * opts->hash_bits of ann_build (log2 of the size in 32-bit words, 4..13; 0 =
+ * chosen from the beam width).  For the sizing study of Sec. 4.5: results never
+ * depend on it, only the number of repeated distance evaluations does.       */
+int ann_graph_set_filter_bits(ann_graph* g, uint32_t hash_bits);
 void ann_graph_free(ann_graph* g);
 
 /* Stable LSD radix sort of `count` 64-bit keys by bits [32, 32+key_bits) only
@@ -386,7 +391,8 @@ void ann_hnsw_free(ann_hnsw* h);
  *   ANN_U8 / ANN_I8 with ANN_L2SQ and d <= 128 (exact integers throughout), or
  *   ANN_F32 with either metric, d % 4 == 0 and d <= 256 (fp32 sums on the
  *   vector units and the fp32 matrix cores; squared L2 inside a leaf is taken
- *   as |a|^2 + |b|^2 - 2<a,b>);
+ *   as |a|^2 + |b|^2 - 2<a,b> to pick a point's l candidates, whose distances
+ *   are then taken again as sum (a - b)^2);
  *   1 <= T < 2^20, 2 <= Ls <= 1024, 1 <= l <= 16, Ls * l <= 16384,
  *   1 <= s <= 255, 1 <= R <= 512, T * 2n < 2^32.
  * Blocks until done.
@@ -408,6 +414,17 @@ int ann_hcnng_tree_edges(const void* points_dev, uint64_t n, uint32_t d, ann_dty
                          uint32_t Ls, uint32_t s, uint32_t l, uint64_t seed, uint32_t tree, void* stream,
                          uint32_t* perm_host, uint64_t* leaf_off_host, uint64_t* nleaves,
                          uint32_t* pairs_host, uint64_t* npairs);
+
+/* The nearest neighbours inside the leaves of one cluster tree, as the builder's
+ * kernels computed them before the pairs are sorted (for tests of Sec. 4.3's
+ * "l nearest neighbours in the leaf"): perm_host / leaf_off_host / nleaves as in
+ * ann_hcnng_tree_edges; knn_ids_host receives n x l point ids, row i for the
+ * point perm_host[i], nearest first by (distance, position in the leaf),
+ * ANN_NONE where the leaf has fewer other points; knn_dists_host the n x l
+ * distances (int32 for u8/i8, float for f32; INT32_MAX / +inf padding).       */
+int ann_hcnng_leaf_knn(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric,
+                       uint32_t Ls, uint32_t l, uint64_t seed, uint32_t tree, void* stream, uint32_t* perm_host,
+                       uint64_t* leaf_off_host, uint64_t* nleaves, uint32_t* knn_ids_host, void* knn_dists_host);
 
 /* Thread-local description of the last error on this thread ("" if none).   */
 const char* ann_last_error(void);

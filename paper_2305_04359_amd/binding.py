@@ -69,11 +69,11 @@ class HnswInfo(C.Structure):
 
 EXPORTS = [
     "ann_build", "ann_insert_batch", "ann_insert_points", "ann_graph_reserve", "ann_search", "ann_search_eps", "ann_search_noalloc", "ann_start_vertex", "ann_graph_from_host",
-    "ann_graph_copy_neighbors", "ann_graph_device_rows", "ann_graph_info", "ann_get_stats", "ann_graph_set_stats",
+    "ann_graph_copy_neighbors", "ann_graph_device_rows", "ann_graph_info", "ann_get_stats", "ann_graph_set_stats", "ann_graph_set_filter_bits",
     "ann_graph_free", "ann_sort_edges", "ann_last_error",
     "ann_hnsw_build", "ann_hnsw_insert_points", "ann_hnsw_from_host", "ann_hnsw_search", "ann_hnsw_info", "ann_hnsw_copy_levels", "ann_hnsw_layer_size",
     "ann_hnsw_copy_layer", "ann_hnsw_get_stats", "ann_hnsw_free",
-    "ann_hcnng_build", "ann_hcnng_tree_edges",
+    "ann_hcnng_build", "ann_hcnng_tree_edges", "ann_hcnng_leaf_knn",
 ]
 
 _lib = None
@@ -122,6 +122,8 @@ def lib():
         L.ann_get_stats.argtypes = [vp, C.POINTER(Stats)]
         L.ann_graph_set_stats.restype = C.c_int
         L.ann_graph_set_stats.argtypes = [vp, C.c_int]
+        L.ann_graph_set_filter_bits.restype = C.c_int
+        L.ann_graph_set_filter_bits.argtypes = [vp, u32]
         L.ann_graph_free.restype = None
         L.ann_graph_free.argtypes = [vp]
         L.ann_sort_edges.restype = C.c_int
@@ -154,6 +156,9 @@ def lib():
         L.ann_hcnng_tree_edges.restype = C.c_int
         L.ann_hcnng_tree_edges.argtypes = [vp, u64, u32, C.c_int, C.c_int, u32, u32, u32, u64, u32, vp, vp, vp,
                                            C.POINTER(u64), vp, C.POINTER(u64)]
+        L.ann_hcnng_leaf_knn.restype = C.c_int
+        L.ann_hcnng_leaf_knn.argtypes = [vp, u64, u32, C.c_int, C.c_int, u32, u32, u64, u32, vp, vp, vp,
+                                         C.POINTER(u64), vp, vp]
         L.ann_last_error.restype = C.c_char_p
         L.ann_last_error.argtypes = []
         _lib = L
@@ -288,6 +293,9 @@ class Graph:
 
     def set_stats(self, on: bool) -> None:
         _check(lib().ann_graph_set_stats(self._h, 1 if on else 0))
+
+    def set_filter_bits(self, hash_bits: int) -> None:
+        _check(lib().ann_graph_set_filter_bits(self._h, int(hash_bits)))
 
     def neighbors(self) -> np.ndarray:
         gi = self.info()
@@ -568,3 +576,20 @@ def ann_hcnng_tree_edges(points, Ls, s, l, seed, tree, metric=L2SQ):
                                       off.ctypes.data_as(C.c_void_p), C.byref(nl),
                                       pairs.ctypes.data_as(C.c_void_p), C.byref(npairs)))
     return perm, off[:nl.value + 1].astype(np.int64), pairs[:npairs.value].copy()
+
+
+def ann_hcnng_leaf_knn(points, Ls, l, seed, tree, metric=L2SQ):
+    """One cluster tree's leaves and every point's l nearest neighbours inside its leaf:
+    (perm, leaf_off, knn_ids[n, l], knn_dists[n, l]); row i belongs to the point perm[i]."""
+    points = _dev2d(points, "points")
+    n = points.shape[0]
+    perm = np.empty(n, np.uint32)
+    off = np.empty(n + 1, np.uint64)
+    ids = np.empty((n, l), np.uint32)
+    dists = np.empty((n, l), np.float32 if _dtype_code(points) == F32 else np.int32)
+    nl = C.c_uint64(0)
+    _check(lib().ann_hcnng_leaf_knn(points.data_ptr(), n, points.shape[1], _dtype_code(points), int(metric), Ls, l, seed,
+                                    tree, _stream_ptr(), perm.ctypes.data_as(C.c_void_p),
+                                    off.ctypes.data_as(C.c_void_p), C.byref(nl), ids.ctypes.data_as(C.c_void_p),
+                                    dists.ctypes.data_as(C.c_void_p)))
+    return perm, off[:nl.value + 1].astype(np.int64), ids, dists

@@ -685,6 +685,13 @@ int ann_graph_set_stats(ann_graph* g, int on) {
   return ANN_OK;
 }
 
+int ann_graph_set_filter_bits(ann_graph* g, uint32_t hash_bits) {
+  if (!g) return fail(ANN_EINVAL, "null argument");
+  if (hash_bits && (hash_bits < 4 || hash_bits > 13)) return fail(ANN_EINVAL, "hash_bits must be in [4, 13]");
+  g->hash_bits = hash_bits;
+  return ANN_OK;
+}
+
 const uint32_t* ann_graph_device_rows(const ann_graph* g) { return g ? g->rows : nullptr; }
 
 int ann_graph_copy_neighbors(const ann_graph* g, uint32_t* rows_host) try {

@@ -448,8 +448,9 @@ __global__ __launch_bounds__(256) void hc_gather_f32_kernel(const unsigned char*
 // elements of the inner product per instruction; a lane feeds it, one after the other, the four
 // floats of a 16-byte piece, the lower half-wave taking bytes 0..15 of every 32 and the upper half
 // bytes 16..31: a reordering of the sum's terms that both operands share).  Squared L2 comes out
-// as |a|^2 + |b|^2 - 2<a,b>, clamped at zero.  Selection as in the integer kernel; knn_d receives
-// the order-preserving 32-bit image of the distance.
+// as |a|^2 + |b|^2 - 2<a,b>, clamped at zero, for the selection (as in the integer kernel); the
+// distances of the l candidates selected are then taken again as sum (a - b)^2 (see the end of the
+// kernel).  knn_d receives the order-preserving 32-bit image of the distance.
 template <int LCAP, bool MIPS>
 __global__ __launch_bounds__(64) void hc_knn_f32_kernel(const unsigned char* leafvec, const float* leafnorm,
                                                         u32 lv_stride, const u32* leaf_off, const u32* tile_of_leaf,
@@ -542,6 +543,57 @@ __global__ __launch_bounds__(64) void hc_knn_f32_kernel(const unsigned char* lea
       const u64 lo = key < best[i] ? key : best[i];
       key = key < best[i] ? best[i] : key;
       best[i] = lo;
+    }
+  }
+  if constexpr (!MIPS) {
+    // |a|^2 + |b|^2 - 2<a,b> loses the leading digits of a small distance (unit vectors a hundredth
+    // apart: errors of a few 1e-5 of the value), which is fine for picking candidates but not for
+    // what the pairs are sorted by, nor for deciding the last places of the list.  So the list
+    // kept so far is longer than l (LCAP entries: the launch picks LCAP = 16 for l <= 10 and 24
+    // beyond); the distances of all of them are taken again as sum (a - b)^2, a chain of fused
+    // multiply-adds in the order of the elements, the list is put in (distance, position) order
+    // once more and its first l entries are the result.  Both lanes of a point hold the same
+    // merged list by now; each takes every other entry and the two exchange the results.
+    const u32 npc = lv_stride / 16u;
+    const unsigned char* qbase = tiles + (u64)(qrow >> 5) * 32u * lv_stride + (u64)(qrow & 31u) * 16u;
+    u64 fresh[LCAP];
+#pragma unroll
+    for (int j = 0; j < LCAP; ++j) {
+      fresh[j] = KEY_INF;
+      if (((u32)j & 1u) == half && best[j] != KEY_INF) {
+        const u32 cand = (u32)(best[j] & 0xFFFFull);
+        const unsigned char* cbase = tiles + (u64)(cand >> 5) * 32u * lv_stride + (u64)(cand & 31u) * 16u;
+        float dd = 0.0f;
+        for (u32 c = 0; c < npc; ++c) {
+          const float4 a = *reinterpret_cast<const float4*>(qbase + (u64)c * 512u);
+          const float4 b = *reinterpret_cast<const float4*>(cbase + (u64)c * 512u);
+          float t = a.x - b.x;
+          dd = __builtin_fmaf(t, t, dd);
+          t = a.y - b.y;
+          dd = __builtin_fmaf(t, t, dd);
+          t = a.z - b.z;
+          dd = __builtin_fmaf(t, t, dd);
+          t = a.w - b.w;
+          dd = __builtin_fmaf(t, t, dd);
+        }
+        fresh[j] = ((u64)dkey_from_float(dd) << 32) | cand;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < LCAP; ++j) {
+      const u64 o = (u64)__shfl_xor((unsigned long long)fresh[j], 32, 64);
+      fresh[j] = ((u32)j & 1u) == half ? fresh[j] : o;
+      best[j] = KEY_INF;
+    }
+#pragma unroll
+    for (int j = 0; j < LCAP; ++j) {
+      u64 key = fresh[j];
+#pragma unroll
+      for (int i = 0; i < LCAP; ++i) {
+        const u64 lo = key < best[i] ? key : best[i];
+        key = key < best[i] ? best[i] : key;
+        best[i] = lo;
+      }
     }
   }
   if (half == 0 && q < cnt) {
@@ -1034,6 +1086,10 @@ struct HcCtx {
   u64 leaf_tiles = 0;  // tiles of 32 rows that leafvec holds
   u64 seg_words = 0;
   HostBuf h_up, h_route, h_first;  // a level's node table, its routing table, the left counts read back
+  // test hook (ann_hcnng_leaf_knn): host arrays that receive every point's neighbour positions
+  // and distance keys as the nearest-neighbour kernel leaves them
+  unsigned short* dump_pos = nullptr;
+  i32* dump_d = nullptr;
   int alloc() {
     HIP_TRY(final_keys.alloc(N * 8));
     for (auto& k : work) HIP_TRY(k.alloc(N * 8));
@@ -1226,10 +1282,11 @@ int hc_leaves(HcCtx& X, u32 G, const std::vector<Leaf>& leaves, u64* arcs, hipSt
     else
       HC_KNN((hc_knn_f32_kernel<16, true>), float);
   } else if (X.is_f32) {
+    // squared L2: a few more candidates than l are kept, see the end of the kernel
     if (X.l <= 10)
-      HC_KNN((hc_knn_f32_kernel<10, false>), float);
-    else
       HC_KNN((hc_knn_f32_kernel<16, false>), float);
+    else
+      HC_KNN((hc_knn_f32_kernel<24, false>), float);
   } else if (X.l <= 4) {
     HC_KNN(hc_knn_kernel<4>, i32);
   } else if (X.l <= 8) {
@@ -1241,6 +1298,11 @@ int hc_leaves(HcCtx& X, u32 G, const std::vector<Leaf>& leaves, u64* arcs, hipSt
   }
 #undef HC_KNN
   HIP_TRY(hipGetLastError());
+  if (X.dump_pos != nullptr) {
+    HIP_TRY(hipMemcpyAsync(X.dump_pos, X.knn_pos.p, N * X.l * 2, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(X.dump_d, X.knn_d.p, N * X.l * 4, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+  }
   if (X.pair_cnt_cap < nleaves) {
     HIP_TRY(hipStreamSynchronize(st));
     HIP_TRY(X.pair_cnt.alloc(((size_t)nleaves + 1) * 4));
@@ -1320,10 +1382,16 @@ using namespace annmi::hcnng;
 
 extern "C" {
 
-int ann_hcnng_tree_edges(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric,
-                         uint32_t Ls, uint32_t s, uint32_t l, uint64_t seed, uint32_t tree, void* stream, uint32_t* perm_host,
-                         uint64_t* leaf_off_host, uint64_t* nleaves, uint32_t* pairs_host, uint64_t* npairs) try {
-  if (!points_dev || !perm_host || !leaf_off_host || !nleaves || !pairs_host || !npairs)
+}  // extern "C"
+
+// One tree: the order of its leaves, their accepted pairs and (when knn_ids is given) every
+// point's nearest neighbours inside its leaf with their distances, as the kernels left them.
+static int hc_one_tree(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric,
+                       uint32_t Ls, uint32_t s, uint32_t l, uint64_t seed, uint32_t tree, void* stream, uint32_t* perm_host,
+                       uint64_t* leaf_off_host, uint64_t* nleaves, uint32_t* pairs_host, uint64_t* npairs,
+                       uint32_t* knn_ids, void* knn_dists) {
+  if (!points_dev || !perm_host || !leaf_off_host || !nleaves || (!pairs_host && !knn_ids) || (pairs_host && !npairs) ||
+      (knn_ids && !knn_dists))
     return fail(ANN_EINVAL, "null argument");
   int rc = hc_check(n, d, dtype, metric, Ls, s, l);
   if (rc) return rc;
@@ -1345,6 +1413,14 @@ int ann_hcnng_tree_edges(const void* points_dev, uint64_t n, uint32_t d, ann_dty
   DevBuf arcs;
   HIP_TRY(arcs.alloc(2 * n * 8));
   HIP_TRY(hipMemsetAsync(arcs.p, 0xFF, 2 * n * 8, st));
+  std::vector<unsigned short> kpos;
+  std::vector<i32> kd;
+  if (knn_ids) {
+    kpos.resize(n * l);
+    kd.resize(n * l);
+    X.dump_pos = kpos.data();
+    X.dump_d = kd.data();
+  }
   std::vector<Leaf> leaves;
   rc = hc_partition(X, tree, 1, leaves, st);
   if (rc) return rc;
@@ -1358,15 +1434,58 @@ int ann_hcnng_tree_edges(const void* points_dev, uint64_t n, uint32_t d, ann_dty
   for (size_t j = 0; j < leaves.size(); ++j) leaf_off_host[j] = leaves[j].goff;
   leaf_off_host[leaves.size()] = n;
   *nleaves = leaves.size();
-  u64 np = 0;
-  for (u64 i = 0; i + 1 < 2 * n; i += 2)
-    if (ha[i] != ~0ull) {
-      pairs_host[2 * np] = (u32)(ha[i] >> 32);
-      pairs_host[2 * np + 1] = (u32)ha[i];
-      ++np;
+  if (pairs_host) {
+    u64 np = 0;
+    for (u64 i = 0; i + 1 < 2 * n; i += 2)
+      if (ha[i] != ~0ull) {
+        pairs_host[2 * np] = (u32)(ha[i] >> 32);
+        pairs_host[2 * np + 1] = (u32)ha[i];
+        ++np;
+      }
+    *npairs = np;
+  }
+  if (knn_ids) {
+    // positions inside the leaf -> point ids; distance keys -> distances
+    for (size_t j = 0; j < leaves.size(); ++j) {
+      const u64 lo = leaves[j].goff;
+      for (u64 i = lo; i < lo + leaves[j].cnt; ++i)
+        for (u32 t = 0; t < l; ++t) {
+          const u64 o = i * l + t;
+          const bool none = kpos[o] == 0xFFFFu;
+          knn_ids[o] = none ? ANN_NONE : perm_host[lo + kpos[o]];
+          const u32 key = (u32)kd[o];
+          if (dtype == ANN_F32) {
+            const u32 bits = (key & 0x80000000u) ? (key & 0x7FFFFFFFu) : ~key;  // inverse of the order-preserving image
+            float f;
+            memcpy(&f, &bits, 4);
+            static_cast<float*>(knn_dists)[o] = none ? INFINITY : f;
+          } else {
+            static_cast<int32_t*>(knn_dists)[o] = none ? INT32_MAX : (int32_t)key;
+          }
+        }
     }
-  *npairs = np;
+  }
   return ANN_OK;
+}
+
+extern "C" {
+
+int ann_hcnng_tree_edges(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric,
+                         uint32_t Ls, uint32_t s, uint32_t l, uint64_t seed, uint32_t tree, void* stream, uint32_t* perm_host,
+                         uint64_t* leaf_off_host, uint64_t* nleaves, uint32_t* pairs_host, uint64_t* npairs) try {
+  if (!pairs_host || !npairs) return fail(ANN_EINVAL, "null argument");
+  return hc_one_tree(points_dev, n, d, dtype, metric, Ls, s, l, seed, tree, stream, perm_host, leaf_off_host, nleaves,
+                     pairs_host, npairs, nullptr, nullptr);
+} catch (...) {
+  return annmi::on_exception();
+}
+
+int ann_hcnng_leaf_knn(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, ann_metric metric, uint32_t Ls,
+                       uint32_t l, uint64_t seed, uint32_t tree, void* stream, uint32_t* perm_host,
+                       uint64_t* leaf_off_host, uint64_t* nleaves, uint32_t* knn_ids_host, void* knn_dists_host) try {
+  if (!knn_ids_host || !knn_dists_host) return fail(ANN_EINVAL, "null argument");
+  return hc_one_tree(points_dev, n, d, dtype, metric, Ls, 1, l, seed, tree, stream, perm_host, leaf_off_host, nleaves,
+                     nullptr, nullptr, knn_ids_host, knn_dists_host);
 } catch (...) {
   return annmi::on_exception();
 }

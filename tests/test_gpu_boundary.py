@@ -205,3 +205,62 @@ def test_counters_switch(env, c1, c1_oracle):
     A.ann_search(g, pts, qs, 10, 40)
     torch.cuda.synchronize()
     assert g.stats()["searches"] == 100
+
+
+@pytest.mark.parametrize("kind", ["u8", "f32_l2", "f32_ip", "f32_l2_close"])
+def test_hcnng_leaf_neighbours_one_by_one(env, kind):
+    """The l nearest neighbours inside a leaf (Sec. 4.3), every (point, neighbour, distance) entry
+    checked on its own: integer rows exactly; float rows within 1e-5 of the fp64 value (inner
+    products: of sum |p_i q_i|), also where the points of a leaf are a hundredth apart on the unit
+    sphere and |a|^2 + |b|^2 - 2<a,b> alone would lose the leading digits."""
+    torch, A, O = env
+    Ls, l = 150, 10
+    if kind == "u8":
+        w = W.c1(n=4000, nq=1)
+        pts_h, metric = w.points, 0
+    elif kind == "f32_l2_close":
+        rng = np.random.default_rng(5)
+        cen = rng.standard_normal((40, 96))
+        cen /= np.linalg.norm(cen, axis=1, keepdims=True)
+        x = cen[rng.integers(0, 40, 4000)] + 0.001 * rng.standard_normal((4000, 96))
+        pts_h, metric = (x / np.linalg.norm(x, axis=1, keepdims=True)).astype(np.float32), 0
+    else:
+        w = W.c4(n=4000, nq=1)
+        pts_h, metric = w.points, (0 if kind == "f32_l2" else 1)
+    perm, off, ids, dists = A.ann_hcnng_leaf_knn(dev(torch, pts_h), Ls, l, 3, 1, metric=metric)
+    n = len(pts_h)
+    assert sorted(perm.tolist()) == list(range(n))
+    P = pts_h.astype(np.float64)
+    same_lists = 0
+    for j in range(len(off) - 1):
+        leaf = perm[off[j]:off[j + 1]]
+        X = P[leaf]
+        if metric == 0:
+            D = ((X[:, None, :] - X[None, :, :]) ** 2).sum(-1)
+            scale = D
+        else:
+            D = -(X @ X.T)
+            scale = np.abs(X[:, None, :] * X[None, :, :]).sum(-1)
+        pos = {int(p): i for i, p in enumerate(leaf)}
+        k = min(l, len(leaf) - 1)
+        for i, p in enumerate(leaf):
+            row_i, row_d = ids[off[j] + i], dists[off[j] + i]
+            assert (row_i[k:] == 0xFFFFFFFF).all() and (row_i[:k] != 0xFFFFFFFF).all()
+            c = np.array([pos[int(x)] for x in row_i[:k]])
+            assert i not in c and len(set(c.tolist())) == k
+            ref = D[i, c]
+            if pts_h.dtype == np.uint8:
+                assert (row_d[:k].astype(np.int64) == ref.astype(np.int64)).all()
+            else:
+                err = np.abs(row_d[:k].astype(np.float64) - ref)
+                assert (err <= 1e-5 * scale[i, c] + 1e-30).all(), \
+                    f"leaf {j} point {p}: relative error {np.max(err / (scale[i, c] + 1e-30)):.2e}"
+            assert (np.diff(row_d[:k].astype(np.float64)) >= 0).all()
+            # the list against the exact one under (distance, position in the leaf)
+            d_i = D[i].copy()
+            d_i[i] = np.inf
+            want = np.lexsort((np.arange(len(leaf)), d_i))[:k]
+            same_lists += int((want == c).all())
+    share = same_lists / n
+    say(f"  {kind}: {len(off) - 1} leaves, lists identical to the exact ones: {share:.4f}")
+    assert share == 1.0 if pts_h.dtype == np.uint8 else share >= 0.97
