@@ -2,6 +2,7 @@
 // (batchBuild) and the per-batch launch sequence of BatchInsert.
 #include "driver_internal.hpp"
 
+#include <algorithm>
 #include <mutex>
 
 using namespace annmi;
@@ -710,6 +711,18 @@ int ann_graph_from_host(const uint32_t* rows_host, uint64_t n, uint32_t d, ann_d
   // every id must be a vertex or ANN_NONE: the kernels follow them without further checks
   for (u64 i = 0; i < n * R; ++i)
     if (rows_host[i] != ANN_NONE && rows_host[i] >= n) return fail(ANN_EINVAL, "neighbour id out of range");
+  {
+    // and no id twice in a row: a search takes the neighbours of a vertex as distinct candidates
+    std::vector<u32> row(R);
+    for (u64 v = 0; v < n; ++v) {
+      u32 c = 0;
+      for (u32 j = 0; j < R; ++j)
+        if (rows_host[v * R + j] != ANN_NONE) row[c++] = rows_host[v * R + j];
+      std::sort(row.begin(), row.begin() + c);
+      for (u32 j = 1; j < c; ++j)
+        if (row[j] == row[j - 1]) return fail(ANN_EINVAL, "vertex %llu lists neighbour %u twice", (unsigned long long)v, row[j]);
+    }
+  }
   ann_graph* g = nullptr;
   int rc = new_graph(n, d, dtype, metric, R, &g);
   if (rc) return rc;

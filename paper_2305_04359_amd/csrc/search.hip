@@ -10,16 +10,18 @@ namespace annmi {
 u32 search_lds_bytes(u32 L, u32 hash_buckets) { return search_nslot_for(L) * 64 * 8 + 64 * 8 + hash_buckets * 16; }
 
 // Size of the visited filter.  An explicit hash_bits (log2 of the size in 32-bit words) is taken
-// as it is.  Otherwise: 8 words per beam entry, rounded up to a power of two (512..4096 words;
-// 8192 for beams above 512, where a wave's LDS is dominated by the beam anyway),
-// then adjusted so that the wave's LDS lands exactly on the next occupancy step (waves per CU a
-// multiple of four, at most 32, LDS handed out in 512-byte units of 160 KB): measured on 128-d
-// uint8 data, occupancy is worth more than the evaluations a larger table saves.  The table is
-// never cut below 3/4 of the power of two.
+// as it is.  Otherwise: 8 words per beam entry, rounded up to a power of two, but never more than
+// 1,024 words (512 for beams above 512 entries), then adjusted so that the wave's LDS lands
+// exactly on the next occupancy step (waves per CU a multiple of four, at most 32, LDS handed
+// out in 512-byte units of 160 KB).  Occupancy is worth more than the evaluations a larger table
+// saves: measured on 128-d uint8 data at beam 128 (a million points), and at beams of 200 to
+// 2,048 on a hundred million points, where tables of 1,024 and 512 words answer 1.7 to 2.3 times
+// the queries per second of tables of 4,096 and 8,192.  The table is never cut below 3/4 of the
+// power of two.
 u32 search_hash_buckets(u32 L, u32 hash_bits) {
   if (hash_bits) return 1u << (hash_bits - 2u);
   u32 want = 8u * L, bits = 9;
-  while ((1u << bits) < want && bits < (L > 512u ? 13u : 12u)) ++bits;
+  while ((1u << bits) < want && bits < (L > 512u ? 9u : 10u)) ++bits;
   const u32 full = 1u << (bits - 2u);
   const u32 base = search_lds_bytes(L, 0);
   const u32 lds_full = (search_lds_bytes(L, full) + 511u) & ~511u;
