@@ -415,6 +415,9 @@ def main():
     ap.add_argument("--filter-sweep", action="store_true",
                     help="also build with several sizes of the search's visited filter (Sec. 4.5) and report "
                          "the search time and distance evaluations of each")
+    ap.add_argument("--batch-sweep", action="store_true",
+                    help="also build with several bounds theta on the batch size (Sec. 3.1) and report the time of "
+                         "the build's phases for each: what a batch costs whatever its size, and what a search costs")
     ap.add_argument("--only-build", action="store_true", help="profiling: builds only (plus --search-L launches)")
     ap.add_argument("--search-L", type=int, default=0)
     ap.add_argument("--search-eps", type=float, default=None)
@@ -569,6 +572,19 @@ def main():
                                  "evals_per_search": round(sf["evals"] / max(1, sf["searches"]), 1)})
             del gf
             say(f"filter sweep: hash_bits={hb} search {sf['ms_search']:.1f} ms")
+    # the bound on the batch size (Sec. 3.1): every batch ends with searches that run on an emptying
+    # chip, so a build of many small batches pays that latency more often
+    batch_sweep = None
+    if args.batch_sweep:
+        batch_sweep = []
+        for cap in (w.theta // 4, w.theta // 2, w.theta, 2 * w.theta, 4 * w.theta):
+            gb = build(collect_stats=True, batch_cap=cap)
+            sb = gb.stats()
+            batch_sweep.append({"batch_cap": cap, "rounds": int(sb["rounds"]),
+                                **{kk: round(sb[kk], 2) for kk in ("ms_search", "ms_prune", "ms_sort", "ms_merge",
+                                                                   "ms_total")}})
+            del gb
+            say(f"batch sweep: cap={cap} search {sb['ms_search']:.1f} ms of {sb['ms_total']:.1f}")
     ms_per_step = float(np.mean(step_ms))
     bms = float(np.mean(build_ms))
     points_per_s = w.n / (bms / 1e3)
@@ -590,6 +606,7 @@ def main():
         "qps_at_recall_0.95": qpoints[0.95],
         "search_sweep": sweep,
         "filter_sweep": filter_sweep,
+        "batch_sweep": batch_sweep,
         **extras,
         "build_counters": {kk: int(st[kk]) for kk in ("searches", "hops", "evals", "prunes", "reprunes", "appends",
                                                       "edges", "prune_evals", "redone", "rounds", "passes", "survivors",

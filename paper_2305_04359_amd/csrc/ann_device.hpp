@@ -251,8 +251,12 @@ struct PassBatch {
 // candidate cand_of_lane(l) = 8*(l&7) + (l>>3) when that index is < cnt.
 __device__ __forceinline__ u32 cand_of_lane(int lane) { return (u32)(8 * (lane & 7) + (lane >> 3)); }
 
-// passes t0 .. t0+PBX-1 (a pass = 8 candidates): all loads first, then the arithmetic
-template <int KIND, int VEC, int NCH, int PBX, class IdAt>
+// passes t0 .. t0+PBX-1 (a pass = 8 candidates): all loads first, then the arithmetic.
+// FULL: every lane's pieces exist (rows of exactly 8 * NCH pieces), and a group without a
+// candidate reads candidate 0's row again (a line the pass fetches anyway) instead of being
+// masked off and handed zeros: no compare, branch or register clearing per pass; its result is
+// never looked at.
+template <int KIND, int VEC, int NCH, int PBX, bool FULL, class IdAt>
 __device__ __forceinline__ void eval_passes(const VecTable& T, const QueryRegs<KIND, VEC, NCH>& Q, IdAt id_at,
                                             u32 cnt, u32 t0, int sub, u32 grp, u32& result) {
   Piece<VEC> x[PBX][NCH];
@@ -260,12 +264,19 @@ __device__ __forceinline__ void eval_passes(const VecTable& T, const QueryRegs<K
   for (int tt = 0; tt < PBX; ++tt) {
     const u32 c = 8u * (t0 + tt) + grp;
     const bool ok = c < cnt;
-    const u32 id = ok ? id_at(c) : 0u;
-    const char* row = T.base + (u64)id * T.row_bytes;
+    if constexpr (FULL) {
+      const u32 id = id_at(ok ? c : 0u);
+      const char* row = T.base + (u64)id * T.row_bytes;
 #pragma unroll
-    for (int u = 0; u < NCH; ++u) {
-      const u32 pc = sub + LPC * u;
-      x[tt][u] = (ok && pc < T.npieces) ? load_piece<VEC>(row + (u64)pc * VEC) : zero_piece<VEC>();
+      for (int u = 0; u < NCH; ++u) x[tt][u] = load_piece<VEC>(row + (u64)(sub + LPC * u) * VEC);
+    } else {
+      const u32 id = ok ? id_at(c) : 0u;
+      const char* row = T.base + (u64)id * T.row_bytes;
+#pragma unroll
+      for (int u = 0; u < NCH; ++u) {
+        const u32 pc = sub + LPC * u;
+        x[tt][u] = (ok && pc < T.npieces) ? load_piece<VEC>(row + (u64)pc * VEC) : zero_piece<VEC>();
+      }
     }
   }
 #pragma unroll
@@ -275,9 +286,9 @@ __device__ __forceinline__ void eval_passes(const VecTable& T, const QueryRegs<K
   }
 }
 
-template <int KIND, int VEC, int NCH, class IdAt>
-__device__ __forceinline__ u32 eval_up_to_64(const VecTable& T, const QueryRegs<KIND, VEC, NCH>& Q,
-                                             IdAt id_at, u32 cnt, int lane) {
+template <int KIND, int VEC, int NCH, bool FULL, class IdAt>
+__device__ __forceinline__ u32 eval_up_to_64_impl(const VecTable& T, const QueryRegs<KIND, VEC, NCH>& Q,
+                                                  IdAt id_at, u32 cnt, int lane) {
   constexpr int PB = PassBatch<VEC, NCH>::value;
   const int sub = lane & (LPC - 1);
   const u32 grp = (u32)lane >> 3;
@@ -287,31 +298,46 @@ __device__ __forceinline__ u32 eval_up_to_64(const VecTable& T, const QueryRegs<
   // whole batches, then the remainder with the smallest batch that covers it, so that a short
   // candidate list does not pay for eight passes of arithmetic
   while (npass - t0 >= (u32)PB) {
-    eval_passes<KIND, VEC, NCH, PB>(T, Q, id_at, cnt, t0, sub, grp, result);
+    eval_passes<KIND, VEC, NCH, PB, FULL>(T, Q, id_at, cnt, t0, sub, grp, result);
     t0 += PB;
   }
   const u32 rem = npass - t0;
   if (rem == 0) return result;
   if constexpr (PB >= 8) {
     if (rem > 4) {
-      eval_passes<KIND, VEC, NCH, 8>(T, Q, id_at, cnt, t0, sub, grp, result);
+      eval_passes<KIND, VEC, NCH, 8, FULL>(T, Q, id_at, cnt, t0, sub, grp, result);
       return result;
     }
   }
   if constexpr (PB >= 4) {
     if (rem > 2) {
-      eval_passes<KIND, VEC, NCH, 4>(T, Q, id_at, cnt, t0, sub, grp, result);
+      eval_passes<KIND, VEC, NCH, 4, FULL>(T, Q, id_at, cnt, t0, sub, grp, result);
       return result;
     }
   }
   if constexpr (PB >= 2) {
     if (rem > 1) {
-      eval_passes<KIND, VEC, NCH, 2>(T, Q, id_at, cnt, t0, sub, grp, result);
+      eval_passes<KIND, VEC, NCH, 2, FULL>(T, Q, id_at, cnt, t0, sub, grp, result);
       return result;
     }
   }
-  eval_passes<KIND, VEC, NCH, 1>(T, Q, id_at, cnt, t0, sub, grp, result);
+  eval_passes<KIND, VEC, NCH, 1, FULL>(T, Q, id_at, cnt, t0, sub, grp, result);
   return result;
+}
+
+template <int KIND, int VEC, int NCH, class IdAt>
+__device__ __forceinline__ u32 eval_up_to_64(const VecTable& T, const QueryRegs<KIND, VEC, NCH>& Q,
+                                             IdAt id_at, u32 cnt, int lane) {
+  return eval_up_to_64_impl<KIND, VEC, NCH, false>(T, Q, id_at, cnt, lane);
+}
+
+// The same for callers that pass cnt >= 1 and whose id_at(0) is a vertex: rows that fill every
+// lane's pieces take the unmasked passes.
+template <int KIND, int VEC, int NCH, class IdAt>
+__device__ __forceinline__ u32 eval_up_to_64_full_rows(const VecTable& T, const QueryRegs<KIND, VEC, NCH>& Q,
+                                                       IdAt id_at, u32 cnt, int lane) {
+  if (T.npieces == (u32)(LPC * NCH)) return eval_up_to_64_impl<KIND, VEC, NCH, true>(T, Q, id_at, cnt, lane);
+  return eval_up_to_64_impl<KIND, VEC, NCH, false>(T, Q, id_at, cnt, lane);
 }
 
 // alpha * d(p*,p') <= d(p,p')  (Sec. 4.1).  Integer kinds: alpha is held as a16 = round(alpha*2^16)
