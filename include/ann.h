@@ -146,7 +146,10 @@ typedef struct {
  *   alpha       > 0 (must be <= 1 for ANN_MIPS, Appendix A).  For u8/i8 it is
  *               quantised to llround(alpha * 65536) / 65536, which must be
  *               at least 1 / 65536.
- *   seed        drives the insertion order (SplitMix64 Fisher-Yates)
+ *   seed        drives the insertion order: the ids other than s in ascending
+ *               order, shuffled by Fisher-Yates from the front (step i exchanges
+ *               positions i and i + mulhi64(r, m - i), r the next SplitMix64(seed)
+ *               output), so the build starts while the order is still drawn
  *   opts        may be NULL
  *   *out        receives the graph; free with ann_graph_free
  * Blocks until the build is complete.

@@ -431,18 +431,26 @@ static uint64_t splitmix64(uint64_t* state) {
   return z ^ (z >> 31);
 }
 
-void vo_insertion_order(uint64_t n, uint32_t start, uint64_t seed, uint32_t* order) {
-  uint64_t m = 0;
-  for (uint64_t i = 0; i < n; ++i)
-    if (i != start) order[m++] = (uint32_t)i;
+/* Fisher-Yates from the front: step i = 0, 1, ..., m-2 draws the next output r
+ * of SplitMix64(seed) and exchanges positions i and i + floor(r * (m - i) / 2^64),
+ * a uniform choice among the positions not yet fixed.  Position i is final once
+ * step i is done, so the order can be consumed while it is still being drawn.  */
+static void shuffle_from_the_front(uint32_t* order, uint64_t m, uint64_t seed) {
   uint64_t state = seed;
-  for (uint64_t i = m; i-- > 1;) {
+  for (uint64_t i = 0; i + 1 < m; ++i) {
     uint64_t r = splitmix64(&state);
-    uint64_t j = (uint64_t)(((unsigned __int128)r * (unsigned __int128)(i + 1)) >> 64);
+    uint64_t j = i + (uint64_t)(((unsigned __int128)r * (unsigned __int128)(m - i)) >> 64);
     uint32_t t = order[i];
     order[i] = order[j];
     order[j] = t;
   }
+}
+
+void vo_insertion_order(uint64_t n, uint32_t start, uint64_t seed, uint32_t* order) {
+  uint64_t m = 0;
+  for (uint64_t i = 0; i < n; ++i)
+    if (i != start) order[m++] = (uint32_t)i;
+  shuffle_from_the_front(order, m, seed);
 }
 
 uint64_t vo_schedule(uint64_t m, uint64_t theta, uint64_t* bounds) {
@@ -724,14 +732,7 @@ int vo_build(const vo_data* D, uint32_t R, uint32_t L, double alpha, uint64_t se
 
 void vo_new_points_order(uint64_t first, uint64_t count, uint64_t seed, uint32_t* order) {
   for (uint64_t i = 0; i < count; ++i) order[i] = (uint32_t)(first + i);
-  uint64_t state = seed;
-  for (uint64_t i = count; i-- > 1;) {
-    uint64_t r = splitmix64(&state);
-    uint64_t j = (uint64_t)(((unsigned __int128)r * (unsigned __int128)(i + 1)) >> 64);
-    uint32_t t = order[i];
-    order[i] = order[j];
-    order[j] = t;
-  }
+  shuffle_from_the_front(order, count, seed);
 }
 
 uint64_t vo_schedule_from(uint64_t present, uint64_t m, uint64_t theta, uint64_t* bounds) {

@@ -24,8 +24,10 @@
  *   - start vertex = point nearest (squared L2) to the mean, smallest id on
  *     ties; it is present from the beginning with an empty row and is never
  *     re-inserted;
- *   - insertion order = Fisher-Yates shuffle of the ids other than the start
- *     vertex, driven by SplitMix64(seed), index drawn as mulhi64(r, i+1);
+ *   - insertion order = Fisher-Yates shuffle, from the front, of the ids other
+ *     than the start vertex in ascending order: step i = 0..m-2 exchanges
+ *     positions i and i + mulhi64(r, m - i), r the next output of
+ *     SplitMix64(seed) (position i is final after step i);
  *   - batch sizes: with `done` points already taken from the order and
  *     m = n-1 in total, the next batch has  min(done+2, theta, m-done)
  *     points, i.e. 2,4,8,... capped by theta (Alg. 3 with the batch size,
@@ -157,7 +159,7 @@ int vo_insert_points(const vo_data* data, uint32_t* graph, uint32_t R, uint32_t 
                      const uint32_t* order, uint64_t max_rounds, int threads, vo_stats* stats);
 
 /* The ids first..first+count-1 shuffled like vo_insertion_order shuffles
- * the ids of a build (Fisher-Yates from the back, SplitMix64(seed)).        */
+ * the ids of a build (Fisher-Yates from the front, SplitMix64(seed)).        */
 void vo_new_points_order(uint64_t first, uint64_t count, uint64_t seed, uint32_t* order);
 
 /* vo_schedule for m further points when `present` are already in: bounds[0]

@@ -3,6 +3,8 @@
 #include "driver_internal.hpp"
 
 #include <algorithm>
+#include <atomic>
+#include <chrono>
 #include <mutex>
 
 using namespace annmi;
@@ -113,6 +115,40 @@ u64 splitmix64(u64& state) {
   return z ^ (z >> 31);
 }
 
+// Fisher-Yates from the front, driven by SplitMix64(seed): step i = 0 .. m-2 exchanges positions
+// i and i + mulhi64(r, m - i), r the next output of the stream; position i is final once step i
+// is done.  `ready`, when given, is raised to the number of final positions every few thousand
+// steps, so that a build can hand the first batches to the GPU while the rest is still drawn
+// (a hundred million steps take the host half a second).  A step's partner depends on the random
+// stream alone, so it is known AHEAD steps early and its cache line is requested then: without
+// that the walk waits for memory at every step.
+void shuffle_in_place(u32* order, u64 m, u64 seed, std::atomic<u64>* ready) {
+  constexpr u64 AHEAD = 32;
+  u64 ring[AHEAD];
+  u64 state = seed;
+  const u64 steps = m > 1 ? m - 1 : 0;
+  u64 drawn = 0;  // partners drawn so far
+  for (; drawn < AHEAD && drawn < steps; ++drawn) {
+    const u64 r = splitmix64(state);
+    ring[drawn % AHEAD] = drawn + (u64)(((unsigned __int128)r * (unsigned __int128)(m - drawn)) >> 64);
+    __builtin_prefetch(order + ring[drawn % AHEAD], 1);
+  }
+  for (u64 i = 0; i < steps; ++i) {
+    const u64 j = ring[i % AHEAD];
+    if (drawn < steps) {  // the slot of step i is free now: it takes the partner of step i + AHEAD
+      const u64 r = splitmix64(state);
+      ring[drawn % AHEAD] = drawn + (u64)(((unsigned __int128)r * (unsigned __int128)(m - drawn)) >> 64);
+      __builtin_prefetch(order + ring[drawn % AHEAD], 1);
+      ++drawn;
+    }
+    const u32 t = order[i];
+    order[i] = order[j];
+    order[j] = t;
+    if (ready != nullptr && (i & 8191u) == 8191u) ready->store(i + 1, std::memory_order_release);
+  }
+  if (ready != nullptr) ready->store(m, std::memory_order_release);
+}
+
 }  // namespace annmi
 
 
@@ -139,6 +175,12 @@ __global__ __launch_bounds__(256) void pad_rows_kernel(const unsigned char* src,
 __global__ __launch_bounds__(256) void count_inserted_kernel(const u32* ids, u64 b, const u32* meta, u32* count) {
   const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < b && (meta[ids[i]] & 0xFFFFu) != 0u) atomicAdd(count, 1u);
+}
+
+// positions among the ids other than s -> ids: every position from s on stands for the next id
+__global__ __launch_bounds__(256) void skip_start_kernel(u32* ids, u64 count, u32 s) {
+  const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) ids[i] += ids[i] >= s ? 1u : 0u;
 }
 
 int pad_rows(const void* src, u64 nrows, u32 rb, void* dst, u64 stride, hipStream_t st) {
@@ -863,14 +905,7 @@ int ann_insert_points(ann_graph* g, const void* points_dev, uint64_t n_total, ui
     }
   } else {
     for (u64 i = 0; i < m; ++i) order[i] = (u32)(n_old + i);
-    u64 state = seed;
-    for (u64 i = m; i-- > 1;) {
-      const u64 r = splitmix64(state);
-      const u64 j = (u64)(((unsigned __int128)r * (unsigned __int128)(i + 1)) >> 64);
-      const u32 t = order[i];
-      order[i] = order[j];
-      order[j] = t;
-    }
+    shuffle_in_place(order.data(), m, seed);
   }
 
   // the schedule of the build carried on: a batch at most doubles what is there, theta caps it
@@ -940,23 +975,35 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
     return ts.tv_sec * 1e3 + ts.tv_nsec / 1e6;
   };
   const double t_begin = now_ms();
-  // Insertion order: the ids other than s, shuffled (Fisher-Yates driven by SplitMix64).  The
-  // shuffle moves positions, whatever they hold, so it runs on the positions 0..m-1 on a host
-  // thread while the graph is allocated and the GPU finds s; position j then stands for the j-th id other than s.
+  // Insertion order: the ids other than s, shuffled (Fisher-Yates from the front, driven by
+  // SplitMix64).  The shuffle moves positions, whatever they hold, so it runs on the positions
+  // 0..m-1 on a host thread (position j stands for the j-th id other than s) while the graph is
+  // allocated and the GPU finds s, and goes on while the first batches run: its first `ready`
+  // positions are final, and a batch waits only for its own.
   const u64 m = n ? n - 1 : 0;
   std::vector<u32> order(m && n < (1ull << 31) ? m : 1);
+  // Large inputs (the shuffle of 10^8 positions takes the host half a second): page-locked
+  // positions, handed to the device batch by batch while the shuffle goes on (from ordinary
+  // memory every such copy would wait for the batch before it).  Small inputs: the shuffle is
+  // over before the GPU has found s, page-locking would cost more than it saves, and the whole
+  // order goes to the device in one copy.
+  const bool stream_order = m >= (1ull << 23);
+  HostBuf pos_buf;
+  std::vector<u32> pos_vec;
+  std::atomic<u64> ready{0};
   std::thread shuffler;
+  u32* pos = nullptr;
   if (!o.order && n >= 1 && n < (1ull << 31)) {
-    shuffler = std::thread([&order, m, seed] {
-      for (u64 i = 0; i < m; ++i) order[i] = (u32)i;
-      u64 state = seed;
-      for (u64 i = m; i-- > 1;) {
-        const u64 r = splitmix64(state);
-        const u64 j = (u64)(((unsigned __int128)r * (unsigned __int128)(i + 1)) >> 64);
-        const u32 t = order[i];
-        order[i] = order[j];
-        order[j] = t;
-      }
+    if (stream_order) {
+      HIP_TRY(pos_buf.alloc(m * sizeof(u32)));
+      pos = pos_buf.as<u32>();
+    } else {
+      pos_vec.resize(m ? m : 1);
+      pos = pos_vec.data();
+    }
+    shuffler = std::thread([pos, &ready, m, seed] {
+      for (u64 i = 0; i < m; ++i) pos[i] = (u32)i;
+      shuffle_in_place(pos, m, seed, &ready);
     });
   }
   struct Joiner {
@@ -1028,14 +1075,32 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
       seen[id] = 1;
       order[i] = id;
     }
-  } else {
+  }
+  // ids of the positions [lo, hi) of the order, on the host and on the device (waits for the
+  // shuffle where it has not come that far yet)
+  u64 filled = o.order ? m : 0;
+  auto fill_order = [&](u64 hi) -> int {
+    if (hi <= filled) return ANN_OK;
+    while (ready.load(std::memory_order_acquire) < hi) std::this_thread::sleep_for(std::chrono::microseconds(20));
+    const u32 s = g->start;
+    for (u64 i = filled; i < hi; ++i) order[i] = pos[i] + (pos[i] >= s ? 1u : 0u);  // (the host's copy)
+    const u64 cnt = hi - filled;
+    HIP_TRY(hipMemcpyAsync(order_dev.as<u32>() + filled, pos + filled, cnt * 4, hipMemcpyHostToDevice, st));
+    hipLaunchKernelGGL(skip_start_kernel, dim3((u32)((cnt + 255) / 256)), dim3(256), 0, st, order_dev.as<u32>() + filled,
+                       cnt, s);
+    HIP_TRY(hipGetLastError());
+    filled = hi;
+    return ANN_OK;
+  };
+
+  if (!o.order && !stream_order) {
     shuffler.join();
     const u32 s = g->start;
-    for (u64 i = 0; i < m; ++i) order[i] += order[i] >= s ? 1u : 0u;
+    for (u64 i = 0; i < m; ++i) order[i] = pos[i] + (pos[i] >= s ? 1u : 0u);
+    filled = m;
   }
-
   const double t_order = now_ms();
-  if (m) HIP_TRY(hipMemcpyAsync(order_dev.p, order.data(), m * 4, hipMemcpyHostToDevice, st));
+  if (filled == m && m) HIP_TRY(hipMemcpyAsync(order_dev.p, order.data(), m * 4, hipMemcpyHostToDevice, st));
   const void* pts = nullptr;
   rc = resolve_points(g, points_dev, st, &pts);
   if (rc) return rc;
@@ -1050,6 +1115,8 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
     for (size_t r = 0; r + 1 < bounds.size(); ++r) {
       if (o.max_rounds && r >= o.max_rounds) break;
       const u64 lo = bounds[r], b = bounds[r + 1] - bounds[r];
+      rc = fill_order(bounds[r + 1]);
+      if (rc) return rc;
       rc = batch_insert(g, pts, order.data() + lo, order_dev.as<u32>() + lo, b, L, alpha, S, tm, st, sync);
       if (rc) return rc;
     }

@@ -3,6 +3,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -99,8 +100,27 @@ struct DevBuf {
   }
 };
 
+// Page-locked host memory: small copies to and from it are queued without a staging copy, and the
+// device reads it when the copy runs, so its contents must stay until then.
+struct HostBuf {
+  void* p = nullptr;
+  HostBuf() = default;
+  HostBuf(const HostBuf&) = delete;
+  HostBuf& operator=(const HostBuf&) = delete;
+  ~HostBuf() {
+    if (p) (void)hipHostFree(p);
+  }
+  hipError_t alloc(size_t bytes) { return hipHostMalloc(&p, bytes, hipHostMallocDefault); }
+  template <class T>
+  T* as() const {
+    return static_cast<T*>(p);
+  }
+};
+
 u64 default_spill_keys(u64 batch);
 u64 splitmix64(u64& state);
+// Fisher-Yates from the front, SplitMix64(seed); *ready follows the number of final positions
+void shuffle_in_place(u32* order, u64 m, u64 seed, std::atomic<u64>* ready = nullptr);
 
 struct BatchScratch;
 

@@ -1055,23 +1055,6 @@ struct Leaf {
 
 // Everything one group of trees needs on the device.  The trees of a group are cut side by side:
 // tree g of the group owns the positions g*n .. (g+1)*n of every array.
-// Page-locked host memory: small copies to and from it are queued without a staging copy, and the
-// device reads it when the copy runs, so its contents must stay until then.
-struct HostBuf {
-  void* p = nullptr;
-  HostBuf() = default;
-  HostBuf(const HostBuf&) = delete;
-  HostBuf& operator=(const HostBuf&) = delete;
-  ~HostBuf() {
-    if (p) (void)hipHostFree(p);
-  }
-  hipError_t alloc(size_t bytes) { return hipHostMalloc(&p, bytes, hipHostMallocDefault); }
-  template <class T>
-  T* as() const {
-    return static_cast<T*>(p);
-  }
-};
-
 struct HcCtx {
   u64 n = 0, N = 0;  // points; positions of a full group
   u32 G = 1;

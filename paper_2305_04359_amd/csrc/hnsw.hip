@@ -409,14 +409,7 @@ int ann_hnsw_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dty
     }
   } else {
     for (u64 i = 0; i < cnt; ++i) order[i] = (u32)i;
-    u64 state = seed;
-    for (u64 i = cnt; i-- > 1;) {
-      const u64 r = splitmix64(state);
-      const u64 j = (u64)(((unsigned __int128)r * (unsigned __int128)(i + 1)) >> 64);
-      const u32 t = order[i];
-      order[i] = order[j];
-      order[j] = t;
-    }
+    shuffle_in_place(order.data(), cnt, seed);
     for (u64 i = 0; i < cnt; ++i) order[i] += order[i] >= h->entry ? 1u : 0u;
   }
 
@@ -484,14 +477,7 @@ int ann_hnsw_insert_points(ann_hnsw* h, const void* points_dev, uint64_t n_total
     }
   } else {
     for (u64 i = 0; i < mnew; ++i) order[i] = (u32)(n_old + i);
-    u64 state = seed;
-    for (u64 i = mnew; i-- > 1;) {
-      const u64 r = splitmix64(state);
-      const u64 j = (u64)(((unsigned __int128)r * (unsigned __int128)(i + 1)) >> 64);
-      const u32 t = order[i];
-      order[i] = order[j];
-      order[j] = t;
-    }
+    shuffle_in_place(order.data(), mnew, seed);
   }
   // the build's schedule carried on
   u64 theta = o.batch_cap ? o.batch_cap : (n_total / 50 > 1 ? n_total / 50 : 1);

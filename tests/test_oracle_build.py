@@ -47,9 +47,9 @@ def test_insertion_order(oracle):
         got = oracle.insertion_order(n, start, seed)
         ids = [i for i in range(n) if i != start]
         st = seed
-        for i in range(len(ids) - 1, 0, -1):
+        for i in range(len(ids) - 1):  # Fisher-Yates from the front: position i is final after step i
             st, r = _splitmix64(st)
-            j = (r * (i + 1)) >> 64
+            j = i + ((r * (len(ids) - i)) >> 64)
             ids[i], ids[j] = ids[j], ids[i]
         assert got.tolist() == ids
         assert sorted(got.tolist()) == [i for i in range(n) if i != start]
@@ -245,9 +245,9 @@ def test_new_points_order(oracle):
         got = oracle.new_points_order(first, count, seed)
         ids = list(range(first, first + count))
         st = seed
-        for i in range(count - 1, 0, -1):
+        for i in range(count - 1):
             st, r = _splitmix64(st)
-            j = (r * (i + 1)) >> 64
+            j = i + ((r * (count - i)) >> 64)
             ids[i], ids[j] = ids[j], ids[i]
         assert got.tolist() == ids
     assert oracle.new_points_order(5, 0, 1).tolist() == []
