@@ -52,7 +52,7 @@ struct SearchArgs {
   u32 L;
   u32 k;
   u32* batch_counters;  // build only: the batch's counter words (overflow count [0], arena top [4..5], work
-                        // list lengths [8..10]); workgroup 0 zeroes them for the steps that follow
+                        // list lengths [8..11]); workgroup 0 zeroes them for the steps that follow
   // (1 + eps) rule of the search (Sec. 4.5): off when eps16 < 0; integer kinds use eps16 =
   // round(eps * 2^16), float kinds epsf
   long long eps16;
@@ -139,8 +139,11 @@ struct MergeArgs {
   u32 R;
   const u64* keys;  // sorted edge keys (dest << 32 | source)
   u64 nkeys;
-  u32* list_count;     // [3]: segments filed for the fast / gram / generic re-prune
-  MergeItem* list_items[3];
+  u32* list_count;     // [4]: segments filed for the fast / gram / large / medium re-prune
+  // the four work lists; the medium list shares the large one's array and grows down from its
+  // last element (item k at list_items[3][-k]): a segment is in one of the two
+  MergeItem* list_items[4];
+  u32 medium_max;      // candidate lists of up to this length go to the medium list (0: no such list)
   u32 fast_amax;       // most new entries the fast path takes
   u32 gram_ok;         // the matrix-core path applies to this dtype / row size
   u32 gram_tmax;       // and to at most this many candidates
@@ -158,6 +161,7 @@ struct MergeArgs {
 };
 
 constexpr u32 PRUNE_LDS_CAP = 512;     // candidate keys sorted in LDS by the step-1 prune kernel (a power of two)
+constexpr u32 MERGE_MEDIUM_MAX = 512;  // step-2 candidate lists up to this length have a kernel instance of their own
 constexpr u32 MERGE_SPILL_MIN = 4096;  // step-2 candidate lists longer than this go to the spill arena (a power of two)
 constexpr u32 STAGE_BUDGET = 10240;    // LDS bytes the prune kernels may spend on the selected points' vectors
 
@@ -167,7 +171,7 @@ hipError_t launch_descend(const DistCfg& cfg, const DescendArgs& a, hipStream_t 
 hipError_t launch_prune(const DistCfg& cfg, const PruneArgs& a, hipStream_t s);
 hipError_t launch_plan(const MergeArgs& a, hipStream_t s);
 hipError_t launch_merge(const DistCfg& cfg, const MergeArgs& a, u32 grid, hipStream_t s, hipStream_t s_gram,
-                        hipStream_t s_generic);
+                        hipStream_t s_generic, hipStream_t s_medium);
 hipError_t launch_meta_from_rows(const u32* graph, u64 n, u32 R, u32* meta, hipStream_t s);
 hipError_t launch_meta_forget_clean(u64 n, u32* meta, hipStream_t s);
 bool gram_path_ok(const DistCfg& cfg);

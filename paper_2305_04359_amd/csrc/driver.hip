@@ -435,9 +435,15 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   ma.nkeys = E;
   ma.list_count = small + 8;
   for (int c = 0; c < 3; ++c) ma.list_items[c] = S.lists.as<MergeItem>() + (u64)c * E;
+  ma.list_items[3] = ma.list_items[2] + (E - 1);  // grows down from the end of the large list's array
   ma.fast_amax = fast_path_amax(g->cfg);
   ma.gram_ok = gram_path_ok(g->cfg) ? 1u : 0u;
   ma.gram_tmax = gram_path_tmax();
+  // rows between the matrix-core kernel's reach and 512 candidates are many where that kernel
+  // does not apply (float rows, long rows) and in batches of millions of points: there they get
+  // a kernel instance of their own; elsewhere one more launch per batch would cost more than
+  // the few rows gain
+  ma.medium_max = (!ma.gram_ok || E >= (1ull << 22)) ? MERGE_MEDIUM_MAX : 0u;
   ma.stage_bytes = prune_stage_bytes(R, g->cfg);
   ma.use_mfma = mfma_prune_ok(R, g->cfg) ? 1u : 0u;
   ma.arena = S.arena.as<u64>();
@@ -453,14 +459,15 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   const u64 want = E < 8192 ? E : 8192;
   if (S.side[0] != nullptr) {
     HIP_TRY(hipEventRecord(S.ev_plan, st));
-    for (int i = 0; i < 2; ++i) HIP_TRY(hipStreamWaitEvent(S.side[i], S.ev_plan, 0));
-    HIP_TRY(launch_merge(g->cfg, ma, (u32)(want ? want : 1), st, S.side[0], S.side[1]));
-    for (int i = 0; i < 2; ++i) {
+    const int nside = ma.medium_max ? 3 : 2;
+    for (int i = 0; i < nside; ++i) HIP_TRY(hipStreamWaitEvent(S.side[i], S.ev_plan, 0));
+    HIP_TRY(launch_merge(g->cfg, ma, (u32)(want ? want : 1), st, S.side[0], S.side[1], S.side[2]));
+    for (int i = 0; i < nside; ++i) {
       HIP_TRY(hipEventRecord(S.ev_side[i], S.side[i]));
       HIP_TRY(hipStreamWaitEvent(st, S.ev_side[i], 0));
     }
   } else {
-    HIP_TRY(launch_merge(g->cfg, ma, (u32)(want ? want : 1), st, st, st));  // small batches: one stream
+    HIP_TRY(launch_merge(g->cfg, ma, (u32)(want ? want : 1), st, st, st, st));  // small batches: one stream
   }
   tm.mark(4, st);
   g->rounds += 1;

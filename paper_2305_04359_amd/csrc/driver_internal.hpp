@@ -170,10 +170,10 @@ struct BatchScratch {
   u64 spill_cap = 0;    // keys
   u32 spill_chunk = 0;  // extra keys a spilled list gets on top of vis_cap
   u64 arena_cap = 0;
-  // side streams (default priority) on which two of the three re-prune kernels run, and the
+  // side streams (default priority) on which three of the four re-prune kernels run, and the
   // events that order them against the caller's stream
-  hipStream_t side[2] = {nullptr, nullptr};
-  hipEvent_t ev_plan = nullptr, ev_side[2] = {nullptr, nullptr};
+  hipStream_t side[3] = {nullptr, nullptr, nullptr};
+  hipEvent_t ev_plan = nullptr, ev_side[3] = {nullptr, nullptr, nullptr};
   u32* host_flag = nullptr;  // pinned: where the host reads the overflow count of a batch
   ~BatchScratch() {
     if (host_flag) (void)hipHostFree(host_flag);
@@ -185,7 +185,7 @@ struct BatchScratch {
   }
   // small: [0] overflow_count u32, [2] arena error flag, [3] "a visited list was lost" flag,
   // [4..5] arena_top u64, [6..7] spill_top u64, [8..10] work list counts
-  // with_side = false: the three re-prune kernels share the caller's stream (small batches)
+  // with_side = false: the re-prune kernels share the caller's stream (small batches)
   int alloc(u64 b, u32 R, u32 cap, u64 spill_keys, bool with_side = true) {
     bmax = b;
     vis_cap = cap;

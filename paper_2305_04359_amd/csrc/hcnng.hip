@@ -1574,6 +1574,7 @@ int ann_hcnng_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dt
   u32* sm = small.as<u32>();
   ma.list_count = sm + 8;
   for (int c = 0; c < 3; ++c) ma.list_items[c] = lists.as<MergeItem>() + (u64)c * n;
+  ma.list_items[3] = ma.list_items[2] + (n - 1);  // (not filled here: every list is pruned by the large instance)
   ma.fast_amax = fast_path_amax(g->cfg);
   ma.gram_ok = gram_path_ok(g->cfg) ? 1u : 0u;
   ma.gram_tmax = gram_path_tmax();
@@ -1590,7 +1591,7 @@ int ann_hcnng_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dt
   g->clean_alpha = alpha;
   HIP_TRY(launch_plan(ma, st));
   const u64 want = nuniq < 8192 ? nuniq : 8192;
-  HIP_TRY(launch_merge(g->cfg, ma, (u32)(want ? want : 1), st, st, st));
+  HIP_TRY(launch_merge(g->cfg, ma, (u32)(want ? want : 1), st, st, st, st));
   u32 flags[4] = {0, 0, 0, 0};
   HIP_TRY(hipMemcpyAsync(flags, small.p, 16, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));

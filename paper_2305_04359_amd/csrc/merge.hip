@@ -34,15 +34,15 @@ __device__ __forceinline__ u32 make_meta(u32 deg, u32 clean) { return deg | (cle
 // planning: one thread per edge key; the first key of each segment does the work
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void plan_kernel(MergeArgs a) {
-  __shared__ u32 cnt_lds[3];
-  __shared__ u32 base_lds[3];
+  __shared__ u32 cnt_lds[4];
+  __shared__ u32 base_lds[4];
   __shared__ u32 stat_lds[2];  // appends, appended edges
-  if (threadIdx.x < 3) cnt_lds[threadIdx.x] = 0;
+  if (threadIdx.x < 4) cnt_lds[threadIdx.x] = 0;
   if (threadIdx.x < 2) stat_lds[threadIdx.x] = 0;
   __syncthreads();
 
   const u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
-  int kind = -1;  // 0 fast, 1 gram, 2 generic
+  int kind = -1;  // 0 fast, 1 gram, 2 generic with a long candidate list, 3 generic with a list of up to 512
   u32 slot = 0, cnt = 0, b = 0, m = 0;
   if (i < a.nkeys) {
     b = (u32)(a.keys[i] >> 32);
@@ -83,6 +83,7 @@ __global__ __launch_bounds__(256) void plan_kernel(MergeArgs a) {
           kind = 1;
         else
           kind = 2;
+        if (kind == 2 && deg + cnt <= a.medium_max) kind = 3;
         slot = atomicAdd(&cnt_lds[kind], 1u);
       }
     }
@@ -90,14 +91,17 @@ __global__ __launch_bounds__(256) void plan_kernel(MergeArgs a) {
   __syncthreads();
   // one global atomic per work list and workgroup; the order of a list has no influence on any
   // result, every segment is processed on its own
-  if (threadIdx.x < 3 && cnt_lds[threadIdx.x] != 0)
+  if (threadIdx.x < 4 && cnt_lds[threadIdx.x] != 0)
     base_lds[threadIdx.x] = atomicAdd(&a.list_count[threadIdx.x], cnt_lds[threadIdx.x]);
   if (a.counters != nullptr && threadIdx.x == 0 && stat_lds[0] != 0) {
     atomicAdd(&block_counters(a.counters)->appends, (unsigned long long)stat_lds[0]);
     atomicAdd(&block_counters(a.counters)->edges, (unsigned long long)stat_lds[1]);
   }
   __syncthreads();
-  if (kind >= 0) a.list_items[kind][base_lds[kind] + slot] = MergeItem{(u32)i, cnt, b, m};
+  if (kind >= 0) {
+    const long long at = (long long)(base_lds[kind] + slot);
+    a.list_items[kind][kind == 3 ? -at : at] = MergeItem{(u32)i, cnt, b, m};
+  }
 }
 
 hipError_t launch_plan(const MergeArgs& a, hipStream_t s) {
@@ -802,9 +806,14 @@ __global__ __launch_bounds__(64) void merge_gram_kernel(MergeArgs a, VecTable T)
 // ---------------------------------------------------------------------------------------------
 // generic path kernel
 // ---------------------------------------------------------------------------------------------
-template <int KIND, int VEC, int NCH>
+// CAP: candidate keys the kernel sorts in LDS.  Two instances: MERGE_SPILL_MIN for the few rows
+// with long lists (hub vertices; beyond it the list goes to the arena), and MERGE_MEDIUM_MAX for
+// the rows in between, which are many when batches hold millions of points: with the large
+// buffer three waves fit a compute unit, with the small one sixteen.
+template <int KIND, int VEC, int NCH, u32 CAP>
 __global__ __launch_bounds__(64) void merge_generic_kernel(MergeArgs a, VecTable T) {
-  __shared__ u64 cand_lds[MERGE_SPILL_MIN];
+  constexpr int LIST = CAP == MERGE_SPILL_MIN ? 2 : 3;
+  __shared__ u64 cand_lds[CAP];
   extern __shared__ __align__(16) unsigned char smem[];
   u32* out = reinterpret_cast<u32*>(smem);  // R entries
   SelStage st;
@@ -816,13 +825,13 @@ __global__ __launch_bounds__(64) void merge_generic_kernel(MergeArgs a, VecTable
   const MfmaLds M = mfma_lds_carve(smem + ((a.R * 4u + 15u) & ~15u), a.R, T.row_bytes);  // used when a.use_mfma
 
   const int lane = threadIdx.x;
-  const u32 nitems = a.list_count[2];
+  const u32 nitems = a.list_count[LIST];
   if (blockIdx.x >= nitems) return;
   const AlphaParam al{a.a16, a.af};
   unsigned long long n_rep = 0, n_edges = 0, n_pair = 0;
 
   for (u32 it = blockIdx.x; it < nitems; it += gridDim.x) {
-    const MergeItem item = a.list_items[2][it];
+    const MergeItem item = a.list_items[LIST][LIST == 3 ? -(long long)it : (long long)it];
     const u32 i0 = item.i0, cnt = item.cnt, b = item.b;
     const u32 deg = meta_deg(item.meta);
     const u32 total = deg + cnt;
@@ -830,7 +839,7 @@ __global__ __launch_bounds__(64) void merge_generic_kernel(MergeArgs a, VecTable
 
     // candidate list U = N_out(b) followed by the new sources
     u64* cand;
-    const bool in_lds = total <= MERGE_SPILL_MIN;
+    const bool in_lds = total <= CAP;
     if (in_lds) {
       cand = cand_lds;
     } else {
@@ -904,13 +913,17 @@ __global__ __launch_bounds__(64) void merge_generic_kernel(MergeArgs a, VecTable
 // side streams the caller has already made wait for the planning kernel.
 template <int KIND, int VEC, int NCH>
 static hipError_t launch_merge_t(const MergeArgs& a, const VecTable& T, u32 grid, hipStream_t s, hipStream_t s_gram,
-                                 hipStream_t s_generic) {
+                                 hipStream_t s_generic, hipStream_t s_medium) {
   // the generic kernel's few, long items first, so that they start at once instead of waiting
   // for LDS that the other two kernels' workgroups hold; a small grid serves its short list
   const u32 lds = a.use_mfma ? ((a.R * 4u + 15u) & ~15u) + mfma_lds_bytes(a.R, T.row_bytes)
                             : ((a.R * 8u + 15u) & ~15u) + 8u * stage_stride(T.row_bytes) + 32u + a.stage_bytes;
   const u32 grid_generic = (grid < 1024u || a.force_prune) ? grid : 1024u;
-  hipLaunchKernelGGL((merge_generic_kernel<KIND, VEC, NCH>), dim3(grid_generic), dim3(64), lds, s_generic, a, T);
+  hipLaunchKernelGGL((merge_generic_kernel<KIND, VEC, NCH, MERGE_SPILL_MIN>), dim3(grid_generic), dim3(64), lds,
+                     s_generic, a, T);
+  if (a.medium_max)
+    hipLaunchKernelGGL((merge_generic_kernel<KIND, VEC, NCH, MERGE_MEDIUM_MAX>), dim3(grid), dim3(64), lds, s_medium, a,
+                       T);
   // the caller's stream takes the kernel that usually ends last, so that its waits for the other
   // two streams are already satisfied when it reaches them
   if (a.gram_ok) {
@@ -923,10 +936,10 @@ static hipError_t launch_merge_t(const MergeArgs& a, const VecTable& T, u32 grid
 }
 
 hipError_t launch_merge(const DistCfg& cfg, const MergeArgs& a, u32 grid, hipStream_t s, hipStream_t s_gram,
-                        hipStream_t s_generic) {
+                        hipStream_t s_generic, hipStream_t s_medium) {
   if (grid == 0) return hipSuccess;
   VecTable T{a.points, (u32)cfg.row_bytes, cfg.npieces};
-  ANN_DISPATCH_CFG(launch_merge_t, a, T, grid, s, s_gram, s_generic);
+  ANN_DISPATCH_CFG(launch_merge_t, a, T, grid, s, s_gram, s_generic, s_medium);
 }
 
 bool gram_path_ok(const DistCfg& cfg) { return cfg.kind <= 1 && 8 * cfg.nch * cfg.vec <= 128; }

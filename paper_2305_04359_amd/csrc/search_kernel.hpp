@@ -85,6 +85,7 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
     a.batch_counters[8] = 0;
     a.batch_counters[9] = 0;
     a.batch_counters[10] = 0;
+    a.batch_counters[11] = 0;
   }
 
   u64 A[NSLOT];

@@ -264,3 +264,23 @@ def test_hcnng_leaf_neighbours_one_by_one(env, kind):
     share = same_lists / n
     say(f"  {kind}: {len(off) - 1} leaves, lists identical to the exact ones: {share:.4f}")
     assert share == 1.0 if pts_h.dtype == np.uint8 else share >= 0.97
+
+
+def test_build_with_a_batch_of_a_hundred_thousand_points(env, capsys):
+    """Batches of 65,536 and 68,929 points (4.2 and 4.4 million reverse edges): the size at which
+    rows with 97 to 512 candidates get a re-prune kernel instance of their own, next to the one
+    for hub rows with thousands.  Every row against the oracle."""
+    torch, A, O = env
+    w = W.c1(n=200_000, nq=10)
+    R, L, alpha, cap = 64, 64, 1.2, 140_000
+    ds = O.Dataset(w.points, 0)
+    og, s = O.build(ds, R, L, alpha, seed=3, theta=cap, threads=0)
+    g = A.ann_build(dev(torch, w.points), R, L, alpha, seed=3, batch_cap=cap, collect_stats=True)
+    st = g.stats()
+    assert g.info().start == s and int(g.info().rounds) == 17
+    rows = g.neighbors()
+    bad = np.nonzero((rows != og).any(1))[0]
+    assert len(bad) == 0, f"{len(bad)} rows differ, first {bad[:10]}"
+    with capsys.disabled():
+        print(f"\n  [one batch of {cap} points: {st['reprunes']} re-prunes, {st['appends']} appends, graph identical]",
+              flush=True)
