@@ -247,7 +247,13 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
         const u32 rank = __builtin_popcountll(fm & lanemask_lt(lane));
         if (fresh) cid[rank] = x;
         __syncthreads();
-        const u32 dk = eval_up_to_64_full_rows<KIND, VEC, NCH>(T, Q, [cid](u32 c) { return cid[c]; }, m, lane);
+        // (the variants with start vertices of their own sit at the register count that eight
+        // waves per SIMD allow: the second code path of the full-row passes would cost them a wave)
+        u32 dk;
+        if constexpr (OWN)
+          dk = eval_up_to_64<KIND, VEC, NCH>(T, Q, [cid](u32 c) { return cid[c]; }, m, lane);
+        else
+          dk = eval_up_to_64_full_rows<KIND, VEC, NCH>(T, Q, [cid](u32 c) { return cid[c]; }, m, lane);
         const u32 c = cand_of_lane(lane);
         u64 mykey = c < m ? make_key(dk, cid[c]) : KEY_INF;
         __syncthreads();
