@@ -460,6 +460,10 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   if (S.side[0] != nullptr) {
     HIP_TRY(hipEventRecord(S.ev_plan, st));
     const int nside = ma.medium_max ? 3 : 2;
+    if (nside == 3) {
+      const int rc_side = S.medium_stream();
+      if (rc_side) return rc_side;
+    }
     for (int i = 0; i < nside; ++i) HIP_TRY(hipStreamWaitEvent(S.side[i], S.ev_plan, 0));
     HIP_TRY(launch_merge(g->cfg, ma, (u32)(want ? want : 1), st, S.side[0], S.side[1], S.side[2]));
     for (int i = 0; i < nside; ++i) {

@@ -209,10 +209,19 @@ struct BatchScratch {
     HIP_TRY(vis_where.alloc(b * 8));
     HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&host_flag), 64, hipHostMallocDefault));
     if (with_side) {
-      for (auto& s : side) HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+      // the third stream is made when a batch first needs it (medium_stream): a process has few
+      // hardware queues, and a stream nobody uses still takes its turn on one of them
+      for (int i = 0; i < 2; ++i) HIP_TRY(hipStreamCreateWithFlags(&side[i], hipStreamNonBlocking));
       HIP_TRY(hipEventCreateWithFlags(&ev_plan, hipEventDisableTiming));
-      for (auto& e : ev_side) HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+      for (int i = 0; i < 2; ++i) HIP_TRY(hipEventCreateWithFlags(&ev_side[i], hipEventDisableTiming));
     }
+    return ANN_OK;
+  }
+  // The stream of the medium re-prune instance, made on first use.
+  int medium_stream() {
+    if (side[2] != nullptr) return ANN_OK;
+    HIP_TRY(hipStreamCreateWithFlags(&side[2], hipStreamNonBlocking));
+    HIP_TRY(hipEventCreateWithFlags(&ev_side[2], hipEventDisableTiming));
     return ANN_OK;
   }
 };
