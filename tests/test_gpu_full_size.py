@@ -1,9 +1,11 @@
-"""GPU parity at the benchmark's sizes (10^6 points), in the launch configuration bench.py times.
+"""GPU parity at the benchmark's sizes (10^6 and 10^8 points), in the launch configuration
+bench.py times.
 
 C2 (the benchmark workload): the oracle builds the WHOLE graph, batch by batch on all host
 threads, and every row, the start vertex and all 10,000 queries are compared bit for bit.
 C3 (int8, padded rows) and C4 (float, inner product): the last batch is sampled, as the oracle's
-full build of those would not fit the time a test may take.
+full build of those would not fit the time a test may take.  C5 (10^8 points): likewise a sample
+of the last batch, compared over all 10^8 rows.
 """
 import time
 
@@ -131,3 +133,56 @@ def test_c4_full_size_sampled_against_oracle(env):
     say(f"  C4 at full size, L=50: recall gpu={r_g:.4f} oracle={r_o:.4f}; same ids {np.mean(ids == oi):.5f}")
     assert abs(r_g - r_o) <= 0.002
     assert (ids == oi).mean() >= 0.99
+
+
+def test_c5_full_size_sampled_against_oracle(env, capsys):
+    """10^8 x 128 uint8, the largest configuration: ids of 27 bits (21-bit filter tags, row
+    offsets beyond 32 bits), batches of two million points.  The oracle cannot build this graph
+    in a test's time, so a GPU build is stopped one batch early and both sides insert the same
+    3,000 points of the last batch into it: all 10^8 rows and the queries are compared bit for
+    bit.  About a minute; 64 GB of host memory (two copies of the graph and the points)."""
+    import psutil
+    torch, A, O = env
+    if psutil.virtual_memory().available < 100 * 2**30:
+        pytest.skip("needs about 64 GB of free host memory")
+    if torch.cuda.mem_get_info()[0] < 80 * 2**30:
+        pytest.skip("needs about 60 GB of free device memory")
+
+    def note(msg):
+        with capsys.disabled():
+            print(f"\n  [C5: {msg}, {time.time() - t0:.0f} s]", end="", flush=True)
+
+    t0 = time.time()
+    w = W.c5(nq=300)
+    note("points drawn")
+    pts = dev(torch, w.points)
+    ds = O.Dataset(w.points, 0)
+    bounds = O.schedule(w.n - 1, w.theta).astype(np.int64)
+    rounds = len(bounds) - 1
+    snap = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, max_rounds=rounds - 1)
+    assert int(snap.info().rounds) == rounds - 1
+    note(f"GPU build stopped after {rounds - 1} of {rounds} batches")
+    s = int(snap.info().start)
+    assert s == O.start_vertex(ds)
+    order = O.insertion_order(w.n, s, w.seed)
+    batch = order[bounds[rounds - 1]:bounds[rounds]][:3000]
+    og = snap.neighbors()
+    ost = O.Stats()
+    O.batch_insert(ds, og, s, batch, w.L, w.alpha, threads=0, stats=ost)
+    assert ost.searches == len(batch) and ost.reprunes + ost.appends > len(batch)
+    note(f"oracle inserted {len(batch)} points into the {int(bounds[rounds - 1]) + 1}-point graph")
+    A.ann_insert_batch(snap, pts, batch, w.L, w.alpha)
+    gg = snap.neighbors()
+    bad, step = [], 1 << 22
+    for i in range(0, w.n, step):
+        bad.extend((i + np.nonzero((gg[i:i + step] != og[i:i + step]).any(1))[0]).tolist())
+    assert not bad, f"{len(bad)} rows differ from the oracle's, first {bad[:10]}"
+    del gg
+    note("all rows identical")
+    qs = dev(torch, w.queries)
+    for L in (10, 128, 700):
+        ids, dists = A.ann_search(snap, pts, qs, 10, L)
+        oi, od = O.search_batch(ds, og, s, w.queries, 10, L, threads=0)
+        assert (ids.cpu().numpy().view(np.uint32) == oi).all(), f"query ids differ at L={L}"
+        assert (dists.cpu().numpy().view(np.int32) == od.view(np.int32)).all(), f"query distances differ at L={L}"
+    note("queries identical at beams of 10, 128 and 700")
