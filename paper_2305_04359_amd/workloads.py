@@ -146,7 +146,7 @@ def c2(n=1_000_000, nq=10_000):
     return Workload("C2", gaussian_mixture_u8(n, 128, cen, 12.0, DATA_SEED, 0),
                     gaussian_mixture_u8(nq, 128, cen, 12.0, QUERY_SEED, 1), L2SQ,
                     R=64, L=128, alpha=1.2,
-                    search_L=(10, 11, 12, 13, 14, 15, 20, 30, 40, 50, 60, 80, 100, 120, 150, 200),
+                    search_L=(10, 11, 12, 13, 14, 15, 16, 18, 20, 30, 40, 50, 60, 80, 100, 120, 150, 200),
                     note="stand-in for BIGANN-1M (128-d uint8, L2)")
 
 
