@@ -277,21 +277,17 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
             // many survivors: each finds its rank among the beam entries by bisection in the LDS
             // copy of the beam; a survivor that is already in the beam (the filter lost it) sits
             // exactly at its rank there and is dropped
-            // positions 0..size are possible answers: ceil(log2(64 * NSLOT + 1)) halvings
-            constexpr int STEPS = (NSLOT == 1 ? 7 : NSLOT == 2 ? 8 : NSLOT == 4 ? 9 : NSLOT == 8 ? 10 : NSLOT == 16 ? 11 : 12);
+            // the rank is at most 64 * NSLOT - 1 (a survivor lies below the last entry of a full
+            // beam): one step per bit of it, each keeping the bit if that many entries lie below
+            // the key; entries past `size` are never counted (the read stays inside the array)
+            constexpr int BITS = (NSLOT == 1 ? 6 : NSLOT == 2 ? 7 : NSLOT == 4 ? 8 : NSLOT == 8 ? 9 : NSLOT == 16 ? 10 : 11);
             const u64 sk1 = mykey | 1ull;
-            u32 lo = 0, hi = size;
+            u32 lo = 0;
 #pragma unroll
-            for (int it = 0; it < STEPS; ++it) {
-              const u32 mid = (lo + hi) >> 1;
-              const bool open = lo < hi;
-              const u64 v = beam[open ? mid : 0u] | 1ull;
-              if (open) {
-                if (v < sk1)
-                  lo = mid + 1;
-                else
-                  hi = mid;
-              }
+            for (int bit = BITS - 1; bit >= 0; --bit) {
+              const u32 t = lo + (1u << bit);
+              const u64 v = beam[t - 1u] | 1ull;
+              lo = (t <= size && v < sk1) ? t : lo;
             }
             myrA = lo;
             if (surv && lo < size && (beam[lo] | 1ull) == sk1) surv = false;
@@ -300,9 +296,10 @@ __global__ __launch_bounds__(64) void search_kernel(SearchArgs a, VecTable T) {
             if (surv) skeys[__builtin_popcountll(sm & lanemask_lt(lane))] = mykey;
             __syncthreads();
             // ranks among the survivors, and how far each beam entry moves
+            // (a lane without a survivor counts too: its sum is never read)
             for (u32 j = 0; j < ns; ++j) {
               const u64 sj = skeys[j];
-              myrB += (surv && sj < mykey) ? 1u : 0u;
+              myrB += (sj < mykey) ? 1u : 0u;
 #pragma unroll
               for (int s = 0; s < NSLOT; ++s) shift[s] += (sj < A[s]) ? 1u : 0u;
             }
