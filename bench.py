@@ -193,8 +193,16 @@ def query_point(torch, A, O, w, g_stats, pts, qs, qs_stream, k, setting, gt, kth
                              "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                              "hops_per_query": round(hops, 2), "evals_per_query": round(evals, 2),
                              "distinct_eval_fraction": round(distinct, 4), "bytes_per_query": int(per_query),
-                             "launch_ms": round(ms_s, 4)}
+                             "launch_ms": round(ms_s, 4), **working_set(w)}
     return out
+
+
+def working_set(w):
+    """Bytes the searches draw from (vectors and adjacency rows), and whether the chip's last-level
+    cache (256 MB) can hold a large part of them: then bytes per second against the HBM peak says
+    how fast the kernel gathers, not how close it is to the memory's limit."""
+    ws = w.n * w.d * w.points.dtype.itemsize + w.n * w.R * 4
+    return {"working_set_bytes": int(ws), "cache_assisted": bool(ws < 1 << 30)}
 
 
 def build_roofline(st, w, distinct_frac, traffic):
@@ -214,6 +222,7 @@ def build_roofline(st, w, distinct_frac, traffic):
         "bytes_per_launch": int(srch_bytes / max(1, st["rounds"])),
         "distinct_eval_fraction": round(distinct_frac, 4),
         "evals_counted": "distinct (repeats of the lossy visited filter excluded)",
+        **working_set(w),
     }
 
 
