@@ -457,7 +457,8 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   // grid-stride kernels over work lists whose lengths stay on the device: enough waves to fill
   // the chip, no more (idle workgroups are not free)
   const u64 want = E < 8192 ? E : 8192;
-  if (S.side[0] != nullptr) {
+  // (a small batch's kernels are over before a wait between streams has been served)
+  if (S.side[0] != nullptr && b >= 2048) {
     HIP_TRY(hipEventRecord(S.ev_plan, st));
     const int nside = ma.medium_max ? 3 : 2;
     if (nside == 3) {
