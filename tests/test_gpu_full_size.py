@@ -140,7 +140,9 @@ def test_c5_full_size_sampled_against_oracle(env, capsys):
     offsets beyond 32 bits), batches of two million points.  The oracle cannot build this graph
     in a test's time, so a GPU build is stopped one batch early and both sides insert the same
     3,000 points of the last batch into it: all 10^8 rows and the queries are compared bit for
-    bit.  About a minute; 64 GB of host memory (two copies of the graph and the points)."""
+    bit.  The build is also run twice (same bytes) and every inserted point must have a
+    neighbour.  About a minute and a half; 64 GB of host memory (two copies of the graph and the
+    points)."""
     import psutil
     torch, A, O = env
     if psutil.virtual_memory().available < 100 * 2**30:
@@ -167,13 +169,27 @@ def test_c5_full_size_sampled_against_oracle(env, capsys):
     order = O.insertion_order(w.n, s, w.seed)
     batch = order[bounds[rounds - 1]:bounds[rounds]][:3000]
     og = snap.neighbors()
+    # the same build again gives the same bytes; every point inserted so far has a neighbour
+    again = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, max_rounds=rounds - 1)
+    rows2 = again.neighbors()
+    del again
+    inserted = np.zeros(w.n, bool)
+    inserted[order[:bounds[rounds - 1]]] = True
+    step = 1 << 22
+    for i in range(0, w.n, step):
+        a = og[i:i + step]
+        assert (a == rows2[i:i + step]).all(), "two builds of the same input differ"
+        has = (a != NONE).any(1)
+        assert has[inserted[i:i + step]].all(), "an inserted point has no neighbour"
+    del rows2, inserted
+    note("a second build gives the same graph; every inserted point has a neighbour")
     ost = O.Stats()
     O.batch_insert(ds, og, s, batch, w.L, w.alpha, threads=0, stats=ost)
     assert ost.searches == len(batch) and ost.reprunes + ost.appends > len(batch)
     note(f"oracle inserted {len(batch)} points into the {int(bounds[rounds - 1]) + 1}-point graph")
     A.ann_insert_batch(snap, pts, batch, w.L, w.alpha)
     gg = snap.neighbors()
-    bad, step = [], 1 << 22
+    bad = []
     for i in range(0, w.n, step):
         bad.extend((i + np.nonzero((gg[i:i + step] != og[i:i + step]).any(1))[0]).tolist())
     assert not bad, f"{len(bad)} rows differ from the oracle's, first {bad[:10]}"
