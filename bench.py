@@ -226,6 +226,31 @@ def build_roofline(st, w, distinct_frac, traffic):
     }
 
 
+def other_phases(st, w):
+    """Algorithmic bytes per second of the build's other phases, from the library's counters and
+    phase times (all against the HBM peak; none of them is the dominant kernel).
+    prune (step 1): the vectors of V are gathered once (|V| = hops), V is written by the search and
+    read here (2 x 8 B per entry), the new row is written.  sort: every pass reads and writes the
+    8-byte keys.  merge (step 2): a touched row is read and written; a re-pruned row's old entries
+    and its new sources are gathered (R vectors + one per new edge: an upper bound, rows are not
+    always full and appended edges need no vector)."""
+    row_bytes = w.d * w.points.dtype.itemsize
+    passes = (int(w.n).bit_length() + 9) // 10  # ten key bits per pass over the destination's bits
+    b = {
+        "prune": st["hops"] * (row_bytes + 16) + st["prunes"] * 4 * w.R,
+        "sort": passes * 2 * 8 * st["edges"],
+        "merge": (st["reprunes"] + st["appends"]) * 2 * 4 * w.R + (st["reprunes"] * w.R + st["edges"]) * row_bytes,
+    }
+    out = {}
+    for k, v in b.items():
+        sec = st["ms_" + k] / 1e3
+        gbs = v / sec / 1e9 if sec > 0 else 0.0
+        out[k] = {"algorithmic_bytes": int(v), "ms": round(st["ms_" + k], 2), "achieved": round(gbs, 1), "unit": "GB/s",
+                  "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+    out["sort"]["passes"] = passes
+    return out
+
+
 def measured_traffic(workload):
     """HBM bytes per launch of the search kernel from the committed rocprofv3 --pmc summary
     (FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size), or None."""
@@ -403,6 +428,7 @@ def measure_c5(torch, A, W, args, say):
         "build_phase_ms": {kk: round(st[kk], 1) for kk in ("ms_search", "ms_prune", "ms_sort", "ms_merge", "ms_total")},
         "counters_cover": counted,
         "roofline": build_roofline(st, w, distinct, measured_traffic("C5")),
+        "other_phases": other_phases(st, w),
         "qps_at_recall_0.90": points[0.90], "qps_at_recall_0.95": points[0.95],
         "highest_recall_in_sweep": highest_recall(sweep),
         "recall_measured_on": f"the first {gt_rows} queries (exact neighbours by exhaustive search)",
@@ -631,6 +657,7 @@ def main():
                                                       "insert_hops")},
         "build_phase_ms": {kk: round(st[kk], 2) for kk in ("ms_search", "ms_prune", "ms_sort", "ms_merge", "ms_total")},
         "roofline": build_roofline(st, w, distinct_frac, measured_traffic(w.name)),
+        "other_phases": other_phases(st, w),
         "datagen_s": round(t_gen, 1),
     }
     if cpu is not None:
