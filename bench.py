@@ -202,7 +202,7 @@ def working_set(w):
     cache (256 MB) can hold a large part of them: then bytes per second against the HBM peak says
     how fast the kernel gathers, not how close it is to the memory's limit."""
     ws = w.n * w.d * w.points.dtype.itemsize + w.n * w.R * 4
-    return {"working_set_bytes": int(ws), "cache_assisted": bool(ws < 1 << 30)}
+    return {"working_set_bytes": int(ws), "cache_assisted": bool(ws < 2 * (256 << 20))}
 
 
 def build_roofline(st, w, distinct_frac, traffic, distinct_known=True):
