@@ -129,7 +129,13 @@ typedef struct {
   uint64_t passes;      /* searches: 8-vertex distance passes                    */
   uint64_t survivors;   /* searches: candidates inserted into a beam             */
   uint64_t insert_hops; /* searches: hops that inserted at least one candidate   */
-  double ms_search, ms_prune, ms_sort, ms_merge, ms_total; /* device time per phase */
+  /* device time per phase.  A batch of 8,192 points or more runs step 1 in three parts side by
+   * side (a part that is through its searches prunes while the others still search):
+   * ms_search lasts from a batch's start until the last of its searches is over, ms_prune from
+   * then until its last prune is over.                                                      */
+  double ms_search, ms_prune, ms_sort, ms_merge, ms_total;
+  uint64_t search_launches;  /* launches of the search kernel in batches (with statistics on) */
+  double ms_search_launches; /* their durations added up; launches of one batch overlap      */
 } ann_stats;
 
 /*

@@ -50,7 +50,8 @@ class Stats(C.Structure):
     _fields_ = [(k, C.c_uint64) for k in ("searches", "hops", "evals", "prunes", "reprunes", "appends",
                                            "edges", "prune_evals", "redone", "restarts", "rounds", "passes", "survivors",
                                            "insert_hops")] + \
-               [(k, C.c_double) for k in ("ms_search", "ms_prune", "ms_sort", "ms_merge", "ms_total")]
+               [(k, C.c_double) for k in ("ms_search", "ms_prune", "ms_sort", "ms_merge", "ms_total")] + \
+               [("search_launches", C.c_uint64), ("ms_search_launches", C.c_double)]
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}

@@ -228,7 +228,12 @@ struct BatchScratch {
 
 // HIP events around the phases of every batch, read when the batches have finished.
 struct PhaseTimer {
-  std::vector<hipEvent_t> ev;  // 5 per batch
+  // per batch: 0 start, 1 the caller's stream is through its searches, 2 every prune is over,
+  // 3 sorted, 4 merged, 5 and 6 the side streams are through their searches (a batch whose
+  // searches run in parts, see batch_insert; otherwise recorded with 1)
+  static constexpr int PER_BATCH = 7;
+  std::vector<hipEvent_t> ev;
+  std::vector<int> parts;  // per batch: search launches (1 or 3)
   bool on = false;
   size_t cur = 0;  // batch being recorded
   int init(bool enable) {
@@ -237,8 +242,9 @@ struct PhaseTimer {
   }
   int begin_batch() {
     if (!on) return ANN_OK;
-    cur = ev.size() / 5;
-    for (int i = 0; i < 5; ++i) {
+    cur = ev.size() / PER_BATCH;
+    parts.push_back(1);
+    for (int i = 0; i < PER_BATCH; ++i) {
       hipEvent_t e;
       HIP_TRY(hipEventCreate(&e));
       ev.push_back(e);
@@ -246,11 +252,15 @@ struct PhaseTimer {
     return ANN_OK;
   }
   void mark(int i, hipStream_t s) {
-    if (on) (void)hipEventRecord(ev[cur * 5 + i], s);
+    if (on) (void)hipEventRecord(ev[cur * PER_BATCH + i], s);
+  }
+  void set_parts(int n) {
+    if (on) parts[cur] = n;
   }
   void clear() {
     for (auto& e : ev) (void)hipEventDestroy(e);
     ev.clear();
+    parts.clear();
   }
   ~PhaseTimer() { clear(); }
 };
