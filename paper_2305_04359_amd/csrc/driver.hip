@@ -338,12 +338,15 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   // A batch of many points runs step 1 in parts, each on a stream of its own (the caller's and
   // the side streams, idle until step 2): a part that is through its searches prunes while the
   // others still search, which fills the end of the search phase, when the chip runs empty
-  // (C2 build 83.7 -> 81.7 ms, C5 19.85 -> 19.40 s with three parts; two parts gain half of
-  // that; parts one after the other on one stream lose 12 ms at C2, each paying the tail).
+  // (C2 build 83.7 -> 81.5 ms, C5 19.85 -> 19.40 s with three parts; two parts gain less;
+  // parts one after the other on one stream lose 12 ms at C2, each paying the tail).
   // Not for the synchronised attempt, whose host check reads one overflow list for the batch.
   const int nparts = (!sync && S.side[0] != nullptr && b >= STEP1_PARTS_MIN) ? 3 : 1;
   u64 cut[4] = {0, b, b, b};
-  for (int c = 1; c < nparts; ++c) cut[c] = b * (u64)c / (u64)nparts;
+  if (nparts == 3) {  // a half for the caller's stream, then 30 % and 20 % (measured against other splits)
+    cut[1] = b / 2;
+    cut[2] = b * 4 / 5;
+  }
   auto part_stream = [&](int c) { return c ? S.side[c - 1] : st; };
   if (nparts > 1) {
     HIP_TRY(hipEventRecord(S.ev_plan, st));
