@@ -11,6 +11,7 @@ the cpu_baseline objects time the CPU oracle on a bounded sample of the same wor
 
 Modes for profilers (everything after `--` of a rocprofv3 command is this file itself):
   --only-build            inputs, warm-up builds, `--steps` builds, nothing else
+  --one-part              (with the above, for counter passes) step 1 of a batch as one launch
   --only-build --search-L 15 [--search-eps E] [--search-nq N]
                           ... followed by query launches at that beam width
   --copy-probe MIB        a plain device copy of known size: the calibration of the
@@ -223,6 +224,7 @@ def build_roofline(st, w, distinct_frac, traffic, distinct_known=True):
         "bound": "hbm", "kernel": "search_kernel (build, step 1 of BatchInsert)",
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+        "traffic_is": "HBM bytes per batch (compare bytes_per_batch), counters taken with the batch's searches as one launch",
         "batches": int(st["rounds"]), "launches": nl,
         "launches_side_by_side": "3 per batch of 8,192 points or more, else 1",
         "search_span_ms_per_batch": round(st["ms_search"] / max(1, st["rounds"]), 4),
@@ -264,12 +266,12 @@ def other_phases(st, w):
 
 
 def measured_traffic(workload):
-    """HBM bytes per launch of the search kernel from the committed rocprofv3 --pmc summary
+    """HBM bytes per batch of the search kernel from the committed rocprofv3 --pmc summary
     (FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size), or None."""
     path = os.path.join(ROOT, "profiles", "search_kernel_traffic.json")
     try:
         with open(path) as f:
-            return json.load(f).get(workload, {}).get("bytes_per_launch")
+            return json.load(f).get(workload, {}).get("bytes_per_batch")
     except (OSError, ValueError):
         return None
 
@@ -474,6 +476,9 @@ def main():
                     help="also build with several bounds theta on the batch size (Sec. 3.1) and report the time of "
                          "the build's phases for each: what a batch costs whatever its size, and what a search costs")
     ap.add_argument("--only-build", action="store_true", help="profiling: builds only (plus --search-L launches)")
+    ap.add_argument("--one-part", action="store_true",
+                    help="profiling with counters: step 1 of every batch as one launch (a profiler that runs one "
+                         "kernel at a time would otherwise see a third of a batch alone on the chip)")
     ap.add_argument("--search-L", type=int, default=0)
     ap.add_argument("--search-eps", type=float, default=None)
     ap.add_argument("--search-nq", type=int, default=STREAM_QUERIES)
@@ -508,7 +513,8 @@ def main():
     alloc = "torch" if args.allocator == "torch" else None
 
     def build(**kw):
-        return A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, metric=metric, allocator=alloc, **kw)
+        return A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, metric=metric, allocator=alloc,
+                           step1_parts=1 if args.one_part else 0, **kw)
 
     t_gen = time.time()
     w = W.make(args.config, args.n, args.nq)

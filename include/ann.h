@@ -102,6 +102,9 @@ typedef struct {
   ann_alloc_fn alloc;    /* device memory for the graph and all scratch; NULL = hipMalloc */
   ann_free_fn free;      /* its counterpart; both or neither                           */
   void* alloc_user;      /* passed to both                                             */
+  uint32_t step1_parts;  /* 0: batches of 8,192 points and more run step 1 of BatchInsert in
+                            three parts side by side (see ann_stats); 1: always in one part.
+                            The graph does not depend on it.                            */
 } ann_build_opts;
 
 typedef struct {

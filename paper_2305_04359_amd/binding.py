@@ -38,6 +38,7 @@ class BuildOpts(C.Structure):
         ("alloc", C.c_void_p),
         ("free", C.c_void_p),
         ("alloc_user", C.c_void_p),
+        ("step1_parts", C.c_uint32),
     ]
 
 
@@ -307,13 +308,14 @@ class Graph:
 
 def ann_build(points, R, L, alpha, seed=1, metric=L2SQ, batch_cap=0, start=None, order=None,
               visited_cap=0, hash_bits=0, max_rounds=0, collect_stats=False, spill_cap=0,
-              allocator="torch") -> Graph:
+              allocator="torch", step1_parts=0) -> Graph:
     """batchBuild of Alg. 3 over a device tensor of points (n x d; uint8, int8 or float32).
     The graph and the build's scratch are PyTorch's memory unless allocator=None."""
     points = _dev2d(points, "points")
     o = BuildOpts()
     al = _use_allocator(o, allocator)
     o.batch_cap = batch_cap
+    o.step1_parts = step1_parts
     o.use_start = 0 if start is None else 1
     o.start = 0 if start is None else int(start)
     keep = None

@@ -341,7 +341,7 @@ int batch_insert(ann_graph* g, const void* points, const u32* ids_host, const u3
   // (C2 build 83.7 -> 81.5 ms, C5 19.85 -> 19.40 s with three parts; two parts gain less;
   // parts one after the other on one stream lose 12 ms at C2, each paying the tail).
   // Not for the synchronised attempt, whose host check reads one overflow list for the batch.
-  const int nparts = (!sync && S.side[0] != nullptr && b >= STEP1_PARTS_MIN) ? 3 : 1;
+  const int nparts = (!sync && S.side[0] != nullptr && b >= STEP1_PARTS_MIN && g->step1_parts != 1) ? 3 : 1;
   u64 cut[4] = {0, b, b, b};
   if (nparts == 3) {  // a half for the caller's stream, then 30 % and 20 % (measured against other splits)
     cut[1] = b / 2;
@@ -1102,6 +1102,7 @@ int ann_build(const void* points_dev, uint64_t n, uint32_t d, ann_dtype dtype, a
   rc = check_insert_params(g, L, alpha);
   if (rc) return rc;
   g->collect = o.collect_stats != 0;
+  g->step1_parts = o.step1_parts;
   g->hash_bits = o.hash_bits;
   if (g->hash_bits && (g->hash_bits < 4 || g->hash_bits > 13)) return fail(ANN_EINVAL, "hash_bits must be in [4, 13]");
   g->visited_cap = o.visited_cap;

@@ -144,6 +144,7 @@ struct ann_graph {
   annmi::u32 visited_cap = 0;
   annmi::u64 spill_keys = 0;  // 0 = default
   bool collect = false;
+  annmi::u32 step1_parts = 0;  // 1: step 1 of a batch is never split into parts
   // u8/i8 rows whose size is not a multiple of 16 bytes: the kernels work on a copy with rows of
   // pad_stride bytes (zero tail, which changes no distance), made once per points array; queries
   // are copied the same way on every call.  cfg describes the padded rows.

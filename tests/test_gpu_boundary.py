@@ -284,3 +284,30 @@ def test_build_with_a_batch_of_a_hundred_thousand_points(env, capsys):
     with capsys.disabled():
         print(f"\n  [one batch of {cap} points: {st['reprunes']} re-prunes, {st['appends']} appends, graph identical]",
               flush=True)
+
+
+def test_step_one_in_parts_or_in_one(env):
+    """Batches of 8,192 points and more run their searches and prunes in three parts side by side
+    on three streams; `step1_parts = 1` keeps them in one.  Same graph either way, the oracle's,
+    and the statistics count the launches: with a bound of 9,000 the 30,000-point build has three
+    batches of that size after the doubling ones."""
+    torch, A, O = env
+    w = W.c1(n=30_000, nq=10)
+    R, L, alpha, cap = 32, 64, 1.2, 9_000
+    ds = O.Dataset(w.points, 0)
+    og, s = O.build(ds, R, L, alpha, seed=5, theta=cap, threads=0)
+    pts = dev(torch, w.points)
+    rows = {}
+    for parts in (0, 1):
+        g = A.ann_build(pts, R, L, alpha, seed=5, batch_cap=cap, collect_stats=True, step1_parts=parts)
+        st = g.stats()
+        rounds = int(g.info().rounds)
+        big = sum(1 for a, b in zip(O.schedule(w.n - 1, cap)[:-1], O.schedule(w.n - 1, cap)[1:]) if b - a >= 8192)
+        assert big >= 2
+        assert st["search_launches"] == rounds + (2 * big if parts == 0 else 0)
+        assert st["ms_search_launches"] >= st["ms_search"] > 0
+        rows[parts] = g.neighbors()
+        assert g.info().start == s
+    assert (rows[0] == rows[1]).all()
+    bad = np.nonzero((rows[0] != og).any(1))[0]
+    assert len(bad) == 0, f"{len(bad)} rows differ from the oracle's, first {bad[:10]}"
