@@ -262,6 +262,12 @@ def other_phases(st, w):
         out[k] = {"algorithmic_bytes": int(v), "ms": round(st["ms_" + k], 2), "achieved": round(gbs, 1), "unit": "GB/s",
                   "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
     out["sort"]["passes"] = passes
+    if st.get("search_launches", 0) > st["rounds"]:
+        # step 1 ran in parts: most of the prune work runs inside the search span
+        out["prune"].update({"achieved": None, "frac_of_hbm_peak": None,
+                             "note": "ms is what remains of step 1 after the search span (parts that are through "
+                                     "their searches prune while the others still search); search and prune together: "
+                                     f"{st['ms_search'] + st['ms_prune']:.2f} ms"})
     return out
 
 
