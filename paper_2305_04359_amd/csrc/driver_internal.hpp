@@ -171,8 +171,9 @@ struct BatchScratch {
   u64 spill_cap = 0;    // keys
   u32 spill_chunk = 0;  // extra keys a spilled list gets on top of vis_cap
   u64 arena_cap = 0;
-  // side streams (default priority) on which three of the four re-prune kernels run, and the
-  // events that order them against the caller's stream
+  // side streams (default priority): two of the three parts of a large batch's step 1 and three
+  // of the four re-prune kernels of step 2 run on them; the events order them against the
+  // caller's stream
   hipStream_t side[3] = {nullptr, nullptr, nullptr};
   hipEvent_t ev_plan = nullptr, ev_side[3] = {nullptr, nullptr, nullptr};
   u32* host_flag = nullptr;  // pinned: where the host reads the overflow count of a batch
