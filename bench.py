@@ -209,29 +209,29 @@ def working_set(w):
 def build_roofline(st, w, distinct_frac, traffic, distinct_known=True):
     """Roofline of the dominant kernel, the build's beam search.  Algorithmic bytes = hops * 4R
     (adjacency rows) + DISTINCT distance evaluations * row bytes (gathered vectors) + 8 * hops
-    (visited list).  A batch of 8,192 points or more issues its searches as three launches side by
-    side on three streams (a part that is through prunes while the others still search), so the
-    time the bytes are divided by is, per batch, the span from the first launch's start to the
-    last launch's end (HIP events the library records on those streams), summed over the batches.
-    The launches' own durations (they overlap) are reported beside it: their average is what a
-    kernel trace of the same build shows."""
+    (visited list).  One launch here is the searches of one batch.  A batch of 8,192 points or more
+    issues them as three kernel dispatches side by side on three streams (a part that is through
+    prunes while the others still search), and the launch's time is the span from the first
+    dispatch's start to the last one's end (HIP events the library records on those streams).
+    The dispatches' own durations (they overlap) are reported beside it: their average is what a
+    kernel trace of the same build shows per dispatch."""
     row_bytes = w.d * w.points.dtype.itemsize
     srch_bytes = st["hops"] * (4 * w.R + 8) + st["evals"] * distinct_frac * row_bytes
     srch_s = st["ms_search"] / 1e3
     achieved = srch_bytes / srch_s / 1e9 if srch_s > 0 else 0.0
-    nl = max(1, int(st.get("search_launches", 0)) or int(st["rounds"]))
+    nd = max(1, int(st.get("search_launches", 0)) or int(st["rounds"]))
+    nb = max(1, int(st["rounds"]))
     return {
         "bound": "hbm", "kernel": "search_kernel (build, step 1 of BatchInsert)",
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-        "traffic_is": "HBM bytes per batch (compare bytes_per_batch), counters taken with the batch's searches as one launch",
-        "batches": int(st["rounds"]), "launches": nl,
-        "launches_side_by_side": "3 per batch of 8,192 points or more, else 1",
-        "search_span_ms_per_batch": round(st["ms_search"] / max(1, st["rounds"]), 4),
-        "avg_launch_ms": round(st.get("ms_search_launches", st["ms_search"]) / nl, 4),
-        "bytes_per_batch": int(srch_bytes / max(1, st["rounds"])),
-        "bytes_per_launch": int(srch_bytes / nl),
-        "time_basis": "sum over batches of the span of the batch's search launches (ms_search)",
+        # one launch = the searches of one batch; achieved = bytes_per_launch / avg_launch_ms
+        "launches": nb, "avg_launch_ms": round(st["ms_search"] / nb, 4),
+        "bytes_per_launch": int(srch_bytes / nb),
+        "launch_is": "the searches of one batch: three kernel dispatches side by side on three streams for a batch of "
+                     "8,192 points or more, else one; its time is the span from the first dispatch's start to the "
+                     "last one's end (HIP events on those streams)",
+        "dispatches": nd, "avg_dispatch_ms": round(st.get("ms_search_launches", st["ms_search"]) / nd, 4),
         "distinct_eval_fraction": round(distinct_frac, 4),
         "evals_counted": ("distinct (repeats of the lossy visited filter excluded)" if distinct_known else
                           "all, repeats of the lossy visited filter included (no oracle leg in this run to "
