@@ -602,6 +602,14 @@ def main():
     # cost about 2 % of the build time): the source of the roofline figures and of the query counters
     gs = build(collect_stats=True)
     st = gs.stats()
+    # the same with step 1 of every batch as one dispatch: the search kernel's time on its own,
+    # without the prunes that run beside it when a batch is issued in parts
+    st_one = None
+    if not args.one_part and w.n <= 20_000_000:
+        g1 = A.ann_build(pts, w.R, w.L, w.alpha, seed=w.seed, metric=metric, allocator=alloc, step1_parts=1,
+                         collect_stats=True)
+        st_one = g1.stats()
+        del g1
     say("build with statistics done")
 
     cpu, rows_final = None, None
@@ -685,7 +693,13 @@ def main():
                                                       "insert_hops")},
         "build_phase_ms": {kk: round(st[kk], 2) for kk in ("ms_search", "ms_prune", "ms_sort", "ms_merge", "ms_total")},
         "roofline": build_roofline(st, w, distinct_frac, measured_traffic(w.name), not args.no_cpu),
-        "other_phases": other_phases(st, w),
+        "roofline_one_dispatch_per_batch": (None if st_one is None else {
+            k_: v_ for k_, v_ in build_roofline(st_one, w, distinct_frac, None, not args.no_cpu).items()
+            if k_ in ("achieved", "frac", "launches", "avg_launch_ms", "bytes_per_launch", "dispatches")} | {
+            "what": "a build with step1_parts = 1 (same graph, 2 ms slower at a million points): the kernel's rate "
+                    "when a batch's searches are one dispatch and no prune runs beside them",
+            "build_phase_ms": {kk: round(st_one[kk], 2) for kk in ("ms_search", "ms_prune", "ms_total")}}),
+        "other_phases": other_phases(st_one if st_one is not None else st, w),
         "datagen_s": round(t_gen, 1),
     }
     if cpu is not None:
